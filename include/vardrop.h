@@ -1,0 +1,157 @@
+/*
+ * vardrop.h -- C ABI of the VarDrop training hot path for AMD MI355X (gfx950).
+ *
+ * One training step of VarDrop (arXiv 2501.14183, Sec. 3, Fig. 2) is
+ *   k-dominant frequency hashing of every variate of a batch  (vardrop_hash)
+ *   -> grouping by hash + stratified sampling of representatives (vardrop_sample)
+ *   -> gather of the kept variate tokens                       (vardrop_gather)
+ *   -> multi-head scaled dot-product attention over the kept tokens, forward and
+ *      backward                                               (vardrop_attn_fwd / _bwd).
+ *
+ * General rules
+ *   - Every pointer is a DEVICE pointer owned by the caller unless its name ends in
+ *     "_host".  The library never frees or keeps caller memory.
+ *   - Every call only enqueues work on `stream` (a hipStream_t passed as void*; NULL is
+ *     the default stream) and returns without waiting, except where stated.
+ *   - Scratch memory comes from the caller: ask the matching *_workspace_bytes function
+ *     and pass a buffer of at least that size, 256-byte aligned.  The library allocates
+ *     device memory only inside vardrop_create.
+ *   - Return value: VARDROP_OK (0) or a negative error code.  On an argument error
+ *     nothing is enqueued and no output is touched.  Nothing throws, nothing aborts.
+ *   - A context serves one device; calls that share a context must not overlap in time
+ *     on different streams (the context caches a twiddle table).
+ */
+#ifndef VARDROP_H
+#define VARDROP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct vardrop_ctx vardrop_ctx;
+
+enum {
+  VARDROP_OK = 0,
+  VARDROP_EINVAL = -1,       /* null pointer, size or parameter out of range            */
+  VARDROP_EWORKSPACE = -2,   /* workspace missing, misaligned or too small               */
+  VARDROP_EHIP = -3,         /* a HIP call failed; see vardrop_last_hip_error            */
+  VARDROP_EUNSUPPORTED = -4  /* valid request outside what the kernels implement         */
+};
+
+enum { VARDROP_F32 = 0, VARDROP_BF16 = 1 };   /* element type of tokens / weights */
+
+/* Creates a context on HIP device `device_id` (allocates a 64 KiB twiddle table there).
+ * Synchronous. */
+int vardrop_create(vardrop_ctx** out, int device_id);
+void vardrop_destroy(vardrop_ctx* ctx);
+/* Static, never-null description of an error code. */
+const char* vardrop_strerror(int code);
+/* hipError_t of the last failed HIP call made through this context (0 if none). */
+int vardrop_last_hip_error(const vardrop_ctx* ctx);
+
+/* ---------------------------------------------------------------------------------
+ * k-dominant frequency hashing -- Alg. 1 and Def. 1 of the paper.
+ *
+ * For every variate n: amplitude spectrum |X_f| of each of its B windows (step 1) on the
+ * candidate bins f_min..f_max only (low-pass, step 2; the paper's cut-off epsilon is the
+ * number of candidate bins, 25 for T = 96, App. E), mean over the B windows (step 3), the
+ * k bins of largest mean amplitude in descending order, ties to the lower bin (step 4),
+ * and hash[n] = sum_j topk[n][j] * R^(k-1-j) with R = floor(L/2)+1 (step 5).
+ *
+ *   x      fp32 [B][N][L] with element strides sb, sn, st (st must be 1)
+ *   topk   int32 [N][k]   bin indices, rank 1 first
+ *   hash   uint64 [N]
+ *   abar   fp32 [N][f_max-f_min+1] mean amplitudes, or NULL
+ * Requires 1 <= k <= f_max-f_min+1, 0 <= f_min <= f_max <= floor(L/2), R^k < 2^63,
+ * 2 <= L <= 1024, at most 512 candidate bins, and staging buffers that fit the 160 KiB LDS:
+ * 4*(35 L + 1056 + V*(f_max-f_min+1)) bytes with V = 32/min(32, B rounded up to a power of
+ * two); always true for L <= 768 (EUNSUPPORTED otherwise).  N == 0 is a no-op.  Arithmetic is fp32; ranks agree
+ * with an exact evaluation whenever neighbouring amplitudes differ by much more than 1e-6
+ * relative.  Non-finite inputs give unspecified ranks.
+ */
+size_t vardrop_hash_workspace_bytes(int B, int N, int L, int k, int f_min, int f_max);
+int vardrop_hash(vardrop_ctx* ctx, const float* x, int B, int N, int L,
+                 int64_t sb, int64_t sn, int64_t st, int k, int f_min, int f_max,
+                 int32_t* topk, uint64_t* hash, float* abar,
+                 void* ws, size_t ws_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------
+ * Grouping and stratified sampling -- Sec. 3.3, Eq. 1-2.
+ *
+ * Variates with equal hash form a group; group ids number the distinct hashes in
+ * ascending order.  A group of size g keeps
+ *     n_i = min(g, gs', max(1, ceil(g * ratio_num / ratio_den)))   (gs' = gs, or no cap if gs == 0)
+ * members; ratio 1/1 leaves Eq. 1, |S_i| = min(|G_i|, gs), as printed.  "Random": variate n
+ * draws u[n] = r0<<32|r1 from Philox4x32-10 with counter (n, 0, step_lo, step_hi) and key
+ * (seed_lo, seed_hi); a group keeps the members with the smallest (u[n], n).
+ *
+ *   hash      uint64 [N]
+ *   group_id  int32 [N]
+ *   sel       int32 [N] capacity; the first N' entries are the kept variates, ascending
+ *   counts    int32 [2] = {N', G}
+ *   counts_host  optional HOST pointer (pinned memory recommended): receives the same two
+ *             values through an asynchronous copy on `stream`; valid after the stream is
+ *             synchronised.
+ * Requires 1 <= N <= 8192 (EUNSUPPORTED above), ratio_num <= ratio_den, ratio_den > 0.
+ */
+size_t vardrop_sample_workspace_bytes(int N);
+int vardrop_sample(vardrop_ctx* ctx, const uint64_t* hash, int N,
+                   uint32_t gs, uint32_t ratio_num, uint32_t ratio_den,
+                   uint64_t seed, uint64_t step,
+                   int32_t* group_id, int32_t* sel, int32_t* counts, int32_t* counts_host,
+                   void* ws, size_t ws_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------
+ * Gather of the kept tokens (Sec. 3.1: attention runs on the selected tokens only) and
+ * its adjoint.
+ *
+ *   gather :  out[b][i][:]     = tokens[b][sel[i]][:]          out [B][n_sel][d]
+ *   scatter:  dtokens[b][n][:] = dxs[b][i][:] if n == sel[i], else 0   (every row written)
+ * tokens / dtokens are [B][N][d]; dtype is VARDROP_F32 or VARDROP_BF16.  sel must be
+ * ascending and within 0..N-1 (as vardrop_sample writes it); an out-of-range entry
+ * yields a zero row.  n_sel == 0 is a no-op for gather; scatter then zero-fills.
+ */
+int vardrop_gather(vardrop_ctx* ctx, const void* tokens, int B, int N, int d, int dtype,
+                   const int32_t* sel, int n_sel, void* out, void* stream);
+int vardrop_scatter(vardrop_ctx* ctx, const void* dxs, int B, int N, int d, int dtype,
+                    const int32_t* sel, int n_sel, void* dtokens, void* stream);
+
+/* ---------------------------------------------------------------------------------
+ * Multi-head scaled dot-product attention over the kept tokens -- Eq. 3,
+ * softmax(Q K^T / sqrt(d_k)) V, with d_k = d / H; no mask, no dropout.
+ *
+ *   Q = xs Wq (+bq), K = xs Wk (+bk), V = xs Wv (+bv), heads = H contiguous chunks of d,
+ *   O = concat_h softmax(Q_h K_h^T / sqrt(d_k)) V_h,  y = O Wo (+bo).
+ *
+ *   xs, y, dy, dxs   [B][n][d]        element type `dtype`
+ *   Wq, Wk, Wv, Wo   [d][d] row-major (y = x W), `dtype`; biases [d], `dtype`, NULL = none
+ *   saved            vardrop_attn_saved_bytes: Q, K, V, O in `dtype` and the row log-sum-exp
+ *                    in fp32; written by fwd, read by bwd
+ *   dWq..dWo         fp32 [d][d], overwritten;  dbq..dbo fp32 [d], overwritten, NULL = skip
+ * VARDROP_BF16 multiplies bf16 operands on the matrix cores with fp32 accumulation and
+ * fp32 softmax, and requires d_k == 64 and d % 64 == 0; VARDROP_F32 is plain fp32 and
+ * requires d_k in {16, 32, 64, 128}.  n == 0 is a no-op (weight gradients zero-filled).
+ * The backward recomputes the attention probabilities from Q, K and the saved
+ * log-sum-exp; it does not store them.
+ */
+size_t vardrop_attn_saved_bytes(int B, int n, int d, int H, int dtype);
+size_t vardrop_attn_workspace_bytes(int B, int n, int d, int H, int dtype);
+int vardrop_attn_fwd(vardrop_ctx* ctx, const void* xs, int B, int n, int d, int H, int dtype,
+                     const void* Wq, const void* Wk, const void* Wv, const void* Wo,
+                     const void* bq, const void* bk, const void* bv, const void* bo,
+                     void* y, void* saved, void* ws, size_t ws_bytes, void* stream);
+int vardrop_attn_bwd(vardrop_ctx* ctx, const void* dy, const void* xs,
+                     int B, int n, int d, int H, int dtype,
+                     const void* Wq, const void* Wk, const void* Wv, const void* Wo,
+                     const void* saved,
+                     void* dxs, float* dWq, float* dWk, float* dWv, float* dWo,
+                     float* dbq, float* dbk, float* dbv, float* dbo,
+                     void* ws, size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VARDROP_H */

@@ -1,0 +1,204 @@
+"""ctypes binding of libvardrop.so: argument marshalling only.
+
+Every function has the name of the C entry point it calls (include/vardrop.h).  Tensors
+are torch tensors on the GPU; torch provides device memory and the current HIP stream,
+nothing else.  There is no fallback: if the shared library is missing, loading fails.
+"""
+import ctypes
+import os
+
+import torch
+
+F32 = 0
+BF16 = 1
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+_c_int = ctypes.c_int
+_c_i64 = ctypes.c_int64
+_c_u32 = ctypes.c_uint32
+_c_u64 = ctypes.c_uint64
+_c_size = ctypes.c_size_t
+_ptr = ctypes.c_void_p
+
+_SIGNATURES = {
+    "vardrop_create": (_c_int, [ctypes.POINTER(_ptr), _c_int]),
+    "vardrop_destroy": (None, [_ptr]),
+    "vardrop_strerror": (ctypes.c_char_p, [_c_int]),
+    "vardrop_last_hip_error": (_c_int, [_ptr]),
+    "vardrop_hash_workspace_bytes": (_c_size, [_c_int] * 6),
+    "vardrop_hash": (_c_int, [_ptr, _ptr, _c_int, _c_int, _c_int, _c_i64, _c_i64, _c_i64, _c_int, _c_int, _c_int,
+                              _ptr, _ptr, _ptr, _ptr, _c_size, _ptr]),
+    "vardrop_sample_workspace_bytes": (_c_size, [_c_int]),
+    "vardrop_sample": (_c_int, [_ptr, _ptr, _c_int, _c_u32, _c_u32, _c_u32, _c_u64, _c_u64,
+                                _ptr, _ptr, _ptr, _ptr, _ptr, _c_size, _ptr]),
+    "vardrop_gather": (_c_int, [_ptr, _ptr, _c_int, _c_int, _c_int, _c_int, _ptr, _c_int, _ptr, _ptr]),
+    "vardrop_scatter": (_c_int, [_ptr, _ptr, _c_int, _c_int, _c_int, _c_int, _ptr, _c_int, _ptr, _ptr]),
+    "vardrop_attn_saved_bytes": (_c_size, [_c_int] * 5),
+    "vardrop_attn_workspace_bytes": (_c_size, [_c_int] * 5),
+    "vardrop_attn_fwd": (_c_int, [_ptr, _ptr, _c_int, _c_int, _c_int, _c_int, _c_int] + [_ptr] * 8 +
+                         [_ptr, _ptr, _ptr, _c_size, _ptr]),
+    "vardrop_attn_bwd": (_c_int, [_ptr, _ptr, _ptr, _c_int, _c_int, _c_int, _c_int, _c_int] + [_ptr] * 4 +
+                         [_ptr] + [_ptr] * 9 + [_ptr, _c_size, _ptr]),
+}
+
+
+class VarDropError(RuntimeError):
+    def __init__(self, code, where, detail=""):
+        self.code = code
+        super().__init__("%s failed: %s (%d)%s" % (where, _strerror(code), code, detail))
+
+
+def library_path():
+    return os.path.join(_HERE, "libvardrop.so")
+
+
+def load_library():
+    """Loads libvardrop.so (built by paper_2501_14183_amd/build.py) and declares its signatures."""
+    global _LIB
+    if _LIB is None:
+        path = library_path()
+        if not os.path.exists(path):
+            raise ImportError("libvardrop.so is not built: run `python -m paper_2501_14183_amd.build` "
+                              "(there is no fallback implementation)")
+        lib = ctypes.CDLL(path)
+        for name, (res, args) in _SIGNATURES.items():
+            fn = getattr(lib, name)
+            fn.restype = res
+            fn.argtypes = args
+        _LIB = lib
+    return _LIB
+
+
+def _strerror(code):
+    return load_library().vardrop_strerror(code).decode()
+
+
+def _p(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(t):
+    return ctypes.c_void_p(torch.cuda.current_stream(t.device).cuda_stream)
+
+
+def _dtype_code(t):
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError("tokens and weights must be float32 or bfloat16")
+
+
+class Context:
+    """Owns a vardrop_ctx on one device."""
+
+    def __init__(self, device=0):
+        self._lib = load_library()
+        self.device = torch.device("cuda", device) if isinstance(device, int) else torch.device(device)
+        h = ctypes.c_void_p()
+        rc = self._lib.vardrop_create(ctypes.byref(h), self.device.index or 0)
+        if rc != 0:
+            raise VarDropError(rc, "vardrop_create")
+        self.handle = h
+
+    def check(self, rc, where):
+        if rc != 0:
+            detail = ""
+            if rc == -3:
+                detail = " hipError=%d" % self._lib.vardrop_last_hip_error(self.handle)
+            raise VarDropError(rc, where, detail)
+
+    def close(self):
+        if getattr(self, "handle", None):
+            self._lib.vardrop_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def vardrop_hash(ctx, x, k, f_min=1, f_max=None, want_abar=False):
+    """x float32 [B, N, L] -> (topk int32 [N, k], hash int64 [N] (the uint64 bits), abar or None)."""
+    if x.dtype != torch.float32 or x.dim() != 3:
+        raise TypeError("x must be float32 [B, N, L]")
+    B, N, L = x.shape
+    if f_max is None:
+        f_max = (L // 2 + 2) // 2
+    topk = torch.empty((N, k), dtype=torch.int32, device=x.device)
+    hsh = torch.empty((N,), dtype=torch.int64, device=x.device)
+    abar = torch.empty((N, f_max - f_min + 1), dtype=torch.float32, device=x.device) if want_abar else None
+    sb, sn, st = x.stride()
+    rc = ctx._lib.vardrop_hash(ctx.handle, _p(x), B, N, L, sb, sn, st, k, f_min, f_max,
+                               _p(topk), _p(hsh), _p(abar), None, 0, _stream(x))
+    ctx.check(rc, "vardrop_hash")
+    return topk, hsh, abar
+
+
+def vardrop_sample(ctx, hsh, gs, ratio_num, ratio_den, seed, step, counts_host=None):
+    """hash int64 [N] -> (group_id int32 [N], sel int32 [N] (first N' valid), counts int32 [2] = {N', G}).
+
+    counts_host: optional pinned int32 [2] CPU tensor that receives the counts asynchronously.
+    """
+    N = hsh.shape[0]
+    gid = torch.empty((N,), dtype=torch.int32, device=hsh.device)
+    sel = torch.empty((N,), dtype=torch.int32, device=hsh.device)
+    counts = torch.empty((2,), dtype=torch.int32, device=hsh.device)
+    rc = ctx._lib.vardrop_sample(ctx.handle, _p(hsh), N, gs, ratio_num, ratio_den, seed, step,
+                                 _p(gid), _p(sel), _p(counts), _p(counts_host), None, 0, _stream(hsh))
+    ctx.check(rc, "vardrop_sample")
+    return gid, sel, counts
+
+
+def vardrop_gather(ctx, tokens, sel, n_sel):
+    """tokens [B, N, d], sel int32 -> [B, n_sel, d]."""
+    B, N, d = tokens.shape
+    out = torch.empty((B, n_sel, d), dtype=tokens.dtype, device=tokens.device)
+    rc = ctx._lib.vardrop_gather(ctx.handle, _p(tokens), B, N, d, _dtype_code(tokens), _p(sel), n_sel, _p(out),
+                                 _stream(tokens))
+    ctx.check(rc, "vardrop_gather")
+    return out
+
+
+def vardrop_scatter(ctx, dxs, sel, n_sel, N):
+    """dxs [B, n_sel, d] -> dtokens [B, N, d] with zeros at dropped variates."""
+    B, _, d = dxs.shape
+    out = torch.empty((B, N, d), dtype=dxs.dtype, device=dxs.device)
+    rc = ctx._lib.vardrop_scatter(ctx.handle, _p(dxs), B, N, d, _dtype_code(dxs), _p(sel), n_sel, _p(out),
+                                  _stream(dxs))
+    ctx.check(rc, "vardrop_scatter")
+    return out
+
+
+def vardrop_attn_fwd(ctx, xs, Wq, Wk, Wv, Wo, H, bq=None, bk=None, bv=None, bo=None, saved=None):
+    """xs [B, n, d] -> (y [B, n, d], saved uint8 buffer for the backward)."""
+    B, n, d = xs.shape
+    code = _dtype_code(xs)
+    nbytes = ctx._lib.vardrop_attn_saved_bytes(B, n, d, H, code)
+    if saved is None or saved.numel() < nbytes:
+        saved = torch.empty((max(nbytes, 256),), dtype=torch.uint8, device=xs.device)
+    y = torch.empty_like(xs)
+    rc = ctx._lib.vardrop_attn_fwd(ctx.handle, _p(xs), B, n, d, H, code, _p(Wq), _p(Wk), _p(Wv), _p(Wo),
+                                   _p(bq), _p(bk), _p(bv), _p(bo), _p(y), _p(saved), None, 0, _stream(xs))
+    ctx.check(rc, "vardrop_attn_fwd")
+    return y, saved
+
+
+def vardrop_attn_bwd(ctx, dy, xs, Wq, Wk, Wv, Wo, H, saved, bias_grads=False, ws=None):
+    """-> (dxs, dWq, dWk, dWv, dWo) or, with bias_grads, (..., dbq, dbk, dbv, dbo); weight grads are float32."""
+    B, n, d = xs.shape
+    code = _dtype_code(xs)
+    nbytes = ctx._lib.vardrop_attn_workspace_bytes(B, n, d, H, code)
+    if ws is None or ws.numel() < nbytes:
+        ws = torch.empty((max(nbytes, 256),), dtype=torch.uint8, device=xs.device)
+    dxs = torch.empty_like(xs)
+    dW = [torch.empty((d, d), dtype=torch.float32, device=xs.device) for _ in range(4)]
+    db = [torch.empty((d,), dtype=torch.float32, device=xs.device) if bias_grads else None for _ in range(4)]
+    rc = ctx._lib.vardrop_attn_bwd(ctx.handle, _p(dy), _p(xs), B, n, d, H, code, _p(Wq), _p(Wk), _p(Wv), _p(Wo),
+                                   _p(saved), _p(dxs), *[_p(t) for t in dW], *[_p(t) for t in db],
+                                   _p(ws), ws.numel(), _stream(xs))
+    ctx.check(rc, "vardrop_attn_bwd")
+    return (dxs, *dW, *db) if bias_grads else (dxs, *dW)

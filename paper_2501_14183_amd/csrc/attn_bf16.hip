@@ -1,0 +1,604 @@
+// bf16 matrix-core back end of the multi-head attention (Eq. 3), forward and backward.
+//
+// All contractions run on v_mfma_f32_32x32x16_bf16 (bf16 operands, fp32 accumulation):
+//   * the projections and their gradients through one LDS-tiled GEMM kernel with three
+//     operand-layout variants;
+//   * softmax(Q K^T / sqrt(d_k)) V as a tiled online-softmax kernel (no n x n matrix is
+//     stored) that works on the TRANSPOSED score tile S^T = K Q^T: in the accumulator
+//     layout of the 32x32 instruction a lane then owns one query, so running maximum,
+//     running sum and rescaling are per-lane scalars, and the probability registers are
+//     directly the right-hand operand of O^T = V^T P^T;
+//   * the backward recomputes the probabilities from Q, K and the saved log-sum-exp in two
+//     kernels (dQ by query block, dK/dV by key block), so no atomics are needed and the
+//     result is deterministic.
+//
+// Operand layout of the instruction (64 lanes, half = lane / 32):
+//   A[i][k]: lane holds row i = lane % 32, eight k values of group `half`
+//   B[k][j]: lane holds column j = lane % 32, the same eight k values
+//   C[i][j]: lane holds column j = lane % 32, register r holds row 8*(r/4) + 4*half + r%4
+#include "common.h"
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+namespace {
+
+typedef uint16_t bf16_t;   // raw storage
+
+__device__ inline bf16_t f2bf(float f) {
+  const uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)0x7fc0;
+  return (bf16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+}
+__device__ inline float bf2f(bf16_t b) { return __uint_as_float((uint32_t)b << 16); }
+__device__ inline uint32_t pack2(float lo, float hi) { return (uint32_t)f2bf(lo) | ((uint32_t)f2bf(hi) << 16); }
+
+union Frag {
+  uint4 q;
+  uint2 d[2];
+  uint32_t w[4];
+  bf16_t h[8];
+  bf16x8 v;
+};
+
+__device__ inline floatx16 zero16() {
+  floatx16 z = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  return z;
+}
+__device__ inline floatx16 mfma(const Frag& a, const Frag& b, floatx16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, b.v, c, 0, 0, 0);
+}
+// eight accumulator registers (8*s2 .. 8*s2+7) as a bf16 right-hand operand
+__device__ inline Frag regs_to_frag(const floatx16& p, int s2) {
+  Frag f;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) f.w[e] = pack2(p[8 * s2 + 2 * e], p[8 * s2 + 2 * e + 1]);
+  return f;
+}
+
+// ================================================================== GEMM
+struct GemmBf16 {
+  const bf16_t* A[3];
+  const bf16_t* B[3];
+  void* C[3];
+  const bf16_t* bias[3];
+  int lda, ldb, ldc;
+  int M, N, K;
+  int nseg;           // > 1: segments accumulate into C[0]
+};
+
+constexpr int kLd = 40;   // LDS row stride in elements: 32 k values + 8 pad
+
+// k-contiguous source P[mn][k]: 128 rows x 32 k, two 16-byte chunks per thread
+__device__ inline void load_kc(const bf16_t* P, int ld, int mn0, int MN, int k0, int K, uint4 r[2]) {
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    const int c = threadIdx.x + u * 256;
+    const int row = c >> 2, kc = c & 3;
+    r[u] = make_uint4(0, 0, 0, 0);
+    if (mn0 + row < MN && k0 + kc * 8 < K)
+      r[u] = *reinterpret_cast<const uint4*>(P + (long long)(mn0 + row) * ld + k0 + kc * 8);
+  }
+}
+__device__ inline void store_kc(bf16_t* S, const uint4 r[2]) {
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    const int c = threadIdx.x + u * 256;
+    const int row = c >> 2, kc = c & 3;
+    *reinterpret_cast<uint4*>(S + row * kLd + kc * 8) = r[u];
+  }
+}
+// mn-contiguous source P[k][mn]: two k rows x eight mn per thread, transposed on the way into LDS
+__device__ inline void load_mc(const bf16_t* P, int ld, int mn0, int MN, int k0, int K, uint4 r[2]) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int kp = lane & 15, mc = wave * 4 + (lane >> 4);
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    const int k = k0 + 2 * kp + u;
+    r[u] = make_uint4(0, 0, 0, 0);
+    if (k < K && mn0 + mc * 8 < MN)
+      r[u] = *reinterpret_cast<const uint4*>(P + (long long)k * ld + mn0 + mc * 8);
+  }
+}
+__device__ inline void store_mc(bf16_t* S, const uint4 r[2]) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int kp = lane & 15, mc = wave * 4 + (lane >> 4);
+  Frag a, b;
+  a.q = r[0];
+  b.q = r[1];
+#pragma unroll
+  for (int j = 0; j < 8; ++j)
+    *reinterpret_cast<uint32_t*>(S + (mc * 8 + j) * kLd + 2 * kp) = (uint32_t)a.h[j] | ((uint32_t)b.h[j] << 16);
+}
+
+template <bool AKC, bool BKC, typename OutT>
+__global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmBf16 g) {
+  __shared__ __attribute__((aligned(16))) bf16_t As[128 * kLd];
+  __shared__ __attribute__((aligned(16))) bf16_t Bs[128 * kLd];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int col = lane & 31, half = lane >> 5;
+  const int z = blockIdx.z;
+  const int m0 = blockIdx.y * 128, n0 = blockIdx.x * 128;
+  floatx16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) acc[i][j] = zero16();
+
+  const int nseg = g.nseg > 1 ? g.nseg : 1;
+  const int nk = (g.K + 31) >> 5;
+  for (int seg = 0; seg < nseg; ++seg) {
+    const bf16_t* A = g.A[g.nseg > 1 ? seg : z];
+    const bf16_t* Bm = g.B[g.nseg > 1 ? seg : z];
+    uint4 ra[2], rb[2];
+    if (AKC) load_kc(A, g.lda, m0, g.M, 0, g.K, ra); else load_mc(A, g.lda, m0, g.M, 0, g.K, ra);
+    if (BKC) load_kc(Bm, g.ldb, n0, g.N, 0, g.K, rb); else load_mc(Bm, g.ldb, n0, g.N, 0, g.K, rb);
+    for (int kt = 0; kt < nk; ++kt) {
+      __syncthreads();
+      if (AKC) store_kc(As, ra); else store_mc(As, ra);
+      if (BKC) store_kc(Bs, rb); else store_mc(Bs, rb);
+      __syncthreads();
+      if (kt + 1 < nk) {
+        const int k0 = (kt + 1) << 5;
+        if (AKC) load_kc(A, g.lda, m0, g.M, k0, g.K, ra); else load_mc(A, g.lda, m0, g.M, k0, g.K, ra);
+        if (BKC) load_kc(Bm, g.ldb, n0, g.N, k0, g.K, rb); else load_mc(Bm, g.ldb, n0, g.N, k0, g.K, rb);
+      }
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
+        Frag fa[2], fb[2];
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+          fa[t].q = *reinterpret_cast<const uint4*>(As + (wm * 64 + t * 32 + col) * kLd + ks * 16 + half * 8);
+          fb[t].q = *reinterpret_cast<const uint4*>(Bs + (wn * 64 + t * 32 + col) * kLd + ks * 16 + half * 8);
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+          for (int j = 0; j < 2; ++j) acc[i][j] = mfma(fa[i], fb[j], acc[i][j]);
+      }
+    }
+  }
+  OutT* C = reinterpret_cast<OutT*>(g.C[g.nseg > 1 ? 0 : z]);
+  const bf16_t* bias = g.bias[g.nseg > 1 ? 0 : z];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int n = n0 + wn * 64 + j * 32 + col;
+      const float bv = (bias && n < g.N) ? bf2f(bias[n]) : 0.f;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = m0 + wm * 64 + i * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+        if (m < g.M && n < g.N) {
+          const float val = acc[i][j][r] + bv;
+          if (sizeof(OutT) == 2) reinterpret_cast<bf16_t*>(C)[(long long)m * g.ldc + n] = f2bf(val);
+          else reinterpret_cast<float*>(C)[(long long)m * g.ldc + n] = val;
+        }
+      }
+    }
+}
+
+template <bool AKC, bool BKC, typename OutT>
+int launch_gemm(vardrop_ctx* ctx, const GemmBf16& g, int nz, hipStream_t s) {
+  if (g.M == 0 || g.N == 0) return VARDROP_OK;
+  dim3 grid(vd_ceil_div(g.N, 128), vd_ceil_div(g.M, 128), nz);
+  hipLaunchKernelGGL((gemm_bf16_kernel<AKC, BKC, OutT>), grid, dim3(256), 0, s, g);
+  VD_LAUNCH_CHECK(ctx);
+  return VARDROP_OK;
+}
+
+// ================================================================== attention core (d_k = 64)
+constexpr int kDh = 64;
+constexpr int kTs = 72;              // LDS row stride of a 64-wide tile: 64 + 8 pad
+constexpr float kLog2e = 1.4426950408889634f;
+
+// rows [r0, r0+64) x 64 columns of a [n][d] head slice into LDS, row-major (k-contiguous)
+template <int NT>
+__device__ inline void tile_rows(bf16_t* S, const bf16_t* P, long long ld, int r0, int n) {
+  for (int c = threadIdx.x; c < 64 * 8; c += NT) {
+    const int row = c >> 3, ch = c & 7;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (r0 + row < n) v = *reinterpret_cast<const uint4*>(P + (long long)(r0 + row) * ld + ch * 8);
+    *reinterpret_cast<uint4*>(S + row * kTs + ch * 8) = v;
+  }
+}
+// the same rows transposed: S[c][row]
+template <int NT>
+__device__ inline void tile_cols(bf16_t* S, const bf16_t* P, long long ld, int r0, int n) {
+  for (int c = threadIdx.x; c < 32 * 8; c += NT) {
+    const int rp = c & 31, ch = c >> 5;            // row pair, 8-column chunk
+    Frag a, b;
+    a.q = make_uint4(0, 0, 0, 0);
+    b.q = a.q;
+    if (r0 + 2 * rp < n) a.q = *reinterpret_cast<const uint4*>(P + (long long)(r0 + 2 * rp) * ld + ch * 8);
+    if (r0 + 2 * rp + 1 < n) b.q = *reinterpret_cast<const uint4*>(P + (long long)(r0 + 2 * rp + 1) * ld + ch * 8);
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      *reinterpret_cast<uint32_t*>(S + (ch * 8 + j) * kTs + 2 * rp) = (uint32_t)a.h[j] | ((uint32_t)b.h[j] << 16);
+  }
+}
+// a lane's row of a head slice as four right-hand (or left-hand) operands: k = 16*s + 8*half + e
+__device__ inline void row_frags(Frag f[4], const bf16_t* P, long long ld, int row, int n, int half) {
+#pragma unroll
+  for (int s = 0; s < 4; ++s) {
+    f[s].q = make_uint4(0, 0, 0, 0);
+    if (row < n) f[s].q = *reinterpret_cast<const uint4*>(P + (long long)row * ld + s * 16 + half * 8);
+  }
+}
+// left-hand operand from a row-major tile: rows sub*32 + col, k = 16*s + 8*half ..
+__device__ inline Frag tile_frag(const bf16_t* S, int sub, int col, int s, int half) {
+  Frag f;
+  f.q = *reinterpret_cast<const uint4*>(S + (sub * 32 + col) * kTs + s * 16 + half * 8);
+  return f;
+}
+// left-hand operand from a transposed tile T[c][row] matching accumulator registers 8*s2 .. 8*s2+7 of
+// row sub-tile `sub`: rows sub*32 + 16*s2 + 4*half + {0..3} and the same + 8
+__device__ inline Frag tileT_frag(const bf16_t* T, int ctile, int col, int sub, int s2, int half) {
+  Frag f;
+  const bf16_t* p = T + (ctile * 32 + col) * kTs + sub * 32 + 16 * s2 + 4 * half;
+  f.d[0] = *reinterpret_cast<const uint2*>(p);
+  f.d[1] = *reinterpret_cast<const uint2*>(p + 8);
+  return f;
+}
+// accumulator (transposed: rows = head dims, column = this lane's token) -> out[token][32*ct + ...]
+__device__ inline void store_accT(bf16_t* out_row, const floatx16& acc, int ct, int half, float mul) {
+#pragma unroll
+  for (int g4 = 0; g4 < 4; ++g4) {
+    uint2 w;
+    w.x = pack2(acc[4 * g4] * mul, acc[4 * g4 + 1] * mul);
+    w.y = pack2(acc[4 * g4 + 2] * mul, acc[4 * g4 + 3] * mul);
+    *reinterpret_cast<uint2*>(out_row + ct * 32 + 8 * g4 + 4 * half) = w;
+  }
+}
+
+struct SdpaArgs {
+  const bf16_t *q, *k, *v, *o, *dout;
+  bf16_t *out, *dq, *dk, *dv;
+  float *lse, *Dsum;
+  int n, d, H;
+  float scale;
+};
+
+// ---- forward: one wavefront per 32 queries, NW wavefronts share the K / V tiles
+template <int NW>
+__global__ __launch_bounds__(NW * 64) void sdpa_fwd_bf16(SdpaArgs a) {
+  __shared__ __attribute__((aligned(16))) bf16_t Ks[64 * kTs];
+  __shared__ __attribute__((aligned(16))) bf16_t Vt[64 * kTs];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int col = lane & 31, half = lane >> 5;
+  const int b = blockIdx.z, h = blockIdx.y;
+  const int n = a.n;
+  const long long ld = a.d;
+  const long long base = (long long)b * n * ld + h * kDh;
+  const int qi = blockIdx.x * (NW * 32) + wave * 32 + col;
+  Frag qf[4];
+  row_frags(qf, a.q + base, ld, qi, n, half);
+  floatx16 acc[2] = {zero16(), zero16()};
+  float m = -INFINITY, l = 0.f;
+  const float c = a.scale * kLog2e;
+  for (int j0 = 0; j0 < n; j0 += 64) {
+    __syncthreads();
+    tile_rows<NW * 64>(Ks, a.k + base, ld, j0, n);
+    tile_cols<NW * 64>(Vt, a.v + base, ld, j0, n);
+    __syncthreads();
+    floatx16 st[2];
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt) {
+      st[kt] = zero16();
+#pragma unroll
+      for (int s = 0; s < 4; ++s) st[kt] = mfma(tile_frag(Ks, kt, col, s, half), qf[s], st[kt]);
+    }
+    float mt = -INFINITY;
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int j = j0 + kt * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+        st[kt][r] = j < n ? st[kt][r] * c : -INFINITY;
+        mt = fmaxf(mt, st[kt][r]);
+      }
+    mt = fmaxf(mt, __shfl_xor(mt, 32, 64));
+    const float mn = fmaxf(m, mt);
+    const float alpha = exp2f(m - mn);
+    float rs = 0.f;
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        st[kt][r] = exp2f(st[kt][r] - mn);
+        rs += st[kt][r];
+      }
+    l = l * alpha + rs;
+    m = mn;
+#pragma unroll
+    for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[dt][r] *= alpha;
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2) {
+        const Frag pf = regs_to_frag(st[kt], s2);
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt) acc[dt] = mfma(tileT_frag(Vt, dt, col, kt, s2, half), pf, acc[dt]);
+      }
+  }
+  l += __shfl_xor(l, 32, 64);
+  if (qi < n) {
+    const float inv = 1.f / l;
+    bf16_t* orow = a.out + base + (long long)qi * ld;
+    store_accT(orow, acc[0], 0, half, inv);
+    store_accT(orow, acc[1], 1, half, inv);
+    if (half == 0) a.lse[((long long)b * a.H + h) * n + qi] = (m + log2f(l)) * 0.6931471805599453f;
+  }
+}
+
+// ---- backward, part 1: dQ and D = rowsum(dO * O); one wavefront per 32 queries
+template <int NW>
+__global__ __launch_bounds__(NW * 64) void sdpa_bwd_dq_bf16(SdpaArgs a) {
+  __shared__ __attribute__((aligned(16))) bf16_t Ks[64 * kTs];
+  __shared__ __attribute__((aligned(16))) bf16_t Vs[64 * kTs];
+  __shared__ __attribute__((aligned(16))) bf16_t Kt[64 * kTs];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int col = lane & 31, half = lane >> 5;
+  const int b = blockIdx.z, h = blockIdx.y;
+  const int n = a.n;
+  const long long ld = a.d;
+  const long long base = (long long)b * n * ld + h * kDh;
+  const int qi = blockIdx.x * (NW * 32) + wave * 32 + col;
+  Frag qf[4], dof[4];
+  row_frags(qf, a.q + base, ld, qi, n, half);
+  row_frags(dof, a.dout + base, ld, qi, n, half);
+  float D = 0.f;
+  {
+    Frag of[4];
+    row_frags(of, a.o + base, ld, qi, n, half);
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) D = fmaf(bf2f(dof[s].h[e]), bf2f(of[s].h[e]), D);
+    D += __shfl_xor(D, 32, 64);
+  }
+  const long long srow = ((long long)b * a.H + h) * n;
+  const float lse2 = qi < n ? a.lse[srow + qi] * kLog2e : INFINITY;
+  const float c = a.scale * kLog2e;
+  floatx16 acc[2] = {zero16(), zero16()};
+  for (int j0 = 0; j0 < n; j0 += 64) {
+    __syncthreads();
+    tile_rows<NW * 64>(Ks, a.k + base, ld, j0, n);
+    tile_rows<NW * 64>(Vs, a.v + base, ld, j0, n);
+    tile_cols<NW * 64>(Kt, a.k + base, ld, j0, n);
+    __syncthreads();
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt) {
+      floatx16 st = zero16(), dp = zero16();
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        st = mfma(tile_frag(Ks, kt, col, s, half), qf[s], st);
+        dp = mfma(tile_frag(Vs, kt, col, s, half), dof[s], dp);
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int j = j0 + kt * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+        const float p = j < n ? exp2f(st[r] * c - lse2) : 0.f;
+        st[r] = p * (dp[r] - D);
+      }
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2) {
+        const Frag dsf = regs_to_frag(st, s2);
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt) acc[dt] = mfma(tileT_frag(Kt, dt, col, kt, s2, half), dsf, acc[dt]);
+      }
+    }
+  }
+  if (qi < n) {
+    bf16_t* row = a.dq + base + (long long)qi * ld;
+    store_accT(row, acc[0], 0, half, a.scale);
+    store_accT(row, acc[1], 1, half, a.scale);
+    if (half == 0) a.Dsum[srow + qi] = D;
+  }
+}
+
+// ---- backward, part 2: dK and dV; one wavefront per 32 keys, loop over query blocks
+template <int NW>
+__global__ __launch_bounds__(NW * 64) void sdpa_bwd_dkv_bf16(SdpaArgs a) {
+  __shared__ __attribute__((aligned(16))) bf16_t Qs[64 * kTs];
+  __shared__ __attribute__((aligned(16))) bf16_t Os[64 * kTs];
+  __shared__ __attribute__((aligned(16))) bf16_t Qt[64 * kTs];
+  __shared__ __attribute__((aligned(16))) bf16_t Ot[64 * kTs];
+  __shared__ float Ls[64], Ds[64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int col = lane & 31, half = lane >> 5;
+  const int b = blockIdx.z, h = blockIdx.y;
+  const int n = a.n;
+  const long long ld = a.d;
+  const long long base = (long long)b * n * ld + h * kDh;
+  const long long srow = ((long long)b * a.H + h) * n;
+  const int kj = blockIdx.x * (NW * 32) + wave * 32 + col;
+  Frag kf[4], vf[4];
+  row_frags(kf, a.k + base, ld, kj, n, half);
+  row_frags(vf, a.v + base, ld, kj, n, half);
+  const float c = a.scale * kLog2e;
+  floatx16 accK[2] = {zero16(), zero16()}, accV[2] = {zero16(), zero16()};
+  for (int i0 = 0; i0 < n; i0 += 64) {
+    __syncthreads();
+    tile_rows<NW * 64>(Qs, a.q + base, ld, i0, n);
+    tile_rows<NW * 64>(Os, a.dout + base, ld, i0, n);
+    tile_cols<NW * 64>(Qt, a.q + base, ld, i0, n);
+    tile_cols<NW * 64>(Ot, a.dout + base, ld, i0, n);
+    if (threadIdx.x < 64) {
+      const bool ok = i0 + (int)threadIdx.x < n;
+      Ls[threadIdx.x] = ok ? a.lse[srow + i0 + threadIdx.x] * kLog2e : INFINITY;
+      Ds[threadIdx.x] = ok ? a.Dsum[srow + i0 + threadIdx.x] : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int qt = 0; qt < 2; ++qt) {
+      floatx16 st = zero16(), dp = zero16();
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        st = mfma(tile_frag(Qs, qt, col, s, half), kf[s], st);     // S[query][key]
+        dp = mfma(tile_frag(Os, qt, col, s, half), vf[s], dp);     // dP[query][key]
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int iq = qt * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+        const float p = exp2f(st[r] * c - Ls[iq]);
+        st[r] = p;
+        dp[r] = p * (dp[r] - Ds[iq]);
+      }
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2) {
+        const Frag pf = regs_to_frag(st, s2);
+        const Frag dsf = regs_to_frag(dp, s2);
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt) {
+          accV[dt] = mfma(tileT_frag(Ot, dt, col, qt, s2, half), pf, accV[dt]);
+          accK[dt] = mfma(tileT_frag(Qt, dt, col, qt, s2, half), dsf, accK[dt]);
+        }
+      }
+    }
+  }
+  if (kj < n) {
+    bf16_t* rk = a.dk + base + (long long)kj * ld;
+    bf16_t* rv = a.dv + base + (long long)kj * ld;
+    store_accT(rk, accK[0], 0, half, a.scale);
+    store_accT(rk, accK[1], 1, half, a.scale);
+    store_accT(rv, accV[0], 0, half, 1.f);
+    store_accT(rv, accV[1], 1, half, 1.f);
+  }
+}
+
+// column sums of up to four bf16 [rows][d] matrices (bias gradients)
+struct ColSumBf16 {
+  const bf16_t* src[4];
+  float* dst[4];
+  long long rows;
+  int d;
+};
+__global__ __launch_bounds__(256) void colsum_bf16_kernel(ColSumBf16 a) {
+  const bf16_t* src = a.src[blockIdx.y];
+  float* dst = a.dst[blockIdx.y];
+  if (!dst) return;
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= a.d) return;
+  float s = 0.f;
+  for (long long r = 0; r < a.rows; ++r) s += bf2f(src[r * a.d + c]);
+  dst[c] = s;
+}
+
+template <typename F>
+int launch_core(vardrop_ctx* ctx, F kernel2, F kernel4, const SdpaArgs& a, int B, hipStream_t s) {
+  if (a.n <= 256) {
+    hipLaunchKernelGGL(kernel2, dim3(vd_ceil_div(a.n, 64), a.H, B), dim3(128), 0, s, a);
+  } else {
+    hipLaunchKernelGGL(kernel4, dim3(vd_ceil_div(a.n, 128), a.H, B), dim3(256), 0, s, a);
+  }
+  VD_LAUNCH_CHECK(ctx);
+  return VARDROP_OK;
+}
+
+}  // namespace
+
+// saved: q, k, v, o ([M][d] bf16 each, M = B*n) then lse fp32 [B][H][n]
+int vd_attn_fwd_bf16(vardrop_ctx* ctx, const void* xs, int B, int n, int d, int H,
+                     const void* const W[4], const void* const bias[4],
+                     void* y, void* saved, void* ws, hipStream_t s) {
+  (void)ws;
+  const long long M = (long long)B * n;
+  bf16_t* q = (bf16_t*)saved;
+  bf16_t* k = q + M * d;
+  bf16_t* v = k + M * d;
+  bf16_t* o = v + M * d;
+  float* lse = (float*)(o + M * d);
+  GemmBf16 g = {};
+  for (int z = 0; z < 3; ++z) {
+    g.A[z] = (const bf16_t*)xs;
+    g.B[z] = (const bf16_t*)W[z];
+    g.bias[z] = (const bf16_t*)bias[z];
+  }
+  g.C[0] = q; g.C[1] = k; g.C[2] = v;
+  g.lda = d; g.ldb = d; g.ldc = d;
+  g.M = (int)M; g.N = d; g.K = d; g.nseg = 1;
+  int rc = launch_gemm<true, false, bf16_t>(ctx, g, 3, s);
+  if (rc) return rc;
+  SdpaArgs a = {};
+  a.q = q; a.k = k; a.v = v; a.out = o; a.lse = lse;
+  a.n = n; a.d = d; a.H = H; a.scale = 1.0f / sqrtf((float)kDh);
+  rc = launch_core(ctx, sdpa_fwd_bf16<2>, sdpa_fwd_bf16<4>, a, B, s);
+  if (rc) return rc;
+  GemmBf16 go = {};
+  go.A[0] = o; go.B[0] = (const bf16_t*)W[3]; go.C[0] = y; go.bias[0] = (const bf16_t*)bias[3];
+  go.lda = d; go.ldb = d; go.ldc = d;
+  go.M = (int)M; go.N = d; go.K = d; go.nseg = 1;
+  return launch_gemm<true, false, bf16_t>(ctx, go, 1, s);
+}
+
+// ws: dO, dq, dk, dv ([M][d] bf16 each) then D fp32 [B][H][n]
+int vd_attn_bwd_bf16(vardrop_ctx* ctx, const void* dy, const void* xs, int B, int n, int d, int H,
+                     const void* const W[4], const void* saved, void* dxs,
+                     float* const dW[4], float* const db[4], void* ws, hipStream_t s) {
+  const long long M = (long long)B * n;
+  const bf16_t* q = (const bf16_t*)saved;
+  const bf16_t* k = q + M * d;
+  const bf16_t* v = k + M * d;
+  const bf16_t* o = v + M * d;
+  const float* lse = (const float*)(o + M * d);
+  bf16_t* dO = (bf16_t*)ws;
+  bf16_t* dq = dO + M * d;
+  bf16_t* dk = dq + M * d;
+  bf16_t* dv = dk + M * d;
+  float* D = (float*)(dv + M * d);
+  int rc;
+  {  // dO = dy Wo^T
+    GemmBf16 g = {};
+    g.A[0] = (const bf16_t*)dy; g.B[0] = (const bf16_t*)W[3]; g.C[0] = dO;
+    g.lda = d; g.ldb = d; g.ldc = d;
+    g.M = (int)M; g.N = d; g.K = d; g.nseg = 1;
+    if ((rc = launch_gemm<true, true, bf16_t>(ctx, g, 1, s))) return rc;
+  }
+  SdpaArgs a = {};
+  a.q = q; a.k = k; a.v = v; a.o = o; a.dout = dO; a.lse = const_cast<float*>(lse);
+  a.dq = dq; a.dk = dk; a.dv = dv; a.Dsum = D;
+  a.n = n; a.d = d; a.H = H; a.scale = 1.0f / sqrtf((float)kDh);
+  if ((rc = launch_core(ctx, sdpa_bwd_dq_bf16<2>, sdpa_bwd_dq_bf16<4>, a, B, s))) return rc;
+  if ((rc = launch_core(ctx, sdpa_bwd_dkv_bf16<2>, sdpa_bwd_dkv_bf16<4>, a, B, s))) return rc;
+  {  // dWo = o^T dy
+    GemmBf16 g = {};
+    g.A[0] = o; g.B[0] = (const bf16_t*)dy; g.C[0] = dW[3];
+    g.lda = d; g.ldb = d; g.ldc = d;
+    g.M = d; g.N = d; g.K = (int)M; g.nseg = 1;
+    if ((rc = launch_gemm<false, false, float>(ctx, g, 1, s))) return rc;
+  }
+  {  // dWq, dWk, dWv = xs^T dq, xs^T dk, xs^T dv
+    GemmBf16 g = {};
+    const bf16_t* grads[3] = {dq, dk, dv};
+    for (int z = 0; z < 3; ++z) {
+      g.A[z] = (const bf16_t*)xs; g.B[z] = grads[z]; g.C[z] = dW[z];
+    }
+    g.lda = d; g.ldb = d; g.ldc = d;
+    g.M = d; g.N = d; g.K = (int)M; g.nseg = 1;
+    if ((rc = launch_gemm<false, false, float>(ctx, g, 3, s))) return rc;
+  }
+  {  // dxs = dq Wq^T + dk Wk^T + dv Wv^T
+    GemmBf16 g = {};
+    const bf16_t* grads[3] = {dq, dk, dv};
+    for (int z = 0; z < 3; ++z) {
+      g.A[z] = grads[z]; g.B[z] = (const bf16_t*)W[z];
+    }
+    g.C[0] = dxs;
+    g.lda = d; g.ldb = d; g.ldc = d;
+    g.M = (int)M; g.N = d; g.K = d; g.nseg = 3;
+    if ((rc = launch_gemm<true, true, bf16_t>(ctx, g, 1, s))) return rc;
+  }
+  if (db[0] || db[1] || db[2] || db[3]) {
+    ColSumBf16 c = {};
+    c.src[0] = dq; c.src[1] = dk; c.src[2] = dv; c.src[3] = (const bf16_t*)dy;
+    for (int z = 0; z < 4; ++z) c.dst[z] = db[z];
+    c.rows = M; c.d = d;
+    hipLaunchKernelGGL(colsum_bf16_kernel, dim3(vd_ceil_div(d, 256), 4), dim3(256), 0, s, c);
+    VD_LAUNCH_CHECK(ctx);
+  }
+  return VARDROP_OK;
+}

@@ -1,0 +1,45 @@
+// Shared host-side declarations of libvardrop (context, error plumbing, small helpers).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+#include "../../include/vardrop.h"
+
+struct vardrop_ctx {
+  int device;
+  int last_hip_error;
+  float* twiddle;        // device: cos(2 pi j / L), j < L, then sin(2 pi j / L), j < L
+  int twiddle_L;         // L the table currently holds (0: none)
+  int lds_per_block;     // bytes of LDS one workgroup may use
+};
+
+static const int kMaxTwiddleL = 8192;
+
+#define VD_HIP(ctx, call)                                   \
+  do {                                                      \
+    hipError_t e__ = (call);                                \
+    if (e__ != hipSuccess) {                                \
+      (ctx)->last_hip_error = (int)e__;                     \
+      return VARDROP_EHIP;                                  \
+    }                                                       \
+  } while (0)
+
+#define VD_LAUNCH_CHECK(ctx) VD_HIP(ctx, hipGetLastError())
+
+static inline size_t vd_align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+static inline bool vd_aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
+static inline int vd_ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+// attention back ends (attn_f32.hip, attn_bf16.hip); argument checks are done by the caller
+int vd_attn_fwd_f32(vardrop_ctx*, const float* xs, int B, int n, int d, int H,
+                    const float* const W[4], const float* const bias[4],
+                    float* y, void* saved, void* ws, hipStream_t s);
+int vd_attn_bwd_f32(vardrop_ctx*, const float* dy, const float* xs, int B, int n, int d, int H,
+                    const float* const W[4], const void* saved, float* dxs,
+                    float* const dW[4], float* const db[4], void* ws, hipStream_t s);
+int vd_attn_fwd_bf16(vardrop_ctx*, const void* xs, int B, int n, int d, int H,
+                     const void* const W[4], const void* const bias[4],
+                     void* y, void* saved, void* ws, hipStream_t s);
+int vd_attn_bwd_bf16(vardrop_ctx*, const void* dy, const void* xs, int B, int n, int d, int H,
+                     const void* const W[4], const void* saved, void* dxs,
+                     float* const dW[4], float* const db[4], void* ws, hipStream_t s);

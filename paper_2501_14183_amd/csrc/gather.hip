@@ -1,0 +1,107 @@
+// Gather of the kept variate tokens and its adjoint (Sec. 3.1: only the selected tokens
+// enter the attention).  Pure data movement: every row is d * sizeof(elem) contiguous
+// bytes, moved with 16-byte accesses when the row size and the pointers allow it.
+#include "common.h"
+
+namespace {
+
+// out[b][i][:] = src[b][sel[i]][:].  One 16-byte (or `unit`-byte) chunk per thread.
+template <typename T>
+__global__ __launch_bounds__(256) void gather_kernel(const T* __restrict__ src, T* __restrict__ out,
+                                                    const int32_t* __restrict__ sel,
+                                                    int B, int N, int n_sel, int row_units) {
+  const long long total = (long long)B * n_sel * row_units;
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+       i += (long long)gridDim.x * blockDim.x) {
+    const int c = (int)(i % row_units);
+    const long long row = i / row_units;
+    const int j = (int)(row % n_sel);
+    const int b = (int)(row / n_sel);
+    const int n = sel[j];
+    T v = T();
+    if ((unsigned)n < (unsigned)N) v = src[((long long)b * N + n) * row_units + c];
+    out[i] = v;
+  }
+}
+
+// dst[b][n][:] = src[b][i][:] if sel[i] == n for some i (sel ascending), else 0.
+template <typename T>
+__global__ __launch_bounds__(256) void scatter_kernel(const T* __restrict__ src, T* __restrict__ dst,
+                                                     const int32_t* __restrict__ sel,
+                                                     int B, int N, int n_sel, int row_units) {
+  const long long total = (long long)B * N * row_units;
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+       i += (long long)gridDim.x * blockDim.x) {
+    const int c = (int)(i % row_units);
+    const long long row = i / row_units;
+    const int n = (int)(row % N);
+    const int b = (int)(row / N);
+    int lo = 0, hi = n_sel;                       // first position with sel[pos] >= n
+    while (lo < hi) {
+      const int mid = (lo + hi) >> 1;
+      if (sel[mid] < n) lo = mid + 1; else hi = mid;
+    }
+    T v = T();
+    if (lo < n_sel && sel[lo] == n) v = src[((long long)b * n_sel + lo) * row_units + c];
+    dst[i] = v;
+  }
+}
+
+struct alignas(16) Chunk16 { uint32_t w[4]; };
+
+int elem_size(int dtype) { return dtype == VARDROP_F32 ? 4 : (dtype == VARDROP_BF16 ? 2 : 0); }
+
+template <bool kScatter>
+int launch(vardrop_ctx* ctx, const void* src, void* dst, const int32_t* sel, int B, int N, int n_sel,
+           int d, int dtype, hipStream_t s) {
+  const int es = elem_size(dtype);
+  const long long row_bytes = (long long)d * es;
+  const long long rows = (long long)B * (kScatter ? N : n_sel);
+  if (rows == 0) return VARDROP_OK;
+  const bool wide = row_bytes % 16 == 0 && vd_aligned(src, 16) && vd_aligned(dst, 16);
+  const int unit = wide ? 16 : es;
+  const int row_units = (int)(row_bytes / unit);
+  const long long total = rows * row_units;
+  long long blocks = (total + 255) / 256;
+  if (blocks > 256 * 32) blocks = 256 * 32;
+  dim3 grid((unsigned)blocks), block(256);
+  if (wide) {
+    if (kScatter) hipLaunchKernelGGL(scatter_kernel<Chunk16>, grid, block, 0, s, (const Chunk16*)src, (Chunk16*)dst, sel, B, N, n_sel, row_units);
+    else hipLaunchKernelGGL(gather_kernel<Chunk16>, grid, block, 0, s, (const Chunk16*)src, (Chunk16*)dst, sel, B, N, n_sel, row_units);
+  } else if (es == 4) {
+    if (kScatter) hipLaunchKernelGGL(scatter_kernel<uint32_t>, grid, block, 0, s, (const uint32_t*)src, (uint32_t*)dst, sel, B, N, n_sel, row_units);
+    else hipLaunchKernelGGL(gather_kernel<uint32_t>, grid, block, 0, s, (const uint32_t*)src, (uint32_t*)dst, sel, B, N, n_sel, row_units);
+  } else {
+    if (kScatter) hipLaunchKernelGGL(scatter_kernel<uint16_t>, grid, block, 0, s, (const uint16_t*)src, (uint16_t*)dst, sel, B, N, n_sel, row_units);
+    else hipLaunchKernelGGL(gather_kernel<uint16_t>, grid, block, 0, s, (const uint16_t*)src, (uint16_t*)dst, sel, B, N, n_sel, row_units);
+  }
+  VD_LAUNCH_CHECK(ctx);
+  return VARDROP_OK;
+}
+
+int check(vardrop_ctx* ctx, int B, int N, int d, int dtype, int n_sel) {
+  if (!ctx) return VARDROP_EINVAL;
+  if (B < 0 || N < 0 || d < 1 || n_sel < 0 || n_sel > N) return VARDROP_EINVAL;
+  if (elem_size(dtype) == 0) return VARDROP_EINVAL;
+  return VARDROP_OK;
+}
+
+}  // namespace
+
+extern "C" int vardrop_gather(vardrop_ctx* ctx, const void* tokens, int B, int N, int d, int dtype,
+                              const int32_t* sel, int n_sel, void* out, void* stream) {
+  int rc = check(ctx, B, N, d, dtype, n_sel);
+  if (rc != VARDROP_OK) return rc;
+  if ((long long)B * n_sel == 0) return VARDROP_OK;
+  if (!tokens || !out || !sel) return VARDROP_EINVAL;
+  return launch<false>(ctx, tokens, out, sel, B, N, n_sel, d, dtype, (hipStream_t)stream);
+}
+
+extern "C" int vardrop_scatter(vardrop_ctx* ctx, const void* dxs, int B, int N, int d, int dtype,
+                               const int32_t* sel, int n_sel, void* dtokens, void* stream) {
+  int rc = check(ctx, B, N, d, dtype, n_sel);
+  if (rc != VARDROP_OK) return rc;
+  if ((long long)B * N == 0) return VARDROP_OK;
+  if (!dtokens || (n_sel > 0 && (!dxs || !sel))) return VARDROP_EINVAL;
+  return launch<true>(ctx, dxs, dtokens, sel, B, N, n_sel, d, dtype, (hipStream_t)stream);
+}

@@ -1,0 +1,281 @@
+// k-dominant frequency hashing (Alg. 1, Def. 1) as one fused gfx950 kernel.
+//
+// Mapping.  A wavefront owns a block of 32 (variate, window) rows: all B windows of one
+// variate when B >= 32 (several blocks in sequence when B > 32), or 32/Bp variates with
+// Bp = B rounded up to a power of two when B < 32.  The block's windows are staged in LDS
+// (time-major, padded), and the amplitude spectrum on the candidate bins is a dense
+// contraction of the folded window with a cosine / sine table:
+//     Re X_f =  x[0] + (-1)^f x[L/2] + sum_{0<t<L/2} (x[t] + x[L-t]) cos(2 pi f t / L)
+//     Im X_f = -sum_{0<t<L/2} (x[t] - x[L-t]) sin(2 pi f t / L)
+// evaluated with the fp32 matrix instruction v_mfma_f32_32x32x2_f32 (rows = windows,
+// columns = 32 bins, contraction = folded time).  The bins above the cut-off are never
+// produced (Alg. 1 step 2).  Amplitudes are summed over the batch in ascending window
+// order in fp32 (step 3), and the ranked top-k (step 4) is k rounds of a wavefront
+// arg-max with the lower bin winning ties; the hash is the tuple in radix R (step 5).
+#include "common.h"
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+namespace {
+
+constexpr int kTilePad = 33;     // LDS row stride of the time-major tile (32 rows + 1)
+constexpr int kMaxBinsPerLane = 8;
+
+__global__ void twiddle_kernel(float* tw, int L) {
+  int j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (j < L) {
+    double s, c;
+    sincospi(2.0 * (double)j / (double)L, &s, &c);
+    tw[j] = (float)c;
+    tw[L + j] = (float)s;
+  }
+}
+
+struct KdfhArgs {
+  const float* x;
+  const float* tw;
+  int32_t* topk;
+  uint64_t* hash;
+  float* abar;
+  long long sb, sn;
+  int B, N, L, k, f_min, F;
+  int log2_rpv;   // rows per variate inside a 32-row block = 1 << log2_rpv
+  int nrb;        // 32-row blocks per variate group (> 1 only when B > 32)
+  int vec;        // rows can be read as aligned float4
+  float inv_B;
+};
+
+__global__ __launch_bounds__(64) void kdfh_kernel(KdfhArgs a) {
+  extern __shared__ float lds[];
+  const int L = a.L, F = a.F;
+  const int lane = threadIdx.x;
+  const int col = lane & 31, half = lane >> 5;
+  const int rpv = 1 << a.log2_rpv;
+  const int Vb = 32 >> a.log2_rpv;               // variates per block
+  const int n0 = blockIdx.x * Vb;
+  float* cosT = lds;
+  float* sinT = lds + L;
+  float* tile = sinT + L;                        // [L][kTilePad]
+  float* ampT = tile + L * kTilePad;             // [32][kTilePad]
+  float* asum = ampT + 32 * kTilePad;            // [Vb][F]
+
+  for (int i = lane; i < 2 * L; i += 64) lds[i] = a.tw[i];
+  for (int i = lane; i < Vb * F; i += 64) asum[i] = 0.f;
+
+  const int Lh = L >> 1;
+  const int Sc = (Lh + 2) >> 1;                  // cosine steps: t = 0 .. floor(L/2), two per step
+  const int Ss = ((L - 1) / 2 + 1) >> 1;         // sine steps:   t = 1 .. ceil(L/2)-1
+  const int nct = (F + 31) >> 5;
+
+  for (int rb = 0; rb < a.nrb; ++rb) {
+    __syncthreads();
+    // ---- stage 32 windows in LDS, time-major: tile[t][row]
+    if (a.vec) {
+      const int L4 = L >> 2;
+      const int items = 32 * L4;
+      for (int base = 0; base < items; base += 64 * 8) {
+        float4 v[8];
+        int rr[8], cc[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const int i = base + u * 64 + lane;
+          rr[u] = -1;
+          cc[u] = 0;
+          v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+          if (i < items) {
+            const int r = i / L4;
+            const int c = i - r * L4;
+            rr[u] = r;
+            cc[u] = c;
+            const int n = n0 + (r >> a.log2_rpv);
+            const int b = rb * 32 + (r & (rpv - 1));
+            if (n < a.N && b < a.B)
+              v[u] = *reinterpret_cast<const float4*>(a.x + (long long)b * a.sb + (long long)n * a.sn + 4 * c);
+          }
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          if (rr[u] >= 0) {
+            float* p = tile + (4 * cc[u]) * kTilePad + rr[u];
+            p[0] = v[u].x;
+            p[kTilePad] = v[u].y;
+            p[2 * kTilePad] = v[u].z;
+            p[3 * kTilePad] = v[u].w;
+          }
+        }
+      }
+    } else {
+      for (int r = 0; r < 32; ++r) {
+        const int n = n0 + (r >> a.log2_rpv);
+        const int b = rb * 32 + (r & (rpv - 1));
+        const bool ok = n < a.N && b < a.B;
+        const float* p = a.x + (long long)b * a.sb + (long long)n * a.sn;
+        for (int t = lane; t < L; t += 64) tile[t * kTilePad + r] = ok ? p[t] : 0.f;
+      }
+    }
+    __syncthreads();
+
+    // ---- spectrum of the 32 rows, 32 bins at a time
+    for (int ct = 0; ct < nct; ++ct) {
+      const int f = a.f_min + ct * 32 + col;
+      const int twof = (2 * f) % L;
+      int mc = (f * half) % L;
+      int ms = (f * (1 + half)) % L;
+      floatx16 re = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      floatx16 im = re;
+      for (int s = 0; s < Sc; ++s) {
+        const int tc = 2 * s + half;
+        float ac = 0.f;
+        if (tc <= Lh) {
+          ac = tile[tc * kTilePad + col];
+          if (tc != 0 && 2 * tc != L) ac += tile[(L - tc) * kTilePad + col];
+        }
+        const float bc = cosT[mc];
+        mc += twof;
+        if (mc >= L) mc -= L;
+        re = __builtin_amdgcn_mfma_f32_32x32x2f32(ac, bc, re, 0, 0, 0);
+        if (s < Ss) {
+          const int ts = tc + 1;
+          float as = 0.f;
+          if (2 * ts < L) as = tile[ts * kTilePad + col] - tile[(L - ts) * kTilePad + col];
+          const float bs = sinT[ms];
+          ms += twof;
+          if (ms >= L) ms -= L;
+          im = __builtin_amdgcn_mfma_f32_32x32x2f32(as, bs, im, 0, 0, 0);
+        }
+      }
+      // accumulator register r of a lane holds row 8*(r/4) + 4*half + r%4, column col
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = 8 * (r >> 2) + 4 * half + (r & 3);
+        ampT[row * kTilePad + col] = sqrtf(re[r] * re[r] + im[r] * im[r]);
+      }
+      __syncthreads();
+      const int bin = ct * 32 + col;
+      for (int v = half; v < Vb; v += 2) {
+        float sum = 0.f;
+        for (int b = 0; b < rpv; ++b) sum += ampT[(v * rpv + b) * kTilePad + col];
+        if (bin < F) asum[v * F + bin] += sum;
+      }
+      __syncthreads();
+    }
+  }
+
+  // ---- ranked top-k and hash, one variate after the other
+  const unsigned long long R = (unsigned long long)(L / 2 + 1);
+  for (int v = 0; v < Vb; ++v) {
+    const int n = n0 + v;
+    if (n >= a.N) break;
+    float vals[kMaxBinsPerLane];
+#pragma unroll
+    for (int j = 0; j < kMaxBinsPerLane; ++j) {
+      const int idx = lane + 64 * j;
+      vals[j] = idx < F ? asum[v * F + idx] : -2.f;
+    }
+    unsigned long long h = 0;
+    for (int r = 0; r < a.k; ++r) {
+      float best = -3.f;
+      int bi = 0x7fffffff;
+#pragma unroll
+      for (int j = 0; j < kMaxBinsPerLane; ++j) {
+        if (vals[j] > best) {
+          best = vals[j];
+          bi = lane + 64 * j;
+        }
+      }
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) {
+        const float ov = __shfl_xor(best, off, 64);
+        const int oi = __shfl_xor(bi, off, 64);
+        if (ov > best || (ov == best && oi < bi)) {
+          best = ov;
+          bi = oi;
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < kMaxBinsPerLane; ++j)
+        if (bi == lane + 64 * j) vals[j] = -2.f;
+      const int fsel = a.f_min + bi;
+      if (lane == 0) a.topk[(long long)n * a.k + r] = fsel;
+      h = h * R + (unsigned long long)(unsigned)fsel;
+    }
+    if (lane == 0) a.hash[n] = h;
+    if (a.abar)
+      for (int idx = lane; idx < F; idx += 64) a.abar[(long long)n * F + idx] = asum[v * F + idx] * a.inv_B;
+  }
+}
+
+size_t kdfh_lds_bytes(int L, int F, int Vb) {
+  return sizeof(float) * ((size_t)2 * L + (size_t)L * kTilePad + 32 * kTilePad + (size_t)Vb * F);
+}
+
+}  // namespace
+
+extern "C" size_t vardrop_hash_workspace_bytes(int, int, int, int, int, int) { return 0; }
+
+extern "C" int vardrop_hash(vardrop_ctx* ctx, const float* x, int B, int N, int L,
+                            int64_t sb, int64_t sn, int64_t st, int k, int f_min, int f_max,
+                            int32_t* topk, uint64_t* hash, float* abar,
+                            void* ws, size_t ws_bytes, void* stream) {
+  (void)ws;
+  (void)ws_bytes;
+  if (!ctx) return VARDROP_EINVAL;
+  if (B < 1 || N < 0 || L < 2) return VARDROP_EINVAL;
+  if (f_min < 0 || f_max < f_min || f_max > L / 2) return VARDROP_EINVAL;
+  const int F = f_max - f_min + 1;
+  if (k < 1 || k > F) return VARDROP_EINVAL;
+  {
+    const unsigned long long R = (unsigned long long)(L / 2 + 1);
+    unsigned long long p = 1;
+    for (int j = 0; j < k; ++j) {
+      if (p > (1ull << 63) / R) return VARDROP_EINVAL;
+      p *= R;
+    }
+    if (p >= (1ull << 63)) return VARDROP_EINVAL;
+  }
+  if (N == 0) return VARDROP_OK;
+  if (!x || !topk || !hash) return VARDROP_EINVAL;
+  if (sb < 0 || sn < 0) return VARDROP_EINVAL;
+  if (st != 1) return VARDROP_EUNSUPPORTED;
+  if (L > 1024 || F > 64 * kMaxBinsPerLane) return VARDROP_EUNSUPPORTED;
+
+  int log2_rpv = 5, nrb = vd_ceil_div(B, 32);
+  if (B < 32) {
+    log2_rpv = 0;
+    while ((1 << log2_rpv) < B) ++log2_rpv;
+    nrb = 1;
+  }
+  const int Vb = 32 >> log2_rpv;
+  const size_t lds = kdfh_lds_bytes(L, F, Vb);
+  if (lds > (size_t)ctx->lds_per_block) return VARDROP_EUNSUPPORTED;
+
+  hipStream_t s = (hipStream_t)stream;
+  if (ctx->twiddle_L != L) {
+    hipLaunchKernelGGL(twiddle_kernel, dim3(vd_ceil_div(L, 256)), dim3(256), 0, s, ctx->twiddle, L);
+    VD_LAUNCH_CHECK(ctx);
+    ctx->twiddle_L = L;
+  }
+  KdfhArgs a;
+  a.x = x;
+  a.tw = ctx->twiddle;
+  a.topk = topk;
+  a.hash = hash;
+  a.abar = abar;
+  a.sb = sb;
+  a.sn = sn;
+  a.B = B;
+  a.N = N;
+  a.L = L;
+  a.k = k;
+  a.f_min = f_min;
+  a.F = F;
+  a.log2_rpv = log2_rpv;
+  a.nrb = nrb;
+  a.vec = (L % 4 == 0 && sb % 4 == 0 && sn % 4 == 0 && vd_aligned(x, 16)) ? 1 : 0;
+  a.inv_B = 1.0f / (float)B;
+  if (lds > 65536)
+    VD_HIP(ctx, hipFuncSetAttribute((const void*)kdfh_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+  hipLaunchKernelGGL(kdfh_kernel, dim3(vd_ceil_div(N, Vb)), dim3(64), lds, s, a);
+  VD_LAUNCH_CHECK(ctx);
+  return VARDROP_OK;
+}

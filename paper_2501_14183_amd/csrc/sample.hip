@@ -1,0 +1,238 @@
+// Grouping by hash and stratified sampling (Sec. 3.3, Eq. 1-2) in one workgroup.
+//
+// N <= 8192 variates fit the LDS of one compute unit, so a single workgroup does the whole
+// step without global round trips:
+//   1. bitonic sort of (hash, n)            -> equal hashes become contiguous segments
+//   2. flag scan over the segments          -> dense group id (ascending hash), start, size
+//   3. bitonic sort of (group, u[n], n)     -> members of a group in random-key order,
+//      u[n] from Philox4x32-10, counter (n, 0, step_lo, step_hi), key (seed_lo, seed_hi)
+//   4. keep the first n_i of every segment  -> flag per variate
+//   5. flag scan in variate order           -> sel ascending, N'
+#include "common.h"
+
+namespace {
+
+constexpr int kMaxN = 8192;
+
+__device__ inline void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                     uint32_t k0, uint32_t k1, uint32_t& r0, uint32_t& r1) {
+  const uint32_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u;
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint32_t hi0 = __umulhi(M0, c0), lo0 = M0 * c0;
+    const uint32_t hi1 = __umulhi(M1, c2), lo1 = M1 * c2;
+    c0 = hi1 ^ c1 ^ k0;
+    c1 = lo1;
+    c2 = hi0 ^ c3 ^ k1;
+    c3 = lo0;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  r0 = c0;
+  r1 = c1;
+}
+
+// order of sort 1: (key, payload) lexicographic; payload = variate index (padding: >= N)
+__device__ inline bool less_hash(uint64_t ka, uint32_t pa, uint64_t kb, uint32_t pb) {
+  return ka < kb || (ka == kb && pa < pb);
+}
+// order of sort 2: payload = group << 16 | n; (group, key, n) lexicographic
+__device__ inline bool less_group(uint64_t ka, uint32_t pa, uint64_t kb, uint32_t pb) {
+  const uint32_t ga = pa >> 16, gb = pb >> 16;
+  if (ga != gb) return ga < gb;
+  if (ka != kb) return ka < kb;
+  return (pa & 0xffffu) < (pb & 0xffffu);
+}
+
+template <bool kByGroup>
+__device__ void bitonic_sort(uint64_t* key, uint32_t* pay, int npad) {
+  const int tid = threadIdx.x, nt = blockDim.x;
+  for (int size = 2; size <= npad; size <<= 1) {
+    for (int stride = size >> 1; stride > 0; stride >>= 1) {
+      __syncthreads();
+      for (int p = tid; p < (npad >> 1); p += nt) {
+        const int lo = ((p & ~(stride - 1)) << 1) | (p & (stride - 1));
+        const int hi = lo + stride;
+        const bool up = (lo & size) == 0;
+        const uint64_t ka = key[lo], kb = key[hi];
+        const uint32_t pa = pay[lo], pb = pay[hi];
+        const bool b_lt_a = kByGroup ? less_group(kb, pb, ka, pa) : less_hash(kb, pb, ka, pa);
+        if (b_lt_a == up) {
+          key[lo] = kb;
+          key[hi] = ka;
+          pay[lo] = pb;
+          pay[hi] = pa;
+        }
+      }
+    }
+  }
+  __syncthreads();
+}
+
+// Exclusive prefix sum over vals[0..count) (count <= per * blockDim.x), in place; returns the total
+// to every thread.  `wsum` holds one slot per wavefront plus one.
+__device__ int block_exclusive_scan(int* vals, int count, int* wsum) {
+  const int tid = threadIdx.x, nt = blockDim.x;
+  const int per = (count + nt - 1) / nt;
+  const int begin = tid * per;
+  int local = 0;
+  for (int i = 0; i < per; ++i)
+    if (begin + i < count) local += vals[begin + i];
+  int incl = local;
+  const int lane = tid & 63, wave = tid >> 6;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const int o = __shfl_up(incl, off, 64);
+    if (lane >= off) incl += o;
+  }
+  if (lane == 63) wsum[wave] = incl;
+  __syncthreads();
+  if (tid == 0) {
+    int run = 0;
+    const int nw = (nt + 63) >> 6;
+    for (int w = 0; w < nw; ++w) {
+      const int t = wsum[w];
+      wsum[w] = run;
+      run += t;
+    }
+    wsum[nw] = run;
+  }
+  __syncthreads();
+  int run = wsum[wave] + incl - local;
+  const int total = wsum[(nt + 63) >> 6];
+  for (int i = 0; i < per; ++i)
+    if (begin + i < count) {
+      const int t = vals[begin + i];
+      vals[begin + i] = run;
+      run += t;
+    }
+  __syncthreads();
+  return total;
+}
+
+struct SampleArgs {
+  const uint64_t* hash;
+  int32_t* group_id;
+  int32_t* sel;
+  int32_t* counts;
+  int N, npad;
+  uint32_t gs, num, den;
+  uint32_t seed_lo, seed_hi, step_lo, step_hi;
+};
+
+__global__ __launch_bounds__(1024) void sample_kernel(SampleArgs a) {
+  extern __shared__ unsigned char smem[];
+  const int N = a.N, npad = a.npad;
+  uint64_t* key = reinterpret_cast<uint64_t*>(smem);                   // [npad]
+  uint32_t* pay = reinterpret_cast<uint32_t*>(key + npad);             // [npad]
+  int* scan = reinterpret_cast<int*>(pay + npad);                      // [npad]: flags -> ids / offsets
+  int* wsum = scan + npad;                                             // [20]
+  uint16_t* gstart = reinterpret_cast<uint16_t*>(wsum + 20);           // [npad + 1], values <= 8192
+  const int tid = threadIdx.x, nt = blockDim.x;
+
+  for (int i = tid; i < npad; i += nt) {
+    key[i] = i < N ? a.hash[i] : ~0ull;
+    pay[i] = (uint32_t)i;
+  }
+  bitonic_sort<false>(key, pay, npad);
+
+  // segment heads -> dense group ids
+  for (int p = tid; p < N; p += nt) scan[p] = (p == 0 || key[p] != key[p - 1]) ? 1 : 0;
+  __syncthreads();
+  const int G = block_exclusive_scan(scan, N, wsum);    // scan[p] = heads before p
+  for (int p = tid; p < N; p += nt) {
+    const bool head = (p == 0 || key[p] != key[p - 1]);
+    const int g = scan[p] - (head ? 0 : 1);              // heads at or before p, minus one
+    if (head) gstart[g] = (uint16_t)p;
+    scan[p] = g;
+  }
+  if (tid == 0) gstart[G] = (uint16_t)N;
+  __syncthreads();
+  for (int p = tid; p < N; p += nt) {
+    const uint32_t n = pay[p];
+    const int g = scan[p];
+    a.group_id[n] = g;
+    uint32_t r0, r1;
+    philox4x32_10(n, 0u, a.step_lo, a.step_hi, a.seed_lo, a.seed_hi, r0, r1);
+    key[p] = ((uint64_t)r0 << 32) | r1;
+    pay[p] = ((uint32_t)g << 16) | n;
+  }
+  for (int p = N + tid; p < npad; p += nt) {
+    key[p] = ~0ull;
+    pay[p] = 0xffffffffu;                                 // group 65535 sorts after every real group
+  }
+  bitonic_sort<true>(key, pay, npad);
+
+  // keep the first n_i members of every segment; flags indexed by variate
+  for (int p = tid; p < N; p += nt) {
+    const uint32_t g = pay[p] >> 16, n = pay[p] & 0xffffu;
+    const uint32_t size = (uint32_t)gstart[g + 1] - (uint32_t)gstart[g];
+    uint64_t by_ratio = ((uint64_t)size * a.num + a.den - 1) / a.den;
+    if (by_ratio < 1) by_ratio = 1;
+    uint32_t keep = by_ratio < size ? (uint32_t)by_ratio : size;
+    if (a.gs != 0 && keep > a.gs) keep = a.gs;
+    scan[n] = ((uint32_t)p - (uint32_t)gstart[g] < keep) ? 1 : 0;
+  }
+  __syncthreads();
+  // the flags are needed after the scan as well: keep a copy in the payload array
+  for (int n = tid; n < N; n += nt) pay[n] = (uint32_t)scan[n];
+  __syncthreads();
+  const int n_sel = block_exclusive_scan(scan, N, wsum);
+  for (int n = tid; n < N; n += nt)
+    if (pay[n]) a.sel[scan[n]] = n;
+  if (tid == 0) {
+    a.counts[0] = n_sel;
+    a.counts[1] = G;
+  }
+}
+
+int next_pow2(int v) {
+  int p = 1;
+  while (p < v) p <<= 1;
+  return p;
+}
+
+}  // namespace
+
+extern "C" size_t vardrop_sample_workspace_bytes(int) { return 0; }
+
+extern "C" int vardrop_sample(vardrop_ctx* ctx, const uint64_t* hash, int N,
+                              uint32_t gs, uint32_t ratio_num, uint32_t ratio_den,
+                              uint64_t seed, uint64_t step,
+                              int32_t* group_id, int32_t* sel, int32_t* counts, int32_t* counts_host,
+                              void* ws, size_t ws_bytes, void* stream) {
+  (void)ws;
+  (void)ws_bytes;
+  if (!ctx || !hash || !group_id || !sel || !counts) return VARDROP_EINVAL;
+  if (N < 1) return VARDROP_EINVAL;
+  if (ratio_den == 0 || ratio_num > ratio_den) return VARDROP_EINVAL;
+  if (N > kMaxN) return VARDROP_EUNSUPPORTED;
+  int npad = next_pow2(N);
+  if (npad < 128) npad = 128;
+  const size_t lds = (size_t)npad * 16 + 20 * 4 + (size_t)(npad + 1) * 2 + 14;
+  if (lds > (size_t)ctx->lds_per_block) return VARDROP_EUNSUPPORTED;
+  int threads = npad / 2;
+  if (threads > 1024) threads = 1024;
+  SampleArgs a;
+  a.hash = hash;
+  a.group_id = group_id;
+  a.sel = sel;
+  a.counts = counts;
+  a.N = N;
+  a.npad = npad;
+  a.gs = gs;
+  a.num = ratio_num;
+  a.den = ratio_den;
+  a.seed_lo = (uint32_t)seed;
+  a.seed_hi = (uint32_t)(seed >> 32);
+  a.step_lo = (uint32_t)step;
+  a.step_hi = (uint32_t)(step >> 32);
+  hipStream_t s = (hipStream_t)stream;
+  if (lds > 65536)
+    VD_HIP(ctx, hipFuncSetAttribute((const void*)sample_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+  hipLaunchKernelGGL(sample_kernel, dim3(1), dim3(threads), lds, s, a);
+  VD_LAUNCH_CHECK(ctx);
+  if (counts_host)
+    VD_HIP(ctx, hipMemcpyAsync(counts_host, counts, 2 * sizeof(int32_t), hipMemcpyDeviceToHost, s));
+  return VARDROP_OK;
+}

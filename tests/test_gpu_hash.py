@@ -1,0 +1,146 @@
+"""GPU k-DFH (vardrop_hash) against the fp64 oracle: ranked top-k and hash bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from oracle import kdfh as o_kdfh
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def vd():
+    import paper_2501_14183_amd as m
+    return m
+
+
+@pytest.fixture(scope="module")
+def ctx(vd):
+    return vd.Context(0)
+
+
+def run(vd, ctx, x, k, f_min=1, f_max=None):
+    xt = x if isinstance(x, torch.Tensor) else torch.from_numpy(np.ascontiguousarray(x)).cuda()
+    topk, hsh, abar = vd.vardrop_hash(ctx, xt, k, f_min, f_max, want_abar=True)
+    torch.cuda.synchronize()
+    return topk.cpu().numpy().astype(np.int64), hsh.cpu().numpy().view(np.uint64), abar.cpu().numpy()
+
+
+def compare(vd, ctx, x, k, f_min=1, f_max=None):
+    L = x.shape[-1]
+    fm = o_kdfh.default_cutoff(L) if f_max is None else f_max
+    want_topk, want_hash, want_abar = o_kdfh.kdfh(x, k, f_min, fm)
+    topk, hsh, abar = run(vd, ctx, x, k, f_min, f_max)
+    scale = np.abs(want_abar).max(axis=1, keepdims=True)
+    scale[scale == 0] = 1.0
+    assert np.all(np.abs(abar - want_abar) <= 2e-5 * scale)
+    ok = o_kdfh.gap_ok(want_abar, k)
+    flips = int((topk != want_topk).any(axis=1).sum())
+    flips_screened = int((topk[ok] != want_topk[ok]).any(axis=1).sum())
+    return topk, hsh, want_topk, want_hash, flips, flips_screened, ok
+
+
+@pytest.mark.parametrize("name", wl.ORDER)
+def test_five_workloads_bit_exact(vd, ctx, name):
+    from util_gpu import workload_inputs
+    w, x, info, want_topk, want_hash, want_abar = workload_inputs(name)
+    assert info["unresolved"] == 0
+    topk, hsh, abar = run(vd, ctx, x, w.k)
+    assert np.array_equal(topk, want_topk)
+    assert np.array_equal(hsh, want_hash)
+    scale = np.abs(want_abar).max(axis=1, keepdims=True)
+    assert np.all(np.abs(abar - want_abar) <= 2e-5 * scale)
+    # the unscreened draw of the same workload: rank flips may only occur below the 1e-3 gap
+    w, xu, _, tu, hu, au = workload_inputs(name, screened=False)
+    t2, h2, _ = run(vd, ctx, xu, w.k)
+    ok = o_kdfh.gap_ok(au, w.k)
+    assert np.array_equal(t2[ok], tu[ok])
+    below = int((t2[~ok] != tu[~ok]).any(axis=1).sum())
+    print("%s: %d variates below the gap, %d rank flips among them" % (name, int((~ok).sum()), below))
+
+
+def test_planted_sinusoids_and_order(vd, ctx):
+    L = 96
+    t = np.arange(L)
+    x = np.zeros((4, 3, L), dtype=np.float32)
+    for n, (fs, amps) in enumerate([((4, 12, 8), (3, 2, 1)), ((12, 4, 8), (3, 2, 1)), ((5, 24, 1), (1.0, 0.8, 0.5))]):
+        for b in range(4):
+            x[b, n] = sum(a * np.sin(2 * np.pi * f * t / L + 0.37 * b + f) for f, a in zip(fs, amps))
+    topk, hsh, _ = run(vd, ctx, x, 3)
+    assert topk.tolist() == [[4, 12, 8], [12, 4, 8], [5, 24, 1]]
+    assert hsh[0] != hsh[1] and int(hsh[0]) == (4 * 49 + 12) * 49 + 8
+
+
+def test_flat_variate_hashes_to_lowest_bins(vd, ctx):
+    topk, hsh, abar = run(vd, ctx, np.zeros((8, 5, 96), dtype=np.float32), 3)
+    assert topk.tolist() == [[1, 2, 3]] * 5 and np.all(abar == 0)
+    topk, _, _ = run(vd, ctx, np.zeros((2, 3, 512), dtype=np.float32), 5)
+    assert topk.tolist() == [[1, 2, 3, 4, 5]] * 3
+
+
+@pytest.mark.parametrize("B,N,L,k", [(1, 7, 96, 3), (5, 13, 96, 3), (32, 3, 96, 2), (33, 5, 96, 3), (70, 4, 64, 4),
+                                      (3, 40, 97, 3), (6, 9, 98, 2), (2, 5, 10, 2), (4, 3, 2, 1), (16, 37, 336, 4),
+                                      (8, 11, 512, 5), (33, 2, 1024, 6)])
+def test_shapes_and_ragged_edges(vd, ctx, B, N, L, k):
+    rng = np.random.default_rng(B * 1000 + L)
+    x = rng.standard_normal((B, N, L)).astype(np.float32)
+    t = np.arange(L)
+    for n in range(N):                                   # a few dominant lines on top of the noise
+        for j, f in enumerate(rng.choice(np.arange(1, max(2, L // 4)), size=min(3, max(1, L // 4 - 1)), replace=False)):
+            x[:, n] += (4.0 / (1 + j)) * np.sin(2 * np.pi * f * t / L + rng.uniform(0, 6, size=(B, 1))).astype(np.float32)
+    topk, hsh, want_topk, want_hash, flips, flips_screened, ok = compare(vd, ctx, x, k)
+    assert flips_screened == 0
+    assert np.array_equal(hsh[ok], want_hash[ok])
+    assert flips <= (~ok).sum()
+
+
+def test_candidate_range_parameters(vd, ctx):
+    rng = np.random.default_rng(3)
+    x = (rng.standard_normal((4, 6, 96)) + 2.0).astype(np.float32)        # large mean: bin 0 dominates when allowed
+    topk, hsh, want_topk, want_hash, flips, fs, ok = compare(vd, ctx, x, 3, f_min=0, f_max=48)
+    assert fs == 0 and np.all(topk[:, 0] == 0)
+    topk, hsh, want_topk, want_hash, flips, fs, ok = compare(vd, ctx, x, 10, f_min=7, f_max=16)
+    assert fs == 0 and topk.min() >= 7 and topk.max() <= 16 and sorted(topk[0].tolist()) == list(range(7, 17))
+
+
+def test_strided_input_and_determinism(vd, ctx):
+    rng = np.random.default_rng(5)
+    big = torch.from_numpy(rng.standard_normal((6, 20, 128)).astype(np.float32)).cuda()
+    view = big[1:5, 2:19, :96]                                         # non-contiguous, unaligned rows
+    want = o_kdfh.kdfh(view.cpu().numpy(), 3)
+    topk, hsh, _ = run(vd, ctx, view, 3)
+    ok = o_kdfh.gap_ok(want[2], 3)
+    assert np.array_equal(topk[ok], want[0][ok])
+    again = run(vd, ctx, view, 3)
+    assert np.array_equal(topk, again[0]) and np.array_equal(hsh, again[1])
+
+
+def test_window_order_and_scale_invariance(vd, ctx):
+    from util_gpu import workload_inputs
+    w, x, _, want_topk, _, _ = workload_inputs("electricity")
+    topk, _, _ = run(vd, ctx, x[::-1].copy(), w.k)
+    assert np.array_equal(topk, want_topk)
+    topk, _, _ = run(vd, ctx, (x * np.float32(8.0)), w.k)              # exact power-of-two scaling
+    assert np.array_equal(topk, want_topk)
+
+
+def test_error_codes(vd, ctx):
+    x = torch.zeros((2, 3, 96), device="cuda")
+    for kwargs, code in [(dict(k=30), -1), (dict(k=0), -1), (dict(k=3, f_min=5, f_max=4), -1),
+                         (dict(k=3, f_max=49), -1)]:
+        with pytest.raises(vd.VarDropError) as e:
+            vd.vardrop_hash(ctx, x, **kwargs)
+        assert e.value.code == code
+    with pytest.raises(vd.VarDropError) as e:
+        vd.vardrop_hash(ctx, torch.zeros((2, 3, 2048), device="cuda"), 3)
+    assert e.value.code == -4
+    with pytest.raises(vd.VarDropError) as e:                      # 16 variates x 257 bins of sums + tile > LDS
+        vd.vardrop_hash(ctx, torch.zeros((2, 2, 1024), device="cuda"), 6)
+    assert e.value.code == -4
+    with pytest.raises(vd.VarDropError) as e:
+        vd.vardrop_hash(ctx, torch.zeros((2, 96, 3), device="cuda").transpose(1, 2), 3)      # time stride != 1
+    assert e.value.code == -4
+    with pytest.raises(vd.VarDropError) as e:
+        vd.vardrop_hash(ctx, torch.zeros((1, 1, 1024), device="cuda"), 8, 1, 512)          # 513**8 >= 2**63
+    assert e.value.code == -1
