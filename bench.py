@@ -1,0 +1,222 @@
+#!/usr/bin/env python3
+"""Benchmark of the VarDrop training hot path on one MI355X.
+
+One step = vardrop_hash -> vardrop_sample -> (read N') -> vardrop_gather -> vardrop_attn_fwd
+-> vardrop_attn_bwd over one batch of synthetic windows and tokens that already sit in HBM.
+Prints ONE JSON line: steps/s, the roofline figure of the dominant kernel, and the CPU
+oracle timed on a bounded sample of the same workload.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload traffic] [--no-cpu-baseline]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_FP32_TFLOPS = 157.3      # MI355X fp32 vector
+PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+
+
+def algorithmic_work(w, n):
+    """Per launch: kernel name -> (bound, algorithmic bytes or flops).  n = kept tokens N'.
+
+    Bytes are what the method must move once (inputs read once, outputs written once); flops are
+    those of the contractions the method defines (2 per multiply-add).  The second evaluation of
+    S = Q K^T and dP = dO V^T inside the two-kernel backward is not counted as useful work.
+    """
+    B, N, L, d = w.B, w.N, w.L, w.d
+    M = B * n
+    es = 2 if w.dtype == "bf16" else 4
+    mm = "mfma" if w.dtype == "bf16" else "alu"
+    return {
+        "hash": ("hbm", 4.0 * B * N * L),
+        "sample": ("hbm", 8.0 * N + 4.0 * N + 4.0 * n + 8),
+        "gather": ("hbm", 2.0 * M * d * es),
+        "scatter": ("hbm", (M + B * N) * d * es),
+        "gemm_qkv": (mm, 6.0 * M * d * d),
+        "sdpa_fwd": (mm, 4.0 * B * n * n * d),
+        "gemm_out": (mm, 2.0 * M * d * d),
+        "gemm_do": (mm, 2.0 * M * d * d),
+        "sdpa_bwd_dq": (mm, 4.0 * B * n * n * d),
+        "sdpa_bwd_dkv": (mm, 6.0 * B * n * n * d),
+        "gemm_dw": (mm, 8.0 * M * d * d),
+        "reduce_dw": ("hbm", 4.0 * 4 * d * d * 2),
+        "gemm_dxs": (mm, 6.0 * M * d * d),
+    }
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=30)
+    ap.add_argument("--workload", default="traffic")
+    ap.add_argument("--batches", type=int, default=4, help="distinct pre-generated batches the steps rotate through")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+def cpu_baseline(w, x_np, tok_np, W_np, seed):
+    """The oracle, as it stands, on a bounded sample: the whole path for the first `nb` windows of one batch."""
+    import numpy as np
+    from oracle import attention as o_attn
+    from oracle import kdfh as o_kdfh
+    from oracle import sampling as o_samp
+    import workloads as wl
+
+    try:
+        import threadpoolctl
+        cores = max(int(i.get("num_threads", 1)) for i in threadpoolctl.threadpool_info()) if threadpoolctl.threadpool_info() else 1
+    except Exception:
+        cores = os.cpu_count() or 1
+    t0 = time.perf_counter()
+    topk, hsh, _ = o_kdfh.kdfh(x_np, w.k)                                   # the hash needs the full batch
+    t1 = time.perf_counter()
+    gid, sel, G = o_samp.stratified_sample(hsh, 0, w.ratio[0], w.ratio[1], seed, 0)
+    t2 = time.perf_counter()
+    # attention cost is linear in the batch: time `nb` windows and scale
+    per_window = None
+    nb = 1
+    while True:
+        xs = o_attn.gather(tok_np[:nb], sel)
+        dy = wl.make_upstream(w, len(sel))[:nb]
+        ta = time.perf_counter()
+        y, cache = o_attn.mha_forward(xs, *W_np, w.H)
+        o_attn.mha_backward(dy, cache)
+        tb = time.perf_counter()
+        per_window = (tb - ta) / nb
+        if (tb - ta) > 3.0 or nb >= w.B:
+            break
+        nb = min(w.B, nb * 4)
+    step_s = (t1 - t0) + (t2 - t1) + per_window * w.B
+    return {
+        "value": 1.0 / step_s, "unit": "steps/s", "cores": cores, "kind": "oracle",
+        "sample": "one batch of the same workload: k-DFH and sampling on all %d windows (%.3f s + %.3f s), "
+                  "gather + attention fwd/bwd timed on %d of %d windows and scaled linearly (%.3f s per window), N'=%d"
+                  % (w.B, t1 - t0, t2 - t1, nb, w.B, per_window, len(sel)),
+    }
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (see DESIGN.md); run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    import paper_2501_14183_amd as vd
+    import workloads as wl
+
+    w = wl.WORKLOADS[args.workload]
+    td = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+    dev = torch.device("cuda", 0)
+    torch.cuda.set_device(dev)
+    ctx = vd.Context(0)
+
+    # ---- synthetic inputs, resident in HBM before anything is timed
+    xs_dev, tok_dev, host = [], [], None
+    for i in range(args.batches):
+        x_np, _ = wl.make_signals(w, seed=i)
+        tok_np = wl.make_tokens(w, x_np, seed=i)
+        if i == 0:
+            host = (x_np, tok_np)
+        xs_dev.append(torch.from_numpy(x_np).to(dev))
+        tok_dev.append(torch.from_numpy(tok_np).to(dev).to(td))
+    W_np = wl.make_weights(w, seed=0)
+    W_dev = [torch.from_numpy(m).to(dev).to(td) for m in W_np]
+    dy_full = torch.from_numpy(wl.make_upstream(w, w.N, seed=0)).to(dev).to(td).reshape(-1)
+    pinned = torch.zeros(2, dtype=torch.int32).pin_memory()
+    stream = torch.cuda.current_stream()
+    seed = 0x5EED
+    saved = ws = None
+    stats = {"n_sel": [], "G": []}
+
+    def step(i):
+        nonlocal saved, ws
+        x = xs_dev[i % args.batches]
+        tok = tok_dev[i % args.batches]
+        topk, hsh, _ = vd.vardrop_hash(ctx, x, w.k)
+        gid, sel, counts = vd.vardrop_sample(ctx, hsh, 0, w.ratio[0], w.ratio[1], seed, i, counts_host=pinned)
+        stream.synchronize()                       # N' sizes the attention launch
+        n_sel, G = int(pinned[0]), int(pinned[1])
+        xs = vd.vardrop_gather(ctx, tok, sel, n_sel)
+        y, saved = vd.vardrop_attn_fwd(ctx, xs, *W_dev, w.H, saved=saved)
+        dy = dy_full[: w.B * n_sel * w.d].view(w.B, n_sel, w.d)
+        grads = vd.vardrop_attn_bwd(ctx, dy, xs, *W_dev, w.H, saved, ws=ws)
+        stats["n_sel"].append(n_sel)
+        stats["G"].append(G)
+        return grads
+
+    # size the reusable buffers for the largest selection (never re-allocated inside the timed region)
+    lib = vd.load_library()
+    code = vd.BF16 if w.dtype == "bf16" else vd.F32
+    saved = torch.empty(lib.vardrop_attn_saved_bytes(w.B, w.N, w.d, w.H, code), dtype=torch.uint8, device=dev)
+    ws = torch.empty(lib.vardrop_attn_workspace_bytes(w.B, w.N, w.d, w.H, code), dtype=torch.uint8, device=dev)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+
+    # ---- which kernel takes the largest share of a step?  (untimed census, HIP events around one kernel at a time)
+    census = {}
+    for kid in range(64):
+        name = vd.vardrop_kernel_name(kid)
+        if name is None:
+            break
+        vd.vardrop_profile_select(ctx, kid)
+        for i in range(8):
+            step(i)
+        total_ms, launches = vd.vardrop_profile_read(ctx)
+        if launches:
+            census[name] = (kid, total_ms * 1e3 / 8)            # microseconds per step
+    dominant = max(census, key=lambda k: census[k][1])
+    vd.vardrop_profile_select(ctx, census[dominant][0])          # only this kernel is bracketed while timing
+    torch.cuda.synchronize()
+
+    stats = {"n_sel": [], "G": []}
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms = (t1 - t0) * 1e3 / args.steps
+    n_mean = float(np.mean(stats["n_sel"]))
+
+    # ---- roofline of the dominant kernel: algorithmic work per launch / mean launch duration (HIP events)
+    total_ms, launches = vd.vardrop_profile_read(ctx)
+    vd.vardrop_profile_select(ctx, -1)
+    bound, work = algorithmic_work(w, n_mean)[dominant]
+    avg_s = total_ms * 1e-3 / max(launches, 1)
+    if bound == "hbm":
+        achieved, peak, unit = work / avg_s / 1e9, PEAK_HBM_GBS, "GB/s"
+    else:
+        achieved, unit = work / avg_s / 1e12, "TFLOP/s"
+        peak = PEAK_BF16_TFLOPS if bound == "mfma" else PEAK_FP32_TFLOPS
+    roof = {"kernel": dominant, "bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
+            "frac": achieved / peak, "traffic": None, "avg_launch_us": avg_s * 1e6, "launches": launches,
+            "us_per_step_by_kernel": {k: round(v[1], 2) for k, v in census.items()}}
+
+    out = {
+        "metric": "variate-attn train steps/s (kDFH+sample+SDPA fwd/bwd), HBM GB/s, MFMA %peak",
+        "value": 1e3 / ms, "unit": "steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": "%s-shaped: B=%d N=%d L=%d k=%d keep=%d/%d d=%d H=%d" %
+                               (w.name, w.B, w.N, w.L, w.k, w.ratio[0], w.ratio[1], w.d, w.H),
+                   "kept_tokens_mean": n_mean, "groups_mean": float(np.mean(stats["G"])),
+                   "batches": args.batches},
+        "roofline": roof,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, host[0], host[1], W_np, seed)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -53,6 +53,34 @@ const char* vardrop_strerror(int code);
 int vardrop_last_hip_error(const vardrop_ctx* ctx);
 
 /* ---------------------------------------------------------------------------------
+ * Per-kernel timing for benchmarks.  While a kernel id is selected, every launch of that
+ * kernel is bracketed by a pair of HIP events on the stream it is launched on (at most 4096
+ * launches between two reads; further ones are not recorded).  vardrop_profile_read waits for
+ * the recorded launches, returns their summed duration in milliseconds and their number,
+ * and starts a new collection.  Selecting -1 switches the timing off (the default).
+ */
+enum {
+  VARDROP_K_HASH = 0,        /* k-DFH: spectrum, batch mean, ranked top-k, hash            */
+  VARDROP_K_SAMPLE,          /* grouping + stratified sampling                              */
+  VARDROP_K_GATHER,          /* gather of the kept tokens                                   */
+  VARDROP_K_GEMM_QKV,        /* [Q|K|V] = xs [Wq|Wk|Wv]                                     */
+  VARDROP_K_SDPA_FWD,        /* softmax(Q K^T / sqrt(d_k)) V                                */
+  VARDROP_K_GEMM_OUT,        /* y = O Wo                                                    */
+  VARDROP_K_GEMM_DO,         /* dO = dy Wo^T                                                */
+  VARDROP_K_SDPA_BWD_DQ,     /* dQ and rowsum(dO * O)                                       */
+  VARDROP_K_SDPA_BWD_DKV,    /* dK, dV                                                      */
+  VARDROP_K_GEMM_DW,         /* dWq, dWk, dWv, dWo (K slices)                               */
+  VARDROP_K_REDUCE_DW,       /* sum of the K slices                                         */
+  VARDROP_K_GEMM_DXS,        /* dxs = dQ Wq^T + dK Wk^T + dV Wv^T                           */
+  VARDROP_K_SCATTER,         /* adjoint of the gather                                       */
+  VARDROP_K_COUNT
+};
+int vardrop_profile_select(vardrop_ctx* ctx, int kernel_id);
+int vardrop_profile_read(vardrop_ctx* ctx, double* total_ms, int* launches);
+/* Static name of a kernel id ("hash", "gemm_qkv", ...), or NULL when out of range. */
+const char* vardrop_kernel_name(int kernel_id);
+
+/* ---------------------------------------------------------------------------------
  * k-dominant frequency hashing -- Alg. 1 and Def. 1 of the paper.
  *
  * For every variate n: amplitude spectrum |X_f| of each of its B windows (step 1) on the

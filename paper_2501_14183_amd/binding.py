@@ -26,6 +26,9 @@ _SIGNATURES = {
     "vardrop_destroy": (None, [_ptr]),
     "vardrop_strerror": (ctypes.c_char_p, [_c_int]),
     "vardrop_last_hip_error": (_c_int, [_ptr]),
+    "vardrop_profile_select": (_c_int, [_ptr, _c_int]),
+    "vardrop_profile_read": (_c_int, [_ptr, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(_c_int)]),
+    "vardrop_kernel_name": (ctypes.c_char_p, [_c_int]),
     "vardrop_hash_workspace_bytes": (_c_size, [_c_int] * 6),
     "vardrop_hash": (_c_int, [_ptr, _ptr, _c_int, _c_int, _c_int, _c_i64, _c_i64, _c_i64, _c_int, _c_int, _c_int,
                               _ptr, _ptr, _ptr, _ptr, _c_size, _ptr]),
@@ -119,6 +122,24 @@ class Context:
             self.close()
         except Exception:
             pass
+
+
+def vardrop_kernel_name(kid):
+    name = load_library().vardrop_kernel_name(kid)
+    return None if name is None else name.decode()
+
+
+def vardrop_profile_select(ctx, kid):
+    """Brackets every launch of kernel `kid` with HIP events (-1: off)."""
+    ctx.check(ctx._lib.vardrop_profile_select(ctx.handle, kid), "vardrop_profile_select")
+
+
+def vardrop_profile_read(ctx):
+    """-> (summed duration in ms, number of launches) since the last read or select."""
+    ms = ctypes.c_double()
+    n = _c_int()
+    ctx.check(ctx._lib.vardrop_profile_read(ctx.handle, ctypes.byref(ms), ctypes.byref(n)), "vardrop_profile_read")
+    return ms.value, n.value
 
 
 def vardrop_hash(ctx, x, k, f_min=1, f_max=None, want_abar=False):

@@ -42,6 +42,8 @@ extern "C" size_t vardrop_attn_saved_bytes(int B, int n, int d, int H, int dtype
 }
 
 extern "C" size_t vardrop_attn_workspace_bytes(int B, int n, int d, int H, int dtype) {
+  if (check_shape(B, n, d, H, dtype) != VARDROP_OK) return 0;
+  if (dtype == VARDROP_BF16) return vd_attn_bf16_ws_bytes(B, n, d, H);
   return vardrop_attn_saved_bytes(B, n, d, H, dtype);   // dO, dq, dk, dv and D have the same shapes
 }
 

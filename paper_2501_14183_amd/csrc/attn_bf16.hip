@@ -57,69 +57,91 @@ __device__ inline Frag regs_to_frag(const floatx16& p, int s2) {
 }
 
 // ================================================================== GEMM
+// C[z] = A[z] * B[z] (+ bias[z]), or with nseg > 1 the sum over segments into C[0], or with
+// splitk > 1 an fp32 partial product per K slice (summed afterwards by splitk_reduce_kernel).
+// Workgroup tile 128 x 128 x 64, four wavefronts of 64 x 64, LDS double-buffered; global loads
+// for the next K slice are in flight while the matrix cores work on the current one.
 struct GemmBf16 {
-  const bf16_t* A[3];
-  const bf16_t* B[3];
-  void* C[3];
-  const bf16_t* bias[3];
+  const bf16_t* A[4];
+  const bf16_t* B[4];
+  void* C[4];
+  const bf16_t* bias[4];
   int lda, ldb, ldc;
   int M, N, K;
   int nseg;           // > 1: segments accumulate into C[0]
+  int splitk;         // > 1: grid.z = batches * splitk, slice s writes fp32 to C[0] + (z * splitk + s) * M * N
+  int kchunk;         // K elements per slice (multiple of 64)
 };
 
-constexpr int kLd = 40;   // LDS row stride in elements: 32 k values + 8 pad
+constexpr int kBK = 64;                 // K elements per LDS stage
+constexpr int kStage = 128 * kBK;       // elements of one operand stage (no padding, XOR-swizzled)
 
-// k-contiguous source P[mn][k]: 128 rows x 32 k, two 16-byte chunks per thread
-__device__ inline void load_kc(const bf16_t* P, int ld, int mn0, int MN, int k0, int K, uint4 r[2]) {
+// 16-byte chunk position of (row, k-chunk) inside a 128-byte LDS row
+__device__ inline int swz(int row, int kc) { return kc ^ (((row >> 1) ^ (row >> 4)) & 7); }
+
+// k-contiguous source P[mn][k]: 128 rows x 64 k, four 16-byte chunks per thread, no branches
+__device__ inline void load_kc(const bf16_t* P, int ld, int mn0, int MN, int k0, int kend, uint4 r[4]) {
 #pragma unroll
-  for (int u = 0; u < 2; ++u) {
+  for (int u = 0; u < 4; ++u) {
     const int c = threadIdx.x + u * 256;
-    const int row = c >> 2, kc = c & 3;
-    r[u] = make_uint4(0, 0, 0, 0);
-    if (mn0 + row < MN && k0 + kc * 8 < K)
-      r[u] = *reinterpret_cast<const uint4*>(P + (long long)(mn0 + row) * ld + k0 + kc * 8);
+    const int row = mn0 + (c >> 3), k = k0 + (c & 7) * 8;
+    const bool ok = row < MN && k < kend;
+    const uint4 v = *reinterpret_cast<const uint4*>(P + (long long)(ok ? row : 0) * ld + (ok ? k : 0));
+    r[u] = ok ? v : make_uint4(0, 0, 0, 0);
   }
 }
-__device__ inline void store_kc(bf16_t* S, const uint4 r[2]) {
+__device__ inline void store_kc(bf16_t* S, const uint4 r[4]) {
 #pragma unroll
-  for (int u = 0; u < 2; ++u) {
+  for (int u = 0; u < 4; ++u) {
     const int c = threadIdx.x + u * 256;
-    const int row = c >> 2, kc = c & 3;
-    *reinterpret_cast<uint4*>(S + row * kLd + kc * 8) = r[u];
+    const int row = c >> 3, kc = c & 7;
+    *reinterpret_cast<uint4*>(S + row * kBK + swz(row, kc) * 8) = r[u];
   }
 }
-// mn-contiguous source P[k][mn]: two k rows x eight mn per thread, transposed on the way into LDS
-__device__ inline void load_mc(const bf16_t* P, int ld, int mn0, int MN, int k0, int K, uint4 r[2]) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int kp = lane & 15, mc = wave * 4 + (lane >> 4);
+// mn-contiguous source P[k][mn]: per task two k rows x eight mn, transposed on the way into LDS
+__device__ inline void load_mc(const bf16_t* P, int ld, int mn0, int MN, int k0, int kend, uint4 r[4]) {
 #pragma unroll
   for (int u = 0; u < 2; ++u) {
-    const int k = k0 + 2 * kp + u;
-    r[u] = make_uint4(0, 0, 0, 0);
-    if (k < K && mn0 + mc * 8 < MN)
-      r[u] = *reinterpret_cast<const uint4*>(P + (long long)k * ld + mn0 + mc * 8);
+    const int t = threadIdx.x + u * 256;
+    const int mn = mn0 + (t & 15) * 8, kp = t >> 4;
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+      const int k = k0 + 2 * kp + e;
+      const bool ok = k < kend && mn < MN;
+      const uint4 v = *reinterpret_cast<const uint4*>(P + (long long)(ok ? k : 0) * ld + (ok ? mn : 0));
+      r[2 * u + e] = ok ? v : make_uint4(0, 0, 0, 0);
+    }
   }
 }
-__device__ inline void store_mc(bf16_t* S, const uint4 r[2]) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int kp = lane & 15, mc = wave * 4 + (lane >> 4);
-  Frag a, b;
-  a.q = r[0];
-  b.q = r[1];
+__device__ inline void store_mc(bf16_t* S, const uint4 r[4]) {
 #pragma unroll
-  for (int j = 0; j < 8; ++j)
-    *reinterpret_cast<uint32_t*>(S + (mc * 8 + j) * kLd + 2 * kp) = (uint32_t)a.h[j] | ((uint32_t)b.h[j] << 16);
+  for (int u = 0; u < 2; ++u) {
+    const int t = threadIdx.x + u * 256;
+    const int mc = t & 15, kp = t >> 4;
+    Frag a, b;
+    a.q = r[2 * u];
+    b.q = r[2 * u + 1];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int row = mc * 8 + j;
+      *reinterpret_cast<uint32_t*>(S + row * kBK + swz(row, kp >> 2) * 8 + 2 * (kp & 3)) =
+          (uint32_t)a.h[j] | ((uint32_t)b.h[j] << 16);
+    }
+  }
 }
 
 template <bool AKC, bool BKC, typename OutT>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmBf16 g) {
-  __shared__ __attribute__((aligned(16))) bf16_t As[128 * kLd];
-  __shared__ __attribute__((aligned(16))) bf16_t Bs[128 * kLd];
+  __shared__ __attribute__((aligned(16))) bf16_t As[2 * kStage];
+  __shared__ __attribute__((aligned(16))) bf16_t Bs[2 * kStage];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   const int col = lane & 31, half = lane >> 5;
-  const int z = blockIdx.z;
+  const int zb = g.splitk > 1 ? blockIdx.z / g.splitk : blockIdx.z;
+  const int sk = g.splitk > 1 ? blockIdx.z % g.splitk : 0;
   const int m0 = blockIdx.y * 128, n0 = blockIdx.x * 128;
+  const int kbeg = g.splitk > 1 ? sk * g.kchunk : 0;
+  const int kend = g.splitk > 1 ? min(g.K, kbeg + g.kchunk) : g.K;
   floatx16 acc[2][2];
 #pragma unroll
   for (int i = 0; i < 2; ++i)
@@ -127,40 +149,51 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmBf16 g) {
     for (int j = 0; j < 2; ++j) acc[i][j] = zero16();
 
   const int nseg = g.nseg > 1 ? g.nseg : 1;
-  const int nk = (g.K + 31) >> 5;
-  for (int seg = 0; seg < nseg; ++seg) {
-    const bf16_t* A = g.A[g.nseg > 1 ? seg : z];
-    const bf16_t* Bm = g.B[g.nseg > 1 ? seg : z];
-    uint4 ra[2], rb[2];
-    if (AKC) load_kc(A, g.lda, m0, g.M, 0, g.K, ra); else load_mc(A, g.lda, m0, g.M, 0, g.K, ra);
-    if (BKC) load_kc(Bm, g.ldb, n0, g.N, 0, g.K, rb); else load_mc(Bm, g.ldb, n0, g.N, 0, g.K, rb);
-    for (int kt = 0; kt < nk; ++kt) {
-      __syncthreads();
-      if (AKC) store_kc(As, ra); else store_mc(As, ra);
-      if (BKC) store_kc(Bs, rb); else store_mc(Bs, rb);
-      __syncthreads();
-      if (kt + 1 < nk) {
-        const int k0 = (kt + 1) << 5;
-        if (AKC) load_kc(A, g.lda, m0, g.M, k0, g.K, ra); else load_mc(A, g.lda, m0, g.M, k0, g.K, ra);
-        if (BKC) load_kc(Bm, g.ldb, n0, g.N, k0, g.K, rb); else load_mc(Bm, g.ldb, n0, g.N, k0, g.K, rb);
-      }
-#pragma unroll
-      for (int ks = 0; ks < 2; ++ks) {
-        Frag fa[2], fb[2];
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-          fa[t].q = *reinterpret_cast<const uint4*>(As + (wm * 64 + t * 32 + col) * kLd + ks * 16 + half * 8);
-          fb[t].q = *reinterpret_cast<const uint4*>(Bs + (wn * 64 + t * 32 + col) * kLd + ks * 16 + half * 8);
-        }
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-          for (int j = 0; j < 2; ++j) acc[i][j] = mfma(fa[i], fb[j], acc[i][j]);
-      }
-    }
+  const int nk = (kend - kbeg + kBK - 1) / kBK;
+  const int total = nseg * nk;
+  uint4 ra[4], rb[4];
+  auto fetch = [&](int it) {
+    const int seg = it / nk, k0 = kbeg + (it - seg * nk) * kBK;
+    const bf16_t* A = g.A[g.nseg > 1 ? seg : zb];
+    const bf16_t* Bm = g.B[g.nseg > 1 ? seg : zb];
+    if (AKC) load_kc(A, g.lda, m0, g.M, k0, kend, ra); else load_mc(A, g.lda, m0, g.M, k0, kend, ra);
+    if (BKC) load_kc(Bm, g.ldb, n0, g.N, k0, kend, rb); else load_mc(Bm, g.ldb, n0, g.N, k0, kend, rb);
+  };
+  auto stash = [&](int buf) {
+    if (AKC) store_kc(As + buf * kStage, ra); else store_mc(As + buf * kStage, ra);
+    if (BKC) store_kc(Bs + buf * kStage, rb); else store_mc(Bs + buf * kStage, rb);
+  };
+  if (total > 0) {
+    fetch(0);
+    stash(0);
   }
-  OutT* C = reinterpret_cast<OutT*>(g.C[g.nseg > 1 ? 0 : z]);
-  const bf16_t* bias = g.bias[g.nseg > 1 ? 0 : z];
+  __syncthreads();
+  for (int it = 0; it < total; ++it) {
+    const int cur = it & 1;
+    if (it + 1 < total) fetch(it + 1);
+    const bf16_t* Ab = As + cur * kStage;
+    const bf16_t* Bb = Bs + cur * kStage;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      Frag fa[2], fb[2];
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        const int ra_ = wm * 64 + t * 32 + col, rb_ = wn * 64 + t * 32 + col;
+        fa[t].q = *reinterpret_cast<const uint4*>(Ab + ra_ * kBK + swz(ra_, ks * 2 + half) * 8);
+        fb[t].q = *reinterpret_cast<const uint4*>(Bb + rb_ * kBK + swz(rb_, ks * 2 + half) * 8);
+      }
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = mfma(fa[i], fb[j], acc[i][j]);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    if (it + 1 < total) stash(cur ^ 1);
+    __syncthreads();
+  }
+
+  const int zc = g.nseg > 1 ? 0 : zb;
+  const bf16_t* bias = g.splitk > 1 ? nullptr : g.bias[zc];
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -172,18 +205,49 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmBf16 g) {
         const int m = m0 + wm * 64 + i * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
         if (m < g.M && n < g.N) {
           const float val = acc[i][j][r] + bv;
-          if (sizeof(OutT) == 2) reinterpret_cast<bf16_t*>(C)[(long long)m * g.ldc + n] = f2bf(val);
-          else reinterpret_cast<float*>(C)[(long long)m * g.ldc + n] = val;
+          if (g.splitk > 1) {
+            reinterpret_cast<float*>(g.C[0])[((long long)blockIdx.z * g.M + m) * g.N + n] = val;
+          } else if (sizeof(OutT) == 2) {
+            reinterpret_cast<bf16_t*>(g.C[zc])[(long long)m * g.ldc + n] = f2bf(val);
+          } else {
+            reinterpret_cast<float*>(g.C[zc])[(long long)m * g.ldc + n] = val;
+          }
         }
       }
     }
 }
 
+// out[z][i] = sum_s part[(z * splitk + s)][i], slices added in ascending order
+struct SplitkReduce {
+  const float* part;
+  float* out[4];
+  long long count;     // elements per matrix
+  int splitk;
+};
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(SplitkReduce a) {
+  const int z = blockIdx.y;
+  const float4* src = reinterpret_cast<const float4*>(a.part + (long long)z * a.splitk * a.count);
+  float4* dst = reinterpret_cast<float4*>(a.out[z]);
+  const long long n4 = a.count >> 2;
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += (long long)gridDim.x * blockDim.x) {
+    float4 s = src[i];
+    for (int k = 1; k < a.splitk; ++k) {
+      const float4 v = src[(long long)k * n4 + i];
+      s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+    }
+    dst[i] = s;
+  }
+}
+
 template <bool AKC, bool BKC, typename OutT>
-int launch_gemm(vardrop_ctx* ctx, const GemmBf16& g, int nz, hipStream_t s) {
+int launch_gemm(vardrop_ctx* ctx, int kid, const GemmBf16& g, int nz, hipStream_t s) {
   if (g.M == 0 || g.N == 0) return VARDROP_OK;
-  dim3 grid(vd_ceil_div(g.N, 128), vd_ceil_div(g.M, 128), nz);
-  hipLaunchKernelGGL((gemm_bf16_kernel<AKC, BKC, OutT>), grid, dim3(256), 0, s, g);
+  const int sk = g.splitk > 1 ? g.splitk : 1;
+  dim3 grid(vd_ceil_div(g.N, 128), vd_ceil_div(g.M, 128), nz * sk);
+  {
+    VdTimer timer(ctx, kid, s);
+    hipLaunchKernelGGL((gemm_bf16_kernel<AKC, BKC, OutT>), grid, dim3(256), 0, s, g);
+  }
   VD_LAUNCH_CHECK(ctx);
   return VARDROP_OK;
 }
@@ -489,7 +553,8 @@ __global__ __launch_bounds__(256) void colsum_bf16_kernel(ColSumBf16 a) {
 }
 
 template <typename F>
-int launch_core(vardrop_ctx* ctx, F kernel2, F kernel4, const SdpaArgs& a, int B, hipStream_t s) {
+int launch_core(vardrop_ctx* ctx, int kid, F kernel2, F kernel4, const SdpaArgs& a, int B, hipStream_t s) {
+  VdTimer timer(ctx, kid, s);
   if (a.n <= 256) {
     hipLaunchKernelGGL(kernel2, dim3(vd_ceil_div(a.n, 64), a.H, B), dim3(128), 0, s, a);
   } else {
@@ -500,6 +565,29 @@ int launch_core(vardrop_ctx* ctx, F kernel2, F kernel4, const SdpaArgs& a, int B
 }
 
 }  // namespace
+
+// Number of K slices of the weight-gradient GEMMs (K = B*n rows): enough workgroups to fill the
+// chip, slices of at least 256 rows, a multiple of the 64-row stage.
+int vd_attn_bf16_splitk(int d, long long M, int* kchunk) {
+  const int tiles = vd_ceil_div(d, 128) * vd_ceil_div(d, 128) * 4;
+  int s = 512 / tiles;
+  if (s > 8) s = 8;
+  while (s > 1 && M / s < 256) --s;
+  if (s < 1) s = 1;
+  int chunk = (int)vd_align_up((size_t)vd_ceil_div((int)M, s), 64);
+  if (chunk < 64) chunk = 64;
+  s = M > 0 ? vd_ceil_div((int)M, chunk) : 1;
+  if (kchunk) *kchunk = chunk;
+  return s;
+}
+size_t vd_attn_bf16_partial_offset(int B, int n, int d, int H) {
+  const size_t M = (size_t)B * n;
+  return vd_align_up(4 * M * d * 2 + (size_t)B * H * n * sizeof(float), 256);
+}
+size_t vd_attn_bf16_ws_bytes(int B, int n, int d, int H) {
+  const int s = vd_attn_bf16_splitk(d, (long long)B * n, nullptr);
+  return vd_attn_bf16_partial_offset(B, n, d, H) + (s > 1 ? (size_t)4 * s * d * d * sizeof(float) : 0);
+}
 
 // saved: q, k, v, o ([M][d] bf16 each, M = B*n) then lse fp32 [B][H][n]
 int vd_attn_fwd_bf16(vardrop_ctx* ctx, const void* xs, int B, int n, int d, int H,
@@ -521,21 +609,21 @@ int vd_attn_fwd_bf16(vardrop_ctx* ctx, const void* xs, int B, int n, int d, int 
   g.C[0] = q; g.C[1] = k; g.C[2] = v;
   g.lda = d; g.ldb = d; g.ldc = d;
   g.M = (int)M; g.N = d; g.K = d; g.nseg = 1;
-  int rc = launch_gemm<true, false, bf16_t>(ctx, g, 3, s);
+  int rc = launch_gemm<true, false, bf16_t>(ctx, VARDROP_K_GEMM_QKV, g, 3, s);
   if (rc) return rc;
   SdpaArgs a = {};
   a.q = q; a.k = k; a.v = v; a.out = o; a.lse = lse;
   a.n = n; a.d = d; a.H = H; a.scale = 1.0f / sqrtf((float)kDh);
-  rc = launch_core(ctx, sdpa_fwd_bf16<2>, sdpa_fwd_bf16<4>, a, B, s);
+  rc = launch_core(ctx, VARDROP_K_SDPA_FWD, sdpa_fwd_bf16<2>, sdpa_fwd_bf16<4>, a, B, s);
   if (rc) return rc;
   GemmBf16 go = {};
   go.A[0] = o; go.B[0] = (const bf16_t*)W[3]; go.C[0] = y; go.bias[0] = (const bf16_t*)bias[3];
   go.lda = d; go.ldb = d; go.ldc = d;
   go.M = (int)M; go.N = d; go.K = d; go.nseg = 1;
-  return launch_gemm<true, false, bf16_t>(ctx, go, 1, s);
+  return launch_gemm<true, false, bf16_t>(ctx, VARDROP_K_GEMM_OUT, go, 1, s);
 }
 
-// ws: dO, dq, dk, dv ([M][d] bf16 each) then D fp32 [B][H][n]
+// ws: dO, dq, dk, dv ([M][d] bf16 each), D fp32 [B][H][n], then the split-K partial products
 int vd_attn_bwd_bf16(vardrop_ctx* ctx, const void* dy, const void* xs, int B, int n, int d, int H,
                      const void* const W[4], const void* saved, void* dxs,
                      float* const dW[4], float* const db[4], void* ws, hipStream_t s) {
@@ -556,30 +644,43 @@ int vd_attn_bwd_bf16(vardrop_ctx* ctx, const void* dy, const void* xs, int B, in
     g.A[0] = (const bf16_t*)dy; g.B[0] = (const bf16_t*)W[3]; g.C[0] = dO;
     g.lda = d; g.ldb = d; g.ldc = d;
     g.M = (int)M; g.N = d; g.K = d; g.nseg = 1;
-    if ((rc = launch_gemm<true, true, bf16_t>(ctx, g, 1, s))) return rc;
+    if ((rc = launch_gemm<true, true, bf16_t>(ctx, VARDROP_K_GEMM_DO, g, 1, s))) return rc;
   }
   SdpaArgs a = {};
   a.q = q; a.k = k; a.v = v; a.o = o; a.dout = dO; a.lse = const_cast<float*>(lse);
   a.dq = dq; a.dk = dk; a.dv = dv; a.Dsum = D;
   a.n = n; a.d = d; a.H = H; a.scale = 1.0f / sqrtf((float)kDh);
-  if ((rc = launch_core(ctx, sdpa_bwd_dq_bf16<2>, sdpa_bwd_dq_bf16<4>, a, B, s))) return rc;
-  if ((rc = launch_core(ctx, sdpa_bwd_dkv_bf16<2>, sdpa_bwd_dkv_bf16<4>, a, B, s))) return rc;
-  {  // dWo = o^T dy
+  if ((rc = launch_core(ctx, VARDROP_K_SDPA_BWD_DQ, sdpa_bwd_dq_bf16<2>, sdpa_bwd_dq_bf16<4>, a, B, s))) return rc;
+  if ((rc = launch_core(ctx, VARDROP_K_SDPA_BWD_DKV, sdpa_bwd_dkv_bf16<2>, sdpa_bwd_dkv_bf16<4>, a, B, s))) return rc;
+  {  // dWq, dWk, dWv, dWo = xs^T dq, xs^T dk, xs^T dv, o^T dy: one launch, K = B*n cut into slices
     GemmBf16 g = {};
-    g.A[0] = o; g.B[0] = (const bf16_t*)dy; g.C[0] = dW[3];
-    g.lda = d; g.ldb = d; g.ldc = d;
-    g.M = d; g.N = d; g.K = (int)M; g.nseg = 1;
-    if ((rc = launch_gemm<false, false, float>(ctx, g, 1, s))) return rc;
-  }
-  {  // dWq, dWk, dWv = xs^T dq, xs^T dk, xs^T dv
-    GemmBf16 g = {};
-    const bf16_t* grads[3] = {dq, dk, dv};
-    for (int z = 0; z < 3; ++z) {
-      g.A[z] = (const bf16_t*)xs; g.B[z] = grads[z]; g.C[z] = dW[z];
+    const bf16_t* lhs[4] = {(const bf16_t*)xs, (const bf16_t*)xs, (const bf16_t*)xs, o};
+    const bf16_t* rhs[4] = {dq, dk, dv, (const bf16_t*)dy};
+    for (int z = 0; z < 4; ++z) {
+      g.A[z] = lhs[z]; g.B[z] = rhs[z]; g.C[z] = dW[z];
     }
     g.lda = d; g.ldb = d; g.ldc = d;
     g.M = d; g.N = d; g.K = (int)M; g.nseg = 1;
-    if ((rc = launch_gemm<false, false, float>(ctx, g, 3, s))) return rc;
+    int kchunk = 0;
+    g.splitk = vd_attn_bf16_splitk(d, M, &kchunk);
+    g.kchunk = kchunk;
+    if (g.splitk > 1) {
+      float* part = (float*)((char*)ws + vd_attn_bf16_partial_offset(B, n, d, H));
+      g.C[0] = part;
+      if ((rc = launch_gemm<false, false, float>(ctx, VARDROP_K_GEMM_DW, g, 4, s))) return rc;
+      SplitkReduce r = {};
+      r.part = part;
+      for (int z = 0; z < 4; ++z) r.out[z] = dW[z];
+      r.count = (long long)d * d;
+      r.splitk = g.splitk;
+      {
+        VdTimer timer(ctx, VARDROP_K_REDUCE_DW, s);
+        hipLaunchKernelGGL(splitk_reduce_kernel, dim3(vd_ceil_div(d * d / 4, 256), 4), dim3(256), 0, s, r);
+      }
+      VD_LAUNCH_CHECK(ctx);
+    } else {
+      if ((rc = launch_gemm<false, false, float>(ctx, VARDROP_K_GEMM_DW, g, 4, s))) return rc;
+    }
   }
   {  // dxs = dq Wq^T + dk Wk^T + dv Wv^T
     GemmBf16 g = {};
@@ -590,7 +691,7 @@ int vd_attn_bwd_bf16(vardrop_ctx* ctx, const void* dy, const void* xs, int B, in
     g.C[0] = dxs;
     g.lda = d; g.ldb = d; g.ldc = d;
     g.M = (int)M; g.N = d; g.K = d; g.nseg = 3;
-    if ((rc = launch_gemm<true, true, bf16_t>(ctx, g, 1, s))) return rc;
+    if ((rc = launch_gemm<true, true, bf16_t>(ctx, VARDROP_K_GEMM_DXS, g, 1, s))) return rc;
   }
   if (db[0] || db[1] || db[2] || db[3]) {
     ColSumBf16 c = {};

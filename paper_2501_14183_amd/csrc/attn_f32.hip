@@ -78,9 +78,10 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmF32 g) {
     }
 }
 
-int launch_gemm(vardrop_ctx* ctx, const GemmF32& g, int nz, hipStream_t s) {
+int launch_gemm(vardrop_ctx* ctx, int kid, const GemmF32& g, int nz, hipStream_t s) {
   if (g.M == 0 || g.N == 0) return VARDROP_OK;
   dim3 grid(vd_ceil_div(g.N, 64), vd_ceil_div(g.M, 64), nz);
+  VdTimer timer(ctx, kid, s);
   hipLaunchKernelGGL(gemm_f32_kernel, grid, dim3(256), 0, s, g);
   VD_LAUNCH_CHECK(ctx);
   return VARDROP_OK;
@@ -273,6 +274,7 @@ __global__ __launch_bounds__(256) void colsum_f32_kernel(ColSumF32 a) {
 template <int DH>
 int run_fwd_core(vardrop_ctx* ctx, const float* q, const float* k, const float* v, float* o, float* lse,
                  int B, int n, int d, int H, hipStream_t s) {
+  VdTimer timer(ctx, VARDROP_K_SDPA_FWD, s);
   hipLaunchKernelGGL(sdpa_fwd_f32<DH>, dim3(vd_ceil_div(n, 64), H, B), dim3(64), 0, s, q, k, v, o, lse, n, d, H,
                      1.0f / sqrtf((float)DH));
   VD_LAUNCH_CHECK(ctx);
@@ -285,8 +287,12 @@ int run_bwd_core(vardrop_ctx* ctx, const float* q, const float* k, const float* 
                  hipStream_t s) {
   const float scale = 1.0f / sqrtf((float)DH);
   dim3 grid(vd_ceil_div(n, 64), H, B);
-  hipLaunchKernelGGL(sdpa_bwd_dq_f32<DH>, grid, dim3(64), 0, s, q, k, v, o, dO, lse, dq, D, n, d, H, scale);
+  {
+    VdTimer timer(ctx, VARDROP_K_SDPA_BWD_DQ, s);
+    hipLaunchKernelGGL(sdpa_bwd_dq_f32<DH>, grid, dim3(64), 0, s, q, k, v, o, dO, lse, dq, D, n, d, H, scale);
+  }
   VD_LAUNCH_CHECK(ctx);
+  VdTimer timer(ctx, VARDROP_K_SDPA_BWD_DKV, s);
   hipLaunchKernelGGL(sdpa_bwd_dkv_f32<DH>, grid, dim3(64), 0, s, q, k, v, dO, lse, D, dk, dv, n, d, H, scale);
   VD_LAUNCH_CHECK(ctx);
   return VARDROP_OK;
@@ -316,7 +322,7 @@ int vd_attn_fwd_f32(vardrop_ctx* ctx, const float* xs, int B, int n, int d, int 
   g.C[2] = v;
   g.sam = d; g.sak = 1; g.sbk = d; g.sbn = 1;
   g.M = (int)M; g.N = d; g.K = d; g.ldc = d; g.nseg = 1;
-  int rc = launch_gemm(ctx, g, 3, s);
+  int rc = launch_gemm(ctx, VARDROP_K_GEMM_QKV, g, 3, s);
   if (rc) return rc;
   const int dh = d / H;
   switch (dh) {
@@ -331,7 +337,7 @@ int vd_attn_fwd_f32(vardrop_ctx* ctx, const float* xs, int B, int n, int d, int 
   go.A[0] = o; go.B[0] = W[3]; go.C[0] = y; go.bias[0] = bias[3];
   go.sam = d; go.sak = 1; go.sbk = d; go.sbn = 1;
   go.M = (int)M; go.N = d; go.K = d; go.ldc = d; go.nseg = 1;
-  return launch_gemm(ctx, go, 1, s);
+  return launch_gemm(ctx, VARDROP_K_GEMM_OUT, go, 1, s);
 }
 
 // ws: dO, dq, dk, dv ([M][d] fp32 each) then D [B][H][n]
@@ -355,7 +361,7 @@ int vd_attn_bwd_f32(vardrop_ctx* ctx, const float* dy, const float* xs, int B, i
     g.A[0] = dy; g.B[0] = W[3]; g.C[0] = dO;
     g.sam = d; g.sak = 1; g.sbk = 1; g.sbn = d;      // B(k, n) = Wo[n][k]
     g.M = (int)M; g.N = d; g.K = d; g.ldc = d; g.nseg = 1;
-    if ((rc = launch_gemm(ctx, g, 1, s))) return rc;
+    if ((rc = launch_gemm(ctx, VARDROP_K_GEMM_DO, g, 1, s))) return rc;
   }
   const int dh = d / H;
   switch (dh) {
@@ -371,7 +377,7 @@ int vd_attn_bwd_f32(vardrop_ctx* ctx, const float* dy, const float* xs, int B, i
     g.A[0] = o; g.B[0] = dy; g.C[0] = dW[3];
     g.sam = 1; g.sak = d; g.sbk = d; g.sbn = 1;      // A(m, k) = o[k][m]
     g.M = d; g.N = d; g.K = (int)M; g.ldc = d; g.nseg = 1;
-    if ((rc = launch_gemm(ctx, g, 1, s))) return rc;
+    if ((rc = launch_gemm(ctx, VARDROP_K_GEMM_DW, g, 1, s))) return rc;
   }
   {  // dWq, dWk, dWv = xs^T dq, xs^T dk, xs^T dv
     GemmF32 g = {};
@@ -381,7 +387,7 @@ int vd_attn_bwd_f32(vardrop_ctx* ctx, const float* dy, const float* xs, int B, i
     }
     g.sam = 1; g.sak = d; g.sbk = d; g.sbn = 1;
     g.M = d; g.N = d; g.K = (int)M; g.ldc = d; g.nseg = 1;
-    if ((rc = launch_gemm(ctx, g, 3, s))) return rc;
+    if ((rc = launch_gemm(ctx, VARDROP_K_GEMM_DW, g, 3, s))) return rc;
   }
   {  // dxs = dq Wq^T + dk Wk^T + dv Wv^T
     GemmF32 g = {};
@@ -392,7 +398,7 @@ int vd_attn_bwd_f32(vardrop_ctx* ctx, const float* dy, const float* xs, int B, i
     g.C[0] = dxs;
     g.sam = d; g.sak = 1; g.sbk = 1; g.sbn = d;
     g.M = (int)M; g.N = d; g.K = d; g.ldc = d; g.nseg = 3;
-    if ((rc = launch_gemm(ctx, g, 1, s))) return rc;
+    if ((rc = launch_gemm(ctx, VARDROP_K_GEMM_DXS, g, 1, s))) return rc;
   }
   if (db[0] || db[1] || db[2] || db[3]) {
     ColSumF32 c = {};

@@ -5,9 +5,14 @@
 #include <stdint.h>
 #include "../../include/vardrop.h"
 
+static const int kProfPairs = 4096;   // event pairs held between two vardrop_profile_read calls
+
 struct vardrop_ctx {
   int device;
   int last_hip_error;
+  int prof_kid;          // kernel whose launches are bracketed by events (-1: none)
+  int prof_n;            // pairs recorded since the last read
+  hipEvent_t* prof_ev;   // 2 * kProfPairs events, created on first use
   float* twiddle;        // device: cos(2 pi j / L), j < L, then sin(2 pi j / L), j < L
   int twiddle_L;         // L the table currently holds (0: none)
   int lds_per_block;     // bytes of LDS one workgroup may use
@@ -26,9 +31,28 @@ static const int kMaxTwiddleL = 8192;
 
 #define VD_LAUNCH_CHECK(ctx) VD_HIP(ctx, hipGetLastError())
 
+// Brackets the launches issued during its lifetime with a pair of events when the context is
+// profiling kernel `kid`; costs one integer compare otherwise.
+struct VdTimer {
+  vardrop_ctx* ctx;
+  hipStream_t stream;
+  bool active;
+  VdTimer(vardrop_ctx* c, int kid, hipStream_t s) : ctx(c), stream(s), active(false) {
+    if (c->prof_kid == kid && c->prof_ev && c->prof_n < kProfPairs)
+      active = hipEventRecord(c->prof_ev[2 * c->prof_n], s) == hipSuccess;
+  }
+  ~VdTimer() {
+    if (active && hipEventRecord(ctx->prof_ev[2 * ctx->prof_n + 1], stream) == hipSuccess) ++ctx->prof_n;
+  }
+};
+
 static inline size_t vd_align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 static inline bool vd_aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
 static inline int vd_ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+int vd_attn_bf16_splitk(int d, long long M, int* kchunk);
+size_t vd_attn_bf16_partial_offset(int B, int n, int d, int H);
+size_t vd_attn_bf16_ws_bytes(int B, int n, int d, int H);
 
 // attention back ends (attn_f32.hip, attn_bf16.hip); argument checks are done by the caller
 int vd_attn_fwd_f32(vardrop_ctx*, const float* xs, int B, int n, int d, int H,

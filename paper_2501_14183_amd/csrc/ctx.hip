@@ -13,6 +13,9 @@ extern "C" int vardrop_create(vardrop_ctx** out, int device_id) {
   c->last_hip_error = 0;
   c->twiddle = nullptr;
   c->twiddle_L = 0;
+  c->prof_kid = -1;
+  c->prof_n = 0;
+  c->prof_ev = nullptr;
   c->lds_per_block = 65536;
   int prev = 0;
   hipError_t e = hipGetDevice(&prev);
@@ -35,6 +38,10 @@ extern "C" int vardrop_create(vardrop_ctx** out, int device_id) {
 extern "C" void vardrop_destroy(vardrop_ctx* ctx) {
   if (!ctx) return;
   if (ctx->twiddle) (void)hipFree(ctx->twiddle);
+  if (ctx->prof_ev) {
+    for (int i = 0; i < 2 * kProfPairs; ++i) (void)hipEventDestroy(ctx->prof_ev[i]);
+    delete[] ctx->prof_ev;
+  }
   delete ctx;
 }
 
@@ -50,3 +57,46 @@ extern "C" const char* vardrop_strerror(int code) {
 }
 
 extern "C" int vardrop_last_hip_error(const vardrop_ctx* ctx) { return ctx ? ctx->last_hip_error : 0; }
+
+extern "C" const char* vardrop_kernel_name(int kernel_id) {
+  static const char* const names[VARDROP_K_COUNT] = {
+      "hash", "sample", "gather", "gemm_qkv", "sdpa_fwd", "gemm_out", "gemm_do",
+      "sdpa_bwd_dq", "sdpa_bwd_dkv", "gemm_dw", "reduce_dw", "gemm_dxs", "scatter"};
+  return (kernel_id >= 0 && kernel_id < VARDROP_K_COUNT) ? names[kernel_id] : nullptr;
+}
+
+extern "C" int vardrop_profile_select(vardrop_ctx* ctx, int kernel_id) {
+  if (!ctx || kernel_id < -1 || kernel_id >= VARDROP_K_COUNT) return VARDROP_EINVAL;
+  if (kernel_id >= 0 && !ctx->prof_ev) {
+    hipEvent_t* ev = new (std::nothrow) hipEvent_t[2 * kProfPairs];
+    if (!ev) return VARDROP_EHIP;
+    for (int i = 0; i < 2 * kProfPairs; ++i) {
+      hipError_t e = hipEventCreate(&ev[i]);
+      if (e != hipSuccess) {
+        for (int j = 0; j < i; ++j) (void)hipEventDestroy(ev[j]);
+        delete[] ev;
+        ctx->last_hip_error = (int)e;
+        return VARDROP_EHIP;
+      }
+    }
+    ctx->prof_ev = ev;
+  }
+  ctx->prof_kid = kernel_id;
+  ctx->prof_n = 0;
+  return VARDROP_OK;
+}
+
+extern "C" int vardrop_profile_read(vardrop_ctx* ctx, double* total_ms, int* launches) {
+  if (!ctx || !total_ms || !launches) return VARDROP_EINVAL;
+  double sum = 0.0;
+  for (int i = 0; i < ctx->prof_n; ++i) {
+    VD_HIP(ctx, hipEventSynchronize(ctx->prof_ev[2 * i + 1]));
+    float ms = 0.f;
+    VD_HIP(ctx, hipEventElapsedTime(&ms, ctx->prof_ev[2 * i], ctx->prof_ev[2 * i + 1]));
+    sum += ms;
+  }
+  *total_ms = sum;
+  *launches = ctx->prof_n;
+  ctx->prof_n = 0;
+  return VARDROP_OK;
+}

@@ -5,22 +5,28 @@
 
 namespace {
 
-// out[b][i][:] = src[b][sel[i]][:].  One 16-byte (or `unit`-byte) chunk per thread.
+// Element types: the kernels move opaque units of 16, 4 or 2 bytes.
+template <typename T> __device__ inline T zero_unit() { return T(0); }
+template <> __device__ inline uint4 zero_unit<uint4>() { return make_uint4(0, 0, 0, 0); }
+
+// out[b][i][:] = src[b][sel[i]][:].  A workgroup of 256 threads moves blockDim.y rows at a time,
+// `row_units` units each; threadIdx.y walks the rows, threadIdx.x the units of a row.
 template <typename T>
 __global__ __launch_bounds__(256) void gather_kernel(const T* __restrict__ src, T* __restrict__ out,
                                                     const int32_t* __restrict__ sel,
                                                     int B, int N, int n_sel, int row_units) {
-  const long long total = (long long)B * n_sel * row_units;
-  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total;
-       i += (long long)gridDim.x * blockDim.x) {
-    const int c = (int)(i % row_units);
-    const long long row = i / row_units;
-    const int j = (int)(row % n_sel);
-    const int b = (int)(row / n_sel);
+  const int rows = B * n_sel;
+  for (int row = blockIdx.x * blockDim.y + threadIdx.y; row < rows; row += gridDim.x * blockDim.y) {
+    const int b = row / n_sel, j = row - b * n_sel;
     const int n = sel[j];
-    T v = T();
-    if ((unsigned)n < (unsigned)N) v = src[((long long)b * N + n) * row_units + c];
-    out[i] = v;
+    const bool ok = (unsigned)n < (unsigned)N;
+    const T* p = src + ((long long)b * N + (ok ? n : 0)) * row_units;
+    T* q = out + (long long)row * row_units;
+    for (int c = threadIdx.x; c < row_units; c += blockDim.x) {
+      T v = p[c];
+      if (!ok) v = zero_unit<T>();
+      q[c] = v;
+    }
   }
 }
 
@@ -29,25 +35,26 @@ template <typename T>
 __global__ __launch_bounds__(256) void scatter_kernel(const T* __restrict__ src, T* __restrict__ dst,
                                                      const int32_t* __restrict__ sel,
                                                      int B, int N, int n_sel, int row_units) {
-  const long long total = (long long)B * N * row_units;
-  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total;
-       i += (long long)gridDim.x * blockDim.x) {
-    const int c = (int)(i % row_units);
-    const long long row = i / row_units;
-    const int n = (int)(row % N);
-    const int b = (int)(row / N);
+  const int rows = B * N;
+  for (int row = blockIdx.x * blockDim.y + threadIdx.y; row < rows; row += gridDim.x * blockDim.y) {
+    const int b = row / N, n = row - b * N;
     int lo = 0, hi = n_sel;                       // first position with sel[pos] >= n
     while (lo < hi) {
       const int mid = (lo + hi) >> 1;
       if (sel[mid] < n) lo = mid + 1; else hi = mid;
     }
-    T v = T();
-    if (lo < n_sel && sel[lo] == n) v = src[((long long)b * n_sel + lo) * row_units + c];
-    dst[i] = v;
+    const bool hit = lo < n_sel && sel[lo] == n;
+    T* q = dst + (long long)row * row_units;
+    if (hit) {
+      const T* p = src + ((long long)b * n_sel + lo) * row_units;
+      for (int c = threadIdx.x; c < row_units; c += blockDim.x) q[c] = p[c];
+    } else {
+      for (int c = threadIdx.x; c < row_units; c += blockDim.x) q[c] = zero_unit<T>();
+    }
   }
 }
 
-struct alignas(16) Chunk16 { uint32_t w[4]; };
+typedef uint4 Chunk16;
 
 int elem_size(int dtype) { return dtype == VARDROP_F32 ? 4 : (dtype == VARDROP_BF16 ? 2 : 0); }
 
@@ -61,10 +68,14 @@ int launch(vardrop_ctx* ctx, const void* src, void* dst, const int32_t* sel, int
   const bool wide = row_bytes % 16 == 0 && vd_aligned(src, 16) && vd_aligned(dst, 16);
   const int unit = wide ? 16 : es;
   const int row_units = (int)(row_bytes / unit);
-  const long long total = rows * row_units;
-  long long blocks = (total + 255) / 256;
-  if (blocks > 256 * 32) blocks = 256 * 32;
-  dim3 grid((unsigned)blocks), block(256);
+  if (rows >= (1ll << 31)) return VARDROP_EUNSUPPORTED;
+  int tx = 1;                                     // threads along a row: power of two, at most 64
+  while (tx < 64 && tx < row_units) tx <<= 1;
+  const int ty = 256 / tx;
+  long long blocks = (rows + ty - 1) / ty;
+  if (blocks > 256 * 64) blocks = 256 * 64;
+  dim3 grid((unsigned)blocks), block(tx, ty);
+  VdTimer timer(ctx, kScatter ? VARDROP_K_SCATTER : VARDROP_K_GATHER, s);
   if (wide) {
     if (kScatter) hipLaunchKernelGGL(scatter_kernel<Chunk16>, grid, block, 0, s, (const Chunk16*)src, (Chunk16*)dst, sel, B, N, n_sel, row_units);
     else hipLaunchKernelGGL(gather_kernel<Chunk16>, grid, block, 0, s, (const Chunk16*)src, (Chunk16*)dst, sel, B, N, n_sel, row_units);

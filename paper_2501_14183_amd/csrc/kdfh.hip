@@ -275,7 +275,10 @@ extern "C" int vardrop_hash(vardrop_ctx* ctx, const float* x, int B, int N, int 
   a.inv_B = 1.0f / (float)B;
   if (lds > 65536)
     VD_HIP(ctx, hipFuncSetAttribute((const void*)kdfh_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-  hipLaunchKernelGGL(kdfh_kernel, dim3(vd_ceil_div(N, Vb)), dim3(64), lds, s, a);
+  {
+    VdTimer timer(ctx, VARDROP_K_HASH, s);
+    hipLaunchKernelGGL(kdfh_kernel, dim3(vd_ceil_div(N, Vb)), dim3(64), lds, s, a);
+  }
   VD_LAUNCH_CHECK(ctx);
   return VARDROP_OK;
 }

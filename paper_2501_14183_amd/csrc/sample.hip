@@ -230,7 +230,10 @@ extern "C" int vardrop_sample(vardrop_ctx* ctx, const uint64_t* hash, int N,
   hipStream_t s = (hipStream_t)stream;
   if (lds > 65536)
     VD_HIP(ctx, hipFuncSetAttribute((const void*)sample_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-  hipLaunchKernelGGL(sample_kernel, dim3(1), dim3(threads), lds, s, a);
+  {
+    VdTimer timer(ctx, VARDROP_K_SAMPLE, s);
+    hipLaunchKernelGGL(sample_kernel, dim3(1), dim3(threads), lds, s, a);
+  }
   VD_LAUNCH_CHECK(ctx);
   if (counts_host)
     VD_HIP(ctx, hipMemcpyAsync(counts_host, counts, 2 * sizeof(int32_t), hipMemcpyDeviceToHost, s));
