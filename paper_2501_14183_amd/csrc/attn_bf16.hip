@@ -20,6 +20,9 @@
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // 16-byte unit of data movement (a native vector,
+                                                               // so that staging arrays stay in registers)
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 namespace {
 
@@ -34,8 +37,8 @@ __device__ inline float bf2f(bf16_t b) { return __uint_as_float((uint32_t)b << 1
 __device__ inline uint32_t pack2(float lo, float hi) { return (uint32_t)f2bf(lo) | ((uint32_t)f2bf(hi) << 16); }
 
 union Frag {
-  uint4 q;
-  uint2 d[2];
+  u32x4 q;
+  u32x2 d[2];
   uint32_t w[4];
   bf16_t h[8];
   bf16x8 v;
@@ -62,84 +65,140 @@ __device__ inline Frag regs_to_frag(const floatx16& p, int s2) {
 // Workgroup tile 128 x 128 x 64, four wavefronts of 64 x 64, LDS double-buffered; global loads
 // for the next K slice are in flight while the matrix cores work on the current one.
 struct GemmBf16 {
-  const bf16_t* A[4];
-  const bf16_t* B[4];
-  void* C[4];
-  const bf16_t* bias[4];
+  // up to four batch entries (grid z) or three accumulated segments; named fields rather than arrays so
+  // that the argument block is never indexed at run time (that would force it into private memory)
+  const bf16_t *A0, *A1, *A2, *A3;
+  const bf16_t *B0, *B1, *B2, *B3;
+  void *C0, *C1, *C2, *C3;
+  const bf16_t *bias0, *bias1, *bias2, *bias3;
   int lda, ldb, ldc;
   int M, N, K;
-  int nseg;           // > 1: segments accumulate into C[0]
-  int splitk;         // > 1: grid.z = batches * splitk, slice s writes fp32 to C[0] + (z * splitk + s) * M * N
+  int nseg;           // > 1: segments accumulate into C0
+  int splitk;         // > 1: grid.z = batches * splitk, slice s writes fp32 to C0 + (z * splitk + s) * M * N
   int kchunk;         // K elements per slice (multiple of 64)
+  void set(int z, const void* a, const void* b, void* c, const void* bias) {
+    const bf16_t* pa = (const bf16_t*)a;
+    const bf16_t* pb = (const bf16_t*)b;
+    const bf16_t* pbias = (const bf16_t*)bias;
+    switch (z) {
+      case 0: A0 = pa; B0 = pb; C0 = c; bias0 = pbias; break;
+      case 1: A1 = pa; B1 = pb; C1 = c; bias1 = pbias; break;
+      case 2: A2 = pa; B2 = pb; C2 = c; bias2 = pbias; break;
+      default: A3 = pa; B3 = pb; C3 = c; bias3 = pbias; break;
+    }
+  }
 };
 
 constexpr int kBK = 64;                 // K elements per LDS stage
-constexpr int kStage = 128 * kBK;       // elements of one operand stage (no padding, XOR-swizzled)
 
 // 16-byte chunk position of (row, k-chunk) inside a 128-byte LDS row
 __device__ inline int swz(int row, int kc) { return kc ^ (((row >> 1) ^ (row >> 4)) & 7); }
 
-// k-contiguous source P[mn][k]: 128 rows x 64 k, four 16-byte chunks per thread, no branches
-__device__ inline void load_kc(const bf16_t* P, int ld, int mn0, int MN, int k0, int kend, uint4 r[4]) {
-#pragma unroll
-  for (int u = 0; u < 4; ++u) {
-    const int c = threadIdx.x + u * 256;
-    const int row = mn0 + (c >> 3), k = k0 + (c & 7) * 8;
-    const bool ok = row < MN && k < kend;
-    const uint4 v = *reinterpret_cast<const uint4*>(P + (long long)(ok ? row : 0) * ld + (ok ? k : 0));
-    r[u] = ok ? v : make_uint4(0, 0, 0, 0);
-  }
-}
-__device__ inline void store_kc(bf16_t* S, const uint4 r[4]) {
-#pragma unroll
-  for (int u = 0; u < 4; ++u) {
-    const int c = threadIdx.x + u * 256;
-    const int row = c >> 3, kc = c & 7;
-    *reinterpret_cast<uint4*>(S + row * kBK + swz(row, kc) * 8) = r[u];
-  }
-}
-// mn-contiguous source P[k][mn]: per task two k rows x eight mn, transposed on the way into LDS
-__device__ inline void load_mc(const bf16_t* P, int ld, int mn0, int MN, int k0, int kend, uint4 r[4]) {
-#pragma unroll
-  for (int u = 0; u < 2; ++u) {
-    const int t = threadIdx.x + u * 256;
-    const int mn = mn0 + (t & 15) * 8, kp = t >> 4;
-#pragma unroll
-    for (int e = 0; e < 2; ++e) {
-      const int k = k0 + 2 * kp + e;
-      const bool ok = k < kend && mn < MN;
-      const uint4 v = *reinterpret_cast<const uint4*>(P + (long long)(ok ? k : 0) * ld + (ok ? mn : 0));
-      r[2 * u + e] = ok ? v : make_uint4(0, 0, 0, 0);
-    }
-  }
-}
-__device__ inline void store_mc(bf16_t* S, const uint4 r[4]) {
-#pragma unroll
-  for (int u = 0; u < 2; ++u) {
-    const int t = threadIdx.x + u * 256;
-    const int mc = t & 15, kp = t >> 4;
-    Frag a, b;
-    a.q = r[2 * u];
-    b.q = r[2 * u + 1];
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const int row = mc * 8 + j;
-      *reinterpret_cast<uint32_t*>(S + row * kBK + swz(row, kp >> 2) * 8 + 2 * (kp & 3)) =
-          (uint32_t)a.h[j] | ((uint32_t)b.h[j] << 16);
-    }
-  }
-}
+__device__ inline u32x4 and4(u32x4 v, uint32_t m) { return v & m; }
 
-template <bool AKC, bool BKC, typename OutT>
-__global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmBf16 g) {
-  __shared__ __attribute__((aligned(16))) bf16_t As[2 * kStage];
-  __shared__ __attribute__((aligned(16))) bf16_t Bs[2 * kStage];
+// One K slice (64 k) of one operand, staged in registers between global memory and LDS.
+//   KC = true : k-contiguous source P[mn][k].  Rows past the end are read from the last row (their
+//               products land in output rows or columns that are never stored); the host guarantees
+//               that K is a multiple of 64, so there is no tail along k.
+//   KC = false: mn-contiguous source P[k][mn]; a task is two k rows x eight mn, transposed on the way
+//               into LDS.  In the last, partial slice the k rows past kend are read from row kend-1 and
+//               zeroed with a mask.
+// Per-thread element offsets into the source and into LDS are computed once; a load is then one
+// 64-bit add per 16 bytes, unconditional, so the loads of a slice issue back to back.
+template <int ROWS, int NT, bool KC>
+struct Stage {
+  static constexpr int kRegs = ROWS * 8 / NT;
+  u32x4 r[kRegs];
+  int goff[kRegs];      // KC: row * ld + 8 * chunk          MC: krel * ld + mn
+  int loff[KC ? kRegs : kRegs / 2];
+  __device__ inline void init(int ld, int mn0, int MN) {
+    if constexpr (KC) {
+#pragma unroll
+      for (int u = 0; u < kRegs; ++u) {
+        const int c = threadIdx.x + u * NT;
+        const int row = c >> 3, kc = c & 7;
+        goff[u] = min(mn0 + row, MN - 1) * ld + kc * 8;
+        loff[u] = row * kBK + swz(row, kc) * 8;
+      }
+    } else {
+#pragma unroll
+      for (int u = 0; u < kRegs / 2; ++u) {
+        const int t = threadIdx.x + u * NT;
+        const int mc = t % (ROWS / 8), kp = t / (ROWS / 8);
+        const int mn = min(mn0 + mc * 8, MN - 8);
+        goff[2 * u] = (2 * kp) * ld + mn;
+        goff[2 * u + 1] = (2 * kp + 1) * ld + mn;
+        loff[u] = (mc * 8) * kBK + 2 * (kp & 3);          // row and chunk swizzle are added per element
+      }
+    }
+  }
+  // quarter `part` (0..3) of the loads of a full slice: issued between the matrix instructions
+  __device__ inline void load_part(const bf16_t* P, int ld, int k0, int part) {
+    const bf16_t* base = KC ? P + k0 : P + (long long)k0 * ld;
+#pragma unroll
+    for (int u = 0; u < kRegs / 4; ++u)
+      r[part * (kRegs / 4) + u] = *reinterpret_cast<const u32x4*>(base + goff[part * (kRegs / 4) + u]);
+  }
+  // whole slice at once; the only path that handles a partial slice (k0 + 64 > kend, MC only)
+  __device__ inline void load(const bf16_t* P, int ld, int k0, int kend) {
+    if constexpr (KC) {
+      const bf16_t* base = P + k0;
+#pragma unroll
+      for (int u = 0; u < kRegs; ++u) r[u] = *reinterpret_cast<const u32x4*>(base + goff[u]);
+    } else if (k0 + kBK <= kend) {
+      const bf16_t* base = P + (long long)k0 * ld;
+#pragma unroll
+      for (int u = 0; u < kRegs; ++u) r[u] = *reinterpret_cast<const u32x4*>(base + goff[u]);
+    } else {
+#pragma unroll
+      for (int u = 0; u < kRegs / 2; ++u) {
+        const int t = threadIdx.x + u * NT;
+        const int kp = t / (ROWS / 8);
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+          const int k = k0 + 2 * kp + e;
+          const int back = max(k - (kend - 1), 0);         // rows to step back to stay inside the slice
+          const uint32_t mask = k < kend ? 0xffffffffu : 0u;
+          r[2 * u + e] = and4(*reinterpret_cast<const u32x4*>(P + (long long)(k0 - back) * ld + goff[2 * u + e]), mask);
+        }
+      }
+    }
+  }
+  __device__ inline void store(bf16_t* S) const {
+    if constexpr (KC) {
+#pragma unroll
+      for (int u = 0; u < kRegs; ++u) *reinterpret_cast<u32x4*>(S + loff[u]) = r[u];
+    } else {
+#pragma unroll
+      for (int u = 0; u < kRegs / 2; ++u) {
+        const int t = threadIdx.x + u * NT;
+        const int mc = t % (ROWS / 8), kp = t / (ROWS / 8);
+        Frag a, b;
+        a.q = r[2 * u];
+        b.q = r[2 * u + 1];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const int row = mc * 8 + j;
+          *reinterpret_cast<uint32_t*>(S + loff[u] + j * kBK + swz(row, kp >> 2) * 8) =
+              (uint32_t)a.h[j] | ((uint32_t)b.h[j] << 16);
+        }
+      }
+    }
+  }
+};
+
+// WM wavefront rows: tile (64*WM) x 128, 2*WM wavefronts of 64 x 64 each.
+template <bool AKC, bool BKC, typename OutT, int WM>
+__global__ __launch_bounds__(128 * WM, 1) void gemm_bf16_kernel(GemmBf16 g) {
+  constexpr int BM = 64 * WM, BN = 128, NT = 128 * WM;
+  __shared__ __attribute__((aligned(16))) bf16_t As[2 * BM * kBK];
+  __shared__ __attribute__((aligned(16))) bf16_t Bs[2 * BN * kBK];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   const int col = lane & 31, half = lane >> 5;
   const int zb = g.splitk > 1 ? blockIdx.z / g.splitk : blockIdx.z;
   const int sk = g.splitk > 1 ? blockIdx.z % g.splitk : 0;
-  const int m0 = blockIdx.y * 128, n0 = blockIdx.x * 128;
+  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
   const int kbeg = g.splitk > 1 ? sk * g.kchunk : 0;
   const int kend = g.splitk > 1 ? min(g.K, kbeg + g.kchunk) : g.K;
   floatx16 acc[2][2];
@@ -151,49 +210,89 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmBf16 g) {
   const int nseg = g.nseg > 1 ? g.nseg : 1;
   const int nk = (kend - kbeg + kBK - 1) / kBK;
   const int total = nseg * nk;
-  uint4 ra[4], rb[4];
-  auto fetch = [&](int it) {
-    const int seg = it / nk, k0 = kbeg + (it - seg * nk) * kBK;
-    const bf16_t* A = g.A[g.nseg > 1 ? seg : zb];
-    const bf16_t* Bm = g.B[g.nseg > 1 ? seg : zb];
-    if (AKC) load_kc(A, g.lda, m0, g.M, k0, kend, ra); else load_mc(A, g.lda, m0, g.M, k0, kend, ra);
-    if (BKC) load_kc(Bm, g.ldb, n0, g.N, k0, kend, rb); else load_mc(Bm, g.ldb, n0, g.N, k0, kend, rb);
-  };
-  auto stash = [&](int buf) {
-    if (AKC) store_kc(As + buf * kStage, ra); else store_mc(As + buf * kStage, ra);
-    if (BKC) store_kc(Bs + buf * kStage, rb); else store_mc(Bs + buf * kStage, rb);
-  };
-  if (total > 0) {
-    fetch(0);
-    stash(0);
+  // operand pointers of the (up to three) segments, or of this batch entry
+  const int zsel = g.nseg > 1 ? 0 : zb;
+  const bf16_t* A1 = g.A1; const bf16_t* B1 = g.B1;
+  const bf16_t* A2 = g.A2; const bf16_t* B2 = g.B2;
+  const bf16_t* A0 = zsel == 0 ? g.A0 : (zsel == 1 ? A1 : (zsel == 2 ? A2 : g.A3));
+  const bf16_t* B0 = zsel == 0 ? g.B0 : (zsel == 1 ? B1 : (zsel == 2 ? B2 : g.B3));
+  const bf16_t* Ap = A0;
+  const bf16_t* Bp = B0;
+  int fseg = 0, fk = kbeg;            // position of the next fetch
+  Stage<BM, NT, AKC> sa;
+  Stage<BN, NT, BKC> sb;
+  sa.init(g.lda, m0, g.M);
+  sb.init(g.ldb, n0, g.N);
+  // LDS offsets of this lane's fragments (k-chunk index 2*ks + half, swizzled per row)
+  int offA[2], offB[2], swA[2], swB[2];
+#pragma unroll
+  for (int t = 0; t < 2; ++t) {
+    const int ra_ = wm * 64 + t * 32 + col, rb_ = wn * 64 + t * 32 + col;
+    offA[t] = ra_ * kBK; swA[t] = ((ra_ >> 1) ^ (ra_ >> 4)) & 7;
+    offB[t] = rb_ * kBK; swB[t] = ((rb_ >> 1) ^ (rb_ >> 4)) & 7;
   }
+  // the host never launches with an empty K range
+  sa.load(Ap, g.lda, fk, kend);
+  sb.load(Bp, g.ldb, fk, kend);
+  sa.store(As);
+  sb.store(Bs);
   __syncthreads();
   for (int it = 0; it < total; ++it) {
     const int cur = it & 1;
-    if (it + 1 < total) fetch(it + 1);
-    const bf16_t* Ab = As + cur * kStage;
-    const bf16_t* Bb = Bs + cur * kStage;
+    const bf16_t* Ab = As + cur * BM * kBK;
+    const bf16_t* Bb = Bs + cur * BN * kBK;
+    // position of the slice after this one (branch-free; past the end it re-reads a valid slice,
+    // which is dropped, so that no load sits inside control flow)
+    const bool wrap = fk + kBK >= kend;
+    fk = wrap ? kbeg : fk + kBK;
+    fseg = min(fseg + (wrap ? 1 : 0), nseg - 1);
+    Ap = fseg == 0 ? A0 : (fseg == 1 ? A1 : A2);
+    Bp = fseg == 0 ? B0 : (fseg == 1 ? B1 : B2);
+    const bool full = fk + kBK <= kend;        // partial slices (weight gradients only) load in one go
+    bf16x8 fa[2][2], fb[2][2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      fa[0][t] = *reinterpret_cast<const bf16x8*>(Ab + offA[t] + (half ^ swA[t]) * 8);
+      fb[0][t] = *reinterpret_cast<const bf16x8*>(Bb + offB[t] + (half ^ swB[t]) * 8);
+    }
+    if (!full) {
+      sa.load(Ap, g.lda, fk, kend);
+      sb.load(Bp, g.ldb, fk, kend);
+    }
+    // Four steps of 16 k.  Each step issues a quarter of the next slice's global loads and the LDS
+    // reads of the following step, then its four matrix instructions; the scheduling barriers pin
+    // that order so that memory traffic sits in the shadow of the matrix cores.
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
-      Frag fa[2], fb[2];
+      __builtin_amdgcn_sched_barrier(0);
+      if (full) {
+        sa.load_part(Ap, g.lda, fk, ks);
+        sb.load_part(Bp, g.ldb, fk, ks);
+      }
+      if (ks < 3) {
 #pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        const int ra_ = wm * 64 + t * 32 + col, rb_ = wn * 64 + t * 32 + col;
-        fa[t].q = *reinterpret_cast<const uint4*>(Ab + ra_ * kBK + swz(ra_, ks * 2 + half) * 8);
-        fb[t].q = *reinterpret_cast<const uint4*>(Bb + rb_ * kBK + swz(rb_, ks * 2 + half) * 8);
+        for (int t = 0; t < 2; ++t) {
+          fa[(ks + 1) & 1][t] = *reinterpret_cast<const bf16x8*>(Ab + offA[t] + (((ks + 1) * 2 + half) ^ swA[t]) * 8);
+          fb[(ks + 1) & 1][t] = *reinterpret_cast<const bf16x8*>(Bb + offB[t] + (((ks + 1) * 2 + half) ^ swB[t]) * 8);
+        }
       }
 #pragma unroll
       for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = mfma(fa[i], fb[j], acc[i][j]);
+        for (int j = 0; j < 2; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][i], fb[ks & 1][j], acc[i][j], 0, 0, 0);
     }
     __builtin_amdgcn_sched_barrier(0);
-    if (it + 1 < total) stash(cur ^ 1);
+    if (it + 1 < total) {
+      sa.store(As + (cur ^ 1) * BM * kBK);
+      sb.store(Bs + (cur ^ 1) * BN * kBK);
+    }
     __syncthreads();
   }
 
-  const int zc = g.nseg > 1 ? 0 : zb;
-  const bf16_t* bias = g.splitk > 1 ? nullptr : g.bias[zc];
+  const bf16_t* bias_z = zsel == 0 ? g.bias0 : (zsel == 1 ? g.bias1 : (zsel == 2 ? g.bias2 : g.bias3));
+  void* C_z = zsel == 0 ? g.C0 : (zsel == 1 ? g.C1 : (zsel == 2 ? g.C2 : g.C3));
+  const bf16_t* bias = g.splitk > 1 ? nullptr : bias_z;
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -206,11 +305,11 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmBf16 g) {
         if (m < g.M && n < g.N) {
           const float val = acc[i][j][r] + bv;
           if (g.splitk > 1) {
-            reinterpret_cast<float*>(g.C[0])[((long long)blockIdx.z * g.M + m) * g.N + n] = val;
+            reinterpret_cast<float*>(g.C0)[((long long)blockIdx.z * g.M + m) * g.N + n] = val;
           } else if (sizeof(OutT) == 2) {
-            reinterpret_cast<bf16_t*>(g.C[zc])[(long long)m * g.ldc + n] = f2bf(val);
+            reinterpret_cast<bf16_t*>(C_z)[(long long)m * g.ldc + n] = f2bf(val);
           } else {
-            reinterpret_cast<float*>(g.C[zc])[(long long)m * g.ldc + n] = val;
+            reinterpret_cast<float*>(C_z)[(long long)m * g.ldc + n] = val;
           }
         }
       }
@@ -239,14 +338,22 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(SplitkReduce a) {
   }
 }
 
+// Tall tiles (128 x 128, four wavefronts) when they still give every compute unit work to overlap,
+// otherwise 64 x 128 tiles (two wavefronts) so that small problems spread over the chip.
 template <bool AKC, bool BKC, typename OutT>
 int launch_gemm(vardrop_ctx* ctx, int kid, const GemmBf16& g, int nz, hipStream_t s) {
   if (g.M == 0 || g.N == 0) return VARDROP_OK;
   const int sk = g.splitk > 1 ? g.splitk : 1;
-  dim3 grid(vd_ceil_div(g.N, 128), vd_ceil_div(g.M, 128), nz * sk);
+  const long long big = (long long)vd_ceil_div(g.N, 128) * vd_ceil_div(g.M, 128) * nz * sk;
   {
     VdTimer timer(ctx, kid, s);
-    hipLaunchKernelGGL((gemm_bf16_kernel<AKC, BKC, OutT>), grid, dim3(256), 0, s, g);
+    if (big >= 1024) {
+      dim3 grid(vd_ceil_div(g.N, 128), vd_ceil_div(g.M, 128), nz * sk);
+      hipLaunchKernelGGL((gemm_bf16_kernel<AKC, BKC, OutT, 2>), grid, dim3(256), 0, s, g);
+    } else {
+      dim3 grid(vd_ceil_div(g.N, 128), vd_ceil_div(g.M, 64), nz * sk);
+      hipLaunchKernelGGL((gemm_bf16_kernel<AKC, BKC, OutT, 1>), grid, dim3(128), 0, s, g);
+    }
   }
   VD_LAUNCH_CHECK(ctx);
   return VARDROP_OK;
@@ -257,43 +364,65 @@ constexpr int kDh = 64;
 constexpr int kTs = 72;              // LDS row stride of a 64-wide tile: 64 + 8 pad
 constexpr float kLog2e = 1.4426950408889634f;
 
-// rows [r0, r0+64) x 64 columns of a [n][d] head slice into LDS, row-major (k-contiguous)
+// 64 rows [r0, r0+64) x 64 columns of a [n][d] head slice, staged in registers so that the loads of
+// the next block are in flight while the current one is used.  A task is a pair of rows times an
+// 8-column chunk; the registers can be written to LDS row-major, transposed, or both.
 template <int NT>
-__device__ inline void tile_rows(bf16_t* S, const bf16_t* P, long long ld, int r0, int n) {
-  for (int c = threadIdx.x; c < 64 * 8; c += NT) {
-    const int row = c >> 3, ch = c & 7;
-    uint4 v = make_uint4(0, 0, 0, 0);
-    if (r0 + row < n) v = *reinterpret_cast<const uint4*>(P + (long long)(r0 + row) * ld + ch * 8);
-    *reinterpret_cast<uint4*>(S + row * kTs + ch * 8) = v;
-  }
-}
-// the same rows transposed: S[c][row]
-template <int NT>
-__device__ inline void tile_cols(bf16_t* S, const bf16_t* P, long long ld, int r0, int n) {
-  for (int c = threadIdx.x; c < 32 * 8; c += NT) {
-    const int rp = c & 31, ch = c >> 5;            // row pair, 8-column chunk
-    Frag a, b;
-    a.q = make_uint4(0, 0, 0, 0);
-    b.q = a.q;
-    if (r0 + 2 * rp < n) a.q = *reinterpret_cast<const uint4*>(P + (long long)(r0 + 2 * rp) * ld + ch * 8);
-    if (r0 + 2 * rp + 1 < n) b.q = *reinterpret_cast<const uint4*>(P + (long long)(r0 + 2 * rp + 1) * ld + ch * 8);
+struct Tile64 {
+  static constexpr int kTasks = 256 / NT;
+  u32x4 r[2 * kTasks];
+  __device__ inline void load(const bf16_t* P, long long ld, int r0, int n) {
 #pragma unroll
-    for (int j = 0; j < 8; ++j)
-      *reinterpret_cast<uint32_t*>(S + (ch * 8 + j) * kTs + 2 * rp) = (uint32_t)a.h[j] | ((uint32_t)b.h[j] << 16);
+    for (int u = 0; u < kTasks; ++u) {
+      const int c = threadIdx.x + u * NT;
+      const int rp = c & 31, ch = c >> 5;
+#pragma unroll
+      for (int e = 0; e < 2; ++e) {
+        const int row = r0 + 2 * rp + e;
+        const bool ok = row < n;
+        const u32x4 v = *reinterpret_cast<const u32x4*>(P + (long long)(ok ? row : 0) * ld + ch * 8);
+        r[2 * u + e] = ok ? v : u32x4{0u, 0u, 0u, 0u};
+      }
+    }
   }
-}
+  // S[row][col], row stride kTs
+  __device__ inline void store_rows(bf16_t* S) const {
+#pragma unroll
+    for (int u = 0; u < kTasks; ++u) {
+      const int c = threadIdx.x + u * NT;
+      const int rp = c & 31, ch = c >> 5;
+      *reinterpret_cast<u32x4*>(S + (2 * rp) * kTs + ch * 8) = r[2 * u];
+      *reinterpret_cast<u32x4*>(S + (2 * rp + 1) * kTs + ch * 8) = r[2 * u + 1];
+    }
+  }
+  // T[col][row], row stride kTs
+  __device__ inline void store_cols(bf16_t* T) const {
+#pragma unroll
+    for (int u = 0; u < kTasks; ++u) {
+      const int c = threadIdx.x + u * NT;
+      const int rp = c & 31, ch = c >> 5;
+      Frag a, b;
+      a.q = r[2 * u];
+      b.q = r[2 * u + 1];
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        *reinterpret_cast<uint32_t*>(T + (ch * 8 + j) * kTs + 2 * rp) = (uint32_t)a.h[j] | ((uint32_t)b.h[j] << 16);
+    }
+  }
+};
 // a lane's row of a head slice as four right-hand (or left-hand) operands: k = 16*s + 8*half + e
 __device__ inline void row_frags(Frag f[4], const bf16_t* P, long long ld, int row, int n, int half) {
+  const bool ok = row < n;
 #pragma unroll
   for (int s = 0; s < 4; ++s) {
-    f[s].q = make_uint4(0, 0, 0, 0);
-    if (row < n) f[s].q = *reinterpret_cast<const uint4*>(P + (long long)row * ld + s * 16 + half * 8);
+    const u32x4 v = *reinterpret_cast<const u32x4*>(P + (long long)(ok ? row : 0) * ld + s * 16 + half * 8);
+    f[s].q = ok ? v : u32x4{0u, 0u, 0u, 0u};
   }
 }
 // left-hand operand from a row-major tile: rows sub*32 + col, k = 16*s + 8*half ..
 __device__ inline Frag tile_frag(const bf16_t* S, int sub, int col, int s, int half) {
   Frag f;
-  f.q = *reinterpret_cast<const uint4*>(S + (sub * 32 + col) * kTs + s * 16 + half * 8);
+  f.q = *reinterpret_cast<const u32x4*>(S + (sub * 32 + col) * kTs + s * 16 + half * 8);
   return f;
 }
 // left-hand operand from a transposed tile T[c][row] matching accumulator registers 8*s2 .. 8*s2+7 of
@@ -301,18 +430,18 @@ __device__ inline Frag tile_frag(const bf16_t* S, int sub, int col, int s, int h
 __device__ inline Frag tileT_frag(const bf16_t* T, int ctile, int col, int sub, int s2, int half) {
   Frag f;
   const bf16_t* p = T + (ctile * 32 + col) * kTs + sub * 32 + 16 * s2 + 4 * half;
-  f.d[0] = *reinterpret_cast<const uint2*>(p);
-  f.d[1] = *reinterpret_cast<const uint2*>(p + 8);
+  f.d[0] = *reinterpret_cast<const u32x2*>(p);
+  f.d[1] = *reinterpret_cast<const u32x2*>(p + 8);
   return f;
 }
 // accumulator (transposed: rows = head dims, column = this lane's token) -> out[token][32*ct + ...]
 __device__ inline void store_accT(bf16_t* out_row, const floatx16& acc, int ct, int half, float mul) {
 #pragma unroll
   for (int g4 = 0; g4 < 4; ++g4) {
-    uint2 w;
+    u32x2 w;
     w.x = pack2(acc[4 * g4] * mul, acc[4 * g4 + 1] * mul);
     w.y = pack2(acc[4 * g4 + 2] * mul, acc[4 * g4 + 3] * mul);
-    *reinterpret_cast<uint2*>(out_row + ct * 32 + 8 * g4 + 4 * half) = w;
+    *reinterpret_cast<u32x2*>(out_row + ct * 32 + 8 * g4 + 4 * half) = w;
   }
 }
 
@@ -341,11 +470,18 @@ __global__ __launch_bounds__(NW * 64) void sdpa_fwd_bf16(SdpaArgs a) {
   floatx16 acc[2] = {zero16(), zero16()};
   float m = -INFINITY, l = 0.f;
   const float c = a.scale * kLog2e;
+  Tile64<NW * 64> tk, tv;
+  tk.load(a.k + base, ld, 0, n);
+  tv.load(a.v + base, ld, 0, n);
   for (int j0 = 0; j0 < n; j0 += 64) {
     __syncthreads();
-    tile_rows<NW * 64>(Ks, a.k + base, ld, j0, n);
-    tile_cols<NW * 64>(Vt, a.v + base, ld, j0, n);
+    tk.store_rows(Ks);
+    tv.store_cols(Vt);
     __syncthreads();
+    if (j0 + 64 < n) {
+      tk.load(a.k + base, ld, j0 + 64, n);
+      tv.load(a.v + base, ld, j0 + 64, n);
+    }
     floatx16 st[2];
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt) {
@@ -428,12 +564,19 @@ __global__ __launch_bounds__(NW * 64) void sdpa_bwd_dq_bf16(SdpaArgs a) {
   const float lse2 = qi < n ? a.lse[srow + qi] * kLog2e : INFINITY;
   const float c = a.scale * kLog2e;
   floatx16 acc[2] = {zero16(), zero16()};
+  Tile64<NW * 64> tk, tv;
+  tk.load(a.k + base, ld, 0, n);
+  tv.load(a.v + base, ld, 0, n);
   for (int j0 = 0; j0 < n; j0 += 64) {
     __syncthreads();
-    tile_rows<NW * 64>(Ks, a.k + base, ld, j0, n);
-    tile_rows<NW * 64>(Vs, a.v + base, ld, j0, n);
-    tile_cols<NW * 64>(Kt, a.k + base, ld, j0, n);
+    tk.store_rows(Ks);
+    tk.store_cols(Kt);
+    tv.store_rows(Vs);
     __syncthreads();
+    if (j0 + 64 < n) {
+      tk.load(a.k + base, ld, j0 + 64, n);
+      tv.load(a.v + base, ld, j0 + 64, n);
+    }
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt) {
       floatx16 st = zero16(), dp = zero16();
@@ -485,18 +628,32 @@ __global__ __launch_bounds__(NW * 64) void sdpa_bwd_dkv_bf16(SdpaArgs a) {
   row_frags(vf, a.v + base, ld, kj, n, half);
   const float c = a.scale * kLog2e;
   floatx16 accK[2] = {zero16(), zero16()}, accV[2] = {zero16(), zero16()};
+  Tile64<NW * 64> tq, to;
+  float lreg = 0.f, dreg = 0.f;
+  auto fetch = [&](int i0) {
+    tq.load(a.q + base, ld, i0, n);
+    to.load(a.dout + base, ld, i0, n);
+    if (threadIdx.x < 64) {
+      const int i = i0 + (int)threadIdx.x;
+      const bool ok = i < n;
+      const float l = a.lse[srow + (ok ? i : 0)], dd = a.Dsum[srow + (ok ? i : 0)];
+      lreg = ok ? l * kLog2e : INFINITY;
+      dreg = ok ? dd : 0.f;
+    }
+  };
+  fetch(0);
   for (int i0 = 0; i0 < n; i0 += 64) {
     __syncthreads();
-    tile_rows<NW * 64>(Qs, a.q + base, ld, i0, n);
-    tile_rows<NW * 64>(Os, a.dout + base, ld, i0, n);
-    tile_cols<NW * 64>(Qt, a.q + base, ld, i0, n);
-    tile_cols<NW * 64>(Ot, a.dout + base, ld, i0, n);
+    tq.store_rows(Qs);
+    tq.store_cols(Qt);
+    to.store_rows(Os);
+    to.store_cols(Ot);
     if (threadIdx.x < 64) {
-      const bool ok = i0 + (int)threadIdx.x < n;
-      Ls[threadIdx.x] = ok ? a.lse[srow + i0 + threadIdx.x] * kLog2e : INFINITY;
-      Ds[threadIdx.x] = ok ? a.Dsum[srow + i0 + threadIdx.x] : 0.f;
+      Ls[threadIdx.x] = lreg;
+      Ds[threadIdx.x] = dreg;
     }
     __syncthreads();
+    if (i0 + 64 < n) fetch(i0 + 64);
 #pragma unroll
     for (int qt = 0; qt < 2; ++qt) {
       floatx16 st = zero16(), dp = zero16();
@@ -569,8 +726,8 @@ int launch_core(vardrop_ctx* ctx, int kid, F kernel2, F kernel4, const SdpaArgs&
 // Number of K slices of the weight-gradient GEMMs (K = B*n rows): enough workgroups to fill the
 // chip, slices of at least 256 rows, a multiple of the 64-row stage.
 int vd_attn_bf16_splitk(int d, long long M, int* kchunk) {
-  const int tiles = vd_ceil_div(d, 128) * vd_ceil_div(d, 128) * 4;
-  int s = 512 / tiles;
+  const int tiles = vd_ceil_div(d, 128) * vd_ceil_div(d, 64) * 4;
+  int s = 768 / tiles;
   if (s > 8) s = 8;
   while (s > 1 && M / s < 256) --s;
   if (s < 1) s = 1;
@@ -601,12 +758,8 @@ int vd_attn_fwd_bf16(vardrop_ctx* ctx, const void* xs, int B, int n, int d, int 
   bf16_t* o = v + M * d;
   float* lse = (float*)(o + M * d);
   GemmBf16 g = {};
-  for (int z = 0; z < 3; ++z) {
-    g.A[z] = (const bf16_t*)xs;
-    g.B[z] = (const bf16_t*)W[z];
-    g.bias[z] = (const bf16_t*)bias[z];
-  }
-  g.C[0] = q; g.C[1] = k; g.C[2] = v;
+  bf16_t* qkv[3] = {q, k, v};
+  for (int z = 0; z < 3; ++z) g.set(z, xs, W[z], qkv[z], bias[z]);
   g.lda = d; g.ldb = d; g.ldc = d;
   g.M = (int)M; g.N = d; g.K = d; g.nseg = 1;
   int rc = launch_gemm<true, false, bf16_t>(ctx, VARDROP_K_GEMM_QKV, g, 3, s);
@@ -617,7 +770,7 @@ int vd_attn_fwd_bf16(vardrop_ctx* ctx, const void* xs, int B, int n, int d, int 
   rc = launch_core(ctx, VARDROP_K_SDPA_FWD, sdpa_fwd_bf16<2>, sdpa_fwd_bf16<4>, a, B, s);
   if (rc) return rc;
   GemmBf16 go = {};
-  go.A[0] = o; go.B[0] = (const bf16_t*)W[3]; go.C[0] = y; go.bias[0] = (const bf16_t*)bias[3];
+  go.set(0, o, W[3], y, bias[3]);
   go.lda = d; go.ldb = d; go.ldc = d;
   go.M = (int)M; go.N = d; go.K = d; go.nseg = 1;
   return launch_gemm<true, false, bf16_t>(ctx, VARDROP_K_GEMM_OUT, go, 1, s);
@@ -641,7 +794,7 @@ int vd_attn_bwd_bf16(vardrop_ctx* ctx, const void* dy, const void* xs, int B, in
   int rc;
   {  // dO = dy Wo^T
     GemmBf16 g = {};
-    g.A[0] = (const bf16_t*)dy; g.B[0] = (const bf16_t*)W[3]; g.C[0] = dO;
+    g.set(0, dy, W[3], dO, nullptr);
     g.lda = d; g.ldb = d; g.ldc = d;
     g.M = (int)M; g.N = d; g.K = d; g.nseg = 1;
     if ((rc = launch_gemm<true, true, bf16_t>(ctx, VARDROP_K_GEMM_DO, g, 1, s))) return rc;
@@ -656,9 +809,7 @@ int vd_attn_bwd_bf16(vardrop_ctx* ctx, const void* dy, const void* xs, int B, in
     GemmBf16 g = {};
     const bf16_t* lhs[4] = {(const bf16_t*)xs, (const bf16_t*)xs, (const bf16_t*)xs, o};
     const bf16_t* rhs[4] = {dq, dk, dv, (const bf16_t*)dy};
-    for (int z = 0; z < 4; ++z) {
-      g.A[z] = lhs[z]; g.B[z] = rhs[z]; g.C[z] = dW[z];
-    }
+    for (int z = 0; z < 4; ++z) g.set(z, lhs[z], rhs[z], dW[z], nullptr);
     g.lda = d; g.ldb = d; g.ldc = d;
     g.M = d; g.N = d; g.K = (int)M; g.nseg = 1;
     int kchunk = 0;
@@ -666,7 +817,7 @@ int vd_attn_bwd_bf16(vardrop_ctx* ctx, const void* dy, const void* xs, int B, in
     g.kchunk = kchunk;
     if (g.splitk > 1) {
       float* part = (float*)((char*)ws + vd_attn_bf16_partial_offset(B, n, d, H));
-      g.C[0] = part;
+      g.C0 = part;
       if ((rc = launch_gemm<false, false, float>(ctx, VARDROP_K_GEMM_DW, g, 4, s))) return rc;
       SplitkReduce r = {};
       r.part = part;
@@ -685,10 +836,7 @@ int vd_attn_bwd_bf16(vardrop_ctx* ctx, const void* dy, const void* xs, int B, in
   {  // dxs = dq Wq^T + dk Wk^T + dv Wv^T
     GemmBf16 g = {};
     const bf16_t* grads[3] = {dq, dk, dv};
-    for (int z = 0; z < 3; ++z) {
-      g.A[z] = grads[z]; g.B[z] = (const bf16_t*)W[z];
-    }
-    g.C[0] = dxs;
+    for (int z = 0; z < 3; ++z) g.set(z, grads[z], W[z], z == 0 ? dxs : nullptr, nullptr);
     g.lda = d; g.ldb = d; g.ldc = d;
     g.M = (int)M; g.N = d; g.K = d; g.nseg = 3;
     if ((rc = launch_gemm<true, true, bf16_t>(ctx, VARDROP_K_GEMM_DXS, g, 1, s))) return rc;
