@@ -136,8 +136,8 @@ struct Stage {
   __device__ inline void load_part(const bf16_t* P, int ld, int k0, int part) {
     const bf16_t* base = KC ? P + k0 : P + (long long)k0 * ld;
 #pragma unroll
-    for (int u = 0; u < kRegs / 4; ++u)
-      r[part * (kRegs / 4) + u] = *reinterpret_cast<const u32x4*>(base + goff[part * (kRegs / 4) + u]);
+    for (int u = 0; u < kRegs; ++u)
+      if (u * 4 / kRegs == part) r[u] = *reinterpret_cast<const u32x4*>(base + goff[u]);
   }
   // whole slice at once; the only path that handles a partial slice (k0 + 64 > kend, MC only)
   __device__ inline void load(const bf16_t* P, int ld, int k0, int kend) {
@@ -187,10 +187,12 @@ struct Stage {
   }
 };
 
-// WM wavefront rows: tile (64*WM) x 128, 2*WM wavefronts of 64 x 64 each.
-template <bool AKC, bool BKC, typename OutT, int WM>
-__global__ __launch_bounds__(128 * WM, 1) void gemm_bf16_kernel(GemmBf16 g) {
-  constexpr int BM = 64 * WM, BN = 128, NT = 128 * WM;
+// Tile (32*MI*WR) x 128 computed by WR x 2 wavefronts of (32*MI) x 64 each:
+//   MI = 2, WR = 2: 128 x 128, for problems with enough tiles to fill the chip;
+//   MI = 1, WR = 2:  64 x 128, four wavefronts so that a lone workgroup still uses all four SIMDs.
+template <bool AKC, bool BKC, typename OutT, int MI, int WR>
+__global__ __launch_bounds__(128 * WR, 1) void gemm_bf16_kernel(GemmBf16 g) {
+  constexpr int BM = 32 * MI * WR, BN = 128, NT = 128 * WR;
   __shared__ __attribute__((aligned(16))) bf16_t As[2 * BM * kBK];
   __shared__ __attribute__((aligned(16))) bf16_t Bs[2 * BN * kBK];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -201,9 +203,9 @@ __global__ __launch_bounds__(128 * WM, 1) void gemm_bf16_kernel(GemmBf16 g) {
   const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
   const int kbeg = g.splitk > 1 ? sk * g.kchunk : 0;
   const int kend = g.splitk > 1 ? min(g.K, kbeg + g.kchunk) : g.K;
-  floatx16 acc[2][2];
+  floatx16 acc[MI][2];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < MI; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j) acc[i][j] = zero16();
 
@@ -224,11 +226,15 @@ __global__ __launch_bounds__(128 * WM, 1) void gemm_bf16_kernel(GemmBf16 g) {
   sa.init(g.lda, m0, g.M);
   sb.init(g.ldb, n0, g.N);
   // LDS offsets of this lane's fragments (k-chunk index 2*ks + half, swizzled per row)
-  int offA[2], offB[2], swA[2], swB[2];
+  int offA[MI], offB[2], swA[MI], swB[2];
+#pragma unroll
+  for (int t = 0; t < MI; ++t) {
+    const int ra_ = wm * 32 * MI + t * 32 + col;
+    offA[t] = ra_ * kBK; swA[t] = ((ra_ >> 1) ^ (ra_ >> 4)) & 7;
+  }
 #pragma unroll
   for (int t = 0; t < 2; ++t) {
-    const int ra_ = wm * 64 + t * 32 + col, rb_ = wn * 64 + t * 32 + col;
-    offA[t] = ra_ * kBK; swA[t] = ((ra_ >> 1) ^ (ra_ >> 4)) & 7;
+    const int rb_ = wn * 64 + t * 32 + col;
     offB[t] = rb_ * kBK; swB[t] = ((rb_ >> 1) ^ (rb_ >> 4)) & 7;
   }
   // the host never launches with an empty K range
@@ -249,12 +255,11 @@ __global__ __launch_bounds__(128 * WM, 1) void gemm_bf16_kernel(GemmBf16 g) {
     Ap = fseg == 0 ? A0 : (fseg == 1 ? A1 : A2);
     Bp = fseg == 0 ? B0 : (fseg == 1 ? B1 : B2);
     const bool full = fk + kBK <= kend;        // partial slices (weight gradients only) load in one go
-    bf16x8 fa[2][2], fb[2][2];
+    bf16x8 fa[2][MI], fb[2][2];
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      fa[0][t] = *reinterpret_cast<const bf16x8*>(Ab + offA[t] + (half ^ swA[t]) * 8);
-      fb[0][t] = *reinterpret_cast<const bf16x8*>(Bb + offB[t] + (half ^ swB[t]) * 8);
-    }
+    for (int t = 0; t < MI; ++t) fa[0][t] = *reinterpret_cast<const bf16x8*>(Ab + offA[t] + (half ^ swA[t]) * 8);
+#pragma unroll
+    for (int t = 0; t < 2; ++t) fb[0][t] = *reinterpret_cast<const bf16x8*>(Bb + offB[t] + (half ^ swB[t]) * 8);
     if (!full) {
       sa.load(Ap, g.lda, fk, kend);
       sb.load(Bp, g.ldb, fk, kend);
@@ -271,13 +276,14 @@ __global__ __launch_bounds__(128 * WM, 1) void gemm_bf16_kernel(GemmBf16 g) {
       }
       if (ks < 3) {
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
+        for (int t = 0; t < MI; ++t)
           fa[(ks + 1) & 1][t] = *reinterpret_cast<const bf16x8*>(Ab + offA[t] + (((ks + 1) * 2 + half) ^ swA[t]) * 8);
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
           fb[(ks + 1) & 1][t] = *reinterpret_cast<const bf16x8*>(Bb + offB[t] + (((ks + 1) * 2 + half) ^ swB[t]) * 8);
-        }
       }
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+      for (int i = 0; i < MI; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][i], fb[ks & 1][j], acc[i][j], 0, 0, 0);
@@ -294,14 +300,14 @@ __global__ __launch_bounds__(128 * WM, 1) void gemm_bf16_kernel(GemmBf16 g) {
   void* C_z = zsel == 0 ? g.C0 : (zsel == 1 ? g.C1 : (zsel == 2 ? g.C2 : g.C3));
   const bf16_t* bias = g.splitk > 1 ? nullptr : bias_z;
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < MI; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       const int n = n0 + wn * 64 + j * 32 + col;
       const float bv = (bias && n < g.N) ? bf2f(bias[n]) : 0.f;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int m = m0 + wm * 64 + i * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+        const int m = m0 + wm * 32 * MI + i * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
         if (m < g.M && n < g.N) {
           const float val = acc[i][j][r] + bv;
           if (g.splitk > 1) {
@@ -338,8 +344,8 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(SplitkReduce a) {
   }
 }
 
-// Tall tiles (128 x 128, four wavefronts) when they still give every compute unit work to overlap,
-// otherwise 64 x 128 tiles (two wavefronts) so that small problems spread over the chip.
+// 128 x 128 tiles when they still give every compute unit several workgroups to overlap, otherwise
+// 64 x 128 tiles so that small problems spread over the chip.
 template <bool AKC, bool BKC, typename OutT>
 int launch_gemm(vardrop_ctx* ctx, int kid, const GemmBf16& g, int nz, hipStream_t s) {
   if (g.M == 0 || g.N == 0) return VARDROP_OK;
@@ -349,10 +355,10 @@ int launch_gemm(vardrop_ctx* ctx, int kid, const GemmBf16& g, int nz, hipStream_
     VdTimer timer(ctx, kid, s);
     if (big >= 1024) {
       dim3 grid(vd_ceil_div(g.N, 128), vd_ceil_div(g.M, 128), nz * sk);
-      hipLaunchKernelGGL((gemm_bf16_kernel<AKC, BKC, OutT, 2>), grid, dim3(256), 0, s, g);
+      hipLaunchKernelGGL((gemm_bf16_kernel<AKC, BKC, OutT, 2, 2>), grid, dim3(256), 0, s, g);
     } else {
       dim3 grid(vd_ceil_div(g.N, 128), vd_ceil_div(g.M, 64), nz * sk);
-      hipLaunchKernelGGL((gemm_bf16_kernel<AKC, BKC, OutT, 1>), grid, dim3(128), 0, s, g);
+      hipLaunchKernelGGL((gemm_bf16_kernel<AKC, BKC, OutT, 1, 2>), grid, dim3(256), 0, s, g);
     }
   }
   VD_LAUNCH_CHECK(ctx);

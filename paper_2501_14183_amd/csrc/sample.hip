@@ -44,27 +44,164 @@ __device__ inline bool less_group(uint64_t ka, uint32_t pa, uint64_t kb, uint32_
   return (pa & 0xffffu) < (pb & 0xffffu);
 }
 
+// Bitonic sort of npad = E * blockDim.x (key, payload) pairs, E consecutive elements per thread
+// (element i = tid * E + e).  A compare-exchange with partner i ^ stride stays inside the thread
+// for stride < E, inside the wavefront (lane shuffles) for stride < 64 * E, and only goes through
+// LDS above that, which leaves a handful of barrier-separated passes instead of log^2(npad) / 2.
 template <bool kByGroup>
-__device__ void bitonic_sort(uint64_t* key, uint32_t* pay, int npad) {
-  const int tid = threadIdx.x, nt = blockDim.x;
-  for (int size = 2; size <= npad; size <<= 1) {
-    for (int stride = size >> 1; stride > 0; stride >>= 1) {
-      __syncthreads();
-      for (int p = tid; p < (npad >> 1); p += nt) {
-        const int lo = ((p & ~(stride - 1)) << 1) | (p & (stride - 1));
-        const int hi = lo + stride;
-        const bool up = (lo & size) == 0;
-        const uint64_t ka = key[lo], kb = key[hi];
-        const uint32_t pa = pay[lo], pb = pay[hi];
-        const bool b_lt_a = kByGroup ? less_group(kb, pb, ka, pa) : less_hash(kb, pb, ka, pa);
-        if (b_lt_a == up) {
-          key[lo] = kb;
-          key[hi] = ka;
-          pay[lo] = pb;
-          pay[hi] = pa;
-        }
+__device__ inline bool pair_less(uint64_t ka, uint32_t pa, uint64_t kb, uint32_t pb) {
+  return kByGroup ? less_group(ka, pa, kb, pb) : less_hash(ka, pa, kb, pb);
+}
+
+// compare-exchange of the register pairs (e, e ^ S) of one thread; all indices are compile-time
+template <int E, int S, bool kByGroup>
+__device__ inline void in_thread_exchange(uint64_t (&k)[E], uint32_t (&p)[E], int tid, int size) {
+#pragma unroll
+  for (int e = 0; e < E; ++e) {
+    const int f = e ^ S;
+    if (f > e && f < E) {
+      const bool up = ((tid * E + e) & size) == 0;
+      const bool f_less = pair_less<kByGroup>(k[f], p[f], k[e], p[e]);
+      if (f_less == up) {
+        const uint64_t tk = k[e];
+        const uint32_t tp = p[e];
+        k[e] = k[f];
+        p[e] = p[f];
+        k[f] = tk;
+        p[f] = tp;
       }
     }
+  }
+}
+
+// The same network for bare 64-bit keys (ascending): two shuffles and one compare per exchange.
+template <int E, int S>
+__device__ inline void in_thread_exchange_u64(uint64_t (&k)[E], int tid, int size) {
+#pragma unroll
+  for (int e = 0; e < E; ++e) {
+    const int f = e ^ S;
+    if (f > e && f < E) {
+      const bool up = ((tid * E + e) & size) == 0;
+      if ((k[f] < k[e]) == up) {
+        const uint64_t t = k[e];
+        k[e] = k[f];
+        k[f] = t;
+      }
+    }
+  }
+}
+
+template <int E>
+__device__ void bitonic_sort_u64(uint64_t* key, int npad) {
+  const int tid = threadIdx.x;
+  uint64_t k[E];
+  __syncthreads();
+#pragma unroll
+  for (int e = 0; e < E; ++e) k[e] = key[tid * E + e];
+  for (int size = 2; size <= npad; size <<= 1) {
+    for (int stride = size >> 1; stride > 0; stride >>= 1) {
+      if (stride >= 64 * E) {
+        __syncthreads();
+#pragma unroll
+        for (int e = 0; e < E; ++e) key[tid * E + e] = k[e];
+        __syncthreads();
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+          const int i = tid * E + e;
+          const uint64_t ok = key[i ^ stride];
+          const bool keep_min = ((i & stride) == 0) == ((i & size) == 0);
+          if ((ok < k[e]) == keep_min) k[e] = ok;
+        }
+      } else if (stride >= E) {
+        const int d = stride / E;
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+          const int i = tid * E + e;
+          const uint32_t lo = __shfl_xor((uint32_t)k[e], d, 64);
+          const uint32_t hi = __shfl_xor((uint32_t)(k[e] >> 32), d, 64);
+          const uint64_t ok = ((uint64_t)hi << 32) | lo;
+          const bool keep_min = ((i & stride) == 0) == ((i & size) == 0);
+          if ((ok < k[e]) == keep_min) k[e] = ok;
+        }
+      } else if (stride == 4) {
+        in_thread_exchange_u64<E, 4>(k, tid, size);
+      } else if (stride == 2) {
+        in_thread_exchange_u64<E, 2>(k, tid, size);
+      } else {
+        in_thread_exchange_u64<E, 1>(k, tid, size);
+      }
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int e = 0; e < E; ++e) key[tid * E + e] = k[e];
+  __syncthreads();
+}
+
+template <int E, bool kByGroup>
+__device__ void bitonic_sort(uint64_t* key, uint32_t* pay, int npad) {
+  const int tid = threadIdx.x;
+  uint64_t k[E];
+  uint32_t p[E];
+  __syncthreads();                               // the arrays were filled by other threads
+#pragma unroll
+  for (int e = 0; e < E; ++e) {
+    k[e] = key[tid * E + e];
+    p[e] = pay[tid * E + e];
+  }
+  for (int size = 2; size <= npad; size <<= 1) {
+    for (int stride = size >> 1; stride > 0; stride >>= 1) {
+      if (stride >= 64 * E) {
+        // partner lives in another wavefront: exchange through LDS
+        __syncthreads();
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+          key[tid * E + e] = k[e];
+          pay[tid * E + e] = p[e];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+          const int i = tid * E + e, j = i ^ stride;
+          const uint64_t ok = key[j];
+          const uint32_t op = pay[j];
+          const bool keep_min = ((i & stride) == 0) == ((i & size) == 0);
+          const bool other_less = pair_less<kByGroup>(ok, op, k[e], p[e]);
+          if (other_less == keep_min) {
+            k[e] = ok;
+            p[e] = op;
+          }
+        }
+      } else if (stride >= E) {
+        const int d = stride / E;             // lane distance
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+          const int i = tid * E + e;
+          const uint32_t lo = __shfl_xor((uint32_t)k[e], d, 64);
+          const uint32_t hi = __shfl_xor((uint32_t)(k[e] >> 32), d, 64);
+          const uint32_t op = __shfl_xor(p[e], d, 64);
+          const uint64_t ok = ((uint64_t)hi << 32) | lo;
+          const bool keep_min = ((i & stride) == 0) == ((i & size) == 0);
+          const bool other_less = pair_less<kByGroup>(ok, op, k[e], p[e]);
+          if (other_less == keep_min) {
+            k[e] = ok;
+            p[e] = op;
+          }
+        }
+      } else if (stride == 4) {
+        in_thread_exchange<E, 4, kByGroup>(k, p, tid, size);
+      } else if (stride == 2) {
+        in_thread_exchange<E, 2, kByGroup>(k, p, tid, size);
+      } else {
+        in_thread_exchange<E, 1, kByGroup>(k, p, tid, size);
+      }
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int e = 0; e < E; ++e) {
+    key[tid * E + e] = k[e];
+    pay[tid * E + e] = p[e];
   }
   __syncthreads();
 }
@@ -110,6 +247,10 @@ __device__ int block_exclusive_scan(int* vals, int count, int* wsum) {
   return total;
 }
 
+constexpr int kIndexBits = 14;              // variate index (and padding index) below 16384
+constexpr int kPackShift = 64 - kIndexBits;  // hashes below 2^50 can share a key with the index
+constexpr int kCountMax = 1024;             // largest group ranked by counting instead of sorting
+
 struct SampleArgs {
   const uint64_t* hash;
   int32_t* group_id;
@@ -120,6 +261,16 @@ struct SampleArgs {
   uint32_t seed_lo, seed_hi, step_lo, step_hi;
 };
 
+// members kept from a group of `size` (Eq. 1 with the optional keep ratio)
+__device__ inline uint32_t keep_count(uint32_t size, const SampleArgs& a) {
+  uint64_t by_ratio = ((uint64_t)size * a.num + a.den - 1) / a.den;
+  if (by_ratio < 1) by_ratio = 1;
+  uint32_t keep = by_ratio < size ? (uint32_t)by_ratio : size;
+  if (a.gs != 0 && keep > a.gs) keep = a.gs;
+  return keep;
+}
+
+template <int E>
 __global__ __launch_bounds__(1024) void sample_kernel(SampleArgs a) {
   extern __shared__ unsigned char smem[];
   const int N = a.N, npad = a.npad;
@@ -130,11 +281,27 @@ __global__ __launch_bounds__(1024) void sample_kernel(SampleArgs a) {
   uint16_t* gstart = reinterpret_cast<uint16_t*>(wsum + 20);           // [npad + 1], values <= 8192
   const int tid = threadIdx.x, nt = blockDim.x;
 
-  for (int i = tid; i < npad; i += nt) {
-    key[i] = i < N ? a.hash[i] : ~0ull;
-    pay[i] = (uint32_t)i;
+  // Sort 1.  When every hash fits 50 bits (always for the radix-R code of k <= 5 bins), hash and
+  // variate index share one 64-bit key and the cheaper key-only network applies.
+  int wide = 0;
+  for (int i = tid; i < N; i += nt) wide |= (a.hash[i] >> kPackShift) != 0;
+  wide = __syncthreads_or(wide);
+  if (!wide) {
+    for (int i = tid; i < npad; i += nt) key[i] = i < N ? ((a.hash[i] << kIndexBits) | (uint64_t)i) : ~0ull;
+    bitonic_sort_u64<E>(key, npad);
+    for (int i = tid; i < npad; i += nt) {
+      const uint64_t v = key[i];
+      pay[i] = (uint32_t)(v & ((1u << kIndexBits) - 1));
+      key[i] = v >> kIndexBits;
+    }
+    __syncthreads();
+  } else {
+    for (int i = tid; i < npad; i += nt) {
+      key[i] = i < N ? a.hash[i] : ~0ull;
+      pay[i] = (uint32_t)i;
+    }
+    bitonic_sort<E, false>(key, pay, npad);
   }
-  bitonic_sort<false>(key, pay, npad);
 
   // segment heads -> dense group ids
   for (int p = tid; p < N; p += nt) scan[p] = (p == 0 || key[p] != key[p - 1]) ? 1 : 0;
@@ -146,8 +313,12 @@ __global__ __launch_bounds__(1024) void sample_kernel(SampleArgs a) {
     if (head) gstart[g] = (uint16_t)p;
     scan[p] = g;
   }
-  if (tid == 0) gstart[G] = (uint16_t)N;
+  if (tid == 0) {
+    gstart[G] = (uint16_t)N;
+    wsum[18] = 0;
+  }
   __syncthreads();
+  for (int g = tid; g < G; g += nt) atomicMax(&wsum[18], (int)gstart[g + 1] - (int)gstart[g]);
   for (int p = tid; p < N; p += nt) {
     const uint32_t n = pay[p];
     const int g = scan[p];
@@ -157,21 +328,34 @@ __global__ __launch_bounds__(1024) void sample_kernel(SampleArgs a) {
     key[p] = ((uint64_t)r0 << 32) | r1;
     pay[p] = ((uint32_t)g << 16) | n;
   }
-  for (int p = N + tid; p < npad; p += nt) {
-    key[p] = ~0ull;
-    pay[p] = 0xffffffffu;                                 // group 65535 sorts after every real group
-  }
-  bitonic_sort<true>(key, pay, npad);
-
-  // keep the first n_i members of every segment; flags indexed by variate
-  for (int p = tid; p < N; p += nt) {
-    const uint32_t g = pay[p] >> 16, n = pay[p] & 0xffffu;
-    const uint32_t size = (uint32_t)gstart[g + 1] - (uint32_t)gstart[g];
-    uint64_t by_ratio = ((uint64_t)size * a.num + a.den - 1) / a.den;
-    if (by_ratio < 1) by_ratio = 1;
-    uint32_t keep = by_ratio < size ? (uint32_t)by_ratio : size;
-    if (a.gs != 0 && keep > a.gs) keep = a.gs;
-    scan[n] = ((uint32_t)p - (uint32_t)gstart[g] < keep) ? 1 : 0;
+  __syncthreads();
+  const int max_group = wsum[18];
+  if (max_group <= kCountMax) {
+    // Groups are short: the rank of a member inside its group is a count over the group.
+    for (int p = tid; p < N; p += nt) {
+      const uint32_t g = pay[p] >> 16, n = pay[p] & 0xffffu;
+      const int s0 = gstart[g], s1 = gstart[g + 1];
+      const uint64_t ku = key[p];
+      uint32_t rank = 0;
+      for (int q = s0; q < s1; ++q) {
+        const uint64_t kq = key[q];
+        const uint32_t nq = pay[q] & 0xffffu;
+        rank += (kq < ku || (kq == ku && nq < n)) ? 1u : 0u;
+      }
+      scan[n] = rank < keep_count((uint32_t)(s1 - s0), a) ? 1 : 0;
+    }
+  } else {
+    for (int p = N + tid; p < npad; p += nt) {
+      key[p] = ~0ull;
+      pay[p] = 0xffffffffu;                               // group 65535 sorts after every real group
+    }
+    bitonic_sort<E, true>(key, pay, npad);
+    // keep the first n_i members of every segment; flags indexed by variate
+    for (int p = tid; p < N; p += nt) {
+      const uint32_t g = pay[p] >> 16, n = pay[p] & 0xffffu;
+      const uint32_t size = (uint32_t)gstart[g + 1] - (uint32_t)gstart[g];
+      scan[n] = ((uint32_t)p - (uint32_t)gstart[g] < keep_count(size, a)) ? 1 : 0;
+    }
   }
   __syncthreads();
   // the flags are needed after the scan as well: keep a copy in the payload array
@@ -211,8 +395,8 @@ extern "C" int vardrop_sample(vardrop_ctx* ctx, const uint64_t* hash, int N,
   if (npad < 128) npad = 128;
   const size_t lds = (size_t)npad * 16 + 20 * 4 + (size_t)(npad + 1) * 2 + 14;
   if (lds > (size_t)ctx->lds_per_block) return VARDROP_EUNSUPPORTED;
-  int threads = npad / 2;
-  if (threads > 1024) threads = 1024;
+  const int E = npad <= 2048 ? 2 : (npad == 4096 ? 4 : 8);     // elements per thread of the sort
+  const int threads = npad / E;
   SampleArgs a;
   a.hash = hash;
   a.group_id = group_id;
@@ -228,11 +412,14 @@ extern "C" int vardrop_sample(vardrop_ctx* ctx, const uint64_t* hash, int N,
   a.step_lo = (uint32_t)step;
   a.step_hi = (uint32_t)(step >> 32);
   hipStream_t s = (hipStream_t)stream;
+  const void* fn = E == 2 ? (const void*)sample_kernel<2> : (E == 4 ? (const void*)sample_kernel<4> : (const void*)sample_kernel<8>);
   if (lds > 65536)
-    VD_HIP(ctx, hipFuncSetAttribute((const void*)sample_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    VD_HIP(ctx, hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
   {
     VdTimer timer(ctx, VARDROP_K_SAMPLE, s);
-    hipLaunchKernelGGL(sample_kernel, dim3(1), dim3(threads), lds, s, a);
+    if (E == 2) hipLaunchKernelGGL(sample_kernel<2>, dim3(1), dim3(threads), lds, s, a);
+    else if (E == 4) hipLaunchKernelGGL(sample_kernel<4>, dim3(1), dim3(threads), lds, s, a);
+    else hipLaunchKernelGGL(sample_kernel<8>, dim3(1), dim3(threads), lds, s, a);
   }
   VD_LAUNCH_CHECK(ctx);
   if (counts_host)
