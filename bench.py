@@ -50,6 +50,27 @@ def algorithmic_work(w, n):
     }
 
 
+def recorded_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel` from the committed hardware-counter summary, or None when the
+    kernels have changed since the counters were taken (the summary records a hash of csrc/)."""
+    import glob
+    import hashlib
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_%s.txt" % workload)
+    if not os.path.exists(path):
+        return None
+    h = hashlib.sha256()
+    for f in sorted(glob.glob(os.path.join(ROOT, "paper_2501_14183_amd", "csrc", "*"))):
+        h.update(open(f, "rb").read())
+    lines = open(path).read().splitlines()
+    if not lines or ("csrc=" + h.hexdigest()[:16]) not in lines[0]:
+        return None
+    for line in lines[1:]:
+        value, name = line.split("\t")
+        if name == kernel:
+            return float(value)
+    return None
+
+
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -58,6 +79,8 @@ def parse():
     ap.add_argument("--workload", default="traffic")
     ap.add_argument("--batches", type=int, default=4, help="distinct pre-generated batches the steps rotate through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run five plain 256 MiB device copies (reference for hardware byte counters)")
     return ap.parse_args()
 
 
@@ -159,6 +182,14 @@ def main():
     saved = torch.empty(lib.vardrop_attn_saved_bytes(w.B, w.N, w.d, w.H, code), dtype=torch.uint8, device=dev)
     ws = torch.empty(lib.vardrop_attn_workspace_bytes(w.B, w.N, w.d, w.H, code), dtype=torch.uint8, device=dev)
 
+    if args.copy_calibration:
+        src = torch.zeros(256 << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -192,14 +223,24 @@ def main():
     total_ms, launches = vd.vardrop_profile_read(ctx)
     vd.vardrop_profile_select(ctx, -1)
     bound, work = algorithmic_work(w, n_mean)[dominant]
-    avg_s = total_ms * 1e-3 / max(launches, 1)
+    # an empty event pair on the same stream measures what the bracket itself adds
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    gaps = []
+    for _ in range(50):
+        e0.record()
+        e1.record()
+        e1.synchronize()
+        gaps.append(e0.elapsed_time(e1))
+    gap_ms = float(np.median(gaps))
+    avg_s = max(total_ms / max(launches, 1) - gap_ms, 1e-6) * 1e-3
     if bound == "hbm":
         achieved, peak, unit = work / avg_s / 1e9, PEAK_HBM_GBS, "GB/s"
     else:
         achieved, unit = work / avg_s / 1e12, "TFLOP/s"
         peak = PEAK_BF16_TFLOPS if bound == "mfma" else PEAK_FP32_TFLOPS
     roof = {"kernel": dominant, "bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
-            "frac": achieved / peak, "traffic": None, "avg_launch_us": avg_s * 1e6, "launches": launches,
+            "frac": achieved / peak, "traffic": recorded_traffic(w.name, dominant),
+            "avg_launch_us": avg_s * 1e6, "event_pair_overhead_us": gap_ms * 1e3, "launches": launches,
             "us_per_step_by_kernel": {k: round(v[1], 2) for k, v in census.items()}}
 
     out = {
