@@ -2,7 +2,8 @@
 """Benchmark of the VarDrop training hot path on one MI355X.
 
 One step = vardrop_hash -> vardrop_sample -> (read N') -> vardrop_gather -> vardrop_attn_fwd
--> vardrop_attn_bwd over one batch of synthetic windows and tokens that already sit in HBM.
+-> vardrop_attn_bwd over one batch of synthetic windows and tokens that already sit in HBM.  The
+selection (hash + sample) of batch i+1 is enqueued before the attention of batch i, on the same stream.
 Prints ONE JSON line: steps/s, the roofline figure of the dominant kernel, and the CPU
 oracle timed on a bounded sample of the same workload.
 
@@ -154,20 +155,29 @@ def main():
     W_np = wl.make_weights(w, seed=0)
     W_dev = [torch.from_numpy(m).to(dev).to(td) for m in W_np]
     dy_full = torch.from_numpy(wl.make_upstream(w, w.N, seed=0)).to(dev).to(td).reshape(-1)
-    pinned = torch.zeros(2, dtype=torch.int32).pin_memory()
     stream = torch.cuda.current_stream()
     seed = 0x5EED
     saved = ws = None
     stats = {"n_sel": [], "G": []}
 
-    def step(i):
-        nonlocal saved, ws
+    # The selection of a batch depends on its windows only, not on the model, so it runs one batch
+    # ahead of the attention on the same stream: the 8-byte read-back of {N', G} that sizes the attention
+    # launch is then already complete when the host needs it, and the GPU never waits for the host.
+    pinned = [torch.zeros(2, dtype=torch.int32).pin_memory() for _ in range(2)]
+    events = [torch.cuda.Event() for _ in range(2)]
+
+    def select(i):
         x = xs_dev[i % args.batches]
-        tok = tok_dev[i % args.batches]
         topk, hsh, _ = vd.vardrop_hash(ctx, x, w.k)
-        gid, sel, counts = vd.vardrop_sample(ctx, hsh, 0, w.ratio[0], w.ratio[1], seed, i, counts_host=pinned)
-        stream.synchronize()                       # N' sizes the attention launch
-        n_sel, G = int(pinned[0]), int(pinned[1])
+        gid, sel, counts = vd.vardrop_sample(ctx, hsh, 0, w.ratio[0], w.ratio[1], seed, i, counts_host=pinned[i % 2])
+        events[i % 2].record(stream)
+        return sel
+
+    def attend(i, sel):
+        nonlocal saved, ws
+        tok = tok_dev[i % args.batches]
+        events[i % 2].synchronize()                # N' of batch i (launched one step earlier)
+        n_sel, G = int(pinned[i % 2][0]), int(pinned[i % 2][1])
         xs = vd.vardrop_gather(ctx, tok, sel, n_sel)
         y, saved = vd.vardrop_attn_fwd(ctx, xs, *W_dev, w.H, saved=saved)
         dy = dy_full[: w.B * n_sel * w.d].view(w.B, n_sel, w.d)
@@ -175,6 +185,14 @@ def main():
         stats["n_sel"].append(n_sel)
         stats["G"].append(G)
         return grads
+
+    def run(first, count):
+        """`count` whole steps: every batch gets its selection and its attention inside this call."""
+        sel = select(first)
+        for i in range(first, first + count):
+            nxt = select(i + 1) if i + 1 < first + count else None
+            attend(i, sel)
+            sel = nxt
 
     # size the reusable buffers for the largest selection (never re-allocated inside the timed region)
     lib = vd.load_library()
@@ -190,8 +208,7 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    for i in range(args.warmup):
-        step(i)
+    run(0, args.warmup)
     torch.cuda.synchronize()
 
     # ---- which kernel takes the largest share of a step?  (untimed census, HIP events around one kernel at a time)
@@ -201,8 +218,7 @@ def main():
         if name is None:
             break
         vd.vardrop_profile_select(ctx, kid)
-        for i in range(8):
-            step(i)
+        run(0, 8)
         total_ms, launches = vd.vardrop_profile_read(ctx)
         if launches:
             census[name] = (kid, total_ms * 1e3 / 8)            # microseconds per step
@@ -212,8 +228,7 @@ def main():
 
     stats = {"n_sel": [], "G": []}
     t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(args.warmup + i)
+    run(args.warmup, args.steps)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms = (t1 - t0) * 1e3 / args.steps

@@ -89,25 +89,29 @@ struct GemmBf16 {
   }
 };
 
-constexpr int kBK = 64;                 // K elements per LDS stage
-
-// 16-byte chunk position of (row, k-chunk) inside a 128-byte LDS row
-__device__ inline int swz(int row, int kc) { return kc ^ (((row >> 1) ^ (row >> 4)) & 7); }
+// 16-byte chunk position of (row, k-chunk) inside an LDS row of BK elements (BK / 8 chunks, no padding).
+// The XOR pattern keeps the 16-byte fragment reads of 16 consecutive rows, the 16-byte staging
+// stores, and the 4-byte transposing stores (rows 8 apart) on distinct banks.
+template <int BK>
+__device__ inline int swz(int row, int kc) {
+  return BK == 64 ? kc ^ (((row >> 1) ^ (row >> 4)) & 7) : kc ^ ((row ^ (row >> 3)) & 15);
+}
 
 __device__ inline u32x4 and4(u32x4 v, uint32_t m) { return v & m; }
 
-// One K slice (64 k) of one operand, staged in registers between global memory and LDS.
+// One K slice (BK k) of one operand, staged in registers between global memory and LDS.
 //   KC = true : k-contiguous source P[mn][k].  Rows past the end are read from the last row (their
-//               products land in output rows or columns that are never stored); the host guarantees
-//               that K is a multiple of 64, so there is no tail along k.
+//               products land in output rows or columns that are never stored); the host picks BK so
+//               that K is a multiple of it, so there is no tail along k.
 //   KC = false: mn-contiguous source P[k][mn]; a task is two k rows x eight mn, transposed on the way
 //               into LDS.  In the last, partial slice the k rows past kend are read from row kend-1 and
 //               zeroed with a mask.
 // Per-thread element offsets into the source and into LDS are computed once; a load is then one
 // 64-bit add per 16 bytes, unconditional, so the loads of a slice issue back to back.
-template <int ROWS, int NT, bool KC>
+template <int ROWS, int NT, bool KC, int BK>
 struct Stage {
-  static constexpr int kRegs = ROWS * 8 / NT;
+  static constexpr int kCh = BK / 8;                 // 16-byte chunks per row
+  static constexpr int kRegs = ROWS * kCh / NT;
   u32x4 r[kRegs];
   int goff[kRegs];      // KC: row * ld + 8 * chunk          MC: krel * ld + mn
   int loff[KC ? kRegs : kRegs / 2];
@@ -116,9 +120,9 @@ struct Stage {
 #pragma unroll
       for (int u = 0; u < kRegs; ++u) {
         const int c = threadIdx.x + u * NT;
-        const int row = c >> 3, kc = c & 7;
+        const int row = c / kCh, kc = c % kCh;
         goff[u] = min(mn0 + row, MN - 1) * ld + kc * 8;
-        loff[u] = row * kBK + swz(row, kc) * 8;
+        loff[u] = row * BK + swz<BK>(row, kc) * 8;
       }
     } else {
 #pragma unroll
@@ -128,7 +132,7 @@ struct Stage {
         const int mn = min(mn0 + mc * 8, MN - 8);
         goff[2 * u] = (2 * kp) * ld + mn;
         goff[2 * u + 1] = (2 * kp + 1) * ld + mn;
-        loff[u] = (mc * 8) * kBK + 2 * (kp & 3);          // row and chunk swizzle are added per element
+        loff[u] = (mc * 8) * BK + 2 * (kp & 3);           // row and chunk swizzle are added per element
       }
     }
   }
@@ -139,13 +143,13 @@ struct Stage {
     for (int u = 0; u < kRegs; ++u)
       if (u * 4 / kRegs == part) r[u] = *reinterpret_cast<const u32x4*>(base + goff[u]);
   }
-  // whole slice at once; the only path that handles a partial slice (k0 + 64 > kend, MC only)
+  // whole slice at once; the only path that handles a partial slice (k0 + BK > kend, MC only)
   __device__ inline void load(const bf16_t* P, int ld, int k0, int kend) {
     if constexpr (KC) {
       const bf16_t* base = P + k0;
 #pragma unroll
       for (int u = 0; u < kRegs; ++u) r[u] = *reinterpret_cast<const u32x4*>(base + goff[u]);
-    } else if (k0 + kBK <= kend) {
+    } else if (k0 + BK <= kend) {
       const bf16_t* base = P + (long long)k0 * ld;
 #pragma unroll
       for (int u = 0; u < kRegs; ++u) r[u] = *reinterpret_cast<const u32x4*>(base + goff[u]);
@@ -179,7 +183,7 @@ struct Stage {
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
           const int row = mc * 8 + j;
-          *reinterpret_cast<uint32_t*>(S + loff[u] + j * kBK + swz(row, kp >> 2) * 8) =
+          *reinterpret_cast<uint32_t*>(S + loff[u] + j * BK + swz<BK>(row, kp >> 2) * 8) =
               (uint32_t)a.h[j] | ((uint32_t)b.h[j] << 16);
         }
       }
@@ -187,14 +191,17 @@ struct Stage {
   }
 };
 
-// Tile (32*MI*WR) x 128 computed by WR x 2 wavefronts of (32*MI) x 64 each:
-//   MI = 2, WR = 2: 128 x 128, for problems with enough tiles to fill the chip;
-//   MI = 1, WR = 2:  64 x 128, four wavefronts so that a lone workgroup still uses all four SIMDs.
-template <bool AKC, bool BKC, typename OutT, int MI, int WR>
+// Tile (32*MI*WR) x 128 computed by WR x 2 wavefronts of (32*MI) x 64 each, K slices of BK:
+//   MI = 2, WR = 2, BK = 64 : 128 x 128, for problems with enough tiles to fill the chip;
+//   MI = 1, WR = 2, BK = 128:  64 x 128 for few tiles: four wavefronts so that a lone workgroup still
+//                              uses all four SIMDs, and long slices because with one workgroup per
+//                              compute unit the time per slice is set by memory latency, not by work.
+template <bool AKC, bool BKC, typename OutT, int MI, int WR, int BK>
 __global__ __launch_bounds__(128 * WR, 1) void gemm_bf16_kernel(GemmBf16 g) {
   constexpr int BM = 32 * MI * WR, BN = 128, NT = 128 * WR;
-  __shared__ __attribute__((aligned(16))) bf16_t As[2 * BM * kBK];
-  __shared__ __attribute__((aligned(16))) bf16_t Bs[2 * BN * kBK];
+  constexpr int KS = BK / 16;                        // matrix-instruction steps per slice
+  __shared__ __attribute__((aligned(16))) bf16_t As[2 * BM * BK];
+  __shared__ __attribute__((aligned(16))) bf16_t Bs[2 * BN * BK];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   const int col = lane & 31, half = lane >> 5;
@@ -210,7 +217,7 @@ __global__ __launch_bounds__(128 * WR, 1) void gemm_bf16_kernel(GemmBf16 g) {
     for (int j = 0; j < 2; ++j) acc[i][j] = zero16();
 
   const int nseg = g.nseg > 1 ? g.nseg : 1;
-  const int nk = (kend - kbeg + kBK - 1) / kBK;
+  const int nk = (kend - kbeg + BK - 1) / BK;
   const int total = nseg * nk;
   // operand pointers of the (up to three) segments, or of this batch entry
   const int zsel = g.nseg > 1 ? 0 : zb;
@@ -221,21 +228,21 @@ __global__ __launch_bounds__(128 * WR, 1) void gemm_bf16_kernel(GemmBf16 g) {
   const bf16_t* Ap = A0;
   const bf16_t* Bp = B0;
   int fseg = 0, fk = kbeg;            // position of the next fetch
-  Stage<BM, NT, AKC> sa;
-  Stage<BN, NT, BKC> sb;
+  Stage<BM, NT, AKC, BK> sa;
+  Stage<BN, NT, BKC, BK> sb;
   sa.init(g.lda, m0, g.M);
   sb.init(g.ldb, n0, g.N);
-  // LDS offsets of this lane's fragments (k-chunk index 2*ks + half, swizzled per row)
+  // LDS offsets of this lane's fragments; the k-chunk 2*ks + half is XORed with the row's pattern
   int offA[MI], offB[2], swA[MI], swB[2];
 #pragma unroll
   for (int t = 0; t < MI; ++t) {
     const int ra_ = wm * 32 * MI + t * 32 + col;
-    offA[t] = ra_ * kBK; swA[t] = ((ra_ >> 1) ^ (ra_ >> 4)) & 7;
+    offA[t] = ra_ * BK; swA[t] = swz<BK>(ra_, 0);
   }
 #pragma unroll
   for (int t = 0; t < 2; ++t) {
     const int rb_ = wn * 64 + t * 32 + col;
-    offB[t] = rb_ * kBK; swB[t] = ((rb_ >> 1) ^ (rb_ >> 4)) & 7;
+    offB[t] = rb_ * BK; swB[t] = swz<BK>(rb_, 0);
   }
   // the host never launches with an empty K range
   sa.load(Ap, g.lda, fk, kend);
@@ -245,16 +252,16 @@ __global__ __launch_bounds__(128 * WR, 1) void gemm_bf16_kernel(GemmBf16 g) {
   __syncthreads();
   for (int it = 0; it < total; ++it) {
     const int cur = it & 1;
-    const bf16_t* Ab = As + cur * BM * kBK;
-    const bf16_t* Bb = Bs + cur * BN * kBK;
+    const bf16_t* Ab = As + cur * BM * BK;
+    const bf16_t* Bb = Bs + cur * BN * BK;
     // position of the slice after this one (branch-free; past the end it re-reads a valid slice,
     // which is dropped, so that no load sits inside control flow)
-    const bool wrap = fk + kBK >= kend;
-    fk = wrap ? kbeg : fk + kBK;
+    const bool wrap = fk + BK >= kend;
+    fk = wrap ? kbeg : fk + BK;
     fseg = min(fseg + (wrap ? 1 : 0), nseg - 1);
     Ap = fseg == 0 ? A0 : (fseg == 1 ? A1 : A2);
     Bp = fseg == 0 ? B0 : (fseg == 1 ? B1 : B2);
-    const bool full = fk + kBK <= kend;        // partial slices (weight gradients only) load in one go
+    const bool full = fk + BK <= kend;         // partial slices (weight gradients only) load in one go
     bf16x8 fa[2][MI], fb[2][2];
 #pragma unroll
     for (int t = 0; t < MI; ++t) fa[0][t] = *reinterpret_cast<const bf16x8*>(Ab + offA[t] + (half ^ swA[t]) * 8);
@@ -264,17 +271,17 @@ __global__ __launch_bounds__(128 * WR, 1) void gemm_bf16_kernel(GemmBf16 g) {
       sa.load(Ap, g.lda, fk, kend);
       sb.load(Bp, g.ldb, fk, kend);
     }
-    // Four steps of 16 k.  Each step issues a quarter of the next slice's global loads and the LDS
-    // reads of the following step, then its four matrix instructions; the scheduling barriers pin
-    // that order so that memory traffic sits in the shadow of the matrix cores.
+    // KS steps of 16 k.  A step issues its share of the next slice's global loads and the LDS reads of
+    // the following step, then its matrix instructions; the scheduling barriers pin that order so
+    // that memory traffic sits in the shadow of the matrix cores.
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
+    for (int ks = 0; ks < KS; ++ks) {
       __builtin_amdgcn_sched_barrier(0);
-      if (full) {
-        sa.load_part(Ap, g.lda, fk, ks);
-        sb.load_part(Bp, g.ldb, fk, ks);
+      if (full && ks % (KS / 4) == 0) {
+        sa.load_part(Ap, g.lda, fk, ks / (KS / 4));
+        sb.load_part(Bp, g.ldb, fk, ks / (KS / 4));
       }
-      if (ks < 3) {
+      if (ks + 1 < KS) {
 #pragma unroll
         for (int t = 0; t < MI; ++t)
           fa[(ks + 1) & 1][t] = *reinterpret_cast<const bf16x8*>(Ab + offA[t] + (((ks + 1) * 2 + half) ^ swA[t]) * 8);
@@ -290,8 +297,8 @@ __global__ __launch_bounds__(128 * WR, 1) void gemm_bf16_kernel(GemmBf16 g) {
     }
     __builtin_amdgcn_sched_barrier(0);
     if (it + 1 < total) {
-      sa.store(As + (cur ^ 1) * BM * kBK);
-      sb.store(Bs + (cur ^ 1) * BN * kBK);
+      sa.store(As + (cur ^ 1) * BM * BK);
+      sb.store(Bs + (cur ^ 1) * BN * BK);
     }
     __syncthreads();
   }
@@ -345,20 +352,26 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(SplitkReduce a) {
 }
 
 // 128 x 128 tiles when they still give every compute unit several workgroups to overlap, otherwise
-// 64 x 128 tiles so that small problems spread over the chip.
+// 64 x 128 tiles with long K slices so that small problems spread over the chip.  `kc_operand` tells
+// whether a k-contiguous operand is present (then K must be a multiple of the slice length).
 template <bool AKC, bool BKC, typename OutT>
 int launch_gemm(vardrop_ctx* ctx, int kid, const GemmBf16& g, int nz, hipStream_t s) {
   if (g.M == 0 || g.N == 0) return VARDROP_OK;
   const int sk = g.splitk > 1 ? g.splitk : 1;
   const long long big = (long long)vd_ceil_div(g.N, 128) * vd_ceil_div(g.M, 128) * nz * sk;
+  const long long small = (long long)vd_ceil_div(g.N, 128) * vd_ceil_div(g.M, 64) * nz * sk;
+  const bool long_ok = (!(AKC || BKC) || g.K % 128 == 0) && (g.splitk <= 1 || g.kchunk % 128 == 0);
   {
     VdTimer timer(ctx, kid, s);
     if (big >= 1024) {
       dim3 grid(vd_ceil_div(g.N, 128), vd_ceil_div(g.M, 128), nz * sk);
-      hipLaunchKernelGGL((gemm_bf16_kernel<AKC, BKC, OutT, 2, 2>), grid, dim3(256), 0, s, g);
+      hipLaunchKernelGGL((gemm_bf16_kernel<AKC, BKC, OutT, 2, 2, 64>), grid, dim3(256), 0, s, g);
+    } else if (long_ok && small <= 320) {   // at most about one workgroup per compute unit
+      dim3 grid(vd_ceil_div(g.N, 128), vd_ceil_div(g.M, 64), nz * sk);
+      hipLaunchKernelGGL((gemm_bf16_kernel<AKC, BKC, OutT, 1, 2, 128>), grid, dim3(256), 0, s, g);
     } else {
       dim3 grid(vd_ceil_div(g.N, 128), vd_ceil_div(g.M, 64), nz * sk);
-      hipLaunchKernelGGL((gemm_bf16_kernel<AKC, BKC, OutT, 1, 2>), grid, dim3(256), 0, s, g);
+      hipLaunchKernelGGL((gemm_bf16_kernel<AKC, BKC, OutT, 1, 2, 64>), grid, dim3(256), 0, s, g);
     }
   }
   VD_LAUNCH_CHECK(ctx);
@@ -737,8 +750,8 @@ int vd_attn_bf16_splitk(int d, long long M, int* kchunk) {
   if (s > 8) s = 8;
   while (s > 1 && M / s < 256) --s;
   if (s < 1) s = 1;
-  int chunk = (int)vd_align_up((size_t)vd_ceil_div((int)M, s), 64);
-  if (chunk < 64) chunk = 64;
+  int chunk = (int)vd_align_up((size_t)vd_ceil_div((int)M, s), 128);
+  if (chunk < 128) chunk = 128;
   s = M > 0 ? vd_ceil_div((int)M, chunk) : 1;
   if (kchunk) *kchunk = chunk;
   return s;
