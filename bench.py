@@ -3,7 +3,7 @@
 
 One step = vardrop_hash -> vardrop_sample -> (read N') -> vardrop_gather -> vardrop_attn_fwd
 -> vardrop_attn_bwd over one batch of synthetic windows and tokens that already sit in HBM.  The
-selection (hash + sample) of batch i+1 is enqueued before the attention of batch i, on the same stream.
+selection (hash + sample) of batch i+1 is enqueued before the attention of batch i, on a second stream.
 Prints ONE JSON line: steps/s, the roofline figure of the dominant kernel, and the CPU
 oracle timed on a bounded sample of the same workload.
 
@@ -161,16 +161,26 @@ def main():
     stats = {"n_sel": [], "G": []}
 
     # The selection of a batch depends on its windows only, not on the model, so it runs one batch
-    # ahead of the attention on the same stream: the 8-byte read-back of {N', G} that sizes the attention
-    # launch is then already complete when the host needs it, and the GPU never waits for the host.
+    # ahead of the attention and on a stream of its own (default priority): the small k-DFH and sampling
+    # kernels then overlap the attention of the previous batch, and the 8-byte read-back of {N', G}
+    # that sizes the attention launch is already complete when the host needs it.  Outputs of the
+    # selection are double-buffered so that no buffer is rewritten while the attention still reads it.
     pinned = [torch.zeros(2, dtype=torch.int32).pin_memory() for _ in range(2)]
     events = [torch.cuda.Event() for _ in range(2)]
+    side = torch.cuda.Stream(device=dev)
+    sel_bufs = [(torch.empty((w.N, w.k), dtype=torch.int32, device=dev), torch.empty(w.N, dtype=torch.int64, device=dev),
+                 torch.empty(w.N, dtype=torch.int32, device=dev), torch.empty(w.N, dtype=torch.int32, device=dev),
+                 torch.empty(2, dtype=torch.int32, device=dev)) for _ in range(2)]
+    done = [torch.cuda.Event() for _ in range(2)]      # attention of the batch that used buffer set j
 
     def select(i):
-        x = xs_dev[i % args.batches]
-        topk, hsh, _ = vd.vardrop_hash(ctx, x, w.k)
-        gid, sel, counts = vd.vardrop_sample(ctx, hsh, 0, w.ratio[0], w.ratio[1], seed, i, counts_host=pinned[i % 2])
-        events[i % 2].record(stream)
+        j = i % 2
+        topk, hsh, gid, sel, counts = sel_bufs[j]
+        side.wait_event(done[j])                       # the gather two batches ago has read this `sel`
+        with torch.cuda.stream(side):
+            vd.vardrop_hash(ctx, xs_dev[i % args.batches], w.k, out=(topk, hsh))
+            vd.vardrop_sample(ctx, hsh, 0, w.ratio[0], w.ratio[1], seed, i, counts_host=pinned[j], out=(gid, sel, counts))
+            events[j].record(side)
         return sel
 
     def attend(i, sel):
@@ -179,6 +189,7 @@ def main():
         events[i % 2].synchronize()                # N' of batch i (launched one step earlier)
         n_sel, G = int(pinned[i % 2][0]), int(pinned[i % 2][1])
         xs = vd.vardrop_gather(ctx, tok, sel, n_sel)
+        done[i % 2].record(stream)
         y, saved = vd.vardrop_attn_fwd(ctx, xs, *W_dev, w.H, saved=saved)
         dy = dy_full[: w.B * n_sel * w.d].view(w.B, n_sel, w.d)
         grads = vd.vardrop_attn_bwd(ctx, dy, xs, *W_dev, w.H, saved, ws=ws)

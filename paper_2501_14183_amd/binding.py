@@ -142,15 +142,20 @@ def vardrop_profile_read(ctx):
     return ms.value, n.value
 
 
-def vardrop_hash(ctx, x, k, f_min=1, f_max=None, want_abar=False):
-    """x float32 [B, N, L] -> (topk int32 [N, k], hash int64 [N] (the uint64 bits), abar or None)."""
+def vardrop_hash(ctx, x, k, f_min=1, f_max=None, want_abar=False, out=None):
+    """x float32 [B, N, L] -> (topk int32 [N, k], hash int64 [N] (the uint64 bits), abar or None).
+
+    out: optional (topk, hash) tensors to write into instead of allocating."""
     if x.dtype != torch.float32 or x.dim() != 3:
         raise TypeError("x must be float32 [B, N, L]")
     B, N, L = x.shape
     if f_max is None:
         f_max = (L // 2 + 2) // 2
-    topk = torch.empty((N, k), dtype=torch.int32, device=x.device)
-    hsh = torch.empty((N,), dtype=torch.int64, device=x.device)
+    if out is not None:
+        topk, hsh = out
+    else:
+        topk = torch.empty((N, k), dtype=torch.int32, device=x.device)
+        hsh = torch.empty((N,), dtype=torch.int64, device=x.device)
     abar = torch.empty((N, f_max - f_min + 1), dtype=torch.float32, device=x.device) if want_abar else None
     sb, sn, st = x.stride()
     rc = ctx._lib.vardrop_hash(ctx.handle, _p(x), B, N, L, sb, sn, st, k, f_min, f_max,
@@ -159,15 +164,19 @@ def vardrop_hash(ctx, x, k, f_min=1, f_max=None, want_abar=False):
     return topk, hsh, abar
 
 
-def vardrop_sample(ctx, hsh, gs, ratio_num, ratio_den, seed, step, counts_host=None):
+def vardrop_sample(ctx, hsh, gs, ratio_num, ratio_den, seed, step, counts_host=None, out=None):
     """hash int64 [N] -> (group_id int32 [N], sel int32 [N] (first N' valid), counts int32 [2] = {N', G}).
 
     counts_host: optional pinned int32 [2] CPU tensor that receives the counts asynchronously.
+    out: optional (group_id, sel, counts) tensors to write into instead of allocating.
     """
     N = hsh.shape[0]
-    gid = torch.empty((N,), dtype=torch.int32, device=hsh.device)
-    sel = torch.empty((N,), dtype=torch.int32, device=hsh.device)
-    counts = torch.empty((2,), dtype=torch.int32, device=hsh.device)
+    if out is not None:
+        gid, sel, counts = out
+    else:
+        gid = torch.empty((N,), dtype=torch.int32, device=hsh.device)
+        sel = torch.empty((N,), dtype=torch.int32, device=hsh.device)
+        counts = torch.empty((2,), dtype=torch.int32, device=hsh.device)
     rc = ctx._lib.vardrop_sample(ctx.handle, _p(hsh), N, gs, ratio_num, ratio_den, seed, step,
                                  _p(gid), _p(sel), _p(counts), _p(counts_host), None, 0, _stream(hsh))
     ctx.check(rc, "vardrop_sample")

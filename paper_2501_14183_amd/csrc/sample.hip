@@ -74,16 +74,24 @@ __device__ inline void in_thread_exchange(uint64_t (&k)[E], uint32_t (&p)[E], in
   }
 }
 
-// The same network for bare 64-bit keys (ascending): two shuffles and one compare per exchange.
-template <int E, int S>
-__device__ inline void in_thread_exchange_u64(uint64_t (&k)[E], int tid, int size) {
+// The same network for bare keys of type K (uint32_t or uint64_t), ascending: one or two shuffles
+// and one compare per exchange.
+__device__ inline uint32_t lane_xor(uint32_t v, int d) { return __shfl_xor(v, d, 64); }
+__device__ inline uint64_t lane_xor(uint64_t v, int d) {
+  const uint32_t lo = __shfl_xor((uint32_t)v, d, 64);
+  const uint32_t hi = __shfl_xor((uint32_t)(v >> 32), d, 64);
+  return ((uint64_t)hi << 32) | lo;
+}
+
+template <typename K, int E, int S>
+__device__ inline void in_thread_exchange_keys(K (&k)[E], int tid, int size) {
 #pragma unroll
   for (int e = 0; e < E; ++e) {
     const int f = e ^ S;
     if (f > e && f < E) {
       const bool up = ((tid * E + e) & size) == 0;
       if ((k[f] < k[e]) == up) {
-        const uint64_t t = k[e];
+        const K t = k[e];
         k[e] = k[f];
         k[f] = t;
       }
@@ -91,10 +99,10 @@ __device__ inline void in_thread_exchange_u64(uint64_t (&k)[E], int tid, int siz
   }
 }
 
-template <int E>
-__device__ void bitonic_sort_u64(uint64_t* key, int npad) {
+template <typename K, int E>
+__device__ void bitonic_sort_keys(K* key, int npad) {
   const int tid = threadIdx.x;
-  uint64_t k[E];
+  K k[E];
   __syncthreads();
 #pragma unroll
   for (int e = 0; e < E; ++e) k[e] = key[tid * E + e];
@@ -108,7 +116,7 @@ __device__ void bitonic_sort_u64(uint64_t* key, int npad) {
 #pragma unroll
         for (int e = 0; e < E; ++e) {
           const int i = tid * E + e;
-          const uint64_t ok = key[i ^ stride];
+          const K ok = key[i ^ stride];
           const bool keep_min = ((i & stride) == 0) == ((i & size) == 0);
           if ((ok < k[e]) == keep_min) k[e] = ok;
         }
@@ -117,18 +125,16 @@ __device__ void bitonic_sort_u64(uint64_t* key, int npad) {
 #pragma unroll
         for (int e = 0; e < E; ++e) {
           const int i = tid * E + e;
-          const uint32_t lo = __shfl_xor((uint32_t)k[e], d, 64);
-          const uint32_t hi = __shfl_xor((uint32_t)(k[e] >> 32), d, 64);
-          const uint64_t ok = ((uint64_t)hi << 32) | lo;
+          const K ok = lane_xor(k[e], d);
           const bool keep_min = ((i & stride) == 0) == ((i & size) == 0);
           if ((ok < k[e]) == keep_min) k[e] = ok;
         }
       } else if (stride == 4) {
-        in_thread_exchange_u64<E, 4>(k, tid, size);
+        in_thread_exchange_keys<K, E, 4>(k, tid, size);
       } else if (stride == 2) {
-        in_thread_exchange_u64<E, 2>(k, tid, size);
+        in_thread_exchange_keys<K, E, 2>(k, tid, size);
       } else {
-        in_thread_exchange_u64<E, 1>(k, tid, size);
+        in_thread_exchange_keys<K, E, 1>(k, tid, size);
       }
     }
   }
@@ -247,8 +253,6 @@ __device__ int block_exclusive_scan(int* vals, int count, int* wsum) {
   return total;
 }
 
-constexpr int kIndexBits = 14;              // variate index (and padding index) below 16384
-constexpr int kPackShift = 64 - kIndexBits;  // hashes below 2^50 can share a key with the index
 constexpr int kCountMax = 1024;             // largest group ranked by counting instead of sorting
 
 struct SampleArgs {
@@ -257,6 +261,7 @@ struct SampleArgs {
   int32_t* sel;
   int32_t* counts;
   int N, npad;
+  int index_bits;      // log2(npad): room for a variate (or padding) index below the hash in a packed key
   uint32_t gs, num, den;
   uint32_t seed_lo, seed_hi, step_lo, step_hi;
 };
@@ -281,18 +286,38 @@ __global__ __launch_bounds__(1024) void sample_kernel(SampleArgs a) {
   uint16_t* gstart = reinterpret_cast<uint16_t*>(wsum + 20);           // [npad + 1], values <= 8192
   const int tid = threadIdx.x, nt = blockDim.x;
 
-  // Sort 1.  When every hash fits 50 bits (always for the radix-R code of k <= 5 bins), hash and
-  // variate index share one 64-bit key and the cheaper key-only network applies.
-  int wide = 0;
-  for (int i = tid; i < N; i += nt) wide |= (a.hash[i] >> kPackShift) != 0;
-  wide = __syncthreads_or(wide);
-  if (!wide) {
-    for (int i = tid; i < npad; i += nt) key[i] = i < N ? ((a.hash[i] << kIndexBits) | (uint64_t)i) : ~0ull;
-    bitonic_sort_u64<E>(key, npad);
+  // Sort 1.  Hash and variate index share one key when they fit: 32 bits (one shuffle per exchange;
+  // the radix-R code of three bins of a 96-sample window needs 17 bits), else 64 bits, else the pair
+  // network.  Padding keys are all ones and sort last.
+  const int ib = a.index_bits;
+  int too_wide = 0;                                   // bit 0: not in 32 bits, bit 1: not in 64 bits
+  for (int i = tid; i < N; i += nt) {
+    const uint64_t h = a.hash[i];
+    too_wide |= ((h >> (32 - ib)) != 0 ? 1 : 0) | ((h >> (64 - ib)) != 0 ? 2 : 0);
+  }
+  // (the block-wide OR is a logical one: reduce the two bits separately)
+  const int over32 = __syncthreads_or(too_wide & 1);
+  const int over64 = __syncthreads_or(too_wide & 2);
+  too_wide = (over32 ? 1 : 0) | (over64 ? 2 : 0);
+  if (too_wide == 0) {
+    uint32_t* key32 = reinterpret_cast<uint32_t*>(key) + npad;      // upper half of the key array
+    for (int i = tid; i < npad; i += nt) key32[i] = i < N ? (((uint32_t)a.hash[i] << ib) | (uint32_t)i) : ~0u;
+    bitonic_sort_keys<uint32_t, E>(key32, npad);
+    for (int i = tid; i < npad; i += nt) {
+      const uint32_t v = key32[i];
+      pay[i] = v & ((1u << ib) - 1);
+      scan[i] = (int)(v >> ib);                       // parked: key32 overlaps key[npad/2 ..]
+    }
+    __syncthreads();
+    for (int i = tid; i < npad; i += nt) key[i] = (uint64_t)(uint32_t)scan[i];
+    __syncthreads();
+  } else if ((too_wide & 2) == 0) {
+    for (int i = tid; i < npad; i += nt) key[i] = i < N ? ((a.hash[i] << ib) | (uint64_t)i) : ~0ull;
+    bitonic_sort_keys<uint64_t, E>(key, npad);
     for (int i = tid; i < npad; i += nt) {
       const uint64_t v = key[i];
-      pay[i] = (uint32_t)(v & ((1u << kIndexBits) - 1));
-      key[i] = v >> kIndexBits;
+      pay[i] = (uint32_t)(v & ((1u << ib) - 1));
+      key[i] = v >> ib;
     }
     __syncthreads();
   } else {
@@ -404,6 +429,8 @@ extern "C" int vardrop_sample(vardrop_ctx* ctx, const uint64_t* hash, int N,
   a.counts = counts;
   a.N = N;
   a.npad = npad;
+  a.index_bits = 0;
+  while ((1 << a.index_bits) < npad) ++a.index_bits;
   a.gs = gs;
   a.num = ratio_num;
   a.den = ratio_den;
