@@ -230,15 +230,17 @@ __device__ int block_exclusive_scan(int* vals, int count, int* wsum) {
   }
   if (lane == 63) wsum[wave] = incl;
   __syncthreads();
-  if (tid == 0) {
-    int run = 0;
+  if (tid < 64) {                                   // at most 16 wavefront totals: one shuffle scan
     const int nw = (nt + 63) >> 6;
-    for (int w = 0; w < nw; ++w) {
-      const int t = wsum[w];
-      wsum[w] = run;
-      run += t;
+    const int t = tid < nw ? wsum[tid] : 0;
+    int inc = t;
+#pragma unroll
+    for (int off = 1; off < 16; off <<= 1) {
+      const int o = __shfl_up(inc, off, 64);
+      if (tid >= off) inc += o;
     }
-    wsum[nw] = run;
+    if (tid < nw) wsum[tid] = inc - t;
+    if (tid == nw - 1) wsum[nw] = inc;
   }
   __syncthreads();
   int run = wsum[wave] + incl - local;
@@ -253,6 +255,7 @@ __device__ int block_exclusive_scan(int* vals, int count, int* wsum) {
   return total;
 }
 
+constexpr int kBuckets = 1024;              // order-preserving buckets of the first sort
 constexpr int kCountMax = 1024;             // largest group ranked by counting instead of sorting
 
 struct SampleArgs {
@@ -275,6 +278,30 @@ __device__ inline uint32_t keep_count(uint32_t size, const SampleArgs& a) {
   return keep;
 }
 
+// Number of pairs (key[q], idx(q)) with q in [s0, s1) that order before (kp, np), where idx(q) is
+// pay[q] & mask.  Four independent LDS reads are in flight per round: the loop is latency-bound.
+__device__ inline int count_before(const uint64_t* key, const uint32_t* pay, uint32_t mask, int s0, int s1,
+                                   uint64_t kp, uint32_t np) {
+  int r = 0;
+  int q = s0;
+  for (; q + 4 <= s1; q += 4) {
+    uint64_t kq[4];
+    uint32_t nq[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      kq[u] = key[q + u];
+      nq[u] = pay[q + u] & mask;
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) r += (kq[u] < kp || (kq[u] == kp && nq[u] < np)) ? 1 : 0;
+  }
+  for (; q < s1; ++q) {
+    const uint64_t kq = key[q];
+    r += (kq < kp || (kq == kp && (pay[q] & mask) < np)) ? 1 : 0;
+  }
+  return r;
+}
+
 template <int E>
 __global__ __launch_bounds__(1024) void sample_kernel(SampleArgs a) {
   extern __shared__ unsigned char smem[];
@@ -284,9 +311,102 @@ __global__ __launch_bounds__(1024) void sample_kernel(SampleArgs a) {
   int* scan = reinterpret_cast<int*>(pay + npad);                      // [npad]: flags -> ids / offsets
   int* wsum = scan + npad;                                             // [20]
   uint16_t* gstart = reinterpret_cast<uint16_t*>(wsum + 20);           // [npad + 1], values <= 8192
+  unsigned long long* mm = reinterpret_cast<unsigned long long*>(
+      smem + (((size_t)npad * 16 + 80 + (size_t)(npad + 1) * 2 + 7) & ~(size_t)7));   // [2]: min, max hash
+  int* bstart = reinterpret_cast<int*>(mm + 2);                        // [kBuckets + 1]
+  int* bcur = bstart + kBuckets + 1;                                   // [kBuckets]
+  int* bmax = bcur + kBuckets;                                         // [1]
   const int tid = threadIdx.x, nt = blockDim.x;
 
-  // Sort 1.  Hash and variate index share one key when they fit: 32 bits (one shuffle per exchange;
+  // Sort 1, usual path.  (hash, n) pairs are dropped into kBuckets order-preserving buckets (equal
+  // width over [min, max] of the hashes, a shift instead of a division); inside a bucket the position
+  // of a pair is a count over the bucket.  The result is the same total order as the sorting
+  // networks below, which remain for inputs that crowd one bucket.
+  bool sorted = false;
+  {
+    if (tid == 0) {
+      mm[0] = ~0ull;
+      mm[1] = 0ull;
+      *bmax = 0;
+    }
+    for (int i = tid; i <= kBuckets; i += nt) bstart[i] = 0;
+    __syncthreads();
+    unsigned long long lo = ~0ull, hi = 0ull;
+    for (int i = tid; i < N; i += nt) {
+      const unsigned long long h = a.hash[i];
+      lo = h < lo ? h : lo;
+      hi = h > hi ? h : hi;
+    }
+    // one atomic per wavefront, not per thread: same-address LDS atomics serialise
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+      const unsigned long long ol = lane_xor((uint64_t)lo, off), oh = lane_xor((uint64_t)hi, off);
+      lo = ol < lo ? ol : lo;
+      hi = oh > hi ? oh : hi;
+    }
+    if ((tid & 63) == 0) {
+      atomicMin(&mm[0], lo);
+      atomicMax(&mm[1], hi);
+    }
+    __syncthreads();
+    const unsigned long long hmin = mm[0], range = mm[1] - mm[0];
+    int shift = 0;
+    while ((range >> shift) >= (unsigned long long)kBuckets) ++shift;
+    for (int i = tid; i < N; i += nt) atomicAdd(&bstart[(int)((a.hash[i] - hmin) >> shift)], 1);
+    __syncthreads();
+    {
+      int m = 0;
+      for (int i = tid; i < kBuckets; i += nt) m = max(m, bstart[i]);
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) m = max(m, __shfl_xor(m, off, 64));
+      if ((tid & 63) == 0) atomicMax(bmax, m);
+    }
+    __syncthreads();
+    if (*bmax <= kCountMax) {
+      block_exclusive_scan(bstart, kBuckets, wsum);                    // counts -> bucket starts
+      for (int i = tid; i < kBuckets; i += nt) bcur[i] = bstart[i];
+      __syncthreads();
+      for (int i = tid; i < N; i += nt) {
+        const unsigned long long h = a.hash[i];
+        const int pos = atomicAdd(&bcur[(int)((h - hmin) >> shift)], 1);
+        key[pos] = h;
+        pay[pos] = (uint32_t)i;
+      }
+      __syncthreads();
+      for (int p = tid; p < N; p += nt) {
+        const uint64_t kp = key[p];
+        const uint32_t np = pay[p];
+        const int b = (int)((kp - hmin) >> shift);
+        const int s0 = bstart[b], s1 = bcur[b];
+        scan[p] = s0 + count_before(key, pay, 0xffffffffu, s0, s1, kp, np);
+      }
+      __syncthreads();
+      uint64_t rk[E];
+      uint32_t rp[E];
+      int rpos[E];
+#pragma unroll
+      for (int e = 0; e < E; ++e) {
+        const int p = tid + e * nt;
+        rpos[e] = -1;
+        if (p < N) {
+          rk[e] = key[p];
+          rp[e] = pay[p];
+          rpos[e] = scan[p];
+        }
+      }
+      __syncthreads();
+#pragma unroll
+      for (int e = 0; e < E; ++e)
+        if (rpos[e] >= 0) {
+          key[rpos[e]] = rk[e];
+          pay[rpos[e]] = rp[e];
+        }
+      __syncthreads();
+      sorted = true;
+    }
+  }
+
+  // Sort 1, sorting networks.  Hash and variate index share one key when they fit: 32 bits (one shuffle per exchange;
   // the radix-R code of three bins of a 96-sample window needs 17 bits), else 64 bits, else the pair
   // network.  Padding keys are all ones and sort last.
   const int ib = a.index_bits;
@@ -299,7 +419,9 @@ __global__ __launch_bounds__(1024) void sample_kernel(SampleArgs a) {
   const int over32 = __syncthreads_or(too_wide & 1);
   const int over64 = __syncthreads_or(too_wide & 2);
   too_wide = (over32 ? 1 : 0) | (over64 ? 2 : 0);
-  if (too_wide == 0) {
+  if (sorted) {
+    // nothing left to do
+  } else if (too_wide == 0) {
     uint32_t* key32 = reinterpret_cast<uint32_t*>(key) + npad;      // upper half of the key array
     for (int i = tid; i < npad; i += nt) key32[i] = i < N ? (((uint32_t)a.hash[i] << ib) | (uint32_t)i) : ~0u;
     bitonic_sort_keys<uint32_t, E>(key32, npad);
@@ -343,7 +465,13 @@ __global__ __launch_bounds__(1024) void sample_kernel(SampleArgs a) {
     wsum[18] = 0;
   }
   __syncthreads();
-  for (int g = tid; g < G; g += nt) atomicMax(&wsum[18], (int)gstart[g + 1] - (int)gstart[g]);
+  {
+    int m = 0;
+    for (int g = tid; g < G; g += nt) m = max(m, (int)gstart[g + 1] - (int)gstart[g]);
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) m = max(m, __shfl_xor(m, off, 64));
+    if ((tid & 63) == 0) atomicMax(&wsum[18], m);
+  }
   for (int p = tid; p < N; p += nt) {
     const uint32_t n = pay[p];
     const int g = scan[p];
@@ -361,12 +489,7 @@ __global__ __launch_bounds__(1024) void sample_kernel(SampleArgs a) {
       const uint32_t g = pay[p] >> 16, n = pay[p] & 0xffffu;
       const int s0 = gstart[g], s1 = gstart[g + 1];
       const uint64_t ku = key[p];
-      uint32_t rank = 0;
-      for (int q = s0; q < s1; ++q) {
-        const uint64_t kq = key[q];
-        const uint32_t nq = pay[q] & 0xffffu;
-        rank += (kq < ku || (kq == ku && nq < n)) ? 1u : 0u;
-      }
+      const uint32_t rank = (uint32_t)count_before(key, pay, 0xffffu, s0, s1, ku, n);
       scan[n] = rank < keep_count((uint32_t)(s1 - s0), a) ? 1 : 0;
     }
   } else {
@@ -418,7 +541,7 @@ extern "C" int vardrop_sample(vardrop_ctx* ctx, const uint64_t* hash, int N,
   if (N > kMaxN) return VARDROP_EUNSUPPORTED;
   int npad = next_pow2(N);
   if (npad < 128) npad = 128;
-  const size_t lds = (size_t)npad * 16 + 20 * 4 + (size_t)(npad + 1) * 2 + 14;
+  const size_t lds = (size_t)npad * 16 + 20 * 4 + (size_t)(npad + 1) * 2 + 14 + 16 + (2 * kBuckets + 2) * 4;
   if (lds > (size_t)ctx->lds_per_block) return VARDROP_EUNSUPPORTED;
   const int E = npad <= 2048 ? 2 : (npad == 4096 ? 4 : 8);     // elements per thread of the sort
   const int threads = npad / E;
