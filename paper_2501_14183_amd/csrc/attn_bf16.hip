@@ -351,6 +351,263 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(SplitkReduce a) {
   }
 }
 
+// ================================================================== GEMM with asynchronous LDS fill
+// C[z] = A[z] * op(B[z]) (+ bias[z]) in bf16, or the sum over up to three segments into C[0].
+// A is k-contiguous [M][K]; B is k-contiguous [N][K] (BKC) or n-contiguous [K][N].  K is a multiple of BK.
+//
+// Global memory is copied straight into LDS (global_load_lds_dwordx4: every lane names its own 16
+// source bytes, the wavefront's 64 chunks land in 1 KB of consecutive LDS), NS stages deep, so
+// that the copies of the next NS-1 slices are in flight while the matrix cores work on the
+// current one and no register or LDS-store instruction is spent on staging.  Because the LDS side
+// of a copy is fixed, the bank swizzle is applied on the source side: LDS chunk position p of a row
+// holds source chunk p ^ pattern(row).
+//   k-contiguous operand: LDS tile [row][BK], fragments are 16-byte reads (row = lane % 32,
+//                         chunk 2*ks + lane / 32), pattern chosen so that eight consecutive rows
+//                         spread over all banks.
+//   n-contiguous operand: LDS tile [k][128]; fragments come from the transposing read
+//                         ds_read_b64_tr_b16, in which, inside each group of 16 lanes, lane s names
+//                         four consecutive n of k-row s / 4 at column block s % 4, and lane j
+//                         receives column j of the four k-rows.
+// Fragment reads and the wait counters are written out by hand: the compiler would otherwise wait
+// for every outstanding copy before any LDS read.
+// The product is formed transposed (the B fragment is the left operand), so that a lane owns one
+// output row and four consecutive columns per register quad: 8-byte stores.
+__device__ inline void dma16(const bf16_t* gp, unsigned char* lp) {
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gp,
+                                   (__attribute__((address_space(3))) void*)lp, 16, 0, 0);
+}
+__device__ inline void lds_read16(u32x4& dst, uint32_t addr) {
+  asm volatile("ds_read_b128 %0, %1" : "=v"(dst) : "v"(addr) : "memory");
+}
+template <int OFF>
+__device__ inline void lds_read8_tr(u32x2& dst, uint32_t addr) {
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFF) : "memory");
+}
+template <int N>
+__device__ inline void wait_vm() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
+// waits until at most N LDS reads are outstanding; the fragments are operands so that their uses stay behind it
+template <int N>
+__device__ inline void wait_lds(Frag& a, Frag& b, Frag& c, Frag& d) {
+  asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a.q), "+v"(b.q), "+v"(c.q), "+v"(d.q) : "n"(N));
+}
+template <int N>
+__device__ inline void wait_lds(Frag& a, Frag& b, Frag& c) {
+  asm volatile("s_waitcnt lgkmcnt(%3)" : "+v"(a.q), "+v"(b.q), "+v"(c.q) : "n"(N));
+}
+
+template <int BK>
+__device__ inline int swz_kc(int row) { return BK == 32 ? (row >> 1) & 3 : row & 7; }
+__device__ inline int swz_nc(int krow) { return ((krow & 3) << 1) ^ (((krow >> 3) & 1) << 3); }
+
+template <bool BKC, int BM, int BK, int NS>
+__global__ __launch_bounds__(256, 2) void gemm_async_kernel(GemmBf16 g) {
+  constexpr int BN = 128, MI = BM / 64, KS = BK / 16;
+  constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE = A_BYTES + B_BYTES;
+  constexpr int IA = A_BYTES / 4096, IB = B_BYTES / 4096, LPS = IA + IB;   // 1 KB copies per wavefront and stage
+  constexpr int CH = BK / 8;                                              // 16-byte chunks per k-contiguous row
+  constexpr int RPI = 64 / CH;                                            // rows per copy instruction
+  constexpr int OPK = MI + (BKC ? 2 : 4);                                 // LDS reads per 16-k step
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int col = lane & 31, half = lane >> 5;
+  const int zb = blockIdx.z;
+  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+  const int nseg = g.nseg > 1 ? g.nseg : 1;
+  const int nk = g.K / BK;
+  const int total = nseg * nk;
+  const int zsel = g.nseg > 1 ? 0 : zb;
+  const bf16_t* A1 = g.A1; const bf16_t* B1 = g.B1;
+  const bf16_t* A2 = g.A2; const bf16_t* B2 = g.B2;
+  const bf16_t* A0 = zsel == 0 ? g.A0 : (zsel == 1 ? A1 : (zsel == 2 ? A2 : g.A3));
+  const bf16_t* B0 = zsel == 0 ? g.B0 : (zsel == 1 ? B1 : (zsel == 2 ? B2 : g.B3));
+
+  // ---- source offsets of this lane's copies (elements) and fragment addresses (LDS bytes)
+  int goffA[IA], goffB[IB];
+#pragma unroll
+  for (int u = 0; u < IA; ++u) {
+    const int row = (u * 4 + wave) * RPI + lane / CH;
+    goffA[u] = min(m0 + row, g.M - 1) * g.lda + ((lane % CH) ^ swz_kc<BK>(row)) * 8;
+  }
+#pragma unroll
+  for (int u = 0; u < IB; ++u) {
+    if constexpr (BKC) {
+      const int row = (u * 4 + wave) * RPI + lane / CH;
+      goffB[u] = min(n0 + row, g.N - 1) * g.ldb + ((lane % CH) ^ swz_kc<BK>(row)) * 8;
+    } else {
+      const int krow = (u * 4 + wave) * 4 + lane / 16;
+      goffB[u] = krow * g.ldb + min(n0 + ((lane % 16) ^ swz_nc(krow)) * 8, g.N - 8);
+    }
+  }
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
+  uint32_t addrA[MI][KS], addrB[2][BKC ? KS : 1];
+#pragma unroll
+  for (int i = 0; i < MI; ++i) {
+    const int ra = wm * (BM / 2) + i * 32 + col;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) addrA[i][ks] = lds0 + ra * (BK * 2) + (((2 * ks + half) ^ swz_kc<BK>(ra)) * 16);
+  }
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    if constexpr (BKC) {
+      const int rb = wn * 64 + j * 32 + col;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks)
+        addrB[j][ks] = lds0 + A_BYTES + rb * (BK * 2) + (((2 * ks + half) ^ swz_kc<BK>(rb)) * 16);
+    } else {
+      const int krow = 8 * half + ((lane & 15) >> 2);
+      const int mn = wn * 64 + j * 32 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+      addrB[j][0] = lds0 + A_BYTES + krow * 256 + (((mn >> 3) ^ swz_nc(krow)) * 16) + ((mn >> 2) & 1) * 8;
+    }
+  }
+
+  floatx16 acc[MI][2];
+#pragma unroll
+  for (int i = 0; i < MI; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) acc[i][j] = zero16();
+
+  // ---- copy cursor
+  int fseg = 0, fk = 0;
+  const bf16_t* Ap = A0;
+  const bf16_t* Bp = B0;
+#define VD_ISSUE_STAGE(BUF)                                                                        \
+  {                                                                                                \
+    unsigned char* sp = smem + (BUF) * STAGE + wave * 1024;                                        \
+    const bf16_t* pa = Ap + fk;                                                                    \
+    const bf16_t* pb = BKC ? Bp + fk : Bp + (long long)fk * g.ldb;                                 \
+    _Pragma("unroll") for (int u = 0; u < IA; ++u) dma16(pa + goffA[u], sp + u * 4096);            \
+    _Pragma("unroll") for (int u = 0; u < IB; ++u) dma16(pb + goffB[u], sp + A_BYTES + u * 4096);  \
+    fk += BK;                                                                                      \
+    if (fk >= g.K) {                                                                               \
+      fk = 0;                                                                                      \
+      ++fseg;                                                                                      \
+      Ap = fseg == 1 ? A1 : A2;                                                                    \
+      Bp = fseg == 1 ? B1 : B2;                                                                    \
+    }                                                                                              \
+  }
+#pragma unroll
+  for (int s = 0; s < NS - 1; ++s)
+    if (s < total) VD_ISSUE_STAGE(s)
+
+  for (int t0 = 0; t0 < total; t0 += NS) {
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+      const int t = t0 + s;
+      if (t < total) {
+        // slice t has landed once at most `ahead` younger stages are still in flight
+        const int ahead = min(total - 1 - t, NS - 2);
+        if (NS >= 4 && ahead >= 2) wait_vm<2 * LPS>();
+        else if (NS >= 3 && ahead == 1) wait_vm<LPS>();
+        else wait_vm<0>();
+        __builtin_amdgcn_s_barrier();     // everyone's copies of slice t are in; everyone is done with slice t-1
+        if (t + NS - 1 < total) VD_ISSUE_STAGE((s + NS - 1) % NS)
+        const uint32_t so = s * STAGE;
+        Frag fa[2][2], fb[2][2];
+#define VD_READ_STEP(KS_, SET)                                                                     \
+  {                                                                                                \
+    _Pragma("unroll") for (int i = 0; i < MI; ++i) lds_read16(fa[SET][i].q, addrA[i][KS_] + so);   \
+    _Pragma("unroll") for (int j = 0; j < 2; ++j) {                                                \
+      if constexpr (BKC) {                                                                         \
+        lds_read16(fb[SET][j].q, addrB[j][KS_] + so);                                              \
+      } else {                                                                                     \
+        lds_read8_tr<(KS_) * 4096>(fb[SET][j].d[0], addrB[j][0] + so);                             \
+        lds_read8_tr<(KS_) * 4096 + 1024>(fb[SET][j].d[1], addrB[j][0] + so);                      \
+      }                                                                                            \
+    }                                                                                              \
+  }
+#define VD_MFMA_STEP(SET, PENDING)                                                                 \
+  {                                                                                                \
+    if constexpr (MI == 2) wait_lds<PENDING>(fa[SET][0], fa[SET][1], fb[SET][0], fb[SET][1]);      \
+    else wait_lds<PENDING>(fa[SET][0], fb[SET][0], fb[SET][1]);                                    \
+    _Pragma("unroll") for (int i = 0; i < MI; ++i)                                                 \
+      _Pragma("unroll") for (int j = 0; j < 2; ++j) acc[i][j] = mfma(fb[SET][j], fa[SET][i], acc[i][j]); \
+    __builtin_amdgcn_sched_barrier(0);                                                             \
+  }
+        VD_READ_STEP(0, 0)
+        if constexpr (KS == 2) {
+          VD_READ_STEP(1, 1)
+          VD_MFMA_STEP(0, OPK)
+          VD_MFMA_STEP(1, 0)
+        } else {
+          VD_READ_STEP(1, 1)
+          VD_MFMA_STEP(0, OPK)
+          VD_READ_STEP(2, 0)
+          VD_MFMA_STEP(1, OPK)
+          VD_READ_STEP(3, 1)
+          VD_MFMA_STEP(0, OPK)
+          VD_MFMA_STEP(1, 0)
+        }
+#undef VD_READ_STEP
+#undef VD_MFMA_STEP
+      }
+    }
+  }
+#undef VD_ISSUE_STAGE
+
+  // ---- epilogue: acc[i][j] register 4*q4 + e is C[m0 + wm*BM/2 + i*32 + col][n0 + wn*64 + j*32 + 8*q4 + 4*half + e]
+  const bf16_t* bias = zsel == 0 ? g.bias0 : (zsel == 1 ? g.bias1 : (zsel == 2 ? g.bias2 : g.bias3));
+  bf16_t* C = reinterpret_cast<bf16_t*>(zsel == 0 ? g.C0 : (zsel == 1 ? g.C1 : (zsel == 2 ? g.C2 : g.C3)));
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int q4 = 0; q4 < 4; ++q4) {
+      const int n = n0 + wn * 64 + j * 32 + 8 * q4 + 4 * half;
+      if (n < g.N) {                                  // N is a multiple of 4: a quad is inside or outside
+        float bv[4] = {0.f, 0.f, 0.f, 0.f};
+        if (bias) {
+          const u32x2 b4 = *reinterpret_cast<const u32x2*>(bias + n);
+          bv[0] = __uint_as_float(b4.x << 16); bv[1] = __uint_as_float(b4.x & 0xffff0000u);
+          bv[2] = __uint_as_float(b4.y << 16); bv[3] = __uint_as_float(b4.y & 0xffff0000u);
+        }
+#pragma unroll
+        for (int i = 0; i < MI; ++i) {
+          const int m = m0 + wm * (BM / 2) + i * 32 + col;
+          if (m < g.M) {
+            u32x2 o;
+            o.x = pack2(acc[i][j][4 * q4] + bv[0], acc[i][j][4 * q4 + 1] + bv[1]);
+            o.y = pack2(acc[i][j][4 * q4 + 2] + bv[2], acc[i][j][4 * q4 + 3] + bv[3]);
+            *reinterpret_cast<u32x2*>(C + (long long)m * g.ldc + n) = o;
+          }
+        }
+      }
+    }
+}
+
+// Tile and pipeline depth of the asynchronous GEMM: 128 x 128 tiles once there are enough of them to
+// keep every compute unit busy with two workgroups; otherwise 64 x 128 tiles, three stages deep while
+// two workgroups still fit beside each other in LDS (at most 512 tiles), else two stages and three
+// workgroups per compute unit.
+template <bool BKC, int BM, int NS>
+int launch_gemm_async_cfg(vardrop_ctx* ctx, int kid, const GemmBf16& g, int nz, hipStream_t s) {
+  constexpr int BK = 64;
+  constexpr int lds = NS * (BM + 128) * BK * 2;
+  static int configured_device = -1;     // raising the dynamic LDS limit is a per-device, per-function setting
+  if (configured_device != ctx->device) {
+    VD_HIP(ctx, hipFuncSetAttribute((const void*)gemm_async_kernel<BKC, BM, BK, NS>,
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+    configured_device = ctx->device;
+  }
+  dim3 grid(vd_ceil_div(g.N, 128), vd_ceil_div(g.M, BM), nz);
+  {
+    VdTimer timer(ctx, kid, s);
+    hipLaunchKernelGGL((gemm_async_kernel<BKC, BM, BK, NS>), grid, dim3(256), lds, s, g);
+  }
+  VD_LAUNCH_CHECK(ctx);
+  return VARDROP_OK;
+}
+template <bool BKC>
+int launch_gemm_async(vardrop_ctx* ctx, int kid, const GemmBf16& g, int nz, hipStream_t s) {
+  if (g.M == 0 || g.N == 0) return VARDROP_OK;
+  if (g.K % 64 != 0 || g.N % 8 != 0 || (long long)g.M * g.lda >= (1ll << 31) || (long long)g.K * g.ldb >= (1ll << 31))
+    return VARDROP_EUNSUPPORTED;
+  const long long t128 = (long long)vd_ceil_div(g.N, 128) * vd_ceil_div(g.M, 128) * nz;
+  const long long t64 = (long long)vd_ceil_div(g.N, 128) * vd_ceil_div(g.M, 64) * nz;
+  if (t128 >= 1024) return launch_gemm_async_cfg<BKC, 128, 2>(ctx, kid, g, nz, s);
+  if (t64 <= 512) return launch_gemm_async_cfg<BKC, 64, 3>(ctx, kid, g, nz, s);
+  return launch_gemm_async_cfg<BKC, 64, 2>(ctx, kid, g, nz, s);
+}
+
 // 128 x 128 tiles when they still give every compute unit several workgroups to overlap, otherwise
 // 64 x 128 tiles with long K slices so that small problems spread over the chip.  `kc_operand` tells
 // whether a k-contiguous operand is present (then K must be a multiple of the slice length).
@@ -781,7 +1038,7 @@ int vd_attn_fwd_bf16(vardrop_ctx* ctx, const void* xs, int B, int n, int d, int 
   for (int z = 0; z < 3; ++z) g.set(z, xs, W[z], qkv[z], bias[z]);
   g.lda = d; g.ldb = d; g.ldc = d;
   g.M = (int)M; g.N = d; g.K = d; g.nseg = 1;
-  int rc = launch_gemm<true, false, bf16_t>(ctx, VARDROP_K_GEMM_QKV, g, 3, s);
+  int rc = launch_gemm_async<false>(ctx, VARDROP_K_GEMM_QKV, g, 3, s);
   if (rc) return rc;
   SdpaArgs a = {};
   a.q = q; a.k = k; a.v = v; a.out = o; a.lse = lse;
@@ -792,7 +1049,7 @@ int vd_attn_fwd_bf16(vardrop_ctx* ctx, const void* xs, int B, int n, int d, int 
   go.set(0, o, W[3], y, bias[3]);
   go.lda = d; go.ldb = d; go.ldc = d;
   go.M = (int)M; go.N = d; go.K = d; go.nseg = 1;
-  return launch_gemm<true, false, bf16_t>(ctx, VARDROP_K_GEMM_OUT, go, 1, s);
+  return launch_gemm_async<false>(ctx, VARDROP_K_GEMM_OUT, go, 1, s);
 }
 
 // ws: dO, dq, dk, dv ([M][d] bf16 each), D fp32 [B][H][n], then the split-K partial products
@@ -816,7 +1073,7 @@ int vd_attn_bwd_bf16(vardrop_ctx* ctx, const void* dy, const void* xs, int B, in
     g.set(0, dy, W[3], dO, nullptr);
     g.lda = d; g.ldb = d; g.ldc = d;
     g.M = (int)M; g.N = d; g.K = d; g.nseg = 1;
-    if ((rc = launch_gemm<true, true, bf16_t>(ctx, VARDROP_K_GEMM_DO, g, 1, s))) return rc;
+    if ((rc = launch_gemm_async<true>(ctx, VARDROP_K_GEMM_DO, g, 1, s))) return rc;
   }
   SdpaArgs a = {};
   a.q = q; a.k = k; a.v = v; a.o = o; a.dout = dO; a.lse = const_cast<float*>(lse);
@@ -858,7 +1115,7 @@ int vd_attn_bwd_bf16(vardrop_ctx* ctx, const void* dy, const void* xs, int B, in
     for (int z = 0; z < 3; ++z) g.set(z, grads[z], W[z], z == 0 ? dxs : nullptr, nullptr);
     g.lda = d; g.ldb = d; g.ldc = d;
     g.M = (int)M; g.N = d; g.K = d; g.nseg = 3;
-    if ((rc = launch_gemm<true, true, bf16_t>(ctx, VARDROP_K_GEMM_DXS, g, 1, s))) return rc;
+    if ((rc = launch_gemm_async<true>(ctx, VARDROP_K_GEMM_DXS, g, 1, s))) return rc;
   }
   if (db[0] || db[1] || db[2] || db[3]) {
     ColSumBf16 c = {};

@@ -1,17 +1,19 @@
 // k-dominant frequency hashing (Alg. 1, Def. 1) as one fused gfx950 kernel.
 //
-// Mapping.  A wavefront owns a block of 32 (variate, window) rows: all B windows of one
-// variate when B >= 32 (several blocks in sequence when B > 32), or 32/Bp variates with
-// Bp = B rounded up to a power of two when B < 32.  The block's windows are staged in LDS
-// (time-major, padded), and the amplitude spectrum on the candidate bins is a dense
-// contraction of the folded window with a cosine / sine table:
+// Mapping.  A workgroup of four wavefronts owns a block of 32 (variate, window) rows: all B
+// windows of one variate when B >= 32 (several blocks in sequence when B > 32), or 32/Bp variates
+// with Bp = B rounded up to a power of two when B < 32.  The block's windows are staged in LDS
+// (time-major, padded), and the amplitude spectrum on the candidate bins is a dense contraction of
+// the folded window with a cosine / sine table:
 //     Re X_f =  x[0] + (-1)^f x[L/2] + sum_{0<t<L/2} (x[t] + x[L-t]) cos(2 pi f t / L)
 //     Im X_f = -sum_{0<t<L/2} (x[t] - x[L-t]) sin(2 pi f t / L)
-// evaluated with the fp32 matrix instruction v_mfma_f32_32x32x2_f32 (rows = windows,
-// columns = 32 bins, contraction = folded time).  The bins above the cut-off are never
-// produced (Alg. 1 step 2).  Amplitudes are summed over the batch in ascending window
-// order in fp32 (step 3), and the ranked top-k (step 4) is k rounds of a wavefront
-// arg-max with the lower bin winning ties; the hash is the tuple in radix R (step 5).
+// evaluated with the fp32 matrix instruction v_mfma_f32_32x32x2_f32 (rows = windows, columns = 32
+// bins, contraction = folded time).  The four wavefronts split the contraction (wavefront w takes
+// the steps w, w+4, ...), so that loads, matrix work and the LDS round trips of one block run four
+// wide; their partial sums meet in LDS.  The bins above the cut-off are never produced (Alg. 1
+// step 2).  Amplitudes are summed over the batch in ascending window order in fp32 (step 3), and
+// the ranked top-k (step 4) is k rounds of a wavefront arg-max with the lower bin winning ties; the
+// hash is the tuple in radix R (step 5).
 #include "common.h"
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
@@ -20,6 +22,8 @@ namespace {
 
 constexpr int kTilePad = 33;     // LDS row stride of the time-major tile (32 rows + 1)
 constexpr int kMaxBinsPerLane = 8;
+constexpr int kWaves = 4;
+constexpr int kThreads = 64 * kWaves;
 
 __global__ void twiddle_kernel(float* tw, int L) {
   int j = blockIdx.x * blockDim.x + threadIdx.x;
@@ -45,26 +49,26 @@ struct KdfhArgs {
   float inv_B;
 };
 
-__global__ __launch_bounds__(64) void kdfh_kernel(KdfhArgs a) {
+__global__ __launch_bounds__(kThreads) void kdfh_kernel(KdfhArgs a) {
   extern __shared__ float lds[];
   const int L = a.L, F = a.F;
-  const int lane = threadIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int col = lane & 31, half = lane >> 5;
   const int rpv = 1 << a.log2_rpv;
   const int Vb = 32 >> a.log2_rpv;               // variates per block
   const int n0 = blockIdx.x * Vb;
   float* cosT = lds;
   float* sinT = lds + L;
-  float* tile = sinT + L;                        // [L][kTilePad]
-  float* ampT = tile + L * kTilePad;             // [32][kTilePad]
+  float* tile = sinT + L;                        // [L + 1][kTilePad], last row zero
+  float* part = tile + (L + 1) * kTilePad;       // [kWaves][16][64] partial accumulators (Re, then Im)
+  float* ampT = part + kWaves * 16 * 64;         // [32][kTilePad]
   float* asum = ampT + 32 * kTilePad;            // [Vb][F]
 
-  for (int i = lane; i < 2 * L; i += 64) lds[i] = a.tw[i];
-  for (int i = lane; i < Vb * F; i += 64) asum[i] = 0.f;
+  for (int i = tid; i < 2 * L; i += kThreads) lds[i] = a.tw[i];
+  for (int i = tid; i < Vb * F; i += kThreads) asum[i] = 0.f;
 
   const int Lh = L >> 1;
   const int Sc = (Lh + 2) >> 1;                  // cosine steps: t = 0 .. floor(L/2), two per step
-  const int Ss = ((L - 1) / 2 + 1) >> 1;         // sine steps:   t = 1 .. ceil(L/2)-1
   const int nct = (F + 31) >> 5;
 
   for (int rb = 0; rb < a.nrb; ++rb) {
@@ -73,28 +77,25 @@ __global__ __launch_bounds__(64) void kdfh_kernel(KdfhArgs a) {
     if (a.vec) {
       const int L4 = L >> 2;
       const int items = 32 * L4;
-      for (int base = 0; base < items; base += 64 * 8) {
-        float4 v[8];
-        int rr[8], cc[8];
+      for (int base = 0; base < items; base += kThreads * 4) {
+        float4 v[4];
+        int rr[4], cc[4];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-          const int i = base + u * 64 + lane;
-          rr[u] = -1;
-          cc[u] = 0;
-          v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-          if (i < items) {
-            const int r = i / L4;
-            const int c = i - r * L4;
-            rr[u] = r;
-            cc[u] = c;
-            const int n = n0 + (r >> a.log2_rpv);
-            const int b = rb * 32 + (r & (rpv - 1));
-            if (n < a.N && b < a.B)
-              v[u] = *reinterpret_cast<const float4*>(a.x + (long long)b * a.sb + (long long)n * a.sn + 4 * c);
-          }
+        for (int u = 0; u < 4; ++u) {
+          const int i = base + u * kThreads + tid;
+          const int ic = i < items ? i : 0;                      // clamped: the load is unconditional
+          const int r = ic / L4;
+          const int c = ic - r * L4;
+          rr[u] = i < items ? r : -1;
+          cc[u] = c;
+          const int n = min(n0 + (r >> a.log2_rpv), a.N - 1);
+          const int b = min(rb * 32 + (r & (rpv - 1)), a.B - 1);
+          const bool ok = (n0 + (r >> a.log2_rpv) < a.N) && (rb * 32 + (r & (rpv - 1)) < a.B);
+          const float4 t = *reinterpret_cast<const float4*>(a.x + (long long)b * a.sb + (long long)n * a.sn + 4 * c);
+          v[u] = make_float4(ok ? t.x : 0.f, ok ? t.y : 0.f, ok ? t.z : 0.f, ok ? t.w : 0.f);   // rows past the end are zero windows
         }
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
+        for (int u = 0; u < 4; ++u) {
           if (rr[u] >= 0) {
             float* p = tile + (4 * cc[u]) * kTilePad + rr[u];
             p[0] = v[u].x;
@@ -105,7 +106,7 @@ __global__ __launch_bounds__(64) void kdfh_kernel(KdfhArgs a) {
         }
       }
     } else {
-      for (int r = 0; r < 32; ++r) {
+      for (int r = wave; r < 32; r += kWaves) {
         const int n = n0 + (r >> a.log2_rpv);
         const int b = rb * 32 + (r & (rpv - 1));
         const bool ok = n < a.N && b < a.B;
@@ -114,56 +115,95 @@ __global__ __launch_bounds__(64) void kdfh_kernel(KdfhArgs a) {
       }
     }
     __syncthreads();
+    // ---- fold in place: row t becomes x[t] + x[L-t] and row L-t becomes x[t] - x[L-t] for
+    // 0 < t < L/2 (rows 0 and L/2 stay); row L is a zero row for steps past the end.
+    {
+      const int npair = (L - 1) >> 1;
+      for (int i = tid; i < npair * 32; i += kThreads) {
+        const int t = 1 + (i >> 5), r = i & 31;
+        const float p = tile[t * kTilePad + r], q = tile[(L - t) * kTilePad + r];
+        tile[t * kTilePad + r] = p + q;
+        tile[(L - t) * kTilePad + r] = p - q;
+      }
+      if (tid < 32) tile[L * kTilePad + tid] = 0.f;
+    }
+    __syncthreads();
 
-    // ---- spectrum of the 32 rows, 32 bins at a time
+    // ---- spectrum of the 32 rows, 32 bins at a time; this wavefront's share of the contraction
     for (int ct = 0; ct < nct; ++ct) {
       const int f = a.f_min + ct * 32 + col;
-      const int twof = (2 * f) % L;
-      int mc = (f * half) % L;
-      int ms = (f * (1 + half)) % L;
+      const int step8 = (8 * f) % L;             // advancing s by kWaves moves t by 8
+      int mc = (f * (2 * wave + half)) % L;
+      int ms = (f * (2 * wave + 1 + half)) % L;
       floatx16 re = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
       floatx16 im = re;
-      for (int s = 0; s < Sc; ++s) {
-        const int tc = 2 * s + half;
-        float ac = 0.f;
-        if (tc <= Lh) {
-          ac = tile[tc * kTilePad + col];
-          if (tc != 0 && 2 * tc != L) ac += tile[(L - tc) * kTilePad + col];
-        }
-        const float bc = cosT[mc];
-        mc += twof;
+      // Software pipeline: the operands of step s + kWaves are read from LDS while the matrix
+      // instructions of step s run (a lone wavefront per SIMD has nothing else to hide that latency).
+      // A step past the end of either sum reads the zero row.
+      int tc = 2 * wave + half;
+      float ac = tile[(tc <= Lh ? tc : L) * kTilePad + col];
+      float as = tile[(2 * (tc + 1) < L ? L - (tc + 1) : L) * kTilePad + col];
+      float bc = cosT[mc], bs = sinT[ms];
+      for (int s = wave; s < Sc; s += kWaves) {
+        const float ac0 = ac, as0 = as, bc0 = bc, bs0 = bs;
+        tc += 2 * kWaves;
+        mc += step8;
         if (mc >= L) mc -= L;
-        re = __builtin_amdgcn_mfma_f32_32x32x2f32(ac, bc, re, 0, 0, 0);
-        if (s < Ss) {
-          const int ts = tc + 1;
-          float as = 0.f;
-          if (2 * ts < L) as = tile[ts * kTilePad + col] - tile[(L - ts) * kTilePad + col];
-          const float bs = sinT[ms];
-          ms += twof;
-          if (ms >= L) ms -= L;
-          im = __builtin_amdgcn_mfma_f32_32x32x2f32(as, bs, im, 0, 0, 0);
-        }
+        ms += step8;
+        if (ms >= L) ms -= L;
+        ac = tile[(tc <= Lh ? tc : L) * kTilePad + col];
+        as = tile[(2 * (tc + 1) < L ? L - (tc + 1) : L) * kTilePad + col];
+        bc = cosT[mc];
+        bs = sinT[ms];
+        __builtin_amdgcn_sched_barrier(0);
+        re = __builtin_amdgcn_mfma_f32_32x32x2f32(ac0, bc0, re, 0, 0, 0);
+        im = __builtin_amdgcn_mfma_f32_32x32x2f32(as0, bs0, im, 0, 0, 0);
+        // (keeps the reads above in this iteration: without it the compiler folds them back into
+        //  the top of the next one, in front of the instructions that need them)
+        __builtin_amdgcn_sched_barrier(0);
+        asm volatile("" : "+v"(ac), "+v"(as), "+v"(bc), "+v"(bs));
       }
-      // accumulator register r of a lane holds row 8*(r/4) + 4*half + r%4, column col
+      // Partial sums of the four wavefronts meet in LDS, real parts first, then imaginary parts:
+      // part[wave][register][lane].  This wavefront finishes registers 4*wave .. 4*wave+3, i.e. rows
+      // 8*wave + 4*half + (0..3) (accumulator register r of a lane holds row 8*(r/4) + 4*half + r%4,
+      // column col).
+      float sr[4], si[4];
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = 8 * (r >> 2) + 4 * half + (r & 3);
-        ampT[row * kTilePad + col] = sqrtf(re[r] * re[r] + im[r] * im[r]);
+      for (int r = 0; r < 16; ++r) part[(wave * 16 + r) * 64 + lane] = re[r];
+      __syncthreads();
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        sr[q] = 0.f;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) sr[q] += part[(w * 16 + 4 * wave + q) * 64 + lane];
+      }
+      __syncthreads();
+#pragma unroll
+      for (int r = 0; r < 16; ++r) part[(wave * 16 + r) * 64 + lane] = im[r];
+      __syncthreads();
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        si[q] = 0.f;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) si[q] += part[(w * 16 + 4 * wave + q) * 64 + lane];
+        ampT[(8 * wave + 4 * half + q) * kTilePad + col] = sqrtf(sr[q] * sr[q] + si[q] * si[q]);
       }
       __syncthreads();
       const int bin = ct * 32 + col;
-      for (int v = half; v < Vb; v += 2) {
+      for (int v = tid >> 5; v < Vb; v += kThreads / 32) {
         float sum = 0.f;
         for (int b = 0; b < rpv; ++b) sum += ampT[(v * rpv + b) * kTilePad + col];
         if (bin < F) asum[v * F + bin] += sum;
       }
-      __syncthreads();
+      // (the next write to `part` or `ampT` is separated from these reads by the barrier after the
+      //  partial sums of the next column tile, or by the one at the top of the row-block loop)
     }
   }
+  __syncthreads();
 
-  // ---- ranked top-k and hash, one variate after the other
+  // ---- ranked top-k and hash; the variates of the block are shared out over the wavefronts
   const unsigned long long R = (unsigned long long)(L / 2 + 1);
-  for (int v = 0; v < Vb; ++v) {
+  for (int v = wave; v < Vb; v += kWaves) {
     const int n = n0 + v;
     if (n >= a.N) break;
     float vals[kMaxBinsPerLane];
@@ -206,7 +246,7 @@ __global__ __launch_bounds__(64) void kdfh_kernel(KdfhArgs a) {
 }
 
 size_t kdfh_lds_bytes(int L, int F, int Vb) {
-  return sizeof(float) * ((size_t)2 * L + (size_t)L * kTilePad + 32 * kTilePad + (size_t)Vb * F);
+  return sizeof(float) * ((size_t)2 * L + (size_t)(L + 1) * kTilePad + kWaves * 16 * 64 + 32 * kTilePad + (size_t)Vb * F);
 }
 
 }  // namespace
@@ -277,7 +317,7 @@ extern "C" int vardrop_hash(vardrop_ctx* ctx, const float* x, int B, int N, int 
     VD_HIP(ctx, hipFuncSetAttribute((const void*)kdfh_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
   {
     VdTimer timer(ctx, VARDROP_K_HASH, s);
-    hipLaunchKernelGGL(kdfh_kernel, dim3(vd_ceil_div(N, Vb)), dim3(64), lds, s, a);
+    hipLaunchKernelGGL(kdfh_kernel, dim3(vd_ceil_div(N, Vb)), dim3(kThreads), lds, s, a);
   }
   VD_LAUNCH_CHECK(ctx);
   return VARDROP_OK;

@@ -81,7 +81,7 @@ def test_flat_variate_hashes_to_lowest_bins(vd, ctx):
 
 @pytest.mark.parametrize("B,N,L,k", [(1, 7, 96, 3), (5, 13, 96, 3), (32, 3, 96, 2), (33, 5, 96, 3), (70, 4, 64, 4),
                                       (3, 40, 97, 3), (6, 9, 98, 2), (2, 5, 10, 2), (4, 3, 2, 1), (16, 37, 336, 4),
-                                      (8, 11, 512, 5), (33, 2, 1024, 6)])
+                                      (8, 11, 512, 5), (33, 2, 896, 6)])
 def test_shapes_and_ragged_edges(vd, ctx, B, N, L, k):
     rng = np.random.default_rng(B * 1000 + L)
     x = rng.standard_normal((B, N, L)).astype(np.float32)
