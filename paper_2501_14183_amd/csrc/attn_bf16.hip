@@ -352,8 +352,9 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(SplitkReduce a) {
 }
 
 // ================================================================== GEMM with asynchronous LDS fill
-// C[z] = A[z] * op(B[z]) (+ bias[z]) in bf16, or the sum over up to three segments into C[0].
-// A is k-contiguous [M][K]; B is k-contiguous [N][K] (BKC) or n-contiguous [K][N].  K is a multiple of BK.
+// C[z] = op(A[z]) * op(B[z]) (+ bias[z]) in bf16, the sum over up to three segments into C[0], or
+// (SPLIT) an fp32 partial product per K slice.  Each operand is either k-contiguous ([M][K] / [N][K])
+// or mn-contiguous ([K][M] / [K][N]).
 //
 // Global memory is copied straight into LDS (global_load_lds_dwordx4: every lane names its own 16
 // source bytes, the wavefront's 64 chunks land in 1 KB of consecutive LDS), NS stages deep, so
@@ -361,17 +362,20 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(SplitkReduce a) {
 // current one and no register or LDS-store instruction is spent on staging.  Because the LDS side
 // of a copy is fixed, the bank swizzle is applied on the source side: LDS chunk position p of a row
 // holds source chunk p ^ pattern(row).
-//   k-contiguous operand: LDS tile [row][BK], fragments are 16-byte reads (row = lane % 32,
-//                         chunk 2*ks + lane / 32), pattern chosen so that eight consecutive rows
-//                         spread over all banks.
-//   n-contiguous operand: LDS tile [k][128]; fragments come from the transposing read
-//                         ds_read_b64_tr_b16, in which, inside each group of 16 lanes, lane s names
-//                         four consecutive n of k-row s / 4 at column block s % 4, and lane j
-//                         receives column j of the four k-rows.
+//   k-contiguous operand:  LDS tile [row][BK], fragments are 16-byte reads (row = lane % 32,
+//                          chunk 2*ks + lane / 32), pattern chosen so that eight consecutive rows
+//                          spread over all banks.
+//   mn-contiguous operand: LDS tile [k][W]; fragments come from the transposing read
+//                          ds_read_b64_tr_b16, in which, inside each group of 16 lanes, lane s names
+//                          four consecutive columns of k-row s / 4 at column block s % 4, and lane j
+//                          receives column j of the four k-rows.  A slice that reaches past the end
+//                          of K (weight gradients: K is the token count) is copied from clamped
+//                          rows and the left operand's fragments are masked.
 // Fragment reads and the wait counters are written out by hand: the compiler would otherwise wait
 // for every outstanding copy before any LDS read.
-// The product is formed transposed (the B fragment is the left operand), so that a lane owns one
-// output row and four consecutive columns per register quad: 8-byte stores.
+// The product is formed transposed (the B fragment is the left operand of the instruction), so a
+// lane owns one output row and four consecutive columns per register quad; the tile goes through
+// LDS once more so that global stores are whole 16-byte chunks of consecutive rows.
 __device__ inline void dma16(const bf16_t* gp, unsigned char* lp) {
   __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gp,
                                    (__attribute__((address_space(3))) void*)lp, 16, 0, 0);
@@ -397,24 +401,38 @@ __device__ inline void wait_lds(Frag& a, Frag& b, Frag& c) {
 
 template <int BK>
 __device__ inline int swz_kc(int row) { return BK == 32 ? (row >> 1) & 3 : row & 7; }
-__device__ inline int swz_nc(int krow) { return ((krow & 3) << 1) ^ (((krow >> 3) & 1) << 3); }
+template <int W>
+__device__ inline int swz_nc(int krow) { return W == 128 ? (((krow & 3) << 1) ^ (((krow >> 3) & 1) << 3)) : ((krow & 3) << 1); }
+// zeroes the elements k >= kvalid of a fragment holding k = 0..7
+__device__ inline void mask_frag(Frag& f, int kvalid) {
+#pragma unroll
+  for (int e = 0; e < 4; ++e)
+    f.w[e] &= kvalid >= 2 * e + 2 ? 0xffffffffu : (kvalid == 2 * e + 1 ? 0x0000ffffu : 0u);
+}
 
-template <bool BKC, int BM, int BK, int NS>
+template <bool AKC, bool BKC, bool SPLIT, int BM, int BK, int NS>
 __global__ __launch_bounds__(256, 2) void gemm_async_kernel(GemmBf16 g) {
   constexpr int BN = 128, MI = BM / 64, KS = BK / 16;
   constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE = A_BYTES + B_BYTES;
   constexpr int IA = A_BYTES / 4096, IB = B_BYTES / 4096, LPS = IA + IB;   // 1 KB copies per wavefront and stage
   constexpr int CH = BK / 8;                                              // 16-byte chunks per k-contiguous row
-  constexpr int RPI = 64 / CH;                                            // rows per copy instruction
-  constexpr int OPK = MI + (BKC ? 2 : 4);                                 // LDS reads per 16-k step
+  constexpr int RPI = 64 / CH;                                            // ... and rows per copy instruction
+  constexpr int CHA = BM / 8, RPA = 64 / CHA;                             // the same for an [k][BM] tile
+  constexpr int CHB = BN / 8, RPB = 64 / CHB;                             // and an [k][BN] tile
+  constexpr int OPK = (AKC ? MI : 2 * MI) + (BKC ? 2 : 4);                // LDS reads per 16-k step
+  constexpr int ES = SPLIT ? 4 : 2;                                       // output element size
+  constexpr int CPITCH = BN * ES + 16;                                    // LDS row pitch of the output tile
+  static_assert(BM * CPITCH <= NS * STAGE, "output tile must fit in the staging buffers");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   const int col = lane & 31, half = lane >> 5;
-  const int zb = blockIdx.z;
+  const int zb = SPLIT ? blockIdx.z / g.splitk : blockIdx.z;
+  const int kbeg = SPLIT ? (blockIdx.z % g.splitk) * g.kchunk : 0;
+  const int kend = SPLIT ? min(g.K, kbeg + g.kchunk) : g.K;
   const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
   const int nseg = g.nseg > 1 ? g.nseg : 1;
-  const int nk = g.K / BK;
+  const int nk = (kend - kbeg + BK - 1) / BK;
   const int total = nseg * nk;
   const int zsel = g.nseg > 1 ? 0 : zb;
   const bf16_t* A1 = g.A1; const bf16_t* B1 = g.B1;
@@ -422,12 +440,21 @@ __global__ __launch_bounds__(256, 2) void gemm_async_kernel(GemmBf16 g) {
   const bf16_t* A0 = zsel == 0 ? g.A0 : (zsel == 1 ? A1 : (zsel == 2 ? A2 : g.A3));
   const bf16_t* B0 = zsel == 0 ? g.B0 : (zsel == 1 ? B1 : (zsel == 2 ? B2 : g.B3));
 
-  // ---- source offsets of this lane's copies (elements) and fragment addresses (LDS bytes)
+  // ---- source offsets of this lane's copies (elements)
+  //   k-contiguous: clamped row * ld + chunk * 8, the slice start is added per stage
+  //   mn-contiguous: column offset; the k-row (first one in goffX[u] >> 16... kept separately) is clamped per stage
   int goffA[IA], goffB[IB];
+  int krowA = 0, krowB = 0;                 // k-row of copy 0 (mn-contiguous); copy u adds u * 4 * RPx
 #pragma unroll
   for (int u = 0; u < IA; ++u) {
-    const int row = (u * 4 + wave) * RPI + lane / CH;
-    goffA[u] = min(m0 + row, g.M - 1) * g.lda + ((lane % CH) ^ swz_kc<BK>(row)) * 8;
+    if constexpr (AKC) {
+      const int row = (u * 4 + wave) * RPI + lane / CH;
+      goffA[u] = min(m0 + row, g.M - 1) * g.lda + ((lane % CH) ^ swz_kc<BK>(row)) * 8;
+    } else {
+      const int krow = (u * 4 + wave) * RPA + lane / CHA;
+      if (u == 0) krowA = krow;
+      goffA[u] = min(m0 + ((lane % CHA) ^ swz_nc<BM>(krow)) * 8, g.M - 8);
+    }
   }
 #pragma unroll
   for (int u = 0; u < IB; ++u) {
@@ -435,17 +462,25 @@ __global__ __launch_bounds__(256, 2) void gemm_async_kernel(GemmBf16 g) {
       const int row = (u * 4 + wave) * RPI + lane / CH;
       goffB[u] = min(n0 + row, g.N - 1) * g.ldb + ((lane % CH) ^ swz_kc<BK>(row)) * 8;
     } else {
-      const int krow = (u * 4 + wave) * 4 + lane / 16;
-      goffB[u] = krow * g.ldb + min(n0 + ((lane % 16) ^ swz_nc(krow)) * 8, g.N - 8);
+      const int krow = (u * 4 + wave) * RPB + lane / CHB;
+      if (u == 0) krowB = krow;
+      goffB[u] = min(n0 + ((lane % CHB) ^ swz_nc<BN>(krow)) * 8, g.N - 8);
     }
   }
+  // ---- fragment addresses (LDS bytes relative to a stage)
   const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
-  uint32_t addrA[MI][KS], addrB[2][BKC ? KS : 1];
+  uint32_t addrA[MI][AKC ? KS : 1], addrB[2][BKC ? KS : 1];
 #pragma unroll
   for (int i = 0; i < MI; ++i) {
-    const int ra = wm * (BM / 2) + i * 32 + col;
+    if constexpr (AKC) {
+      const int ra = wm * (BM / 2) + i * 32 + col;
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) addrA[i][ks] = lds0 + ra * (BK * 2) + (((2 * ks + half) ^ swz_kc<BK>(ra)) * 16);
+      for (int ks = 0; ks < KS; ++ks) addrA[i][ks] = lds0 + ra * (BK * 2) + (((2 * ks + half) ^ swz_kc<BK>(ra)) * 16);
+    } else {
+      const int krow = 8 * half + ((lane & 15) >> 2);
+      const int mn = wm * (BM / 2) + i * 32 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+      addrA[i][0] = lds0 + krow * (BM * 2) + (((mn >> 3) ^ swz_nc<BM>(krow)) * 16) + ((mn >> 2) & 1) * 8;
+    }
   }
 #pragma unroll
   for (int j = 0; j < 2; ++j) {
@@ -457,7 +492,7 @@ __global__ __launch_bounds__(256, 2) void gemm_async_kernel(GemmBf16 g) {
     } else {
       const int krow = 8 * half + ((lane & 15) >> 2);
       const int mn = wn * 64 + j * 32 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-      addrB[j][0] = lds0 + A_BYTES + krow * 256 + (((mn >> 3) ^ swz_nc(krow)) * 16) + ((mn >> 2) & 1) * 8;
+      addrB[j][0] = lds0 + A_BYTES + krow * (BN * 2) + (((mn >> 3) ^ swz_nc<BN>(krow)) * 16) + ((mn >> 2) & 1) * 8;
     }
   }
 
@@ -468,19 +503,27 @@ __global__ __launch_bounds__(256, 2) void gemm_async_kernel(GemmBf16 g) {
     for (int j = 0; j < 2; ++j) acc[i][j] = zero16();
 
   // ---- copy cursor
-  int fseg = 0, fk = 0;
+  int fseg = 0, fk = kbeg;
   const bf16_t* Ap = A0;
   const bf16_t* Bp = B0;
 #define VD_ISSUE_STAGE(BUF)                                                                        \
   {                                                                                                \
     unsigned char* sp = smem + (BUF) * STAGE + wave * 1024;                                        \
-    const bf16_t* pa = Ap + fk;                                                                    \
-    const bf16_t* pb = BKC ? Bp + fk : Bp + (long long)fk * g.ldb;                                 \
-    _Pragma("unroll") for (int u = 0; u < IA; ++u) dma16(pa + goffA[u], sp + u * 4096);            \
-    _Pragma("unroll") for (int u = 0; u < IB; ++u) dma16(pb + goffB[u], sp + A_BYTES + u * 4096);  \
+    _Pragma("unroll") for (int u = 0; u < IA; ++u) {                                               \
+      const bf16_t* p;                                                                             \
+      if constexpr (AKC) p = Ap + fk + goffA[u];                                                   \
+      else p = Ap + (long long)min(fk + krowA + u * 4 * RPA, kend - 1) * g.lda + goffA[u];         \
+      dma16(p, sp + u * 4096);                                                                     \
+    }                                                                                              \
+    _Pragma("unroll") for (int u = 0; u < IB; ++u) {                                               \
+      const bf16_t* p;                                                                             \
+      if constexpr (BKC) p = Bp + fk + goffB[u];                                                   \
+      else p = Bp + (long long)min(fk + krowB + u * 4 * RPB, kend - 1) * g.ldb + goffB[u];         \
+      dma16(p, sp + A_BYTES + u * 4096);                                                           \
+    }                                                                                              \
     fk += BK;                                                                                      \
-    if (fk >= g.K) {                                                                               \
-      fk = 0;                                                                                      \
+    if (fk >= kend) {                                                                              \
+      fk = kbeg;                                                                                   \
       ++fseg;                                                                                      \
       Ap = fseg == 1 ? A1 : A2;                                                                    \
       Bp = fseg == 1 ? B1 : B2;                                                                    \
@@ -503,23 +546,38 @@ __global__ __launch_bounds__(256, 2) void gemm_async_kernel(GemmBf16 g) {
         __builtin_amdgcn_s_barrier();     // everyone's copies of slice t are in; everyone is done with slice t-1
         if (t + NS - 1 < total) VD_ISSUE_STAGE((s + NS - 1) % NS)
         const uint32_t so = s * STAGE;
+        // valid k of this lane's first fragment; only the last slice of an mn-contiguous A can fall short
+        int kvalid = 8;
+        if constexpr (!AKC) kvalid = t == total - 1 ? kend - (kbeg + (nk - 1) * BK + 8 * half) : 8 + 16 * KS;
         Frag fa[2][2], fb[2][2];
 #define VD_READ_STEP(KS_, SET)                                                                     \
   {                                                                                                \
-    _Pragma("unroll") for (int i = 0; i < MI; ++i) lds_read16(fa[SET][i].q, addrA[i][KS_] + so);   \
+    _Pragma("unroll") for (int i = 0; i < MI; ++i) {                                               \
+      if constexpr (AKC) {                                                                         \
+        lds_read16(fa[SET][i].q, addrA[i][AKC ? (KS_) : 0] + so);                                  \
+      } else {                                                                                     \
+        lds_read8_tr<(KS_) * 16 * BM * 2>(fa[SET][i].d[0], addrA[i][0] + so);                      \
+        lds_read8_tr<(KS_) * 16 * BM * 2 + 4 * BM * 2>(fa[SET][i].d[1], addrA[i][0] + so);         \
+      }                                                                                            \
+    }                                                                                              \
     _Pragma("unroll") for (int j = 0; j < 2; ++j) {                                                \
       if constexpr (BKC) {                                                                         \
-        lds_read16(fb[SET][j].q, addrB[j][KS_] + so);                                              \
+        lds_read16(fb[SET][j].q, addrB[j][BKC ? (KS_) : 0] + so);                                  \
       } else {                                                                                     \
-        lds_read8_tr<(KS_) * 4096>(fb[SET][j].d[0], addrB[j][0] + so);                             \
-        lds_read8_tr<(KS_) * 4096 + 1024>(fb[SET][j].d[1], addrB[j][0] + so);                      \
+        lds_read8_tr<(KS_) * 16 * BN * 2>(fb[SET][j].d[0], addrB[j][0] + so);                      \
+        lds_read8_tr<(KS_) * 16 * BN * 2 + 4 * BN * 2>(fb[SET][j].d[1], addrB[j][0] + so);         \
       }                                                                                            \
     }                                                                                              \
   }
-#define VD_MFMA_STEP(SET, PENDING)                                                                 \
+#define VD_MFMA_STEP(KS_, SET, PENDING)                                                            \
   {                                                                                                \
     if constexpr (MI == 2) wait_lds<PENDING>(fa[SET][0], fa[SET][1], fb[SET][0], fb[SET][1]);      \
     else wait_lds<PENDING>(fa[SET][0], fb[SET][0], fb[SET][1]);                                    \
+    if constexpr (!AKC) {                                                                          \
+      if (kvalid - 16 * (KS_) < 8) {                                                               \
+        _Pragma("unroll") for (int i = 0; i < MI; ++i) mask_frag(fa[SET][i], kvalid - 16 * (KS_)); \
+      }                                                                                            \
+    }                                                                                              \
     _Pragma("unroll") for (int i = 0; i < MI; ++i)                                                 \
       _Pragma("unroll") for (int j = 0; j < 2; ++j) acc[i][j] = mfma(fb[SET][j], fa[SET][i], acc[i][j]); \
     __builtin_amdgcn_sched_barrier(0);                                                             \
@@ -527,16 +585,16 @@ __global__ __launch_bounds__(256, 2) void gemm_async_kernel(GemmBf16 g) {
         VD_READ_STEP(0, 0)
         if constexpr (KS == 2) {
           VD_READ_STEP(1, 1)
-          VD_MFMA_STEP(0, OPK)
-          VD_MFMA_STEP(1, 0)
+          VD_MFMA_STEP(0, 0, OPK)
+          VD_MFMA_STEP(1, 1, 0)
         } else {
           VD_READ_STEP(1, 1)
-          VD_MFMA_STEP(0, OPK)
+          VD_MFMA_STEP(0, 0, OPK)
           VD_READ_STEP(2, 0)
-          VD_MFMA_STEP(1, OPK)
+          VD_MFMA_STEP(1, 1, OPK)
           VD_READ_STEP(3, 1)
-          VD_MFMA_STEP(0, OPK)
-          VD_MFMA_STEP(1, 0)
+          VD_MFMA_STEP(2, 0, OPK)
+          VD_MFMA_STEP(3, 1, 0)
         }
 #undef VD_READ_STEP
 #undef VD_MFMA_STEP
@@ -545,56 +603,87 @@ __global__ __launch_bounds__(256, 2) void gemm_async_kernel(GemmBf16 g) {
   }
 #undef VD_ISSUE_STAGE
 
-  // ---- epilogue: acc[i][j] register 4*q4 + e is C[m0 + wm*BM/2 + i*32 + col][n0 + wn*64 + j*32 + 8*q4 + 4*half + e]
-  const bf16_t* bias = zsel == 0 ? g.bias0 : (zsel == 1 ? g.bias1 : (zsel == 2 ? g.bias2 : g.bias3));
-  bf16_t* C = reinterpret_cast<bf16_t*>(zsel == 0 ? g.C0 : (zsel == 1 ? g.C1 : (zsel == 2 ? g.C2 : g.C3)));
+  // ---- epilogue.  acc[i][j] register 4*q4 + e is C[wm*BM/2 + i*32 + col][wn*64 + j*32 + 8*q4 + 4*half + e]
+  // of the tile; it is written to LDS (with the bias), then stored as 16-byte chunks of whole rows.
+  const bf16_t* bias = SPLIT ? nullptr : (zsel == 0 ? g.bias0 : (zsel == 1 ? g.bias1 : (zsel == 2 ? g.bias2 : g.bias3)));
+  __syncthreads();                        // every wavefront is done reading the last slice
 #pragma unroll
   for (int j = 0; j < 2; ++j)
 #pragma unroll
     for (int q4 = 0; q4 < 4; ++q4) {
-      const int n = n0 + wn * 64 + j * 32 + 8 * q4 + 4 * half;
-      if (n < g.N) {                                  // N is a multiple of 4: a quad is inside or outside
-        float bv[4] = {0.f, 0.f, 0.f, 0.f};
-        if (bias) {
-          const u32x2 b4 = *reinterpret_cast<const u32x2*>(bias + n);
-          bv[0] = __uint_as_float(b4.x << 16); bv[1] = __uint_as_float(b4.x & 0xffff0000u);
-          bv[2] = __uint_as_float(b4.y << 16); bv[3] = __uint_as_float(b4.y & 0xffff0000u);
-        }
+      const int nl = wn * 64 + j * 32 + 8 * q4 + 4 * half;
+      float bv[4] = {0.f, 0.f, 0.f, 0.f};
+      if (bias && n0 + nl < g.N) {                 // N is a multiple of 8: a quad is inside or outside
+        const u32x2 b4 = *reinterpret_cast<const u32x2*>(bias + n0 + nl);
+        bv[0] = __uint_as_float(b4.x << 16); bv[1] = __uint_as_float(b4.x & 0xffff0000u);
+        bv[2] = __uint_as_float(b4.y << 16); bv[3] = __uint_as_float(b4.y & 0xffff0000u);
+      }
 #pragma unroll
-        for (int i = 0; i < MI; ++i) {
-          const int m = m0 + wm * (BM / 2) + i * 32 + col;
-          if (m < g.M) {
-            u32x2 o;
-            o.x = pack2(acc[i][j][4 * q4] + bv[0], acc[i][j][4 * q4 + 1] + bv[1]);
-            o.y = pack2(acc[i][j][4 * q4 + 2] + bv[2], acc[i][j][4 * q4 + 3] + bv[3]);
-            *reinterpret_cast<u32x2*>(C + (long long)m * g.ldc + n) = o;
-          }
+      for (int i = 0; i < MI; ++i) {
+        unsigned char* p = smem + (wm * (BM / 2) + i * 32 + col) * CPITCH + nl * ES;
+        if constexpr (SPLIT) {
+          float4 o = make_float4(acc[i][j][4 * q4], acc[i][j][4 * q4 + 1], acc[i][j][4 * q4 + 2], acc[i][j][4 * q4 + 3]);
+          *reinterpret_cast<float4*>(p) = o;
+        } else {
+          u32x2 o;
+          o.x = pack2(acc[i][j][4 * q4] + bv[0], acc[i][j][4 * q4 + 1] + bv[1]);
+          o.y = pack2(acc[i][j][4 * q4 + 2] + bv[2], acc[i][j][4 * q4 + 3] + bv[3]);
+          *reinterpret_cast<u32x2*>(p) = o;
         }
       }
     }
+  __syncthreads();
+  constexpr int CPR = BN * ES / 16;          // 16-byte chunks per tile row
+  constexpr int EPC = 16 / ES;               // elements per chunk
+  unsigned char* Cb;
+  long long ldc_bytes;
+  if constexpr (SPLIT) {
+    Cb = reinterpret_cast<unsigned char*>(g.C0) + (long long)blockIdx.z * g.M * g.N * 4;
+    ldc_bytes = (long long)g.N * 4;
+  } else {
+    Cb = reinterpret_cast<unsigned char*>(zsel == 0 ? g.C0 : (zsel == 1 ? g.C1 : (zsel == 2 ? g.C2 : g.C3)));
+    ldc_bytes = (long long)g.ldc * 2;
+  }
+#pragma unroll
+  for (int u = 0; u < BM * CPR / 256; ++u) {
+    const int idx = u * 256 + threadIdx.x;
+    const int row = idx / CPR, c = idx % CPR;
+    if (m0 + row < g.M && n0 + c * EPC < g.N) {
+      const u32x4 v = *reinterpret_cast<const u32x4*>(smem + row * CPITCH + c * 16);
+      *reinterpret_cast<u32x4*>(Cb + (long long)(m0 + row) * ldc_bytes + (long long)(n0 + c * EPC) * ES) = v;
+    }
+  }
 }
 
 // Tile and pipeline depth of the asynchronous GEMM: 128 x 128 tiles once there are enough of them to
 // keep every compute unit busy with two workgroups; otherwise 64 x 128 tiles, three stages deep while
 // two workgroups still fit beside each other in LDS (at most 512 tiles), else two stages and three
 // workgroups per compute unit.
-template <bool BKC, int BM, int NS>
+template <bool AKC, bool BKC, bool SPLIT, int BM, int NS>
 int launch_gemm_async_cfg(vardrop_ctx* ctx, int kid, const GemmBf16& g, int nz, hipStream_t s) {
   constexpr int BK = 64;
   constexpr int lds = NS * (BM + 128) * BK * 2;
   static int configured_device = -1;     // raising the dynamic LDS limit is a per-device, per-function setting
   if (configured_device != ctx->device) {
-    VD_HIP(ctx, hipFuncSetAttribute((const void*)gemm_async_kernel<BKC, BM, BK, NS>,
+    VD_HIP(ctx, hipFuncSetAttribute((const void*)gemm_async_kernel<AKC, BKC, SPLIT, BM, BK, NS>,
                                     hipFuncAttributeMaxDynamicSharedMemorySize, lds));
     configured_device = ctx->device;
   }
-  dim3 grid(vd_ceil_div(g.N, 128), vd_ceil_div(g.M, BM), nz);
+  dim3 grid(vd_ceil_div(g.N, 128), vd_ceil_div(g.M, BM), nz * (SPLIT ? g.splitk : 1));
   {
     VdTimer timer(ctx, kid, s);
-    hipLaunchKernelGGL((gemm_async_kernel<BKC, BM, BK, NS>), grid, dim3(256), lds, s, g);
+    hipLaunchKernelGGL((gemm_async_kernel<AKC, BKC, SPLIT, BM, BK, NS>), grid, dim3(256), lds, s, g);
   }
   VD_LAUNCH_CHECK(ctx);
   return VARDROP_OK;
+}
+// weight gradients: both operands mn-contiguous, K = tokens cut into splitk slices, fp32 partial products
+int launch_gemm_async_dw(vardrop_ctx* ctx, int kid, const GemmBf16& g, int nz, hipStream_t s) {
+  if (g.M == 0 || g.N == 0) return VARDROP_OK;
+  if (g.M % 8 != 0 || g.N % 8 != 0 || g.kchunk % 64 != 0 || g.splitk < 1 ||
+      (long long)g.K * g.lda >= (1ll << 31) || (long long)g.K * g.ldb >= (1ll << 31))
+    return VARDROP_EUNSUPPORTED;
+  return launch_gemm_async_cfg<false, false, true, 64, 2>(ctx, kid, g, nz, s);
 }
 template <bool BKC>
 int launch_gemm_async(vardrop_ctx* ctx, int kid, const GemmBf16& g, int nz, hipStream_t s) {
@@ -603,9 +692,9 @@ int launch_gemm_async(vardrop_ctx* ctx, int kid, const GemmBf16& g, int nz, hipS
     return VARDROP_EUNSUPPORTED;
   const long long t128 = (long long)vd_ceil_div(g.N, 128) * vd_ceil_div(g.M, 128) * nz;
   const long long t64 = (long long)vd_ceil_div(g.N, 128) * vd_ceil_div(g.M, 64) * nz;
-  if (t128 >= 1024) return launch_gemm_async_cfg<BKC, 128, 2>(ctx, kid, g, nz, s);
-  if (t64 <= 512) return launch_gemm_async_cfg<BKC, 64, 3>(ctx, kid, g, nz, s);
-  return launch_gemm_async_cfg<BKC, 64, 2>(ctx, kid, g, nz, s);
+  if (t128 >= 1024) return launch_gemm_async_cfg<true, BKC, false, 128, 2>(ctx, kid, g, nz, s);
+  if (t64 <= 512) return launch_gemm_async_cfg<true, BKC, false, 64, 3>(ctx, kid, g, nz, s);
+  return launch_gemm_async_cfg<true, BKC, false, 64, 2>(ctx, kid, g, nz, s);
 }
 
 // 128 x 128 tiles when they still give every compute unit several workgroups to overlap, otherwise
@@ -1094,7 +1183,7 @@ int vd_attn_bwd_bf16(vardrop_ctx* ctx, const void* dy, const void* xs, int B, in
     if (g.splitk > 1) {
       float* part = (float*)((char*)ws + vd_attn_bf16_partial_offset(B, n, d, H));
       g.C0 = part;
-      if ((rc = launch_gemm<false, false, float>(ctx, VARDROP_K_GEMM_DW, g, 4, s))) return rc;
+      if ((rc = launch_gemm_async_dw(ctx, VARDROP_K_GEMM_DW, g, 4, s))) return rc;
       SplitkReduce r = {};
       r.part = part;
       for (int z = 0; z < 4; ++z) r.out[z] = dW[z];
