@@ -48,6 +48,7 @@ def algorithmic_work(w, n):
         "gemm_dw": (mm, 8.0 * M * d * d),
         "reduce_dw": ("hbm", 4.0 * 4 * d * d * 2),
         "gemm_dxs": (mm, 6.0 * M * d * d),
+        "gemm_dw_dxs": (mm, 14.0 * M * d * d),
     }
 
 

@@ -73,6 +73,7 @@ enum {
   VARDROP_K_REDUCE_DW,       /* sum of the K slices                                         */
   VARDROP_K_GEMM_DXS,        /* dxs = dQ Wq^T + dK Wk^T + dV Wv^T                           */
   VARDROP_K_SCATTER,         /* adjoint of the gather                                       */
+  VARDROP_K_GEMM_DW_DXS,     /* weight gradients (K slices) and dxs in one launch           */
   VARDROP_K_COUNT
 };
 int vardrop_profile_select(vardrop_ctx* ctx, int kernel_id);

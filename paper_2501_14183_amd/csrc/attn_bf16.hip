@@ -411,7 +411,7 @@ __device__ inline void mask_frag(Frag& f, int kvalid) {
 }
 
 template <bool AKC, bool BKC, bool SPLIT, int BM, int BK, int NS>
-__global__ __launch_bounds__(256, 2) void gemm_async_kernel(GemmBf16 g) {
+__device__ __forceinline__ void gemm_async_tile(const GemmBf16& g, const int bx, const int by, const int bz) {
   constexpr int BN = 128, MI = BM / 64, KS = BK / 16;
   constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE = A_BYTES + B_BYTES;
   constexpr int IA = A_BYTES / 4096, IB = B_BYTES / 4096, LPS = IA + IB;   // 1 KB copies per wavefront and stage
@@ -422,15 +422,14 @@ __global__ __launch_bounds__(256, 2) void gemm_async_kernel(GemmBf16 g) {
   constexpr int OPK = (AKC ? MI : 2 * MI) + (BKC ? 2 : 4);                // LDS reads per 16-k step
   constexpr int ES = SPLIT ? 4 : 2;                                       // output element size
   constexpr int CPITCH = BN * ES + 16;                                    // LDS row pitch of the output tile
-  static_assert(BM * CPITCH <= NS * STAGE, "output tile must fit in the staging buffers");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   const int col = lane & 31, half = lane >> 5;
-  const int zb = SPLIT ? blockIdx.z / g.splitk : blockIdx.z;
-  const int kbeg = SPLIT ? (blockIdx.z % g.splitk) * g.kchunk : 0;
+  const int zb = SPLIT ? bz / g.splitk : bz;
+  const int kbeg = SPLIT ? (bz % g.splitk) * g.kchunk : 0;
   const int kend = SPLIT ? min(g.K, kbeg + g.kchunk) : g.K;
-  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+  const int m0 = by * BM, n0 = bx * BN;
   const int nseg = g.nseg > 1 ? g.nseg : 1;
   const int nk = (kend - kbeg + BK - 1) / BK;
   const int total = nseg * nk;
@@ -638,7 +637,7 @@ __global__ __launch_bounds__(256, 2) void gemm_async_kernel(GemmBf16 g) {
   unsigned char* Cb;
   long long ldc_bytes;
   if constexpr (SPLIT) {
-    Cb = reinterpret_cast<unsigned char*>(g.C0) + (long long)blockIdx.z * g.M * g.N * 4;
+    Cb = reinterpret_cast<unsigned char*>(g.C0) + (long long)bz * g.M * g.N * 4;
     ldc_bytes = (long long)g.N * 4;
   } else {
     Cb = reinterpret_cast<unsigned char*>(zsel == 0 ? g.C0 : (zsel == 1 ? g.C1 : (zsel == 2 ? g.C2 : g.C3)));
@@ -655,6 +654,31 @@ __global__ __launch_bounds__(256, 2) void gemm_async_kernel(GemmBf16 g) {
   }
 }
 
+// LDS a workgroup of the asynchronous GEMM needs: the staging ring, or the output tile if that is larger
+template <bool SPLIT, int BM, int BK, int NS>
+constexpr int gemm_async_lds() {
+  constexpr int ring = NS * (BM + 128) * BK * 2, out = BM * (128 * (SPLIT ? 4 : 2) + 16);
+  return ring > out ? ring : out;
+}
+template <bool AKC, bool BKC, bool SPLIT, int BM, int BK, int NS>
+__global__ __launch_bounds__(256, 2) void gemm_async_kernel(GemmBf16 g) {
+  gemm_async_tile<AKC, BKC, SPLIT, BM, BK, NS>(g, blockIdx.x, blockIdx.y, blockIdx.z);
+}
+// The input gradient (gx: k-contiguous operands, up to three accumulated segments) and the weight
+// gradients (gw: mn-contiguous operands, K slices, fp32 partial products) depend on the same dQ, dK,
+// dV and on nothing of each other, so they share one launch: workgroups [0, nx) take tiles of gx,
+// the rest tiles of gw.  The longer-running input-gradient tiles are dispatched first.
+template <int BMX>
+__global__ __launch_bounds__(256, 2) void gemm_bwd_pair_kernel(GemmBf16 gx, GemmBf16 gw, int nx, int gxn, int gwn, int gwm) {
+  const int id = blockIdx.x;
+  if (id < nx) {
+    gemm_async_tile<true, true, false, BMX, 64, 2>(gx, id % gxn, id / gxn, 0);
+  } else {
+    const int r = id - nx;
+    gemm_async_tile<false, false, true, 128, 64, 2>(gw, r % gwn, (r / gwn) % gwm, r / (gwn * gwm));
+  }
+}
+
 // Tile and pipeline depth of the asynchronous GEMM: 128 x 128 tiles once there are enough of them to
 // keep every compute unit busy with two workgroups; otherwise 64 x 128 tiles, three stages deep while
 // two workgroups still fit beside each other in LDS (at most 512 tiles), else two stages and three
@@ -662,7 +686,7 @@ __global__ __launch_bounds__(256, 2) void gemm_async_kernel(GemmBf16 g) {
 template <bool AKC, bool BKC, bool SPLIT, int BM, int NS>
 int launch_gemm_async_cfg(vardrop_ctx* ctx, int kid, const GemmBf16& g, int nz, hipStream_t s) {
   constexpr int BK = 64;
-  constexpr int lds = NS * (BM + 128) * BK * 2;
+  constexpr int lds = gemm_async_lds<SPLIT, BM, BK, NS>();
   static int configured_device = -1;     // raising the dynamic LDS limit is a per-device, per-function setting
   if (configured_device != ctx->device) {
     VD_HIP(ctx, hipFuncSetAttribute((const void*)gemm_async_kernel<AKC, BKC, SPLIT, BM, BK, NS>,
@@ -677,14 +701,36 @@ int launch_gemm_async_cfg(vardrop_ctx* ctx, int kid, const GemmBf16& g, int nz, 
   VD_LAUNCH_CHECK(ctx);
   return VARDROP_OK;
 }
-// weight gradients: both operands mn-contiguous, K = tokens cut into splitk slices, fp32 partial products
-int launch_gemm_async_dw(vardrop_ctx* ctx, int kid, const GemmBf16& g, int nz, hipStream_t s) {
-  if (g.M == 0 || g.N == 0) return VARDROP_OK;
-  if (g.M % 8 != 0 || g.N % 8 != 0 || g.kchunk % 64 != 0 || g.splitk < 1 ||
-      (long long)g.K * g.lda >= (1ll << 31) || (long long)g.K * g.ldb >= (1ll << 31))
-    return VARDROP_EUNSUPPORTED;
-  return launch_gemm_async_cfg<false, false, true, 64, 2>(ctx, kid, g, nz, s);
+// one launch for the input gradient gx and the sliced weight gradients gw (nzw matrices)
+template <int BMX>
+int launch_gemm_bwd_pair_cfg(vardrop_ctx* ctx, const GemmBf16& gx, const GemmBf16& gw, int nzw, hipStream_t s) {
+  constexpr int ldsx = gemm_async_lds<false, BMX, 64, 2>(), ldsw = gemm_async_lds<true, 128, 64, 2>();
+  constexpr int lds = ldsx > ldsw ? ldsx : ldsw;
+  static int configured_device = -1;
+  if (configured_device != ctx->device) {
+    VD_HIP(ctx, hipFuncSetAttribute((const void*)gemm_bwd_pair_kernel<BMX>, hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+    configured_device = ctx->device;
+  }
+  const int gxn = vd_ceil_div(gx.N, 128), gxm = vd_ceil_div(gx.M, BMX);
+  const int gwn = vd_ceil_div(gw.N, 128), gwm = vd_ceil_div(gw.M, 128);
+  const int nx = gxn * gxm, nw = gwn * gwm * nzw * gw.splitk;
+  {
+    VdTimer timer(ctx, VARDROP_K_GEMM_DW_DXS, s);
+    hipLaunchKernelGGL(gemm_bwd_pair_kernel<BMX>, dim3(nx + nw), dim3(256), lds, s, gx, gw, nx, gxn, gwn, gwm);
+  }
+  VD_LAUNCH_CHECK(ctx);
+  return VARDROP_OK;
 }
+int launch_gemm_bwd_pair(vardrop_ctx* ctx, const GemmBf16& gx, const GemmBf16& gw, int nzw, hipStream_t s) {
+  if (gx.K % 64 != 0 || gx.N % 8 != 0 || (long long)gx.M * gx.lda >= (1ll << 31) || (long long)gx.N * gx.ldb >= (1ll << 31) ||
+      gw.M % 8 != 0 || gw.N % 8 != 0 || gw.kchunk % 64 != 0 || gw.splitk < 1 ||
+      (long long)gw.K * gw.lda >= (1ll << 31) || (long long)gw.K * gw.ldb >= (1ll << 31))
+    return VARDROP_EUNSUPPORTED;
+  const long long t128 = (long long)vd_ceil_div(gx.N, 128) * vd_ceil_div(gx.M, 128);
+  if (t128 >= 1024) return launch_gemm_bwd_pair_cfg<128>(ctx, gx, gw, nzw, s);
+  return launch_gemm_bwd_pair_cfg<64>(ctx, gx, gw, nzw, s);
+}
+
 template <bool BKC>
 int launch_gemm_async(vardrop_ctx* ctx, int kid, const GemmBf16& g, int nz, hipStream_t s) {
   if (g.M == 0 || g.N == 0) return VARDROP_OK;
@@ -1088,16 +1134,23 @@ int launch_core(vardrop_ctx* ctx, int kid, F kernel2, F kernel4, const SdpaArgs&
 
 }  // namespace
 
-// Number of K slices of the weight-gradient GEMMs (K = B*n rows): enough workgroups to fill the
-// chip, slices of at least 256 rows, a multiple of the 64-row stage.
+// Number of K slices of the weight-gradient GEMMs (K = B*n rows, 128 x 128 tiles).  They share a
+// launch with the input gradient, two workgroups per compute unit: enough slices that the two
+// together fill those 512 places when the input gradient leaves room, else enough for the weight
+// gradients alone to do so; slices hold at least 256 rows and are a multiple of the 64-row stage.
 int vd_attn_bf16_splitk(int d, long long M, int* kchunk) {
-  const int tiles = vd_ceil_div(d, 128) * vd_ceil_div(d, 64) * 4;
-  int s = 768 / tiles;
+  const int tiles = vd_ceil_div(d, 128) * vd_ceil_div(d, 128) * 4;
+  const long long dxs_wgs = (long long)vd_ceil_div((int)M, 64) * vd_ceil_div(d, 128);
+  int s = vd_ceil_div(512, tiles);
+  if (dxs_wgs < 512) {
+    const int fit = (int)((512 - dxs_wgs) / tiles);
+    if (fit >= 1 && fit < s) s = fit;
+  }
   if (s > 8) s = 8;
   while (s > 1 && M / s < 256) --s;
   if (s < 1) s = 1;
-  int chunk = (int)vd_align_up((size_t)vd_ceil_div((int)M, s), 128);
-  if (chunk < 128) chunk = 128;
+  int chunk = (int)vd_align_up((size_t)vd_ceil_div((int)M, s), 64);
+  if (chunk < 64) chunk = 64;
   s = M > 0 ? vd_ceil_div((int)M, chunk) : 1;
   if (kchunk) *kchunk = chunk;
   return s;
@@ -1106,9 +1159,10 @@ size_t vd_attn_bf16_partial_offset(int B, int n, int d, int H) {
   const size_t M = (size_t)B * n;
   return vd_align_up(4 * M * d * 2 + (size_t)B * H * n * sizeof(float), 256);
 }
+// Room for the largest slice count, so that a workspace sized for n tokens also serves any smaller
+// selection (the slice count is not monotone in the token count).
 size_t vd_attn_bf16_ws_bytes(int B, int n, int d, int H) {
-  const int s = vd_attn_bf16_splitk(d, (long long)B * n, nullptr);
-  return vd_attn_bf16_partial_offset(B, n, d, H) + (s > 1 ? (size_t)4 * s * d * d * sizeof(float) : 0);
+  return vd_attn_bf16_partial_offset(B, n, d, H) + (size_t)4 * 8 * d * d * sizeof(float);
 }
 
 // saved: q, k, v, o ([M][d] bf16 each, M = B*n) then lse fp32 [B][H][n]
@@ -1170,41 +1224,41 @@ int vd_attn_bwd_bf16(vardrop_ctx* ctx, const void* dy, const void* xs, int B, in
   a.n = n; a.d = d; a.H = H; a.scale = 1.0f / sqrtf((float)kDh);
   if ((rc = launch_core(ctx, VARDROP_K_SDPA_BWD_DQ, sdpa_bwd_dq_bf16<2>, sdpa_bwd_dq_bf16<4>, a, B, s))) return rc;
   if ((rc = launch_core(ctx, VARDROP_K_SDPA_BWD_DKV, sdpa_bwd_dkv_bf16<2>, sdpa_bwd_dkv_bf16<4>, a, B, s))) return rc;
-  {  // dWq, dWk, dWv, dWo = xs^T dq, xs^T dk, xs^T dv, o^T dy: one launch, K = B*n cut into slices
-    GemmBf16 g = {};
+  {
+    // dxs = dq Wq^T + dk Wk^T + dv Wv^T
+    GemmBf16 gx = {};
+    const bf16_t* grads[3] = {dq, dk, dv};
+    for (int z = 0; z < 3; ++z) gx.set(z, grads[z], W[z], z == 0 ? dxs : nullptr, nullptr);
+    gx.lda = d; gx.ldb = d; gx.ldc = d;
+    gx.M = (int)M; gx.N = d; gx.K = d; gx.nseg = 3;
+    // dWq, dWk, dWv, dWo = xs^T dq, xs^T dk, xs^T dv, o^T dy, K = B*n cut into slices
+    GemmBf16 gw = {};
     const bf16_t* lhs[4] = {(const bf16_t*)xs, (const bf16_t*)xs, (const bf16_t*)xs, o};
     const bf16_t* rhs[4] = {dq, dk, dv, (const bf16_t*)dy};
-    for (int z = 0; z < 4; ++z) g.set(z, lhs[z], rhs[z], dW[z], nullptr);
-    g.lda = d; g.ldb = d; g.ldc = d;
-    g.M = d; g.N = d; g.K = (int)M; g.nseg = 1;
+    for (int z = 0; z < 4; ++z) gw.set(z, lhs[z], rhs[z], dW[z], nullptr);
+    gw.lda = d; gw.ldb = d; gw.ldc = d;
+    gw.M = d; gw.N = d; gw.K = (int)M; gw.nseg = 1;
     int kchunk = 0;
-    g.splitk = vd_attn_bf16_splitk(d, M, &kchunk);
-    g.kchunk = kchunk;
-    if (g.splitk > 1) {
+    gw.splitk = vd_attn_bf16_splitk(d, M, &kchunk);
+    gw.kchunk = kchunk;
+    if (gw.splitk > 1) {
       float* part = (float*)((char*)ws + vd_attn_bf16_partial_offset(B, n, d, H));
-      g.C0 = part;
-      if ((rc = launch_gemm_async_dw(ctx, VARDROP_K_GEMM_DW, g, 4, s))) return rc;
+      gw.C0 = part;
+      if ((rc = launch_gemm_bwd_pair(ctx, gx, gw, 4, s))) return rc;
       SplitkReduce r = {};
       r.part = part;
       for (int z = 0; z < 4; ++z) r.out[z] = dW[z];
       r.count = (long long)d * d;
-      r.splitk = g.splitk;
+      r.splitk = gw.splitk;
       {
         VdTimer timer(ctx, VARDROP_K_REDUCE_DW, s);
         hipLaunchKernelGGL(splitk_reduce_kernel, dim3(vd_ceil_div(d * d / 4, 256), 4), dim3(256), 0, s, r);
       }
       VD_LAUNCH_CHECK(ctx);
-    } else {
-      if ((rc = launch_gemm<false, false, float>(ctx, VARDROP_K_GEMM_DW, g, 4, s))) return rc;
+    } else {   // few tokens: one slice, written directly
+      if ((rc = launch_gemm<false, false, float>(ctx, VARDROP_K_GEMM_DW, gw, 4, s))) return rc;
+      if ((rc = launch_gemm_async<true>(ctx, VARDROP_K_GEMM_DXS, gx, 1, s))) return rc;
     }
-  }
-  {  // dxs = dq Wq^T + dk Wk^T + dv Wv^T
-    GemmBf16 g = {};
-    const bf16_t* grads[3] = {dq, dk, dv};
-    for (int z = 0; z < 3; ++z) g.set(z, grads[z], W[z], z == 0 ? dxs : nullptr, nullptr);
-    g.lda = d; g.ldb = d; g.ldc = d;
-    g.M = (int)M; g.N = d; g.K = d; g.nseg = 3;
-    if ((rc = launch_gemm_async<true>(ctx, VARDROP_K_GEMM_DXS, g, 1, s))) return rc;
   }
   if (db[0] || db[1] || db[2] || db[3]) {
     ColSumBf16 c = {};
