@@ -49,6 +49,7 @@ def algorithmic_work(w, n):
         "reduce_dw": ("hbm", 4.0 * 4 * d * d * 2),
         "gemm_dxs": (mm, 6.0 * M * d * d),
         "gemm_dw_dxs": (mm, 14.0 * M * d * d),
+        "sdpa_bwd": (mm, 10.0 * B * n * n * d),
     }
 
 
@@ -189,11 +190,13 @@ def main():
         tok = tok_dev[i % args.batches]
         events[i % 2].synchronize()                # N' of batch i (launched one step earlier)
         n_sel, G = int(pinned[i % 2][0]), int(pinned[i % 2][1])
-        xs = vd.vardrop_gather(ctx, tok, sel, n_sel)
+        count = w.B * n_sel * w.d
+        shape = (w.B, n_sel, w.d)
+        xs = vd.vardrop_gather(ctx, tok, sel, n_sel, out=xs_buf[:count].view(shape))
         done[i % 2].record(stream)
-        y, saved = vd.vardrop_attn_fwd(ctx, xs, *W_dev, w.H, saved=saved)
-        dy = dy_full[: w.B * n_sel * w.d].view(w.B, n_sel, w.d)
-        grads = vd.vardrop_attn_bwd(ctx, dy, xs, *W_dev, w.H, saved, ws=ws)
+        y, saved = vd.vardrop_attn_fwd(ctx, xs, *W_dev, w.H, saved=saved, out=y_buf[:count].view(shape))
+        dy = dy_full[:count].view(shape)
+        grads = vd.vardrop_attn_bwd(ctx, dy, xs, *W_dev, w.H, saved, ws=ws, out=(dxs_buf[:count].view(shape), *dW_buf))
         stats["n_sel"].append(n_sel)
         stats["G"].append(G)
         return grads
@@ -211,6 +214,10 @@ def main():
     code = vd.BF16 if w.dtype == "bf16" else vd.F32
     saved = torch.empty(lib.vardrop_attn_saved_bytes(w.B, w.N, w.d, w.H, code), dtype=torch.uint8, device=dev)
     ws = torch.empty(lib.vardrop_attn_workspace_bytes(w.B, w.N, w.d, w.H, code), dtype=torch.uint8, device=dev)
+
+    # outputs of a step, sized for the largest selection as well (every call writes all of what it returns)
+    xs_buf, y_buf, dxs_buf = (torch.empty(w.B * w.N * w.d, dtype=td, device=dev) for _ in range(3))
+    dW_buf = [torch.empty((w.d, w.d), dtype=torch.float32, device=dev) for _ in range(4)]
 
     if args.copy_calibration:
         src = torch.zeros(256 << 20, dtype=torch.uint8, device=dev)
@@ -234,7 +241,10 @@ def main():
         total_ms, launches = vd.vardrop_profile_read(ctx)
         if launches:
             census[name] = (kid, total_ms * 1e3 / 8)            # microseconds per step
-    dominant = max(census, key=lambda k: census[k][1])
+    # The step time is set by the attention stream; hashing and sampling of the next batch run beside it
+    # on the second stream, so the dominant kernel is the largest one on the attention stream.
+    on_critical_path = {k: v for k, v in census.items() if k not in ("hash", "sample")}
+    dominant = max(on_critical_path, key=lambda k: on_critical_path[k][1])
     vd.vardrop_profile_select(ctx, census[dominant][0])          # only this kernel is bracketed while timing
     torch.cuda.synchronize()
 

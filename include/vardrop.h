@@ -74,6 +74,7 @@ enum {
   VARDROP_K_GEMM_DXS,        /* dxs = dQ Wq^T + dK Wk^T + dV Wv^T                           */
   VARDROP_K_SCATTER,         /* adjoint of the gather                                       */
   VARDROP_K_GEMM_DW_DXS,     /* weight gradients (K slices) and dxs in one launch           */
+  VARDROP_K_SDPA_BWD,        /* dQ, dK, dV of a short selection (n <= 128) in one launch    */
   VARDROP_K_COUNT
 };
 int vardrop_profile_select(vardrop_ctx* ctx, int kernel_id);

@@ -183,10 +183,11 @@ def vardrop_sample(ctx, hsh, gs, ratio_num, ratio_den, seed, step, counts_host=N
     return gid, sel, counts
 
 
-def vardrop_gather(ctx, tokens, sel, n_sel):
-    """tokens [B, N, d], sel int32 -> [B, n_sel, d]."""
+def vardrop_gather(ctx, tokens, sel, n_sel, out=None):
+    """tokens [B, N, d], sel int32 -> [B, n_sel, d] (written into `out` when given)."""
     B, N, d = tokens.shape
-    out = torch.empty((B, n_sel, d), dtype=tokens.dtype, device=tokens.device)
+    if out is None:
+        out = torch.empty((B, n_sel, d), dtype=tokens.dtype, device=tokens.device)
     rc = ctx._lib.vardrop_gather(ctx.handle, _p(tokens), B, N, d, _dtype_code(tokens), _p(sel), n_sel, _p(out),
                                  _stream(tokens))
     ctx.check(rc, "vardrop_gather")
@@ -203,30 +204,35 @@ def vardrop_scatter(ctx, dxs, sel, n_sel, N):
     return out
 
 
-def vardrop_attn_fwd(ctx, xs, Wq, Wk, Wv, Wo, H, bq=None, bk=None, bv=None, bo=None, saved=None):
-    """xs [B, n, d] -> (y [B, n, d], saved uint8 buffer for the backward)."""
+def vardrop_attn_fwd(ctx, xs, Wq, Wk, Wv, Wo, H, bq=None, bk=None, bv=None, bo=None, saved=None, out=None):
+    """xs [B, n, d] -> (y [B, n, d], saved uint8 buffer for the backward); y is written into `out` when given."""
     B, n, d = xs.shape
     code = _dtype_code(xs)
     nbytes = ctx._lib.vardrop_attn_saved_bytes(B, n, d, H, code)
     if saved is None or saved.numel() < nbytes:
         saved = torch.empty((max(nbytes, 256),), dtype=torch.uint8, device=xs.device)
-    y = torch.empty_like(xs)
+    y = torch.empty_like(xs) if out is None else out
     rc = ctx._lib.vardrop_attn_fwd(ctx.handle, _p(xs), B, n, d, H, code, _p(Wq), _p(Wk), _p(Wv), _p(Wo),
                                    _p(bq), _p(bk), _p(bv), _p(bo), _p(y), _p(saved), None, 0, _stream(xs))
     ctx.check(rc, "vardrop_attn_fwd")
     return y, saved
 
 
-def vardrop_attn_bwd(ctx, dy, xs, Wq, Wk, Wv, Wo, H, saved, bias_grads=False, ws=None):
-    """-> (dxs, dWq, dWk, dWv, dWo) or, with bias_grads, (..., dbq, dbk, dbv, dbo); weight grads are float32."""
+def vardrop_attn_bwd(ctx, dy, xs, Wq, Wk, Wv, Wo, H, saved, bias_grads=False, ws=None, out=None):
+    """-> (dxs, dWq, dWk, dWv, dWo) or, with bias_grads, (..., dbq, dbk, dbv, dbo); weight grads are float32.
+    `out`, when given, is that tuple of preallocated tensors."""
     B, n, d = xs.shape
     code = _dtype_code(xs)
     nbytes = ctx._lib.vardrop_attn_workspace_bytes(B, n, d, H, code)
     if ws is None or ws.numel() < nbytes:
         ws = torch.empty((max(nbytes, 256),), dtype=torch.uint8, device=xs.device)
-    dxs = torch.empty_like(xs)
-    dW = [torch.empty((d, d), dtype=torch.float32, device=xs.device) for _ in range(4)]
-    db = [torch.empty((d,), dtype=torch.float32, device=xs.device) if bias_grads else None for _ in range(4)]
+    if out is not None:
+        dxs, dW = out[0], list(out[1:5])
+        db = list(out[5:9]) if bias_grads else [None] * 4
+    else:
+        dxs = torch.empty_like(xs)
+        dW = [torch.empty((d, d), dtype=torch.float32, device=xs.device) for _ in range(4)]
+        db = [torch.empty((d,), dtype=torch.float32, device=xs.device) if bias_grads else None for _ in range(4)]
     rc = ctx._lib.vardrop_attn_bwd(ctx.handle, _p(dy), _p(xs), B, n, d, H, code, _p(Wq), _p(Wk), _p(Wv), _p(Wo),
                                    _p(saved), _p(dxs), *[_p(t) for t in dW], *[_p(t) for t in db],
                                    _p(ws), ws.numel(), _stream(xs))

@@ -28,13 +28,15 @@ namespace {
 
 typedef uint16_t bf16_t;   // raw storage
 
-__device__ inline bf16_t f2bf(float f) {
-  const uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)0x7fc0;
-  return (bf16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
-}
+// fp32 -> bf16, round to nearest even (v_cvt_pk_bf16_f32)
+__device__ inline bf16_t f2bf(float f) { return __builtin_bit_cast(bf16_t, (__bf16)f); }
 __device__ inline float bf2f(bf16_t b) { return __uint_as_float((uint32_t)b << 16); }
-__device__ inline uint32_t pack2(float lo, float hi) { return (uint32_t)f2bf(lo) | ((uint32_t)f2bf(hi) << 16); }
+__device__ inline uint32_t pack2(float lo, float hi) {
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  typedef float floatx2 __attribute__((ext_vector_type(2)));
+  const floatx2 v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
 
 union Frag {
   u32x4 q;
@@ -1102,6 +1104,195 @@ __global__ __launch_bounds__(NW * 64) void sdpa_bwd_dkv_bf16(SdpaArgs a) {
   }
 }
 
+// ---- backward for short selections (n <= 128, the regime variate dropping produces): one workgroup
+// per (batch, head) holds Q, K, V, dO and O of the head in LDS (asynchronous copies, one round trip to
+// memory) and forms S and dP once for both gradients.
+//   phase 1, a wavefront owns 32 keys (lane = key):  S^T-free orientation S[query][key] = Q k^T and
+//            dP = dO v^T with the key fragments in registers; P and dS feed dV^T = dO^T P and
+//            dK^T = Q^T dS, whose left operands (contraction over queries) are transposing reads of
+//            the dO and Q tiles; dS goes to LDS as dS^T[key][query].
+//   phase 2, a wavefront owns 32 queries (lane = query): dQ^T = K^T dS^T, both operands transposing
+//            reads (contraction over keys).
+// Tiles are [token][64] with the 16-byte chunk position XORed with token % 8, as the copies write them.
+constexpr int kSmallN = 128;
+constexpr int kDsPitch = 272;                 // bytes per dS^T row: 128 queries * 2 + 16
+constexpr int kSmallTile = kSmallN * kDh * 2;  // bytes of one [128][64] tile
+constexpr int kSmallLds = 5 * kSmallTile + kSmallN * kDsPitch + 2 * kSmallN * 4;
+
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+// 16-byte chunk (k = 8*chunk ..) of a token row of a swizzled tile
+__device__ inline Frag small_row_frag(const unsigned char* tile, int row, int chunk) {
+  Frag f;
+  f.q = *reinterpret_cast<const u32x4*>(tile + row * 128 + ((chunk ^ (row & 7)) * 16));
+  return f;
+}
+// transposing read of a swizzled tile: this lane receives, for column mn0 + lane % 16 of the 16-lane
+// group's column block, the four token rows krow0 .. krow0+3 and krow0+8 .. krow0+11
+__device__ inline Frag small_tr_frag(const unsigned char* tile, int krow0, int mn0, int lane) {
+  Frag f;
+  const int mn = mn0 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+#pragma unroll
+  for (int rd = 0; rd < 2; ++rd) {
+    const int krow = krow0 + 8 * rd + ((lane & 15) >> 2);
+    const unsigned char* p = tile + krow * 128 + (((mn >> 3) ^ (krow & 7)) * 16) + ((mn >> 2) & 1) * 8;
+    const s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)p);
+    f.d[rd] = __builtin_bit_cast(u32x2, v);
+  }
+  return f;
+}
+__global__ __launch_bounds__(256) void sdpa_bwd_small_bf16(SdpaArgs a) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  unsigned char* Qs = smem;
+  unsigned char* Ks = Qs + kSmallTile;
+  unsigned char* Vs = Ks + kSmallTile;
+  unsigned char* dOs = Vs + kSmallTile;
+  unsigned char* Os = dOs + kSmallTile;
+  unsigned char* dSt = Os + kSmallTile;                                   // [key][kDsPitch]
+  float* Ls = reinterpret_cast<float*>(dSt + kSmallN * kDsPitch);
+  float* Ds = Ls + kSmallN;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int col = lane & 31, half = lane >> 5;
+  const int h = blockIdx.x, b = blockIdx.y;
+  const int n = a.n;
+  const long long ld = a.d;
+  const long long base = (long long)b * n * ld + h * kDh;
+  const long long srow = ((long long)b * a.H + h) * n;
+
+  // ---- phase 0: copies.  A wavefront-wide copy fills 8 token rows; rows past n repeat row n-1.
+  {
+    const bf16_t* src[5] = {a.q + base, a.k + base, a.v + base, a.dout + base, a.o + base};
+#pragma unroll
+    for (int t = 0; t < 5; ++t)
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int row = (u * 4 + wave) * 8 + (lane >> 3);
+        const int chunk = (lane & 7) ^ (row & 7);
+        dma16(src[t] + (long long)min(row, n - 1) * ld + chunk * 8, smem + t * kSmallTile + (u * 4 + wave) * 1024);
+      }
+    if (threadIdx.x < kSmallN) {
+      const int i = threadIdx.x;
+      Ls[i] = i < n ? a.lse[srow + i] * kLog2e : INFINITY;
+    }
+  }
+  wait_vm<0>();                         // this wavefront's copies have landed ...
+  __syncthreads();                      // ... and so have everyone else's
+  // D = rowsum(dO * O) of this wavefront's queries
+  {
+    const int qi = wave * 32 + col;
+    float D = 0.f;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      const Frag x = small_row_frag(dOs, qi, 2 * s + half), y = small_row_frag(Os, qi, 2 * s + half);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) D = fmaf(bf2f(x.h[e]), bf2f(y.h[e]), D);
+    }
+    D += __shfl_xor(D, 32, 64);
+    if (half == 0) Ds[qi] = D;
+  }
+  __syncthreads();
+
+  // ---- phase 1: lane = key
+  const float c = a.scale * kLog2e;
+  const int kj = wave * 32 + col;
+  {
+    Frag kf[4], vf[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      kf[s] = small_row_frag(Ks, kj, 2 * s + half);
+      vf[s] = small_row_frag(Vs, kj, 2 * s + half);
+    }
+    floatx16 accK[2] = {zero16(), zero16()}, accV[2] = {zero16(), zero16()};
+#pragma unroll
+    for (int qt = 0; qt < kSmallN / 32; ++qt) {
+      if (qt * 32 >= n) break;
+      floatx16 st = zero16(), dp = zero16();
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        st = mfma(small_row_frag(Qs, qt * 32 + col, 2 * s + half), kf[s], st);     // S[query][key]
+        dp = mfma(small_row_frag(dOs, qt * 32 + col, 2 * s + half), vf[s], dp);    // dP[query][key]
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int iq = qt * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+        const float p = kj < n ? exp2f(st[r] * c - Ls[iq]) : 0.f;      // Ls = +inf past the last query
+        st[r] = p;
+        dp[r] = p * (dp[r] - Ds[iq]);
+      }
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        u32x2 w;
+        w.x = pack2(dp[4 * q4], dp[4 * q4 + 1]);
+        w.y = pack2(dp[4 * q4 + 2], dp[4 * q4 + 3]);
+        *reinterpret_cast<u32x2*>(dSt + kj * kDsPitch + (qt * 32 + 8 * q4 + 4 * half) * 2) = w;
+      }
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2) {
+        // registers 8*s2 .. 8*s2+7 hold queries qt*32 + 16*s2 + 4*half + {0..3} and the same + 8
+        const Frag pf = regs_to_frag(st, s2);
+        const Frag dsf = regs_to_frag(dp, s2);
+        const int krow0 = qt * 32 + 16 * s2 + 4 * half;
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt) {
+          accV[dt] = mfma(small_tr_frag(dOs, krow0, dt * 32, lane), pf, accV[dt]);
+          accK[dt] = mfma(small_tr_frag(Qs, krow0, dt * 32, lane), dsf, accK[dt]);
+        }
+      }
+    }
+    if (kj < n) {
+      bf16_t* rk = a.dk + base + (long long)kj * ld;
+      bf16_t* rv = a.dv + base + (long long)kj * ld;
+      store_accT(rk, accK[0], 0, half, a.scale);
+      store_accT(rk, accK[1], 1, half, a.scale);
+      store_accT(rv, accV[0], 0, half, 1.f);
+      store_accT(rv, accV[1], 1, half, 1.f);
+    }
+  }
+  // query tiles that phase 1 skipped were never written: their dS^T columns are read below only for
+  // queries >= n, whose results are not stored
+  __syncthreads();
+
+  // ---- phase 2: lane = query
+  {
+    const int qi = wave * 32 + col;
+    floatx16 acc[2] = {zero16(), zero16()};
+#pragma unroll
+    for (int ks = 0; ks < kSmallN / 16; ++ks) {
+      if (ks * 16 >= n) break;
+      // right operand: dS^T[key][query], keys 16*ks + 8*half + e
+      Frag dsf;
+      {
+        const int mn = wave * 32 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+#pragma unroll
+        for (int rd = 0; rd < 2; ++rd) {
+          const int krow = 16 * ks + 8 * half + 4 * rd + ((lane & 15) >> 2);
+          const s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+              (__attribute__((address_space(3))) s16x4*)(dSt + krow * kDsPitch + mn * 2));
+          dsf.d[rd] = __builtin_bit_cast(u32x2, v);
+        }
+      }
+#pragma unroll
+      for (int dt = 0; dt < 2; ++dt) {
+        // left operand: K^T[dim][key] with the standard k order: rows 16*ks + 8*half + {0..3}, + {4..7}
+        Frag kf;
+        const int mn = dt * 32 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+#pragma unroll
+        for (int rd = 0; rd < 2; ++rd) {
+          const int krow = 16 * ks + 8 * half + 4 * rd + ((lane & 15) >> 2);
+          const unsigned char* p = Ks + krow * 128 + (((mn >> 3) ^ (krow & 7)) * 16) + ((mn >> 2) & 1) * 8;
+          const s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)p);
+          kf.d[rd] = __builtin_bit_cast(u32x2, v);
+        }
+        acc[dt] = mfma(kf, dsf, acc[dt]);
+      }
+    }
+    if (qi < n) {
+      bf16_t* row = a.dq + base + (long long)qi * ld;
+      store_accT(row, acc[0], 0, half, a.scale);
+      store_accT(row, acc[1], 1, half, a.scale);
+    }
+  }
+}
+
 // column sums of up to four bf16 [rows][d] matrices (bias gradients)
 struct ColSumBf16 {
   const bf16_t* src[4];
@@ -1222,8 +1413,21 @@ int vd_attn_bwd_bf16(vardrop_ctx* ctx, const void* dy, const void* xs, int B, in
   a.q = q; a.k = k; a.v = v; a.o = o; a.dout = dO; a.lse = const_cast<float*>(lse);
   a.dq = dq; a.dk = dk; a.dv = dv; a.Dsum = D;
   a.n = n; a.d = d; a.H = H; a.scale = 1.0f / sqrtf((float)kDh);
-  if ((rc = launch_core(ctx, VARDROP_K_SDPA_BWD_DQ, sdpa_bwd_dq_bf16<2>, sdpa_bwd_dq_bf16<4>, a, B, s))) return rc;
-  if ((rc = launch_core(ctx, VARDROP_K_SDPA_BWD_DKV, sdpa_bwd_dkv_bf16<2>, sdpa_bwd_dkv_bf16<4>, a, B, s))) return rc;
+  if (n <= kSmallN) {
+    static int configured_device = -1;
+    if (configured_device != ctx->device) {
+      VD_HIP(ctx, hipFuncSetAttribute((const void*)sdpa_bwd_small_bf16, hipFuncAttributeMaxDynamicSharedMemorySize, kSmallLds));
+      configured_device = ctx->device;
+    }
+    {
+      VdTimer timer(ctx, VARDROP_K_SDPA_BWD, s);
+      hipLaunchKernelGGL(sdpa_bwd_small_bf16, dim3(H, B), dim3(256), kSmallLds, s, a);
+    }
+    VD_LAUNCH_CHECK(ctx);
+  } else {
+    if ((rc = launch_core(ctx, VARDROP_K_SDPA_BWD_DQ, sdpa_bwd_dq_bf16<2>, sdpa_bwd_dq_bf16<4>, a, B, s))) return rc;
+    if ((rc = launch_core(ctx, VARDROP_K_SDPA_BWD_DKV, sdpa_bwd_dkv_bf16<2>, sdpa_bwd_dkv_bf16<4>, a, B, s))) return rc;
+  }
   {
     // dxs = dq Wq^T + dk Wk^T + dv Wv^T
     GemmBf16 gx = {};
