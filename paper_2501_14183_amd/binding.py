@@ -78,11 +78,12 @@ def _strerror(code):
 
 
 def _p(t):
-    return None if t is None else ctypes.c_void_p(t.data_ptr())
+    return None if t is None else t.data_ptr()
 
 
-def _stream(t):
-    return ctypes.c_void_p(torch.cuda.current_stream(t.device).cuda_stream)
+def _stream(t, stream=None):
+    """Raw hipStream_t: `stream` (an integer handle, e.g. torch.cuda.Stream.cuda_stream) or torch's current one."""
+    return torch.cuda.current_stream(t.device).cuda_stream if stream is None else stream
 
 
 def _dtype_code(t):
@@ -142,7 +143,7 @@ def vardrop_profile_read(ctx):
     return ms.value, n.value
 
 
-def vardrop_hash(ctx, x, k, f_min=1, f_max=None, want_abar=False, out=None):
+def vardrop_hash(ctx, x, k, f_min=1, f_max=None, want_abar=False, out=None, stream=None):
     """x float32 [B, N, L] -> (topk int32 [N, k], hash int64 [N] (the uint64 bits), abar or None).
 
     out: optional (topk, hash) tensors to write into instead of allocating."""
@@ -159,12 +160,12 @@ def vardrop_hash(ctx, x, k, f_min=1, f_max=None, want_abar=False, out=None):
     abar = torch.empty((N, f_max - f_min + 1), dtype=torch.float32, device=x.device) if want_abar else None
     sb, sn, st = x.stride()
     rc = ctx._lib.vardrop_hash(ctx.handle, _p(x), B, N, L, sb, sn, st, k, f_min, f_max,
-                               _p(topk), _p(hsh), _p(abar), None, 0, _stream(x))
+                               _p(topk), _p(hsh), _p(abar), None, 0, _stream(x, stream))
     ctx.check(rc, "vardrop_hash")
     return topk, hsh, abar
 
 
-def vardrop_sample(ctx, hsh, gs, ratio_num, ratio_den, seed, step, counts_host=None, out=None):
+def vardrop_sample(ctx, hsh, gs, ratio_num, ratio_den, seed, step, counts_host=None, out=None, stream=None):
     """hash int64 [N] -> (group_id int32 [N], sel int32 [N] (first N' valid), counts int32 [2] = {N', G}).
 
     counts_host: optional pinned int32 [2] CPU tensor that receives the counts asynchronously.
@@ -178,33 +179,33 @@ def vardrop_sample(ctx, hsh, gs, ratio_num, ratio_den, seed, step, counts_host=N
         sel = torch.empty((N,), dtype=torch.int32, device=hsh.device)
         counts = torch.empty((2,), dtype=torch.int32, device=hsh.device)
     rc = ctx._lib.vardrop_sample(ctx.handle, _p(hsh), N, gs, ratio_num, ratio_den, seed, step,
-                                 _p(gid), _p(sel), _p(counts), _p(counts_host), None, 0, _stream(hsh))
+                                 _p(gid), _p(sel), _p(counts), _p(counts_host), None, 0, _stream(hsh, stream))
     ctx.check(rc, "vardrop_sample")
     return gid, sel, counts
 
 
-def vardrop_gather(ctx, tokens, sel, n_sel, out=None):
+def vardrop_gather(ctx, tokens, sel, n_sel, out=None, stream=None):
     """tokens [B, N, d], sel int32 -> [B, n_sel, d] (written into `out` when given)."""
     B, N, d = tokens.shape
     if out is None:
         out = torch.empty((B, n_sel, d), dtype=tokens.dtype, device=tokens.device)
     rc = ctx._lib.vardrop_gather(ctx.handle, _p(tokens), B, N, d, _dtype_code(tokens), _p(sel), n_sel, _p(out),
-                                 _stream(tokens))
+                                 _stream(tokens, stream))
     ctx.check(rc, "vardrop_gather")
     return out
 
 
-def vardrop_scatter(ctx, dxs, sel, n_sel, N):
+def vardrop_scatter(ctx, dxs, sel, n_sel, N, stream=None):
     """dxs [B, n_sel, d] -> dtokens [B, N, d] with zeros at dropped variates."""
     B, _, d = dxs.shape
     out = torch.empty((B, N, d), dtype=dxs.dtype, device=dxs.device)
     rc = ctx._lib.vardrop_scatter(ctx.handle, _p(dxs), B, N, d, _dtype_code(dxs), _p(sel), n_sel, _p(out),
-                                  _stream(dxs))
+                                  _stream(dxs, stream))
     ctx.check(rc, "vardrop_scatter")
     return out
 
 
-def vardrop_attn_fwd(ctx, xs, Wq, Wk, Wv, Wo, H, bq=None, bk=None, bv=None, bo=None, saved=None, out=None):
+def vardrop_attn_fwd(ctx, xs, Wq, Wk, Wv, Wo, H, bq=None, bk=None, bv=None, bo=None, saved=None, out=None, stream=None):
     """xs [B, n, d] -> (y [B, n, d], saved uint8 buffer for the backward); y is written into `out` when given."""
     B, n, d = xs.shape
     code = _dtype_code(xs)
@@ -213,12 +214,12 @@ def vardrop_attn_fwd(ctx, xs, Wq, Wk, Wv, Wo, H, bq=None, bk=None, bv=None, bo=N
         saved = torch.empty((max(nbytes, 256),), dtype=torch.uint8, device=xs.device)
     y = torch.empty_like(xs) if out is None else out
     rc = ctx._lib.vardrop_attn_fwd(ctx.handle, _p(xs), B, n, d, H, code, _p(Wq), _p(Wk), _p(Wv), _p(Wo),
-                                   _p(bq), _p(bk), _p(bv), _p(bo), _p(y), _p(saved), None, 0, _stream(xs))
+                                   _p(bq), _p(bk), _p(bv), _p(bo), _p(y), _p(saved), None, 0, _stream(xs, stream))
     ctx.check(rc, "vardrop_attn_fwd")
     return y, saved
 
 
-def vardrop_attn_bwd(ctx, dy, xs, Wq, Wk, Wv, Wo, H, saved, bias_grads=False, ws=None, out=None):
+def vardrop_attn_bwd(ctx, dy, xs, Wq, Wk, Wv, Wo, H, saved, bias_grads=False, ws=None, out=None, stream=None):
     """-> (dxs, dWq, dWk, dWv, dWo) or, with bias_grads, (..., dbq, dbk, dbv, dbo); weight grads are float32.
     `out`, when given, is that tuple of preallocated tensors."""
     B, n, d = xs.shape
@@ -235,6 +236,6 @@ def vardrop_attn_bwd(ctx, dy, xs, Wq, Wk, Wv, Wo, H, saved, bias_grads=False, ws
         db = [torch.empty((d,), dtype=torch.float32, device=xs.device) if bias_grads else None for _ in range(4)]
     rc = ctx._lib.vardrop_attn_bwd(ctx.handle, _p(dy), _p(xs), B, n, d, H, code, _p(Wq), _p(Wk), _p(Wv), _p(Wo),
                                    _p(saved), _p(dxs), *[_p(t) for t in dW], *[_p(t) for t in db],
-                                   _p(ws), ws.numel(), _stream(xs))
+                                   _p(ws), ws.numel(), _stream(xs, stream))
     ctx.check(rc, "vardrop_attn_bwd")
     return (dxs, *dW, *db) if bias_grads else (dxs, *dW)

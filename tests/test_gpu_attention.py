@@ -80,11 +80,20 @@ def test_five_workloads(vd, ctx, name):
     print("%s: n=%d %s" % (name, len(sel), {k: "%.2e" % v for k, v in errs.items()}))
 
 
-@pytest.mark.parametrize("n", [1, 2, 31, 32, 33, 63, 64, 65, 127, 130, 257, 300])
+@pytest.mark.parametrize("n", [1, 2, 31, 32, 33, 63, 64, 65, 127, 128, 129, 130, 257, 300])
 def test_bf16_ragged_token_counts_with_biases(vd, ctx, n):
     xs, W, dy, b = random_case(n, 3, n, 128, "bf16", bias=True)
     want = oracle_attention(xs, W, 2, dy, tuple(b))
     got = run_gpu(vd, ctx, xs, W, 2, dy, "bf16", biases=b)
+    compare(got, want, "bf16", ("y",) + GRADS + ("dbq", "dbk", "dbv", "dbo"))
+
+
+@pytest.mark.parametrize("B,n,d,H", [(4, 150, 192, 3), (8, 100, 320, 5), (6, 90, 64, 1)])
+def test_bf16_model_widths_off_the_tile_grid(vd, ctx, B, n, d, H):
+    """d is a multiple of 64 but not of the 128-wide GEMM tiles; B*n large enough for sliced weight gradients."""
+    xs, W, dy, b = random_case(7 * d + n, B, n, d, "bf16", bias=True)
+    want = oracle_attention(xs, W, H, dy, tuple(b))
+    got = run_gpu(vd, ctx, xs, W, H, dy, "bf16", biases=b)
     compare(got, want, "bf16", ("y",) + GRADS + ("dbq", "dbk", "dbv", "dbo"))
 
 
