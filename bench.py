@@ -50,6 +50,7 @@ def algorithmic_work(w, n):
         "gemm_dxs": (mm, 6.0 * M * d * d),
         "gemm_dw_dxs": (mm, 14.0 * M * d * d),
         "sdpa_bwd": (mm, 10.0 * B * n * n * d),
+        "qkv_sdpa_fwd": (mm, 6.0 * M * d * d + 4.0 * B * n * n * d),
     }
 
 
@@ -165,25 +166,25 @@ def main():
     # The selection of a batch depends on its windows only, not on the model, so it runs LOOK batches
     # ahead of the attention and on a stream of its own (default priority): the small k-DFH and sampling
     # kernels then overlap the attention of earlier batches, and the 8-byte read-back of {N', G}
-    # that sizes the attention launch is already complete when the host needs it.  (The sampling
-    # workgroup needs a whole compute unit's LDS, so under load it can wait for one to drain; two
-    # batches of lead hide that.)  Outputs of the selection are kept in LOOK + 1 buffer sets so that
-    # none is rewritten while the attention still reads it.
-    LOOK = 2
-    NB = LOOK + 1
-    pinned = [torch.zeros(2, dtype=torch.int32).pin_memory() for _ in range(NB)]
-    events = [torch.cuda.Event() for _ in range(NB)]
+    # that sizes the attention launch is complete when the host needs it.
+    # Cross-stream events on the attention stream cost several microseconds each (a marker packet
+    # between two kernels), so the attention stream carries none per step: the outputs of the
+    # selection live in a ring of RING buffer sets, and the host never runs more than RING - LOOK - FENCE
+    # batches ahead of the attention stream (one event every FENCE steps, waited for FENCE steps
+    # later), so a set is never rewritten while a gather may still read it.
+    LOOK, FENCE, RING = 2, 8, 32
+    pinned = [torch.zeros(2, dtype=torch.int32).pin_memory() for _ in range(RING)]
+    events = [torch.cuda.Event() for _ in range(RING)]
     side = torch.cuda.Stream(device=dev)
     main_h, side_h = stream.cuda_stream, side.cuda_stream      # raw handles: the binding then skips torch's stream lookup
     sel_bufs = [(torch.empty((w.N, w.k), dtype=torch.int32, device=dev), torch.empty(w.N, dtype=torch.int64, device=dev),
                  torch.empty(w.N, dtype=torch.int32, device=dev), torch.empty(w.N, dtype=torch.int32, device=dev),
-                 torch.empty(2, dtype=torch.int32, device=dev)) for _ in range(NB)]
-    done = [torch.cuda.Event() for _ in range(NB)]     # gather of the batch that last used buffer set j
+                 torch.empty(2, dtype=torch.int32, device=dev)) for _ in range(RING)]
+    fences = {}                                         # step -> event recorded on the attention stream after it
 
     def select(i):
-        j = i % NB
+        j = i % RING
         topk, hsh, gid, sel, counts = sel_bufs[j]
-        side.wait_event(done[j])                       # the gather NB batches ago has read this `sel`
         vd.vardrop_hash(ctx, xs_dev[i % args.batches], w.k, out=(topk, hsh), stream=side_h)
         vd.vardrop_sample(ctx, hsh, 0, w.ratio[0], w.ratio[1], seed, i, counts_host=pinned[j], out=(gid, sel, counts),
                           stream=side_h)
@@ -191,7 +192,7 @@ def main():
 
     def attend(i):
         nonlocal saved, ws
-        j = i % NB
+        j = i % RING
         tok = tok_dev[i % args.batches]
         sel = sel_bufs[j][3]
         events[j].synchronize()                    # N' of batch i (launched LOOK steps earlier)
@@ -199,7 +200,6 @@ def main():
         count = w.B * n_sel * w.d
         shape = (w.B, n_sel, w.d)
         xs = vd.vardrop_gather(ctx, tok, sel, n_sel, out=xs_buf[:count].view(shape), stream=main_h)
-        done[j].record(stream)
         y, saved = vd.vardrop_attn_fwd(ctx, xs, *W_dev, w.H, saved=saved, out=y_buf[:count].view(shape), stream=main_h)
         dy = dy_full[:count].view(shape)
         grads = vd.vardrop_attn_bwd(ctx, dy, xs, *W_dev, w.H, saved, ws=ws, out=(dxs_buf[:count].view(shape), *dW_buf),
@@ -210,9 +210,18 @@ def main():
 
     def run(first, count):
         """`count` whole steps: every batch gets its selection and its attention inside this call."""
+        torch.cuda.synchronize()                   # buffer sets are reused from the start: nothing of an earlier call is left
+        fences.clear()
         for i in range(first, min(first + LOOK, first + count)):
             select(i)
         for i in range(first, first + count):
+            if (i - first) % FENCE == 0:
+                old = fences.pop(i - FENCE, None)
+                if old is not None:
+                    old.synchronize()              # the attention stream has finished step i - FENCE - 1
+                ev = torch.cuda.Event()
+                ev.record(stream)
+                fences[i] = ev
             if i + LOOK < first + count:
                 select(i + LOOK)
             attend(i)

@@ -75,6 +75,7 @@ enum {
   VARDROP_K_SCATTER,         /* adjoint of the gather                                       */
   VARDROP_K_GEMM_DW_DXS,     /* weight gradients (K slices) and dxs in one launch           */
   VARDROP_K_SDPA_BWD,        /* dQ, dK, dV of a short selection (n <= 128) in one launch    */
+  VARDROP_K_QKV_SDPA_FWD,    /* Q, K, V projection and attention of a short selection       */
   VARDROP_K_COUNT
 };
 int vardrop_profile_select(vardrop_ctx* ctx, int kernel_id);

@@ -1293,6 +1293,233 @@ __global__ __launch_bounds__(256) void sdpa_bwd_small_bf16(SdpaArgs a) {
   }
 }
 
+// ---- forward for short selections (n <= 128): one workgroup per (batch, head) computes the head's
+// Q, K and V (a 128 x 192 x d product: xs of the batch times the head's columns of Wq | Wk | Wv,
+// asynchronous copies three stages deep), leaves them in LDS, and runs the attention of the head on
+// them; Q, K, V, O and the log-sum-exp are written for the backward pass.  Compared with a projection
+// GEMM followed by an attention kernel this saves a launch and the round trip of Q, K, V through memory.
+//   projection: four wavefronts as 2 x 2, each 64 tokens x 96 columns (2 x 3 matrix-instruction tiles);
+//               xs tile [token][64 k] read as 16-byte fragments, weight tiles [64 k][64 columns]
+//               through transposing reads; product formed transposed so that a lane owns a token.
+//   attention:  a wavefront owns 32 queries (lane = query); S^T = K q^T over all keys at once, exact
+//               softmax, O^T = V^T P^T with V^T taken from the V tile by transposing reads.
+struct FusedFwdArgs {
+  const bf16_t* xs;
+  const bf16_t *Wq, *Wk, *Wv;
+  const bf16_t *bq, *bk, *bv;
+  bf16_t *q, *k, *v, *o;
+  float* lse;
+  int n, d, H;
+  float scale;
+};
+constexpr int kFusedStage = kSmallN * 64 * 2 + 3 * 64 * 64 * 2;     // xs tile + three weight tiles: 40 KB
+constexpr int kFusedStages = 3;
+constexpr int kFusedLds = kFusedStages * kFusedStage;
+
+template <int N>
+__device__ inline void wait_lds5(Frag& a, Frag& b, Frag& c, Frag& d, Frag& e) {
+  asm volatile("s_waitcnt lgkmcnt(%5)" : "+v"(a.q), "+v"(b.q), "+v"(c.q), "+v"(d.q), "+v"(e.q) : "n"(N));
+}
+
+__global__ __launch_bounds__(256) void attn_fwd_small_bf16(FusedFwdArgs a) {
+  constexpr int NS = kFusedStages, STAGE = kFusedStage, A_BYTES = kSmallN * 64 * 2, BT = 64 * 64 * 2;
+  constexpr int LPS = 10;                                       // copies per wavefront and stage: 4 of xs, 6 of weights
+  constexpr int OPK = 8;                                        // LDS reads per 16-k step: 2 + 3 * 2
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wr = wave & 1, wc = wave >> 1;
+  const int col = lane & 31, half = lane >> 5;
+  const int h = blockIdx.x, b = blockIdx.y;
+  const int n = a.n, d = a.d;
+  const long long ld = d;
+  const bf16_t* xs_b = a.xs + (long long)b * n * ld;
+  const int total = d / 64;
+
+  // ---- copy sources.  xs: copy u covers token rows 8*(4u + wave) .. +7.  Weights: copy u (0..5) belongs
+  // to matrix u / 2 and covers its k-rows 8*(4*(u % 2) + wave) .. +7 of the slice.
+  const bf16_t* srcA[4];
+  const bf16_t* srcB[6];
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const int row = (u * 4 + wave) * 8 + (lane >> 3);
+    srcA[u] = xs_b + (long long)min(row, n - 1) * ld + (((lane & 7) ^ (row & 7)) * 8);
+  }
+#pragma unroll
+  for (int u = 0; u < 6; ++u) {
+    const bf16_t* Wz = (u >> 1) == 0 ? a.Wq : ((u >> 1) == 1 ? a.Wk : a.Wv);
+    const int krow = (4 * (u & 1) + wave) * 8 + (lane >> 3);
+    srcB[u] = Wz + (long long)krow * ld + h * kDh + (((lane & 7) ^ swz_nc<64>(krow)) * 8);
+  }
+  // ---- fragment addresses relative to a stage
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
+  uint32_t addrA[2][4], addrB[3];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int ra = wr * 64 + i * 32 + col;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) addrA[i][ks] = lds0 + ra * 128 + (((2 * ks + half) ^ (ra & 7)) * 16);
+  }
+#pragma unroll
+  for (int j = 0; j < 3; ++j) {
+    const int ct = 3 * wc + j;                                   // 32-column tile of [q | k | v]
+    const int krow = 8 * half + ((lane & 15) >> 2);
+    const int mn = (ct & 1) * 32 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+    addrB[j] = lds0 + A_BYTES + (ct >> 1) * BT + krow * 128 + (((mn >> 3) ^ swz_nc<64>(krow)) * 16) + ((mn >> 2) & 1) * 8;
+  }
+  floatx16 acc[2][3];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 3; ++j) acc[i][j] = zero16();
+
+  int fk = 0;        // slice whose copies are issued next
+#define VD_ISSUE(BUF)                                                                               \
+  {                                                                                                \
+    unsigned char* sp = smem + (BUF) * STAGE + wave * 1024;                                        \
+    _Pragma("unroll") for (int u = 0; u < 4; ++u) dma16(srcA[u] + fk * 64, sp + u * 4096);         \
+    _Pragma("unroll") for (int u = 0; u < 6; ++u)                                                  \
+      dma16(srcB[u] + (long long)fk * 64 * ld, sp + A_BYTES + (u >> 1) * BT + (u & 1) * 4096);     \
+    ++fk;                                                                                          \
+  }
+#pragma unroll
+  for (int s = 0; s < NS - 1; ++s)
+    if (s < total) VD_ISSUE(s)
+  for (int t0 = 0; t0 < total; t0 += NS) {
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+      const int t = t0 + s;
+      if (t < total) {
+        if (total - 1 - t >= 1) wait_vm<LPS>(); else wait_vm<0>();
+        __builtin_amdgcn_s_barrier();
+        if (t + NS - 1 < total) VD_ISSUE((s + NS - 1) % NS)
+        const uint32_t so = s * STAGE;
+        Frag fa[2][2], fb[2][3];
+#define VD_READ(KS_, SET)                                                                          \
+  {                                                                                                \
+    _Pragma("unroll") for (int i = 0; i < 2; ++i) lds_read16(fa[SET][i].q, addrA[i][KS_] + so);    \
+    _Pragma("unroll") for (int j = 0; j < 3; ++j) {                                                \
+      lds_read8_tr<(KS_) * 2048>(fb[SET][j].d[0], addrB[j] + so);                                  \
+      lds_read8_tr<(KS_) * 2048 + 512>(fb[SET][j].d[1], addrB[j] + so);                            \
+    }                                                                                              \
+  }
+#define VD_MMA(SET, PENDING)                                                                       \
+  {                                                                                                \
+    wait_lds5<PENDING>(fa[SET][0], fa[SET][1], fb[SET][0], fb[SET][1], fb[SET][2]);                \
+    _Pragma("unroll") for (int i = 0; i < 2; ++i)                                                  \
+      _Pragma("unroll") for (int j = 0; j < 3; ++j) acc[i][j] = mfma(fb[SET][j], fa[SET][i], acc[i][j]); \
+    __builtin_amdgcn_sched_barrier(0);                                                             \
+  }
+        VD_READ(0, 0)
+        VD_READ(1, 1)
+        VD_MMA(0, OPK)
+        VD_READ(2, 0)
+        VD_MMA(1, OPK)
+        VD_READ(3, 1)
+        VD_MMA(0, OPK)
+        VD_MMA(1, 0)
+#undef VD_READ
+#undef VD_MMA
+      }
+    }
+  }
+#undef VD_ISSUE
+
+  // ---- Q, K, V tiles (bf16, with bias) into LDS: [token][64], 16-byte chunk position XORed with token % 8
+  unsigned char* Qs = smem;
+  unsigned char* Ks = Qs + kSmallTile;
+  unsigned char* Vs = Ks + kSmallTile;
+  __syncthreads();                       // every wavefront is done with the last slice
+#pragma unroll
+  for (int j = 0; j < 3; ++j) {
+    const int ct = 3 * wc + j, z = ct >> 1;
+    const bf16_t* bias = z == 0 ? a.bq : (z == 1 ? a.bk : a.bv);
+#pragma unroll
+    for (int q4 = 0; q4 < 4; ++q4) {
+      const int dim = (ct & 1) * 32 + 8 * q4 + 4 * half;
+      float bv[4] = {0.f, 0.f, 0.f, 0.f};
+      if (bias) {
+        const u32x2 b4 = *reinterpret_cast<const u32x2*>(bias + h * kDh + dim);
+        bv[0] = __uint_as_float(b4.x << 16); bv[1] = __uint_as_float(b4.x & 0xffff0000u);
+        bv[2] = __uint_as_float(b4.y << 16); bv[3] = __uint_as_float(b4.y & 0xffff0000u);
+      }
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const int row = wr * 64 + i * 32 + col;
+        u32x2 o;
+        o.x = pack2(acc[i][j][4 * q4] + bv[0], acc[i][j][4 * q4 + 1] + bv[1]);
+        o.y = pack2(acc[i][j][4 * q4 + 2] + bv[2], acc[i][j][4 * q4 + 3] + bv[3]);
+        *reinterpret_cast<u32x2*>(smem + z * kSmallTile + row * 128 + (((dim >> 3) ^ (row & 7)) * 16) + ((dim >> 2) & 1) * 8) = o;
+      }
+    }
+  }
+  __syncthreads();
+  // copy the tiles out for the backward pass: 16-byte chunks, eight per token row
+  const long long base = (long long)b * n * ld + h * kDh;
+#pragma unroll
+  for (int u = 0; u < 3 * kSmallN * 8 / 256; ++u) {
+    const int idx = u * 256 + threadIdx.x;
+    const int z = idx / (kSmallN * 8), row = (idx / 8) % kSmallN, c = idx & 7;
+    if (row < n) {
+      bf16_t* dst = z == 0 ? a.q : (z == 1 ? a.k : a.v);
+      const u32x4 v = *reinterpret_cast<const u32x4*>(smem + z * kSmallTile + row * 128 + ((c ^ (row & 7)) * 16));
+      *reinterpret_cast<u32x4*>(dst + base + (long long)row * ld + c * 8) = v;
+    }
+  }
+
+  // ---- attention: lane = query
+  const int qi = wave * 32 + col;
+  Frag qf[4];
+#pragma unroll
+  for (int s = 0; s < 4; ++s) qf[s] = small_row_frag(Qs, qi, 2 * s + half);
+  const float c = a.scale * kLog2e;
+  floatx16 st[4];
+  float m = -INFINITY;
+#pragma unroll
+  for (int kt = 0; kt < 4; ++kt) {
+    st[kt] = zero16();
+    if (kt * 32 < n) {
+#pragma unroll
+      for (int s = 0; s < 4; ++s) st[kt] = mfma(small_row_frag(Ks, kt * 32 + col, 2 * s + half), qf[s], st[kt]);
+    }
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int j = kt * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+      st[kt][r] = j < n ? st[kt][r] * c : -INFINITY;
+      m = fmaxf(m, st[kt][r]);
+    }
+  }
+  m = fmaxf(m, __shfl_xor(m, 32, 64));
+  float l = 0.f;
+#pragma unroll
+  for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      st[kt][r] = exp2f(st[kt][r] - m);
+      l += st[kt][r];
+    }
+  l += __shfl_xor(l, 32, 64);
+  floatx16 out[2] = {zero16(), zero16()};
+#pragma unroll
+  for (int kt = 0; kt < 4; ++kt) {
+    if (kt * 32 < n) {
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2) {
+        const Frag pf = regs_to_frag(st[kt], s2);
+        const int krow0 = kt * 32 + 16 * s2 + 4 * half;
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt) out[dt] = mfma(small_tr_frag(Vs, krow0, dt * 32, lane), pf, out[dt]);
+      }
+    }
+  }
+  if (qi < n) {
+    const float inv = 1.f / l;
+    bf16_t* orow = a.o + base + (long long)qi * ld;
+    store_accT(orow, out[0], 0, half, inv);
+    store_accT(orow, out[1], 1, half, inv);
+    if (half == 0) a.lse[((long long)b * a.H + h) * n + qi] = (m + log2f(l)) * 0.6931471805599453f;
+  }
+}
+
 // column sums of up to four bf16 [rows][d] matrices (bias gradients)
 struct ColSumBf16 {
   const bf16_t* src[4];
@@ -1367,18 +1594,38 @@ int vd_attn_fwd_bf16(vardrop_ctx* ctx, const void* xs, int B, int n, int d, int 
   bf16_t* v = k + M * d;
   bf16_t* o = v + M * d;
   float* lse = (float*)(o + M * d);
-  GemmBf16 g = {};
-  bf16_t* qkv[3] = {q, k, v};
-  for (int z = 0; z < 3; ++z) g.set(z, xs, W[z], qkv[z], bias[z]);
-  g.lda = d; g.ldb = d; g.ldc = d;
-  g.M = (int)M; g.N = d; g.K = d; g.nseg = 1;
-  int rc = launch_gemm_async<false>(ctx, VARDROP_K_GEMM_QKV, g, 3, s);
-  if (rc) return rc;
-  SdpaArgs a = {};
-  a.q = q; a.k = k; a.v = v; a.out = o; a.lse = lse;
-  a.n = n; a.d = d; a.H = H; a.scale = 1.0f / sqrtf((float)kDh);
-  rc = launch_core(ctx, VARDROP_K_SDPA_FWD, sdpa_fwd_bf16<2>, sdpa_fwd_bf16<4>, a, B, s);
-  if (rc) return rc;
+  int rc;
+  if (n <= kSmallN) {
+    FusedFwdArgs f = {};
+    f.xs = (const bf16_t*)xs;
+    f.Wq = (const bf16_t*)W[0]; f.Wk = (const bf16_t*)W[1]; f.Wv = (const bf16_t*)W[2];
+    f.bq = (const bf16_t*)bias[0]; f.bk = (const bf16_t*)bias[1]; f.bv = (const bf16_t*)bias[2];
+    f.q = q; f.k = k; f.v = v; f.o = o; f.lse = lse;
+    f.n = n; f.d = d; f.H = H; f.scale = 1.0f / sqrtf((float)kDh);
+    static int configured_device = -1;
+    if (configured_device != ctx->device) {
+      VD_HIP(ctx, hipFuncSetAttribute((const void*)attn_fwd_small_bf16, hipFuncAttributeMaxDynamicSharedMemorySize, kFusedLds));
+      configured_device = ctx->device;
+    }
+    {
+      VdTimer timer(ctx, VARDROP_K_QKV_SDPA_FWD, s);
+      hipLaunchKernelGGL(attn_fwd_small_bf16, dim3(H, B), dim3(256), kFusedLds, s, f);
+    }
+    VD_LAUNCH_CHECK(ctx);
+  } else {
+    GemmBf16 g = {};
+    bf16_t* qkv[3] = {q, k, v};
+    for (int z = 0; z < 3; ++z) g.set(z, xs, W[z], qkv[z], bias[z]);
+    g.lda = d; g.ldb = d; g.ldc = d;
+    g.M = (int)M; g.N = d; g.K = d; g.nseg = 1;
+    rc = launch_gemm_async<false>(ctx, VARDROP_K_GEMM_QKV, g, 3, s);
+    if (rc) return rc;
+    SdpaArgs a = {};
+    a.q = q; a.k = k; a.v = v; a.out = o; a.lse = lse;
+    a.n = n; a.d = d; a.H = H; a.scale = 1.0f / sqrtf((float)kDh);
+    rc = launch_core(ctx, VARDROP_K_SDPA_FWD, sdpa_fwd_bf16<2>, sdpa_fwd_bf16<4>, a, B, s);
+    if (rc) return rc;
+  }
   GemmBf16 go = {};
   go.set(0, o, W[3], y, bias[3]);
   go.lda = d; go.ldb = d; go.ldc = d;
