@@ -61,14 +61,10 @@ __device__ inline Frag regs_to_frag(const floatx16& p, int s2) {
   return f;
 }
 
-// ================================================================== GEMM
-// C[z] = A[z] * B[z] (+ bias[z]), or with nseg > 1 the sum over segments into C[0], or with
-// splitk > 1 an fp32 partial product per K slice (summed afterwards by splitk_reduce_kernel).
-// Workgroup tile 128 x 128 x 64, four wavefronts of 64 x 64, LDS double-buffered; global loads
-// for the next K slice are in flight while the matrix cores work on the current one.
+// ================================================================== GEMM arguments
+// Up to four batch entries (grid z) or three accumulated segments.  Named fields rather than arrays so
+// that the argument block is never indexed at run time (that would force it into private memory).
 struct GemmBf16 {
-  // up to four batch entries (grid z) or three accumulated segments; named fields rather than arrays so
-  // that the argument block is never indexed at run time (that would force it into private memory)
   const bf16_t *A0, *A1, *A2, *A3;
   const bf16_t *B0, *B1, *B2, *B3;
   void *C0, *C1, *C2, *C3;
@@ -90,246 +86,6 @@ struct GemmBf16 {
     }
   }
 };
-
-// 16-byte chunk position of (row, k-chunk) inside an LDS row of BK elements (BK / 8 chunks, no padding).
-// The XOR pattern keeps the 16-byte fragment reads of 16 consecutive rows, the 16-byte staging
-// stores, and the 4-byte transposing stores (rows 8 apart) on distinct banks.
-template <int BK>
-__device__ inline int swz(int row, int kc) {
-  return BK == 64 ? kc ^ (((row >> 1) ^ (row >> 4)) & 7) : kc ^ ((row ^ (row >> 3)) & 15);
-}
-
-__device__ inline u32x4 and4(u32x4 v, uint32_t m) { return v & m; }
-
-// One K slice (BK k) of one operand, staged in registers between global memory and LDS.
-//   KC = true : k-contiguous source P[mn][k].  Rows past the end are read from the last row (their
-//               products land in output rows or columns that are never stored); the host picks BK so
-//               that K is a multiple of it, so there is no tail along k.
-//   KC = false: mn-contiguous source P[k][mn]; a task is two k rows x eight mn, transposed on the way
-//               into LDS.  In the last, partial slice the k rows past kend are read from row kend-1 and
-//               zeroed with a mask.
-// Per-thread element offsets into the source and into LDS are computed once; a load is then one
-// 64-bit add per 16 bytes, unconditional, so the loads of a slice issue back to back.
-template <int ROWS, int NT, bool KC, int BK>
-struct Stage {
-  static constexpr int kCh = BK / 8;                 // 16-byte chunks per row
-  static constexpr int kRegs = ROWS * kCh / NT;
-  u32x4 r[kRegs];
-  int goff[kRegs];      // KC: row * ld + 8 * chunk          MC: krel * ld + mn
-  int loff[KC ? kRegs : kRegs / 2];
-  __device__ inline void init(int ld, int mn0, int MN) {
-    if constexpr (KC) {
-#pragma unroll
-      for (int u = 0; u < kRegs; ++u) {
-        const int c = threadIdx.x + u * NT;
-        const int row = c / kCh, kc = c % kCh;
-        goff[u] = min(mn0 + row, MN - 1) * ld + kc * 8;
-        loff[u] = row * BK + swz<BK>(row, kc) * 8;
-      }
-    } else {
-#pragma unroll
-      for (int u = 0; u < kRegs / 2; ++u) {
-        const int t = threadIdx.x + u * NT;
-        const int mc = t % (ROWS / 8), kp = t / (ROWS / 8);
-        const int mn = min(mn0 + mc * 8, MN - 8);
-        goff[2 * u] = (2 * kp) * ld + mn;
-        goff[2 * u + 1] = (2 * kp + 1) * ld + mn;
-        loff[u] = (mc * 8) * BK + 2 * (kp & 3);           // row and chunk swizzle are added per element
-      }
-    }
-  }
-  // quarter `part` (0..3) of the loads of a full slice: issued between the matrix instructions
-  __device__ inline void load_part(const bf16_t* P, int ld, int k0, int part) {
-    const bf16_t* base = KC ? P + k0 : P + (long long)k0 * ld;
-#pragma unroll
-    for (int u = 0; u < kRegs; ++u)
-      if (u * 4 / kRegs == part) r[u] = *reinterpret_cast<const u32x4*>(base + goff[u]);
-  }
-  // whole slice at once; the only path that handles a partial slice (k0 + BK > kend, MC only)
-  __device__ inline void load(const bf16_t* P, int ld, int k0, int kend) {
-    if constexpr (KC) {
-      const bf16_t* base = P + k0;
-#pragma unroll
-      for (int u = 0; u < kRegs; ++u) r[u] = *reinterpret_cast<const u32x4*>(base + goff[u]);
-    } else if (k0 + BK <= kend) {
-      const bf16_t* base = P + (long long)k0 * ld;
-#pragma unroll
-      for (int u = 0; u < kRegs; ++u) r[u] = *reinterpret_cast<const u32x4*>(base + goff[u]);
-    } else {
-#pragma unroll
-      for (int u = 0; u < kRegs / 2; ++u) {
-        const int t = threadIdx.x + u * NT;
-        const int kp = t / (ROWS / 8);
-#pragma unroll
-        for (int e = 0; e < 2; ++e) {
-          const int k = k0 + 2 * kp + e;
-          const int back = max(k - (kend - 1), 0);         // rows to step back to stay inside the slice
-          const uint32_t mask = k < kend ? 0xffffffffu : 0u;
-          r[2 * u + e] = and4(*reinterpret_cast<const u32x4*>(P + (long long)(k0 - back) * ld + goff[2 * u + e]), mask);
-        }
-      }
-    }
-  }
-  __device__ inline void store(bf16_t* S) const {
-    if constexpr (KC) {
-#pragma unroll
-      for (int u = 0; u < kRegs; ++u) *reinterpret_cast<u32x4*>(S + loff[u]) = r[u];
-    } else {
-#pragma unroll
-      for (int u = 0; u < kRegs / 2; ++u) {
-        const int t = threadIdx.x + u * NT;
-        const int mc = t % (ROWS / 8), kp = t / (ROWS / 8);
-        Frag a, b;
-        a.q = r[2 * u];
-        b.q = r[2 * u + 1];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          const int row = mc * 8 + j;
-          *reinterpret_cast<uint32_t*>(S + loff[u] + j * BK + swz<BK>(row, kp >> 2) * 8) =
-              (uint32_t)a.h[j] | ((uint32_t)b.h[j] << 16);
-        }
-      }
-    }
-  }
-};
-
-// Tile (32*MI*WR) x 128 computed by WR x 2 wavefronts of (32*MI) x 64 each, K slices of BK:
-//   MI = 2, WR = 2, BK = 64 : 128 x 128, for problems with enough tiles to fill the chip;
-//   MI = 1, WR = 2, BK = 128:  64 x 128 for few tiles: four wavefronts so that a lone workgroup still
-//                              uses all four SIMDs, and long slices because with one workgroup per
-//                              compute unit the time per slice is set by memory latency, not by work.
-template <bool AKC, bool BKC, typename OutT, int MI, int WR, int BK>
-__global__ __launch_bounds__(128 * WR, 1) void gemm_bf16_kernel(GemmBf16 g) {
-  constexpr int BM = 32 * MI * WR, BN = 128, NT = 128 * WR;
-  constexpr int KS = BK / 16;                        // matrix-instruction steps per slice
-  __shared__ __attribute__((aligned(16))) bf16_t As[2 * BM * BK];
-  __shared__ __attribute__((aligned(16))) bf16_t Bs[2 * BN * BK];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
-  const int col = lane & 31, half = lane >> 5;
-  const int zb = g.splitk > 1 ? blockIdx.z / g.splitk : blockIdx.z;
-  const int sk = g.splitk > 1 ? blockIdx.z % g.splitk : 0;
-  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
-  const int kbeg = g.splitk > 1 ? sk * g.kchunk : 0;
-  const int kend = g.splitk > 1 ? min(g.K, kbeg + g.kchunk) : g.K;
-  floatx16 acc[MI][2];
-#pragma unroll
-  for (int i = 0; i < MI; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j) acc[i][j] = zero16();
-
-  const int nseg = g.nseg > 1 ? g.nseg : 1;
-  const int nk = (kend - kbeg + BK - 1) / BK;
-  const int total = nseg * nk;
-  // operand pointers of the (up to three) segments, or of this batch entry
-  const int zsel = g.nseg > 1 ? 0 : zb;
-  const bf16_t* A1 = g.A1; const bf16_t* B1 = g.B1;
-  const bf16_t* A2 = g.A2; const bf16_t* B2 = g.B2;
-  const bf16_t* A0 = zsel == 0 ? g.A0 : (zsel == 1 ? A1 : (zsel == 2 ? A2 : g.A3));
-  const bf16_t* B0 = zsel == 0 ? g.B0 : (zsel == 1 ? B1 : (zsel == 2 ? B2 : g.B3));
-  const bf16_t* Ap = A0;
-  const bf16_t* Bp = B0;
-  int fseg = 0, fk = kbeg;            // position of the next fetch
-  Stage<BM, NT, AKC, BK> sa;
-  Stage<BN, NT, BKC, BK> sb;
-  sa.init(g.lda, m0, g.M);
-  sb.init(g.ldb, n0, g.N);
-  // LDS offsets of this lane's fragments; the k-chunk 2*ks + half is XORed with the row's pattern
-  int offA[MI], offB[2], swA[MI], swB[2];
-#pragma unroll
-  for (int t = 0; t < MI; ++t) {
-    const int ra_ = wm * 32 * MI + t * 32 + col;
-    offA[t] = ra_ * BK; swA[t] = swz<BK>(ra_, 0);
-  }
-#pragma unroll
-  for (int t = 0; t < 2; ++t) {
-    const int rb_ = wn * 64 + t * 32 + col;
-    offB[t] = rb_ * BK; swB[t] = swz<BK>(rb_, 0);
-  }
-  // the host never launches with an empty K range
-  sa.load(Ap, g.lda, fk, kend);
-  sb.load(Bp, g.ldb, fk, kend);
-  sa.store(As);
-  sb.store(Bs);
-  __syncthreads();
-  for (int it = 0; it < total; ++it) {
-    const int cur = it & 1;
-    const bf16_t* Ab = As + cur * BM * BK;
-    const bf16_t* Bb = Bs + cur * BN * BK;
-    // position of the slice after this one (branch-free; past the end it re-reads a valid slice,
-    // which is dropped, so that no load sits inside control flow)
-    const bool wrap = fk + BK >= kend;
-    fk = wrap ? kbeg : fk + BK;
-    fseg = min(fseg + (wrap ? 1 : 0), nseg - 1);
-    Ap = fseg == 0 ? A0 : (fseg == 1 ? A1 : A2);
-    Bp = fseg == 0 ? B0 : (fseg == 1 ? B1 : B2);
-    const bool full = fk + BK <= kend;         // partial slices (weight gradients only) load in one go
-    bf16x8 fa[2][MI], fb[2][2];
-#pragma unroll
-    for (int t = 0; t < MI; ++t) fa[0][t] = *reinterpret_cast<const bf16x8*>(Ab + offA[t] + (half ^ swA[t]) * 8);
-#pragma unroll
-    for (int t = 0; t < 2; ++t) fb[0][t] = *reinterpret_cast<const bf16x8*>(Bb + offB[t] + (half ^ swB[t]) * 8);
-    if (!full) {
-      sa.load(Ap, g.lda, fk, kend);
-      sb.load(Bp, g.ldb, fk, kend);
-    }
-    // KS steps of 16 k.  A step issues its share of the next slice's global loads and the LDS reads of
-    // the following step, then its matrix instructions; the scheduling barriers pin that order so
-    // that memory traffic sits in the shadow of the matrix cores.
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      __builtin_amdgcn_sched_barrier(0);
-      if (full && ks % (KS / 4) == 0) {
-        sa.load_part(Ap, g.lda, fk, ks / (KS / 4));
-        sb.load_part(Bp, g.ldb, fk, ks / (KS / 4));
-      }
-      if (ks + 1 < KS) {
-#pragma unroll
-        for (int t = 0; t < MI; ++t)
-          fa[(ks + 1) & 1][t] = *reinterpret_cast<const bf16x8*>(Ab + offA[t] + (((ks + 1) * 2 + half) ^ swA[t]) * 8);
-#pragma unroll
-        for (int t = 0; t < 2; ++t)
-          fb[(ks + 1) & 1][t] = *reinterpret_cast<const bf16x8*>(Bb + offB[t] + (((ks + 1) * 2 + half) ^ swB[t]) * 8);
-      }
-#pragma unroll
-      for (int i = 0; i < MI; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][i], fb[ks & 1][j], acc[i][j], 0, 0, 0);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    if (it + 1 < total) {
-      sa.store(As + (cur ^ 1) * BM * BK);
-      sb.store(Bs + (cur ^ 1) * BN * BK);
-    }
-    __syncthreads();
-  }
-
-  const bf16_t* bias_z = zsel == 0 ? g.bias0 : (zsel == 1 ? g.bias1 : (zsel == 2 ? g.bias2 : g.bias3));
-  void* C_z = zsel == 0 ? g.C0 : (zsel == 1 ? g.C1 : (zsel == 2 ? g.C2 : g.C3));
-  const bf16_t* bias = g.splitk > 1 ? nullptr : bias_z;
-#pragma unroll
-  for (int i = 0; i < MI; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const int n = n0 + wn * 64 + j * 32 + col;
-      const float bv = (bias && n < g.N) ? bf2f(bias[n]) : 0.f;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int m = m0 + wm * 32 * MI + i * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-        if (m < g.M && n < g.N) {
-          const float val = acc[i][j][r] + bv;
-          if (g.splitk > 1) {
-            reinterpret_cast<float*>(g.C0)[((long long)blockIdx.z * g.M + m) * g.N + n] = val;
-          } else if (sizeof(OutT) == 2) {
-            reinterpret_cast<bf16_t*>(C_z)[(long long)m * g.ldc + n] = f2bf(val);
-          } else {
-            reinterpret_cast<float*>(C_z)[(long long)m * g.ldc + n] = val;
-          }
-        }
-      }
-    }
-}
 
 // out[z][i] = sum_s part[(z * splitk + s)][i], slices added in ascending order
 struct SplitkReduce {
@@ -639,8 +395,13 @@ __device__ __forceinline__ void gemm_async_tile(const GemmBf16& g, const int bx,
   unsigned char* Cb;
   long long ldc_bytes;
   if constexpr (SPLIT) {
-    Cb = reinterpret_cast<unsigned char*>(g.C0) + (long long)bz * g.M * g.N * 4;
-    ldc_bytes = (long long)g.N * 4;
+    if (g.splitk > 1) {      // partial product of slice bz % splitk of matrix bz / splitk
+      Cb = reinterpret_cast<unsigned char*>(g.C0) + (long long)bz * g.M * g.N * 4;
+      ldc_bytes = (long long)g.N * 4;
+    } else {                 // a single slice is the result itself
+      Cb = reinterpret_cast<unsigned char*>(zsel == 0 ? g.C0 : (zsel == 1 ? g.C1 : (zsel == 2 ? g.C2 : g.C3)));
+      ldc_bytes = (long long)g.ldc * 4;
+    }
   } else {
     Cb = reinterpret_cast<unsigned char*>(zsel == 0 ? g.C0 : (zsel == 1 ? g.C1 : (zsel == 2 ? g.C2 : g.C3)));
     ldc_bytes = (long long)g.ldc * 2;
@@ -743,33 +504,6 @@ int launch_gemm_async(vardrop_ctx* ctx, int kid, const GemmBf16& g, int nz, hipS
   if (t128 >= 1024) return launch_gemm_async_cfg<true, BKC, false, 128, 2>(ctx, kid, g, nz, s);
   if (t64 <= 512) return launch_gemm_async_cfg<true, BKC, false, 64, 3>(ctx, kid, g, nz, s);
   return launch_gemm_async_cfg<true, BKC, false, 64, 2>(ctx, kid, g, nz, s);
-}
-
-// 128 x 128 tiles when they still give every compute unit several workgroups to overlap, otherwise
-// 64 x 128 tiles with long K slices so that small problems spread over the chip.  `kc_operand` tells
-// whether a k-contiguous operand is present (then K must be a multiple of the slice length).
-template <bool AKC, bool BKC, typename OutT>
-int launch_gemm(vardrop_ctx* ctx, int kid, const GemmBf16& g, int nz, hipStream_t s) {
-  if (g.M == 0 || g.N == 0) return VARDROP_OK;
-  const int sk = g.splitk > 1 ? g.splitk : 1;
-  const long long big = (long long)vd_ceil_div(g.N, 128) * vd_ceil_div(g.M, 128) * nz * sk;
-  const long long small = (long long)vd_ceil_div(g.N, 128) * vd_ceil_div(g.M, 64) * nz * sk;
-  const bool long_ok = (!(AKC || BKC) || g.K % 128 == 0) && (g.splitk <= 1 || g.kchunk % 128 == 0);
-  {
-    VdTimer timer(ctx, kid, s);
-    if (big >= 1024) {
-      dim3 grid(vd_ceil_div(g.N, 128), vd_ceil_div(g.M, 128), nz * sk);
-      hipLaunchKernelGGL((gemm_bf16_kernel<AKC, BKC, OutT, 2, 2, 64>), grid, dim3(256), 0, s, g);
-    } else if (long_ok && small <= 320) {   // at most about one workgroup per compute unit
-      dim3 grid(vd_ceil_div(g.N, 128), vd_ceil_div(g.M, 64), nz * sk);
-      hipLaunchKernelGGL((gemm_bf16_kernel<AKC, BKC, OutT, 1, 2, 128>), grid, dim3(256), 0, s, g);
-    } else {
-      dim3 grid(vd_ceil_div(g.N, 128), vd_ceil_div(g.M, 64), nz * sk);
-      hipLaunchKernelGGL((gemm_bf16_kernel<AKC, BKC, OutT, 1, 2, 64>), grid, dim3(256), 0, s, g);
-    }
-  }
-  VD_LAUNCH_CHECK(ctx);
-  return VARDROP_OK;
 }
 
 // ================================================================== attention core (d_k = 64)
@@ -1389,7 +1123,7 @@ __global__ __launch_bounds__(256) void attn_fwd_small_bf16(FusedFwdArgs a) {
     for (int s = 0; s < NS; ++s) {
       const int t = t0 + s;
       if (t < total) {
-        if (total - 1 - t >= 1) wait_vm<LPS>(); else wait_vm<0>();
+        if (NS >= 3 && total - 1 - t >= 1) wait_vm<LPS>(); else wait_vm<0>();
         __builtin_amdgcn_s_barrier();
         if (t + NS - 1 < total) VD_ISSUE((s + NS - 1) % NS)
         const uint32_t so = s * STAGE;
@@ -1707,7 +1441,10 @@ int vd_attn_bwd_bf16(vardrop_ctx* ctx, const void* dy, const void* xs, int B, in
       }
       VD_LAUNCH_CHECK(ctx);
     } else {   // few tokens: one slice, written directly
-      if ((rc = launch_gemm<false, false, float>(ctx, VARDROP_K_GEMM_DW, gw, 4, s))) return rc;
+      if (gw.M % 8 != 0 || (long long)gw.K * gw.lda >= (1ll << 31)) return VARDROP_EUNSUPPORTED;
+      gw.splitk = 1;
+      gw.kchunk = (int)vd_align_up((size_t)gw.K, 64);
+      if ((rc = launch_gemm_async_cfg<false, false, true, 64, 2>(ctx, VARDROP_K_GEMM_DW, gw, 4, s))) return rc;
       if ((rc = launch_gemm_async<true>(ctx, VARDROP_K_GEMM_DXS, gx, 1, s))) return rc;
     }
   }
