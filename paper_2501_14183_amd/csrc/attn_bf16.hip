@@ -423,9 +423,19 @@ constexpr int gemm_async_lds() {
   constexpr int ring = NS * (BM + 128) * BK * 2, out = BM * (128 * (SPLIT ? 4 : 2) + 16);
   return ring > out ? ring : out;
 }
+// Workgroups are handed to the eight accelerator dies (XCDs) in turn, and every die has an L2 of its
+// own.  These helpers turn a workgroup's linear id into its place in an order in which each die works
+// through ONE contiguous range of the tiles, so that tiles sharing an operand meet in the same L2
+// instead of each die fetching its own copy from memory.
+__device__ inline int xcd_range_start(int xcd, int total) { return xcd * (total >> 3) + min(xcd, total & 7); }
+__device__ inline int xcd_contiguous(int id, int total) { return xcd_range_start(id & 7, total) + (id >> 3); }
+
 template <bool AKC, bool BKC, bool SPLIT, int BM, int BK, int NS>
 __global__ __launch_bounds__(256, 2) void gemm_async_kernel(GemmBf16 g) {
-  gemm_async_tile<AKC, BKC, SPLIT, BM, BK, NS>(g, blockIdx.x, blockIdx.y, blockIdx.z);
+  // tiles in the order n fastest, then m, then batch entry: a die's range shares its rows of A
+  const int gx = gridDim.x, gy = gridDim.y;
+  const int t = xcd_contiguous(blockIdx.x + gx * (blockIdx.y + gy * blockIdx.z), gx * gy * gridDim.z);
+  gemm_async_tile<AKC, BKC, SPLIT, BM, BK, NS>(g, t % gx, (t / gx) % gy, t / (gx * gy));
 }
 // The input gradient (gx: k-contiguous operands, up to three accumulated segments) and the weight
 // gradients (gw: mn-contiguous operands, K slices, fp32 partial products) depend on the same dQ, dK,
@@ -433,12 +443,19 @@ __global__ __launch_bounds__(256, 2) void gemm_async_kernel(GemmBf16 g) {
 // the rest tiles of gw.  The longer-running input-gradient tiles are dispatched first.
 template <int BMX>
 __global__ __launch_bounds__(256, 2) void gemm_bwd_pair_kernel(GemmBf16 gx, GemmBf16 gw, int nx, int gxn, int gwn, int gwm) {
-  const int id = blockIdx.x;
-  if (id < nx) {
-    gemm_async_tile<true, true, false, BMX, 64, 2>(gx, id % gxn, id / gxn, 0);
+  // Each die takes a contiguous range of the input-gradient tiles (n fastest: a range shares its rows
+  // of dQ, dK, dV) and a contiguous range of the weight-gradient tiles (n, then m, then K slice, then
+  // matrix: a range shares its K slice of both operands); its input-gradient tiles come first.
+  const int nw = (int)gridDim.x - nx;
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int cntx = (nx >> 3) + (xcd < (nx & 7) ? 1 : 0);
+  const int startx = xcd_range_start(xcd, nx);
+  if (slot < cntx) {
+    const int t = startx + slot;
+    gemm_async_tile<true, true, false, BMX, 64, 2>(gx, t % gxn, t / gxn, 0);
   } else {
-    const int r = id - nx;
-    gemm_async_tile<false, false, true, 128, 64, 2>(gw, r % gwn, (r / gwn) % gwm, r / (gwn * gwm));
+    const int t = xcd_range_start(xcd, nx + nw) - startx + (slot - cntx);
+    gemm_async_tile<false, false, true, 128, 64, 2>(gw, t % gwn, (t / gwn) % gwm, t / (gwn * gwm));
   }
 }
 
@@ -1063,7 +1080,9 @@ __global__ __launch_bounds__(256) void attn_fwd_small_bf16(FusedFwdArgs a) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wr = wave & 1, wc = wave >> 1;
   const int col = lane & 31, half = lane >> 5;
-  const int h = blockIdx.x, b = blockIdx.y;
+  // heads fastest: a die's contiguous range covers whole batches, whose tokens it then fetches once
+  const int tix = xcd_contiguous(blockIdx.x + gridDim.x * blockIdx.y, gridDim.x * gridDim.y);
+  const int h = tix % a.H, b = tix / a.H;
   const int n = a.n, d = a.d;
   const long long ld = d;
   const bf16_t* xs_b = a.xs + (long long)b * n * ld;
