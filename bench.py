@@ -121,12 +121,23 @@ def cpu_baseline(w, x_np, tok_np, W_np, seed):
             break
         nb = min(w.B, nb * 4)
     step_s = (t1 - t0) + (t2 - t1) + per_window * w.B
-    return {
-        "value": 1.0 / step_s, "unit": "steps/s", "cores": cores, "kind": "oracle",
-        "sample": "one batch of the same workload: k-DFH and sampling on all %d windows (%.3f s + %.3f s), "
-                  "gather + attention fwd/bwd timed on %d of %d windows and scaled linearly (%.3f s per window), N'=%d"
-                  % (w.B, t1 - t0, t2 - t1, nb, w.B, per_window, len(sel)),
-    }
+    note = ("one batch of the same workload: k-DFH and sampling on all %d windows (%.3f s + %.3f s), "
+            "gather + attention fwd/bwd timed on %d of %d windows and scaled linearly (%.3f s per window), N'=%d"
+            % (w.B, t1 - t0, t2 - t1, nb, w.B, per_window, len(sel)))
+    if nb >= w.B and step_s < 5.0:
+        # a whole step is cheap enough: repeat whole steps (new selection each) for about ten seconds
+        steps, t_start = 0, time.perf_counter()
+        while time.perf_counter() - t_start < 10.0:
+            steps += 1
+            topk, hsh, _ = o_kdfh.kdfh(x_np, w.k)
+            gid, sel, G = o_samp.stratified_sample(hsh, 0, w.ratio[0], w.ratio[1], seed, steps)
+            xs = o_attn.gather(tok_np, sel)
+            y, cache = o_attn.mha_forward(xs, *W_np, w.H)
+            o_attn.mha_backward(wl.make_upstream(w, len(sel)), cache)
+        step_s = (time.perf_counter() - t_start) / steps
+        note = "%d whole steps of the same workload (all %d windows, a new selection each) in %.1f s" % (
+            steps, w.B, step_s * steps)
+    return {"value": 1.0 / step_s, "unit": "steps/s", "cores": cores, "kind": "oracle", "sample": note}
 
 
 def main():

@@ -166,7 +166,10 @@ int vardrop_scatter(vardrop_ctx* ctx, const void* dxs, int B, int N, int d, int 
  * fp32 softmax, and requires d_k == 64 and d % 64 == 0; VARDROP_F32 is plain fp32 and
  * requires d_k in {16, 32, 64, 128}.  n == 0 is a no-op (weight gradients zero-filled).
  * The backward recomputes the attention probabilities from Q, K and the saved
- * log-sum-exp; it does not store them.
+ * log-sum-exp; it does not store them.  VARDROP_BF16 also requires B*n*d < 2^31
+ * (EUNSUPPORTED otherwise).  Sizes returned for n tokens also serve any call with fewer
+ * tokens (same B, d, H), so buffers can be sized once for the largest selection.
+ * Calls that share a context must not overlap in time on different streams.
  */
 size_t vardrop_attn_saved_bytes(int B, int n, int d, int H, int dtype);
 size_t vardrop_attn_workspace_bytes(int B, int n, int d, int H, int dtype);
