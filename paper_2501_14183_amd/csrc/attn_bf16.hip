@@ -38,6 +38,10 @@ __device__ inline uint32_t pack2(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
+// 2^x on the transcendental unit (v_exp_f32, 1 ulp): arguments here are <= 0 or -inf, results below the
+// normal range may flush to zero
+__device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
 union Frag {
   u32x4 q;
   u32x2 d[2];
@@ -664,13 +668,13 @@ __global__ __launch_bounds__(NW * 64) void sdpa_fwd_bf16(SdpaArgs a) {
       }
     mt = fmaxf(mt, __shfl_xor(mt, 32, 64));
     const float mn = fmaxf(m, mt);
-    const float alpha = exp2f(m - mn);
+    const float alpha = fast_exp2(m - mn);
     float rs = 0.f;
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        st[kt][r] = exp2f(st[kt][r] - mn);
+        st[kt][r] = fast_exp2(st[kt][r] - mn);
         rs += st[kt][r];
       }
     l = l * alpha + rs;
@@ -752,7 +756,7 @@ __global__ __launch_bounds__(NW * 64) void sdpa_bwd_dq_bf16(SdpaArgs a) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int j = j0 + kt * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-        const float p = j < n ? exp2f(st[r] * c - lse2) : 0.f;
+        const float p = j < n ? fast_exp2(st[r] * c - lse2) : 0.f;
         st[r] = p * (dp[r] - D);
       }
 #pragma unroll
@@ -829,7 +833,7 @@ __global__ __launch_bounds__(NW * 64) void sdpa_bwd_dkv_bf16(SdpaArgs a) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int iq = qt * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-        const float p = exp2f(st[r] * c - Ls[iq]);
+        const float p = fast_exp2(st[r] * c - Ls[iq]);
         st[r] = p;
         dp[r] = p * (dp[r] - Ds[iq]);
       }
@@ -891,17 +895,23 @@ __device__ inline Frag small_tr_frag(const unsigned char* tile, int krow0, int m
   }
   return f;
 }
-__global__ __launch_bounds__(256) void sdpa_bwd_small_bf16(SdpaArgs a) {
+__global__ __launch_bounds__(512) void sdpa_bwd_small_bf16(SdpaArgs a) {
+  // Eight wavefronts, two per SIMD so that one's LDS and conversion work hides behind the other's matrix
+  // instructions.  Wavefront w works on token block w % 4; in phase 1 the two wavefronts of a key block
+  // split the query tiles between them (their partial dK, dV meet in LDS), in phase 2 the two
+  // wavefronts of a query block take one 32-wide half of the head dimension each.
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  unsigned char* Qs = smem;
-  unsigned char* Ks = Qs + kSmallTile;
-  unsigned char* Vs = Ks + kSmallTile;
+  unsigned char* Ks = smem;
+  unsigned char* Qs = Ks + kSmallTile;
+  unsigned char* Vs = Qs + kSmallTile;
   unsigned char* dOs = Vs + kSmallTile;
   unsigned char* Os = dOs + kSmallTile;
   unsigned char* dSt = Os + kSmallTile;                                   // [key][kDsPitch]
   float* Ls = reinterpret_cast<float*>(dSt + kSmallN * kDsPitch);
   float* Ds = Ls + kSmallN;
+  float* scratch = reinterpret_cast<float*>(Qs);                          // Q, V, dO, O tiles: free after phase 1
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int blk = wave & 3, part = wave >> 2;
   const int col = lane & 31, half = lane >> 5;
   const int h = blockIdx.x, b = blockIdx.y;
   const int n = a.n;
@@ -911,14 +921,14 @@ __global__ __launch_bounds__(256) void sdpa_bwd_small_bf16(SdpaArgs a) {
 
   // ---- phase 0: copies.  A wavefront-wide copy fills 8 token rows; rows past n repeat row n-1.
   {
-    const bf16_t* src[5] = {a.q + base, a.k + base, a.v + base, a.dout + base, a.o + base};
+    const bf16_t* src[5] = {a.k + base, a.q + base, a.v + base, a.dout + base, a.o + base};
 #pragma unroll
     for (int t = 0; t < 5; ++t)
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const int row = (u * 4 + wave) * 8 + (lane >> 3);
+      for (int u = 0; u < 2; ++u) {
+        const int row = (u * 8 + wave) * 8 + (lane >> 3);
         const int chunk = (lane & 7) ^ (row & 7);
-        dma16(src[t] + (long long)min(row, n - 1) * ld + chunk * 8, smem + t * kSmallTile + (u * 4 + wave) * 1024);
+        dma16(src[t] + (long long)min(row, n - 1) * ld + chunk * 8, smem + t * kSmallTile + (u * 8 + wave) * 1024);
       }
     if (threadIdx.x < kSmallN) {
       const int i = threadIdx.x;
@@ -927,9 +937,9 @@ __global__ __launch_bounds__(256) void sdpa_bwd_small_bf16(SdpaArgs a) {
   }
   wait_vm<0>();                         // this wavefront's copies have landed ...
   __syncthreads();                      // ... and so have everyone else's
-  // D = rowsum(dO * O) of this wavefront's queries
-  {
-    const int qi = wave * 32 + col;
+  // D = rowsum(dO * O), one query per lane pair
+  if (part == 0) {
+    const int qi = blk * 32 + col;
     float D = 0.f;
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
@@ -942,9 +952,10 @@ __global__ __launch_bounds__(256) void sdpa_bwd_small_bf16(SdpaArgs a) {
   }
   __syncthreads();
 
-  // ---- phase 1: lane = key
+  // ---- phase 1: lane = key; this wavefront's query tiles are 2*part and 2*part + 1
   const float c = a.scale * kLog2e;
-  const int kj = wave * 32 + col;
+  const int kj = blk * 32 + col;
+  floatx16 accK[2] = {zero16(), zero16()}, accV[2] = {zero16(), zero16()};
   {
     Frag kf[4], vf[4];
 #pragma unroll
@@ -952,9 +963,9 @@ __global__ __launch_bounds__(256) void sdpa_bwd_small_bf16(SdpaArgs a) {
       kf[s] = small_row_frag(Ks, kj, 2 * s + half);
       vf[s] = small_row_frag(Vs, kj, 2 * s + half);
     }
-    floatx16 accK[2] = {zero16(), zero16()}, accV[2] = {zero16(), zero16()};
 #pragma unroll
-    for (int qt = 0; qt < kSmallN / 32; ++qt) {
+    for (int q2 = 0; q2 < 2; ++q2) {
+      const int qt = 2 * part + q2;
       if (qt * 32 >= n) break;
       floatx16 st = zero16(), dp = zero16();
 #pragma unroll
@@ -965,7 +976,7 @@ __global__ __launch_bounds__(256) void sdpa_bwd_small_bf16(SdpaArgs a) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int iq = qt * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-        const float p = kj < n ? exp2f(st[r] * c - Ls[iq]) : 0.f;      // Ls = +inf past the last query
+        const float p = kj < n ? fast_exp2(st[r] * c - Ls[iq]) : 0.f;      // Ls = +inf past the last query
         st[r] = p;
         dp[r] = p * (dp[r] - Ds[iq]);
       }
@@ -989,6 +1000,30 @@ __global__ __launch_bounds__(256) void sdpa_bwd_small_bf16(SdpaArgs a) {
         }
       }
     }
+  }
+  // query tiles that phase 1 skipped were never written: their dS^T columns are read below only for
+  // queries >= n, whose results are not stored
+  __syncthreads();                      // dS^T is complete; nobody reads the Q, V, dO, O tiles any more
+  if (part == 1) {                      // partial dK^T, dV^T of the upper query tiles: scratch[blk][register][lane]
+    float* sp = scratch + blk * (64 * 64) + lane;
+#pragma unroll
+    for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        sp[(dt * 16 + r) * 64] = accK[dt][r];
+        sp[(32 + dt * 16 + r) * 64] = accV[dt][r];
+      }
+  }
+  __syncthreads();
+  if (part == 0) {
+    const float* sp = scratch + blk * (64 * 64) + lane;
+#pragma unroll
+    for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        accK[dt][r] += sp[(dt * 16 + r) * 64];
+        accV[dt][r] += sp[(32 + dt * 16 + r) * 64];
+      }
     if (kj < n) {
       bf16_t* rk = a.dk + base + (long long)kj * ld;
       bf16_t* rv = a.dv + base + (long long)kj * ld;
@@ -998,21 +1033,19 @@ __global__ __launch_bounds__(256) void sdpa_bwd_small_bf16(SdpaArgs a) {
       store_accT(rv, accV[1], 1, half, 1.f);
     }
   }
-  // query tiles that phase 1 skipped were never written: their dS^T columns are read below only for
-  // queries >= n, whose results are not stored
-  __syncthreads();
 
-  // ---- phase 2: lane = query
+  // ---- phase 2: lane = query; this wavefront's half of the head dimension is dt = part
   {
-    const int qi = wave * 32 + col;
-    floatx16 acc[2] = {zero16(), zero16()};
+    const int qi = blk * 32 + col;
+    const int dt = part;
+    floatx16 acc = zero16();
 #pragma unroll
     for (int ks = 0; ks < kSmallN / 16; ++ks) {
       if (ks * 16 >= n) break;
       // right operand: dS^T[key][query], keys 16*ks + 8*half + e
-      Frag dsf;
+      Frag dsf, kf;
       {
-        const int mn = wave * 32 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+        const int mn = blk * 32 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
 #pragma unroll
         for (int rd = 0; rd < 2; ++rd) {
           const int krow = 16 * ks + 8 * half + 4 * rd + ((lane & 15) >> 2);
@@ -1021,10 +1054,8 @@ __global__ __launch_bounds__(256) void sdpa_bwd_small_bf16(SdpaArgs a) {
           dsf.d[rd] = __builtin_bit_cast(u32x2, v);
         }
       }
-#pragma unroll
-      for (int dt = 0; dt < 2; ++dt) {
+      {
         // left operand: K^T[dim][key] with the standard k order: rows 16*ks + 8*half + {0..3}, + {4..7}
-        Frag kf;
         const int mn = dt * 32 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
 #pragma unroll
         for (int rd = 0; rd < 2; ++rd) {
@@ -1033,14 +1064,10 @@ __global__ __launch_bounds__(256) void sdpa_bwd_small_bf16(SdpaArgs a) {
           const s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)p);
           kf.d[rd] = __builtin_bit_cast(u32x2, v);
         }
-        acc[dt] = mfma(kf, dsf, acc[dt]);
       }
+      acc = mfma(kf, dsf, acc);
     }
-    if (qi < n) {
-      bf16_t* row = a.dq + base + (long long)qi * ld;
-      store_accT(row, acc[0], 0, half, a.scale);
-      store_accT(row, acc[1], 1, half, a.scale);
-    }
+    if (qi < n) store_accT(a.dq + base + (long long)qi * ld, acc, dt, half, a.scale);
   }
 }
 
@@ -1247,7 +1274,7 @@ __global__ __launch_bounds__(256) void attn_fwd_small_bf16(FusedFwdArgs a) {
   for (int kt = 0; kt < 4; ++kt)
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-      st[kt][r] = exp2f(st[kt][r] - m);
+      st[kt][r] = fast_exp2(st[kt][r] - m);
       l += st[kt][r];
     }
   l += __shfl_xor(l, 32, 64);
@@ -1421,7 +1448,7 @@ int vd_attn_bwd_bf16(vardrop_ctx* ctx, const void* dy, const void* xs, int B, in
     }
     {
       VdTimer timer(ctx, VARDROP_K_SDPA_BWD, s);
-      hipLaunchKernelGGL(sdpa_bwd_small_bf16, dim3(H, B), dim3(256), kSmallLds, s, a);
+      hipLaunchKernelGGL(sdpa_bwd_small_bf16, dim3(H, B), dim3(512), kSmallLds, s, a);
     }
     VD_LAUNCH_CHECK(ctx);
   } else {

@@ -148,3 +148,13 @@ def test_empty_and_error_cases(vd, ctx):
     with pytest.raises(vd.VarDropError) as e:                                   # H does not divide d
         vd.vardrop_attn_fwd(ctx, torch.zeros((1, 4, 64), dtype=torch.bfloat16, device="cuda"), *W, 3)
     assert e.value.code == -1
+
+
+def test_bf16_backward_is_bit_reproducible(vd, ctx):
+    """Sliced weight gradients are summed in a fixed order, whichever workgroup finishes last: equal bits on every call."""
+    xs, W, dy, _ = random_case(77, 8, 113, 512, "bf16", bias=False)
+    first = run_gpu(vd, ctx, xs, W, 8, dy, "bf16")
+    for _ in range(3):
+        again = run_gpu(vd, ctx, xs, W, 8, dy, "bf16")
+        for k in GRADS + ("y",):
+            assert torch.equal(first[k], again[k]), k
