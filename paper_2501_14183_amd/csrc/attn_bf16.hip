@@ -1076,11 +1076,12 @@ __global__ __launch_bounds__(512) void sdpa_bwd_small_bf16(SdpaArgs a) {
 // asynchronous copies three stages deep), leaves them in LDS, and runs the attention of the head on
 // them; Q, K, V, O and the log-sum-exp are written for the backward pass.  Compared with a projection
 // GEMM followed by an attention kernel this saves a launch and the round trip of Q, K, V through memory.
-//   projection: four wavefronts as 2 x 2, each 64 tokens x 96 columns (2 x 3 matrix-instruction tiles);
+//   projection: eight wavefronts as 4 x 2, each 32 tokens x 96 columns (three matrix-instruction tiles);
 //               xs tile [token][64 k] read as 16-byte fragments, weight tiles [64 k][64 columns]
 //               through transposing reads; product formed transposed so that a lane owns a token.
-//   attention:  a wavefront owns 32 queries (lane = query); S^T = K q^T over all keys at once, exact
-//               softmax, O^T = V^T P^T with V^T taken from the V tile by transposing reads.
+//   attention:  a wavefront owns 32 queries (lane = query) and half of the keys; S^T = K q^T, softmax
+//               over its keys, O^T = V^T P^T with V^T taken from the V tile by transposing reads; the two
+//               halves of a query block are merged through LDS (maxima, sums, rescaled outputs).
 struct FusedFwdArgs {
   const bf16_t* xs;
   const bf16_t *Wq, *Wk, *Wv;
@@ -1094,18 +1095,17 @@ constexpr int kFusedStage = kSmallN * 64 * 2 + 3 * 64 * 64 * 2;     // xs tile +
 constexpr int kFusedStages = 3;
 constexpr int kFusedLds = kFusedStages * kFusedStage;
 
-template <int N>
-__device__ inline void wait_lds5(Frag& a, Frag& b, Frag& c, Frag& d, Frag& e) {
-  asm volatile("s_waitcnt lgkmcnt(%5)" : "+v"(a.q), "+v"(b.q), "+v"(c.q), "+v"(d.q), "+v"(e.q) : "n"(N));
-}
-
-__global__ __launch_bounds__(256) void attn_fwd_small_bf16(FusedFwdArgs a) {
+__global__ __launch_bounds__(512) void attn_fwd_small_bf16(FusedFwdArgs a) {
+  // Eight wavefronts (two per SIMD).  Projection: wavefront w computes token rows 32*(w % 4) .. +31 of the
+  // column tiles 3*(w / 4) .. +2 of [q | k | v].  Attention: wavefront w owns the queries 32*(w % 4) .. +31
+  // and the key tiles 2*(w / 4), 2*(w / 4) + 1; the two partial softmax results of a query block are merged
+  // through LDS.
   constexpr int NS = kFusedStages, STAGE = kFusedStage, A_BYTES = kSmallN * 64 * 2, BT = 64 * 64 * 2;
-  constexpr int LPS = 10;                                       // copies per wavefront and stage: 4 of xs, 6 of weights
-  constexpr int OPK = 8;                                        // LDS reads per 16-k step: 2 + 3 * 2
+  constexpr int LPS = 5;                                        // copies per wavefront and stage: 2 of xs, 3 of weights
+  constexpr int OPK = 7;                                        // LDS reads per 16-k step: 1 + 3 * 2
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int wr = wave & 1, wc = wave >> 1;
+  const int wr = wave & 3, wc = wave >> 2;
   const int col = lane & 31, half = lane >> 5;
   // heads fastest: a die's contiguous range covers whole batches, whose tokens it then fetches once
   const int tix = xcd_contiguous(blockIdx.x + gridDim.x * blockIdx.y, gridDim.x * gridDim.y);
@@ -1115,29 +1115,28 @@ __global__ __launch_bounds__(256) void attn_fwd_small_bf16(FusedFwdArgs a) {
   const bf16_t* xs_b = a.xs + (long long)b * n * ld;
   const int total = d / 64;
 
-  // ---- copy sources.  xs: copy u covers token rows 8*(4u + wave) .. +7.  Weights: copy u (0..5) belongs
-  // to matrix u / 2 and covers its k-rows 8*(4*(u % 2) + wave) .. +7 of the slice.
-  const bf16_t* srcA[4];
-  const bf16_t* srcB[6];
+  // ---- copy sources.  xs: copy u covers token rows 8*(8u + wave) .. +7.  Weights: copy u belongs to
+  // matrix u and covers its k-rows 8*wave .. +7 of the slice.
+  const bf16_t* srcA[2];
+  const bf16_t* srcB[3];
 #pragma unroll
-  for (int u = 0; u < 4; ++u) {
-    const int row = (u * 4 + wave) * 8 + (lane >> 3);
+  for (int u = 0; u < 2; ++u) {
+    const int row = (u * 8 + wave) * 8 + (lane >> 3);
     srcA[u] = xs_b + (long long)min(row, n - 1) * ld + (((lane & 7) ^ (row & 7)) * 8);
   }
 #pragma unroll
-  for (int u = 0; u < 6; ++u) {
-    const bf16_t* Wz = (u >> 1) == 0 ? a.Wq : ((u >> 1) == 1 ? a.Wk : a.Wv);
-    const int krow = (4 * (u & 1) + wave) * 8 + (lane >> 3);
+  for (int u = 0; u < 3; ++u) {
+    const bf16_t* Wz = u == 0 ? a.Wq : (u == 1 ? a.Wk : a.Wv);
+    const int krow = wave * 8 + (lane >> 3);
     srcB[u] = Wz + (long long)krow * ld + h * kDh + (((lane & 7) ^ swz_nc<64>(krow)) * 8);
   }
   // ---- fragment addresses relative to a stage
   const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
-  uint32_t addrA[2][4], addrB[3];
+  uint32_t addrA[4], addrB[3];
+  {
+    const int ra = wr * 32 + col;
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int ra = wr * 64 + i * 32 + col;
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) addrA[i][ks] = lds0 + ra * 128 + (((2 * ks + half) ^ (ra & 7)) * 16);
+    for (int ks = 0; ks < 4; ++ks) addrA[ks] = lds0 + ra * 128 + (((2 * ks + half) ^ (ra & 7)) * 16);
   }
 #pragma unroll
   for (int j = 0; j < 3; ++j) {
@@ -1146,19 +1145,15 @@ __global__ __launch_bounds__(256) void attn_fwd_small_bf16(FusedFwdArgs a) {
     const int mn = (ct & 1) * 32 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
     addrB[j] = lds0 + A_BYTES + (ct >> 1) * BT + krow * 128 + (((mn >> 3) ^ swz_nc<64>(krow)) * 16) + ((mn >> 2) & 1) * 8;
   }
-  floatx16 acc[2][3];
-#pragma unroll
-  for (int i = 0; i < 2; ++i)
-#pragma unroll
-    for (int j = 0; j < 3; ++j) acc[i][j] = zero16();
+  floatx16 acc[3] = {zero16(), zero16(), zero16()};
 
   int fk = 0;        // slice whose copies are issued next
 #define VD_ISSUE(BUF)                                                                               \
   {                                                                                                \
     unsigned char* sp = smem + (BUF) * STAGE + wave * 1024;                                        \
-    _Pragma("unroll") for (int u = 0; u < 4; ++u) dma16(srcA[u] + fk * 64, sp + u * 4096);         \
-    _Pragma("unroll") for (int u = 0; u < 6; ++u)                                                  \
-      dma16(srcB[u] + (long long)fk * 64 * ld, sp + A_BYTES + (u >> 1) * BT + (u & 1) * 4096);     \
+    _Pragma("unroll") for (int u = 0; u < 2; ++u) dma16(srcA[u] + fk * 64, sp + u * 8192);         \
+    _Pragma("unroll") for (int u = 0; u < 3; ++u)                                                  \
+      dma16(srcB[u] + (long long)fk * 64 * ld, sp + A_BYTES + u * BT);                             \
     ++fk;                                                                                          \
   }
 #pragma unroll
@@ -1173,10 +1168,10 @@ __global__ __launch_bounds__(256) void attn_fwd_small_bf16(FusedFwdArgs a) {
         __builtin_amdgcn_s_barrier();
         if (t + NS - 1 < total) VD_ISSUE((s + NS - 1) % NS)
         const uint32_t so = s * STAGE;
-        Frag fa[2][2], fb[2][3];
+        Frag fa[2], fb[2][3];
 #define VD_READ(KS_, SET)                                                                          \
   {                                                                                                \
-    _Pragma("unroll") for (int i = 0; i < 2; ++i) lds_read16(fa[SET][i].q, addrA[i][KS_] + so);    \
+    lds_read16(fa[SET].q, addrA[KS_] + so);                                                        \
     _Pragma("unroll") for (int j = 0; j < 3; ++j) {                                                \
       lds_read8_tr<(KS_) * 2048>(fb[SET][j].d[0], addrB[j] + so);                                  \
       lds_read8_tr<(KS_) * 2048 + 512>(fb[SET][j].d[1], addrB[j] + so);                            \
@@ -1184,9 +1179,8 @@ __global__ __launch_bounds__(256) void attn_fwd_small_bf16(FusedFwdArgs a) {
   }
 #define VD_MMA(SET, PENDING)                                                                       \
   {                                                                                                \
-    wait_lds5<PENDING>(fa[SET][0], fa[SET][1], fb[SET][0], fb[SET][1], fb[SET][2]);                \
-    _Pragma("unroll") for (int i = 0; i < 2; ++i)                                                  \
-      _Pragma("unroll") for (int j = 0; j < 3; ++j) acc[i][j] = mfma(fb[SET][j], fa[SET][i], acc[i][j]); \
+    wait_lds<PENDING>(fa[SET], fb[SET][0], fb[SET][1], fb[SET][2]);                                \
+    _Pragma("unroll") for (int j = 0; j < 3; ++j) acc[j] = mfma(fb[SET][j], fa[SET], acc[j]);      \
     __builtin_amdgcn_sched_barrier(0);                                                             \
   }
         VD_READ(0, 0)
@@ -1208,6 +1202,7 @@ __global__ __launch_bounds__(256) void attn_fwd_small_bf16(FusedFwdArgs a) {
   unsigned char* Qs = smem;
   unsigned char* Ks = Qs + kSmallTile;
   unsigned char* Vs = Ks + kSmallTile;
+  float* merge = reinterpret_cast<float*>(Vs + kSmallTile);     // [query block][34 registers][lane]
   __syncthreads();                       // every wavefront is done with the last slice
 #pragma unroll
   for (int j = 0; j < 3; ++j) {
@@ -1222,22 +1217,19 @@ __global__ __launch_bounds__(256) void attn_fwd_small_bf16(FusedFwdArgs a) {
         bv[0] = __uint_as_float(b4.x << 16); bv[1] = __uint_as_float(b4.x & 0xffff0000u);
         bv[2] = __uint_as_float(b4.y << 16); bv[3] = __uint_as_float(b4.y & 0xffff0000u);
       }
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        const int row = wr * 64 + i * 32 + col;
-        u32x2 o;
-        o.x = pack2(acc[i][j][4 * q4] + bv[0], acc[i][j][4 * q4 + 1] + bv[1]);
-        o.y = pack2(acc[i][j][4 * q4 + 2] + bv[2], acc[i][j][4 * q4 + 3] + bv[3]);
-        *reinterpret_cast<u32x2*>(smem + z * kSmallTile + row * 128 + (((dim >> 3) ^ (row & 7)) * 16) + ((dim >> 2) & 1) * 8) = o;
-      }
+      const int row = wr * 32 + col;
+      u32x2 o;
+      o.x = pack2(acc[j][4 * q4] + bv[0], acc[j][4 * q4 + 1] + bv[1]);
+      o.y = pack2(acc[j][4 * q4 + 2] + bv[2], acc[j][4 * q4 + 3] + bv[3]);
+      *reinterpret_cast<u32x2*>(smem + z * kSmallTile + row * 128 + (((dim >> 3) ^ (row & 7)) * 16) + ((dim >> 2) & 1) * 8) = o;
     }
   }
   __syncthreads();
   // copy the tiles out for the backward pass: 16-byte chunks, eight per token row
   const long long base = (long long)b * n * ld + h * kDh;
 #pragma unroll
-  for (int u = 0; u < 3 * kSmallN * 8 / 256; ++u) {
-    const int idx = u * 256 + threadIdx.x;
+  for (int u = 0; u < 3 * kSmallN * 8 / 512; ++u) {
+    const int idx = u * 512 + threadIdx.x;
     const int z = idx / (kSmallN * 8), row = (idx / 8) % kSmallN, c = idx & 7;
     if (row < n) {
       bf16_t* dst = z == 0 ? a.q : (z == 1 ? a.k : a.v);
@@ -1246,57 +1238,82 @@ __global__ __launch_bounds__(256) void attn_fwd_small_bf16(FusedFwdArgs a) {
     }
   }
 
-  // ---- attention: lane = query
-  const int qi = wave * 32 + col;
+  // ---- attention: lane = query, this wavefront's key tiles are 2*wc and 2*wc + 1
+  const int qi = wr * 32 + col;
   Frag qf[4];
 #pragma unroll
   for (int s = 0; s < 4; ++s) qf[s] = small_row_frag(Qs, qi, 2 * s + half);
   const float c = a.scale * kLog2e;
-  floatx16 st[4];
+  floatx16 st[2];
   float m = -INFINITY;
 #pragma unroll
-  for (int kt = 0; kt < 4; ++kt) {
-    st[kt] = zero16();
+  for (int k2 = 0; k2 < 2; ++k2) {
+    const int kt = 2 * wc + k2;
+    st[k2] = zero16();
     if (kt * 32 < n) {
 #pragma unroll
-      for (int s = 0; s < 4; ++s) st[kt] = mfma(small_row_frag(Ks, kt * 32 + col, 2 * s + half), qf[s], st[kt]);
+      for (int s = 0; s < 4; ++s) st[k2] = mfma(small_row_frag(Ks, kt * 32 + col, 2 * s + half), qf[s], st[k2]);
     }
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const int j = kt * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-      st[kt][r] = j < n ? st[kt][r] * c : -INFINITY;
-      m = fmaxf(m, st[kt][r]);
+      st[k2][r] = j < n ? st[k2][r] * c : -INFINITY;
+      m = fmaxf(m, st[k2][r]);
     }
   }
   m = fmaxf(m, __shfl_xor(m, 32, 64));
+  // a wavefront whose key tiles are all past n has m = -inf: its probabilities must be zero, not NaN
+  const float mref = m == -INFINITY ? 0.f : m;
   float l = 0.f;
 #pragma unroll
-  for (int kt = 0; kt < 4; ++kt)
+  for (int k2 = 0; k2 < 2; ++k2)
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-      st[kt][r] = fast_exp2(st[kt][r] - m);
-      l += st[kt][r];
+      st[k2][r] = fast_exp2(st[k2][r] - mref);
+      l += st[k2][r];
     }
   l += __shfl_xor(l, 32, 64);
   floatx16 out[2] = {zero16(), zero16()};
 #pragma unroll
-  for (int kt = 0; kt < 4; ++kt) {
+  for (int k2 = 0; k2 < 2; ++k2) {
+    const int kt = 2 * wc + k2;
     if (kt * 32 < n) {
 #pragma unroll
       for (int s2 = 0; s2 < 2; ++s2) {
-        const Frag pf = regs_to_frag(st[kt], s2);
+        const Frag pf = regs_to_frag(st[k2], s2);
         const int krow0 = kt * 32 + 16 * s2 + 4 * half;
 #pragma unroll
         for (int dt = 0; dt < 2; ++dt) out[dt] = mfma(small_tr_frag(Vs, krow0, dt * 32, lane), pf, out[dt]);
       }
     }
   }
-  if (qi < n) {
-    const float inv = 1.f / l;
-    bf16_t* orow = a.o + base + (long long)qi * ld;
-    store_accT(orow, out[0], 0, half, inv);
-    store_accT(orow, out[1], 1, half, inv);
-    if (half == 0) a.lse[((long long)b * a.H + h) * n + qi] = (m + log2f(l)) * 0.6931471805599453f;
+  // merge the two key halves of a query block: the upper one hands over (m, l, out)
+  float* mp = merge + wr * (34 * 64) + lane;
+  if (wc == 1) {
+#pragma unroll
+    for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mp[(dt * 16 + r) * 64] = out[dt][r];
+    mp[32 * 64] = m;
+    mp[33 * 64] = l;
+  }
+  __syncthreads();
+  if (wc == 0) {
+    const float m1 = mp[32 * 64], l1 = mp[33 * 64];
+    const float mm = fmaxf(m, m1);                       // finite: key 0 belongs to the lower half
+    const float f0 = fast_exp2(m - mm), f1 = fast_exp2(m1 - mm);
+    const float lsum = l * f0 + l1 * f1;
+    if (qi < n) {
+      const float inv = 1.f / lsum;
+#pragma unroll
+      for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) out[dt][r] = out[dt][r] * f0 + mp[(dt * 16 + r) * 64] * f1;
+      bf16_t* orow = a.o + base + (long long)qi * ld;
+      store_accT(orow, out[0], 0, half, inv);
+      store_accT(orow, out[1], 1, half, inv);
+      if (half == 0) a.lse[((long long)b * a.H + h) * n + qi] = (mm + log2f(lsum)) * 0.6931471805599453f;
+    }
   }
 }
 
@@ -1389,7 +1406,7 @@ int vd_attn_fwd_bf16(vardrop_ctx* ctx, const void* xs, int B, int n, int d, int 
     }
     {
       VdTimer timer(ctx, VARDROP_K_QKV_SDPA_FWD, s);
-      hipLaunchKernelGGL(attn_fwd_small_bf16, dim3(H, B), dim3(256), kFusedLds, s, f);
+      hipLaunchKernelGGL(attn_fwd_small_bf16, dim3(H, B), dim3(512), kFusedLds, s, f);
     }
     VD_LAUNCH_CHECK(ctx);
   } else {
