@@ -143,7 +143,7 @@ def cpu_baseline(w, x_np, tok_np, W_np, seed):
 def main():
     args = parse()
     if args.gpus != 1:
-        print("bench.py measures one GPU: this build has no multi-GPU path (see DESIGN.md); run with --gpus 1",
+        print("bench.py measures one GPU: the library has no multi-GPU path; run with --gpus 1",
               file=sys.stderr)
         sys.exit(2)
     import numpy as np

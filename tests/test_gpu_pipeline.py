@@ -58,3 +58,62 @@ def test_step_matches_oracle(vd, ctx, name):
     d_np = dtok.float().cpu().numpy()
     assert np.all(d_np[:, ~kept] == 0) and np.array_equal(d_np[:, kept], dxs.float().cpu().numpy())
     print("%s: G=%d N'=%d redrawn=%d errs=%s" % (name, G, n_sel, info["redrawn"], {k: "%.1e" % v for k, v in errs.items()}))
+
+
+def test_pipelined_steps_in_the_benchmark_configuration(vd, ctx):
+    """Traffic-shaped batch, launched the way bench.py launches it: selection on a second stream a step ahead
+    through raw stream handles, a ring of selection buffers, outputs written into buffers sized for all N
+    variates and viewed at N'; three consecutive steps (new selection each), every one against the oracle."""
+    w, x, info, want_topk, want_hash, _ = workload_inputs("traffic")
+    td = torch_dtype(w.dtype)
+    tok = wl.make_tokens(w, x)
+    W = wl.make_weights(w)
+    x_t, tok_t = to_dev(x), to_dev(tok, td)
+    W_t = [to_dev(m, td) for m in W]
+    dev = x_t.device
+    main, side = torch.cuda.current_stream(), torch.cuda.Stream(device=dev)
+    main_h, side_h = main.cuda_stream, side.cuda_stream
+    lib = vd.load_library()
+    saved = torch.empty(lib.vardrop_attn_saved_bytes(w.B, w.N, w.d, w.H, vd.BF16), dtype=torch.uint8, device=dev)
+    ws = torch.empty(lib.vardrop_attn_workspace_bytes(w.B, w.N, w.d, w.H, vd.BF16), dtype=torch.uint8, device=dev)
+    xs_buf, y_buf, dxs_buf = (torch.empty(w.B * w.N * w.d, dtype=td, device=dev) for _ in range(3))
+    dW_buf = [torch.empty((w.d, w.d), dtype=torch.float32, device=dev) for _ in range(4)]
+    ring = 3
+    bufs = [(torch.empty((w.N, w.k), dtype=torch.int32, device=dev), torch.empty(w.N, dtype=torch.int64, device=dev),
+             torch.empty(w.N, dtype=torch.int32, device=dev), torch.empty(w.N, dtype=torch.int32, device=dev),
+             torch.empty(2, dtype=torch.int32, device=dev)) for _ in range(ring)]
+    pinned = [torch.zeros(2, dtype=torch.int32).pin_memory() for _ in range(ring)]
+    events = [torch.cuda.Event() for _ in range(ring)]
+    torch.cuda.synchronize()
+
+    def select(i):
+        topk, hsh, gid, sel, counts = bufs[i % ring]
+        vd.vardrop_hash(ctx, x_t, w.k, out=(topk, hsh), stream=side_h)
+        vd.vardrop_sample(ctx, hsh, 0, w.ratio[0], w.ratio[1], SEED, STEP + i, counts_host=pinned[i % ring],
+                          out=(gid, sel, counts), stream=side_h)
+        events[i % ring].record(side)
+
+    steps = 3
+    select(0)
+    for i in range(steps):
+        if i + 1 < steps:
+            select(i + 1)
+        events[i % ring].synchronize()
+        n_sel, G = int(pinned[i % ring][0]), int(pinned[i % ring][1])
+        sel = bufs[i % ring][3]
+        count, shape = w.B * n_sel * w.d, (w.B, n_sel, w.d)
+        xs = vd.vardrop_gather(ctx, tok_t, sel, n_sel, out=xs_buf[:count].view(shape), stream=main_h)
+        y, _ = vd.vardrop_attn_fwd(ctx, xs, *W_t, w.H, saved=saved, out=y_buf[:count].view(shape), stream=main_h)
+        dy = wl.make_upstream(w, n_sel)
+        grads = vd.vardrop_attn_bwd(ctx, to_dev(dy, td), xs, *W_t, w.H, saved, ws=ws,
+                                    out=(dxs_buf[:count].view(shape), *dW_buf), stream=main_h)
+        torch.cuda.synchronize()          # the check below reads the buffers the next step reuses
+        want_gid, want_sel, want_G = o_samp.stratified_sample(want_hash, 0, w.ratio[0], w.ratio[1], SEED, STEP + i)
+        assert (n_sel, G) == (len(want_sel), want_G)
+        assert np.array_equal(bufs[i % ring][0].cpu().numpy(), want_topk)
+        assert np.array_equal(sel.cpu().numpy()[:n_sel], want_sel)
+        assert np.array_equal(xs.float().cpu().numpy(), tok[:, want_sel, :])
+        want = oracle_attention(tok[:, want_sel, :], W, w.H, dy)
+        got = dict(zip(("dxs", "dWq", "dWk", "dWv", "dWo"), grads), y=y)
+        errs = {k: rel_err(v, want[k]) for k, v in got.items()}
+        assert all(e <= TOL[w.dtype] for e in errs.values()), (i, errs)
