@@ -58,6 +58,9 @@ int vardrop_last_hip_error(const vardrop_ctx* ctx);
  * launches between two reads; further ones are not recorded).  vardrop_profile_read waits for
  * the recorded launches, returns their summed duration in milliseconds and their number,
  * and starts a new collection.  Selecting -1 switches the timing off (the default).
+ * An event pair costs the stream several microseconds, which a benchmark of short kernels
+ * feels: vardrop_profile_stride(ctx, s) brackets only every s-th launch of the selected
+ * kernel (s >= 1, default 1; takes effect at the next vardrop_profile_select).
  */
 enum {
   VARDROP_K_HASH = 0,        /* k-DFH: spectrum, batch mean, ranked top-k, hash            */
@@ -80,6 +83,7 @@ enum {
 };
 int vardrop_profile_select(vardrop_ctx* ctx, int kernel_id);
 int vardrop_profile_read(vardrop_ctx* ctx, double* total_ms, int* launches);
+int vardrop_profile_stride(vardrop_ctx* ctx, int stride);
 /* Static name of a kernel id ("hash", "gemm_qkv", ...), or NULL when out of range. */
 const char* vardrop_kernel_name(int kernel_id);
 

@@ -28,6 +28,7 @@ _SIGNATURES = {
     "vardrop_last_hip_error": (_c_int, [_ptr]),
     "vardrop_profile_select": (_c_int, [_ptr, _c_int]),
     "vardrop_profile_read": (_c_int, [_ptr, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(_c_int)]),
+    "vardrop_profile_stride": (_c_int, [_ptr, _c_int]),
     "vardrop_kernel_name": (ctypes.c_char_p, [_c_int]),
     "vardrop_hash_workspace_bytes": (_c_size, [_c_int] * 6),
     "vardrop_hash": (_c_int, [_ptr, _ptr, _c_int, _c_int, _c_int, _c_i64, _c_i64, _c_i64, _c_int, _c_int, _c_int,
@@ -133,6 +134,11 @@ def vardrop_kernel_name(kid):
 def vardrop_profile_select(ctx, kid):
     """Brackets every launch of kernel `kid` with HIP events (-1: off)."""
     ctx.check(ctx._lib.vardrop_profile_select(ctx.handle, kid), "vardrop_profile_select")
+
+
+def vardrop_profile_stride(ctx, stride):
+    """Bracket only every `stride`-th launch of the selected kernel (takes effect at the next select)."""
+    ctx.check(ctx._lib.vardrop_profile_stride(ctx.handle, stride), "vardrop_profile_stride")
 
 
 def vardrop_profile_read(ctx):

@@ -12,6 +12,8 @@ struct vardrop_ctx {
   int last_hip_error;
   int prof_kid;          // kernel whose launches are bracketed by events (-1: none)
   int prof_n;            // pairs recorded since the last read
+  int prof_stride;       // every prof_stride-th launch of the selected kernel is bracketed
+  int prof_seen;         // launches of the selected kernel seen since it was selected
   hipEvent_t* prof_ev;   // 2 * kProfPairs events, created on first use
   float* twiddle;        // device: cos(2 pi j / L), j < L, then sin(2 pi j / L), j < L
   int twiddle_L;         // L the table currently holds (0: none)
@@ -38,7 +40,7 @@ struct VdTimer {
   hipStream_t stream;
   bool active;
   VdTimer(vardrop_ctx* c, int kid, hipStream_t s) : ctx(c), stream(s), active(false) {
-    if (c->prof_kid == kid && c->prof_ev && c->prof_n < kProfPairs)
+    if (c->prof_kid == kid && c->prof_ev && c->prof_n < kProfPairs && (c->prof_seen++ % c->prof_stride) == 0)
       active = hipEventRecord(c->prof_ev[2 * c->prof_n], s) == hipSuccess;
   }
   ~VdTimer() {

@@ -15,6 +15,8 @@ extern "C" int vardrop_create(vardrop_ctx** out, int device_id) {
   c->twiddle_L = 0;
   c->prof_kid = -1;
   c->prof_n = 0;
+  c->prof_stride = 1;
+  c->prof_seen = 0;
   c->prof_ev = nullptr;
   c->lds_per_block = 65536;
   int prev = 0;
@@ -83,6 +85,13 @@ extern "C" int vardrop_profile_select(vardrop_ctx* ctx, int kernel_id) {
   }
   ctx->prof_kid = kernel_id;
   ctx->prof_n = 0;
+  ctx->prof_seen = 0;
+  return VARDROP_OK;
+}
+
+extern "C" int vardrop_profile_stride(vardrop_ctx* ctx, int stride) {
+  if (!ctx || stride < 1) return VARDROP_EINVAL;
+  ctx->prof_stride = stride;
   return VARDROP_OK;
 }
 
