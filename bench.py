@@ -49,7 +49,7 @@ def algorithmic_work(w, n):
         "reduce_dw": ("hbm", 4.0 * 4 * d * d * 2),
         "gemm_dxs": (mm, 6.0 * M * d * d),
         "gemm_dw_dxs": (mm, 14.0 * M * d * d),
-        "sdpa_bwd": (mm, 10.0 * B * n * n * d),
+        "sdpa_bwd": (mm, 10.0 * B * n * n * d + 2.0 * M * d * d),      # includes dO = dy Wo^T
         "qkv_sdpa_fwd": (mm, 6.0 * M * d * d + 4.0 * B * n * n * d),
     }
 

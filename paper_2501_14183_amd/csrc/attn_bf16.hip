@@ -160,6 +160,10 @@ template <int N>
 __device__ inline void wait_lds(Frag& a, Frag& b, Frag& c) {
   asm volatile("s_waitcnt lgkmcnt(%3)" : "+v"(a.q), "+v"(b.q), "+v"(c.q) : "n"(N));
 }
+template <int N>
+__device__ inline void wait_lds(Frag& a, Frag& b) {
+  asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a.q), "+v"(b.q) : "n"(N));
+}
 
 template <int BK>
 __device__ inline int swz_kc(int row) { return BK == 32 ? (row >> 1) & 3 : row & 7; }
@@ -615,6 +619,7 @@ __device__ inline void store_accT(bf16_t* out_row, const floatx16& acc, int ct, 
 
 struct SdpaArgs {
   const bf16_t *q, *k, *v, *o, *dout;
+  const bf16_t *dy, *wo;          // short selections: dO is formed inside the kernel from dy and Wo
   bf16_t *out, *dq, *dk, *dv;
   float *lse, *Dsum;
   int n, d, H;
@@ -860,8 +865,8 @@ __global__ __launch_bounds__(NW * 64) void sdpa_bwd_dkv_bf16(SdpaArgs a) {
 }
 
 // ---- backward for short selections (n <= 128, the regime variate dropping produces): one workgroup
-// per (batch, head) holds Q, K, V, dO and O of the head in LDS (asynchronous copies, one round trip to
-// memory) and forms S and dP once for both gradients.
+// per (batch, head) holds Q, K, V and O of the head in LDS (asynchronous copies), forms the head's dO tile
+// from dy and Wo itself (dO never goes to memory), and forms S and dP once for all three gradients.
 //   phase 1, a wavefront owns 32 keys (lane = key):  S^T-free orientation S[query][key] = Q k^T and
 //            dP = dO v^T with the key fragments in registers; P and dS feed dV^T = dO^T P and
 //            dK^T = Q^T dS, whose left operands (contraction over queries) are transposing reads of
@@ -872,7 +877,9 @@ __global__ __launch_bounds__(NW * 64) void sdpa_bwd_dkv_bf16(SdpaArgs a) {
 constexpr int kSmallN = 128;
 constexpr int kDsPitch = 272;                 // bytes per dS^T row: 128 queries * 2 + 16
 constexpr int kSmallTile = kSmallN * kDh * 2;  // bytes of one [128][64] tile
-constexpr int kSmallLds = 5 * kSmallTile + kSmallN * kDsPitch + 2 * kSmallN * 4;
+constexpr int kBwdStage = kSmallN * 64 * 2 + 64 * 64 * 2;        // dy tile + Wo tile of one 64-k slice: 24 KB
+constexpr int kBwdStages = 2;
+constexpr int kSmallLds = 5 * kSmallTile + kBwdStages * kBwdStage;   // the ring overlays dS^T and the statistics
 
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 // 16-byte chunk (k = 8*chunk ..) of a token row of a swizzled tile
@@ -919,24 +926,106 @@ __global__ __launch_bounds__(512) void sdpa_bwd_small_bf16(SdpaArgs a) {
   const long long base = (long long)b * n * ld + h * kDh;
   const long long srow = ((long long)b * a.H + h) * n;
 
-  // ---- phase 0: copies.  A wavefront-wide copy fills 8 token rows; rows past n repeat row n-1.
+  // ---- phase 0: copies of K, Q, V, O.  A wavefront-wide copy fills 8 token rows; rows past n repeat row n-1.
   {
-    const bf16_t* src[5] = {a.k + base, a.q + base, a.v + base, a.dout + base, a.o + base};
+    const bf16_t* src[5] = {a.k + base, a.q + base, a.v + base, nullptr, a.o + base};
 #pragma unroll
-    for (int t = 0; t < 5; ++t)
+    for (int t = 0; t < 5; ++t) {
+      if (t == 3) continue;             // the dO tile is computed below
 #pragma unroll
       for (int u = 0; u < 2; ++u) {
         const int row = (u * 8 + wave) * 8 + (lane >> 3);
         const int chunk = (lane & 7) ^ (row & 7);
         dma16(src[t] + (long long)min(row, n - 1) * ld + chunk * 8, smem + t * kSmallTile + (u * 8 + wave) * 1024);
       }
-    if (threadIdx.x < kSmallN) {
-      const int i = threadIdx.x;
-      Ls[i] = i < n ? a.lse[srow + i] * kLog2e : INFINITY;
     }
   }
-  wait_vm<0>();                         // this wavefront's copies have landed ...
-  __syncthreads();                      // ... and so have everyone else's
+  // ---- dO tile of this head: dO[token][i] = sum_j dy[token][j] Wo[64 h + i][j], both operands k-contiguous,
+  // 64-k slices three stages deep in a ring that overlays the (not yet used) dS^T buffer.  Wavefront w
+  // computes token rows 32*(w % 4) .. +31, columns 32*(w / 4) .. +31.
+  {
+    constexpr int NS = kBwdStages, STAGE = kBwdStage, A_BYTES = kSmallN * 64 * 2, LPS = 3;
+    unsigned char* ring = dSt;
+    const bf16_t* dy_b = a.dy + (long long)b * n * ld;
+    const bf16_t* srcA[2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const int row = (u * 8 + wave) * 8 + (lane >> 3);
+      srcA[u] = dy_b + (long long)min(row, n - 1) * ld + (((lane & 7) ^ (row & 7)) * 8);
+    }
+    const int rowB = wave * 8 + (lane >> 3);
+    const bf16_t* srcB = a.wo + (long long)(h * kDh + rowB) * ld + (((lane & 7) ^ (rowB & 7)) * 8);
+    const uint32_t ring0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)ring;
+    uint32_t addrA[4], addrB[4];
+    {
+      const int ra = blk * 32 + col, rb = part * 32 + col;
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        addrA[ks] = ring0 + ra * 128 + (((2 * ks + half) ^ (ra & 7)) * 16);
+        addrB[ks] = ring0 + A_BYTES + rb * 128 + (((2 * ks + half) ^ (rb & 7)) * 16);
+      }
+    }
+    floatx16 acc = zero16();
+    const int total = a.d / 64;
+    int fk = 0;
+#define VD_ISSUE(BUF)                                                                               \
+  {                                                                                                \
+    unsigned char* sp = ring + (BUF) * STAGE + wave * 1024;                                        \
+    dma16(srcA[0] + fk * 64, sp);                                                                  \
+    dma16(srcA[1] + fk * 64, sp + 8192);                                                           \
+    dma16(srcB + fk * 64, sp + A_BYTES);                                                           \
+    ++fk;                                                                                          \
+  }
+#pragma unroll
+    for (int s = 0; s < NS - 1; ++s)
+      if (s < total) VD_ISSUE(s)
+    for (int t0 = 0; t0 < total; t0 += NS) {
+#pragma unroll
+      for (int s = 0; s < NS; ++s) {
+        const int t = t0 + s;
+        if (t < total) {
+          if (NS >= 3 && total - 1 - t >= 1) wait_vm<LPS>(); else wait_vm<0>();   // (the tile copies above are older: done too)
+          __builtin_amdgcn_s_barrier();
+          if (t + NS - 1 < total) VD_ISSUE((s + NS - 1) % NS)
+          const uint32_t so = s * STAGE;
+          Frag fa[2], fb[2];
+          lds_read16(fa[0].q, addrA[0] + so); lds_read16(fb[0].q, addrB[0] + so);
+          lds_read16(fa[1].q, addrA[1] + so); lds_read16(fb[1].q, addrB[1] + so);
+          wait_lds<2>(fa[0], fb[0]);
+          acc = mfma(fb[0], fa[0], acc);
+          __builtin_amdgcn_sched_barrier(0);
+          lds_read16(fa[0].q, addrA[2] + so); lds_read16(fb[0].q, addrB[2] + so);
+          wait_lds<2>(fa[1], fb[1]);
+          acc = mfma(fb[1], fa[1], acc);
+          __builtin_amdgcn_sched_barrier(0);
+          lds_read16(fa[1].q, addrA[3] + so); lds_read16(fb[1].q, addrB[3] + so);
+          wait_lds<2>(fa[0], fb[0]);
+          acc = mfma(fb[0], fa[0], acc);
+          __builtin_amdgcn_sched_barrier(0);
+          wait_lds<0>(fa[1], fb[1]);
+          acc = mfma(fb[1], fa[1], acc);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+    }
+#undef VD_ISSUE
+    // register 4*q4 + e of the accumulator is dO[32*blk + col][32*part + 8*q4 + 4*half + e]
+    const int row = blk * 32 + col;
+#pragma unroll
+    for (int q4 = 0; q4 < 4; ++q4) {
+      const int dim = part * 32 + 8 * q4 + 4 * half;
+      u32x2 o;
+      o.x = pack2(acc[4 * q4], acc[4 * q4 + 1]);
+      o.y = pack2(acc[4 * q4 + 2], acc[4 * q4 + 3]);
+      *reinterpret_cast<u32x2*>(dOs + row * 128 + (((dim >> 3) ^ (row & 7)) * 16) + ((dim >> 2) & 1) * 8) = o;
+    }
+  }
+  __syncthreads();                      // the ring is free: the statistics and later dS^T may use its place
+  if (threadIdx.x < kSmallN) {
+    const int i = threadIdx.x;
+    Ls[i] = i < n ? a.lse[srow + i] * kLog2e : INFINITY;
+  }
+  __syncthreads();
   // D = rowsum(dO * O), one query per lane pair
   if (part == 0) {
     const int qi = blk * 32 + col;
@@ -1446,7 +1535,7 @@ int vd_attn_bwd_bf16(vardrop_ctx* ctx, const void* dy, const void* xs, int B, in
   bf16_t* dv = dk + M * d;
   float* D = (float*)(dv + M * d);
   int rc;
-  {  // dO = dy Wo^T
+  if (n > kSmallN) {  // dO = dy Wo^T (short selections form their dO tiles inside the attention kernel)
     GemmBf16 g = {};
     g.set(0, dy, W[3], dO, nullptr);
     g.lda = d; g.ldb = d; g.ldc = d;
@@ -1456,6 +1545,7 @@ int vd_attn_bwd_bf16(vardrop_ctx* ctx, const void* dy, const void* xs, int B, in
   SdpaArgs a = {};
   a.q = q; a.k = k; a.v = v; a.o = o; a.dout = dO; a.lse = const_cast<float*>(lse);
   a.dq = dq; a.dk = dk; a.dv = dv; a.Dsum = D;
+  a.dy = (const bf16_t*)dy; a.wo = (const bf16_t*)W[3];
   a.n = n; a.d = d; a.H = H; a.scale = 1.0f / sqrtf((float)kDh);
   if (n <= kSmallN) {
     static int configured_device = -1;
