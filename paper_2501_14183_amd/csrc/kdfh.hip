@@ -7,16 +7,16 @@
 // the folded window with a cosine / sine table:
 //     Re X_f =  x[0] + (-1)^f x[L/2] + sum_{0<t<L/2} (x[t] + x[L-t]) cos(2 pi f t / L)
 //     Im X_f = -sum_{0<t<L/2} (x[t] - x[L-t]) sin(2 pi f t / L)
-// evaluated with the fp32 matrix instruction v_mfma_f32_32x32x2_f32 (rows = windows, columns = 32
-// bins, contraction = folded time).  The four wavefronts split the contraction (wavefront w takes
-// the steps w, w+4, ...), so that loads, matrix work and the LDS round trips of one block run four
-// wide; their partial sums meet in LDS.  The bins above the cut-off are never produced (Alg. 1
+// evaluated with the fp32 matrix instruction v_mfma_f32_16x16x4_f32 (rows = windows, columns = bins,
+// contraction = folded time).  Each of the four wavefronts owns a 16 x 16 quadrant of the block's
+// 32 windows x 32 bins and runs the whole contraction on it, so loads, folding and matrix work of
+// a block run four wide and nothing is reduced across wavefronts.  The bins above the cut-off are never produced (Alg. 1
 // step 2).  Amplitudes are summed over the batch in ascending window order in fp32 (step 3), and
 // the ranked top-k (step 4) is k rounds of a wavefront arg-max with the lower bin winning ties; the
 // hash is the tuple in radix R (step 5).
 #include "common.h"
 
-typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 namespace {
 
@@ -60,15 +60,14 @@ __global__ __launch_bounds__(kThreads) void kdfh_kernel(KdfhArgs a) {
   float* cosT = lds;
   float* sinT = lds + L;
   float* tile = sinT + L;                        // [L + 1][kTilePad], last row zero
-  float* part = tile + (L + 1) * kTilePad;       // [kWaves][16][64] partial accumulators (Re, then Im)
-  float* ampT = part + kWaves * 16 * 64;         // [32][kTilePad]
+  float* ampT = tile + (L + 1) * kTilePad;       // [32][kTilePad]
   float* asum = ampT + 32 * kTilePad;            // [Vb][F]
 
   for (int i = tid; i < 2 * L; i += kThreads) lds[i] = a.tw[i];
   for (int i = tid; i < Vb * F; i += kThreads) asum[i] = 0.f;
 
   const int Lh = L >> 1;
-  const int Sc = (Lh + 2) >> 1;                  // cosine steps: t = 0 .. floor(L/2), two per step
+  const int S4 = (Lh + 4) >> 2;                  // steps of four folded time samples: t = 0 .. floor(L/2)
   const int nct = (F + 31) >> 5;
 
   for (int rb = 0; rb < a.nrb; ++rb) {
@@ -129,65 +128,46 @@ __global__ __launch_bounds__(kThreads) void kdfh_kernel(KdfhArgs a) {
     }
     __syncthreads();
 
-    // ---- spectrum of the 32 rows, 32 bins at a time; this wavefront's share of the contraction
+    // ---- spectrum of the 32 rows, 32 bins at a time.  The four wavefronts take one 16 x 16 quadrant of
+    // the 32 x 32 (window, bin) tile each and run the whole contraction on it with
+    // v_mfma_f32_16x16x4_f32 (four folded time samples per instruction), so no partial sums are exchanged.
+    // Operand layout: A[i][k] lane holds row i = lane % 16, k = lane / 16; B[k][j] lane holds column
+    // j = lane % 16, the same k; C[i][j] lane holds column j = lane % 16, register r holds row 4*(lane/16) + r.
     for (int ct = 0; ct < nct; ++ct) {
-      const int f = a.f_min + ct * 32 + col;
-      const int step8 = (8 * f) % L;             // advancing s by kWaves moves t by 8
-      int mc = (f * (2 * wave + half)) % L;
-      int ms = (f * (2 * wave + 1 + half)) % L;
-      floatx16 re = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-      floatx16 im = re;
-      // Software pipeline: the operands of step s + kWaves are read from LDS while the matrix
-      // instructions of step s run (a lone wavefront per SIMD has nothing else to hide that latency).
-      // A step past the end of either sum reads the zero row.
-      int tc = 2 * wave + half;
-      float ac = tile[(tc <= Lh ? tc : L) * kTilePad + col];
-      float as = tile[(2 * (tc + 1) < L ? L - (tc + 1) : L) * kTilePad + col];
-      float bc = cosT[mc], bs = sinT[ms];
-      for (int s = wave; s < Sc; s += kWaves) {
+      const int i16 = lane & 15, kq = lane >> 4;
+      const int rh = wave & 1, ch = wave >> 1;
+      const int f = a.f_min + ct * 32 + ch * 16 + i16;
+      const int step4 = (4 * f) % L;             // advancing one step moves t by 4
+      int m = (f * kq) % L;                      // (f t) mod L: index into both tables
+      floatx4 re = {0.f, 0.f, 0.f, 0.f}, im = re;
+      // Re uses rows t <= L/2 (x[0], the sums, x[L/2]); Im uses rows L - t for 0 < 2t < L (the
+      // differences); every other step reads the zero row L.  Software pipeline: the operands of the
+      // next step are read from LDS while the matrix instructions of this one run.
+      const int arow = rh * 16 + i16;
+      int t = kq;
+      float ac = tile[(t <= Lh ? t : L) * kTilePad + arow];
+      float as = tile[((t > 0 && 2 * t < L) ? L - t : L) * kTilePad + arow];
+      float bc = cosT[m], bs = sinT[m];
+      for (int s = 0; s < S4; ++s) {
         const float ac0 = ac, as0 = as, bc0 = bc, bs0 = bs;
-        tc += 2 * kWaves;
-        mc += step8;
-        if (mc >= L) mc -= L;
-        ms += step8;
-        if (ms >= L) ms -= L;
-        ac = tile[(tc <= Lh ? tc : L) * kTilePad + col];
-        as = tile[(2 * (tc + 1) < L ? L - (tc + 1) : L) * kTilePad + col];
-        bc = cosT[mc];
-        bs = sinT[ms];
+        t += 4;
+        m += step4;
+        if (m >= L) m -= L;
+        ac = tile[(t <= Lh ? t : L) * kTilePad + arow];
+        as = tile[(2 * t < L ? L - t : L) * kTilePad + arow];
+        bc = cosT[m];
+        bs = sinT[m];
         __builtin_amdgcn_sched_barrier(0);
-        re = __builtin_amdgcn_mfma_f32_32x32x2f32(ac0, bc0, re, 0, 0, 0);
-        im = __builtin_amdgcn_mfma_f32_32x32x2f32(as0, bs0, im, 0, 0, 0);
+        re = __builtin_amdgcn_mfma_f32_16x16x4f32(ac0, bc0, re, 0, 0, 0);
+        im = __builtin_amdgcn_mfma_f32_16x16x4f32(as0, bs0, im, 0, 0, 0);
         // (keeps the reads above in this iteration: without it the compiler folds them back into
         //  the top of the next one, in front of the instructions that need them)
         __builtin_amdgcn_sched_barrier(0);
         asm volatile("" : "+v"(ac), "+v"(as), "+v"(bc), "+v"(bs));
       }
-      // Partial sums of the four wavefronts meet in LDS, real parts first, then imaginary parts:
-      // part[wave][register][lane].  This wavefront finishes registers 4*wave .. 4*wave+3, i.e. rows
-      // 8*wave + 4*half + (0..3) (accumulator register r of a lane holds row 8*(r/4) + 4*half + r%4,
-      // column col).
-      float sr[4], si[4];
 #pragma unroll
-      for (int r = 0; r < 16; ++r) part[(wave * 16 + r) * 64 + lane] = re[r];
-      __syncthreads();
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        sr[q] = 0.f;
-#pragma unroll
-        for (int w = 0; w < kWaves; ++w) sr[q] += part[(w * 16 + 4 * wave + q) * 64 + lane];
-      }
-      __syncthreads();
-#pragma unroll
-      for (int r = 0; r < 16; ++r) part[(wave * 16 + r) * 64 + lane] = im[r];
-      __syncthreads();
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        si[q] = 0.f;
-#pragma unroll
-        for (int w = 0; w < kWaves; ++w) si[q] += part[(w * 16 + 4 * wave + q) * 64 + lane];
-        ampT[(8 * wave + 4 * half + q) * kTilePad + col] = sqrtf(sr[q] * sr[q] + si[q] * si[q]);
-      }
+      for (int r = 0; r < 4; ++r)
+        ampT[(rh * 16 + 4 * kq + r) * kTilePad + ch * 16 + i16] = sqrtf(re[r] * re[r] + im[r] * im[r]);
       __syncthreads();
       const int bin = ct * 32 + col;
       for (int v = tid >> 5; v < Vb; v += kThreads / 32) {
@@ -195,8 +175,7 @@ __global__ __launch_bounds__(kThreads) void kdfh_kernel(KdfhArgs a) {
         for (int b = 0; b < rpv; ++b) sum += ampT[(v * rpv + b) * kTilePad + col];
         if (bin < F) asum[v * F + bin] += sum;
       }
-      // (the next write to `part` or `ampT` is separated from these reads by the barrier after the
-      //  partial sums of the next column tile, or by the one at the top of the row-block loop)
+      __syncthreads();                            // ampT is rewritten by the next column tile
     }
   }
   __syncthreads();
@@ -246,7 +225,7 @@ __global__ __launch_bounds__(kThreads) void kdfh_kernel(KdfhArgs a) {
 }
 
 size_t kdfh_lds_bytes(int L, int F, int Vb) {
-  return sizeof(float) * ((size_t)2 * L + (size_t)(L + 1) * kTilePad + kWaves * 16 * 64 + 32 * kTilePad + (size_t)Vb * F);
+  return sizeof(float) * ((size_t)2 * L + (size_t)(L + 1) * kTilePad + 32 * kTilePad + (size_t)Vb * F);
 }
 
 }  // namespace
