@@ -102,7 +102,7 @@ const char* vardrop_kernel_name(int kernel_id);
  *   abar   fp32 [N][f_max-f_min+1] mean amplitudes, or NULL
  * Requires 1 <= k <= f_max-f_min+1, 0 <= f_min <= f_max <= floor(L/2), R^k < 2^63,
  * 2 <= L <= 1024, at most 512 candidate bins, and staging buffers that fit the 160 KiB LDS:
- * 4*(35 L + 1089 + V*(f_max-f_min+1)) bytes with V = 32/min(32, B rounded up to a power of
+ * 4*(35 L + 1345 + V*(f_max-f_min+1)) bytes with V = 32/min(32, B rounded up to a power of
  * two); always true for L <= 768 (EUNSUPPORTED otherwise).  N == 0 is a no-op.  Arithmetic is fp32; ranks agree
  * with an exact evaluation whenever neighbouring amplitudes differ by much more than 1e-6
  * relative.  Non-finite inputs give unspecified ranks.

@@ -61,7 +61,8 @@ __global__ __launch_bounds__(kThreads) void kdfh_kernel(KdfhArgs a) {
   float* sinT = lds + L;
   float* tile = sinT + L;                        // [L + 1][kTilePad], last row zero
   float* ampT = tile + (L + 1) * kTilePad;       // [32][kTilePad]
-  float* asum = ampT + 32 * kTilePad;            // [Vb][F]
+  float* psum = ampT + 32 * kTilePad;            // [8][32] partial batch sums
+  float* asum = psum + 8 * 32;                   // [Vb][F]
 
   for (int i = tid; i < 2 * L; i += kThreads) lds[i] = a.tw[i];
   for (int i = tid; i < Vb * F; i += kThreads) asum[i] = 0.f;
@@ -116,7 +117,8 @@ __global__ __launch_bounds__(kThreads) void kdfh_kernel(KdfhArgs a) {
     __syncthreads();
     // ---- fold in place: row t becomes x[t] + x[L-t] and row L-t becomes x[t] - x[L-t] for
     // 0 < t < L/2 (rows 0 and L/2 stay); row L is a zero row for steps past the end.
-    {
+    const bool folded = nct > 1;      // one column tile reads every sample once: folding on the fly is cheaper
+    if (folded) {
       const int npair = (L - 1) >> 1;
       for (int i = tid; i < npair * 32; i += kThreads) {
         const int t = 1 + (i >> 5), r = i & 31;
@@ -124,8 +126,8 @@ __global__ __launch_bounds__(kThreads) void kdfh_kernel(KdfhArgs a) {
         tile[t * kTilePad + r] = p + q;
         tile[(L - t) * kTilePad + r] = p - q;
       }
-      if (tid < 32) tile[L * kTilePad + tid] = 0.f;
     }
+    if (tid < 32) tile[L * kTilePad + tid] = 0.f;
     __syncthreads();
 
     // ---- spectrum of the 32 rows, 32 bins at a time.  The four wavefronts take one 16 x 16 quadrant of
@@ -145,16 +147,22 @@ __global__ __launch_bounds__(kThreads) void kdfh_kernel(KdfhArgs a) {
       // next step are read from LDS while the matrix instructions of this one run.
       const int arow = rh * 16 + i16;
       int t = kq;
-      float ac = tile[(t <= Lh ? t : L) * kTilePad + arow];
-      float as = tile[((t > 0 && 2 * t < L) ? L - t : L) * kTilePad + arow];
+      // p = row t (or zero past L/2), q = row L - t when 0 < 2t < L (else zero); folded rows already hold
+      // p + q and p - q, unfolded ones are combined here
+      float p = tile[(t <= Lh ? t : L) * kTilePad + arow];
+      float q = tile[((t > 0 && 2 * t < L) ? L - t : L) * kTilePad + arow];
+      float ac = folded ? p : p + q;
+      float as = folded ? q : ((t > 0 && 2 * t < L) ? p - q : 0.f);
       float bc = cosT[m], bs = sinT[m];
       for (int s = 0; s < S4; ++s) {
         const float ac0 = ac, as0 = as, bc0 = bc, bs0 = bs;
         t += 4;
         m += step4;
         if (m >= L) m -= L;
-        ac = tile[(t <= Lh ? t : L) * kTilePad + arow];
-        as = tile[(2 * t < L ? L - t : L) * kTilePad + arow];
+        p = tile[(t <= Lh ? t : L) * kTilePad + arow];
+        q = tile[(2 * t < L ? L - t : L) * kTilePad + arow];
+        ac = folded ? p : p + q;
+        as = folded ? q : (2 * t < L ? p - q : 0.f);
         bc = cosT[m];
         bs = sinT[m];
         __builtin_amdgcn_sched_barrier(0);
@@ -169,13 +177,31 @@ __global__ __launch_bounds__(kThreads) void kdfh_kernel(KdfhArgs a) {
       for (int r = 0; r < 4; ++r)
         ampT[(rh * 16 + 4 * kq + r) * kTilePad + ch * 16 + i16] = sqrtf(re[r] * re[r] + im[r] * im[r]);
       __syncthreads();
+      // batch sums (Alg. 1 step 3).  The eight 32-lane groups add four windows each, ascending; with
+      // fewer than eight variates in the block the groups of a variate then add their partial sums,
+      // ascending again, so the order of the additions is fixed.
       const int bin = ct * 32 + col;
-      for (int v = tid >> 5; v < Vb; v += kThreads / 32) {
+      const int grp = tid >> 5;
+      if (Vb <= 8) {
         float sum = 0.f;
-        for (int b = 0; b < rpv; ++b) sum += ampT[(v * rpv + b) * kTilePad + col];
-        if (bin < F) asum[v * F + bin] += sum;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) sum += ampT[(grp * 4 + b) * kTilePad + col];
+        psum[grp * 32 + col] = sum;
+        __syncthreads();
+        const int gpv = 8 / Vb;                   // groups per variate
+        if (grp % gpv == 0 && bin < F) {
+          float total = 0.f;
+          for (int u = 0; u < gpv; ++u) total += psum[(grp + u) * 32 + col];
+          asum[(grp / gpv) * F + bin] += total;
+        }
+      } else {
+        for (int v = grp; v < Vb; v += kThreads / 32) {
+          float sum = 0.f;
+          for (int b = 0; b < rpv; ++b) sum += ampT[(v * rpv + b) * kTilePad + col];
+          if (bin < F) asum[v * F + bin] += sum;
+        }
       }
-      __syncthreads();                            // ampT is rewritten by the next column tile
+      __syncthreads();                            // ampT and psum are rewritten by the next column tile
     }
   }
   __syncthreads();
@@ -192,6 +218,22 @@ __global__ __launch_bounds__(kThreads) void kdfh_kernel(KdfhArgs a) {
       vals[j] = idx < F ? asum[v * F + idx] : -2.f;
     }
     unsigned long long h = 0;
+    if (F <= 64) {
+      // every lane holds one bin: its rank is the number of bins that beat it (larger mean amplitude, or
+      // equal and lower index); the lanes of rank 0 .. k-1 are the ranked top-k
+      const float mine = vals[0];
+      int rank = 0;
+      for (int j = 0; j < F; ++j) {
+        const float vj = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(mine), j));
+        rank += (vj > mine || (vj == mine && j < lane)) ? 1 : 0;
+      }
+      for (int r = 0; r < a.k; ++r) {
+        const unsigned long long mask = __ballot(lane < F && rank == r);
+        const int fsel = a.f_min + (__ffsll((long long)mask) - 1);
+        if (lane == 0) a.topk[(long long)n * a.k + r] = fsel;
+        h = h * R + (unsigned long long)(unsigned)fsel;
+      }
+    } else
     for (int r = 0; r < a.k; ++r) {
       float best = -3.f;
       int bi = 0x7fffffff;
@@ -225,7 +267,7 @@ __global__ __launch_bounds__(kThreads) void kdfh_kernel(KdfhArgs a) {
 }
 
 size_t kdfh_lds_bytes(int L, int F, int Vb) {
-  return sizeof(float) * ((size_t)2 * L + (size_t)(L + 1) * kTilePad + 32 * kTilePad + (size_t)Vb * F);
+  return sizeof(float) * ((size_t)2 * L + (size_t)(L + 1) * kTilePad + 32 * kTilePad + 8 * 32 + (size_t)Vb * F);
 }
 
 }  // namespace
