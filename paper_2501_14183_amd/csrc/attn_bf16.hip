@@ -926,20 +926,6 @@ __global__ __launch_bounds__(512) void sdpa_bwd_small_bf16(SdpaArgs a) {
   const long long base = (long long)b * n * ld + h * kDh;
   const long long srow = ((long long)b * a.H + h) * n;
 
-  // ---- phase 0: copies of K, Q, V, O.  A wavefront-wide copy fills 8 token rows; rows past n repeat row n-1.
-  {
-    const bf16_t* src[5] = {a.k + base, a.q + base, a.v + base, nullptr, a.o + base};
-#pragma unroll
-    for (int t = 0; t < 5; ++t) {
-      if (t == 3) continue;             // the dO tile is computed below
-#pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        const int row = (u * 8 + wave) * 8 + (lane >> 3);
-        const int chunk = (lane & 7) ^ (row & 7);
-        dma16(src[t] + (long long)min(row, n - 1) * ld + chunk * 8, smem + t * kSmallTile + (u * 8 + wave) * 1024);
-      }
-    }
-  }
   // ---- dO tile of this head: dO[token][i] = sum_j dy[token][j] Wo[64 h + i][j], both operands k-contiguous,
   // 64-k slices three stages deep in a ring that overlays the (not yet used) dS^T buffer.  Wavefront w
   // computes token rows 32*(w % 4) .. +31, columns 32*(w / 4) .. +31.
@@ -976,15 +962,35 @@ __global__ __launch_bounds__(512) void sdpa_bwd_small_bf16(SdpaArgs a) {
     dma16(srcB + fk * 64, sp + A_BYTES);                                                           \
     ++fk;                                                                                          \
   }
+    VD_ISSUE(0)                         // the first slice goes ahead of the tile copies: the product starts on it
+    // copies of K, Q, V, O.  A wavefront-wide copy fills 8 token rows; rows past n repeat row n-1.
+    {
+      const bf16_t* src[5] = {a.k + base, a.q + base, a.v + base, nullptr, a.o + base};
 #pragma unroll
-    for (int s = 0; s < NS - 1; ++s)
+      for (int t = 0; t < 5; ++t) {
+        if (t == 3) continue;           // the dO tile is what this block computes
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          const int row = (u * 8 + wave) * 8 + (lane >> 3);
+          const int chunk = (lane & 7) ^ (row & 7);
+          dma16(src[t] + (long long)min(row, n - 1) * ld + chunk * 8, smem + t * kSmallTile + (u * 8 + wave) * 1024);
+        }
+      }
+    }
+    constexpr int kTileCopies = 8;      // per wavefront
+#pragma unroll
+    for (int s = 1; s < NS - 1; ++s)
       if (s < total) VD_ISSUE(s)
     for (int t0 = 0; t0 < total; t0 += NS) {
 #pragma unroll
       for (int s = 0; s < NS; ++s) {
         const int t = t0 + s;
         if (t < total) {
-          if (NS >= 3 && total - 1 - t >= 1) wait_vm<LPS>(); else wait_vm<0>();   // (the tile copies above are older: done too)
+          // slice t has landed once only younger copies are in flight: after slice 0 the tile copies and
+          // the slices issued with them, later the slices issued since (the tile copies are older: done too)
+          if (t == 0) {
+            if (NS >= 3 && total >= 2) wait_vm<kTileCopies + LPS>(); else wait_vm<kTileCopies>();
+          } else if (NS >= 3 && total - 1 - t >= 1) wait_vm<LPS>(); else wait_vm<0>();
           __builtin_amdgcn_s_barrier();
           if (t + NS - 1 < total) VD_ISSUE((s + NS - 1) % NS)
           const uint32_t so = s * STAGE;
@@ -1009,6 +1015,7 @@ __global__ __launch_bounds__(512) void sdpa_bwd_small_bf16(SdpaArgs a) {
       }
     }
 #undef VD_ISSUE
+    wait_vm<0>();                       // (with a single slice the tile copies can still be in flight here)
     // register 4*q4 + e of the accumulator is dO[32*blk + col][32*part + 8*q4 + 4*half + e]
     const int row = blk * 32 + col;
 #pragma unroll
@@ -1093,33 +1100,34 @@ __global__ __launch_bounds__(512) void sdpa_bwd_small_bf16(SdpaArgs a) {
   // query tiles that phase 1 skipped were never written: their dS^T columns are read below only for
   // queries >= n, whose results are not stored
   __syncthreads();                      // dS^T is complete; nobody reads the Q, V, dO, O tiles any more
-  if (part == 1) {                      // partial dK^T, dV^T of the upper query tiles: scratch[blk][register][lane]
-    float* sp = scratch + blk * (64 * 64) + lane;
+  // The two wavefronts of a key block join their partial sums through LDS: the lower one hands over its
+  // dV^T, the upper one its dK^T; then the lower one finishes and stores dK, the upper one dV.
+  // scratch[blk][part][16-byte register quad][lane]
+  {
+    float4* sp = reinterpret_cast<float4*>(scratch) + (blk * 2 + part) * (8 * 64) + lane;
+    const floatx16* give = part == 0 ? accV : accK;
 #pragma unroll
     for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        sp[(dt * 16 + r) * 64] = accK[dt][r];
-        sp[(32 + dt * 16 + r) * 64] = accV[dt][r];
-      }
+      for (int q4 = 0; q4 < 4; ++q4)
+        sp[(dt * 4 + q4) * 64] = make_float4(give[dt][4 * q4], give[dt][4 * q4 + 1], give[dt][4 * q4 + 2], give[dt][4 * q4 + 3]);
   }
   __syncthreads();
-  if (part == 0) {
-    const float* sp = scratch + blk * (64 * 64) + lane;
+  {
+    const float4* sp = reinterpret_cast<const float4*>(scratch) + (blk * 2 + (1 - part)) * (8 * 64) + lane;
+    floatx16* mine = part == 0 ? accK : accV;
 #pragma unroll
     for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        accK[dt][r] += sp[(dt * 16 + r) * 64];
-        accV[dt][r] += sp[(32 + dt * 16 + r) * 64];
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const float4 v = sp[(dt * 4 + q4) * 64];
+        mine[dt][4 * q4] += v.x; mine[dt][4 * q4 + 1] += v.y; mine[dt][4 * q4 + 2] += v.z; mine[dt][4 * q4 + 3] += v.w;
       }
     if (kj < n) {
-      bf16_t* rk = a.dk + base + (long long)kj * ld;
-      bf16_t* rv = a.dv + base + (long long)kj * ld;
-      store_accT(rk, accK[0], 0, half, a.scale);
-      store_accT(rk, accK[1], 1, half, a.scale);
-      store_accT(rv, accV[0], 0, half, 1.f);
-      store_accT(rv, accV[1], 1, half, 1.f);
+      bf16_t* row = (part == 0 ? a.dk : a.dv) + base + (long long)kj * ld;
+      const float mul = part == 0 ? a.scale : 1.f;
+      store_accT(row, mine[0], 0, half, mul);
+      store_accT(row, mine[1], 1, half, mul);
     }
   }
 
@@ -1291,7 +1299,7 @@ __global__ __launch_bounds__(512) void attn_fwd_small_bf16(FusedFwdArgs a) {
   unsigned char* Qs = smem;
   unsigned char* Ks = Qs + kSmallTile;
   unsigned char* Vs = Ks + kSmallTile;
-  float* merge = reinterpret_cast<float*>(Vs + kSmallTile);     // [query block][34 registers][lane]
+  float* merge = reinterpret_cast<float*>(Vs + kSmallTile);     // 16-byte aligned, 4 * 2 * 5 * 64 * 16 bytes
   __syncthreads();                       // every wavefront is done with the last slice
 #pragma unroll
   for (int j = 0; j < 3; ++j) {
@@ -1376,32 +1384,36 @@ __global__ __launch_bounds__(512) void attn_fwd_small_bf16(FusedFwdArgs a) {
       }
     }
   }
-  // merge the two key halves of a query block: the upper one hands over (m, l, out)
-  float* mp = merge + wr * (34 * 64) + lane;
-  if (wc == 1) {
+  // Merge the two key halves of a query block through LDS: each wavefront hands over its maximum, its
+  // sum and the half of its output that the other one finishes (the lower wavefront finishes head
+  // dimensions 0..31, the upper one 32..63).  merge[query block][giver][5 quads][lane]
+  {
+    float4* mp = reinterpret_cast<float4*>(merge) + (wr * 2 + wc) * (5 * 64) + lane;
+    const floatx16& give = wc == 0 ? out[1] : out[0];
 #pragma unroll
-    for (int dt = 0; dt < 2; ++dt)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) mp[(dt * 16 + r) * 64] = out[dt][r];
-    mp[32 * 64] = m;
-    mp[33 * 64] = l;
+    for (int q4 = 0; q4 < 4; ++q4)
+      mp[q4 * 64] = make_float4(give[4 * q4], give[4 * q4 + 1], give[4 * q4 + 2], give[4 * q4 + 3]);
+    mp[4 * 64] = make_float4(m, l, 0.f, 0.f);
   }
   __syncthreads();
-  if (wc == 0) {
-    const float m1 = mp[32 * 64], l1 = mp[33 * 64];
-    const float mm = fmaxf(m, m1);                       // finite: key 0 belongs to the lower half
-    const float f0 = fast_exp2(m - mm), f1 = fast_exp2(m1 - mm);
-    const float lsum = l * f0 + l1 * f1;
+  {
+    const float4* mp = reinterpret_cast<const float4*>(merge) + (wr * 2 + (1 - wc)) * (5 * 64) + lane;
+    const float4 stat = mp[4 * 64];
+    const float mm = fmaxf(m, stat.x);                   // finite: key 0 belongs to the lower half
+    const float f0 = fast_exp2(m - mm), f1 = fast_exp2(stat.x - mm);
+    const float lsum = l * f0 + stat.y * f1;
     if (qi < n) {
-      const float inv = 1.f / lsum;
+      floatx16 fin = wc == 0 ? out[0] : out[1];
 #pragma unroll
-      for (int dt = 0; dt < 2; ++dt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) out[dt][r] = out[dt][r] * f0 + mp[(dt * 16 + r) * 64] * f1;
-      bf16_t* orow = a.o + base + (long long)qi * ld;
-      store_accT(orow, out[0], 0, half, inv);
-      store_accT(orow, out[1], 1, half, inv);
-      if (half == 0) a.lse[((long long)b * a.H + h) * n + qi] = (mm + log2f(lsum)) * 0.6931471805599453f;
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const float4 v = mp[q4 * 64];
+        fin[4 * q4] = fin[4 * q4] * f0 + v.x * f1;
+        fin[4 * q4 + 1] = fin[4 * q4 + 1] * f0 + v.y * f1;
+        fin[4 * q4 + 2] = fin[4 * q4 + 2] * f0 + v.z * f1;
+        fin[4 * q4 + 3] = fin[4 * q4 + 3] * f0 + v.w * f1;
+      }
+      store_accT(a.o + base + (long long)qi * ld, fin, wc, half, 1.f / lsum);
+      if (wc == 0 && half == 0) a.lse[((long long)b * a.H + h) * n + qi] = (mm + log2f(lsum)) * 0.6931471805599453f;
     }
   }
 }
