@@ -920,7 +920,9 @@ __global__ __launch_bounds__(512) void sdpa_bwd_small_bf16(SdpaArgs a) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int blk = wave & 3, part = wave >> 2;
   const int col = lane & 31, half = lane >> 5;
-  const int h = blockIdx.x, b = blockIdx.y;
+  // heads fastest: a die's contiguous range covers whole batches, whose dy rows it then fetches once
+  const int tix = xcd_contiguous(blockIdx.x + gridDim.x * blockIdx.y, gridDim.x * gridDim.y);
+  const int h = tix % a.H, b = tix / a.H;
   const int n = a.n;
   const long long ld = a.d;
   const long long base = (long long)b * n * ld + h * kDh;
