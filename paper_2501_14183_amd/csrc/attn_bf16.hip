@@ -1,535 +1,18 @@
 // bf16 matrix-core back end of the multi-head attention (Eq. 3), forward and backward.
 //
-// All contractions run on v_mfma_f32_32x32x16_bf16 (bf16 operands, fp32 accumulation):
-//   * the projections and their gradients through one LDS-tiled GEMM kernel with three
-//     operand-layout variants;
-//   * softmax(Q K^T / sqrt(d_k)) V as a tiled online-softmax kernel (no n x n matrix is
-//     stored) that works on the TRANSPOSED score tile S^T = K Q^T: in the accumulator
-//     layout of the 32x32 instruction a lane then owns one query, so running maximum,
-//     running sum and rescaling are per-lane scalars, and the probability registers are
-//     directly the right-hand operand of O^T = V^T P^T;
-//   * the backward recomputes the probabilities from Q, K and the saved log-sum-exp in two
-//     kernels (dQ by query block, dK/dV by key block), so no atomics are needed and the
-//     result is deterministic.
-//
-// Operand layout of the instruction (64 lanes, half = lane / 32):
-//   A[i][k]: lane holds row i = lane % 32, eight k values of group `half`
-//   B[k][j]: lane holds column j = lane % 32, the same eight k values
-//   C[i][j]: lane holds column j = lane % 32, register r holds row 8*(r/4) + 4*half + r%4
-#include "common.h"
-
-typedef float floatx16 __attribute__((ext_vector_type(16)));
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // 16-byte unit of data movement (a native vector,
-                                                               // so that staging arrays stay in registers)
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+//   * softmax(Q K^T / sqrt(d_k)) V works on the TRANSPOSED score tile S^T = K Q^T: in the accumulator
+//     layout of the 32x32 instruction a lane then owns one query, so maximum, sum and rescaling are
+//     per-lane scalars, and the probability registers are directly the right-hand operand of
+//     O^T = V^T P^T;
+//   * the backward recomputes the probabilities from Q, K and the saved log-sum-exp; no atomics, so
+//     the result is deterministic;
+//   * short selections (n <= 128, what variate dropping leaves) have kernels of their own that keep a
+//     whole head in LDS: projection + attention forward, and dO + the whole attention backward;
+//   * the projections and their gradients are the GEMMs of gemm_bf16.hip.
+#include "bf16_mfma.h"
+#include "gemm_bf16.h"
 
 namespace {
-
-typedef uint16_t bf16_t;   // raw storage
-
-// fp32 -> bf16, round to nearest even (v_cvt_pk_bf16_f32)
-__device__ inline bf16_t f2bf(float f) { return __builtin_bit_cast(bf16_t, (__bf16)f); }
-__device__ inline float bf2f(bf16_t b) { return __uint_as_float((uint32_t)b << 16); }
-__device__ inline uint32_t pack2(float lo, float hi) {
-  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-  typedef float floatx2 __attribute__((ext_vector_type(2)));
-  const floatx2 v = {lo, hi};
-  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
-}
-
-// 2^x on the transcendental unit (v_exp_f32, 1 ulp): arguments here are <= 0 or -inf, results below the
-// normal range may flush to zero
-__device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
-
-union Frag {
-  u32x4 q;
-  u32x2 d[2];
-  uint32_t w[4];
-  bf16_t h[8];
-  bf16x8 v;
-};
-
-__device__ inline floatx16 zero16() {
-  floatx16 z = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  return z;
-}
-__device__ inline floatx16 mfma(const Frag& a, const Frag& b, floatx16 c) {
-  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, b.v, c, 0, 0, 0);
-}
-// eight accumulator registers (8*s2 .. 8*s2+7) as a bf16 right-hand operand
-__device__ inline Frag regs_to_frag(const floatx16& p, int s2) {
-  Frag f;
-#pragma unroll
-  for (int e = 0; e < 4; ++e) f.w[e] = pack2(p[8 * s2 + 2 * e], p[8 * s2 + 2 * e + 1]);
-  return f;
-}
-
-// ================================================================== GEMM arguments
-// Up to four batch entries (grid z) or three accumulated segments.  Named fields rather than arrays so
-// that the argument block is never indexed at run time (that would force it into private memory).
-struct GemmBf16 {
-  const bf16_t *A0, *A1, *A2, *A3;
-  const bf16_t *B0, *B1, *B2, *B3;
-  void *C0, *C1, *C2, *C3;
-  const bf16_t *bias0, *bias1, *bias2, *bias3;
-  int lda, ldb, ldc;
-  int M, N, K;
-  int nseg;           // > 1: segments accumulate into C0
-  int splitk;         // > 1: grid.z = batches * splitk, slice s writes fp32 to C0 + (z * splitk + s) * M * N
-  int kchunk;         // K elements per slice (multiple of 64)
-  void set(int z, const void* a, const void* b, void* c, const void* bias) {
-    const bf16_t* pa = (const bf16_t*)a;
-    const bf16_t* pb = (const bf16_t*)b;
-    const bf16_t* pbias = (const bf16_t*)bias;
-    switch (z) {
-      case 0: A0 = pa; B0 = pb; C0 = c; bias0 = pbias; break;
-      case 1: A1 = pa; B1 = pb; C1 = c; bias1 = pbias; break;
-      case 2: A2 = pa; B2 = pb; C2 = c; bias2 = pbias; break;
-      default: A3 = pa; B3 = pb; C3 = c; bias3 = pbias; break;
-    }
-  }
-};
-
-// out[z][i] = sum_s part[(z * splitk + s)][i], slices added in ascending order
-struct SplitkReduce {
-  const float* part;
-  float* out[4];
-  long long count;     // elements per matrix
-  int splitk;
-};
-__global__ __launch_bounds__(256) void splitk_reduce_kernel(SplitkReduce a) {
-  const int z = blockIdx.y;
-  const float4* src = reinterpret_cast<const float4*>(a.part + (long long)z * a.splitk * a.count);
-  float4* dst = reinterpret_cast<float4*>(a.out[z]);
-  const long long n4 = a.count >> 2;
-  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += (long long)gridDim.x * blockDim.x) {
-    float4 s = src[i];
-    for (int k = 1; k < a.splitk; ++k) {
-      const float4 v = src[(long long)k * n4 + i];
-      s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
-    }
-    dst[i] = s;
-  }
-}
-
-// ================================================================== GEMM with asynchronous LDS fill
-// C[z] = op(A[z]) * op(B[z]) (+ bias[z]) in bf16, the sum over up to three segments into C[0], or
-// (SPLIT) an fp32 partial product per K slice.  Each operand is either k-contiguous ([M][K] / [N][K])
-// or mn-contiguous ([K][M] / [K][N]).
-//
-// Global memory is copied straight into LDS (global_load_lds_dwordx4: every lane names its own 16
-// source bytes, the wavefront's 64 chunks land in 1 KB of consecutive LDS), NS stages deep, so
-// that the copies of the next NS-1 slices are in flight while the matrix cores work on the
-// current one and no register or LDS-store instruction is spent on staging.  Because the LDS side
-// of a copy is fixed, the bank swizzle is applied on the source side: LDS chunk position p of a row
-// holds source chunk p ^ pattern(row).
-//   k-contiguous operand:  LDS tile [row][BK], fragments are 16-byte reads (row = lane % 32,
-//                          chunk 2*ks + lane / 32), pattern chosen so that eight consecutive rows
-//                          spread over all banks.
-//   mn-contiguous operand: LDS tile [k][W]; fragments come from the transposing read
-//                          ds_read_b64_tr_b16, in which, inside each group of 16 lanes, lane s names
-//                          four consecutive columns of k-row s / 4 at column block s % 4, and lane j
-//                          receives column j of the four k-rows.  A slice that reaches past the end
-//                          of K (weight gradients: K is the token count) is copied from clamped
-//                          rows and the left operand's fragments are masked.
-// Fragment reads and the wait counters are written out by hand: the compiler would otherwise wait
-// for every outstanding copy before any LDS read.
-// The product is formed transposed (the B fragment is the left operand of the instruction), so a
-// lane owns one output row and four consecutive columns per register quad; the tile goes through
-// LDS once more so that global stores are whole 16-byte chunks of consecutive rows.
-__device__ inline void dma16(const bf16_t* gp, unsigned char* lp) {
-  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gp,
-                                   (__attribute__((address_space(3))) void*)lp, 16, 0, 0);
-}
-__device__ inline void lds_read16(u32x4& dst, uint32_t addr) {
-  asm volatile("ds_read_b128 %0, %1" : "=v"(dst) : "v"(addr) : "memory");
-}
-template <int OFF>
-__device__ inline void lds_read8_tr(u32x2& dst, uint32_t addr) {
-  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFF) : "memory");
-}
-template <int N>
-__device__ inline void wait_vm() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
-// waits until at most N LDS reads are outstanding; the fragments are operands so that their uses stay behind it
-template <int N>
-__device__ inline void wait_lds(Frag& a, Frag& b, Frag& c, Frag& d) {
-  asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a.q), "+v"(b.q), "+v"(c.q), "+v"(d.q) : "n"(N));
-}
-template <int N>
-__device__ inline void wait_lds(Frag& a, Frag& b, Frag& c) {
-  asm volatile("s_waitcnt lgkmcnt(%3)" : "+v"(a.q), "+v"(b.q), "+v"(c.q) : "n"(N));
-}
-template <int N>
-__device__ inline void wait_lds(Frag& a, Frag& b) {
-  asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a.q), "+v"(b.q) : "n"(N));
-}
-
-template <int BK>
-__device__ inline int swz_kc(int row) { return BK == 32 ? (row >> 1) & 3 : row & 7; }
-template <int W>
-__device__ inline int swz_nc(int krow) { return W == 128 ? (((krow & 3) << 1) ^ (((krow >> 3) & 1) << 3)) : ((krow & 3) << 1); }
-// zeroes the elements k >= kvalid of a fragment holding k = 0..7
-__device__ inline void mask_frag(Frag& f, int kvalid) {
-#pragma unroll
-  for (int e = 0; e < 4; ++e)
-    f.w[e] &= kvalid >= 2 * e + 2 ? 0xffffffffu : (kvalid == 2 * e + 1 ? 0x0000ffffu : 0u);
-}
-
-template <bool AKC, bool BKC, bool SPLIT, int BM, int BK, int NS>
-__device__ __forceinline__ void gemm_async_tile(const GemmBf16& g, const int bx, const int by, const int bz) {
-  constexpr int BN = 128, MI = BM / 64, KS = BK / 16;
-  constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE = A_BYTES + B_BYTES;
-  constexpr int IA = A_BYTES / 4096, IB = B_BYTES / 4096, LPS = IA + IB;   // 1 KB copies per wavefront and stage
-  constexpr int CH = BK / 8;                                              // 16-byte chunks per k-contiguous row
-  constexpr int RPI = 64 / CH;                                            // ... and rows per copy instruction
-  constexpr int CHA = BM / 8, RPA = 64 / CHA;                             // the same for an [k][BM] tile
-  constexpr int CHB = BN / 8, RPB = 64 / CHB;                             // and an [k][BN] tile
-  constexpr int OPK = (AKC ? MI : 2 * MI) + (BKC ? 2 : 4);                // LDS reads per 16-k step
-  constexpr int ES = SPLIT ? 4 : 2;                                       // output element size
-  constexpr int CPITCH = BN * ES + 16;                                    // LDS row pitch of the output tile
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
-  const int col = lane & 31, half = lane >> 5;
-  const int zb = SPLIT ? bz / g.splitk : bz;
-  const int kbeg = SPLIT ? (bz % g.splitk) * g.kchunk : 0;
-  const int kend = SPLIT ? min(g.K, kbeg + g.kchunk) : g.K;
-  const int m0 = by * BM, n0 = bx * BN;
-  const int nseg = g.nseg > 1 ? g.nseg : 1;
-  const int nk = (kend - kbeg + BK - 1) / BK;
-  const int total = nseg * nk;
-  const int zsel = g.nseg > 1 ? 0 : zb;
-  const bf16_t* A1 = g.A1; const bf16_t* B1 = g.B1;
-  const bf16_t* A2 = g.A2; const bf16_t* B2 = g.B2;
-  const bf16_t* A0 = zsel == 0 ? g.A0 : (zsel == 1 ? A1 : (zsel == 2 ? A2 : g.A3));
-  const bf16_t* B0 = zsel == 0 ? g.B0 : (zsel == 1 ? B1 : (zsel == 2 ? B2 : g.B3));
-
-  // ---- source offsets of this lane's copies (elements)
-  //   k-contiguous: clamped row * ld + chunk * 8, the slice start is added per stage
-  //   mn-contiguous: column offset; the k-row (first one in goffX[u] >> 16... kept separately) is clamped per stage
-  int goffA[IA], goffB[IB];
-  int krowA = 0, krowB = 0;                 // k-row of copy 0 (mn-contiguous); copy u adds u * 4 * RPx
-#pragma unroll
-  for (int u = 0; u < IA; ++u) {
-    if constexpr (AKC) {
-      const int row = (u * 4 + wave) * RPI + lane / CH;
-      goffA[u] = min(m0 + row, g.M - 1) * g.lda + ((lane % CH) ^ swz_kc<BK>(row)) * 8;
-    } else {
-      const int krow = (u * 4 + wave) * RPA + lane / CHA;
-      if (u == 0) krowA = krow;
-      goffA[u] = min(m0 + ((lane % CHA) ^ swz_nc<BM>(krow)) * 8, g.M - 8);
-    }
-  }
-#pragma unroll
-  for (int u = 0; u < IB; ++u) {
-    if constexpr (BKC) {
-      const int row = (u * 4 + wave) * RPI + lane / CH;
-      goffB[u] = min(n0 + row, g.N - 1) * g.ldb + ((lane % CH) ^ swz_kc<BK>(row)) * 8;
-    } else {
-      const int krow = (u * 4 + wave) * RPB + lane / CHB;
-      if (u == 0) krowB = krow;
-      goffB[u] = min(n0 + ((lane % CHB) ^ swz_nc<BN>(krow)) * 8, g.N - 8);
-    }
-  }
-  // ---- fragment addresses (LDS bytes relative to a stage)
-  const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
-  uint32_t addrA[MI][AKC ? KS : 1], addrB[2][BKC ? KS : 1];
-#pragma unroll
-  for (int i = 0; i < MI; ++i) {
-    if constexpr (AKC) {
-      const int ra = wm * (BM / 2) + i * 32 + col;
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) addrA[i][ks] = lds0 + ra * (BK * 2) + (((2 * ks + half) ^ swz_kc<BK>(ra)) * 16);
-    } else {
-      const int krow = 8 * half + ((lane & 15) >> 2);
-      const int mn = wm * (BM / 2) + i * 32 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-      addrA[i][0] = lds0 + krow * (BM * 2) + (((mn >> 3) ^ swz_nc<BM>(krow)) * 16) + ((mn >> 2) & 1) * 8;
-    }
-  }
-#pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    if constexpr (BKC) {
-      const int rb = wn * 64 + j * 32 + col;
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks)
-        addrB[j][ks] = lds0 + A_BYTES + rb * (BK * 2) + (((2 * ks + half) ^ swz_kc<BK>(rb)) * 16);
-    } else {
-      const int krow = 8 * half + ((lane & 15) >> 2);
-      const int mn = wn * 64 + j * 32 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-      addrB[j][0] = lds0 + A_BYTES + krow * (BN * 2) + (((mn >> 3) ^ swz_nc<BN>(krow)) * 16) + ((mn >> 2) & 1) * 8;
-    }
-  }
-
-  floatx16 acc[MI][2];
-#pragma unroll
-  for (int i = 0; i < MI; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j) acc[i][j] = zero16();
-
-  // ---- copy cursor
-  int fseg = 0, fk = kbeg;
-  const bf16_t* Ap = A0;
-  const bf16_t* Bp = B0;
-#define VD_ISSUE_STAGE(BUF)                                                                        \
-  {                                                                                                \
-    unsigned char* sp = smem + (BUF) * STAGE + wave * 1024;                                        \
-    _Pragma("unroll") for (int u = 0; u < IA; ++u) {                                               \
-      const bf16_t* p;                                                                             \
-      if constexpr (AKC) p = Ap + fk + goffA[u];                                                   \
-      else p = Ap + (long long)min(fk + krowA + u * 4 * RPA, kend - 1) * g.lda + goffA[u];         \
-      dma16(p, sp + u * 4096);                                                                     \
-    }                                                                                              \
-    _Pragma("unroll") for (int u = 0; u < IB; ++u) {                                               \
-      const bf16_t* p;                                                                             \
-      if constexpr (BKC) p = Bp + fk + goffB[u];                                                   \
-      else p = Bp + (long long)min(fk + krowB + u * 4 * RPB, kend - 1) * g.ldb + goffB[u];         \
-      dma16(p, sp + A_BYTES + u * 4096);                                                           \
-    }                                                                                              \
-    fk += BK;                                                                                      \
-    if (fk >= kend) {                                                                              \
-      fk = kbeg;                                                                                   \
-      ++fseg;                                                                                      \
-      Ap = fseg == 1 ? A1 : A2;                                                                    \
-      Bp = fseg == 1 ? B1 : B2;                                                                    \
-    }                                                                                              \
-  }
-#pragma unroll
-  for (int s = 0; s < NS - 1; ++s)
-    if (s < total) VD_ISSUE_STAGE(s)
-
-  for (int t0 = 0; t0 < total; t0 += NS) {
-#pragma unroll
-    for (int s = 0; s < NS; ++s) {
-      const int t = t0 + s;
-      if (t < total) {
-        // slice t has landed once at most `ahead` younger stages are still in flight
-        const int ahead = min(total - 1 - t, NS - 2);
-        if (NS >= 4 && ahead >= 2) wait_vm<2 * LPS>();
-        else if (NS >= 3 && ahead == 1) wait_vm<LPS>();
-        else wait_vm<0>();
-        __builtin_amdgcn_s_barrier();     // everyone's copies of slice t are in; everyone is done with slice t-1
-        if (t + NS - 1 < total) VD_ISSUE_STAGE((s + NS - 1) % NS)
-        const uint32_t so = s * STAGE;
-        // valid k of this lane's first fragment; only the last slice of an mn-contiguous A can fall short
-        int kvalid = 8;
-        if constexpr (!AKC) kvalid = t == total - 1 ? kend - (kbeg + (nk - 1) * BK + 8 * half) : 8 + 16 * KS;
-        Frag fa[2][2], fb[2][2];
-#define VD_READ_STEP(KS_, SET)                                                                     \
-  {                                                                                                \
-    _Pragma("unroll") for (int i = 0; i < MI; ++i) {                                               \
-      if constexpr (AKC) {                                                                         \
-        lds_read16(fa[SET][i].q, addrA[i][AKC ? (KS_) : 0] + so);                                  \
-      } else {                                                                                     \
-        lds_read8_tr<(KS_) * 16 * BM * 2>(fa[SET][i].d[0], addrA[i][0] + so);                      \
-        lds_read8_tr<(KS_) * 16 * BM * 2 + 4 * BM * 2>(fa[SET][i].d[1], addrA[i][0] + so);         \
-      }                                                                                            \
-    }                                                                                              \
-    _Pragma("unroll") for (int j = 0; j < 2; ++j) {                                                \
-      if constexpr (BKC) {                                                                         \
-        lds_read16(fb[SET][j].q, addrB[j][BKC ? (KS_) : 0] + so);                                  \
-      } else {                                                                                     \
-        lds_read8_tr<(KS_) * 16 * BN * 2>(fb[SET][j].d[0], addrB[j][0] + so);                      \
-        lds_read8_tr<(KS_) * 16 * BN * 2 + 4 * BN * 2>(fb[SET][j].d[1], addrB[j][0] + so);         \
-      }                                                                                            \
-    }                                                                                              \
-  }
-#define VD_MFMA_STEP(KS_, SET, PENDING)                                                            \
-  {                                                                                                \
-    if constexpr (MI == 2) wait_lds<PENDING>(fa[SET][0], fa[SET][1], fb[SET][0], fb[SET][1]);      \
-    else wait_lds<PENDING>(fa[SET][0], fb[SET][0], fb[SET][1]);                                    \
-    if constexpr (!AKC) {                                                                          \
-      if (kvalid - 16 * (KS_) < 8) {                                                               \
-        _Pragma("unroll") for (int i = 0; i < MI; ++i) mask_frag(fa[SET][i], kvalid - 16 * (KS_)); \
-      }                                                                                            \
-    }                                                                                              \
-    _Pragma("unroll") for (int i = 0; i < MI; ++i)                                                 \
-      _Pragma("unroll") for (int j = 0; j < 2; ++j) acc[i][j] = mfma(fb[SET][j], fa[SET][i], acc[i][j]); \
-    __builtin_amdgcn_sched_barrier(0);                                                             \
-  }
-        VD_READ_STEP(0, 0)
-        if constexpr (KS == 2) {
-          VD_READ_STEP(1, 1)
-          VD_MFMA_STEP(0, 0, OPK)
-          VD_MFMA_STEP(1, 1, 0)
-        } else {
-          VD_READ_STEP(1, 1)
-          VD_MFMA_STEP(0, 0, OPK)
-          VD_READ_STEP(2, 0)
-          VD_MFMA_STEP(1, 1, OPK)
-          VD_READ_STEP(3, 1)
-          VD_MFMA_STEP(2, 0, OPK)
-          VD_MFMA_STEP(3, 1, 0)
-        }
-#undef VD_READ_STEP
-#undef VD_MFMA_STEP
-      }
-    }
-  }
-#undef VD_ISSUE_STAGE
-
-  // ---- epilogue.  acc[i][j] register 4*q4 + e is C[wm*BM/2 + i*32 + col][wn*64 + j*32 + 8*q4 + 4*half + e]
-  // of the tile; it is written to LDS (with the bias), then stored as 16-byte chunks of whole rows.
-  const bf16_t* bias = SPLIT ? nullptr : (zsel == 0 ? g.bias0 : (zsel == 1 ? g.bias1 : (zsel == 2 ? g.bias2 : g.bias3)));
-  __syncthreads();                        // every wavefront is done reading the last slice
-#pragma unroll
-  for (int j = 0; j < 2; ++j)
-#pragma unroll
-    for (int q4 = 0; q4 < 4; ++q4) {
-      const int nl = wn * 64 + j * 32 + 8 * q4 + 4 * half;
-      float bv[4] = {0.f, 0.f, 0.f, 0.f};
-      if (bias && n0 + nl < g.N) {                 // N is a multiple of 8: a quad is inside or outside
-        const u32x2 b4 = *reinterpret_cast<const u32x2*>(bias + n0 + nl);
-        bv[0] = __uint_as_float(b4.x << 16); bv[1] = __uint_as_float(b4.x & 0xffff0000u);
-        bv[2] = __uint_as_float(b4.y << 16); bv[3] = __uint_as_float(b4.y & 0xffff0000u);
-      }
-#pragma unroll
-      for (int i = 0; i < MI; ++i) {
-        unsigned char* p = smem + (wm * (BM / 2) + i * 32 + col) * CPITCH + nl * ES;
-        if constexpr (SPLIT) {
-          float4 o = make_float4(acc[i][j][4 * q4], acc[i][j][4 * q4 + 1], acc[i][j][4 * q4 + 2], acc[i][j][4 * q4 + 3]);
-          *reinterpret_cast<float4*>(p) = o;
-        } else {
-          u32x2 o;
-          o.x = pack2(acc[i][j][4 * q4] + bv[0], acc[i][j][4 * q4 + 1] + bv[1]);
-          o.y = pack2(acc[i][j][4 * q4 + 2] + bv[2], acc[i][j][4 * q4 + 3] + bv[3]);
-          *reinterpret_cast<u32x2*>(p) = o;
-        }
-      }
-    }
-  __syncthreads();
-  constexpr int CPR = BN * ES / 16;          // 16-byte chunks per tile row
-  constexpr int EPC = 16 / ES;               // elements per chunk
-  unsigned char* Cb;
-  long long ldc_bytes;
-  if constexpr (SPLIT) {
-    if (g.splitk > 1) {      // partial product of slice bz % splitk of matrix bz / splitk
-      Cb = reinterpret_cast<unsigned char*>(g.C0) + (long long)bz * g.M * g.N * 4;
-      ldc_bytes = (long long)g.N * 4;
-    } else {                 // a single slice is the result itself
-      Cb = reinterpret_cast<unsigned char*>(zsel == 0 ? g.C0 : (zsel == 1 ? g.C1 : (zsel == 2 ? g.C2 : g.C3)));
-      ldc_bytes = (long long)g.ldc * 4;
-    }
-  } else {
-    Cb = reinterpret_cast<unsigned char*>(zsel == 0 ? g.C0 : (zsel == 1 ? g.C1 : (zsel == 2 ? g.C2 : g.C3)));
-    ldc_bytes = (long long)g.ldc * 2;
-  }
-#pragma unroll
-  for (int u = 0; u < BM * CPR / 256; ++u) {
-    const int idx = u * 256 + threadIdx.x;
-    const int row = idx / CPR, c = idx % CPR;
-    if (m0 + row < g.M && n0 + c * EPC < g.N) {
-      const u32x4 v = *reinterpret_cast<const u32x4*>(smem + row * CPITCH + c * 16);
-      *reinterpret_cast<u32x4*>(Cb + (long long)(m0 + row) * ldc_bytes + (long long)(n0 + c * EPC) * ES) = v;
-    }
-  }
-}
-
-// LDS a workgroup of the asynchronous GEMM needs: the staging ring, or the output tile if that is larger
-template <bool SPLIT, int BM, int BK, int NS>
-constexpr int gemm_async_lds() {
-  constexpr int ring = NS * (BM + 128) * BK * 2, out = BM * (128 * (SPLIT ? 4 : 2) + 16);
-  return ring > out ? ring : out;
-}
-// Workgroups are handed to the eight accelerator dies (XCDs) in turn, and every die has an L2 of its
-// own.  These helpers turn a workgroup's linear id into its place in an order in which each die works
-// through ONE contiguous range of the tiles, so that tiles sharing an operand meet in the same L2
-// instead of each die fetching its own copy from memory.
-__device__ inline int xcd_range_start(int xcd, int total) { return xcd * (total >> 3) + min(xcd, total & 7); }
-__device__ inline int xcd_contiguous(int id, int total) { return xcd_range_start(id & 7, total) + (id >> 3); }
-
-template <bool AKC, bool BKC, bool SPLIT, int BM, int BK, int NS>
-__global__ __launch_bounds__(256, 2) void gemm_async_kernel(GemmBf16 g) {
-  // tiles in the order n fastest, then m, then batch entry: a die's range shares its rows of A
-  const int gx = gridDim.x, gy = gridDim.y;
-  const int t = xcd_contiguous(blockIdx.x + gx * (blockIdx.y + gy * blockIdx.z), gx * gy * gridDim.z);
-  gemm_async_tile<AKC, BKC, SPLIT, BM, BK, NS>(g, t % gx, (t / gx) % gy, t / (gx * gy));
-}
-// The input gradient (gx: k-contiguous operands, up to three accumulated segments) and the weight
-// gradients (gw: mn-contiguous operands, K slices, fp32 partial products) depend on the same dQ, dK,
-// dV and on nothing of each other, so they share one launch: workgroups [0, nx) take tiles of gx,
-// the rest tiles of gw.  The longer-running input-gradient tiles are dispatched first.
-template <int BMX>
-__global__ __launch_bounds__(256, 2) void gemm_bwd_pair_kernel(GemmBf16 gx, GemmBf16 gw, int nx, int gxn, int gwn, int gwm) {
-  // Each die takes a contiguous range of the input-gradient tiles (n fastest: a range shares its rows
-  // of dQ, dK, dV) and a contiguous range of the weight-gradient tiles (n, then m, then K slice, then
-  // matrix: a range shares its K slice of both operands); its input-gradient tiles come first.
-  const int nw = (int)gridDim.x - nx;
-  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-  const int cntx = (nx >> 3) + (xcd < (nx & 7) ? 1 : 0);
-  const int startx = xcd_range_start(xcd, nx);
-  if (slot < cntx) {
-    const int t = startx + slot;
-    gemm_async_tile<true, true, false, BMX, 64, 2>(gx, t % gxn, t / gxn, 0);
-  } else {
-    const int t = xcd_range_start(xcd, nx + nw) - startx + (slot - cntx);
-    gemm_async_tile<false, false, true, 128, 64, 2>(gw, t % gwn, (t / gwn) % gwm, t / (gwn * gwm));
-  }
-}
-
-// Tile and pipeline depth of the asynchronous GEMM: 128 x 128 tiles once there are enough of them to
-// keep every compute unit busy with two workgroups; otherwise 64 x 128 tiles, three stages deep while
-// two workgroups still fit beside each other in LDS (at most 512 tiles), else two stages and three
-// workgroups per compute unit.
-template <bool AKC, bool BKC, bool SPLIT, int BM, int NS>
-int launch_gemm_async_cfg(vardrop_ctx* ctx, int kid, const GemmBf16& g, int nz, hipStream_t s) {
-  constexpr int BK = 64;
-  constexpr int lds = gemm_async_lds<SPLIT, BM, BK, NS>();
-  static int configured_device = -1;     // raising the dynamic LDS limit is a per-device, per-function setting
-  if (configured_device != ctx->device) {
-    VD_HIP(ctx, hipFuncSetAttribute((const void*)gemm_async_kernel<AKC, BKC, SPLIT, BM, BK, NS>,
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, lds));
-    configured_device = ctx->device;
-  }
-  dim3 grid(vd_ceil_div(g.N, 128), vd_ceil_div(g.M, BM), nz * (SPLIT ? g.splitk : 1));
-  {
-    VdTimer timer(ctx, kid, s);
-    hipLaunchKernelGGL((gemm_async_kernel<AKC, BKC, SPLIT, BM, BK, NS>), grid, dim3(256), lds, s, g);
-  }
-  VD_LAUNCH_CHECK(ctx);
-  return VARDROP_OK;
-}
-// one launch for the input gradient gx and the sliced weight gradients gw (nzw matrices)
-template <int BMX>
-int launch_gemm_bwd_pair_cfg(vardrop_ctx* ctx, const GemmBf16& gx, const GemmBf16& gw, int nzw, hipStream_t s) {
-  constexpr int ldsx = gemm_async_lds<false, BMX, 64, 2>(), ldsw = gemm_async_lds<true, 128, 64, 2>();
-  constexpr int lds = ldsx > ldsw ? ldsx : ldsw;
-  static int configured_device = -1;
-  if (configured_device != ctx->device) {
-    VD_HIP(ctx, hipFuncSetAttribute((const void*)gemm_bwd_pair_kernel<BMX>, hipFuncAttributeMaxDynamicSharedMemorySize, lds));
-    configured_device = ctx->device;
-  }
-  const int gxn = vd_ceil_div(gx.N, 128), gxm = vd_ceil_div(gx.M, BMX);
-  const int gwn = vd_ceil_div(gw.N, 128), gwm = vd_ceil_div(gw.M, 128);
-  const int nx = gxn * gxm, nw = gwn * gwm * nzw * gw.splitk;
-  {
-    VdTimer timer(ctx, VARDROP_K_GEMM_DW_DXS, s);
-    hipLaunchKernelGGL(gemm_bwd_pair_kernel<BMX>, dim3(nx + nw), dim3(256), lds, s, gx, gw, nx, gxn, gwn, gwm);
-  }
-  VD_LAUNCH_CHECK(ctx);
-  return VARDROP_OK;
-}
-int launch_gemm_bwd_pair(vardrop_ctx* ctx, const GemmBf16& gx, const GemmBf16& gw, int nzw, hipStream_t s) {
-  if (gx.K % 64 != 0 || gx.N % 8 != 0 || (long long)gx.M * gx.lda >= (1ll << 31) || (long long)gx.N * gx.ldb >= (1ll << 31) ||
-      gw.M % 8 != 0 || gw.N % 8 != 0 || gw.kchunk % 64 != 0 || gw.splitk < 1 ||
-      (long long)gw.K * gw.lda >= (1ll << 31) || (long long)gw.K * gw.ldb >= (1ll << 31))
-    return VARDROP_EUNSUPPORTED;
-  const long long t128 = (long long)vd_ceil_div(gx.N, 128) * vd_ceil_div(gx.M, 128);
-  if (t128 >= 1024) return launch_gemm_bwd_pair_cfg<128>(ctx, gx, gw, nzw, s);
-  return launch_gemm_bwd_pair_cfg<64>(ctx, gx, gw, nzw, s);
-}
-
-template <bool BKC>
-int launch_gemm_async(vardrop_ctx* ctx, int kid, const GemmBf16& g, int nz, hipStream_t s) {
-  if (g.M == 0 || g.N == 0) return VARDROP_OK;
-  if (g.K % 64 != 0 || g.N % 8 != 0 || (long long)g.M * g.lda >= (1ll << 31) || (long long)g.K * g.ldb >= (1ll << 31))
-    return VARDROP_EUNSUPPORTED;
-  const long long t128 = (long long)vd_ceil_div(g.N, 128) * vd_ceil_div(g.M, 128) * nz;
-  const long long t64 = (long long)vd_ceil_div(g.N, 128) * vd_ceil_div(g.M, 64) * nz;
-  if (t128 >= 1024) return launch_gemm_async_cfg<true, BKC, false, 128, 2>(ctx, kid, g, nz, s);
-  if (t64 <= 512) return launch_gemm_async_cfg<true, BKC, false, 64, 3>(ctx, kid, g, nz, s);
-  return launch_gemm_async_cfg<true, BKC, false, 64, 2>(ctx, kid, g, nz, s);
-}
 
 // ================================================================== attention core (d_k = 64)
 constexpr int kDh = 64;
@@ -1518,7 +1001,7 @@ int vd_attn_fwd_bf16(vardrop_ctx* ctx, const void* xs, int B, int n, int d, int 
     for (int z = 0; z < 3; ++z) g.set(z, xs, W[z], qkv[z], bias[z]);
     g.lda = d; g.ldb = d; g.ldc = d;
     g.M = (int)M; g.N = d; g.K = d; g.nseg = 1;
-    rc = launch_gemm_async<false>(ctx, VARDROP_K_GEMM_QKV, g, 3, s);
+    rc = vd_gemm_bf16(ctx, VARDROP_K_GEMM_QKV, g, 3, false, s);
     if (rc) return rc;
     SdpaArgs a = {};
     a.q = q; a.k = k; a.v = v; a.out = o; a.lse = lse;
@@ -1530,7 +1013,7 @@ int vd_attn_fwd_bf16(vardrop_ctx* ctx, const void* xs, int B, int n, int d, int 
   go.set(0, o, W[3], y, bias[3]);
   go.lda = d; go.ldb = d; go.ldc = d;
   go.M = (int)M; go.N = d; go.K = d; go.nseg = 1;
-  return launch_gemm_async<false>(ctx, VARDROP_K_GEMM_OUT, go, 1, s);
+  return vd_gemm_bf16(ctx, VARDROP_K_GEMM_OUT, go, 1, false, s);
 }
 
 // ws: dO, dq, dk, dv ([M][d] bf16 each), D fp32 [B][H][n], then the split-K partial products
@@ -1554,7 +1037,7 @@ int vd_attn_bwd_bf16(vardrop_ctx* ctx, const void* dy, const void* xs, int B, in
     g.set(0, dy, W[3], dO, nullptr);
     g.lda = d; g.ldb = d; g.ldc = d;
     g.M = (int)M; g.N = d; g.K = d; g.nseg = 1;
-    if ((rc = launch_gemm_async<true>(ctx, VARDROP_K_GEMM_DO, g, 1, s))) return rc;
+    if ((rc = vd_gemm_bf16(ctx, VARDROP_K_GEMM_DO, g, 1, true, s))) return rc;
   }
   SdpaArgs a = {};
   a.q = q; a.k = k; a.v = v; a.o = o; a.dout = dO; a.lse = const_cast<float*>(lse);
@@ -1596,23 +1079,11 @@ int vd_attn_bwd_bf16(vardrop_ctx* ctx, const void* dy, const void* xs, int B, in
     if (gw.splitk > 1) {
       float* part = (float*)((char*)ws + vd_attn_bf16_partial_offset(B, n, d, H));
       gw.C0 = part;
-      if ((rc = launch_gemm_bwd_pair(ctx, gx, gw, 4, s))) return rc;
-      SplitkReduce r = {};
-      r.part = part;
-      for (int z = 0; z < 4; ++z) r.out[z] = dW[z];
-      r.count = (long long)d * d;
-      r.splitk = gw.splitk;
-      {
-        VdTimer timer(ctx, VARDROP_K_REDUCE_DW, s);
-        hipLaunchKernelGGL(splitk_reduce_kernel, dim3(vd_ceil_div(d * d / 4, 256), 4), dim3(256), 0, s, r);
-      }
-      VD_LAUNCH_CHECK(ctx);
+      if ((rc = vd_gemm_bf16_bwd_pair(ctx, gx, gw, 4, s))) return rc;
+      if ((rc = vd_gemm_bf16_sum_slices(ctx, part, dW, (long long)d * d, gw.splitk, s))) return rc;
     } else {   // few tokens: one slice, written directly
-      if (gw.M % 8 != 0 || (long long)gw.K * gw.lda >= (1ll << 31)) return VARDROP_EUNSUPPORTED;
-      gw.splitk = 1;
-      gw.kchunk = (int)vd_align_up((size_t)gw.K, 64);
-      if ((rc = launch_gemm_async_cfg<false, false, true, 64, 2>(ctx, VARDROP_K_GEMM_DW, gw, 4, s))) return rc;
-      if ((rc = launch_gemm_async<true>(ctx, VARDROP_K_GEMM_DXS, gx, 1, s))) return rc;
+      if ((rc = vd_gemm_bf16_wgrad(ctx, VARDROP_K_GEMM_DW, gw, 4, s))) return rc;
+      if ((rc = vd_gemm_bf16(ctx, VARDROP_K_GEMM_DXS, gx, 1, true, s))) return rc;
     }
   }
   if (db[0] || db[1] || db[2] || db[3]) {
@@ -1625,3 +1096,4 @@ int vd_attn_bwd_bf16(vardrop_ctx* ctx, const void* dy, const void* xs, int B, in
   }
   return VARDROP_OK;
 }
+

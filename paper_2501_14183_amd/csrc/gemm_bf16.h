@@ -1,0 +1,44 @@
+// bf16 GEMM entry points shared by the attention back end (gemm_bf16.hip).
+#ifndef VARDROP_GEMM_BF16_H
+#define VARDROP_GEMM_BF16_H
+#include "common.h"
+
+typedef uint16_t bf16_t;   // raw storage
+
+// Up to four batch entries (grid z) or three accumulated segments.  Named fields rather than arrays so
+// that the argument block is never indexed at run time (that would force it into private memory).
+struct GemmBf16 {
+  const bf16_t *A0, *A1, *A2, *A3;
+  const bf16_t *B0, *B1, *B2, *B3;
+  void *C0, *C1, *C2, *C3;
+  const bf16_t *bias0, *bias1, *bias2, *bias3;
+  int lda, ldb, ldc;
+  int M, N, K;
+  int nseg;           // > 1: segments accumulate into C0
+  int splitk;         // > 1: grid.z = batches * splitk, slice s writes fp32 to C0 + (z * splitk + s) * M * N
+  int kchunk;         // K elements per slice (multiple of 64)
+  void set(int z, const void* a, const void* b, void* c, const void* bias) {
+    const bf16_t* pa = (const bf16_t*)a;
+    const bf16_t* pb = (const bf16_t*)b;
+    const bf16_t* pbias = (const bf16_t*)bias;
+    switch (z) {
+      case 0: A0 = pa; B0 = pb; C0 = c; bias0 = pbias; break;
+      case 1: A1 = pa; B1 = pb; C1 = c; bias1 = pbias; break;
+      case 2: A2 = pa; B2 = pb; C2 = c; bias2 = pbias; break;
+      default: A3 = pa; B3 = pb; C3 = c; bias3 = pbias; break;
+    }
+  }
+};
+
+// C[z] = A[z] * op(B[z]) (+ bias) in bf16 for nz batch entries, or the sum over g.nseg segments into C[0].
+// A is k-contiguous [M][K]; B is k-contiguous [N][K] (b_k_contiguous) or n-contiguous [K][N].
+int vd_gemm_bf16(vardrop_ctx* ctx, int kid, const GemmBf16& g, int nz, bool b_k_contiguous, hipStream_t s);
+// C[z] = A[z]^T * B[z] in fp32 for nz matrices, both operands mn-contiguous ([K][M], [K][N]), one K slice.
+int vd_gemm_bf16_wgrad(vardrop_ctx* ctx, int kid, const GemmBf16& g, int nz, hipStream_t s);
+// One launch for the input gradient gx (k-contiguous operands, up to three segments) and the nzw weight
+// gradients gw (mn-contiguous operands, gw.splitk K slices, fp32 partial products in gw.C0).
+int vd_gemm_bf16_bwd_pair(vardrop_ctx* ctx, const GemmBf16& gx, const GemmBf16& gw, int nzw, hipStream_t s);
+// out[z][i] = sum_s part[z * splitk + s][i] for four matrices of `count` elements, slices in ascending order.
+int vd_gemm_bf16_sum_slices(vardrop_ctx* ctx, const float* part, float* const out[4], long long count, int splitk,
+                            hipStream_t s);
+#endif  // VARDROP_GEMM_BF16_H
