@@ -101,10 +101,13 @@ const char* vardrop_kernel_name(int kernel_id);
  *   hash   uint64 [N]
  *   abar   fp32 [N][f_max-f_min+1] mean amplitudes, or NULL
  * Requires 1 <= k <= f_max-f_min+1, 0 <= f_min <= f_max <= floor(L/2), R^k < 2^63,
- * 2 <= L <= 1024, at most 512 candidate bins, and staging buffers that fit the 160 KiB LDS:
- * 4*(35 L + 1345 + V*(f_max-f_min+1)) bytes with V = 32/min(32, B rounded up to a power of
- * two); always true for L <= 768 (EUNSUPPORTED otherwise).  N == 0 is a no-op.  Arithmetic is fp32; ranks agree
- * with an exact evaluation whenever neighbouring amplitudes differ by much more than 1e-6
+ * 2 <= L <= 1024, at most 512 candidate bins, and operand buffers that fit the 160 KiB LDS:
+ * 2048 P + 384 + 4 V (f_max-f_min+1) bytes with P = 2 ceil(ceil(L/2) / 16) + 1 and
+ * V = 32/min(32, B rounded up to a power of two); always true for L <= 768 (EUNSUPPORTED
+ * otherwise).  N == 0 is a no-op.  Arithmetic: the spectrum is contracted on the half-precision
+ * matrix cores with every operand split into two fp16 pieces and fp32 accumulation, which is
+ * as exact as fp32 arithmetic (mean amplitudes within 1e-6 of the largest one of the variate);
+ * ranks agree with an exact evaluation whenever neighbouring amplitudes differ by much more than 1e-6
  * relative.  Non-finite inputs give unspecified ranks.
  */
 size_t vardrop_hash_workspace_bytes(int B, int N, int L, int k, int f_min, int f_max);

@@ -15,12 +15,15 @@ struct vardrop_ctx {
   int prof_stride;       // every prof_stride-th launch of the selected kernel is bracketed
   int prof_seen;         // launches of the selected kernel seen since it was selected
   hipEvent_t* prof_ev;   // 2 * kProfPairs events, created on first use
-  float* twiddle;        // device: cos(2 pi j / L), j < L, then sin(2 pi j / L), j < L
-  int twiddle_L;         // L the table currently holds (0: none)
+  void* twiddle;         // device: k-DFH cosine / sine table in matrix-fragment order (kTwiddleBytes)
+  int twiddle_L;         // window length the table currently holds (0: none),
+  int twiddle_fmin;      //   its first candidate bin
+  int twiddle_F;         //   and its number of candidate bins
   int lds_per_block;     // bytes of LDS one workgroup may use
 };
 
-static const int kMaxTwiddleL = 8192;
+static const int kMaxHashL = 1024;                    // longest window vardrop_hash takes
+static const size_t kTwiddleBytes = (size_t)2 << 20;   // 32 contraction steps x 16 bin tiles x 4 KiB
 
 #define VD_HIP(ctx, call)                                   \
   do {                                                      \

@@ -13,6 +13,8 @@ extern "C" int vardrop_create(vardrop_ctx** out, int device_id) {
   c->last_hip_error = 0;
   c->twiddle = nullptr;
   c->twiddle_L = 0;
+  c->twiddle_fmin = 0;
+  c->twiddle_F = 0;
   c->prof_kid = -1;
   c->prof_n = 0;
   c->prof_stride = 1;
@@ -26,7 +28,7 @@ extern "C" int vardrop_create(vardrop_ctx** out, int device_id) {
     int v = 0;
     if (hipDeviceGetAttribute(&v, hipDeviceAttributeMaxSharedMemoryPerBlock, device_id) == hipSuccess && v > 0)
       c->lds_per_block = v;
-    e = hipMalloc((void**)&c->twiddle, sizeof(float) * 2 * kMaxTwiddleL);
+    e = hipMalloc(&c->twiddle, kTwiddleBytes);
     (void)hipSetDevice(prev);
   }
   if (e != hipSuccess) {

@@ -2,42 +2,88 @@
 //
 // Mapping.  A workgroup of four wavefronts owns a block of 32 (variate, window) rows: all B
 // windows of one variate when B >= 32 (several blocks in sequence when B > 32), or 32/Bp variates
-// with Bp = B rounded up to a power of two when B < 32.  The block's windows are staged in LDS
-// (time-major, padded), and the amplitude spectrum on the candidate bins is a dense contraction of
-// the folded window with a cosine / sine table:
+// with Bp = B rounded up to a power of two when B < 32.  The amplitude spectrum on the candidate
+// bins is a dense contraction of the folded window with a cosine / sine table:
 //     Re X_f =  x[0] + (-1)^f x[L/2] + sum_{0<t<L/2} (x[t] + x[L-t]) cos(2 pi f t / L)
 //     Im X_f = -sum_{0<t<L/2} (x[t] - x[L-t]) sin(2 pi f t / L)
-// evaluated with the fp32 matrix instruction v_mfma_f32_16x16x4_f32 (rows = windows, columns = bins,
-// contraction = folded time).  Each of the four wavefronts owns a 16 x 16 quadrant of the block's
-// 32 windows x 32 bins and runs the whole contraction on it, so loads, folding and matrix work of
-// a block run four wide and nothing is reduced across wavefronts.  The bins above the cut-off are never produced (Alg. 1
-// step 2).  Amplitudes are summed over the batch in ascending window order in fp32 (step 3), and
-// the ranked top-k (step 4) is k rounds of a wavefront arg-max with the lower bin winning ties; the
-// hash is the tuple in radix R (step 5).
+// (rows = windows, columns = bins, contraction = folded time; the x[L/2] term is added afterwards).
+//
+// Arithmetic.  The contraction runs on the half-precision matrix cores at fp32 quality: every
+// operand is split as  v = hi + lo  with hi = fp16(v) and lo = fp16(v - hi), and
+//     sum v w  ~=  sum hi_v hi_w  +  sum hi_v lo_w  +  sum lo_v hi_w
+// accumulated in fp32 by v_mfma_f32_32x32x16_f16; the dropped lo_v lo_w term is 2^-22 of a product.
+// A window is first scaled by a power of two (exact) that brings its largest magnitude to
+// [2^12, 2^13), so that the fp16 range holds both pieces whatever the input's scale is, and the
+// amplitude is scaled back before the batch sum.  The low piece of a cosine or sine is below 2^-12,
+// where fp16 loses precision, so the table stores it times 2^11 and the window's high piece is
+// multiplied by 2^-11 (exact) for that product.  The bins above the cut-off are never produced
+// (Alg. 1 step 2).  Amplitudes are summed over the batch in a fixed order in fp32 (step 3), the
+// ranked top-k (step 4) lets the lower bin win ties, and the hash is the tuple in radix R (step 5).
+//
+// Data flow.  Every thread reads 8 consecutive samples of a row and the 8 mirrored ones straight
+// from global memory, folds them, and writes the four half-precision operand pieces (sum hi / lo,
+// difference hi / lo) to LDS in the layout the matrix instruction reads (row-major, 16 bytes per
+// lane).  The cosine / sine pieces come from a table in global memory that is laid out in
+// matrix-fragment order (it stays in L2) and is rebuilt when L or the candidate bins change.  A
+// wavefront owns a tile of 32 bins at a time and runs the whole contraction for it, real and
+// imaginary part together, so nothing is exchanged between wavefronts until the batch sums.
 #include "common.h"
 
-typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 namespace {
 
-constexpr int kTilePad = 33;     // LDS row stride of the time-major tile (32 rows + 1)
 constexpr int kMaxBinsPerLane = 8;
 constexpr int kWaves = 4;
 constexpr int kThreads = 64 * kWaves;
+constexpr float kLoUnscale = 1.f / 2048.f;   // 2^-11: the table's low pieces are stored times 2^11
 
-__global__ void twiddle_kernel(float* tw, int L) {
-  int j = blockIdx.x * blockDim.x + threadIdx.x;
-  if (j < L) {
-    double s, c;
-    sincospi(2.0 * (double)j / (double)L, &s, &c);
-    tw[j] = (float)c;
-    tw[L + j] = (float)s;
+struct Pieces {
+  halfx8 hi, lo;
+};
+
+__device__ inline void split8(const float (&v)[8], Pieces& p) {
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const _Float16 h = (_Float16)v[j];
+    p.hi[j] = h;
+    p.lo[j] = (_Float16)(v[j] - (float)h);
   }
+}
+
+// Table of the twiddle pieces in fragment order: entry ((s * nct + ct) * 4 + kind) * 64 + lane holds,
+// for contraction step s and bin tile ct, the 8 halves of lane `lane` of the right-hand operand
+// (column = bin f_min + 32 ct + lane % 32, rows t = 16 s + 8 (lane / 32) + 0..7); kind 0 / 1 = cosine
+// hi / lo, 2 / 3 = sine hi / lo.  Entries past the last folded sample or the last bin are zero.
+__global__ void twiddle_kernel(halfx8* tw, int L, int f_min, int F, int T, int steps, int nct) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= steps * nct * 64) return;
+  const int lane = i & 63;
+  const int ct = (i >> 6) % nct;
+  const int s = (i >> 6) / nct;
+  const int c = ct * 32 + (lane & 31);
+  const int f = f_min + c;
+  halfx8 out[4];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const int t = 16 * s + 8 * (lane >> 5) + j;
+    double sn = 0.0, cs = 0.0;
+    if (t < T && c < F) sincospi(2.0 * (double)(((long long)f * t) % L) / (double)L, &sn, &cs);
+    const _Float16 ch = (_Float16)(float)cs, sh = (_Float16)(float)sn;
+    out[0][j] = ch;
+    out[1][j] = (_Float16)(float)((cs - (double)(float)ch) * 2048.0);
+    out[2][j] = sh;
+    out[3][j] = (_Float16)(float)((sn - (double)(float)sh) * 2048.0);
+  }
+  const size_t base = ((size_t)(s * nct + ct) * 4) * 64 + lane;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) tw[base + (size_t)q * 64] = out[q];
 }
 
 struct KdfhArgs {
   const float* x;
-  const float* tw;
+  const halfx8* tw;
   int32_t* topk;
   uint64_t* hash;
   float* abar;
@@ -46,162 +92,282 @@ struct KdfhArgs {
   int log2_rpv;   // rows per variate inside a 32-row block = 1 << log2_rpv
   int nrb;        // 32-row blocks per variate group (> 1 only when B > 32)
   int vec;        // rows can be read as aligned float4
+  int T;          // folded samples in the contraction: t = 0 .. T-1, T = ceil(L / 2)
+  int KS;         // contraction steps of 16 that hold them
+  int steps;      // steps the kernel runs (KS rounded up to the unroll; the table is zero there)
+  int nct;        // bin tiles of 32
+  int pitch;      // LDS row pitch of an operand piece, in 16-byte units (odd)
   float inv_B;
 };
 
-__global__ __launch_bounds__(kThreads) void kdfh_kernel(KdfhArgs a) {
-  extern __shared__ float lds[];
-  const int L = a.L, F = a.F;
+// One step's right-hand pieces of a wavefront.
+struct Tw {
+  halfx8 ch, cl, sh, sl;
+};
+
+__device__ inline void load_tw(Tw& w, const halfx8* p) {
+  w.ch = p[0];
+  w.cl = p[64];
+  w.sh = p[128];
+  w.sl = p[192];
+}
+
+// Maximum or minimum of an integer over the 64 lanes, returned to all of them: four shifts inside the
+// rows of 16 lanes, then the last lane of a row is passed on to the next row, then to the upper half;
+// lane 63 ends up with the result.  Lanes that a step does not reach keep their own value.
+template <bool MAX>
+__device__ inline int wave_reduce(int v) {
+#define KDFH_RED(CTRL, ROWS)                                                      \
+  {                                                                               \
+    const int t = __builtin_amdgcn_update_dpp(v, v, CTRL, ROWS, 0xF, false);      \
+    v = MAX ? max(v, t) : min(v, t);                                              \
+  }
+  KDFH_RED(0x111, 0xF)   // row_shr:1
+  KDFH_RED(0x112, 0xF)   // row_shr:2
+  KDFH_RED(0x114, 0xF)   // row_shr:4
+  KDFH_RED(0x118, 0xF)   // row_shr:8
+  KDFH_RED(0x142, 0xA)   // row_bcast:15 into rows 1 and 3
+  KDFH_RED(0x143, 0xC)   // row_bcast:31 into rows 2 and 3
+#undef KDFH_RED
+  return __builtin_amdgcn_readlane(v, 63);
+}
+
+// ITEMS: 8-sample items a thread reads per row block; RING: contraction steps whose table pieces are in
+// flight (2 keeps the kernel inside 128 registers, so that four blocks share a compute unit).
+template <int ITEMS, int RING>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(RING == 2 ? 4 : 1))) void kdfh_kernel(KdfhArgs a) {
+  extern __shared__ halfx8 lds8[];
+  const int L = a.L, F = a.F, T = a.T;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int col = lane & 31, half = lane >> 5;
   const int rpv = 1 << a.log2_rpv;
   const int Vb = 32 >> a.log2_rpv;               // variates per block
   const int n0 = blockIdx.x * Vb;
-  float* cosT = lds;
-  float* sinT = lds + L;
-  float* tile = sinT + L;                        // [L + 1][kTilePad], last row zero
-  float* ampT = tile + (L + 1) * kTilePad;       // [32][kTilePad]
-  float* psum = ampT + 32 * kTilePad;            // [8][32] partial batch sums
-  float* asum = psum + 8 * 32;                   // [Vb][F]
+  const int KG = 2 * a.KS;                       // groups of 8 folded samples per row
+  const int pitch = a.pitch;
+  halfx8* opnd = lds8;                           // [4][32][pitch]: sum hi, sum lo, difference hi, difference lo
+  unsigned* rowmax = reinterpret_cast<unsigned*>(opnd + 4 * 32 * pitch);   // [32] bits of the largest |x| of a row
+  float* rowinv = reinterpret_cast<float*>(rowmax + 32);                   // [32] 1 / scale of a row
+  float* xnyq = rowinv + 32;                                               // [32] scaled x[L/2] (0 when L is odd)
+  float* asum = xnyq + 32;                                                 // [Vb][F]
 
-  for (int i = tid; i < 2 * L; i += kThreads) lds[i] = a.tw[i];
   for (int i = tid; i < Vb * F; i += kThreads) asum[i] = 0.f;
-
-  const int Lh = L >> 1;
-  const int S4 = (Lh + 4) >> 2;                  // steps of four folded time samples: t = 0 .. floor(L/2)
-  const int nct = (F + 31) >> 5;
+  const bool even = (L & 1) == 0;
+  // which wavefront takes the odd bin tile out rotates with the block, so that the blocks that share a
+  // compute unit do not all load the same one of its four matrix pipelines
+  const int rot = (blockIdx.x + (blockIdx.x >> 8)) & (kWaves - 1);
+  const int ct0 = (wave + rot) & (kWaves - 1);                       // first bin tile of this wavefront
+  const int nt = ct0 < a.nct ? (a.nct - ct0 + kWaves - 1) / kWaves : 0;   // and how many it takes
+  Tw w0, w1, w2, w3;                                                 // right-hand pieces in flight (w2, w3: RING = 4)
+  const int ctp = min(ct0, a.nct - 1);                               // (a wavefront without a tile loads one all the same)
 
   for (int rb = 0; rb < a.nrb; ++rb) {
-    __syncthreads();
-    // ---- stage 32 windows in LDS, time-major: tile[t][row]
-    if (a.vec) {
-      const int L4 = L >> 2;
-      const int items = 32 * L4;
-      for (int base = 0; base < items; base += kThreads * 4) {
-        float4 v[4];
-        int rr[4], cc[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const int i = base + u * kThreads + tid;
-          const int ic = i < items ? i : 0;                      // clamped: the load is unconditional
-          const int r = ic / L4;
-          const int c = ic - r * L4;
-          rr[u] = i < items ? r : -1;
-          cc[u] = c;
-          const int n = min(n0 + (r >> a.log2_rpv), a.N - 1);
-          const int b = min(rb * 32 + (r & (rpv - 1)), a.B - 1);
-          const bool ok = (n0 + (r >> a.log2_rpv) < a.N) && (rb * 32 + (r & (rpv - 1)) < a.B);
-          const float4 t = *reinterpret_cast<const float4*>(a.x + (long long)b * a.sb + (long long)n * a.sn + 4 * c);
-          v[u] = make_float4(ok ? t.x : 0.f, ok ? t.y : 0.f, ok ? t.z : 0.f, ok ? t.w : 0.f);   // rows past the end are zero windows
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          if (rr[u] >= 0) {
-            float* p = tile + (4 * cc[u]) * kTilePad + rr[u];
-            p[0] = v[u].x;
-            p[kTilePad] = v[u].y;
-            p[2 * kTilePad] = v[u].z;
-            p[3 * kTilePad] = v[u].w;
-          }
-        }
-      }
-    } else {
-      for (int r = wave; r < 32; r += kWaves) {
-        const int n = n0 + (r >> a.log2_rpv);
-        const int b = rb * 32 + (r & (rpv - 1));
-        const bool ok = n < a.N && b < a.B;
-        const float* p = a.x + (long long)b * a.sb + (long long)n * a.sn;
-        for (int t = lane; t < L; t += 64) tile[t * kTilePad + r] = ok ? p[t] : 0.f;
-      }
-    }
-    __syncthreads();
-    // ---- fold in place: row t becomes x[t] + x[L-t] and row L-t becomes x[t] - x[L-t] for
-    // 0 < t < L/2 (rows 0 and L/2 stay); row L is a zero row for steps past the end.
-    const bool folded = nct > 1;      // one column tile reads every sample once: folding on the fly is cheaper
-    if (folded) {
-      const int npair = (L - 1) >> 1;
-      for (int i = tid; i < npair * 32; i += kThreads) {
-        const int t = 1 + (i >> 5), r = i & 31;
-        const float p = tile[t * kTilePad + r], q = tile[(L - t) * kTilePad + r];
-        tile[t * kTilePad + r] = p + q;
-        tile[(L - t) * kTilePad + r] = p - q;
-      }
-    }
-    if (tid < 32) tile[L * kTilePad + tid] = 0.f;
+    __syncthreads();                             // the operands of the previous block have been used
+    if (tid < 32) rowmax[tid] = 0u;
+    // the first steps of the wavefront's first bin tile are requested before the windows are when
+    // the windows leave the registers for it (short windows), else right before the contraction
+    constexpr bool kEarly = ITEMS <= 2;
+#define KDFH_PRIME()                                        \
+  {                                                         \
+    const halfx8* tb = a.tw + (size_t)ctp * 256 + lane;     \
+    const size_t sstride = (size_t)a.nct * 256;             \
+    load_tw(w0, tb);                                        \
+    load_tw(w1, tb + sstride);                              \
+    if (RING == 4) {                                        \
+      load_tw(w2, tb + 2 * sstride);                        \
+      load_tw(w3, tb + 3 * sstride);                        \
+    }                                                       \
+  }
+    if (kEarly) KDFH_PRIME()
     __syncthreads();
 
-    // ---- spectrum of the 32 rows, 32 bins at a time.  The four wavefronts take one 16 x 16 quadrant of
-    // the 32 x 32 (window, bin) tile each and run the whole contraction on it with
-    // v_mfma_f32_16x16x4_f32 (four folded time samples per instruction), so no partial sums are exchanged.
-    // Operand layout: A[i][k] lane holds row i = lane % 16, k = lane / 16; B[k][j] lane holds column
-    // j = lane % 16, the same k; C[i][j] lane holds column j = lane % 16, register r holds row 4*(lane/16) + r.
-    for (int ct = 0; ct < nct; ++ct) {
-      const int i16 = lane & 15, kq = lane >> 4;
-      const int rh = wave & 1, ch = wave >> 1;
-      const int f = a.f_min + ct * 32 + ch * 16 + i16;
-      const int step4 = (4 * f) % L;             // advancing one step moves t by 4
-      int m = (f * kq) % L;                      // (f t) mod L: index into both tables
-      floatx4 re = {0.f, 0.f, 0.f, 0.f}, im = re;
-      // Re uses rows t <= L/2 (x[0], the sums, x[L/2]); Im uses rows L - t for 0 < 2t < L (the
-      // differences); every other step reads the zero row L.  Software pipeline: the operands of the
-      // next step are read from LDS while the matrix instructions of this one run.
-      const int arow = rh * 16 + i16;
-      int t = kq;
-      // p = row t (or zero past L/2), q = row L - t when 0 < 2t < L (else zero); folded rows already hold
-      // p + q and p - q, unfolded ones are combined here
-      float p = tile[(t <= Lh ? t : L) * kTilePad + arow];
-      float q = tile[((t > 0 && 2 * t < L) ? L - t : L) * kTilePad + arow];
-      float ac = folded ? p : p + q;
-      float as = folded ? q : ((t > 0 && 2 * t < L) ? p - q : 0.f);
-      float bc = cosT[m], bs = sinT[m];
-      for (int s = 0; s < S4; ++s) {
-        const float ac0 = ac, as0 = as, bc0 = bc, bs0 = bs;
-        t += 4;
-        m += step4;
-        if (m >= L) m -= L;
-        p = tile[(t <= Lh ? t : L) * kTilePad + arow];
-        q = tile[(2 * t < L ? L - t : L) * kTilePad + arow];
-        ac = folded ? p : p + q;
-        as = folded ? q : (2 * t < L ? p - q : 0.f);
-        bc = cosT[m];
-        bs = sinT[m];
-        __builtin_amdgcn_sched_barrier(0);
-        re = __builtin_amdgcn_mfma_f32_16x16x4f32(ac0, bc0, re, 0, 0, 0);
-        im = __builtin_amdgcn_mfma_f32_16x16x4f32(as0, bs0, im, 0, 0, 0);
-        // (keeps the reads above in this iteration: without it the compiler folds them back into
-        //  the top of the next one, in front of the instructions that need them)
-        __builtin_amdgcn_sched_barrier(0);
-        asm volatile("" : "+v"(ac), "+v"(as), "+v"(bc), "+v"(bs));
-      }
+    // ---- read: item (r, g) = samples t = 8g .. 8g+7 of row r and their mirror images L - t
+    float dv[ITEMS][8], mv[ITEMS][8], ny[ITEMS];
 #pragma unroll
-      for (int r = 0; r < 4; ++r)
-        ampT[(rh * 16 + 4 * kq + r) * kTilePad + ch * 16 + i16] = sqrtf(re[r] * re[r] + im[r] * im[r]);
-      __syncthreads();
-      // batch sums (Alg. 1 step 3).  The eight 32-lane groups add four windows each, ascending; with
-      // fewer than eight variates in the block the groups of a variate then add their partial sums,
-      // ascending again, so the order of the additions is fixed.
-      const int bin = ct * 32 + col;
-      const int grp = tid >> 5;
-      if (Vb <= 8) {
-        float sum = 0.f;
-#pragma unroll
-        for (int b = 0; b < 4; ++b) sum += ampT[(grp * 4 + b) * kTilePad + col];
-        psum[grp * 32 + col] = sum;
-        __syncthreads();
-        const int gpv = 8 / Vb;                   // groups per variate
-        if (grp % gpv == 0 && bin < F) {
-          float total = 0.f;
-          for (int u = 0; u < gpv; ++u) total += psum[(grp + u) * 32 + col];
-          asum[(grp / gpv) * F + bin] += total;
-        }
+    for (int it = 0; it < ITEMS; ++it) {
+      const int i = it * kThreads + tid;
+      const bool live = i < 32 * KG;
+      const int r = live ? i / KG : 0;
+      const int g = live ? i - r * KG : 0;
+      const int t0 = 8 * g;
+      const int nn = n0 + (r >> a.log2_rpv), bb = rb * 32 + (r & (rpv - 1));
+      const bool ok = live && nn < a.N && bb < a.B;          // rows past the end are zero windows
+      const float* p = a.x + (long long)min(bb, a.B - 1) * a.sb + (long long)min(nn, a.N - 1) * a.sn;
+      if (a.vec) {
+        // L is a multiple of 4 here, so a float4 that starts below L ends below it
+        const float4 u0 = *reinterpret_cast<const float4*>(p + min(t0, L - 4));
+        const float4 u1 = *reinterpret_cast<const float4*>(p + min(t0 + 4, L - 4));
+        dv[it][0] = u0.x; dv[it][1] = u0.y; dv[it][2] = u0.z; dv[it][3] = u0.w;
+        dv[it][4] = u1.x; dv[it][5] = u1.y; dv[it][6] = u1.z; dv[it][7] = u1.w;
       } else {
-        for (int v = grp; v < Vb; v += kThreads / 32) {
-          float sum = 0.f;
-          for (int b = 0; b < rpv; ++b) sum += ampT[(v * rpv + b) * kTilePad + col];
-          if (bin < F) asum[v * F + bin] += sum;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) dv[it][j] = p[min(t0 + j, L - 1)];
+      }
+      float mr[8];                                 // mirror images x[L - t]
+      if (a.vec) {
+        // x[L - t0 - 7 .. L - t0] = the aligned float4 at L - t0 - 8 (last three), the one at L - t0 - 4 and
+        // one more sample; wherever the clamps move an address, none of its samples is a valid mirror image
+        const int ma = L - t0 - 8;
+        const float4 ua = *reinterpret_cast<const float4*>(p + min(max(ma, 0), L - 4));
+        const float4 ub = *reinterpret_cast<const float4*>(p + min(max(ma + 4, 0), L - 4));
+        mr[0] = p[min(max(ma + 8, 0), L - 1)];
+        mr[1] = ub.w; mr[2] = ub.z; mr[3] = ub.y; mr[4] = ub.x;
+        mr[5] = ua.w; mr[6] = ua.z; mr[7] = ua.y;
+      } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) mr[j] = p[min(max(L - t0 - j, 0), L - 1)];
+      }
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int t = t0 + j;
+        dv[it][j] = (ok && t < T) ? dv[it][j] : 0.f;
+        mv[it][j] = (ok && t >= 1 && t < T) ? mr[j] : 0.f;
+      }
+      ny[it] = (ok && even && g == 0) ? p[L >> 1] : 0.f;
+      float mx = fabsf(ny[it]);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) mx = fmaxf(mx, fmaxf(fabsf(dv[it][j]), fabsf(mv[it][j])));
+      if (live) atomicMax(&rowmax[r], __float_as_uint(mx));
+    }
+    __syncthreads();
+
+    // ---- scale by a power of two, fold, split, store the operand pieces
+#pragma unroll
+    for (int it = 0; it < ITEMS; ++it) {
+      const int i = it * kThreads + tid;
+      const bool live = i < 32 * KG;
+      const int r = live ? i / KG : 0;
+      const int g = live ? i - r * KG : 0;
+      const int e = (int)(rowmax[r] >> 23);                  // biased exponent of the row's largest magnitude
+      const int se = min(max(266 - e, 1), 253);              // scale = 2^(12 - (e - 127)), clamped to normal numbers
+      const float sc = __uint_as_float((unsigned)se << 23);
+      float sum[8], dif[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int t = 8 * g + j;
+        const float d = dv[it][j] * sc, m = mv[it][j] * sc;
+        sum[j] = d + m;
+        dif[j] = (t >= 1 && t < T) ? d - m : 0.f;
+      }
+      Pieces ps, pd;
+      split8(sum, ps);
+      split8(dif, pd);
+      if (live) {
+        halfx8* q = opnd + r * pitch + g;
+        q[0] = ps.hi;
+        q[32 * pitch] = ps.lo;
+        q[64 * pitch] = pd.hi;
+        q[96 * pitch] = pd.lo;
+        if (g == 0) {
+          rowinv[r] = __uint_as_float((unsigned)(254 - se) << 23);
+          xnyq[r] = ny[it] * sc;
         }
       }
-      __syncthreads();                            // ampT and psum are rewritten by the next column tile
+    }
+    if (!kEarly) KDFH_PRIME()
+#undef KDFH_PRIME
+    __syncthreads();
+
+    // ---- spectrum of the 32 rows; a wavefront takes 32 bins at a time.
+    // Operand layout of v_mfma_f32_32x32x16_f16: left lane holds row lane % 32, k = 8 (lane / 32) + 0..7;
+    // right lane holds column lane % 32, the same k; result lane holds column lane % 32, register r holds
+    // row 8 (r / 4) + 4 (lane / 32) + r % 4.
+    for (int ti = 0; ti < nt; ++ti) {
+      const int ct = ct0 + kWaves * ti;
+      floatx16 re = {}, im = {};
+      const halfx8* pa = opnd + col * pitch;
+      const halfx8 lo_unscale = {(_Float16)kLoUnscale, (_Float16)kLoUnscale, (_Float16)kLoUnscale, (_Float16)kLoUnscale,
+                                 (_Float16)kLoUnscale, (_Float16)kLoUnscale, (_Float16)kLoUnscale, (_Float16)kLoUnscale};
+      // the pieces of step S + RING replace those of step S; past the tile's last step they are the first of
+      // the wavefront's next tile (of its last step again when there is none: loaded, never used)
+#define KDFH_STEP(W, S)                                                                   \
+  {                                                                                       \
+    const int g = min(2 * (S) + half, KG - 1); /* steps past KS: the table is zero there */ \
+    const halfx8 sh = pa[g], sl = pa[32 * pitch + g], dh = pa[64 * pitch + g], dl = pa[96 * pitch + g]; \
+    const halfx8 shs = sh * lo_unscale, dhs = dh * lo_unscale;                            \
+    __builtin_amdgcn_sched_barrier(0);                                                    \
+    re = __builtin_amdgcn_mfma_f32_32x32x16_f16(sh, W.ch, re, 0, 0, 0);                   \
+    im = __builtin_amdgcn_mfma_f32_32x32x16_f16(dh, W.sh, im, 0, 0, 0);                   \
+    re = __builtin_amdgcn_mfma_f32_32x32x16_f16(shs, W.cl, re, 0, 0, 0);                  \
+    im = __builtin_amdgcn_mfma_f32_32x32x16_f16(dhs, W.sl, im, 0, 0, 0);                  \
+    re = __builtin_amdgcn_mfma_f32_32x32x16_f16(sl, W.ch, re, 0, 0, 0);                   \
+    im = __builtin_amdgcn_mfma_f32_32x32x16_f16(dl, W.sh, im, 0, 0, 0);                   \
+    __builtin_amdgcn_sched_barrier(0);                                                    \
+    {                                                                                     \
+      const bool wrap = (S) + RING >= a.steps;                                            \
+      const int s2 = wrap ? (ti + 1 < nt ? (S) + RING - a.steps : a.steps - 1) : (S) + RING; \
+      const int c2 = (wrap && ti + 1 < nt) ? ct + kWaves : ct;                            \
+      load_tw(W, a.tw + ((size_t)s2 * a.nct + c2) * 256 + lane);                          \
+    }                                                                                     \
+    __builtin_amdgcn_sched_barrier(0);                                                    \
+  }
+      for (int s = 0; s < a.steps; s += 4) {
+        if (RING == 4) {
+          KDFH_STEP(w0, s)
+          KDFH_STEP(w1, s + 1)
+          KDFH_STEP(w2, s + 2)
+          KDFH_STEP(w3, s + 3)
+        } else {
+          KDFH_STEP(w0, s)
+          KDFH_STEP(w1, s + 1)
+          KDFH_STEP(w0, s + 2)
+          KDFH_STEP(w1, s + 3)
+        }
+      }
+#undef KDFH_STEP
+
+      // ---- amplitudes, scaled back, and the batch sums (Alg. 1 step 3) of this bin tile
+      const int c = ct * 32 + col;
+      const float sgn = ((a.f_min + c) & 1) ? -1.f : 1.f;    // (-1)^f of the x[L/2] term
+      float amp[16];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const float4 inv4 = *reinterpret_cast<const float4*>(rowinv + 8 * q + 4 * half);
+        const float4 nyq4 = *reinterpret_cast<const float4*>(xnyq + 8 * q + 4 * half);
+        const float inv[4] = {inv4.x, inv4.y, inv4.z, inv4.w};
+        const float nyq[4] = {nyq4.x, nyq4.y, nyq4.z, nyq4.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int r = 4 * q + e;
+          const float rv = re[r] + sgn * nyq[e];
+          amp[r] = sqrtf(rv * rv + im[r] * im[r]) * inv[e];
+        }
+      }
+      float qs[4];                                 // rows 8q + 4 half + 0..3
+#pragma unroll
+      for (int q = 0; q < 4; ++q) qs[q] = (amp[4 * q] + amp[4 * q + 1]) + (amp[4 * q + 2] + amp[4 * q + 3]);
+      const bool live = c < F;
+      if (a.log2_rpv >= 3) {
+        // a variate spans 8, 16 or 32 rows: both lane halves hold four rows of every 8
+        float vs[4];
+        if (a.log2_rpv == 3) {
+          vs[0] = qs[0]; vs[1] = qs[1]; vs[2] = qs[2]; vs[3] = qs[3];
+        } else if (a.log2_rpv == 4) {
+          vs[0] = qs[0] + qs[1]; vs[1] = qs[2] + qs[3]; vs[2] = 0.f; vs[3] = 0.f;
+        } else {
+          vs[0] = (qs[0] + qs[1]) + (qs[2] + qs[3]); vs[1] = 0.f; vs[2] = 0.f; vs[3] = 0.f;
+        }
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const float tot = vs[v] + __shfl_xor(vs[v], 32, 64);
+          if (live && half == 0 && v < Vb) asum[v * F + c] += tot;
+        }
+      } else if (a.log2_rpv == 2) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          if (live) asum[(2 * q + half) * F + c] += qs[q];
+      } else if (a.log2_rpv == 1) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          if (live) {
+            asum[(4 * q + 2 * half) * F + c] += amp[4 * q] + amp[4 * q + 1];
+            asum[(4 * q + 2 * half + 1) * F + c] += amp[4 * q + 2] + amp[4 * q + 3];
+          }
+      } else {
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          if (live) asum[(8 * (r >> 2) + 4 * half + (r & 3)) * F + c] += amp[r];
+      }
     }
   }
   __syncthreads();
@@ -233,32 +399,26 @@ __global__ __launch_bounds__(kThreads) void kdfh_kernel(KdfhArgs a) {
         if (lane == 0) a.topk[(long long)n * a.k + r] = fsel;
         h = h * R + (unsigned long long)(unsigned)fsel;
       }
-    } else
-    for (int r = 0; r < a.k; ++r) {
-      float best = -3.f;
-      int bi = 0x7fffffff;
+    } else {
+      // k rounds of a wavefront-wide arg-max.  Mean amplitudes are not negative, so their bit patterns order
+      // like signed integers (the -2 of a used or absent bin is below all of them).
+      for (int r = 0; r < a.k; ++r) {
+        int best = (int)0x80000000;
 #pragma unroll
-      for (int j = 0; j < kMaxBinsPerLane; ++j) {
-        if (vals[j] > best) {
-          best = vals[j];
-          bi = lane + 64 * j;
-        }
+        for (int j = 0; j < kMaxBinsPerLane; ++j) best = max(best, __float_as_int(vals[j]));
+        const int top = wave_reduce<true>(best);
+        int bi = 0x7fffffff;
+#pragma unroll
+        for (int j = kMaxBinsPerLane - 1; j >= 0; --j)
+          if (__float_as_int(vals[j]) == top) bi = lane + 64 * j;
+        bi = wave_reduce<false>(bi);                       // the lowest bin that holds it
+#pragma unroll
+        for (int j = 0; j < kMaxBinsPerLane; ++j)
+          if (bi == lane + 64 * j) vals[j] = -2.f;
+        const int fsel = a.f_min + bi;
+        if (lane == 0) a.topk[(long long)n * a.k + r] = fsel;
+        h = h * R + (unsigned long long)(unsigned)fsel;
       }
-#pragma unroll
-      for (int off = 32; off >= 1; off >>= 1) {
-        const float ov = __shfl_xor(best, off, 64);
-        const int oi = __shfl_xor(bi, off, 64);
-        if (ov > best || (ov == best && oi < bi)) {
-          best = ov;
-          bi = oi;
-        }
-      }
-#pragma unroll
-      for (int j = 0; j < kMaxBinsPerLane; ++j)
-        if (bi == lane + 64 * j) vals[j] = -2.f;
-      const int fsel = a.f_min + bi;
-      if (lane == 0) a.topk[(long long)n * a.k + r] = fsel;
-      h = h * R + (unsigned long long)(unsigned)fsel;
     }
     if (lane == 0) a.hash[n] = h;
     if (a.abar)
@@ -266,8 +426,20 @@ __global__ __launch_bounds__(kThreads) void kdfh_kernel(KdfhArgs a) {
   }
 }
 
-size_t kdfh_lds_bytes(int L, int F, int Vb) {
-  return sizeof(float) * ((size_t)2 * L + (size_t)(L + 1) * kTilePad + 32 * kTilePad + 8 * 32 + (size_t)Vb * F);
+size_t kdfh_lds_bytes(int pitch, int F, int Vb) {
+  return (size_t)4 * 32 * pitch * 16 + sizeof(float) * (3 * 32 + (size_t)Vb * F);
+}
+
+template <int ITEMS, int RING>
+int launch_kdfh(vardrop_ctx* ctx, const KdfhArgs& a, int grid, size_t lds, hipStream_t s) {
+  if (lds > 65536)
+    VD_HIP(ctx, hipFuncSetAttribute((const void*)kdfh_kernel<ITEMS, RING>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+  {
+    VdTimer timer(ctx, VARDROP_K_HASH, s);
+    hipLaunchKernelGGL((kdfh_kernel<ITEMS, RING>), dim3(grid), dim3(kThreads), lds, s, a);
+  }
+  VD_LAUNCH_CHECK(ctx);
+  return VARDROP_OK;
 }
 
 }  // namespace
@@ -298,7 +470,7 @@ extern "C" int vardrop_hash(vardrop_ctx* ctx, const float* x, int B, int N, int 
   if (!x || !topk || !hash) return VARDROP_EINVAL;
   if (sb < 0 || sn < 0) return VARDROP_EINVAL;
   if (st != 1) return VARDROP_EUNSUPPORTED;
-  if (L > 1024 || F > 64 * kMaxBinsPerLane) return VARDROP_EUNSUPPORTED;
+  if (L > kMaxHashL || F > 64 * kMaxBinsPerLane) return VARDROP_EUNSUPPORTED;
 
   int log2_rpv = 5, nrb = vd_ceil_div(B, 32);
   if (B < 32) {
@@ -307,18 +479,28 @@ extern "C" int vardrop_hash(vardrop_ctx* ctx, const float* x, int B, int N, int 
     nrb = 1;
   }
   const int Vb = 32 >> log2_rpv;
-  const size_t lds = kdfh_lds_bytes(L, F, Vb);
+  const int T = (L + 1) / 2;
+  const int KS = vd_ceil_div(T, 16);
+  const int steps = (KS + 3) & ~3;
+  const int nct = vd_ceil_div(F, 32);
+  const int pitch = (2 * KS) | 1;
+  const size_t lds = kdfh_lds_bytes(pitch, F, Vb);
   if (lds > (size_t)ctx->lds_per_block) return VARDROP_EUNSUPPORTED;
+  if ((size_t)steps * nct * 4096 > kTwiddleBytes) return VARDROP_EUNSUPPORTED;   // (cannot happen within the limits above)
 
   hipStream_t s = (hipStream_t)stream;
-  if (ctx->twiddle_L != L) {
-    hipLaunchKernelGGL(twiddle_kernel, dim3(vd_ceil_div(L, 256)), dim3(256), 0, s, ctx->twiddle, L);
+  if (ctx->twiddle_L != L || ctx->twiddle_fmin != f_min || ctx->twiddle_F != F) {
+    const int entries = steps * nct * 64;
+    hipLaunchKernelGGL(twiddle_kernel, dim3(vd_ceil_div(entries, 256)), dim3(256), 0, s,
+                       (halfx8*)ctx->twiddle, L, f_min, F, T, steps, nct);
     VD_LAUNCH_CHECK(ctx);
     ctx->twiddle_L = L;
+    ctx->twiddle_fmin = f_min;
+    ctx->twiddle_F = F;
   }
   KdfhArgs a;
   a.x = x;
-  a.tw = ctx->twiddle;
+  a.tw = (const halfx8*)ctx->twiddle;
   a.topk = topk;
   a.hash = hash;
   a.abar = abar;
@@ -333,13 +515,16 @@ extern "C" int vardrop_hash(vardrop_ctx* ctx, const float* x, int B, int N, int 
   a.log2_rpv = log2_rpv;
   a.nrb = nrb;
   a.vec = (L % 4 == 0 && sb % 4 == 0 && sn % 4 == 0 && vd_aligned(x, 16)) ? 1 : 0;
+  a.T = T;
+  a.KS = KS;
+  a.steps = steps;
+  a.nct = nct;
+  a.pitch = pitch;
   a.inv_B = 1.0f / (float)B;
-  if (lds > 65536)
-    VD_HIP(ctx, hipFuncSetAttribute((const void*)kdfh_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-  {
-    VdTimer timer(ctx, VARDROP_K_HASH, s);
-    hipLaunchKernelGGL(kdfh_kernel, dim3(vd_ceil_div(N, Vb)), dim3(kThreads), lds, s, a);
-  }
-  VD_LAUNCH_CHECK(ctx);
-  return VARDROP_OK;
+  const int grid = vd_ceil_div(N, Vb);
+  const int items = vd_ceil_div(32 * 2 * KS, kThreads);
+  if (items <= 1) return launch_kdfh<1, 2>(ctx, a, grid, lds, s);
+  if (items <= 2) return launch_kdfh<2, 4>(ctx, a, grid, lds, s);
+  if (items <= 4) return launch_kdfh<4, 4>(ctx, a, grid, lds, s);
+  return launch_kdfh<8, 4>(ctx, a, grid, lds, s);
 }

@@ -135,8 +135,8 @@ def test_error_codes(vd, ctx):
     with pytest.raises(vd.VarDropError) as e:
         vd.vardrop_hash(ctx, torch.zeros((2, 3, 2048), device="cuda"), 3)
     assert e.value.code == -4
-    with pytest.raises(vd.VarDropError) as e:                      # 16 variates x 257 bins of sums + tile > LDS
-        vd.vardrop_hash(ctx, torch.zeros((2, 2, 1024), device="cuda"), 6)
+    with pytest.raises(vd.VarDropError) as e:                      # 32 variates x 257 bins of sums + operands > LDS
+        vd.vardrop_hash(ctx, torch.zeros((1, 2, 1024), device="cuda"), 6)
     assert e.value.code == -4
     with pytest.raises(vd.VarDropError) as e:
         vd.vardrop_hash(ctx, torch.zeros((2, 96, 3), device="cuda").transpose(1, 2), 3)      # time stride != 1
