@@ -8,6 +8,10 @@ Prints ONE JSON line: steps/s, the roofline figure of the dominant kernel, and t
 oracle timed on a bounded sample of the same workload.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload traffic] [--no-cpu-baseline]
+
+`--mode bandwidth` instead measures the steady-state HBM bandwidth of the two streaming kernels
+(vardrop_hash, vardrop_gather) over enough distinct batches (>= 1 GiB of input) that the 256 MB
+last-level cache cannot serve the reads, and prints ONE JSON line with both figures.
 """
 import argparse
 import json
@@ -86,6 +90,7 @@ def parse():
     ap.add_argument("--workload", default="traffic")
     ap.add_argument("--batches", type=int, default=4, help="distinct pre-generated batches the steps rotate through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--mode", choices=("steps", "bandwidth"), default="steps")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run five plain 256 MiB device copies (reference for hardware byte counters)")
     return ap.parse_args()
@@ -143,12 +148,106 @@ def cpu_baseline(w, x_np, tok_np, W_np, seed):
     return {"value": 1.0 / step_s, "unit": "steps/s", "cores": cores, "kind": "oracle", "sample": note}
 
 
+def steady_bandwidth(args):
+    """Kernel time of vardrop_hash and vardrop_gather over M distinct inputs each (M x bytes >= 1 GiB), launched
+    back to back on one stream: per-launch durations from HIP events around every launch (library hook), less
+    the cost of an empty event pair, and the wall time of the same loop without events."""
+    import numpy as np
+    import torch
+    import paper_2501_14183_amd as vd
+    import workloads as wl
+
+    w = wl.WORKLOADS[args.workload]
+    td = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+    es = 2 if w.dtype == "bf16" else 4
+    dev = torch.device("cuda", 0)
+    torch.cuda.set_device(dev)
+    ctx = vd.Context(0)
+    stream = torch.cuda.current_stream()
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(1234)
+
+    def empty_pair_us():
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(64)]
+        for i in range(0, 64, 2):
+            e[i].record(stream)
+            e[i + 1].record(stream)
+        torch.cuda.synchronize()
+        return float(np.median([e[i].elapsed_time(e[i + 1]) for i in range(0, 64, 2)])) * 1e3
+
+    def measure(kid, launch, count, reps=3):
+        for i in range(count):                       # warm-up pass (also builds the hash's table)
+            launch(i)
+        torch.cuda.synchronize()
+        vd.vardrop_profile_stride(ctx, 1)
+        vd.vardrop_profile_select(ctx, kid)
+        for _ in range(reps):
+            for i in range(count):
+                launch(i)
+        total_ms, launches = vd.vardrop_profile_read(ctx)
+        vd.vardrop_profile_select(ctx, -1)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            for i in range(count):
+                launch(i)
+        torch.cuda.synchronize()
+        wall_us = (time.perf_counter() - t0) * 1e6 / (reps * count)
+        return total_ms * 1e3 / launches - empty_pair_us(), wall_us, launches
+
+    def report(nbytes, us, wall, n, extra):
+        # "GB/s" is the conservative figure: launches back to back, dispatch gaps included.  The event figure
+        # subtracts an empty bracket of several microseconds and means little for a kernel shorter than that;
+        # rocprofv3 --kernel-trace of this same command gives the kernel's own duration.
+        d = dict(extra)
+        d.update({"bytes_per_launch": nbytes, "back_to_back_us": wall, "GB/s": nbytes / wall * 1e-3,
+                  "frac_of_peak": nbytes / wall * 1e-3 / PEAK_HBM_GBS, "event_bracket_us": us,
+                  "GB/s_event_bracket": (nbytes / us * 1e-3) if us >= 10.0 else None, "launches": n})
+        return d
+
+    kids = {vd.vardrop_kernel_name(k): k for k in range(64) if vd.vardrop_kernel_name(k)}
+    out = {}
+
+    # ---- hash: 4 B N L bytes read per launch
+    x_bytes = 4 * w.B * w.N * w.L
+    M = -(-(1 << 30) // x_bytes)
+    xs = [torch.randn((w.B, w.N, w.L), generator=gen, device=dev) for _ in range(M)]
+    topk = torch.empty((w.N, w.k), dtype=torch.int32, device=dev)
+    hsh = torch.empty(w.N, dtype=torch.int64, device=dev)
+    us, wall, n = measure(kids["hash"], lambda i: vd.vardrop_hash(ctx, xs[i], w.k, out=(topk, hsh), stream=stream.cuda_stream), M)
+    out["hash"] = report(x_bytes, us, wall, n, {"distinct_inputs": M})
+    del xs
+
+    # ---- gather: 2 B N' d es bytes (read + write) per launch, N' = the workload's mean keep
+    n_sel = max(1, int(round(w.N * w.ratio[0] / w.ratio[1] * 1.3)))
+    g_bytes = 2 * w.B * n_sel * w.d * es
+    M = -(-(1 << 30) // g_bytes)
+    tok_bytes = w.B * w.N * w.d * es
+    M = min(M, max(4, (64 << 30) // tok_bytes))       # at most 64 GiB of token buffers
+    toks = [torch.randn((w.B, w.N, w.d), generator=gen, device=dev).to(td) for _ in range(M)]
+    sels = []
+    for i in range(M):
+        pick = torch.randperm(w.N, generator=gen, device=dev)[:n_sel].sort().values.to(torch.int32)
+        sel = torch.zeros(w.N, dtype=torch.int32, device=dev)
+        sel[:n_sel] = pick
+        sels.append(sel)
+    dst = [torch.empty((w.B, n_sel, w.d), dtype=td, device=dev) for _ in range(M)]
+    us, wall, n = measure(kids["gather"], lambda i: vd.vardrop_gather(ctx, toks[i], sels[i], n_sel, out=dst[i], stream=stream.cuda_stream), M)
+    out["gather"] = report(g_bytes, us, wall, n, {"distinct_inputs": M, "kept_tokens": n_sel})
+    print(json.dumps({"metric": "steady-state HBM GB/s of vardrop_hash and vardrop_gather", "unit": "GB/s", "n_gpus": 1,
+                      "peak": PEAK_HBM_GBS, "data": "synthetic", "dtype": w.dtype,
+                      "config": {"workload": "%s-shaped: B=%d N=%d L=%d k=%d d=%d" % (w.name, w.B, w.N, w.L, w.k, w.d)},
+                      "kernels": out}))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
         print("bench.py measures one GPU: the library has no multi-GPU path; run with --gpus 1",
               file=sys.stderr)
         sys.exit(2)
+    if args.mode == "bandwidth":
+        return steady_bandwidth(args)
     import numpy as np
     import torch
     import paper_2501_14183_amd as vd

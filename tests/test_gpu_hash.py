@@ -125,6 +125,38 @@ def test_window_order_and_scale_invariance(vd, ctx):
     assert np.array_equal(topk, want_topk)
 
 
+def test_dynamic_range_of_windows(vd, ctx):
+    """Every window has its own magnitude, from 1e-30 to 1e30: the per-window scaling of the kernel must keep
+    the fp32 quality of the spectrum whatever the scale, also next to an all-zero window."""
+    rng = np.random.default_rng(11)
+    B, N, L = 8, 24, 336
+    t = np.arange(L)
+    x = 0.05 * rng.standard_normal((B, N, L))
+    for n in range(N):
+        for j, f in enumerate(rng.choice(np.arange(1, 80), size=4, replace=False)):
+            x[:, n] += (3.0 / (1 + j)) * np.sin(2 * np.pi * f * t / L + rng.uniform(0, 6, size=(B, 1)))
+    mag = 10.0 ** rng.uniform(-30, 30, size=(B, N, 1))
+    mag[:, :4] = 10.0 ** rng.uniform(-30, 30, size=(1, 4, 1))            # four variates with one scale for all windows
+    x = (x * mag).astype(np.float32)
+    x[3, 7] = 0.0
+    x[:, 9] = 0.0
+    topk, hsh, want_topk, want_hash, flips, flips_screened, ok = compare(vd, ctx, x, 4)
+    assert flips_screened == 0 and ok.sum() >= N - 4
+    assert topk[9].tolist() == [1, 2, 3, 4]
+
+
+def test_longest_window(vd, ctx):
+    rng = np.random.default_rng(12)
+    B, N, L = 2, 5, 1024
+    t = np.arange(L)
+    x = 0.1 * rng.standard_normal((B, N, L))
+    for n in range(N):
+        for j, f in enumerate(rng.choice(np.arange(1, 257), size=6, replace=False)):
+            x[:, n] += (3.0 / (1 + j)) * np.sin(2 * np.pi * f * t / L + rng.uniform(0, 6, size=(B, 1)))
+    topk, hsh, want_topk, want_hash, flips, flips_screened, ok = compare(vd, ctx, x.astype(np.float32), 6)
+    assert flips_screened == 0 and np.array_equal(hsh[ok], want_hash[ok]) and ok.sum() >= 3
+
+
 def test_error_codes(vd, ctx):
     x = torch.zeros((2, 3, 96), device="cuda")
     for kwargs, code in [(dict(k=30), -1), (dict(k=0), -1), (dict(k=3, f_min=5, f_max=4), -1),
