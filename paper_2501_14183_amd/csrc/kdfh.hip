@@ -91,7 +91,6 @@ struct KdfhArgs {
   int B, N, L, k, f_min, F;
   int log2_rpv;   // rows per variate inside a 32-row block = 1 << log2_rpv
   int nrb;        // 32-row blocks per variate group (> 1 only when B > 32)
-  int vec;        // rows can be read as aligned float4
   int T;          // folded samples in the contraction: t = 0 .. T-1, T = ceil(L / 2)
   int KS;         // contraction steps of 16 that hold them
   int steps;      // steps the kernel runs (KS rounded up to the unroll; the table is zero there)
@@ -132,10 +131,11 @@ __device__ inline int wave_reduce(int v) {
   return __builtin_amdgcn_readlane(v, 63);
 }
 
+// VEC: rows can be read as aligned float4 (L and the strides multiples of 4, aligned base).
 // ITEMS: 8-sample items a thread reads per row block; RING: contraction steps whose table pieces are in
 // flight (2 keeps the kernel inside 128 registers, so that four blocks share a compute unit).
-template <int ITEMS, int RING>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(RING == 2 ? 4 : 1))) void kdfh_kernel(KdfhArgs a) {
+template <int ITEMS, int RING, bool VEC>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(RING == 2 ? 4 : (ITEMS <= 4 ? 2 : 1)))) void kdfh_kernel(KdfhArgs a) {
   extern __shared__ halfx8 lds8[];
   const int L = a.L, F = a.F, T = a.T;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -166,7 +166,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(RING =
     if (tid < 32) rowmax[tid] = 0u;
     // the first steps of the wavefront's first bin tile are requested before the windows are when
     // the windows leave the registers for it (short windows), else right before the contraction
-    constexpr bool kEarly = ITEMS <= 2;
+    constexpr bool kEarly = false;
 #define KDFH_PRIME()                                        \
   {                                                         \
     const halfx8* tb = a.tw + (size_t)ctp * 256 + lane;     \
@@ -181,63 +181,74 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(RING =
     if (kEarly) KDFH_PRIME()
     __syncthreads();
 
-    // ---- read: item (r, g) = samples t = 8g .. 8g+7 of row r and their mirror images L - t
-    float dv[ITEMS][8], mv[ITEMS][8], ny[ITEMS];
+    // ---- read: item (r, g) = samples t = 8g .. 8g+7 of row r and their mirror images L - t.  Every load is
+    // unconditional (addresses are clamped into the row, rows into the input) and issued before any is used.
+    float dv[ITEMS][8], mv[ITEMS][8];
+    int ir[ITEMS], ig[ITEMS];
+    float nyv = 0.f;                               // x[L/2] of row tid (threads 0..31, even L)
+    {
+      const int nn = n0 + (tid >> a.log2_rpv), bb = rb * 32 + (tid & (rpv - 1));
+      if (tid < 32 && even && nn < a.N && bb < a.B) nyv = a.x[(long long)bb * a.sb + (long long)nn * a.sn + (L >> 1)];
+    }
 #pragma unroll
     for (int it = 0; it < ITEMS; ++it) {
-      const int i = it * kThreads + tid;
-      const bool live = i < 32 * KG;
-      const int r = live ? i / KG : 0;
-      const int g = live ? i - r * KG : 0;
+      const int i = min(it * kThreads + tid, 32 * KG - 1);   // (a thread past the last item repeats it and stores nothing)
+      const int r = i / KG;
+      const int g = i - r * KG;
+      ir[it] = r;
+      ig[it] = g;
       const int t0 = 8 * g;
       const int nn = n0 + (r >> a.log2_rpv), bb = rb * 32 + (r & (rpv - 1));
-      const bool ok = live && nn < a.N && bb < a.B;          // rows past the end are zero windows
       const float* p = a.x + (long long)min(bb, a.B - 1) * a.sb + (long long)min(nn, a.N - 1) * a.sn;
-      if (a.vec) {
-        // L is a multiple of 4 here, so a float4 that starts below L ends below it
-        const float4 u0 = *reinterpret_cast<const float4*>(p + min(t0, L - 4));
-        const float4 u1 = *reinterpret_cast<const float4*>(p + min(t0 + 4, L - 4));
+      if (VEC) {
+        // L is a multiple of 4 and at least 8 here.  The mirror images x[L - t0 - 7 .. L - t0] are the aligned
+        // float4 at L - t0 - 8 (its last three samples), the one at L - t0 - 4 and one more sample.  An item that
+        // starts past L - 8 reads the row's last 8 samples instead: none of its samples is inside the fold.
+        const int tc = min(t0, L - 8);
+        const float4* pd = reinterpret_cast<const float4*>(p + tc);
+        const float4* pm = reinterpret_cast<const float4*>(p + (L - 8 - tc));
+        const float4 u0 = pd[0], u1 = pd[1], ua = pm[0], ub = pm[1];
+        mv[it][0] = p[min(L - tc, L - 1)];
         dv[it][0] = u0.x; dv[it][1] = u0.y; dv[it][2] = u0.z; dv[it][3] = u0.w;
         dv[it][4] = u1.x; dv[it][5] = u1.y; dv[it][6] = u1.z; dv[it][7] = u1.w;
+        mv[it][1] = ub.w; mv[it][2] = ub.z; mv[it][3] = ub.y; mv[it][4] = ub.x;
+        mv[it][5] = ua.w; mv[it][6] = ua.z; mv[it][7] = ua.y;
       } else {
 #pragma unroll
-        for (int j = 0; j < 8; ++j) dv[it][j] = p[min(t0 + j, L - 1)];
+        for (int j = 0; j < 8; ++j) {
+          dv[it][j] = p[min(t0 + j, L - 1)];
+          mv[it][j] = p[min(max(L - t0 - j, 0), L - 1)];
+        }
       }
-      float mr[8];                                 // mirror images x[L - t]
-      if (a.vec) {
-        // x[L - t0 - 7 .. L - t0] = the aligned float4 at L - t0 - 8 (last three), the one at L - t0 - 4 and
-        // one more sample; wherever the clamps move an address, none of its samples is a valid mirror image
-        const int ma = L - t0 - 8;
-        const float4 ua = *reinterpret_cast<const float4*>(p + min(max(ma, 0), L - 4));
-        const float4 ub = *reinterpret_cast<const float4*>(p + min(max(ma + 4, 0), L - 4));
-        mr[0] = p[min(max(ma + 8, 0), L - 1)];
-        mr[1] = ub.w; mr[2] = ub.z; mr[3] = ub.y; mr[4] = ub.x;
-        mr[5] = ua.w; mr[6] = ua.z; mr[7] = ua.y;
-      } else {
+    }
+    // ---- zero what lies outside the window or the input; largest magnitude of every row
 #pragma unroll
-        for (int j = 0; j < 8; ++j) mr[j] = p[min(max(L - t0 - j, 0), L - 1)];
-      }
+    for (int it = 0; it < ITEMS; ++it) {
+      const int r = ir[it], t0 = 8 * ig[it];
+      const int nn = n0 + (r >> a.log2_rpv), bb = rb * 32 + (r & (rpv - 1));
+      const bool ok = nn < a.N && bb < a.B;                  // rows past the end are zero windows
+      float mx = 0.f;
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
         const int t = t0 + j;
         dv[it][j] = (ok && t < T) ? dv[it][j] : 0.f;
-        mv[it][j] = (ok && t >= 1 && t < T) ? mr[j] : 0.f;
+        mv[it][j] = (ok && t >= 1 && t < T) ? mv[it][j] : 0.f;
+        mx = fmaxf(mx, fmaxf(fabsf(dv[it][j]), fabsf(mv[it][j])));
       }
-      ny[it] = (ok && even && g == 0) ? p[L >> 1] : 0.f;
-      float mx = fabsf(ny[it]);
-#pragma unroll
-      for (int j = 0; j < 8; ++j) mx = fmaxf(mx, fmaxf(fabsf(dv[it][j]), fabsf(mv[it][j])));
-      if (live) atomicMax(&rowmax[r], __float_as_uint(mx));
+      atomicMax(&rowmax[r], __float_as_uint(mx));
     }
+    if (tid < 32) atomicMax(&rowmax[tid], __float_as_uint(fabsf(nyv)));
     __syncthreads();
 
     // ---- scale by a power of two, fold, split, store the operand pieces
+    if (tid < 32) {
+      const int se = min(max(266 - (int)(rowmax[tid] >> 23), 1), 253);
+      rowinv[tid] = __uint_as_float((unsigned)(254 - se) << 23);
+      xnyq[tid] = nyv * __uint_as_float((unsigned)se << 23);
+    }
 #pragma unroll
     for (int it = 0; it < ITEMS; ++it) {
-      const int i = it * kThreads + tid;
-      const bool live = i < 32 * KG;
-      const int r = live ? i / KG : 0;
-      const int g = live ? i - r * KG : 0;
+      const int r = ir[it], g = ig[it];
       const int e = (int)(rowmax[r] >> 23);                  // biased exponent of the row's largest magnitude
       const int se = min(max(266 - e, 1), 253);              // scale = 2^(12 - (e - 127)), clamped to normal numbers
       const float sc = __uint_as_float((unsigned)se << 23);
@@ -252,16 +263,12 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(RING =
       Pieces ps, pd;
       split8(sum, ps);
       split8(dif, pd);
-      if (live) {
+      if (it * kThreads + tid < 32 * KG) {
         halfx8* q = opnd + r * pitch + g;
         q[0] = ps.hi;
         q[32 * pitch] = ps.lo;
         q[64 * pitch] = pd.hi;
         q[96 * pitch] = pd.lo;
-        if (g == 0) {
-          rowinv[r] = __uint_as_float((unsigned)(254 - se) << 23);
-          xnyq[r] = ny[it] * sc;
-        }
       }
     }
     if (!kEarly) KDFH_PRIME()
@@ -430,13 +437,13 @@ size_t kdfh_lds_bytes(int pitch, int F, int Vb) {
   return (size_t)4 * 32 * pitch * 16 + sizeof(float) * (3 * 32 + (size_t)Vb * F);
 }
 
-template <int ITEMS, int RING>
+template <int ITEMS, int RING, bool VEC>
 int launch_kdfh(vardrop_ctx* ctx, const KdfhArgs& a, int grid, size_t lds, hipStream_t s) {
   if (lds > 65536)
-    VD_HIP(ctx, hipFuncSetAttribute((const void*)kdfh_kernel<ITEMS, RING>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    VD_HIP(ctx, hipFuncSetAttribute((const void*)kdfh_kernel<ITEMS, RING, VEC>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
   {
     VdTimer timer(ctx, VARDROP_K_HASH, s);
-    hipLaunchKernelGGL((kdfh_kernel<ITEMS, RING>), dim3(grid), dim3(kThreads), lds, s, a);
+    hipLaunchKernelGGL((kdfh_kernel<ITEMS, RING, VEC>), dim3(grid), dim3(kThreads), lds, s, a);
   }
   VD_LAUNCH_CHECK(ctx);
   return VARDROP_OK;
@@ -514,7 +521,6 @@ extern "C" int vardrop_hash(vardrop_ctx* ctx, const float* x, int B, int N, int 
   a.F = F;
   a.log2_rpv = log2_rpv;
   a.nrb = nrb;
-  a.vec = (L % 4 == 0 && sb % 4 == 0 && sn % 4 == 0 && vd_aligned(x, 16)) ? 1 : 0;
   a.T = T;
   a.KS = KS;
   a.steps = steps;
@@ -523,8 +529,14 @@ extern "C" int vardrop_hash(vardrop_ctx* ctx, const float* x, int B, int N, int 
   a.inv_B = 1.0f / (float)B;
   const int grid = vd_ceil_div(N, Vb);
   const int items = vd_ceil_div(32 * 2 * KS, kThreads);
-  if (items <= 1) return launch_kdfh<1, 2>(ctx, a, grid, lds, s);
-  if (items <= 2) return launch_kdfh<2, 4>(ctx, a, grid, lds, s);
-  if (items <= 4) return launch_kdfh<4, 4>(ctx, a, grid, lds, s);
-  return launch_kdfh<8, 4>(ctx, a, grid, lds, s);
+  if (L % 4 == 0 && L >= 8 && sb % 4 == 0 && sn % 4 == 0 && vd_aligned(x, 16)) {
+    if (items <= 1) return launch_kdfh<1, 2, true>(ctx, a, grid, lds, s);
+    if (items <= 2) return launch_kdfh<2, 4, true>(ctx, a, grid, lds, s);
+    if (items <= 4) return launch_kdfh<4, 4, true>(ctx, a, grid, lds, s);
+    return launch_kdfh<8, 4, true>(ctx, a, grid, lds, s);
+  }
+  if (items <= 1) return launch_kdfh<1, 2, false>(ctx, a, grid, lds, s);
+  if (items <= 2) return launch_kdfh<2, 4, false>(ctx, a, grid, lds, s);
+  if (items <= 4) return launch_kdfh<4, 4, false>(ctx, a, grid, lds, s);
+  return launch_kdfh<8, 4, false>(ctx, a, grid, lds, s);
 }
