@@ -91,6 +91,9 @@ def parse():
     ap.add_argument("--batches", type=int, default=4, help="distinct pre-generated batches the steps rotate through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--mode", choices=("steps", "bandwidth"), default="steps")
+    ap.add_argument("--dense", action="store_true",
+                    help="no dropping: one step = attention forward + backward over all N variate tokens of the batch "
+                         "(the selection is the identity, Sec. 3.3 at inference); the comparison point for the speed-up")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run five plain 256 MiB device copies (reference for hardware byte counters)")
     return ap.parse_args()
@@ -296,6 +299,8 @@ def main():
     fences = {}                                         # step -> event recorded on the attention stream after it
 
     def select(i):
+        if args.dense:
+            return
         j = i % RING
         topk, hsh, gid, sel, counts = sel_bufs[j]
         vd.vardrop_hash(ctx, xs_dev[i % args.batches], w.k, out=(topk, hsh), stream=side_h)
@@ -307,12 +312,18 @@ def main():
         nonlocal saved, ws
         j = i % RING
         tok = tok_dev[i % args.batches]
-        sel = sel_bufs[j][3]
-        events[j].synchronize()                    # N' of batch i (launched LOOK steps earlier)
-        n_sel, G = int(pinned[j][0]), int(pinned[j][1])
-        count = w.B * n_sel * w.d
-        shape = (w.B, n_sel, w.d)
-        xs = vd.vardrop_gather(ctx, tok, sel, n_sel, out=xs_buf[:count].view(shape), stream=main_h)
+        if args.dense:
+            n_sel, G = w.N, w.N
+            count = w.B * n_sel * w.d
+            shape = (w.B, n_sel, w.d)
+            xs = tok
+        else:
+            sel = sel_bufs[j][3]
+            events[j].synchronize()                # N' of batch i (launched LOOK steps earlier)
+            n_sel, G = int(pinned[j][0]), int(pinned[j][1])
+            count = w.B * n_sel * w.d
+            shape = (w.B, n_sel, w.d)
+            xs = vd.vardrop_gather(ctx, tok, sel, n_sel, out=xs_buf[:count].view(shape), stream=main_h)
         y, saved = vd.vardrop_attn_fwd(ctx, xs, *W_dev, w.H, saved=saved, out=y_buf[:count].view(shape), stream=main_h)
         dy = dy_full[:count].view(shape)
         grads = vd.vardrop_attn_bwd(ctx, dy, xs, *W_dev, w.H, saved, ws=ws, out=(dxs_buf[:count].view(shape), *dW_buf),
@@ -417,12 +428,16 @@ def main():
             "bracketed_one_launch_in": BRACKET_EVERY,
             "us_per_step_by_kernel": {k: round(v[1], 2) for k, v in census.items()}}
 
+    if args.dense:
+        args.no_cpu_baseline = True                 # the oracle leg times the dropping path
     out = {
-        "metric": "variate-attn train steps/s (kDFH+sample+SDPA fwd/bwd), HBM GB/s, MFMA %peak",
+        "metric": ("dense (no dropping) variate-attn train steps/s (SDPA fwd/bwd over all N tokens)" if args.dense else
+                   "variate-attn train steps/s (kDFH+sample+SDPA fwd/bwd), HBM GB/s, MFMA %peak"),
         "value": 1e3 / ms, "unit": "steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms, "host_issue_ms_per_step": host_ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
-        "config": {"workload": "%s-shaped: B=%d N=%d L=%d k=%d keep=%d/%d d=%d H=%d" %
+        "config": {"workload": ("%s-shaped, dense: B=%d N=%d d=%d H=%d, selection = identity" % (w.name, w.B, w.N, w.d, w.H))
+                               if args.dense else "%s-shaped: B=%d N=%d L=%d k=%d keep=%d/%d d=%d H=%d" %
                                (w.name, w.B, w.N, w.L, w.k, w.ratio[0], w.ratio[1], w.d, w.H),
                    "kept_tokens_mean": n_mean, "groups_mean": float(np.mean(stats["G"])),
                    "batches": args.batches},

@@ -145,32 +145,43 @@ __global__ __launch_bounds__(NW * 64) void sdpa_fwd_bf16(SdpaArgs a) {
 #pragma unroll
       for (int s = 0; s < 4; ++s) st[kt] = mfma(tile_frag(Ks, kt, col, s, half), qf[s], st[kt]);
     }
+    // online softmax on the raw scores: max, then exp2(c s - c max) as one fused multiply-add per score.
+    // Keys past the end exist only in the last block; the running output is rescaled only when some
+    // lane's maximum moved (after the first blocks it rarely does).
+    if (j0 + 64 > n) {
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int j = j0 + kt * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+          st[kt][r] = j < n ? st[kt][r] : -INFINITY;
+        }
+    }
     float mt = -INFINITY;
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int j = j0 + kt * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-        st[kt][r] = j < n ? st[kt][r] * c : -INFINITY;
-        mt = fmaxf(mt, st[kt][r]);
-      }
+      for (int r = 0; r < 16; ++r) mt = fmaxf(mt, st[kt][r]);
     mt = fmaxf(mt, __shfl_xor(mt, 32, 64));
-    const float mn = fmaxf(m, mt);
-    const float alpha = fast_exp2(m - mn);
+    const float mn = fmaxf(m, mt * c);             // c > 0: scaling commutes with the maximum
     float rs = 0.f;
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        st[kt][r] = fast_exp2(st[kt][r] - mn);
+        st[kt][r] = fast_exp2(fmaf(st[kt][r], c, -mn));
         rs += st[kt][r];
       }
-    l = l * alpha + rs;
+    if (__any(mn != m)) {
+      const float alpha = fast_exp2(m - mn);
+      l *= alpha;
+#pragma unroll
+      for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[dt][r] *= alpha;
+    }
+    l += rs;
     m = mn;
-#pragma unroll
-    for (int dt = 0; dt < 2; ++dt)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[dt][r] *= alpha;
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
@@ -241,12 +252,9 @@ __global__ __launch_bounds__(NW * 64) void sdpa_bwd_dq_bf16(SdpaArgs a) {
         st = mfma(tile_frag(Ks, kt, col, s, half), qf[s], st);
         dp = mfma(tile_frag(Vs, kt, col, s, half), dof[s], dp);
       }
+      // (a key past the end has a zero row in both tiles: its dS is finite and meets zeros in the product below)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int j = j0 + kt * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-        const float p = j < n ? fast_exp2(st[r] * c - lse2) : 0.f;
-        st[r] = p * (dp[r] - D);
-      }
+      for (int r = 0; r < 16; ++r) st[r] = fast_exp2(fmaf(st[r], c, -lse2)) * (dp[r] - D);
 #pragma unroll
       for (int s2 = 0; s2 < 2; ++s2) {
         const Frag dsf = regs_to_frag(st, s2);

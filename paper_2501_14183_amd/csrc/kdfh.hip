@@ -104,6 +104,11 @@ struct Tw {
   halfx8 ch, cl, sh, sl;
 };
 
+// One step's left-hand pieces: folded sums (for the cosine) hi / lo, folded differences (for the sine) hi / lo.
+struct Left {
+  halfx8 sh, sl, dh, dl;
+};
+
 __device__ inline void load_tw(Tw& w, const halfx8* p) {
   w.ch = p[0];
   w.cl = p[64];
@@ -279,6 +284,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(RING =
     // Operand layout of v_mfma_f32_32x32x16_f16: left lane holds row lane % 32, k = 8 (lane / 32) + 0..7;
     // right lane holds column lane % 32, the same k; result lane holds column lane % 32, register r holds
     // row 8 (r / 4) + 4 (lane / 32) + r % 4.
+    Left la, lb;
     for (int ti = 0; ti < nt; ++ti) {
       const int ct = ct0 + kWaves * ti;
       floatx16 re = {}, im = {};
@@ -287,18 +293,28 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(RING =
                                  (_Float16)kLoUnscale, (_Float16)kLoUnscale, (_Float16)kLoUnscale, (_Float16)kLoUnscale};
       // the pieces of step S + RING replace those of step S; past the tile's last step they are the first of
       // the wavefront's next tile (of its last step again when there is none: loaded, never used)
-#define KDFH_STEP(W, S)                                                                   \
+      // With RING = 4 the left pieces of step S + 1 are read from LDS while the matrix instructions of step S run
+      // (the first step of the next tile after the last: the windows are the same for every tile).
+#define KDFH_READ_LEFT(A, S)                                                              \
   {                                                                                       \
-    const int g = min(2 * (S) + half, KG - 1); /* steps past KS: the table is zero there */ \
-    const halfx8 sh = pa[g], sl = pa[32 * pitch + g], dh = pa[64 * pitch + g], dl = pa[96 * pitch + g]; \
-    const halfx8 shs = sh * lo_unscale, dhs = dh * lo_unscale;                            \
+    const int sn = (S) >= a.steps ? 0 : (S);                                              \
+    const int g = min(2 * sn + half, KG - 1); /* steps past KS: the table is zero there */ \
+    A.sh = pa[g];                                                                         \
+    A.sl = pa[32 * pitch + g];                                                            \
+    A.dh = pa[64 * pitch + g];                                                            \
+    A.dl = pa[96 * pitch + g];                                                            \
+  }
+#define KDFH_STEP(W, A, AN, S)                                                            \
+  {                                                                                       \
+    if (RING == 4) KDFH_READ_LEFT(AN, (S) + 1) else KDFH_READ_LEFT(A, S)                  \
+    const halfx8 shs = A.sh * lo_unscale, dhs = A.dh * lo_unscale;                        \
     __builtin_amdgcn_sched_barrier(0);                                                    \
-    re = __builtin_amdgcn_mfma_f32_32x32x16_f16(sh, W.ch, re, 0, 0, 0);                   \
-    im = __builtin_amdgcn_mfma_f32_32x32x16_f16(dh, W.sh, im, 0, 0, 0);                   \
+    re = __builtin_amdgcn_mfma_f32_32x32x16_f16(A.sh, W.ch, re, 0, 0, 0);                 \
+    im = __builtin_amdgcn_mfma_f32_32x32x16_f16(A.dh, W.sh, im, 0, 0, 0);                 \
     re = __builtin_amdgcn_mfma_f32_32x32x16_f16(shs, W.cl, re, 0, 0, 0);                  \
     im = __builtin_amdgcn_mfma_f32_32x32x16_f16(dhs, W.sl, im, 0, 0, 0);                  \
-    re = __builtin_amdgcn_mfma_f32_32x32x16_f16(sl, W.ch, re, 0, 0, 0);                   \
-    im = __builtin_amdgcn_mfma_f32_32x32x16_f16(dl, W.sh, im, 0, 0, 0);                   \
+    re = __builtin_amdgcn_mfma_f32_32x32x16_f16(A.sl, W.ch, re, 0, 0, 0);                 \
+    im = __builtin_amdgcn_mfma_f32_32x32x16_f16(A.dl, W.sh, im, 0, 0, 0);                 \
     __builtin_amdgcn_sched_barrier(0);                                                    \
     {                                                                                     \
       const bool wrap = (S) + RING >= a.steps;                                            \
@@ -308,19 +324,21 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(RING =
     }                                                                                     \
     __builtin_amdgcn_sched_barrier(0);                                                    \
   }
+      if (RING == 4 && ti == 0) KDFH_READ_LEFT(la, 0)
       for (int s = 0; s < a.steps; s += 4) {
         if (RING == 4) {
-          KDFH_STEP(w0, s)
-          KDFH_STEP(w1, s + 1)
-          KDFH_STEP(w2, s + 2)
-          KDFH_STEP(w3, s + 3)
+          KDFH_STEP(w0, la, lb, s)
+          KDFH_STEP(w1, lb, la, s + 1)
+          KDFH_STEP(w2, la, lb, s + 2)
+          KDFH_STEP(w3, lb, la, s + 3)
         } else {
-          KDFH_STEP(w0, s)
-          KDFH_STEP(w1, s + 1)
-          KDFH_STEP(w0, s + 2)
-          KDFH_STEP(w1, s + 3)
+          KDFH_STEP(w0, la, lb, s)
+          KDFH_STEP(w1, lb, la, s + 1)
+          KDFH_STEP(w0, la, lb, s + 2)
+          KDFH_STEP(w1, lb, la, s + 3)
         }
       }
+#undef KDFH_READ_LEFT
 #undef KDFH_STEP
 
       // ---- amplitudes, scaled back, and the batch sums (Alg. 1 step 3) of this bin tile
