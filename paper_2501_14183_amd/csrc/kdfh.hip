@@ -140,7 +140,7 @@ __device__ inline int wave_reduce(int v) {
 // ITEMS: 8-sample items a thread reads per row block; RING: contraction steps whose table pieces are in
 // flight (2 keeps the kernel inside 128 registers, so that four blocks share a compute unit).
 template <int ITEMS, int RING, bool VEC>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(RING == 2 ? 4 : (ITEMS <= 4 ? 2 : 1)))) void kdfh_kernel(KdfhArgs a) {
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(RING == 2 ? 3 : (ITEMS <= 4 ? 2 : 1)))) void kdfh_kernel(KdfhArgs a) {
   extern __shared__ halfx8 lds8[];
   const int L = a.L, F = a.F, T = a.T;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -192,7 +192,9 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(RING =
     int ir[ITEMS], ig[ITEMS];
     float nyv = 0.f;                               // x[L/2] of row tid (threads 0..31, even L)
     {
-      const int nn = n0 + (tid >> a.log2_rpv), bb = rb * 32 + (tid & (rpv - 1));
+      int row = tid;
+      asm volatile("" : "+v"(row));                // (keeps this address out of the registers that live across the loop)
+      const int nn = n0 + (row >> a.log2_rpv), bb = rb * 32 + (row & (rpv - 1));
       if (tid < 32 && even && nn < a.N && bb < a.B) nyv = a.x[(long long)bb * a.sb + (long long)nn * a.sn + (L >> 1)];
     }
 #pragma unroll
