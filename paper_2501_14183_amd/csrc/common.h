@@ -18,7 +18,8 @@ struct vardrop_ctx {
   void* twiddle;         // device: k-DFH cosine / sine table in matrix-fragment order (kTwiddleBytes)
   int twiddle_L;         // window length the table currently holds (0: none),
   int twiddle_fmin;      //   its first candidate bin
-  int twiddle_F;         //   and its number of candidate bins
+  int twiddle_F;         //   its number of candidate bins
+  int twiddle_r2;        //   and whether it is laid out for the radix-2 kernel
   int lds_per_block;     // bytes of LDS one workgroup may use
 };
 

@@ -15,6 +15,7 @@ extern "C" int vardrop_create(vardrop_ctx** out, int device_id) {
   c->twiddle_L = 0;
   c->twiddle_fmin = 0;
   c->twiddle_F = 0;
+  c->twiddle_r2 = 0;
   c->prof_kid = -1;
   c->prof_n = 0;
   c->prof_stride = 1;

@@ -7,6 +7,14 @@
 //     Re X_f =  x[0] + (-1)^f x[L/2] + sum_{0<t<L/2} (x[t] + x[L-t]) cos(2 pi f t / L)
 //     Im X_f = -sum_{0<t<L/2} (x[t] - x[L-t]) sin(2 pi f t / L)
 // (rows = windows, columns = bins, contraction = folded time; the x[L/2] term is added afterwards).
+// When L is a multiple of 8 (and the rows can be read as aligned float4) one radix-2 step comes first:
+// with M = L/2, u[t] = x[t] + x[t+M] and v[t] = x[t] - x[t+M], the even bins are the spectrum of u at
+// f/2 and the odd bins that of v with an odd twist, and both fold once more (t <-> M - t):
+//     even f:  Re =  u[0] + (-1)^(f/2) u[M/2] + sum_{0<t<M/2} (u[t] + u[M-t]) cos(2 pi f t / L)
+//              Im = -sum_{0<t<M/2} (u[t] - u[M-t]) sin(2 pi f t / L)
+//     odd f:   Re =  v[0] + sum_{0<t<M/2} (v[t] - v[M-t]) cos(2 pi f t / L)
+//              Im = -sum_{0<t<M/2} (v[t] + v[M-t]) sin(2 pi f t / L) - v[M/2] sin(pi f / 2)
+// so every bin is a contraction over L/4 samples instead of L/2; even and odd bins get tiles of their own.
 //
 // Arithmetic.  The contraction runs on the half-precision matrix cores at fp32 quality: every
 // operand is split as  v = hi + lo  with hi = fp16(v) and lo = fp16(v - hi), and
@@ -54,22 +62,31 @@ __device__ inline void split8(const float (&v)[8], Pieces& p) {
 
 // Table of the twiddle pieces in fragment order: entry ((s * nct + ct) * 4 + kind) * 64 + lane holds,
 // for contraction step s and bin tile ct, the 8 halves of lane `lane` of the right-hand operand
-// (column = bin f_min + 32 ct + lane % 32, rows t = 16 s + 8 (lane / 32) + 0..7); kind 0 / 1 = cosine
-// hi / lo, 2 / 3 = sine hi / lo.  Entries past the last folded sample or the last bin are zero.
-__global__ void twiddle_kernel(halfx8* tw, int L, int f_min, int F, int T, int steps, int nct) {
+// (column = the bin of column lane % 32 of that tile, rows t = 16 s + 8 (lane / 32) + 0..7); kind 0 / 1 = cosine
+// hi / lo, 2 / 3 = sine hi / lo.  Entries past the last contracted sample or the last bin are zero.
+// Bin of column `c` of bin tile `ct`.  Plain: consecutive bins from f_min.  Radix-2: the first nct_e tiles
+// hold the even candidate bins (from fe0, step 2), the rest the odd ones (from fo0).
+struct BinMap {
+  int r2, f_min, nct_e, fe0, fo0;
+};
+__device__ inline int bin_of(const BinMap& m, int ct, int c) {
+  if (!m.r2) return m.f_min + ct * 32 + c;
+  return ct < m.nct_e ? m.fe0 + 2 * (ct * 32 + c) : m.fo0 + 2 * ((ct - m.nct_e) * 32 + c);
+}
+
+__global__ void twiddle_kernel(halfx8* tw, int L, BinMap m, int f_max, int T, int steps, int nct) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= steps * nct * 64) return;
   const int lane = i & 63;
   const int ct = (i >> 6) % nct;
   const int s = (i >> 6) / nct;
-  const int c = ct * 32 + (lane & 31);
-  const int f = f_min + c;
+  const int f = bin_of(m, ct, lane & 31);
   halfx8 out[4];
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
     const int t = 16 * s + 8 * (lane >> 5) + j;
     double sn = 0.0, cs = 0.0;
-    if (t < T && c < F) sincospi(2.0 * (double)(((long long)f * t) % L) / (double)L, &sn, &cs);
+    if (t < T && f <= f_max) sincospi(2.0 * (double)(((long long)f * t) % L) / (double)L, &sn, &cs);
     const _Float16 ch = (_Float16)(float)cs, sh = (_Float16)(float)sn;
     out[0][j] = ch;
     out[1][j] = (_Float16)(float)((cs - (double)(float)ch) * 2048.0);
@@ -89,9 +106,10 @@ struct KdfhArgs {
   float* abar;
   long long sb, sn;
   int B, N, L, k, f_min, F;
+  BinMap bins;
   int log2_rpv;   // rows per variate inside a 32-row block = 1 << log2_rpv
   int nrb;        // 32-row blocks per variate group (> 1 only when B > 32)
-  int T;          // folded samples in the contraction: t = 0 .. T-1, T = ceil(L / 2)
+  int T;          // folded samples in the contraction: t = 0 .. T-1, T = ceil(L / 2), or L / 4 after the radix-2 step
   int KS;         // contraction steps of 16 that hold them
   int steps;      // steps the kernel runs (KS rounded up to the unroll; the table is zero there)
   int nct;        // bin tiles of 32
@@ -137,9 +155,10 @@ __device__ inline int wave_reduce(int v) {
 }
 
 // VEC: rows can be read as aligned float4 (L and the strides multiples of 4, aligned base).
+// R2: radix-2 step before the fold (needs VEC, L a multiple of 8 and at least 64).
 // ITEMS: 8-sample items a thread reads per row block; RING: contraction steps whose table pieces are in
 // flight (2 keeps the kernel inside 128 registers, so that four blocks share a compute unit).
-template <int ITEMS, int RING, bool VEC>
+template <int ITEMS, int RING, bool VEC, bool R2>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(RING == 2 ? 3 : (ITEMS <= 4 ? 2 : 1)))) void kdfh_kernel(KdfhArgs a) {
   extern __shared__ halfx8 lds8[];
   const int L = a.L, F = a.F, T = a.T;
@@ -150,11 +169,13 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(RING =
   const int n0 = blockIdx.x * Vb;
   const int KG = 2 * a.KS;                       // groups of 8 folded samples per row
   const int pitch = a.pitch;
-  halfx8* opnd = lds8;                           // [4][32][pitch]: sum hi, sum lo, difference hi, difference lo
-  unsigned* rowmax = reinterpret_cast<unsigned*>(opnd + 4 * 32 * pitch);   // [32] bits of the largest |x| of a row
+  // [4][32][pitch]: cosine operand hi, lo, sine operand hi, lo; with R2 a second set of four for the odd bins
+  halfx8* opnd = lds8;
+  unsigned* rowmax = reinterpret_cast<unsigned*>(opnd + (R2 ? 8 : 4) * 32 * pitch);   // [32] bits of the largest |x| of a row
   float* rowinv = reinterpret_cast<float*>(rowmax + 32);                   // [32] 1 / scale of a row
-  float* xnyq = rowinv + 32;                                               // [32] scaled x[L/2] (0 when L is odd)
-  float* asum = xnyq + 32;                                                 // [Vb][F]
+  float* xn1 = rowinv + 32;      // [32] scaled middle term of the cosine sum: x[L/2] (0 when L is odd); R2: u[L/4], even bins
+  float* xn2 = xn1 + 32;         // [32] R2: scaled middle term of the sine sum, v[L/4], odd bins
+  float* asum = xn2 + 32;                                                  // [Vb][F]
 
   for (int i = tid; i < Vb * F; i += kThreads) asum[i] = 0.f;
   const bool even = (L & 1) == 0;
@@ -186,6 +207,115 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(RING =
     if (kEarly) KDFH_PRIME()
     __syncthreads();
 
+    if constexpr (R2) {
+      // ---- read, radix-2: item (r, g) = samples t = 8g .. 8g+7 of row r, the ones half a window later, and
+      // the mirror images M - t and L - t (M = L/2); all loads unconditional and in bounds for L >= 64
+      const int M = L >> 1;
+      float xa[ITEMS][8], xb[ITEMS][8], xc[ITEMS][8], xd[ITEMS][8];
+      int ir[ITEMS], ig[ITEMS];
+      float n1 = 0.f, n2 = 0.f;                    // x[L/4] and x[3L/4] of row tid (threads 0..31)
+      {
+        int row = tid;
+        asm volatile("" : "+v"(row));              // (keeps this address out of the registers that live across the loop)
+        const int nn = n0 + (row >> a.log2_rpv), bb = rb * 32 + (row & (rpv - 1));
+        if (tid < 32 && nn < a.N && bb < a.B) {
+          const float* p = a.x + (long long)bb * a.sb + (long long)nn * a.sn;
+          n1 = p[T];
+          n2 = p[T + M];
+        }
+      }
+#pragma unroll
+      for (int it = 0; it < ITEMS; ++it) {
+        const int i = min(it * kThreads + tid, 32 * KG - 1);   // (a thread past the last item repeats it and stores nothing)
+        const int r = i / KG;
+        const int g = i - r * KG;
+        ir[it] = r;
+        ig[it] = g;
+        const int t0 = 8 * g;
+        const int nn = n0 + (r >> a.log2_rpv), bb = rb * 32 + (r & (rpv - 1));
+        const float* p = a.x + (long long)min(bb, a.B - 1) * a.sb + (long long)min(nn, a.N - 1) * a.sn;
+        const float4* pa4 = reinterpret_cast<const float4*>(p + t0);
+        const float4* pb4 = reinterpret_cast<const float4*>(p + M + t0);
+        const float4* pc4 = reinterpret_cast<const float4*>(p + (M - 8 - t0));     // x[M - t0 - 8 .. M - t0 - 1]
+        const float4* pd4 = reinterpret_cast<const float4*>(p + (L - 8 - t0));     // x[L - t0 - 8 .. L - t0 - 1]
+        const float4 a0 = pa4[0], a1 = pa4[1], b0 = pb4[0], b1 = pb4[1];
+        const float4 c0 = pc4[0], c1 = pc4[1], d0 = pd4[0], d1 = pd4[1];
+        xc[it][0] = p[M - t0];
+        xd[it][0] = p[min(L - t0, L - 1)];         // (t = 0 has no mirror image)
+        xa[it][0] = a0.x; xa[it][1] = a0.y; xa[it][2] = a0.z; xa[it][3] = a0.w;
+        xa[it][4] = a1.x; xa[it][5] = a1.y; xa[it][6] = a1.z; xa[it][7] = a1.w;
+        xb[it][0] = b0.x; xb[it][1] = b0.y; xb[it][2] = b0.z; xb[it][3] = b0.w;
+        xb[it][4] = b1.x; xb[it][5] = b1.y; xb[it][6] = b1.z; xb[it][7] = b1.w;
+        xc[it][1] = c1.w; xc[it][2] = c1.z; xc[it][3] = c1.y; xc[it][4] = c1.x;
+        xc[it][5] = c0.w; xc[it][6] = c0.z; xc[it][7] = c0.y;
+        xd[it][1] = d1.w; xd[it][2] = d1.z; xd[it][3] = d1.y; xd[it][4] = d1.x;
+        xd[it][5] = d0.w; xd[it][6] = d0.z; xd[it][7] = d0.y;
+      }
+      // ---- zero what lies outside the fold or the input; largest magnitude of every row; the four folded
+      // sequences replace the samples: cosine / sine operand of the even bins, then of the odd bins
+#pragma unroll
+      for (int it = 0; it < ITEMS; ++it) {
+        const int r = ir[it], t0 = 8 * ig[it];
+        const int nn = n0 + (r >> a.log2_rpv), bb = rb * 32 + (r & (rpv - 1));
+        const bool ok = nn < a.N && bb < a.B;                  // rows past the end are zero windows
+        float mx = 0.f;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const int t = t0 + j;
+          const bool vd = ok && t < T, vm = vd && t >= 1;
+          const float xa_ = vd ? xa[it][j] : 0.f, xb_ = vd ? xb[it][j] : 0.f;
+          const float xc_ = vm ? xc[it][j] : 0.f, xd_ = vm ? xd[it][j] : 0.f;
+          mx = fmaxf(fmaxf(mx, fmaxf(fabsf(xa_), fabsf(xb_))), fmaxf(fabsf(xc_), fabsf(xd_)));
+          const float u = xa_ + xb_, v = xa_ - xb_, um = xc_ + xd_, vm_ = xc_ - xd_;
+          xa[it][j] = u + um;                      // even bins, cosine
+          xb[it][j] = vm ? u - um : 0.f;           // even bins, sine
+          xc[it][j] = v - vm_;                     // odd bins, cosine
+          xd[it][j] = vm ? v + vm_ : 0.f;          // odd bins, sine
+        }
+        atomicMax(&rowmax[r], __float_as_uint(mx));
+      }
+      if (tid < 32) atomicMax(&rowmax[tid], __float_as_uint(fmaxf(fabsf(n1), fabsf(n2))));
+      __syncthreads();
+
+      // ---- scale by a power of two (the folded values are sums of four samples: below 2^15), split, store
+      if (tid < 32) {
+        const int se = min(max(266 - (int)(rowmax[tid] >> 23), 1), 253);
+        const float sc = __uint_as_float((unsigned)se << 23);
+        rowinv[tid] = __uint_as_float((unsigned)(254 - se) << 23);
+        xn1[tid] = (n1 + n2) * sc;
+        xn2[tid] = (n1 - n2) * sc;
+      }
+#pragma unroll
+      for (int it = 0; it < ITEMS; ++it) {
+        const int r = ir[it], g = ig[it];
+        const int se = min(max(266 - (int)(rowmax[r] >> 23), 1), 253);
+        const float sc = __uint_as_float((unsigned)se << 23);
+        float s0[8], s1[8], s2[8], s3[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          s0[j] = xa[it][j] * sc;
+          s1[j] = xb[it][j] * sc;
+          s2[j] = xc[it][j] * sc;
+          s3[j] = xd[it][j] * sc;
+        }
+        Pieces p0, p1, p2, p3;
+        split8(s0, p0);
+        split8(s1, p1);
+        split8(s2, p2);
+        split8(s3, p3);
+        if (it * kThreads + tid < 32 * KG) {
+          halfx8* q = opnd + r * pitch + g;
+          q[0] = p0.hi;
+          q[32 * pitch] = p0.lo;
+          q[64 * pitch] = p1.hi;
+          q[96 * pitch] = p1.lo;
+          q[128 * pitch] = p2.hi;
+          q[160 * pitch] = p2.lo;
+          q[192 * pitch] = p3.hi;
+          q[224 * pitch] = p3.lo;
+        }
+      }
+    } else {
     // ---- read: item (r, g) = samples t = 8g .. 8g+7 of row r and their mirror images L - t.  Every load is
     // unconditional (addresses are clamped into the row, rows into the input) and issued before any is used.
     float dv[ITEMS][8], mv[ITEMS][8];
@@ -251,7 +381,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(RING =
     if (tid < 32) {
       const int se = min(max(266 - (int)(rowmax[tid] >> 23), 1), 253);
       rowinv[tid] = __uint_as_float((unsigned)(254 - se) << 23);
-      xnyq[tid] = nyv * __uint_as_float((unsigned)se << 23);
+      xn1[tid] = nyv * __uint_as_float((unsigned)se << 23);
+      xn2[tid] = 0.f;
     }
 #pragma unroll
     for (int it = 0; it < ITEMS; ++it) {
@@ -278,6 +409,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(RING =
         q[96 * pitch] = pd.lo;
       }
     }
+    }
     if (!kEarly) KDFH_PRIME()
 #undef KDFH_PRIME
     __syncthreads();
@@ -290,21 +422,24 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(RING =
     for (int ti = 0; ti < nt; ++ti) {
       const int ct = ct0 + kWaves * ti;
       floatx16 re = {}, im = {};
-      const halfx8* pa = opnd + col * pitch;
+      // left operands of this tile and of the wavefront's next one (even and odd bins have sets of their own)
+      const halfx8* pa = opnd + ((R2 && ct >= a.bins.nct_e) ? 128 * pitch : 0) + col * pitch;
+      const halfx8* pn = opnd + ((R2 && ct + kWaves >= a.bins.nct_e) ? 128 * pitch : 0) + col * pitch;
       const halfx8 lo_unscale = {(_Float16)kLoUnscale, (_Float16)kLoUnscale, (_Float16)kLoUnscale, (_Float16)kLoUnscale,
                                  (_Float16)kLoUnscale, (_Float16)kLoUnscale, (_Float16)kLoUnscale, (_Float16)kLoUnscale};
       // the pieces of step S + RING replace those of step S; past the tile's last step they are the first of
       // the wavefront's next tile (of its last step again when there is none: loaded, never used)
       // With RING = 4 the left pieces of step S + 1 are read from LDS while the matrix instructions of step S run
-      // (the first step of the next tile after the last: the windows are the same for every tile).
+      // (the first step of the next tile after the last).
 #define KDFH_READ_LEFT(A, S)                                                              \
   {                                                                                       \
-    const int sn = (S) >= a.steps ? 0 : (S);                                              \
-    const int g = min(2 * sn + half, KG - 1); /* steps past KS: the table is zero there */ \
-    A.sh = pa[g];                                                                         \
-    A.sl = pa[32 * pitch + g];                                                            \
-    A.dh = pa[64 * pitch + g];                                                            \
-    A.dl = pa[96 * pitch + g];                                                            \
+    const bool nx = (S) >= a.steps;           /* first step of the wavefront's next tile */ \
+    const halfx8* pl = nx ? pn : pa;                                                      \
+    const int g = min(2 * (nx ? 0 : (S)) + half, KG - 1); /* steps past KS: the table is zero there */ \
+    A.sh = pl[g];                                                                         \
+    A.sl = pl[32 * pitch + g];                                                            \
+    A.dh = pl[64 * pitch + g];                                                            \
+    A.dl = pl[96 * pitch + g];                                                            \
   }
 #define KDFH_STEP(W, A, AN, S)                                                            \
   {                                                                                       \
@@ -344,26 +479,42 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(RING =
 #undef KDFH_STEP
 
       // ---- amplitudes, scaled back, and the batch sums (Alg. 1 step 3) of this bin tile
-      const int c = ct * 32 + col;
-      const float sgn = ((a.f_min + c) & 1) ? -1.f : 1.f;    // (-1)^f of the x[L/2] term
+      const int f = bin_of(a.bins, ct, col);
+      const int c = f - a.f_min;                   // index of this lane's bin among the candidates
+      // middle terms of the two sums: plain (-1)^f x[L/2] in the cosine sum; radix-2 (-1)^(f/2) u[L/4] in the
+      // cosine sum of an even bin, sin(pi f / 2) v[L/4] in the sine sum of an odd one
+      float cr, ci;
+      if (!R2) {
+        cr = (f & 1) ? -1.f : 1.f;
+        ci = 0.f;
+      } else if (ct < a.bins.nct_e) {
+        cr = (f & 2) ? -1.f : 1.f;
+        ci = 0.f;
+      } else {
+        cr = 0.f;
+        ci = (f & 2) ? -1.f : 1.f;
+      }
       float amp[16];
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         const float4 inv4 = *reinterpret_cast<const float4*>(rowinv + 8 * q + 4 * half);
-        const float4 nyq4 = *reinterpret_cast<const float4*>(xnyq + 8 * q + 4 * half);
+        const float4 m14 = *reinterpret_cast<const float4*>(xn1 + 8 * q + 4 * half);
+        const float4 m24 = *reinterpret_cast<const float4*>(xn2 + 8 * q + 4 * half);
         const float inv[4] = {inv4.x, inv4.y, inv4.z, inv4.w};
-        const float nyq[4] = {nyq4.x, nyq4.y, nyq4.z, nyq4.w};
+        const float m1[4] = {m14.x, m14.y, m14.z, m14.w};
+        const float m2[4] = {m24.x, m24.y, m24.z, m24.w};
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int r = 4 * q + e;
-          const float rv = re[r] + sgn * nyq[e];
-          amp[r] = sqrtf(rv * rv + im[r] * im[r]) * inv[e];
+          const float rv = re[r] + cr * m1[e];
+          const float iv = im[r] + ci * m2[e];
+          amp[r] = sqrtf(rv * rv + iv * iv) * inv[e];
         }
       }
       float qs[4];                                 // rows 8q + 4 half + 0..3
 #pragma unroll
       for (int q = 0; q < 4; ++q) qs[q] = (amp[4 * q] + amp[4 * q + 1]) + (amp[4 * q + 2] + amp[4 * q + 3]);
-      const bool live = c < F;
+      const bool live = c < F;                     // (bins step by 2 with R2, so the tile's last columns may lie past f_max)
       if (a.log2_rpv >= 3) {
         // a variate spans 8, 16 or 32 rows: both lane halves hold four rows of every 8
         float vs[4];
@@ -453,17 +604,17 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(RING =
   }
 }
 
-size_t kdfh_lds_bytes(int pitch, int F, int Vb) {
-  return (size_t)4 * 32 * pitch * 16 + sizeof(float) * (3 * 32 + (size_t)Vb * F);
+size_t kdfh_lds_bytes(int pitch, int F, int Vb, bool r2) {
+  return (size_t)(r2 ? 8 : 4) * 32 * pitch * 16 + sizeof(float) * (4 * 32 + (size_t)Vb * F);
 }
 
-template <int ITEMS, int RING, bool VEC>
+template <int ITEMS, int RING, bool VEC, bool R2>
 int launch_kdfh(vardrop_ctx* ctx, const KdfhArgs& a, int grid, size_t lds, hipStream_t s) {
   if (lds > 65536)
-    VD_HIP(ctx, hipFuncSetAttribute((const void*)kdfh_kernel<ITEMS, RING, VEC>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    VD_HIP(ctx, hipFuncSetAttribute((const void*)kdfh_kernel<ITEMS, RING, VEC, R2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
   {
     VdTimer timer(ctx, VARDROP_K_HASH, s);
-    hipLaunchKernelGGL((kdfh_kernel<ITEMS, RING, VEC>), dim3(grid), dim3(kThreads), lds, s, a);
+    hipLaunchKernelGGL((kdfh_kernel<ITEMS, RING, VEC, R2>), dim3(grid), dim3(kThreads), lds, s, a);
   }
   VD_LAUNCH_CHECK(ctx);
   return VARDROP_OK;
@@ -506,24 +657,37 @@ extern "C" int vardrop_hash(vardrop_ctx* ctx, const float* x, int B, int N, int 
     nrb = 1;
   }
   const int Vb = 32 >> log2_rpv;
-  const int T = (L + 1) / 2;
+  const bool vec = L % 4 == 0 && L >= 8 && sb % 4 == 0 && sn % 4 == 0 && vd_aligned(x, 16);
+  // the radix-2 step pays when it saves contraction steps (they come in fours): from L = 136 on
+  const bool r2 = vec && L % 8 == 0 && L >= 64 &&
+                  ((vd_ceil_div(L / 4, 16) + 3) & ~3) < ((vd_ceil_div((L + 1) / 2, 16) + 3) & ~3);
+  BinMap bins;
+  bins.r2 = r2 ? 1 : 0;
+  bins.f_min = f_min;
+  bins.fe0 = f_min + (f_min & 1);                      // first even and first odd candidate bin
+  bins.fo0 = f_min + 1 - (f_min & 1);
+  const int n_even = bins.fe0 <= f_max ? (f_max - bins.fe0) / 2 + 1 : 0;
+  const int n_odd = bins.fo0 <= f_max ? (f_max - bins.fo0) / 2 + 1 : 0;
+  bins.nct_e = r2 ? vd_ceil_div(n_even, 32) : 0;
+  const int T = r2 ? L / 4 : (L + 1) / 2;
   const int KS = vd_ceil_div(T, 16);
   const int steps = (KS + 3) & ~3;
-  const int nct = vd_ceil_div(F, 32);
+  const int nct = r2 ? bins.nct_e + vd_ceil_div(n_odd, 32) : vd_ceil_div(F, 32);
   const int pitch = (2 * KS) | 1;
-  const size_t lds = kdfh_lds_bytes(pitch, F, Vb);
+  const size_t lds = kdfh_lds_bytes(pitch, F, Vb, r2);
   if (lds > (size_t)ctx->lds_per_block) return VARDROP_EUNSUPPORTED;
   if ((size_t)steps * nct * 4096 > kTwiddleBytes) return VARDROP_EUNSUPPORTED;   // (cannot happen within the limits above)
 
   hipStream_t s = (hipStream_t)stream;
-  if (ctx->twiddle_L != L || ctx->twiddle_fmin != f_min || ctx->twiddle_F != F) {
+  if (ctx->twiddle_L != L || ctx->twiddle_fmin != f_min || ctx->twiddle_F != F || ctx->twiddle_r2 != bins.r2) {
     const int entries = steps * nct * 64;
     hipLaunchKernelGGL(twiddle_kernel, dim3(vd_ceil_div(entries, 256)), dim3(256), 0, s,
-                       (halfx8*)ctx->twiddle, L, f_min, F, T, steps, nct);
+                       (halfx8*)ctx->twiddle, L, bins, f_max, T, steps, nct);
     VD_LAUNCH_CHECK(ctx);
     ctx->twiddle_L = L;
     ctx->twiddle_fmin = f_min;
     ctx->twiddle_F = F;
+    ctx->twiddle_r2 = bins.r2;
   }
   KdfhArgs a;
   a.x = x;
@@ -539,6 +703,7 @@ extern "C" int vardrop_hash(vardrop_ctx* ctx, const float* x, int B, int N, int 
   a.k = k;
   a.f_min = f_min;
   a.F = F;
+  a.bins = bins;
   a.log2_rpv = log2_rpv;
   a.nrb = nrb;
   a.T = T;
@@ -549,14 +714,19 @@ extern "C" int vardrop_hash(vardrop_ctx* ctx, const float* x, int B, int N, int 
   a.inv_B = 1.0f / (float)B;
   const int grid = vd_ceil_div(N, Vb);
   const int items = vd_ceil_div(32 * 2 * KS, kThreads);
-  if (L % 4 == 0 && L >= 8 && sb % 4 == 0 && sn % 4 == 0 && vd_aligned(x, 16)) {
-    if (items <= 1) return launch_kdfh<1, 2, true>(ctx, a, grid, lds, s);
-    if (items <= 2) return launch_kdfh<2, 4, true>(ctx, a, grid, lds, s);
-    if (items <= 4) return launch_kdfh<4, 4, true>(ctx, a, grid, lds, s);
-    return launch_kdfh<8, 4, true>(ctx, a, grid, lds, s);
+  if (r2) {
+    if (items <= 1) return launch_kdfh<1, 2, true, true>(ctx, a, grid, lds, s);
+    if (items <= 2) return launch_kdfh<2, 4, true, true>(ctx, a, grid, lds, s);
+    return launch_kdfh<4, 4, true, true>(ctx, a, grid, lds, s);
   }
-  if (items <= 1) return launch_kdfh<1, 2, false>(ctx, a, grid, lds, s);
-  if (items <= 2) return launch_kdfh<2, 4, false>(ctx, a, grid, lds, s);
-  if (items <= 4) return launch_kdfh<4, 4, false>(ctx, a, grid, lds, s);
-  return launch_kdfh<8, 4, false>(ctx, a, grid, lds, s);
+  if (vec) {
+    if (items <= 1) return launch_kdfh<1, 2, true, false>(ctx, a, grid, lds, s);
+    if (items <= 2) return launch_kdfh<2, 4, true, false>(ctx, a, grid, lds, s);
+    if (items <= 4) return launch_kdfh<4, 4, true, false>(ctx, a, grid, lds, s);
+    return launch_kdfh<8, 4, true, false>(ctx, a, grid, lds, s);
+  }
+  if (items <= 1) return launch_kdfh<1, 2, false, false>(ctx, a, grid, lds, s);
+  if (items <= 2) return launch_kdfh<2, 4, false, false>(ctx, a, grid, lds, s);
+  if (items <= 4) return launch_kdfh<4, 4, false, false>(ctx, a, grid, lds, s);
+  return launch_kdfh<8, 4, false, false>(ctx, a, grid, lds, s);
 }

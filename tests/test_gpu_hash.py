@@ -104,6 +104,23 @@ def test_candidate_range_parameters(vd, ctx):
     assert fs == 0 and topk.min() >= 7 and topk.max() <= 16 and sorted(topk[0].tolist()) == list(range(7, 17))
 
 
+@pytest.mark.parametrize("f_min,f_max,k", [(0, 128, 4), (1, 64, 3), (2, 63, 5), (7, 40, 6), (5, 5, 1), (64, 128, 3)])
+def test_candidate_range_on_a_long_window(vd, ctx, f_min, f_max, k):
+    """Even and odd first bins, ranges that end inside a tile of 32, the DC and the Nyquist bin, at a window
+    length where the kernel splits the bins by parity."""
+    rng = np.random.default_rng(100 * f_min + f_max)
+    B, N, L = 8, 10, 256
+    t = np.arange(L)
+    x = 0.3 * rng.standard_normal((B, N, L)) + 0.5
+    for n in range(N):
+        for j, f in enumerate(rng.choice(np.arange(f_min, f_max + 1), size=min(k, f_max - f_min + 1), replace=False)):
+            x[:, n] += (3.0 / (1 + j)) * np.cos(2 * np.pi * f * t / L + rng.uniform(0, 6, size=(B, 1)))
+    topk, hsh, want_topk, want_hash, flips, fs, ok = compare(vd, ctx, x.astype(np.float32), k, f_min=f_min, f_max=f_max)
+    assert fs == 0 and ok.sum() >= N // 2
+    assert topk.min() >= f_min and topk.max() <= f_max
+    assert np.array_equal(hsh[ok], want_hash[ok])
+
+
 def test_strided_input_and_determinism(vd, ctx):
     rng = np.random.default_rng(5)
     big = torch.from_numpy(rng.standard_normal((6, 20, 128)).astype(np.float32)).cuda()
