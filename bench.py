@@ -1,8 +1,8 @@
 #!/usr/bin/env python3
 """Benchmark of the VarDrop training hot path on one MI355X.
 
-One step = vardrop_hash -> vardrop_sample -> (read N') -> vardrop_gather -> vardrop_attn_fwd
--> vardrop_attn_bwd over one batch of synthetic windows and tokens that already sit in HBM.  The
+One step = vardrop_hash -> vardrop_sample -> (read N') -> vardrop_gather_attn_fwd (= vardrop_gather
++ vardrop_attn_fwd) -> vardrop_attn_bwd over one batch of synthetic windows and tokens that already sit in HBM.  The
 selection (hash + sample) of batch i+1 is enqueued before the attention of batch i, on a second stream.
 Prints ONE JSON line: steps/s, the roofline figure of the dominant kernel, and the CPU
 oracle timed on a bounded sample of the same workload.
@@ -323,8 +323,12 @@ def main():
             n_sel, G = int(pinned[j][0]), int(pinned[j][1])
             count = w.B * n_sel * w.d
             shape = (w.B, n_sel, w.d)
-            xs = vd.vardrop_gather(ctx, tok, sel, n_sel, out=xs_buf[:count].view(shape), stream=main_h)
-        y, saved = vd.vardrop_attn_fwd(ctx, xs, *W_dev, w.H, saved=saved, out=y_buf[:count].view(shape), stream=main_h)
+        if args.dense:
+            y, saved = vd.vardrop_attn_fwd(ctx, xs, *W_dev, w.H, saved=saved, out=y_buf[:count].view(shape), stream=main_h)
+        else:
+            # gather + forward in one call: for N' <= 128 the forward kernel fetches the kept rows itself
+            xs, y, saved = vd.vardrop_gather_attn_fwd(ctx, tok, sel, n_sel, *W_dev, w.H, saved=saved,
+                                                      out=(xs_buf[:count].view(shape), y_buf[:count].view(shape)), stream=main_h)
         dy = dy_full[:count].view(shape)
         grads = vd.vardrop_attn_bwd(ctx, dy, xs, *W_dev, w.H, saved, ws=ws, out=(dxs_buf[:count].view(shape), *dW_buf),
                                       stream=main_h)

@@ -186,6 +186,17 @@ int vardrop_attn_fwd(vardrop_ctx* ctx, const void* xs, int B, int n, int d, int 
                      const void* Wq, const void* Wk, const void* Wv, const void* Wo,
                      const void* bq, const void* bk, const void* bv, const void* bo,
                      void* y, void* saved, void* ws, size_t ws_bytes, void* stream);
+/* vardrop_gather followed by vardrop_attn_fwd in one call (Sec. 3.3: attention runs on the selected
+ * tokens): `tokens` [B][N][d] holds all variates, `sel` (device, int32) the n kept rows in ascending
+ * order; `xs` [B][n][d] receives the kept tokens (the backward pass needs them), y and `saved` are
+ * those of vardrop_attn_fwd.  For VARDROP_BF16 and n <= 128 the gather happens inside the forward
+ * kernel, which saves a launch; otherwise the two steps run one after the other.  Results are
+ * identical to the two separate calls.  Also requires n <= N and, for VARDROP_BF16, B*N*d < 2^31. */
+int vardrop_gather_attn_fwd(vardrop_ctx* ctx, const void* tokens, int B, int N, const int32_t* sel, int n,
+                            int d, int H, int dtype,
+                            const void* Wq, const void* Wk, const void* Wv, const void* Wo,
+                            const void* bq, const void* bk, const void* bv, const void* bo,
+                            void* xs, void* y, void* saved, void* ws, size_t ws_bytes, void* stream);
 int vardrop_attn_bwd(vardrop_ctx* ctx, const void* dy, const void* xs,
                      int B, int n, int d, int H, int dtype,
                      const void* Wq, const void* Wk, const void* Wv, const void* Wo,

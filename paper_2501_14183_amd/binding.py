@@ -42,6 +42,8 @@ _SIGNATURES = {
     "vardrop_attn_workspace_bytes": (_c_size, [_c_int] * 5),
     "vardrop_attn_fwd": (_c_int, [_ptr, _ptr, _c_int, _c_int, _c_int, _c_int, _c_int] + [_ptr] * 8 +
                          [_ptr, _ptr, _ptr, _c_size, _ptr]),
+    "vardrop_gather_attn_fwd": (_c_int, [_ptr, _ptr, _c_int, _c_int, _ptr, _c_int, _c_int, _c_int, _c_int] + [_ptr] * 8 +
+                                [_ptr, _ptr, _ptr, _ptr, _c_size, _ptr]),
     "vardrop_attn_bwd": (_c_int, [_ptr, _ptr, _ptr, _c_int, _c_int, _c_int, _c_int, _c_int] + [_ptr] * 4 +
                          [_ptr] + [_ptr] * 9 + [_ptr, _c_size, _ptr]),
 }
@@ -223,6 +225,27 @@ def vardrop_attn_fwd(ctx, xs, Wq, Wk, Wv, Wo, H, bq=None, bk=None, bv=None, bo=N
                                    _p(bq), _p(bk), _p(bv), _p(bo), _p(y), _p(saved), None, 0, _stream(xs, stream))
     ctx.check(rc, "vardrop_attn_fwd")
     return y, saved
+
+
+def vardrop_gather_attn_fwd(ctx, tokens, sel, n_sel, Wq, Wk, Wv, Wo, H, bq=None, bk=None, bv=None, bo=None,
+                            saved=None, out=None, stream=None):
+    """tokens [B, N, d], sel int32 (first n_sel entries: the kept rows) -> (xs [B, n_sel, d], y [B, n_sel, d], saved):
+    the gather and the attention forward in one call.  `out`, when given, is the pair (xs, y) to write into."""
+    B, N, d = tokens.shape
+    code = _dtype_code(tokens)
+    nbytes = ctx._lib.vardrop_attn_saved_bytes(B, n_sel, d, H, code)
+    if saved is None or saved.numel() < nbytes:
+        saved = torch.empty((max(nbytes, 256),), dtype=torch.uint8, device=tokens.device)
+    if out is not None:
+        xs, y = out
+    else:
+        xs = torch.empty((B, n_sel, d), dtype=tokens.dtype, device=tokens.device)
+        y = torch.empty_like(xs)
+    rc = ctx._lib.vardrop_gather_attn_fwd(ctx.handle, _p(tokens), B, N, _p(sel), n_sel, d, H, code,
+                                          _p(Wq), _p(Wk), _p(Wv), _p(Wo), _p(bq), _p(bk), _p(bv), _p(bo),
+                                          _p(xs), _p(y), _p(saved), None, 0, _stream(tokens, stream))
+    ctx.check(rc, "vardrop_gather_attn_fwd")
+    return xs, y, saved
 
 
 def vardrop_attn_bwd(ctx, dy, xs, Wq, Wk, Wv, Wo, H, saved, bias_grads=False, ws=None, out=None, stream=None):

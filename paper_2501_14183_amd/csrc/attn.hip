@@ -70,6 +70,32 @@ extern "C" int vardrop_attn_fwd(vardrop_ctx* ctx, const void* xs, int B, int n, 
   return vd_attn_fwd_bf16(ctx, xs, B, n, d, H, W, bias, y, saved, ws, s);
 }
 
+extern "C" int vardrop_gather_attn_fwd(vardrop_ctx* ctx, const void* tokens, int B, int N, const int32_t* sel, int n,
+                                       int d, int H, int dtype,
+                                       const void* Wq, const void* Wk, const void* Wv, const void* Wo,
+                                       const void* bq, const void* bk, const void* bv, const void* bo,
+                                       void* xs, void* y, void* saved, void* ws, size_t ws_bytes, void* stream) {
+  if (!ctx) return VARDROP_EINVAL;
+  if (N < 0 || n > N) return VARDROP_EINVAL;
+  int rc = check_shape(B, n, d, H, dtype);
+  if (rc) return rc;
+  if ((long long)B * n == 0) return VARDROP_OK;
+  if (!tokens || !sel || !xs || !vd_aligned(tokens, 16) || !vd_aligned(xs, 16)) return VARDROP_EINVAL;
+  if (dtype == VARDROP_BF16 && (long long)B * N * d >= (1ll << 31)) return VARDROP_EUNSUPPORTED;
+  if (dtype == VARDROP_F32) {
+    rc = vardrop_gather(ctx, tokens, B, N, d, dtype, sel, n, xs, stream);
+    if (rc) return rc;
+    return vardrop_attn_fwd(ctx, xs, B, n, d, H, dtype, Wq, Wk, Wv, Wo, bq, bk, bv, bo, y, saved, ws, ws_bytes, stream);
+  }
+  if (!Wq || !Wk || !Wv || !Wo || !y || !saved) return VARDROP_EINVAL;
+  if (!vd_aligned(saved, 256)) return VARDROP_EWORKSPACE;
+  if (!vd_aligned(y, 16) || !vd_aligned(Wq, 16) || !vd_aligned(Wk, 16) || !vd_aligned(Wv, 16) || !vd_aligned(Wo, 16))
+    return VARDROP_EINVAL;
+  const void* W[4] = {Wq, Wk, Wv, Wo};
+  const void* bias[4] = {bq, bk, bv, bo};
+  return vd_attn_fwd_bf16(ctx, tokens, B, n, d, H, W, bias, y, saved, ws, (hipStream_t)stream, sel, N, xs);
+}
+
 extern "C" int vardrop_attn_bwd(vardrop_ctx* ctx, const void* dy, const void* xs,
                                 int B, int n, int d, int H, int dtype,
                                 const void* Wq, const void* Wk, const void* Wv, const void* Wo,

@@ -666,6 +666,8 @@ __global__ __launch_bounds__(512) void sdpa_bwd_small_bf16(SdpaArgs a) {
 // asynchronous copies three stages deep), leaves them in LDS, and runs the attention of the head on
 // them; Q, K, V, O and the log-sum-exp are written for the backward pass.  Compared with a projection
 // GEMM followed by an attention kernel this saves a launch and the round trip of Q, K, V through memory.
+// With a selection it also gathers: the token rows are fetched through `sel`, and workgroup (batch, head)
+// writes the head's 64 columns of the gathered tokens for the backward pass.
 //   projection: eight wavefronts as 4 x 2, each 32 tokens x 96 columns (three matrix-instruction tiles);
 //               xs tile [token][64 k] read as 16-byte fragments, weight tiles [64 k][64 columns]
 //               through transposing reads; product formed transposed so that a lane owns a token.
@@ -673,7 +675,10 @@ __global__ __launch_bounds__(512) void sdpa_bwd_small_bf16(SdpaArgs a) {
 //               over its keys, O^T = V^T P^T with V^T taken from the V tile by transposing reads; the two
 //               halves of a query block are merged through LDS (maxima, sums, rescaled outputs).
 struct FusedFwdArgs {
-  const bf16_t* xs;
+  const bf16_t* xs;               // [B][n][d]; with `sel` the tokens of all variates, [B][N][d]
+  const int32_t* sel;             // optional: token row i of a batch is row sel[i] of `xs` (the gather of the
+  bf16_t* xs_out;                 //   kept tokens is then part of this kernel, and they are written to xs_out)
+  int N;
   const bf16_t *Wq, *Wk, *Wv;
   const bf16_t *bq, *bk, *bv;
   bf16_t *q, *k, *v, *o;
@@ -702,17 +707,21 @@ __global__ __launch_bounds__(512) void attn_fwd_small_bf16(FusedFwdArgs a) {
   const int h = tix % a.H, b = tix / a.H;
   const int n = a.n, d = a.d;
   const long long ld = d;
-  const bf16_t* xs_b = a.xs + (long long)b * n * ld;
+  const bf16_t* xs_b = a.xs + (long long)b * (a.sel ? a.N : n) * ld;
   const int total = d / 64;
 
   // ---- copy sources.  xs: copy u covers token rows 8*(8u + wave) .. +7.  Weights: copy u belongs to
   // matrix u and covers its k-rows 8*wave .. +7 of the slice.
   const bf16_t* srcA[2];
   const bf16_t* srcB[3];
+  u32x4 kept[2];                  // this thread's 16 bytes of two gathered rows, columns of head h
 #pragma unroll
   for (int u = 0; u < 2; ++u) {
     const int row = (u * 8 + wave) * 8 + (lane >> 3);
-    srcA[u] = xs_b + (long long)min(row, n - 1) * ld + (((lane & 7) ^ (row & 7)) * 8);
+    int src_row = min(row, n - 1);
+    if (a.sel) src_row = a.sel[src_row];
+    srcA[u] = xs_b + (long long)src_row * ld + (((lane & 7) ^ (row & 7)) * 8);
+    if (a.sel) kept[u] = *reinterpret_cast<const u32x4*>(xs_b + (long long)src_row * ld + h * kDh + (lane & 7) * 8);
   }
 #pragma unroll
   for (int u = 0; u < 3; ++u) {
@@ -817,6 +826,13 @@ __global__ __launch_bounds__(512) void attn_fwd_small_bf16(FusedFwdArgs a) {
   __syncthreads();
   // copy the tiles out for the backward pass: 16-byte chunks, eight per token row
   const long long base = (long long)b * n * ld + h * kDh;
+  if (a.sel) {
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const int row = (u * 8 + wave) * 8 + (lane >> 3);
+      if (row < n) *reinterpret_cast<u32x4*>(a.xs_out + base + (long long)row * ld + (lane & 7) * 8) = kept[u];
+    }
+  }
 #pragma unroll
   for (int u = 0; u < 3 * kSmallN * 8 / 512; ++u) {
     const int idx = u * 512 + threadIdx.x;
@@ -975,10 +991,20 @@ size_t vd_attn_bf16_ws_bytes(int B, int n, int d, int H) {
 }
 
 // saved: q, k, v, o ([M][d] bf16 each, M = B*n) then lse fp32 [B][H][n]
+// With `sel` (device, n ascending rows of [0, N)), `xs` holds the tokens of all N variates and the kept ones are
+// gathered on the way: inside the fused kernel for short selections, by the gather kernel otherwise; either
+// way `xs_out` [B][n][d] receives them.
 int vd_attn_fwd_bf16(vardrop_ctx* ctx, const void* xs, int B, int n, int d, int H,
                      const void* const W[4], const void* const bias[4],
-                     void* y, void* saved, void* ws, hipStream_t s) {
+                     void* y, void* saved, void* ws, hipStream_t s,
+                     const int32_t* sel, int N, void* xs_out) {
   (void)ws;
+  if (sel && n > kSmallN) {
+    const int grc = vardrop_gather(ctx, xs, B, N, d, VARDROP_BF16, sel, n, xs_out, (void*)s);
+    if (grc) return grc;
+    xs = xs_out;
+    sel = nullptr;
+  }
   const long long M = (long long)B * n;
   bf16_t* q = (bf16_t*)saved;
   bf16_t* k = q + M * d;
@@ -989,6 +1015,9 @@ int vd_attn_fwd_bf16(vardrop_ctx* ctx, const void* xs, int B, int n, int d, int 
   if (n <= kSmallN) {
     FusedFwdArgs f = {};
     f.xs = (const bf16_t*)xs;
+    f.sel = sel;
+    f.xs_out = (bf16_t*)xs_out;
+    f.N = N;
     f.Wq = (const bf16_t*)W[0]; f.Wk = (const bf16_t*)W[1]; f.Wv = (const bf16_t*)W[2];
     f.bq = (const bf16_t*)bias[0]; f.bk = (const bf16_t*)bias[1]; f.bv = (const bf16_t*)bias[2];
     f.q = q; f.k = k; f.v = v; f.o = o; f.lse = lse;

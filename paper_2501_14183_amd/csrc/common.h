@@ -69,7 +69,8 @@ int vd_attn_bwd_f32(vardrop_ctx*, const float* dy, const float* xs, int B, int n
                     float* const dW[4], float* const db[4], void* ws, hipStream_t s);
 int vd_attn_fwd_bf16(vardrop_ctx*, const void* xs, int B, int n, int d, int H,
                      const void* const W[4], const void* const bias[4],
-                     void* y, void* saved, void* ws, hipStream_t s);
+                     void* y, void* saved, void* ws, hipStream_t s,
+                     const int32_t* sel = nullptr, int N = 0, void* xs_out = nullptr);
 int vd_attn_bwd_bf16(vardrop_ctx*, const void* dy, const void* xs, int B, int n, int d, int H,
                      const void* const W[4], const void* saved, void* dxs,
                      float* const dW[4], float* const db[4], void* ws, hipStream_t s);

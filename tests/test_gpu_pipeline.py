@@ -60,6 +60,58 @@ def test_step_matches_oracle(vd, ctx, name):
     print("%s: G=%d N'=%d redrawn=%d errs=%s" % (name, G, n_sel, info["redrawn"], {k: "%.1e" % v for k, v in errs.items()}))
 
 
+@pytest.mark.parametrize("name", wl.ORDER)
+def test_gather_fused_into_the_forward_pass(vd, ctx, name):
+    """vardrop_gather_attn_fwd: the kept tokens and the attention output against the oracle, and bit for bit
+    against vardrop_gather followed by vardrop_attn_fwd (short selections gather inside the forward kernel,
+    long ones and fp32 run the two steps)."""
+    w, x, info, _, want_hash, _ = workload_inputs(name)
+    td = torch_dtype(w.dtype)
+    tok = wl.make_tokens(w, x)
+    W = wl.make_weights(w)
+    b = wl.make_biases(w)
+    tok_t = to_dev(tok, td)
+    W_t = [to_dev(m, td) for m in W]
+    b_t = [to_dev(m, td) for m in b]
+    _, want_sel, _ = o_samp.stratified_sample(want_hash, 0, w.ratio[0], w.ratio[1], SEED, STEP)
+    cases = [want_sel, want_sel[:1], np.arange(min(w.N, 128)), np.arange(min(w.N, 129)), np.array([w.N - 1])]
+    for sel_np in cases:
+        n = len(sel_np)
+        sel = torch.zeros(w.N, dtype=torch.int32, device="cuda")
+        sel[:n] = torch.from_numpy(np.asarray(sel_np, dtype=np.int32)).cuda()
+        xs, y, saved = vd.vardrop_gather_attn_fwd(ctx, tok_t, sel, n, *W_t, w.H, *b_t)
+        xs2 = vd.vardrop_gather(ctx, tok_t, sel, n)
+        y2, saved2 = vd.vardrop_attn_fwd(ctx, xs2, *W_t, w.H, *b_t)
+        torch.cuda.synchronize()
+        assert np.array_equal(xs.float().cpu().numpy(), tok[:, sel_np, :])
+        assert torch.equal(xs, xs2) and torch.equal(y, y2)
+        if n <= 130:
+            from oracle import attention as o_att
+            want, _ = o_att.mha_forward(tok[:, sel_np, :].astype(np.float64), *[m.astype(np.float64) for m in W], w.H,
+                                        *[m.astype(np.float64) for m in b])
+            assert rel_err(y, want) <= TOL[w.dtype]
+        # the backward pass reads the kept tokens the fused call wrote
+        dy = to_dev(wl.make_upstream(w, n), td)
+        g1 = vd.vardrop_attn_bwd(ctx, dy, xs, *W_t, w.H, saved)
+        g2 = vd.vardrop_attn_bwd(ctx, dy, xs2, *W_t, w.H, saved2)
+        torch.cuda.synchronize()
+        assert all(torch.equal(u, v) for u, v in zip(g1, g2))
+
+
+def test_gather_fused_error_codes(vd, ctx):
+    tok = torch.zeros((2, 10, 128), dtype=torch.bfloat16, device="cuda")
+    W = [torch.zeros((128, 128), dtype=torch.bfloat16, device="cuda") for _ in range(4)]
+    sel = torch.arange(10, dtype=torch.int32, device="cuda")
+    with pytest.raises(vd.VarDropError) as e:
+        vd.vardrop_gather_attn_fwd(ctx, tok, sel, 11, *W, 2)              # more kept rows than variates
+    assert e.value.code == -1
+    with pytest.raises(vd.VarDropError) as e:
+        vd.vardrop_gather_attn_fwd(ctx, tok, None, 4, *W, 2)
+    assert e.value.code == -1
+    xs, y, _ = vd.vardrop_gather_attn_fwd(ctx, tok, sel, 0, *W, 2)       # nothing kept: a no-op
+    assert xs.shape == (2, 0, 128)
+
+
 def test_pipelined_steps_in_the_benchmark_configuration(vd, ctx):
     """Traffic-shaped batch, launched the way bench.py launches it: selection on a second stream a step ahead
     through raw stream handles, a ring of selection buffers, outputs written into buffers sized for all N
@@ -102,8 +154,8 @@ def test_pipelined_steps_in_the_benchmark_configuration(vd, ctx):
         n_sel, G = int(pinned[i % ring][0]), int(pinned[i % ring][1])
         sel = bufs[i % ring][3]
         count, shape = w.B * n_sel * w.d, (w.B, n_sel, w.d)
-        xs = vd.vardrop_gather(ctx, tok_t, sel, n_sel, out=xs_buf[:count].view(shape), stream=main_h)
-        y, _ = vd.vardrop_attn_fwd(ctx, xs, *W_t, w.H, saved=saved, out=y_buf[:count].view(shape), stream=main_h)
+        xs, y, _ = vd.vardrop_gather_attn_fwd(ctx, tok_t, sel, n_sel, *W_t, w.H, saved=saved,
+                                              out=(xs_buf[:count].view(shape), y_buf[:count].view(shape)), stream=main_h)
         dy = wl.make_upstream(w, n_sel)
         grads = vd.vardrop_attn_bwd(ctx, to_dev(dy, td), xs, *W_t, w.H, saved, ws=ws,
                                     out=(dxs_buf[:count].view(shape), *dW_buf), stream=main_h)
