@@ -508,6 +508,8 @@ __global__ __launch_bounds__(512) void sdpa_bwd_small_bf16(SdpaArgs a) {
       }
     }
 #undef VD_ISSUE
+#undef VD_ISSUE_W
+#undef VD_ISSUE_X
     wait_vm<0>();                       // (with a single slice the tile copies can still be in flight here)
     // register 4*q4 + e of the accumulator is dO[32*blk + col][32*part + 8*q4 + 4*half + e]
     const int row = blk * 32 + col;
@@ -715,13 +717,12 @@ __global__ __launch_bounds__(512) void attn_fwd_small_bf16(FusedFwdArgs a) {
   const bf16_t* srcA[2];
   const bf16_t* srcB[3];
   u32x4 kept[2];                  // this thread's 16 bytes of two gathered rows, columns of head h
+  int src_row[2];                 // requested here, used after the first weight copies have been issued
 #pragma unroll
   for (int u = 0; u < 2; ++u) {
     const int row = (u * 8 + wave) * 8 + (lane >> 3);
-    int src_row = min(row, n - 1);
-    if (a.sel) src_row = a.sel[src_row];
-    srcA[u] = xs_b + (long long)src_row * ld + (((lane & 7) ^ (row & 7)) * 8);
-    if (a.sel) kept[u] = *reinterpret_cast<const u32x4*>(xs_b + (long long)src_row * ld + h * kDh + (lane & 7) * 8);
+    src_row[u] = min(row, n - 1);
+    if (a.sel) src_row[u] = a.sel[src_row[u]];
   }
 #pragma unroll
   for (int u = 0; u < 3; ++u) {
@@ -747,17 +748,35 @@ __global__ __launch_bounds__(512) void attn_fwd_small_bf16(FusedFwdArgs a) {
   floatx16 acc[3] = {zero16(), zero16(), zero16()};
 
   int fk = 0;        // slice whose copies are issued next
-#define VD_ISSUE(BUF)                                                                               \
+#define VD_ISSUE_W(BUF)                                                                             \
+  {                                                                                                \
+    unsigned char* sp = smem + (BUF) * STAGE + wave * 1024;                                        \
+    _Pragma("unroll") for (int u = 0; u < 3; ++u)                                                  \
+      dma16(srcB[u] + (long long)fk * 64 * ld, sp + A_BYTES + u * BT);                             \
+  }
+#define VD_ISSUE_X(BUF)                                                                             \
   {                                                                                                \
     unsigned char* sp = smem + (BUF) * STAGE + wave * 1024;                                        \
     _Pragma("unroll") for (int u = 0; u < 2; ++u) dma16(srcA[u] + fk * 64, sp + u * 8192);         \
-    _Pragma("unroll") for (int u = 0; u < 3; ++u)                                                  \
-      dma16(srcB[u] + (long long)fk * 64 * ld, sp + A_BYTES + u * BT);                             \
     ++fk;                                                                                          \
   }
+#define VD_ISSUE(BUF) { VD_ISSUE_W(BUF) VD_ISSUE_X(BUF) }
+  // the weight tiles of the first slice go first: the token rows may still be waiting for their indices
+  VD_ISSUE_W(0)
 #pragma unroll
-  for (int s = 0; s < NS - 1; ++s)
+  for (int u = 0; u < 2; ++u) {
+    const int row = (u * 8 + wave) * 8 + (lane >> 3);
+    srcA[u] = xs_b + (long long)src_row[u] * ld + (((lane & 7) ^ (row & 7)) * 8);
+  }
+  VD_ISSUE_X(0)
+#pragma unroll
+  for (int s = 1; s < NS - 1; ++s)
     if (s < total) VD_ISSUE(s)
+  if (a.sel) {
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+      kept[u] = *reinterpret_cast<const u32x4*>(xs_b + (long long)src_row[u] * ld + h * kDh + (lane & 7) * 8);
+  }
   for (int t0 = 0; t0 < total; t0 += NS) {
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
