@@ -16,55 +16,8 @@ namespace {
 
 // ================================================================== attention core (d_k = 64)
 constexpr int kDh = 64;
-constexpr int kTs = 72;              // LDS row stride of a 64-wide tile: 64 + 8 pad
 constexpr float kLog2e = 1.4426950408889634f;
 
-// 64 rows [r0, r0+64) x 64 columns of a [n][d] head slice, staged in registers so that the loads of
-// the next block are in flight while the current one is used.  A task is a pair of rows times an
-// 8-column chunk; the registers can be written to LDS row-major, transposed, or both.
-template <int NT>
-struct Tile64 {
-  static constexpr int kTasks = 256 / NT;
-  u32x4 r[2 * kTasks];
-  __device__ inline void load(const bf16_t* P, long long ld, int r0, int n) {
-#pragma unroll
-    for (int u = 0; u < kTasks; ++u) {
-      const int c = threadIdx.x + u * NT;
-      const int rp = c & 31, ch = c >> 5;
-#pragma unroll
-      for (int e = 0; e < 2; ++e) {
-        const int row = r0 + 2 * rp + e;
-        const bool ok = row < n;
-        const u32x4 v = *reinterpret_cast<const u32x4*>(P + (long long)(ok ? row : 0) * ld + ch * 8);
-        r[2 * u + e] = ok ? v : u32x4{0u, 0u, 0u, 0u};
-      }
-    }
-  }
-  // S[row][col], row stride kTs
-  __device__ inline void store_rows(bf16_t* S) const {
-#pragma unroll
-    for (int u = 0; u < kTasks; ++u) {
-      const int c = threadIdx.x + u * NT;
-      const int rp = c & 31, ch = c >> 5;
-      *reinterpret_cast<u32x4*>(S + (2 * rp) * kTs + ch * 8) = r[2 * u];
-      *reinterpret_cast<u32x4*>(S + (2 * rp + 1) * kTs + ch * 8) = r[2 * u + 1];
-    }
-  }
-  // T[col][row], row stride kTs
-  __device__ inline void store_cols(bf16_t* T) const {
-#pragma unroll
-    for (int u = 0; u < kTasks; ++u) {
-      const int c = threadIdx.x + u * NT;
-      const int rp = c & 31, ch = c >> 5;
-      Frag a, b;
-      a.q = r[2 * u];
-      b.q = r[2 * u + 1];
-#pragma unroll
-      for (int j = 0; j < 8; ++j)
-        *reinterpret_cast<uint32_t*>(T + (ch * 8 + j) * kTs + 2 * rp) = (uint32_t)a.h[j] | ((uint32_t)b.h[j] << 16);
-    }
-  }
-};
 // a lane's row of a head slice as four right-hand (or left-hand) operands: k = 16*s + 8*half + e
 __device__ inline void row_frags(Frag f[4], const bf16_t* P, long long ld, int row, int n, int half) {
   const bool ok = row < n;
@@ -73,21 +26,6 @@ __device__ inline void row_frags(Frag f[4], const bf16_t* P, long long ld, int r
     const u32x4 v = *reinterpret_cast<const u32x4*>(P + (long long)(ok ? row : 0) * ld + s * 16 + half * 8);
     f[s].q = ok ? v : u32x4{0u, 0u, 0u, 0u};
   }
-}
-// left-hand operand from a row-major tile: rows sub*32 + col, k = 16*s + 8*half ..
-__device__ inline Frag tile_frag(const bf16_t* S, int sub, int col, int s, int half) {
-  Frag f;
-  f.q = *reinterpret_cast<const u32x4*>(S + (sub * 32 + col) * kTs + s * 16 + half * 8);
-  return f;
-}
-// left-hand operand from a transposed tile T[c][row] matching accumulator registers 8*s2 .. 8*s2+7 of
-// row sub-tile `sub`: rows sub*32 + 16*s2 + 4*half + {0..3} and the same + 8
-__device__ inline Frag tileT_frag(const bf16_t* T, int ctile, int col, int sub, int s2, int half) {
-  Frag f;
-  const bf16_t* p = T + (ctile * 32 + col) * kTs + sub * 32 + 16 * s2 + 4 * half;
-  f.d[0] = *reinterpret_cast<const u32x2*>(p);
-  f.d[1] = *reinterpret_cast<const u32x2*>(p + 8);
-  return f;
 }
 // accumulator (transposed: rows = head dims, column = this lane's token) -> out[token][32*ct + ...]
 __device__ inline void store_accT(bf16_t* out_row, const floatx16& acc, int ct, int half, float mul) {
@@ -109,242 +47,412 @@ struct SdpaArgs {
   float scale;
 };
 
-// ---- forward: one wavefront per 32 queries, NW wavefronts share the K / V tiles
+// ---- kernels for long selections (n > 128): staging ring.  A stage holds two [64 tokens][64] bf16 tiles of a
+// head (8 KB each, 128-byte rows, the 16-byte chunk position XORed with token % 8) and 2 x 64 floats; it is
+// filled by asynchronous copies, three stages deep, so that a block of tokens costs one workgroup barrier
+// and no staging registers.  Row-major fragments are 16-byte reads, transposed fragments come from the
+// transposing read; LDS reads and their wait counters are written by hand (the compiler would wait for
+// every outstanding copy before any LDS read).
+constexpr int kRingTile = 64 * kDh * 2;
+constexpr int kRingStage = 2 * kRingTile + 512;
+constexpr int kRingStages = 3;
+constexpr int kRingLds = kRingStages * kRingStage;
+
+// copies rows [j0, j0 + 64) of two head slices into a stage; a wavefront-wide copy fills 8 token rows and
+// rows past n repeat row n-1
 template <int NW>
-__global__ __launch_bounds__(NW * 64) void sdpa_fwd_bf16(SdpaArgs a) {
-  __shared__ __attribute__((aligned(16))) bf16_t Ks[64 * kTs];
-  __shared__ __attribute__((aligned(16))) bf16_t Vt[64 * kTs];
+__device__ inline void ring_issue(const bf16_t* p0, const bf16_t* p1, long long ld, int j0, int n,
+                                  unsigned char* stage, int wave, int lane) {
+#pragma unroll
+  for (int u = 0; u < 8 / NW; ++u) {
+    const int rb = u * NW + wave;
+    const int row = rb * 8 + (lane >> 3);
+    const long long off = (long long)min(j0 + row, n - 1) * ld + (((lane & 7) ^ (row & 7)) * 8);
+    dma16(p0 + off, stage + rb * 1024);
+    dma16(p1 + off, stage + kRingTile + rb * 1024);
+  }
+}
+// Per-lane LDS addresses (relative to a stage's first tile) of the two fragment kinds:
+//   row[s]: token row `col` of a 32-row sub-tile, k = 16 s + 8 half .. +7 (add 4096 per sub-tile);
+//   tr[dt]: transposed fragment, head dimensions 32 dt .. +31 as rows, four token rows 4 half + {0..3}
+//           (add 128 * (first token row of the 8-row group) and 1024 for the second group of four).
+struct RingAddr {
+  uint32_t lds0, row[4], tr[2];
+};
+__device__ inline RingAddr ring_addr(const unsigned char* smem, int lane) {
+  RingAddr r;
+  const int col = lane & 31, half = lane >> 5;
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const unsigned char*)smem;
+  r.lds0 = lds0;
+#pragma unroll
+  for (int s = 0; s < 4; ++s) r.row[s] = lds0 + col * 128 + (((2 * s + half) ^ (col & 7)) * 16);
+  const int kr = 4 * half + ((lane & 15) >> 2);
+#pragma unroll
+  for (int dt = 0; dt < 2; ++dt) {
+    const int mn = dt * 32 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+    r.tr[dt] = lds0 + kr * 128 + (((mn >> 3) ^ kr) * 16) + ((mn >> 2) & 1) * 8;
+  }
+  return r;
+}
+// the workgroup's place in an order in which each die works through whole (batch, head) pairs
+__device__ inline void ring_block(int H, int& xb, int& h, int& b) {
+  const int gx = gridDim.x;
+  const int t = xcd_contiguous(blockIdx.x + gx * (blockIdx.y + gridDim.y * blockIdx.z), gx * gridDim.y * gridDim.z);
+  xb = t % gx;
+  h = (t / gx) % H;
+  b = t / (gx * H);
+}
+
+// four row-major fragments (k steps 0..3) of sub-tile KT of tile TILE
+#define VD_ROW4(F, TILE, KT, SO)                                                        \
+  lds_read16_at<(TILE) * kRingTile + (KT) * 4096>(F[0].q, ra.row[0] + (SO));            \
+  lds_read16_at<(TILE) * kRingTile + (KT) * 4096>(F[1].q, ra.row[1] + (SO));            \
+  lds_read16_at<(TILE) * kRingTile + (KT) * 4096>(F[2].q, ra.row[2] + (SO));            \
+  lds_read16_at<(TILE) * kRingTile + (KT) * 4096>(F[3].q, ra.row[3] + (SO));
+// four transposed fragments of the 32 token rows KT of tile TILE: F[2 * s2 + dt] = rows 16 s2 .., dimensions 32 dt ..
+#define VD_TR4(F, TILE, KT, SO)                                                                              \
+  lds_read8_tr<(TILE) * kRingTile + ((KT) * 32) * 128>(F[0].d[0], ra.tr[0] + (SO));                          \
+  lds_read8_tr<(TILE) * kRingTile + ((KT) * 32 + 8) * 128>(F[0].d[1], ra.tr[0] + (SO));                      \
+  lds_read8_tr<(TILE) * kRingTile + ((KT) * 32) * 128>(F[1].d[0], ra.tr[1] + (SO));                          \
+  lds_read8_tr<(TILE) * kRingTile + ((KT) * 32 + 8) * 128>(F[1].d[1], ra.tr[1] + (SO));                      \
+  lds_read8_tr<(TILE) * kRingTile + ((KT) * 32 + 16) * 128>(F[2].d[0], ra.tr[0] + (SO));                     \
+  lds_read8_tr<(TILE) * kRingTile + ((KT) * 32 + 24) * 128>(F[2].d[1], ra.tr[0] + (SO));                     \
+  lds_read8_tr<(TILE) * kRingTile + ((KT) * 32 + 16) * 128>(F[3].d[0], ra.tr[1] + (SO));                     \
+  lds_read8_tr<(TILE) * kRingTile + ((KT) * 32 + 24) * 128>(F[3].d[1], ra.tr[1] + (SO));
+
+// ---- forward: a wavefront owns 32 QG queries (lane = query of each group), NW wavefronts share the K / V stages.
+// S^T = K q^T, online softmax on per-lane scalars, O^T = V^T P^T with the probability registers as the
+// right-hand operand; every K or V fragment read from LDS serves all QG query groups.
+template <int NW, int QG>
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) void sdpa_fwd_bf16(SdpaArgs a) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  constexpr int LPS = 16 / NW;                 // copies per wavefront and stage
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int col = lane & 31, half = lane >> 5;
-  const int b = blockIdx.z, h = blockIdx.y;
+  int qb, h, b;
+  ring_block(a.H, qb, h, b);
   const int n = a.n;
   const long long ld = a.d;
   const long long base = (long long)b * n * ld + h * kDh;
-  const int qi = blockIdx.x * (NW * 32) + wave * 32 + col;
-  Frag qf[4];
-  row_frags(qf, a.q + base, ld, qi, n, half);
-  floatx16 acc[2] = {zero16(), zero16()};
-  float m = -INFINITY, l = 0.f;
+  const bf16_t* kp = a.k + base;
+  const bf16_t* vp = a.v + base;
+  const int q0 = (qb * NW + wave) * (32 * QG);
+  const int nb = (n + 63) >> 6;
+  ring_issue<NW>(kp, vp, ld, 0, n, smem, wave, lane);
+  if (nb > 1) ring_issue<NW>(kp, vp, ld, 64, n, smem + kRingStage, wave, lane);
+  Frag qf[QG][4];
+#pragma unroll
+  for (int g = 0; g < QG; ++g) row_frags(qf[g], a.q + base, ld, q0 + 32 * g + col, n, half);
+  const RingAddr ra = ring_addr(smem, lane);
+  floatx16 acc[QG][2];
+  float m[QG], l[QG];
+#pragma unroll
+  for (int g = 0; g < QG; ++g) {
+    acc[g][0] = zero16();
+    acc[g][1] = zero16();
+    m[g] = -INFINITY;
+    l[g] = 0.f;
+  }
   const float c = a.scale * kLog2e;
-  Tile64<NW * 64> tk, tv;
-  tk.load(a.k + base, ld, 0, n);
-  tv.load(a.v + base, ld, 0, n);
-  for (int j0 = 0; j0 < n; j0 += 64) {
-    __syncthreads();
-    tk.store_rows(Ks);
-    tv.store_cols(Vt);
-    __syncthreads();
-    if (j0 + 64 < n) {
-      tk.load(a.k + base, ld, j0 + 64, n);
-      tv.load(a.v + base, ld, j0 + 64, n);
-    }
-    floatx16 st[2];
+  int buf = 0;
+  for (int j = 0; j < nb; ++j) {
+    // block j has landed once only the copies of block j+1 are in flight; behind the barrier everyone's have,
+    // and everyone is done with block j-1, whose stage block j+2 takes
+    if (j + 1 < nb) wait_vm<LPS>(); else wait_vm<0>();
+    __builtin_amdgcn_s_barrier();
+    if (j + 2 < nb) ring_issue<NW>(kp, vp, ld, (j + 2) * 64, n, smem + ((buf + 2) % kRingStages) * kRingStage, wave, lane);
+    const uint32_t so = buf * kRingStage;
+    buf = buf == kRingStages - 1 ? 0 : buf + 1;
+    floatx16 st[QG][2];
+    Frag fa[4], fb[4];
+    VD_ROW4(fa, 0, 0, so)
+    VD_ROW4(fb, 0, 1, so)
 #pragma unroll
-    for (int kt = 0; kt < 2; ++kt) {
-      st[kt] = zero16();
-#pragma unroll
-      for (int s = 0; s < 4; ++s) st[kt] = mfma(tile_frag(Ks, kt, col, s, half), qf[s], st[kt]);
+    for (int g = 0; g < QG; ++g) {
+      st[g][0] = zero16();
+      st[g][1] = zero16();
     }
+#define VD_S_STEP(F, KT, S, PENDING)                                                    \
+  wait_lds<PENDING>(F[S]);                                                              \
+  _Pragma("unroll") for (int g = 0; g < QG; ++g) st[g][KT] = mfma(F[S], qf[g][S], st[g][KT]);
+    VD_S_STEP(fa, 0, 0, 7) VD_S_STEP(fa, 0, 1, 6) VD_S_STEP(fa, 0, 2, 5) VD_S_STEP(fa, 0, 3, 4)
+    VD_S_STEP(fb, 1, 0, 3) VD_S_STEP(fb, 1, 1, 2) VD_S_STEP(fb, 1, 2, 1) VD_S_STEP(fb, 1, 3, 0)
+#undef VD_S_STEP
+    __builtin_amdgcn_sched_barrier(0);
+    VD_TR4(fa, 1, 0, so)                        // V^T fragments of the first 32 keys travel during the softmax
     // online softmax on the raw scores: max, then exp2(c s - c max) as one fused multiply-add per score.
     // Keys past the end exist only in the last block; the running output is rescaled only when some
     // lane's maximum moved (after the first blocks it rarely does).
-    if (j0 + 64 > n) {
+    const bool tail = j * 64 + 64 > n;
+#pragma unroll
+    for (int g = 0; g < QG; ++g) {
+      if (tail) {
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int key = j * 64 + kt * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+            st[g][kt][r] = key < n ? st[g][kt][r] : -INFINITY;
+          }
+      }
+      float mt = -INFINITY;
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mt = fmaxf(mt, st[g][kt][r]);
+      mt = fmaxf(mt, __shfl_xor(mt, 32, 64));
+      const float mn = fmaxf(m[g], mt * c);           // c > 0: scaling commutes with the maximum
+      float rs = 0.f;
 #pragma unroll
       for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const int j = j0 + kt * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-          st[kt][r] = j < n ? st[kt][r] : -INFINITY;
+          st[g][kt][r] = fast_exp2(fmaf(st[g][kt][r], c, -mn));
+          rs += st[g][kt][r];
         }
-    }
-    float mt = -INFINITY;
+      if (__any(mn != m[g])) {
+        const float alpha = fast_exp2(m[g] - mn);
+        l[g] *= alpha;
 #pragma unroll
-    for (int kt = 0; kt < 2; ++kt)
+        for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) mt = fmaxf(mt, st[kt][r]);
-    mt = fmaxf(mt, __shfl_xor(mt, 32, 64));
-    const float mn = fmaxf(m, mt * c);             // c > 0: scaling commutes with the maximum
-    float rs = 0.f;
-#pragma unroll
-    for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        st[kt][r] = fast_exp2(fmaf(st[kt][r], c, -mn));
-        rs += st[kt][r];
+          for (int r = 0; r < 16; ++r) acc[g][dt][r] *= alpha;
       }
-    if (__any(mn != m)) {
-      const float alpha = fast_exp2(m - mn);
-      l *= alpha;
-#pragma unroll
-      for (int dt = 0; dt < 2; ++dt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[dt][r] *= alpha;
+      l[g] += rs;
+      m[g] = mn;
     }
-    l += rs;
-    m = mn;
-#pragma unroll
-    for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-      for (int s2 = 0; s2 < 2; ++s2) {
-        const Frag pf = regs_to_frag(st[kt], s2);
-#pragma unroll
-        for (int dt = 0; dt < 2; ++dt) acc[dt] = mfma(tileT_frag(Vt, dt, col, kt, s2, half), pf, acc[dt]);
-      }
+    __builtin_amdgcn_sched_barrier(0);
+    wait_lds_count<7>();                        // (the counter holds 15)
+    VD_TR4(fb, 1, 1, so)
+#define VD_PV_STEP(F, KT, I, PENDING)                                                   \
+  wait_lds<PENDING>(F[I]);                                                              \
+  _Pragma("unroll") for (int g = 0; g < QG; ++g)                                        \
+    acc[g][(I) & 1] = mfma(F[I], regs_to_frag(st[g][KT], (I) >> 1), acc[g][(I) & 1]);
+    VD_PV_STEP(fa, 0, 0, 8) VD_PV_STEP(fa, 0, 1, 8) VD_PV_STEP(fa, 0, 2, 8) VD_PV_STEP(fa, 0, 3, 8)
+    VD_PV_STEP(fb, 1, 0, 6) VD_PV_STEP(fb, 1, 1, 4) VD_PV_STEP(fb, 1, 2, 2) VD_PV_STEP(fb, 1, 3, 0)
+#undef VD_PV_STEP
+    __builtin_amdgcn_sched_barrier(0);
   }
-  l += __shfl_xor(l, 32, 64);
-  if (qi < n) {
-    const float inv = 1.f / l;
-    bf16_t* orow = a.out + base + (long long)qi * ld;
-    store_accT(orow, acc[0], 0, half, inv);
-    store_accT(orow, acc[1], 1, half, inv);
-    if (half == 0) a.lse[((long long)b * a.H + h) * n + qi] = (m + log2f(l)) * 0.6931471805599453f;
+#pragma unroll
+  for (int g = 0; g < QG; ++g) {
+    const int qi = q0 + 32 * g + col;
+    const float lt = l[g] + __shfl_xor(l[g], 32, 64);
+    if (qi < n) {
+      const float inv = 1.f / lt;
+      bf16_t* orow = a.out + base + (long long)qi * ld;
+      store_accT(orow, acc[g][0], 0, half, inv);
+      store_accT(orow, acc[g][1], 1, half, inv);
+      if (half == 0) a.lse[((long long)b * a.H + h) * n + qi] = (m[g] + log2f(lt)) * 0.6931471805599453f;
+    }
   }
 }
 
-// ---- backward, part 1: dQ and D = rowsum(dO * O); one wavefront per 32 queries
-template <int NW>
-__global__ __launch_bounds__(NW * 64) void sdpa_bwd_dq_bf16(SdpaArgs a) {
-  __shared__ __attribute__((aligned(16))) bf16_t Ks[64 * kTs];
-  __shared__ __attribute__((aligned(16))) bf16_t Vs[64 * kTs];
-  __shared__ __attribute__((aligned(16))) bf16_t Kt[64 * kTs];
+// ---- backward, part 1: dQ and D = rowsum(dO * O).  A wavefront owns 32 QG queries (lane = query), loop over
+// key blocks: S^T = K q^T and dP^T = V dO^T from row fragments of the K and V tiles, dS^T in registers as the
+// right-hand operand of dQ^T = K^T dS^T, whose left operand is the K tile again, read transposed.
+template <int NW, int QG>
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) void sdpa_bwd_dq_bf16(SdpaArgs a) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  constexpr int LPS = 16 / NW;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int col = lane & 31, half = lane >> 5;
-  const int b = blockIdx.z, h = blockIdx.y;
+  int qb, h, b;
+  ring_block(a.H, qb, h, b);
   const int n = a.n;
   const long long ld = a.d;
   const long long base = (long long)b * n * ld + h * kDh;
-  const int qi = blockIdx.x * (NW * 32) + wave * 32 + col;
-  Frag qf[4], dof[4];
-  row_frags(qf, a.q + base, ld, qi, n, half);
-  row_frags(dof, a.dout + base, ld, qi, n, half);
-  float D = 0.f;
-  {
+  const long long srow = ((long long)b * a.H + h) * n;
+  const bf16_t* kp = a.k + base;
+  const bf16_t* vp = a.v + base;
+  const int q0 = (qb * NW + wave) * (32 * QG);
+  const int nb = (n + 63) >> 6;
+  ring_issue<NW>(kp, vp, ld, 0, n, smem, wave, lane);
+  if (nb > 1) ring_issue<NW>(kp, vp, ld, 64, n, smem + kRingStage, wave, lane);
+  Frag qf[QG][4], dof[QG][4];
+  float D[QG], lse2[QG];
+#pragma unroll
+  for (int g = 0; g < QG; ++g) {
+    const int qi = q0 + 32 * g + col;
+    row_frags(qf[g], a.q + base, ld, qi, n, half);
+    row_frags(dof[g], a.dout + base, ld, qi, n, half);
     Frag of[4];
     row_frags(of, a.o + base, ld, qi, n, half);
+    float dsum = 0.f;
 #pragma unroll
     for (int s = 0; s < 4; ++s)
 #pragma unroll
-      for (int e = 0; e < 8; ++e) D = fmaf(bf2f(dof[s].h[e]), bf2f(of[s].h[e]), D);
-    D += __shfl_xor(D, 32, 64);
+      for (int e = 0; e < 8; ++e) dsum = fmaf(bf2f(dof[g][s].h[e]), bf2f(of[s].h[e]), dsum);
+    D[g] = dsum + __shfl_xor(dsum, 32, 64);
+    lse2[g] = qi < n ? a.lse[srow + qi] * kLog2e : INFINITY;
   }
-  const long long srow = ((long long)b * a.H + h) * n;
-  const float lse2 = qi < n ? a.lse[srow + qi] * kLog2e : INFINITY;
+  const RingAddr ra = ring_addr(smem, lane);
+  floatx16 acc[QG][2];
+#pragma unroll
+  for (int g = 0; g < QG; ++g) {
+    acc[g][0] = zero16();
+    acc[g][1] = zero16();
+  }
   const float c = a.scale * kLog2e;
-  floatx16 acc[2] = {zero16(), zero16()};
-  Tile64<NW * 64> tk, tv;
-  tk.load(a.k + base, ld, 0, n);
-  tv.load(a.v + base, ld, 0, n);
-  for (int j0 = 0; j0 < n; j0 += 64) {
-    __syncthreads();
-    tk.store_rows(Ks);
-    tk.store_cols(Kt);
-    tv.store_rows(Vs);
-    __syncthreads();
-    if (j0 + 64 < n) {
-      tk.load(a.k + base, ld, j0 + 64, n);
-      tv.load(a.v + base, ld, j0 + 64, n);
-    }
-#pragma unroll
-    for (int kt = 0; kt < 2; ++kt) {
-      floatx16 st = zero16(), dp = zero16();
-#pragma unroll
-      for (int s = 0; s < 4; ++s) {
-        st = mfma(tile_frag(Ks, kt, col, s, half), qf[s], st);
-        dp = mfma(tile_frag(Vs, kt, col, s, half), dof[s], dp);
-      }
-      // (a key past the end has a zero row in both tiles: its dS is finite and meets zeros in the product below)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) st[r] = fast_exp2(fmaf(st[r], c, -lse2)) * (dp[r] - D);
-#pragma unroll
-      for (int s2 = 0; s2 < 2; ++s2) {
-        const Frag dsf = regs_to_frag(st, s2);
-#pragma unroll
-        for (int dt = 0; dt < 2; ++dt) acc[dt] = mfma(tileT_frag(Kt, dt, col, kt, s2, half), dsf, acc[dt]);
-      }
-    }
+  int buf = 0;
+  for (int j = 0; j < nb; ++j) {
+    if (j + 1 < nb) wait_vm<LPS>(); else wait_vm<0>();
+    __builtin_amdgcn_s_barrier();
+    if (j + 2 < nb) ring_issue<NW>(kp, vp, ld, (j + 2) * 64, n, smem + ((buf + 2) % kRingStages) * kRingStage, wave, lane);
+    const uint32_t so = buf * kRingStage;
+    buf = buf == kRingStages - 1 ? 0 : buf + 1;
+    const bool tail = j * 64 + 64 > n;
+#define VD_DQ_HALF(KT)                                                                                   \
+  {                                                                                                      \
+    floatx16 st[QG], dp[QG];                                                                             \
+    Frag fk[4], fv[4], ft[4];                                                                            \
+    VD_ROW4(fk, 0, KT, so)                                                                               \
+    VD_ROW4(fv, 1, KT, so)                                                                               \
+    _Pragma("unroll") for (int g = 0; g < QG; ++g) {                                                     \
+      st[g] = zero16();                                                                                  \
+      dp[g] = zero16();                                                                                  \
+    }                                                                                                    \
+    VD_DQ_STEP(st, fk, qf, 0, 7) VD_DQ_STEP(st, fk, qf, 1, 6) VD_DQ_STEP(st, fk, qf, 2, 5) VD_DQ_STEP(st, fk, qf, 3, 4) \
+    VD_DQ_STEP(dp, fv, dof, 0, 3) VD_DQ_STEP(dp, fv, dof, 1, 2) VD_DQ_STEP(dp, fv, dof, 2, 1) VD_DQ_STEP(dp, fv, dof, 3, 0) \
+    __builtin_amdgcn_sched_barrier(0);                                                                   \
+    VD_TR4(ft, 0, KT, so)                                                                                \
+    _Pragma("unroll") for (int g = 0; g < QG; ++g)                                                       \
+      _Pragma("unroll") for (int r = 0; r < 16; ++r) {                                                   \
+        /* a key past the end repeats the last one: its dS is dropped */                                 \
+        const int key = j * 64 + (KT) * 32 + 8 * (r >> 2) + 4 * half + (r & 3);                          \
+        const float ds = fast_exp2(fmaf(st[g][r], c, -lse2[g])) * (dp[g][r] - D[g]);                     \
+        st[g][r] = (!tail || key < n) ? ds : 0.f;                                                        \
+      }                                                                                                  \
+    __builtin_amdgcn_sched_barrier(0);                                                                   \
+    VD_DQ_ACC(ft, 0, 6) VD_DQ_ACC(ft, 1, 4) VD_DQ_ACC(ft, 2, 2) VD_DQ_ACC(ft, 3, 0)                       \
+    __builtin_amdgcn_sched_barrier(0);                                                                   \
   }
-  if (qi < n) {
-    bf16_t* row = a.dq + base + (long long)qi * ld;
-    store_accT(row, acc[0], 0, half, a.scale);
-    store_accT(row, acc[1], 1, half, a.scale);
-    if (half == 0) a.Dsum[srow + qi] = D;
+#define VD_DQ_STEP(ACC, F, RHS, S, PENDING)                                             \
+  wait_lds<PENDING>(F[S]);                                                              \
+  _Pragma("unroll") for (int g = 0; g < QG; ++g) ACC[g] = mfma(F[S], RHS[g][S], ACC[g]);
+#define VD_DQ_ACC(F, I, PENDING)                                                        \
+  wait_lds<PENDING>(F[I]);                                                              \
+  _Pragma("unroll") for (int g = 0; g < QG; ++g)                                        \
+    acc[g][(I) & 1] = mfma(F[I], regs_to_frag(st[g], (I) >> 1), acc[g][(I) & 1]);
+    VD_DQ_HALF(0)
+    VD_DQ_HALF(1)
+#undef VD_DQ_HALF
+#undef VD_DQ_STEP
+#undef VD_DQ_ACC
+  }
+#pragma unroll
+  for (int g = 0; g < QG; ++g) {
+    const int qi = q0 + 32 * g + col;
+    if (qi < n) {
+      bf16_t* row = a.dq + base + (long long)qi * ld;
+      store_accT(row, acc[g][0], 0, half, a.scale);
+      store_accT(row, acc[g][1], 1, half, a.scale);
+      if (half == 0) a.Dsum[srow + qi] = D[g];
+    }
   }
 }
 
-// ---- backward, part 2: dK and dV; one wavefront per 32 keys, loop over query blocks
+// ---- backward, part 2: dK and dV.  A wavefront owns 32 keys (lane = key), loop over query blocks: a stage holds
+// the Q and dO tiles of 64 queries, their log-sum-exp and their D.  S = Q k^T and dP = dO v^T from row
+// fragments; P and dS in registers are the right-hand operands of dV^T = dO^T P and dK^T = Q^T dS, whose left
+// operands are the same tiles read transposed.
 template <int NW>
-__global__ __launch_bounds__(NW * 64) void sdpa_bwd_dkv_bf16(SdpaArgs a) {
-  __shared__ __attribute__((aligned(16))) bf16_t Qs[64 * kTs];
-  __shared__ __attribute__((aligned(16))) bf16_t Os[64 * kTs];
-  __shared__ __attribute__((aligned(16))) bf16_t Qt[64 * kTs];
-  __shared__ __attribute__((aligned(16))) bf16_t Ot[64 * kTs];
-  __shared__ float Ls[64], Ds[64];
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) void sdpa_bwd_dkv_bf16(SdpaArgs a) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  constexpr int LPS = 16 / NW + 1;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int col = lane & 31, half = lane >> 5;
-  const int b = blockIdx.z, h = blockIdx.y;
+  int kb, h, b;
+  ring_block(a.H, kb, h, b);
   const int n = a.n;
   const long long ld = a.d;
   const long long base = (long long)b * n * ld + h * kDh;
   const long long srow = ((long long)b * a.H + h) * n;
-  const int kj = blockIdx.x * (NW * 32) + wave * 32 + col;
+  const bf16_t* qp = a.q + base;
+  const bf16_t* op = a.dout + base;
+  const int kj = (kb * NW + wave) * 32 + col;
+  const int nb = (n + 63) >> 6;
+  // even wavefronts copy the block's log-sum-exp values, odd ones its D (NW is even); queries past n repeat the last
+  const float* stat = (wave & 1) ? a.Dsum + srow : a.lse + srow;
+  const int stat_off = 2 * kRingTile + (wave & 1) * 256;
+#define VD_ISSUE_Q(J, BUF)                                                                            \
+  {                                                                                                   \
+    unsigned char* sp = smem + (BUF) * kRingStage;                                                    \
+    ring_issue<NW>(qp, op, ld, (J) * 64, n, sp, wave, lane);                                          \
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(stat + min((J) * 64 + lane, n - 1)), \
+                                     (__attribute__((address_space(3))) void*)(sp + stat_off), 4, 0, 0); \
+  }
+  VD_ISSUE_Q(0, 0)
+  if (nb > 1) VD_ISSUE_Q(1, 1)
   Frag kf[4], vf[4];
   row_frags(kf, a.k + base, ld, kj, n, half);
   row_frags(vf, a.v + base, ld, kj, n, half);
-  const float c = a.scale * kLog2e;
+  const RingAddr ra = ring_addr(smem, lane);
+  const uint32_t stat_addr = ra.lds0 + 2 * kRingTile + 16 * half;   // + 32 per 8 queries
   floatx16 accK[2] = {zero16(), zero16()}, accV[2] = {zero16(), zero16()};
-  Tile64<NW * 64> tq, to;
-  float lreg = 0.f, dreg = 0.f;
-  auto fetch = [&](int i0) {
-    tq.load(a.q + base, ld, i0, n);
-    to.load(a.dout + base, ld, i0, n);
-    if (threadIdx.x < 64) {
-      const int i = i0 + (int)threadIdx.x;
-      const bool ok = i < n;
-      const float l = a.lse[srow + (ok ? i : 0)], dd = a.Dsum[srow + (ok ? i : 0)];
-      lreg = ok ? l * kLog2e : INFINITY;
-      dreg = ok ? dd : 0.f;
-    }
-  };
-  fetch(0);
-  for (int i0 = 0; i0 < n; i0 += 64) {
-    __syncthreads();
-    tq.store_rows(Qs);
-    tq.store_cols(Qt);
-    to.store_rows(Os);
-    to.store_cols(Ot);
-    if (threadIdx.x < 64) {
-      Ls[threadIdx.x] = lreg;
-      Ds[threadIdx.x] = dreg;
-    }
-    __syncthreads();
-    if (i0 + 64 < n) fetch(i0 + 64);
-#pragma unroll
-    for (int qt = 0; qt < 2; ++qt) {
-      floatx16 st = zero16(), dp = zero16();
-#pragma unroll
-      for (int s = 0; s < 4; ++s) {
-        st = mfma(tile_frag(Qs, qt, col, s, half), kf[s], st);     // S[query][key]
-        dp = mfma(tile_frag(Os, qt, col, s, half), vf[s], dp);     // dP[query][key]
-      }
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int iq = qt * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-        const float p = fast_exp2(st[r] * c - Ls[iq]);
-        st[r] = p;
-        dp[r] = p * (dp[r] - Ds[iq]);
-      }
-#pragma unroll
-      for (int s2 = 0; s2 < 2; ++s2) {
-        const Frag pf = regs_to_frag(st, s2);
-        const Frag dsf = regs_to_frag(dp, s2);
-#pragma unroll
-        for (int dt = 0; dt < 2; ++dt) {
-          accV[dt] = mfma(tileT_frag(Ot, dt, col, qt, s2, half), pf, accV[dt]);
-          accK[dt] = mfma(tileT_frag(Qt, dt, col, qt, s2, half), dsf, accK[dt]);
-        }
-      }
-    }
+  const float c = a.scale * kLog2e;
+  int buf = 0;
+  for (int i = 0; i < nb; ++i) {
+    if (i + 1 < nb) wait_vm<LPS>(); else wait_vm<0>();
+    __builtin_amdgcn_s_barrier();
+    if (i + 2 < nb) VD_ISSUE_Q(i + 2, (buf + 2) % kRingStages)
+    const uint32_t so = buf * kRingStage;
+    buf = buf == kRingStages - 1 ? 0 : buf + 1;
+    const bool tail = i * 64 + 64 > n;
+#define VD_DKV_HALF(QT)                                                                                  \
+  {                                                                                                      \
+    floatx16 st = zero16(), dp = zero16();                                                               \
+    Frag fq[4], fo[4], ls[4], ds_[4];                                                                    \
+    VD_ROW4(fq, 0, QT, so)                                                                               \
+    VD_ROW4(fo, 1, QT, so)                                                                               \
+    wait_lds<7>(fq[0]); st = mfma(fq[0], kf[0], st);                                                     \
+    wait_lds<6>(fq[1]); st = mfma(fq[1], kf[1], st);                                                     \
+    wait_lds<5>(fq[2]); st = mfma(fq[2], kf[2], st);                                                     \
+    wait_lds<4>(fq[3]); st = mfma(fq[3], kf[3], st);                                                     \
+    __builtin_amdgcn_sched_barrier(0);                                                                   \
+    /* log-sum-exp and D of queries 32 QT + 8 q4 + 4 half + 0..3, the rows of registers 4 q4 .. 4 q4 + 3 */ \
+    lds_read16_at<(QT) * 128>(ls[0].q, stat_addr + so);                                                  \
+    lds_read16_at<(QT) * 128 + 32>(ls[1].q, stat_addr + so);                                             \
+    lds_read16_at<(QT) * 128 + 64>(ls[2].q, stat_addr + so);                                             \
+    lds_read16_at<(QT) * 128 + 96>(ls[3].q, stat_addr + so);                                             \
+    lds_read16_at<(QT) * 128 + 256>(ds_[0].q, stat_addr + so);                                           \
+    lds_read16_at<(QT) * 128 + 256 + 32>(ds_[1].q, stat_addr + so);                                      \
+    lds_read16_at<(QT) * 128 + 256 + 64>(ds_[2].q, stat_addr + so);                                      \
+    lds_read16_at<(QT) * 128 + 256 + 96>(ds_[3].q, stat_addr + so);                                      \
+    wait_lds<11>(fo[0]); dp = mfma(fo[0], vf[0], dp);                                                    \
+    wait_lds<10>(fo[1]); dp = mfma(fo[1], vf[1], dp);                                                    \
+    wait_lds<9>(fo[2]); dp = mfma(fo[2], vf[2], dp);                                                     \
+    wait_lds<8>(fo[3]); dp = mfma(fo[3], vf[3], dp);                                                     \
+    __builtin_amdgcn_sched_barrier(0);                                                                   \
+    wait_lds_count<7>();                        /* (the counter holds 15) */                             \
+    VD_TR4(fo, 1, QT, so)                       /* dO^T */                                               \
+    wait_lds<8>(ls[0], ls[1], ls[2], ls[3]);                                                             \
+    wait_lds<8>(ds_[0], ds_[1], ds_[2], ds_[3]);                                                         \
+    _Pragma("unroll") for (int r = 0; r < 16; ++r) {                                                     \
+      const int iq = i * 64 + (QT) * 32 + 8 * (r >> 2) + 4 * half + (r & 3);                             \
+      const float lr = __uint_as_float(ls[r >> 2].w[r & 3]) * kLog2e;                                    \
+      float p = fast_exp2(fmaf(st[r], c, -lr));                                                          \
+      p = (!tail || iq < n) ? p : 0.f;          /* a query past the end repeats the last one */          \
+      st[r] = p;                                                                                         \
+      dp[r] = p * (dp[r] - __uint_as_float(ds_[r >> 2].w[r & 3]));                                       \
+    }                                                                                                    \
+    __builtin_amdgcn_sched_barrier(0);                                                                   \
+    wait_lds_count<7>();                                                                                 \
+    VD_TR4(fq, 0, QT, so)                       /* Q^T */                                                \
+    wait_lds<8>(fo[0]); accV[0] = mfma(fo[0], regs_to_frag(st, 0), accV[0]);                             \
+    wait_lds<8>(fo[1]); accV[1] = mfma(fo[1], regs_to_frag(st, 0), accV[1]);                             \
+    wait_lds<8>(fo[2]); accV[0] = mfma(fo[2], regs_to_frag(st, 1), accV[0]);                             \
+    wait_lds<8>(fo[3]); accV[1] = mfma(fo[3], regs_to_frag(st, 1), accV[1]);                             \
+    wait_lds<6>(fq[0]); accK[0] = mfma(fq[0], regs_to_frag(dp, 0), accK[0]);                             \
+    wait_lds<4>(fq[1]); accK[1] = mfma(fq[1], regs_to_frag(dp, 0), accK[1]);                             \
+    wait_lds<2>(fq[2]); accK[0] = mfma(fq[2], regs_to_frag(dp, 1), accK[0]);                             \
+    wait_lds<0>(fq[3]); accK[1] = mfma(fq[3], regs_to_frag(dp, 1), accK[1]);                             \
+    __builtin_amdgcn_sched_barrier(0);                                                                   \
   }
+    VD_DKV_HALF(0)
+    VD_DKV_HALF(1)
+#undef VD_DKV_HALF
+  }
+#undef VD_ISSUE_Q
   if (kj < n) {
     bf16_t* rk = a.dk + base + (long long)kj * ld;
     bf16_t* rv = a.dv + base + (long long)kj * ld;
@@ -354,6 +462,8 @@ __global__ __launch_bounds__(NW * 64) void sdpa_bwd_dkv_bf16(SdpaArgs a) {
     store_accT(rv, accV[1], 1, half, 1.f);
   }
 }
+#undef VD_ROW4
+#undef VD_TR4
 
 // ---- backward for short selections (n <= 128, the regime variate dropping produces): one workgroup
 // per (batch, head) holds Q, K, V and O of the head in LDS (asynchronous copies), forms the head's dO tile
@@ -964,16 +1074,29 @@ __global__ __launch_bounds__(256) void colsum_bf16_kernel(ColSumBf16 a) {
   dst[c] = s;
 }
 
-template <typename F>
-int launch_core(vardrop_ctx* ctx, int kid, F kernel2, F kernel4, const SdpaArgs& a, int B, hipStream_t s) {
+// Launches of the kernels for long selections.  A workgroup takes `rows` queries (or keys); the widest
+// shape that still gives the chip two workgroups per compute unit is chosen, else the narrowest.
+template <typename K>
+int launch_ring(vardrop_ctx* ctx, int kid, K kernel, int rows, const SdpaArgs& a, int B, hipStream_t s) {
   VdTimer timer(ctx, kid, s);
-  if (a.n <= 256) {
-    hipLaunchKernelGGL(kernel2, dim3(vd_ceil_div(a.n, 64), a.H, B), dim3(128), 0, s, a);
-  } else {
-    hipLaunchKernelGGL(kernel4, dim3(vd_ceil_div(a.n, 128), a.H, B), dim3(256), 0, s, a);
-  }
+  hipLaunchKernelGGL(kernel, dim3(vd_ceil_div(a.n, rows), a.H, B), dim3(rows >= 128 ? 256 : 128), kRingLds, s, a);
   VD_LAUNCH_CHECK(ctx);
   return VARDROP_OK;
+}
+bool ring_fills(const SdpaArgs& a, int B, int rows) { return (long long)vd_ceil_div(a.n, rows) * a.H * B >= 512; }
+int launch_sdpa_fwd(vardrop_ctx* ctx, const SdpaArgs& a, int B, hipStream_t s) {
+  if (ring_fills(a, B, 256)) return launch_ring(ctx, VARDROP_K_SDPA_FWD, sdpa_fwd_bf16<4, 2>, 256, a, B, s);
+  if (ring_fills(a, B, 128)) return launch_ring(ctx, VARDROP_K_SDPA_FWD, sdpa_fwd_bf16<4, 1>, 128, a, B, s);
+  return launch_ring(ctx, VARDROP_K_SDPA_FWD, sdpa_fwd_bf16<2, 1>, 64, a, B, s);
+}
+int launch_sdpa_bwd_dq(vardrop_ctx* ctx, const SdpaArgs& a, int B, hipStream_t s) {
+  if (ring_fills(a, B, 256)) return launch_ring(ctx, VARDROP_K_SDPA_BWD_DQ, sdpa_bwd_dq_bf16<4, 2>, 256, a, B, s);
+  if (ring_fills(a, B, 128)) return launch_ring(ctx, VARDROP_K_SDPA_BWD_DQ, sdpa_bwd_dq_bf16<4, 1>, 128, a, B, s);
+  return launch_ring(ctx, VARDROP_K_SDPA_BWD_DQ, sdpa_bwd_dq_bf16<2, 1>, 64, a, B, s);
+}
+int launch_sdpa_bwd_dkv(vardrop_ctx* ctx, const SdpaArgs& a, int B, hipStream_t s) {
+  if (ring_fills(a, B, 128)) return launch_ring(ctx, VARDROP_K_SDPA_BWD_DKV, sdpa_bwd_dkv_bf16<4>, 128, a, B, s);
+  return launch_ring(ctx, VARDROP_K_SDPA_BWD_DKV, sdpa_bwd_dkv_bf16<2>, 64, a, B, s);
 }
 
 }  // namespace
@@ -1062,7 +1185,7 @@ int vd_attn_fwd_bf16(vardrop_ctx* ctx, const void* xs, int B, int n, int d, int 
     SdpaArgs a = {};
     a.q = q; a.k = k; a.v = v; a.out = o; a.lse = lse;
     a.n = n; a.d = d; a.H = H; a.scale = 1.0f / sqrtf((float)kDh);
-    rc = launch_core(ctx, VARDROP_K_SDPA_FWD, sdpa_fwd_bf16<2>, sdpa_fwd_bf16<4>, a, B, s);
+    rc = launch_sdpa_fwd(ctx, a, B, s);
     if (rc) return rc;
   }
   GemmBf16 go = {};
@@ -1112,8 +1235,8 @@ int vd_attn_bwd_bf16(vardrop_ctx* ctx, const void* dy, const void* xs, int B, in
     }
     VD_LAUNCH_CHECK(ctx);
   } else {
-    if ((rc = launch_core(ctx, VARDROP_K_SDPA_BWD_DQ, sdpa_bwd_dq_bf16<2>, sdpa_bwd_dq_bf16<4>, a, B, s))) return rc;
-    if ((rc = launch_core(ctx, VARDROP_K_SDPA_BWD_DKV, sdpa_bwd_dkv_bf16<2>, sdpa_bwd_dkv_bf16<4>, a, B, s))) return rc;
+    if ((rc = launch_sdpa_bwd_dq(ctx, a, B, s))) return rc;
+    if ((rc = launch_sdpa_bwd_dkv(ctx, a, B, s))) return rc;
   }
   {
     // dxs = dq Wq^T + dk Wk^T + dv Wv^T

@@ -67,6 +67,10 @@ __device__ inline void lds_read16(u32x4& dst, uint32_t addr) {
   asm volatile("ds_read_b128 %0, %1" : "=v"(dst) : "v"(addr) : "memory");
 }
 template <int OFF>
+__device__ inline void lds_read16_at(u32x4& dst, uint32_t addr) {
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFF) : "memory");
+}
+template <int OFF>
 __device__ inline void lds_read8_tr(u32x2& dst, uint32_t addr) {
   asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFF) : "memory");
 }
@@ -85,6 +89,14 @@ template <int N>
 __device__ inline void wait_lds(Frag& a, Frag& b) {
   asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a.q), "+v"(b.q) : "n"(N));
 }
+template <int N>
+__device__ inline void wait_lds(Frag& a) {
+  asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(a.q) : "n"(N));
+}
+
+// waits until at most N LDS reads are outstanding (nothing tied to it: it only keeps the counter in range)
+template <int N>
+__device__ inline void wait_lds_count() { asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N) : "memory"); }
 
 template <int BK>
 __device__ inline int swz_kc(int row) { return BK == 32 ? (row >> 1) & 3 : row & 7; }
