@@ -43,20 +43,26 @@ struct SdpaArgs {
   const bf16_t *dy, *wo;          // short selections: dO is formed inside the kernel from dy and Wo
   bf16_t *out, *dq, *dk, *dv;
   float *lse, *Dsum;
+  float* nlse2;                   // long selections: -log2(e) * lse, written by the dQ kernel for the dK/dV kernel
   int n, d, H;
   float scale;
 };
 
 // ---- kernels for long selections (n > 128): staging ring.  A stage holds two [64 tokens][64] bf16 tiles of a
-// head (8 KB each, 128-byte rows, the 16-byte chunk position XORed with token % 8) and 2 x 64 floats; it is
+// head (8 KB each, 128-byte rows, the 16-byte chunk position XORed with a permutation of token % 8) and 2 x 64 floats; it is
 // filled by asynchronous copies, three stages deep, so that a block of tokens costs one workgroup barrier
 // and no staging registers.  Row-major fragments are 16-byte reads, transposed fragments come from the
 // transposing read; LDS reads and their wait counters are written by hand (the compiler would wait for
 // every outstanding copy before any LDS read).
 constexpr int kRingTile = 64 * kDh * 2;
+// chunk position p of token row r holds source chunk p ^ ring_swz(r): a bijection of r % 8, so that the eight rows
+// of a row-fragment read spread over all banks, whose bits 1-2 are r % 4, so that the four rows x two chunks that
+// sixteen lanes of a transposing read touch do too
+__device__ inline int ring_swz(int row) { return ((row & 3) << 1) | ((row >> 2) & 1); }
 constexpr int kRingStage = 2 * kRingTile + 512;
 constexpr int kRingStages = 3;
 constexpr int kRingLds = kRingStages * kRingStage;
+constexpr float kSlack = 8.f;                   // log2 of the largest unnormalised probability (see the forward kernel)
 
 // copies rows [j0, j0 + 64) of two head slices into a stage; a wavefront-wide copy fills 8 token rows and
 // rows past n repeat row n-1
@@ -67,7 +73,7 @@ __device__ inline void ring_issue(const bf16_t* p0, const bf16_t* p1, long long 
   for (int u = 0; u < 8 / NW; ++u) {
     const int rb = u * NW + wave;
     const int row = rb * 8 + (lane >> 3);
-    const long long off = (long long)min(j0 + row, n - 1) * ld + (((lane & 7) ^ (row & 7)) * 8);
+    const long long off = (long long)min(j0 + row, n - 1) * ld + (((lane & 7) ^ ring_swz(row)) * 8);
     dma16(p0 + off, stage + rb * 1024);
     dma16(p1 + off, stage + kRingTile + rb * 1024);
   }
@@ -85,12 +91,12 @@ __device__ inline RingAddr ring_addr(const unsigned char* smem, int lane) {
   const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const unsigned char*)smem;
   r.lds0 = lds0;
 #pragma unroll
-  for (int s = 0; s < 4; ++s) r.row[s] = lds0 + col * 128 + (((2 * s + half) ^ (col & 7)) * 16);
+  for (int s = 0; s < 4; ++s) r.row[s] = lds0 + col * 128 + (((2 * s + half) ^ ring_swz(col)) * 16);
   const int kr = 4 * half + ((lane & 15) >> 2);
 #pragma unroll
   for (int dt = 0; dt < 2; ++dt) {
     const int mn = dt * 32 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-    r.tr[dt] = lds0 + kr * 128 + (((mn >> 3) ^ kr) * 16) + ((mn >> 2) & 1) * 8;
+    r.tr[dt] = lds0 + kr * 128 + (((mn >> 3) ^ ring_swz(kr)) * 16) + ((mn >> 2) & 1) * 8;
   }
   return r;
 }
@@ -125,6 +131,7 @@ __device__ inline void ring_block(int H, int& xb, int& h, int& b) {
 // right-hand operand; every K or V fragment read from LDS serves all QG query groups.
 template <int NW, int QG>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) void sdpa_fwd_bf16(SdpaArgs a) {
+  constexpr int NS = kRingStages;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int LPS = 16 / NW;                 // copies per wavefront and stage
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -139,7 +146,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
   const int q0 = (qb * NW + wave) * (32 * QG);
   const int nb = (n + 63) >> 6;
   ring_issue<NW>(kp, vp, ld, 0, n, smem, wave, lane);
-  if (nb > 1) ring_issue<NW>(kp, vp, ld, 64, n, smem + kRingStage, wave, lane);
+  if (NS > 2 && nb > 1) ring_issue<NW>(kp, vp, ld, 64, n, smem + kRingStage, wave, lane);
   Frag qf[QG][4];
 #pragma unroll
   for (int g = 0; g < QG; ++g) row_frags(qf[g], a.q + base, ld, q0 + 32 * g + col, n, half);
@@ -158,11 +165,11 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
   for (int j = 0; j < nb; ++j) {
     // block j has landed once only the copies of block j+1 are in flight; behind the barrier everyone's have,
     // and everyone is done with block j-1, whose stage block j+2 takes
-    if (j + 1 < nb) wait_vm<LPS>(); else wait_vm<0>();
+    if (NS > 2 && j + 1 < nb) wait_vm<LPS>(); else wait_vm<0>();
     __builtin_amdgcn_s_barrier();
-    if (j + 2 < nb) ring_issue<NW>(kp, vp, ld, (j + 2) * 64, n, smem + ((buf + 2) % kRingStages) * kRingStage, wave, lane);
+    if (j + NS - 1 < nb) ring_issue<NW>(kp, vp, ld, (j + NS - 1) * 64, n, smem + ((buf + NS - 1) % NS) * kRingStage, wave, lane);
     const uint32_t so = buf * kRingStage;
-    buf = buf == kRingStages - 1 ? 0 : buf + 1;
+    buf = buf == NS - 1 ? 0 : buf + 1;
     floatx16 st[QG][2];
     Frag fa[4], fb[4];
     VD_ROW4(fa, 0, 0, so)
@@ -175,14 +182,19 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
 #define VD_S_STEP(F, KT, S, PENDING)                                                    \
   wait_lds<PENDING>(F[S]);                                                              \
   _Pragma("unroll") for (int g = 0; g < QG; ++g) st[g][KT] = mfma(F[S], qf[g][S], st[g][KT]);
+    __builtin_amdgcn_s_setprio(1);              // a wavefront feeding the matrix pipeline goes first
     VD_S_STEP(fa, 0, 0, 7) VD_S_STEP(fa, 0, 1, 6) VD_S_STEP(fa, 0, 2, 5) VD_S_STEP(fa, 0, 3, 4)
     VD_S_STEP(fb, 1, 0, 3) VD_S_STEP(fb, 1, 1, 2) VD_S_STEP(fb, 1, 2, 1) VD_S_STEP(fb, 1, 3, 0)
 #undef VD_S_STEP
+    __builtin_amdgcn_s_setprio(0);
     __builtin_amdgcn_sched_barrier(0);
     VD_TR4(fa, 1, 0, so)                        // V^T fragments of the first 32 keys travel during the softmax
-    // online softmax on the raw scores: max, then exp2(c s - c max) as one fused multiply-add per score.
-    // Keys past the end exist only in the last block; the running output is rescaled only when some
-    // lane's maximum moved (after the first blocks it rarely does).
+    // online softmax on the raw scores: exp2(c s - reference) as one fused multiply-add per score.  The
+    // reference of a query is a past maximum of its scaled scores; it moves up (and the running sum and output
+    // are rescaled, for the whole wavefront) only when a new score exceeds it by more than kSlack, so
+    // probabilities stay below 2^kSlack and, after the first blocks, rescaling is rare.  The result is the same
+    // as with the exact running maximum: numerator and denominator share the reference.
+    // Keys past the end exist only in the last block.
     const bool tail = j * 64 + 64 > n;
 #pragma unroll
     for (int g = 0; g < QG; ++g) {
@@ -201,7 +213,8 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
 #pragma unroll
         for (int r = 0; r < 16; ++r) mt = fmaxf(mt, st[g][kt][r]);
       mt = fmaxf(mt, __shfl_xor(mt, 32, 64));
-      const float mn = fmaxf(m[g], mt * c);           // c > 0: scaling commutes with the maximum
+      const float mc = mt * c;                        // c > 0: scaling commutes with the maximum
+      const float mn = mc > m[g] + kSlack ? mc : m[g];
       float rs = 0.f;
 #pragma unroll
       for (int kt = 0; kt < 2; ++kt)
@@ -228,9 +241,11 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
   wait_lds<PENDING>(F[I]);                                                              \
   _Pragma("unroll") for (int g = 0; g < QG; ++g)                                        \
     acc[g][(I) & 1] = mfma(F[I], regs_to_frag(st[g][KT], (I) >> 1), acc[g][(I) & 1]);
+    __builtin_amdgcn_s_setprio(1);
     VD_PV_STEP(fa, 0, 0, 8) VD_PV_STEP(fa, 0, 1, 8) VD_PV_STEP(fa, 0, 2, 8) VD_PV_STEP(fa, 0, 3, 8)
     VD_PV_STEP(fb, 1, 0, 6) VD_PV_STEP(fb, 1, 1, 4) VD_PV_STEP(fb, 1, 2, 2) VD_PV_STEP(fb, 1, 3, 0)
 #undef VD_PV_STEP
+    __builtin_amdgcn_s_setprio(0);
     __builtin_amdgcn_sched_barrier(0);
   }
 #pragma unroll
@@ -252,6 +267,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
 // right-hand operand of dQ^T = K^T dS^T, whose left operand is the K tile again, read transposed.
 template <int NW, int QG>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) void sdpa_bwd_dq_bf16(SdpaArgs a) {
+  constexpr int NS = kRingStages;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int LPS = 16 / NW;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -267,9 +283,9 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
   const int q0 = (qb * NW + wave) * (32 * QG);
   const int nb = (n + 63) >> 6;
   ring_issue<NW>(kp, vp, ld, 0, n, smem, wave, lane);
-  if (nb > 1) ring_issue<NW>(kp, vp, ld, 64, n, smem + kRingStage, wave, lane);
+  if (NS > 2 && nb > 1) ring_issue<NW>(kp, vp, ld, 64, n, smem + kRingStage, wave, lane);
   Frag qf[QG][4], dof[QG][4];
-  float D[QG], lse2[QG];
+  float D[QG], nlse2[QG];                      // nlse2 = -log2(e) * log-sum-exp (-inf for a query past the end)
 #pragma unroll
   for (int g = 0; g < QG; ++g) {
     const int qi = q0 + 32 * g + col;
@@ -283,7 +299,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
 #pragma unroll
       for (int e = 0; e < 8; ++e) dsum = fmaf(bf2f(dof[g][s].h[e]), bf2f(of[s].h[e]), dsum);
     D[g] = dsum + __shfl_xor(dsum, 32, 64);
-    lse2[g] = qi < n ? a.lse[srow + qi] * kLog2e : INFINITY;
+    nlse2[g] = qi < n ? -a.lse[srow + qi] * kLog2e : -INFINITY;
   }
   const RingAddr ra = ring_addr(smem, lane);
   floatx16 acc[QG][2];
@@ -295,11 +311,11 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
   const float c = a.scale * kLog2e;
   int buf = 0;
   for (int j = 0; j < nb; ++j) {
-    if (j + 1 < nb) wait_vm<LPS>(); else wait_vm<0>();
+    if (NS > 2 && j + 1 < nb) wait_vm<LPS>(); else wait_vm<0>();
     __builtin_amdgcn_s_barrier();
-    if (j + 2 < nb) ring_issue<NW>(kp, vp, ld, (j + 2) * 64, n, smem + ((buf + 2) % kRingStages) * kRingStage, wave, lane);
+    if (j + NS - 1 < nb) ring_issue<NW>(kp, vp, ld, (j + NS - 1) * 64, n, smem + ((buf + NS - 1) % NS) * kRingStage, wave, lane);
     const uint32_t so = buf * kRingStage;
-    buf = buf == kRingStages - 1 ? 0 : buf + 1;
+    buf = buf == NS - 1 ? 0 : buf + 1;
     const bool tail = j * 64 + 64 > n;
 #define VD_DQ_HALF(KT)                                                                                   \
   {                                                                                                      \
@@ -311,19 +327,26 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
       st[g] = zero16();                                                                                  \
       dp[g] = zero16();                                                                                  \
     }                                                                                                    \
+    __builtin_amdgcn_s_setprio(1);                                                                       \
     VD_DQ_STEP(st, fk, qf, 0, 7) VD_DQ_STEP(st, fk, qf, 1, 6) VD_DQ_STEP(st, fk, qf, 2, 5) VD_DQ_STEP(st, fk, qf, 3, 4) \
     VD_DQ_STEP(dp, fv, dof, 0, 3) VD_DQ_STEP(dp, fv, dof, 1, 2) VD_DQ_STEP(dp, fv, dof, 2, 1) VD_DQ_STEP(dp, fv, dof, 3, 0) \
+    __builtin_amdgcn_s_setprio(0);                                                                       \
     __builtin_amdgcn_sched_barrier(0);                                                                   \
     VD_TR4(ft, 0, KT, so)                                                                                \
     _Pragma("unroll") for (int g = 0; g < QG; ++g)                                                       \
-      _Pragma("unroll") for (int r = 0; r < 16; ++r) {                                                   \
-        /* a key past the end repeats the last one: its dS is dropped */                                 \
-        const int key = j * 64 + (KT) * 32 + 8 * (r >> 2) + 4 * half + (r & 3);                          \
-        const float ds = fast_exp2(fmaf(st[g][r], c, -lse2[g])) * (dp[g][r] - D[g]);                     \
-        st[g][r] = (!tail || key < n) ? ds : 0.f;                                                        \
-      }                                                                                                  \
+      _Pragma("unroll") for (int r = 0; r < 16; ++r)                                                     \
+        st[g][r] = fast_exp2(fmaf(st[g][r], c, nlse2[g])) * (dp[g][r] - D[g]);                           \
+    if (tail) {                                 /* a key past the end repeats the last one: its dS is dropped */ \
+      _Pragma("unroll") for (int g = 0; g < QG; ++g)                                                     \
+        _Pragma("unroll") for (int r = 0; r < 16; ++r) {                                                 \
+          const int key = j * 64 + (KT) * 32 + 8 * (r >> 2) + 4 * half + (r & 3);                        \
+          st[g][r] = key < n ? st[g][r] : 0.f;                                                           \
+        }                                                                                                \
+    }                                                                                                    \
     __builtin_amdgcn_sched_barrier(0);                                                                   \
+    __builtin_amdgcn_s_setprio(1);                                                                       \
     VD_DQ_ACC(ft, 0, 6) VD_DQ_ACC(ft, 1, 4) VD_DQ_ACC(ft, 2, 2) VD_DQ_ACC(ft, 3, 0)                       \
+    __builtin_amdgcn_s_setprio(0);                                                                       \
     __builtin_amdgcn_sched_barrier(0);                                                                   \
   }
 #define VD_DQ_STEP(ACC, F, RHS, S, PENDING)                                             \
@@ -346,7 +369,10 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
       bf16_t* row = a.dq + base + (long long)qi * ld;
       store_accT(row, acc[g][0], 0, half, a.scale);
       store_accT(row, acc[g][1], 1, half, a.scale);
-      if (half == 0) a.Dsum[srow + qi] = D[g];
+      if (half == 0) {
+        a.Dsum[srow + qi] = D[g];
+        a.nlse2[srow + qi] = nlse2[g];
+      }
     }
   }
 }
@@ -371,8 +397,9 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
   const bf16_t* op = a.dout + base;
   const int kj = (kb * NW + wave) * 32 + col;
   const int nb = (n + 63) >> 6;
-  // even wavefronts copy the block's log-sum-exp values, odd ones its D (NW is even); queries past n repeat the last
-  const float* stat = (wave & 1) ? a.Dsum + srow : a.lse + srow;
+  // even wavefronts copy the block's -log2(e) * log-sum-exp values (written by the dQ kernel), odd ones its D
+  // (NW is even); queries past n repeat the last
+  const float* stat = (wave & 1) ? a.Dsum + srow : a.nlse2 + srow;
   const int stat_off = 2 * kRingTile + (wave & 1) * 256;
 #define VD_ISSUE_Q(J, BUF)                                                                            \
   {                                                                                                   \
@@ -404,6 +431,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
     Frag fq[4], fo[4], ls[4], ds_[4];                                                                    \
     VD_ROW4(fq, 0, QT, so)                                                                               \
     VD_ROW4(fo, 1, QT, so)                                                                               \
+    __builtin_amdgcn_s_setprio(1);                                                                       \
     wait_lds<7>(fq[0]); st = mfma(fq[0], kf[0], st);                                                     \
     wait_lds<6>(fq[1]); st = mfma(fq[1], kf[1], st);                                                     \
     wait_lds<5>(fq[2]); st = mfma(fq[2], kf[2], st);                                                     \
@@ -422,22 +450,28 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
     wait_lds<10>(fo[1]); dp = mfma(fo[1], vf[1], dp);                                                    \
     wait_lds<9>(fo[2]); dp = mfma(fo[2], vf[2], dp);                                                     \
     wait_lds<8>(fo[3]); dp = mfma(fo[3], vf[3], dp);                                                     \
+    __builtin_amdgcn_s_setprio(0);                                                                       \
     __builtin_amdgcn_sched_barrier(0);                                                                   \
     wait_lds_count<7>();                        /* (the counter holds 15) */                             \
     VD_TR4(fo, 1, QT, so)                       /* dO^T */                                               \
     wait_lds<8>(ls[0], ls[1], ls[2], ls[3]);                                                             \
     wait_lds<8>(ds_[0], ds_[1], ds_[2], ds_[3]);                                                         \
     _Pragma("unroll") for (int r = 0; r < 16; ++r) {                                                     \
-      const int iq = i * 64 + (QT) * 32 + 8 * (r >> 2) + 4 * half + (r & 3);                             \
-      const float lr = __uint_as_float(ls[r >> 2].w[r & 3]) * kLog2e;                                    \
-      float p = fast_exp2(fmaf(st[r], c, -lr));                                                          \
-      p = (!tail || iq < n) ? p : 0.f;          /* a query past the end repeats the last one */          \
+      const float p = fast_exp2(fmaf(st[r], c, __uint_as_float(ls[r >> 2].w[r & 3])));                   \
       st[r] = p;                                                                                         \
       dp[r] = p * (dp[r] - __uint_as_float(ds_[r >> 2].w[r & 3]));                                       \
+    }                                                                                                    \
+    if (tail) {                                 /* a query past the end repeats the last one: dropped */ \
+      _Pragma("unroll") for (int r = 0; r < 16; ++r) {                                                   \
+        const int iq = i * 64 + (QT) * 32 + 8 * (r >> 2) + 4 * half + (r & 3);                           \
+        st[r] = iq < n ? st[r] : 0.f;                                                                    \
+        dp[r] = iq < n ? dp[r] : 0.f;                                                                    \
+      }                                                                                                  \
     }                                                                                                    \
     __builtin_amdgcn_sched_barrier(0);                                                                   \
     wait_lds_count<7>();                                                                                 \
     VD_TR4(fq, 0, QT, so)                       /* Q^T */                                                \
+    __builtin_amdgcn_s_setprio(1);                                                                       \
     wait_lds<8>(fo[0]); accV[0] = mfma(fo[0], regs_to_frag(st, 0), accV[0]);                             \
     wait_lds<8>(fo[1]); accV[1] = mfma(fo[1], regs_to_frag(st, 0), accV[1]);                             \
     wait_lds<8>(fo[2]); accV[0] = mfma(fo[2], regs_to_frag(st, 1), accV[0]);                             \
@@ -446,6 +480,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
     wait_lds<4>(fq[1]); accK[1] = mfma(fq[1], regs_to_frag(dp, 0), accK[1]);                             \
     wait_lds<2>(fq[2]); accK[0] = mfma(fq[2], regs_to_frag(dp, 1), accK[0]);                             \
     wait_lds<0>(fq[3]); accK[1] = mfma(fq[3], regs_to_frag(dp, 1), accK[1]);                             \
+    __builtin_amdgcn_s_setprio(0);                                                                       \
     __builtin_amdgcn_sched_barrier(0);                                                                   \
   }
     VD_DKV_HALF(0)
@@ -1074,8 +1109,10 @@ __global__ __launch_bounds__(256) void colsum_bf16_kernel(ColSumBf16 a) {
   dst[c] = s;
 }
 
-// Launches of the kernels for long selections.  A workgroup takes `rows` queries (or keys); the widest
-// shape that still gives the chip two workgroups per compute unit is chosen, else the narrowest.
+// Launches of the kernels for long selections.  A workgroup of four wavefronts takes 128 queries (or keys)
+// when that still gives the chip two workgroups per compute unit, else two wavefronts take 64.  (Two query
+// groups per wavefront, QG = 2, halve the LDS reads per matrix instruction; measured, the kernels are not
+// bound by those: equal at 1936 tokens, slower at 862.)
 template <typename K>
 int launch_ring(vardrop_ctx* ctx, int kid, K kernel, int rows, const SdpaArgs& a, int B, hipStream_t s) {
   VdTimer timer(ctx, kid, s);
@@ -1085,12 +1122,10 @@ int launch_ring(vardrop_ctx* ctx, int kid, K kernel, int rows, const SdpaArgs& a
 }
 bool ring_fills(const SdpaArgs& a, int B, int rows) { return (long long)vd_ceil_div(a.n, rows) * a.H * B >= 512; }
 int launch_sdpa_fwd(vardrop_ctx* ctx, const SdpaArgs& a, int B, hipStream_t s) {
-  if (ring_fills(a, B, 256)) return launch_ring(ctx, VARDROP_K_SDPA_FWD, sdpa_fwd_bf16<4, 2>, 256, a, B, s);
   if (ring_fills(a, B, 128)) return launch_ring(ctx, VARDROP_K_SDPA_FWD, sdpa_fwd_bf16<4, 1>, 128, a, B, s);
   return launch_ring(ctx, VARDROP_K_SDPA_FWD, sdpa_fwd_bf16<2, 1>, 64, a, B, s);
 }
 int launch_sdpa_bwd_dq(vardrop_ctx* ctx, const SdpaArgs& a, int B, hipStream_t s) {
-  if (ring_fills(a, B, 256)) return launch_ring(ctx, VARDROP_K_SDPA_BWD_DQ, sdpa_bwd_dq_bf16<4, 2>, 256, a, B, s);
   if (ring_fills(a, B, 128)) return launch_ring(ctx, VARDROP_K_SDPA_BWD_DQ, sdpa_bwd_dq_bf16<4, 1>, 128, a, B, s);
   return launch_ring(ctx, VARDROP_K_SDPA_BWD_DQ, sdpa_bwd_dq_bf16<2, 1>, 64, a, B, s);
 }
@@ -1124,7 +1159,7 @@ int vd_attn_bf16_splitk(int d, long long M, int* kchunk) {
 }
 size_t vd_attn_bf16_partial_offset(int B, int n, int d, int H) {
   const size_t M = (size_t)B * n;
-  return vd_align_up(4 * M * d * 2 + (size_t)B * H * n * sizeof(float), 256);
+  return vd_align_up(4 * M * d * 2 + (size_t)2 * B * H * n * sizeof(float), 256);
 }
 // Room for the largest slice count, so that a workspace sized for n tokens also serves any smaller
 // selection (the slice count is not monotone in the token count).
@@ -1195,7 +1230,7 @@ int vd_attn_fwd_bf16(vardrop_ctx* ctx, const void* xs, int B, int n, int d, int 
   return vd_gemm_bf16(ctx, VARDROP_K_GEMM_OUT, go, 1, false, s);
 }
 
-// ws: dO, dq, dk, dv ([M][d] bf16 each), D fp32 [B][H][n], then the split-K partial products
+// ws: dO, dq, dk, dv ([M][d] bf16 each), D and -log2(e) lse, fp32 [B][H][n] each, then the split-K partial products
 int vd_attn_bwd_bf16(vardrop_ctx* ctx, const void* dy, const void* xs, int B, int n, int d, int H,
                      const void* const W[4], const void* saved, void* dxs,
                      float* const dW[4], float* const db[4], void* ws, hipStream_t s) {
@@ -1210,6 +1245,7 @@ int vd_attn_bwd_bf16(vardrop_ctx* ctx, const void* dy, const void* xs, int B, in
   bf16_t* dk = dq + M * d;
   bf16_t* dv = dk + M * d;
   float* D = (float*)(dv + M * d);
+  float* nlse2 = D + (size_t)B * H * n;
   int rc;
   if (n > kSmallN) {  // dO = dy Wo^T (short selections form their dO tiles inside the attention kernel)
     GemmBf16 g = {};
@@ -1220,7 +1256,7 @@ int vd_attn_bwd_bf16(vardrop_ctx* ctx, const void* dy, const void* xs, int B, in
   }
   SdpaArgs a = {};
   a.q = q; a.k = k; a.v = v; a.o = o; a.dout = dO; a.lse = const_cast<float*>(lse);
-  a.dq = dq; a.dk = dk; a.dv = dv; a.Dsum = D;
+  a.dq = dq; a.dk = dk; a.dv = dv; a.Dsum = D; a.nlse2 = nlse2;
   a.dy = (const bf16_t*)dy; a.wo = (const bf16_t*)W[3];
   a.n = n; a.d = d; a.H = H; a.scale = 1.0f / sqrtf((float)kDh);
   if (n <= kSmallN) {
