@@ -384,7 +384,7 @@ int launch_gemm_bwd_pair(vardrop_ctx* ctx, const GemmBf16& gx, const GemmBf16& g
       (long long)gw.K * gw.lda >= (1ll << 31) || (long long)gw.K * gw.ldb >= (1ll << 31))
     return VARDROP_EUNSUPPORTED;
   const long long t128 = (long long)vd_ceil_div(gx.N, 128) * vd_ceil_div(gx.M, 128);
-  if (t128 >= 1024) return launch_gemm_bwd_pair_cfg<128>(ctx, gx, gw, nzw, s);
+  if (t128 >= 512) return launch_gemm_bwd_pair_cfg<128>(ctx, gx, gw, nzw, s);
   return launch_gemm_bwd_pair_cfg<64>(ctx, gx, gw, nzw, s);
 }
 
@@ -395,7 +395,7 @@ int launch_gemm_async(vardrop_ctx* ctx, int kid, const GemmBf16& g, int nz, hipS
     return VARDROP_EUNSUPPORTED;
   const long long t128 = (long long)vd_ceil_div(g.N, 128) * vd_ceil_div(g.M, 128) * nz;
   const long long t64 = (long long)vd_ceil_div(g.N, 128) * vd_ceil_div(g.M, 64) * nz;
-  if (t128 >= 1024) return launch_gemm_async_cfg<true, BKC, false, 128, 2>(ctx, kid, g, nz, s);
+  if (t128 >= 512) return launch_gemm_async_cfg<true, BKC, false, 128, 2>(ctx, kid, g, nz, s);
   if (t64 <= 512) return launch_gemm_async_cfg<true, BKC, false, 64, 3>(ctx, kid, g, nz, s);
   return launch_gemm_async_cfg<true, BKC, false, 64, 2>(ctx, kid, g, nz, s);
 }
