@@ -157,9 +157,12 @@ __device__ inline int wave_reduce(int v) {
 // VEC: rows can be read as aligned float4 (L and the strides multiples of 4, aligned base).
 // R2: radix-2 step before the fold (needs VEC, L a multiple of 8 and at least 64).
 // ITEMS: 8-sample items a thread reads per row block; RING: contraction steps whose table pieces are in
-// flight (2 keeps the kernel inside 128 registers, so that four blocks share a compute unit).
-template <int ITEMS, int RING, bool VEC, bool R2>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(RING == 2 ? 3 : (ITEMS <= 4 ? 2 : 1)))) void kdfh_kernel(KdfhArgs a) {
+// flight (2 for the short-window instance, which has to stay inside 128 registers).
+// WPE: wavefronts per SIMD the register budget is set for.  The short-window instance (ITEMS = 1) takes four: at
+// 862 variates of 32 windows the grid is 3448 wavefronts, which only then are all resident at once (3 per SIMD
+// leave 376 of them waiting for a second round: 14.9 us instead of 11.7).
+template <int ITEMS, int RING, bool VEC, bool R2, int WPE = (RING == 2 ? 3 : (ITEMS <= 4 ? 2 : 1))>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(WPE))) void kdfh_kernel(KdfhArgs a) {
   extern __shared__ halfx8 lds8[];
   const int L = a.L, F = a.F, T = a.T;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -608,13 +611,13 @@ size_t kdfh_lds_bytes(int pitch, int F, int Vb, bool r2) {
   return (size_t)(r2 ? 8 : 4) * 32 * pitch * 16 + sizeof(float) * (4 * 32 + (size_t)Vb * F);
 }
 
-template <int ITEMS, int RING, bool VEC, bool R2>
+template <int ITEMS, int RING, bool VEC, bool R2, int WPE = (RING == 2 ? 3 : (ITEMS <= 4 ? 2 : 1))>
 int launch_kdfh(vardrop_ctx* ctx, const KdfhArgs& a, int grid, size_t lds, hipStream_t s) {
   if (lds > 65536)
-    VD_HIP(ctx, hipFuncSetAttribute((const void*)kdfh_kernel<ITEMS, RING, VEC, R2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    VD_HIP(ctx, hipFuncSetAttribute((const void*)kdfh_kernel<ITEMS, RING, VEC, R2, WPE>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
   {
     VdTimer timer(ctx, VARDROP_K_HASH, s);
-    hipLaunchKernelGGL((kdfh_kernel<ITEMS, RING, VEC, R2>), dim3(grid), dim3(kThreads), lds, s, a);
+    hipLaunchKernelGGL((kdfh_kernel<ITEMS, RING, VEC, R2, WPE>), dim3(grid), dim3(kThreads), lds, s, a);
   }
   VD_LAUNCH_CHECK(ctx);
   return VARDROP_OK;
@@ -720,7 +723,7 @@ extern "C" int vardrop_hash(vardrop_ctx* ctx, const float* x, int B, int N, int 
     return launch_kdfh<4, 4, true, true>(ctx, a, grid, lds, s);
   }
   if (vec) {
-    if (items <= 1) return launch_kdfh<1, 2, true, false>(ctx, a, grid, lds, s);
+    if (items <= 1) return launch_kdfh<1, 2, true, false, 4>(ctx, a, grid, lds, s);
     if (items <= 2) return launch_kdfh<2, 4, true, false>(ctx, a, grid, lds, s);
     if (items <= 4) return launch_kdfh<4, 4, true, false>(ctx, a, grid, lds, s);
     return launch_kdfh<8, 4, true, false>(ctx, a, grid, lds, s);
