@@ -96,7 +96,11 @@ const char* vardrop_kernel_name(int kernel_id);
  * k bins of largest mean amplitude in descending order, ties to the lower bin (step 4),
  * and hash[n] = sum_j topk[n][j] * R^(k-1-j) with R = floor(L/2)+1 (step 5).
  *
- *   x      fp32 [B][N][L] with element strides sb, sn, st (st must be 1)
+ *   x      fp32 [B][N][L] with element strides sb, sn >= 0 and st >= 1.  The kernel reads time-contiguous
+ *          rows (st = 1).  Any other layout -- in particular a time-major batch [B][L][N], sb = L N,
+ *          sn = 1, st = N -- is first copied into time-contiguous rows in the workspace `ws`, which
+ *          must then hold vardrop_hash_strided_workspace_bytes(B, N, L) bytes, 16-byte aligned
+ *          (EWORKSPACE otherwise; B <= 65535 on this path); with st = 1 no workspace is used
  *   topk   int32 [N][k]   bin indices, rank 1 first
  *   hash   uint64 [N]
  *   abar   fp32 [N][f_max-f_min+1] mean amplitudes, or NULL
@@ -112,7 +116,8 @@ const char* vardrop_kernel_name(int kernel_id);
  * ranks agree with an exact evaluation whenever neighbouring amplitudes differ by much more than 1e-6
  * relative.  Non-finite inputs give unspecified ranks.
  */
-size_t vardrop_hash_workspace_bytes(int B, int N, int L, int k, int f_min, int f_max);
+size_t vardrop_hash_workspace_bytes(int B, int N, int L, int k, int f_min, int f_max);   /* st = 1: none */
+size_t vardrop_hash_strided_workspace_bytes(int B, int N, int L);                          /* st != 1 */
 int vardrop_hash(vardrop_ctx* ctx, const float* x, int B, int N, int L,
                  int64_t sb, int64_t sn, int64_t st, int k, int f_min, int f_max,
                  int32_t* topk, uint64_t* hash, float* abar,

@@ -26,6 +26,7 @@ _SIGNATURES = {
     "vardrop_destroy": (None, [_ptr]),
     "vardrop_strerror": (ctypes.c_char_p, [_c_int]),
     "vardrop_last_hip_error": (_c_int, [_ptr]),
+    "vardrop_hash_strided_workspace_bytes": (ctypes.c_size_t, [_c_int, _c_int, _c_int]),
     "vardrop_profile_select": (_c_int, [_ptr, _c_int]),
     "vardrop_profile_read": (_c_int, [_ptr, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(_c_int)]),
     "vardrop_profile_stride": (_c_int, [_ptr, _c_int]),
@@ -151,10 +152,11 @@ def vardrop_profile_read(ctx):
     return ms.value, n.value
 
 
-def vardrop_hash(ctx, x, k, f_min=1, f_max=None, want_abar=False, out=None, stream=None):
-    """x float32 [B, N, L] -> (topk int32 [N, k], hash int64 [N] (the uint64 bits), abar or None).
+def vardrop_hash(ctx, x, k, f_min=1, f_max=None, want_abar=False, out=None, stream=None, ws=None):
+    """x float32 [B, N, L] (any strides) -> (topk int32 [N, k], hash int64 [N] (the uint64 bits), abar or None).
 
-    out: optional (topk, hash) tensors to write into instead of allocating."""
+    out: optional (topk, hash) tensors to write into instead of allocating.
+    ws:  optional uint8 workspace for inputs whose time stride is not 1 (allocated when missing)."""
     if x.dtype != torch.float32 or x.dim() != 3:
         raise TypeError("x must be float32 [B, N, L]")
     B, N, L = x.shape
@@ -167,8 +169,11 @@ def vardrop_hash(ctx, x, k, f_min=1, f_max=None, want_abar=False, out=None, stre
         hsh = torch.empty((N,), dtype=torch.int64, device=x.device)
     abar = torch.empty((N, f_max - f_min + 1), dtype=torch.float32, device=x.device) if want_abar else None
     sb, sn, st = x.stride()
+    if st != 1 and ws is None:
+        ws = torch.empty(ctx._lib.vardrop_hash_strided_workspace_bytes(B, N, L), dtype=torch.uint8, device=x.device)
     rc = ctx._lib.vardrop_hash(ctx.handle, _p(x), B, N, L, sb, sn, st, k, f_min, f_max,
-                               _p(topk), _p(hsh), _p(abar), None, 0, _stream(x, stream))
+                               _p(topk), _p(hsh), _p(abar), _p(ws), 0 if ws is None else ws.numel(),
+                               _stream(x, stream))
     ctx.check(rc, "vardrop_hash")
     return topk, hsh, abar
 

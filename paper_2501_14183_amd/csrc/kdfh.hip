@@ -98,6 +98,25 @@ __global__ void twiddle_kernel(halfx8* tw, int L, BinMap m, int f_max, int T, in
   for (int q = 0; q < 4; ++q) tw[base + (size_t)q * 64] = out[q];
 }
 
+// Windows whose time stride is not 1 (time-major batches [B][L][N], as forecasting loaders hand them over) are
+// first copied into time-contiguous rows: 32 x 32 tiles through LDS, read with the variate index fastest
+// (coalesced when the variate stride is 1), written with time fastest.
+__global__ __launch_bounds__(256) void time_contiguous_kernel(const float* x, float* out, int N, int L,
+                                                              long long sb, long long sn, long long st) {
+  __shared__ float tile[32][33];
+  const int n0 = blockIdx.x * 32, t0 = blockIdx.y * 32, b = blockIdx.z;
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+  for (int j = ty; j < 32; j += 8) {
+    const int t = t0 + j, n = n0 + tx;
+    tile[j][tx] = (t < L && n < N) ? x[(long long)b * sb + (long long)n * sn + (long long)t * st] : 0.f;
+  }
+  __syncthreads();
+  for (int i = ty; i < 32; i += 8) {
+    const int n = n0 + i, t = t0 + tx;
+    if (n < N && t < L) out[((long long)b * N + n) * L + t] = tile[tx][i];
+  }
+}
+
 struct KdfhArgs {
   const float* x;
   const halfx8* tw;
@@ -627,12 +646,15 @@ int launch_kdfh(vardrop_ctx* ctx, const KdfhArgs& a, int grid, size_t lds, hipSt
 
 extern "C" size_t vardrop_hash_workspace_bytes(int, int, int, int, int, int) { return 0; }
 
+extern "C" size_t vardrop_hash_strided_workspace_bytes(int B, int N, int L) {
+  if (B < 1 || N < 0 || L < 2) return 0;
+  return vd_align_up((size_t)B * (size_t)N * (size_t)L * sizeof(float), 256);
+}
+
 extern "C" int vardrop_hash(vardrop_ctx* ctx, const float* x, int B, int N, int L,
                             int64_t sb, int64_t sn, int64_t st, int k, int f_min, int f_max,
                             int32_t* topk, uint64_t* hash, float* abar,
                             void* ws, size_t ws_bytes, void* stream) {
-  (void)ws;
-  (void)ws_bytes;
   if (!ctx) return VARDROP_EINVAL;
   if (B < 1 || N < 0 || L < 2) return VARDROP_EINVAL;
   if (f_min < 0 || f_max < f_min || f_max > L / 2) return VARDROP_EINVAL;
@@ -649,9 +671,21 @@ extern "C" int vardrop_hash(vardrop_ctx* ctx, const float* x, int B, int N, int 
   }
   if (N == 0) return VARDROP_OK;
   if (!x || !topk || !hash) return VARDROP_EINVAL;
-  if (sb < 0 || sn < 0) return VARDROP_EINVAL;
-  if (st != 1) return VARDROP_EUNSUPPORTED;
+  if (sb < 0 || sn < 0 || st < 1) return VARDROP_EINVAL;
   if (L > kMaxHashL || F > 64 * kMaxBinsPerLane) return VARDROP_EUNSUPPORTED;
+  hipStream_t s = (hipStream_t)stream;
+  if (st != 1) {
+    // time-contiguous copy of the windows in the workspace; the kernel below then reads that
+    if (!ws || ws_bytes < vardrop_hash_strided_workspace_bytes(B, N, L) || !vd_aligned(ws, 16)) return VARDROP_EWORKSPACE;
+    if (B > 65535) return VARDROP_EUNSUPPORTED;
+    hipLaunchKernelGGL(time_contiguous_kernel, dim3(vd_ceil_div(N, 32), vd_ceil_div(L, 32), B), dim3(256), 0, s,
+                       x, (float*)ws, N, L, (long long)sb, (long long)sn, (long long)st);
+    VD_LAUNCH_CHECK(ctx);
+    x = (const float*)ws;
+    sb = (int64_t)N * L;
+    sn = L;
+    st = 1;
+  }
 
   int log2_rpv = 5, nrb = vd_ceil_div(B, 32);
   if (B < 32) {
@@ -681,7 +715,6 @@ extern "C" int vardrop_hash(vardrop_ctx* ctx, const float* x, int B, int N, int 
   if (lds > (size_t)ctx->lds_per_block) return VARDROP_EUNSUPPORTED;
   if ((size_t)steps * nct * 4096 > kTwiddleBytes) return VARDROP_EUNSUPPORTED;   // (cannot happen within the limits above)
 
-  hipStream_t s = (hipStream_t)stream;
   if (ctx->twiddle_L != L || ctx->twiddle_fmin != f_min || ctx->twiddle_F != F || ctx->twiddle_r2 != bins.r2) {
     const int entries = steps * nct * 64;
     hipLaunchKernelGGL(twiddle_kernel, dim3(vd_ceil_div(entries, 256)), dim3(256), 0, s,

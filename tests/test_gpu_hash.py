@@ -3,6 +3,7 @@ import numpy as np
 import pytest
 import torch
 
+import util_gpu
 import workloads as wl
 from oracle import kdfh as o_kdfh
 
@@ -174,6 +175,33 @@ def test_longest_window(vd, ctx):
     assert flips_screened == 0 and np.array_equal(hsh[ok], want_hash[ok]) and ok.sum() >= 3
 
 
+@pytest.mark.parametrize("name", ["tiny", "traffic", "long"])
+def test_time_major_batches(vd, ctx, name):
+    """[B][L][N] input (time stride N, variate stride 1): same result as the time-contiguous layout, bit for bit,
+    and equal to the oracle wherever the amplitude gap holds."""
+    w, x, info, want_topk, want_hash, abar = util_gpu.workload_inputs(name)
+    xt = torch.from_numpy(np.ascontiguousarray(x.transpose(0, 2, 1))).cuda()           # [B][L][N]
+    view = xt.transpose(1, 2)                                                          # [B][N][L], strides (L N, 1, N)
+    assert view.stride() == (w.L * w.N, 1, w.N)
+    topk, hsh, _ = run(vd, ctx, view, w.k)
+    ref = run(vd, ctx, torch.from_numpy(x).cuda(), w.k)
+    assert np.array_equal(topk, ref[0]) and np.array_equal(hsh, ref[1])
+    assert np.array_equal(topk, want_topk) and np.array_equal(hsh, want_hash)
+
+
+def test_time_strided_ragged_shapes(vd, ctx):
+    rng = np.random.default_rng(11)
+    for B, N, L, k in [(3, 37, 50, 2), (33, 5, 96, 3), (1, 70, 200, 4)]:
+        base = torch.from_numpy(rng.standard_normal((B, L + 3, N + 2)).astype(np.float32)).cuda()
+        view = base[:, 1:L + 1, 1:N + 1].transpose(1, 2)                               # offset, padded, time-major
+        want = o_kdfh.kdfh(view.cpu().numpy(), k)
+        topk, hsh, _ = run(vd, ctx, view, k)
+        ok = o_kdfh.gap_ok(want[2], k)
+        assert np.array_equal(topk[ok], want[0][ok]) and np.array_equal(hsh[ok], want[1][ok])
+        ref = run(vd, ctx, view.contiguous(), k)
+        assert np.array_equal(topk, ref[0]) and np.array_equal(hsh, ref[1])
+
+
 def test_error_codes(vd, ctx):
     x = torch.zeros((2, 3, 96), device="cuda")
     for kwargs, code in [(dict(k=30), -1), (dict(k=0), -1), (dict(k=3, f_min=5, f_max=4), -1),
@@ -187,9 +215,10 @@ def test_error_codes(vd, ctx):
     with pytest.raises(vd.VarDropError) as e:                      # 32 variates x 257 bins of sums + operands > LDS
         vd.vardrop_hash(ctx, torch.zeros((1, 2, 1024), device="cuda"), 6)
     assert e.value.code == -4
-    with pytest.raises(vd.VarDropError) as e:
-        vd.vardrop_hash(ctx, torch.zeros((2, 96, 3), device="cuda").transpose(1, 2), 3)      # time stride != 1
-    assert e.value.code == -4
+    with pytest.raises(vd.VarDropError) as e:                      # time stride != 1 needs the workspace
+        vd.vardrop_hash(ctx, torch.zeros((2, 96, 3), device="cuda").transpose(1, 2), 3,
+                        ws=torch.empty(16, dtype=torch.uint8, device="cuda"))
+    assert e.value.code == -2                                        # EWORKSPACE
     with pytest.raises(vd.VarDropError) as e:
         vd.vardrop_hash(ctx, torch.zeros((1, 1, 1024), device="cuda"), 8, 1, 512)          # 513**8 >= 2**63
     assert e.value.code == -1
