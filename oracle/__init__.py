@@ -1,7 +1,8 @@
 """CPU oracle for the VarDrop training hot path (test infrastructure only).
 
 A plain, slow, fp64 NumPy statement of what the hot path computes, written from
-the paper's method section (Alg. 1, Def. 1, Eq. 1-3) and from the published
+the paper's method section (Alg. 1, Def. 1, Eq. 1-3; the token embedding of the kept
+variates after the backbone of Sec. 4.1) and from the published
 definition of Philox4x32-10 (Salmon et al., SC'11).  It exists so that the GPU
 library can be checked against something that shares no code with it.
 
