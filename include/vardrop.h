@@ -79,6 +79,9 @@ enum {
   VARDROP_K_GEMM_DW_DXS,     /* weight gradients (K slices) and dxs in one launch           */
   VARDROP_K_SDPA_BWD,        /* dQ, dK, dV of a short selection (n <= 128) in one launch    */
   VARDROP_K_QKV_SDPA_FWD,    /* Q, K, V projection and attention of a short selection       */
+  VARDROP_K_EMBED_ROWS,      /* kept windows: gather from the raw batch, standardise, convert */
+  VARDROP_K_GEMM_EMBED,      /* xs = z We + be                                              */
+  VARDROP_K_GEMM_DWE,        /* dWe = z^T dxs (K slices)                                    */
   VARDROP_K_COUNT
 };
 int vardrop_profile_select(vardrop_ctx* ctx, int kernel_id);
@@ -163,6 +166,38 @@ int vardrop_gather(vardrop_ctx* ctx, const void* tokens, int B, int N, int d, in
                    const int32_t* sel, int n_sel, void* out, void* stream);
 int vardrop_scatter(vardrop_ctx* ctx, const void* dxs, int B, int N, int d, int dtype,
                     const int32_t* sel, int n_sel, void* dtokens, void* stream);
+
+/* ---------------------------------------------------------------------------------
+ * Token embedding of the kept variates only -- Sec. 3.1 / 3.3: the reduction works directly from the raw
+ * variates, so the tokens of the dropped ones never have to be formed.  A token is the shared linear map
+ * R^L -> R^d of one variate's whole lookback window (the variate tokenisation of the backbone, Sec. 4.1):
+ *
+ *   z[b][i][:]  = window sel[i] of batch element b; with standardise != 0 brought to zero mean and unit
+ *                 (population) variance over time, a constant window becoming zeros
+ *   xs[b][i][:] = z[b][i][:] We (+ be)                         xs [B][n_sel][d], element type `dtype`
+ *   backward:     dWe = sum_{b,i} z[b][i][:]^T dxs[b][i][:],  dbe = sum_{b,i} dxs[b][i][:]
+ *                 (the windows are data: there is no gradient with respect to x)
+ *
+ *   x      fp32 [B][N][L], element strides sb, sn, time contiguous
+ *   sel    device int32 [n_sel], entries within 0..N-1 (an out-of-range entry gives a zero window)
+ *   We     [L][d] row-major, `dtype`;  be [d], `dtype`, NULL = none
+ *   saved  vardrop_embed_saved_bytes: the windows z in `dtype` (VARDROP_BF16: rows zero-padded to a
+ *          multiple of 64 samples); written by fwd, read by bwd; 256-byte aligned
+ *   dWe    fp32 [L][d], overwritten;  dbe fp32 [d], overwritten, NULL = skip
+ *   ws     bwd only: vardrop_embed_workspace_bytes (partial sums of the gradients), 256-byte aligned
+ * VARDROP_BF16 rounds z to bf16 and multiplies on the matrix cores with fp32 accumulation; it requires
+ * d % 8 == 0, L % 8 == 0 and B*n_sel*max(d, L+63) < 2^31.  VARDROP_F32 is plain fp32.  2 <= L <= 1024.
+ * n_sel == 0 is a no-op for fwd; bwd then zero-fills the gradients.
+ */
+size_t vardrop_embed_saved_bytes(int B, int n_sel, int L, int dtype);
+size_t vardrop_embed_workspace_bytes(int B, int n_sel, int L, int d, int dtype);
+int vardrop_embed_fwd(vardrop_ctx* ctx, const float* x, int B, int N, int L, int64_t sb, int64_t sn,
+                      const int32_t* sel, int n_sel, int standardise,
+                      const void* We, const void* be, int d, int dtype,
+                      void* xs, void* saved, void* stream);
+int vardrop_embed_bwd(vardrop_ctx* ctx, const void* dxs, int B, int n_sel, int L, int d, int dtype,
+                      const void* saved, float* dWe, float* dbe,
+                      void* ws, size_t ws_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------
  * Multi-head scaled dot-product attention over the kept tokens -- Eq. 3,

@@ -39,6 +39,12 @@ _SIGNATURES = {
                                 _ptr, _ptr, _ptr, _ptr, _ptr, _c_size, _ptr]),
     "vardrop_gather": (_c_int, [_ptr, _ptr, _c_int, _c_int, _c_int, _c_int, _ptr, _c_int, _ptr, _ptr]),
     "vardrop_scatter": (_c_int, [_ptr, _ptr, _c_int, _c_int, _c_int, _c_int, _ptr, _c_int, _ptr, _ptr]),
+    "vardrop_embed_saved_bytes": (_c_size, [_c_int] * 4),
+    "vardrop_embed_workspace_bytes": (_c_size, [_c_int] * 5),
+    "vardrop_embed_fwd": (_c_int, [_ptr, _ptr, _c_int, _c_int, _c_int, _c_i64, _c_i64, _ptr, _c_int, _c_int,
+                                   _ptr, _ptr, _c_int, _c_int, _ptr, _ptr, _ptr]),
+    "vardrop_embed_bwd": (_c_int, [_ptr, _ptr, _c_int, _c_int, _c_int, _c_int, _c_int, _ptr, _ptr, _ptr,
+                                   _ptr, _c_size, _ptr]),
     "vardrop_attn_saved_bytes": (_c_size, [_c_int] * 5),
     "vardrop_attn_workspace_bytes": (_c_size, [_c_int] * 5),
     "vardrop_attn_fwd": (_c_int, [_ptr, _ptr, _c_int, _c_int, _c_int, _c_int, _c_int] + [_ptr] * 8 +
@@ -273,3 +279,35 @@ def vardrop_attn_bwd(ctx, dy, xs, Wq, Wk, Wv, Wo, H, saved, bias_grads=False, ws
                                    _p(ws), ws.numel(), _stream(xs, stream))
     ctx.check(rc, "vardrop_attn_bwd")
     return (dxs, *dW, *db) if bias_grads else (dxs, *dW)
+
+
+def vardrop_embed_fwd(ctx, x, sel, n_sel, We, be=None, standardise=True, saved=None, out=None, stream=None):
+    """x float32 [B, N, L] (time contiguous), sel int32, We [L, d] -> (xs [B, n_sel, d] in We's dtype, saved)."""
+    if x.dtype != torch.float32 or x.dim() != 3 or x.stride(2) != 1:
+        raise TypeError("x must be float32 [B, N, L] with contiguous time")
+    B, N, L = x.shape
+    d = We.shape[1]
+    dt = _dtype_code(We)
+    if saved is None:
+        saved = torch.empty(ctx._lib.vardrop_embed_saved_bytes(B, n_sel, L, dt), dtype=torch.uint8, device=x.device)
+    xs = out if out is not None else torch.empty((B, n_sel, d), dtype=We.dtype, device=x.device)
+    rc = ctx._lib.vardrop_embed_fwd(ctx.handle, _p(x), B, N, L, x.stride(0), x.stride(1), _p(sel), n_sel,
+                                    1 if standardise else 0, _p(We), _p(be), d, dt, _p(xs), _p(saved),
+                                    _stream(x, stream))
+    ctx.check(rc, "vardrop_embed_fwd")
+    return xs, saved
+
+
+def vardrop_embed_bwd(ctx, dxs, L, saved, want_bias=True, ws=None, stream=None):
+    """dxs [B, n_sel, d], saved from vardrop_embed_fwd -> (dWe float32 [L, d], dbe float32 [d] or None)."""
+    B, n_sel, d = dxs.shape
+    dt = _dtype_code(dxs)
+    if ws is None:
+        ws = torch.empty(max(ctx._lib.vardrop_embed_workspace_bytes(B, n_sel, L, d, dt), 256), dtype=torch.uint8,
+                         device=dxs.device)
+    dWe = torch.empty((L, d), dtype=torch.float32, device=dxs.device)
+    dbe = torch.empty((d,), dtype=torch.float32, device=dxs.device) if want_bias else None
+    rc = ctx._lib.vardrop_embed_bwd(ctx.handle, _p(dxs), B, n_sel, L, d, dt, _p(saved), _p(dWe), _p(dbe),
+                                    _p(ws), ws.numel(), _stream(dxs, stream))
+    ctx.check(rc, "vardrop_embed_bwd")
+    return dWe, dbe

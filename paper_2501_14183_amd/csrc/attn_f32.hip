@@ -87,6 +87,21 @@ int launch_gemm(vardrop_ctx* ctx, int kid, const GemmF32& g, int nz, hipStream_t
   return VARDROP_OK;
 }
 
+}  // namespace
+
+// C[m][n] = sum_k A(m, k) B(k, n) (+ bias[n]) with element strides (sam, sak) and (sbk, sbn)
+int vd_gemm_f32(vardrop_ctx* ctx, int kid, const float* A, long long sam, long long sak,
+                const float* B, long long sbk, long long sbn, float* C, int ldc, const float* bias,
+                int M, int N, int K, hipStream_t s) {
+  GemmF32 g = {};
+  g.A[0] = A; g.B[0] = B; g.C[0] = C; g.bias[0] = bias;
+  g.sam = sam; g.sak = sak; g.sbk = sbk; g.sbn = sbn;
+  g.M = M; g.N = N; g.K = K; g.ldc = ldc; g.nseg = 1;
+  return launch_gemm(ctx, kid, g, 1, s);
+}
+
+namespace {
+
 // ------------------------------------------------------------------ attention core
 // q, k, v, o: [B][n][d], head h at columns h*DH .. h*DH+DH-1.  One query (or key) per thread.
 constexpr int kTile = 32;

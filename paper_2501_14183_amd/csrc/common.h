@@ -60,6 +60,11 @@ int vd_attn_bf16_splitk(int d, long long M, int* kchunk);
 size_t vd_attn_bf16_partial_offset(int B, int n, int d, int H);
 size_t vd_attn_bf16_ws_bytes(int B, int n, int d, int H);
 
+// strided fp32 GEMM of the fp32 back end (attn_f32.hip)
+int vd_gemm_f32(vardrop_ctx*, int kid, const float* A, long long sam, long long sak,
+                const float* B, long long sbk, long long sbn, float* C, int ldc, const float* bias,
+                int M, int N, int K, hipStream_t s);
+
 // attention back ends (attn_f32.hip, attn_bf16.hip); argument checks are done by the caller
 int vd_attn_fwd_f32(vardrop_ctx*, const float* xs, int B, int n, int d, int H,
                     const float* const W[4], const float* const bias[4],

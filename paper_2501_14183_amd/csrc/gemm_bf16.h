@@ -17,6 +17,8 @@ struct GemmBf16 {
   int nseg;           // > 1: segments accumulate into C0
   int splitk;         // > 1: grid.z = batches * splitk, slice s writes fp32 to C0 + (z * splitk + s) * M * N
   int kchunk;         // K elements per slice (multiple of 64)
+  int a_kpad;         // != 0: the rows of a k-contiguous A hold zeros from K up to the next multiple of 64, so K
+                      // itself need not be one (B must then be n-contiguous: its last k-row is re-read, times zero)
   void set(int z, const void* a, const void* b, void* c, const void* bias) {
     const bf16_t* pa = (const bf16_t*)a;
     const bf16_t* pb = (const bf16_t*)b;
@@ -40,5 +42,8 @@ int vd_gemm_bf16_wgrad(vardrop_ctx* ctx, int kid, const GemmBf16& g, int nz, hip
 int vd_gemm_bf16_bwd_pair(vardrop_ctx* ctx, const GemmBf16& gx, const GemmBf16& gw, int nzw, hipStream_t s);
 // out[z][i] = sum_s part[z * splitk + s][i] for four matrices of `count` elements, slices in ascending order.
 int vd_gemm_bf16_sum_slices(vardrop_ctx* ctx, const float* part, float* const out[4], long long count, int splitk,
-                            hipStream_t s);
+                            hipStream_t s, int nz = 4);
+// C = A^T * B in fp32 for one matrix, both operands mn-contiguous, K cut into g.splitk slices of g.kchunk: the
+// partial products go to g.C0 ([splitk][M][N] fp32) when splitk > 1, the result itself (ldc) when it is 1.
+int vd_gemm_bf16_wgrad_split(vardrop_ctx* ctx, int kid, const GemmBf16& g, hipStream_t s);
 #endif  // VARDROP_GEMM_BF16_H

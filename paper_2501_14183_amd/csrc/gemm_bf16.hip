@@ -391,7 +391,8 @@ int launch_gemm_bwd_pair(vardrop_ctx* ctx, const GemmBf16& gx, const GemmBf16& g
 template <bool BKC>
 int launch_gemm_async(vardrop_ctx* ctx, int kid, const GemmBf16& g, int nz, hipStream_t s) {
   if (g.M == 0 || g.N == 0) return VARDROP_OK;
-  if (g.K % 64 != 0 || g.N % 8 != 0 || (long long)g.M * g.lda >= (1ll << 31) || (long long)g.K * g.ldb >= (1ll << 31))
+  if ((g.K % 64 != 0 && (BKC || !g.a_kpad)) || g.N % 8 != 0 || (long long)g.M * g.lda >= (1ll << 31) ||
+      (long long)g.K * g.ldb >= (1ll << 31))
     return VARDROP_EUNSUPPORTED;
   const long long t128 = (long long)vd_ceil_div(g.N, 128) * vd_ceil_div(g.M, 128) * nz;
   const long long t64 = (long long)vd_ceil_div(g.N, 128) * vd_ceil_div(g.M, 64) * nz;
@@ -420,16 +421,24 @@ int vd_gemm_bf16_bwd_pair(vardrop_ctx* ctx, const GemmBf16& gx, const GemmBf16& 
   return launch_gemm_bwd_pair(ctx, gx, gw, nzw, s);
 }
 
+int vd_gemm_bf16_wgrad_split(vardrop_ctx* ctx, int kid, const GemmBf16& g, hipStream_t s) {
+  if (g.M == 0 || g.N == 0) return VARDROP_OK;
+  if (g.M % 8 != 0 || g.N % 8 != 0 || g.splitk < 1 || g.kchunk % 64 != 0 ||
+      (long long)g.K * g.lda >= (1ll << 31) || (long long)g.K * g.ldb >= (1ll << 31))
+    return VARDROP_EUNSUPPORTED;
+  return launch_gemm_async_cfg<false, false, true, 64, 2>(ctx, kid, g, 1, s);
+}
+
 int vd_gemm_bf16_sum_slices(vardrop_ctx* ctx, const float* part, float* const out[4], long long count, int splitk,
-                            hipStream_t s) {
+                            hipStream_t s, int nz) {
   SplitkReduce r = {};
   r.part = part;
-  for (int z = 0; z < 4; ++z) r.out[z] = out[z];
+  for (int z = 0; z < nz; ++z) r.out[z] = out[z];
   r.count = count;
   r.splitk = splitk;
   {
     VdTimer timer(ctx, VARDROP_K_REDUCE_DW, s);
-    hipLaunchKernelGGL(splitk_reduce_kernel, dim3(vd_ceil_div((int)(count / 4), 256), 4), dim3(256), 0, s, r);
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3(vd_ceil_div((int)(count / 4), 256), nz), dim3(256), 0, s, r);
   }
   VD_LAUNCH_CHECK(ctx);
   return VARDROP_OK;
