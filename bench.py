@@ -55,6 +55,9 @@ def algorithmic_work(w, n):
         "gemm_dw_dxs": (mm, 14.0 * M * d * d),
         "sdpa_bwd": (mm, 10.0 * B * n * n * d + 2.0 * M * d * d),      # includes dO = dy Wo^T
         "qkv_sdpa_fwd": (mm, 6.0 * M * d * d + 4.0 * B * n * n * d),
+        "embed_rows": ("hbm", 4.0 * M * L + float(es) * M * L),
+        "gemm_embed": (mm, 2.0 * M * L * d),
+        "gemm_dwe": (mm, 2.0 * M * L * d),
     }
 
 
@@ -94,6 +97,10 @@ def parse():
     ap.add_argument("--dense", action="store_true",
                     help="no dropping: one step = attention forward + backward over all N variate tokens of the batch "
                          "(the selection is the identity, Sec. 3.3 at inference); the comparison point for the speed-up")
+    ap.add_argument("--embed", action="store_true",
+                    help="the tokens are embedded inside the step from the raw windows, for the kept variates only "
+                         "(vardrop_embed_fwd / vardrop_embed_bwd; with --dense for all variates), instead of being "
+                         "gathered from a pre-embedded batch")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run five plain 256 MiB device copies (reference for hardware byte counters)")
     return ap.parse_args()
@@ -276,6 +283,12 @@ def main():
     dy_full = torch.from_numpy(wl.make_upstream(w, w.N, seed=0)).to(dev).to(td).reshape(-1)
     stream = torch.cuda.current_stream()
     seed = 0x5EED
+    if args.embed:
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(4321)
+        We_dev = (torch.randn((w.L, w.d), generator=gen, device=dev) / w.L ** 0.5).to(td)
+        be_dev = (0.1 * torch.randn(w.d, generator=gen, device=dev)).to(td)
+        all_idx = torch.arange(w.N, dtype=torch.int32, device=dev)
     saved = ws = None
     stats = {"n_sel": [], "G": []}
 
@@ -323,7 +336,12 @@ def main():
             n_sel, G = int(pinned[j][0]), int(pinned[j][1])
             count = w.B * n_sel * w.d
             shape = (w.B, n_sel, w.d)
-        if args.dense:
+        if args.embed:
+            # tokens of the kept variates (all of them with --dense) straight from the raw windows, then attention
+            xs, _ = vd.vardrop_embed_fwd(ctx, xs_dev[i % args.batches], all_idx if args.dense else sel, n_sel, We_dev, be_dev,
+                                         saved=esaved, out=xs_buf[:count].view(shape), stream=main_h)
+            y, saved = vd.vardrop_attn_fwd(ctx, xs, *W_dev, w.H, saved=saved, out=y_buf[:count].view(shape), stream=main_h)
+        elif args.dense:
             y, saved = vd.vardrop_attn_fwd(ctx, xs, *W_dev, w.H, saved=saved, out=y_buf[:count].view(shape), stream=main_h)
         else:
             # gather + forward in one call: for N' <= 128 the forward kernel fetches the kept rows itself
@@ -332,6 +350,8 @@ def main():
         dy = dy_full[:count].view(shape)
         grads = vd.vardrop_attn_bwd(ctx, dy, xs, *W_dev, w.H, saved, ws=ws, out=(dxs_buf[:count].view(shape), *dW_buf),
                                       stream=main_h)
+        if args.embed:
+            vd.vardrop_embed_bwd(ctx, grads[0], w.L, esaved, ws=ews, out=dWe_buf, stream=main_h)
         stats["n_sel"].append(n_sel)
         stats["G"].append(G)
         return grads
@@ -359,6 +379,11 @@ def main():
     code = vd.BF16 if w.dtype == "bf16" else vd.F32
     saved = torch.empty(lib.vardrop_attn_saved_bytes(w.B, w.N, w.d, w.H, code), dtype=torch.uint8, device=dev)
     ws = torch.empty(lib.vardrop_attn_workspace_bytes(w.B, w.N, w.d, w.H, code), dtype=torch.uint8, device=dev)
+
+    if args.embed:
+        esaved = torch.empty(lib.vardrop_embed_saved_bytes(w.B, w.N, w.L, code), dtype=torch.uint8, device=dev)
+        ews = torch.empty(max(lib.vardrop_embed_workspace_bytes(w.B, w.N, w.L, w.d, code), 256), dtype=torch.uint8, device=dev)
+        dWe_buf = (torch.empty((w.L, w.d), dtype=torch.float32, device=dev), torch.empty(w.d, dtype=torch.float32, device=dev))
 
     # outputs of a step, sized for the largest selection as well (every call writes all of what it returns)
     xs_buf, y_buf, dxs_buf = (torch.empty(w.B * w.N * w.d, dtype=td, device=dev) for _ in range(3))
@@ -432,11 +457,12 @@ def main():
             "bracketed_one_launch_in": BRACKET_EVERY,
             "us_per_step_by_kernel": {k: round(v[1], 2) for k, v in census.items()}}
 
-    if args.dense:
-        args.no_cpu_baseline = True                 # the oracle leg times the dropping path
+    if args.dense or args.embed:
+        args.no_cpu_baseline = True                 # the oracle leg times the dropping path on pre-embedded tokens
     out = {
-        "metric": ("dense (no dropping) variate-attn train steps/s (SDPA fwd/bwd over all N tokens)" if args.dense else
-                   "variate-attn train steps/s (kDFH+sample+SDPA fwd/bwd), HBM GB/s, MFMA %peak"),
+        "metric": (("dense (no dropping) variate-attn train steps/s (SDPA fwd/bwd over all N tokens)" if args.dense else
+                    "variate-attn train steps/s (kDFH+sample+SDPA fwd/bwd), HBM GB/s, MFMA %peak") +
+                   (" + token embedding fwd/bwd inside the step" if args.embed else "")),
         "value": 1e3 / ms, "unit": "steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms, "host_issue_ms_per_step": host_ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",

@@ -298,15 +298,19 @@ def vardrop_embed_fwd(ctx, x, sel, n_sel, We, be=None, standardise=True, saved=N
     return xs, saved
 
 
-def vardrop_embed_bwd(ctx, dxs, L, saved, want_bias=True, ws=None, stream=None):
-    """dxs [B, n_sel, d], saved from vardrop_embed_fwd -> (dWe float32 [L, d], dbe float32 [d] or None)."""
+def vardrop_embed_bwd(ctx, dxs, L, saved, want_bias=True, ws=None, out=None, stream=None):
+    """dxs [B, n_sel, d], saved from vardrop_embed_fwd -> (dWe float32 [L, d], dbe float32 [d] or None).
+    `out`, when given, is that pair of preallocated tensors."""
     B, n_sel, d = dxs.shape
     dt = _dtype_code(dxs)
     if ws is None:
         ws = torch.empty(max(ctx._lib.vardrop_embed_workspace_bytes(B, n_sel, L, d, dt), 256), dtype=torch.uint8,
                          device=dxs.device)
-    dWe = torch.empty((L, d), dtype=torch.float32, device=dxs.device)
-    dbe = torch.empty((d,), dtype=torch.float32, device=dxs.device) if want_bias else None
+    if out is not None:
+        dWe, dbe = out
+    else:
+        dWe = torch.empty((L, d), dtype=torch.float32, device=dxs.device)
+        dbe = torch.empty((d,), dtype=torch.float32, device=dxs.device) if want_bias else None
     rc = ctx._lib.vardrop_embed_bwd(ctx.handle, _p(dxs), B, n_sel, L, d, dt, _p(saved), _p(dWe), _p(dbe),
                                     _p(ws), ws.numel(), _stream(dxs, stream))
     ctx.check(rc, "vardrop_embed_bwd")
