@@ -565,7 +565,7 @@ __global__ __launch_bounds__(512) void sdpa_bwd_small_bf16(SdpaArgs a) {
   const long long srow = ((long long)b * a.H + h) * n;
 
   // ---- dO tile of this head: dO[token][i] = sum_j dy[token][j] Wo[64 h + i][j], both operands k-contiguous,
-  // 64-k slices three stages deep in a ring that overlays the (not yet used) dS^T buffer.  Wavefront w
+  // 64-k slices two stages deep in a ring that overlays the (not yet used) dS^T buffer.  Wavefront w
   // computes token rows 32*(w % 4) .. +31, columns 32*(w / 4) .. +31.
   {
     constexpr int NS = kBwdStages, STAGE = kBwdStage, A_BYTES = kSmallN * 64 * 2, LPS = 3;
@@ -810,7 +810,7 @@ __global__ __launch_bounds__(512) void sdpa_bwd_small_bf16(SdpaArgs a) {
 
 // ---- forward for short selections (n <= 128): one workgroup per (batch, head) computes the head's
 // Q, K and V (a 128 x 192 x d product: xs of the batch times the head's columns of Wq | Wk | Wv,
-// asynchronous copies three stages deep), leaves them in LDS, and runs the attention of the head on
+// asynchronous copies four stages deep), leaves them in LDS, and runs the attention of the head on
 // them; Q, K, V, O and the log-sum-exp are written for the backward pass.  Compared with a projection
 // GEMM followed by an attention kernel this saves a launch and the round trip of Q, K, V through memory.
 // With a selection it also gathers: the token rows are fetched through `sel`, and workgroup (batch, head)
@@ -834,7 +834,7 @@ struct FusedFwdArgs {
   float scale;
 };
 constexpr int kFusedStage = kSmallN * 64 * 2 + 3 * 64 * 64 * 2;     // xs tile + three weight tiles: 40 KB
-constexpr int kFusedStages = 3;
+constexpr int kFusedStages = 4;                    // 160 KB: all of a compute unit's LDS (three stages: 1.5 us more per step)
 constexpr int kFusedLds = kFusedStages * kFusedStage;
 
 __global__ __launch_bounds__(512) void attn_fwd_small_bf16(FusedFwdArgs a) {
@@ -927,7 +927,11 @@ __global__ __launch_bounds__(512) void attn_fwd_small_bf16(FusedFwdArgs a) {
     for (int s = 0; s < NS; ++s) {
       const int t = t0 + s;
       if (t < total) {
-        if (NS >= 3 && total - 1 - t >= 1) wait_vm<LPS>(); else wait_vm<0>();
+        // slice t has landed once at most `ahead` younger slices are still in flight
+        const int ahead = min(total - 1 - t, NS - 2);
+        if (NS >= 4 && ahead >= 2) wait_vm<2 * LPS>();
+        else if (NS >= 3 && ahead == 1) wait_vm<LPS>();
+        else wait_vm<0>();
         __builtin_amdgcn_s_barrier();
         if (t + NS - 1 < total) VD_ISSUE((s + NS - 1) % NS)
         const uint32_t so = s * STAGE;
