@@ -93,7 +93,10 @@ def parse():
     ap.add_argument("--workload", default="traffic")
     ap.add_argument("--batches", type=int, default=4, help="distinct pre-generated batches the steps rotate through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--mode", choices=("steps", "bandwidth"), default="steps")
+    ap.add_argument("--mode", choices=("steps", "bandwidth", "sweep"), default="steps")
+    ap.add_argument("--k", type=int, default=0, help="number of dominant frequencies (default: the workload's)")
+    ap.add_argument("--gs", type=int, default=0,
+                    help="Eq. 1 as printed: a group keeps min(|G|, gs) members (default 0: the workload's keep ratio instead)")
     ap.add_argument("--dense", action="store_true",
                     help="no dropping: one step = attention forward + backward over all N variate tokens of the batch "
                          "(the selection is the identity, Sec. 3.3 at inference); the comparison point for the speed-up")
@@ -263,7 +266,12 @@ def main():
     import paper_2501_14183_amd as vd
     import workloads as wl
 
+    import dataclasses
     w = wl.WORKLOADS[args.workload]
+    K_MAX = 5                                           # largest k of the sweep (sizes the top-k buffers)
+    if args.k:
+        w = dataclasses.replace(w, k=args.k)
+    gs_cap = args.gs                                    # > 0: Eq. 1 with this cap and no keep ratio
     td = torch.bfloat16 if w.dtype == "bf16" else torch.float32
     dev = torch.device("cuda", 0)
     torch.cuda.set_device(dev)
@@ -306,7 +314,7 @@ def main():
     events = [torch.cuda.Event() for _ in range(RING)]
     side = torch.cuda.Stream(device=dev)
     main_h, side_h = stream.cuda_stream, side.cuda_stream      # raw handles: the binding then skips torch's stream lookup
-    sel_bufs = [(torch.empty((w.N, w.k), dtype=torch.int32, device=dev), torch.empty(w.N, dtype=torch.int64, device=dev),
+    sel_bufs = [(torch.empty((w.N, max(w.k, K_MAX)), dtype=torch.int32, device=dev), torch.empty(w.N, dtype=torch.int64, device=dev),
                  torch.empty(w.N, dtype=torch.int32, device=dev), torch.empty(w.N, dtype=torch.int32, device=dev),
                  torch.empty(2, dtype=torch.int32, device=dev)) for _ in range(RING)]
     fences = {}                                         # step -> event recorded on the attention stream after it
@@ -317,7 +325,8 @@ def main():
         j = i % RING
         topk, hsh, gid, sel, counts = sel_bufs[j]
         vd.vardrop_hash(ctx, xs_dev[i % args.batches], w.k, out=(topk, hsh), stream=side_h)
-        vd.vardrop_sample(ctx, hsh, 0, w.ratio[0], w.ratio[1], seed, i, counts_host=pinned[j], out=(gid, sel, counts),
+        num, den = (1, 1) if gs_cap else w.ratio
+        vd.vardrop_sample(ctx, hsh, gs_cap, num, den, seed, i, counts_host=pinned[j], out=(gid, sel, counts),
                           stream=side_h)
         events[j].record(side)
 
@@ -397,6 +406,30 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    if args.mode == "sweep":
+        # Sensitivity of the reduction to k and gs (Sec. 4.4, Eq. 1 as printed) on the synthetic workload:
+        # groups, kept tokens, delta = 1 - N'/N and whole-step throughput for every pair.
+        table = []
+        for k in (2, 3, 4, 5):
+            for gs in (1, 2, 3, 5, 8, 10, 15, 20):
+                w = dataclasses.replace(w, k=k)
+                gs_cap = gs
+                run(0, 10)
+                torch.cuda.synchronize()
+                stats = {"n_sel": [], "G": []}
+                t0 = time.perf_counter()
+                run(10, 60)
+                torch.cuda.synchronize()
+                dt = (time.perf_counter() - t0) / 60
+                n_mean, g_mean = float(np.mean(stats["n_sel"])), float(np.mean(stats["G"]))
+                table.append({"k": k, "gs": gs, "groups": g_mean, "kept": n_mean, "delta": 1.0 - n_mean / w.N,
+                              "steps_per_s": 1.0 / dt})
+        print(json.dumps({"metric": "reduction ratio delta and train steps/s over k and gs (Eq. 1)", "n_gpus": 1,
+                          "data": "synthetic", "dtype": w.dtype,
+                          "config": {"workload": "%s-shaped: B=%d N=%d L=%d d=%d H=%d" % (w.name, w.B, w.N, w.L, w.d, w.H)},
+                          "table": table}))
+        return
+
     run(0, args.warmup)
     torch.cuda.synchronize()
 
@@ -469,6 +502,7 @@ def main():
         "config": {"workload": ("%s-shaped, dense: B=%d N=%d d=%d H=%d, selection = identity" % (w.name, w.B, w.N, w.d, w.H))
                                if args.dense else "%s-shaped: B=%d N=%d L=%d k=%d keep=%d/%d d=%d H=%d" %
                                (w.name, w.B, w.N, w.L, w.k, w.ratio[0], w.ratio[1], w.d, w.H),
+                   "k": w.k, "gs": gs_cap if gs_cap else None,
                    "kept_tokens_mean": n_mean, "groups_mean": float(np.mean(stats["G"])),
                    "batches": args.batches},
         "roofline": roof,
