@@ -177,10 +177,11 @@ __device__ inline int wave_reduce(int v) {
 // R2: radix-2 step before the fold (needs VEC, L a multiple of 8 and at least 64).
 // ITEMS: 8-sample items a thread reads per row block; RING: contraction steps whose table pieces are in
 // flight (2 for the short-window instance, which has to stay inside 128 registers).
-// WPE: wavefronts per SIMD the register budget is set for.  The short-window instance (ITEMS = 1) takes four: at
+// WPE: wavefronts per SIMD the register budget is set for.  The short-window instances (ITEMS = 1) take four: at
 // 862 variates of 32 windows the grid is 3448 wavefronts, which only then are all resident at once (3 per SIMD
-// leave 376 of them waiting for a second round: 14.9 us instead of 11.7).
-template <int ITEMS, int RING, bool VEC, bool R2, int WPE = (RING == 2 ? 3 : (ITEMS <= 4 ? 2 : 1))>
+// leave 376 of them waiting for a second round: 14.9 us instead of 11.7).  (Three for ITEMS = 2, which the LDS
+// would hold at L = 336, costs spills and was slower.)
+template <int ITEMS, int RING, bool VEC, bool R2, int WPE = (ITEMS == 1 ? 4 : (ITEMS <= 4 ? 2 : 1))>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(WPE))) void kdfh_kernel(KdfhArgs a) {
   extern __shared__ halfx8 lds8[];
   const int L = a.L, F = a.F, T = a.T;
@@ -212,6 +213,12 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(WPE)))
   for (int rb = 0; rb < a.nrb; ++rb) {
     __syncthreads();                             // the operands of the previous block have been used
     if (tid < 32) rowmax[tid] = 0u;
+    // In the short-window instances the item coordinates and row addresses below are formed from an opaque copy
+    // of the thread index, so that they are computed here and not ahead of the loop: hoisted, they would live
+    // across it (most launches run it once) and cost registers these instances do not have (they spilled).  The
+    // long-window instances have the registers and are faster with the addresses ready.
+    int tl = tid;
+    if constexpr (ITEMS == 1) asm volatile("" : "+v"(tl));
     // the first steps of the wavefront's first bin tile are requested before the windows are when
     // the windows leave the registers for it (short windows), else right before the contraction
     constexpr bool kEarly = false;
@@ -248,7 +255,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(WPE)))
       }
 #pragma unroll
       for (int it = 0; it < ITEMS; ++it) {
-        const int i = min(it * kThreads + tid, 32 * KG - 1);   // (a thread past the last item repeats it and stores nothing)
+        const int i = min(it * kThreads + tl, 32 * KG - 1);    // (a thread past the last item repeats it and stores nothing)
         const int r = i / KG;
         const int g = i - r * KG;
         ir[it] = r;
@@ -351,7 +358,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(WPE)))
     }
 #pragma unroll
     for (int it = 0; it < ITEMS; ++it) {
-      const int i = min(it * kThreads + tid, 32 * KG - 1);   // (a thread past the last item repeats it and stores nothing)
+      const int i = min(it * kThreads + tl, 32 * KG - 1);    // (a thread past the last item repeats it and stores nothing)
       const int r = i / KG;
       const int g = i - r * KG;
       ir[it] = r;
@@ -630,7 +637,7 @@ size_t kdfh_lds_bytes(int pitch, int F, int Vb, bool r2) {
   return (size_t)(r2 ? 8 : 4) * 32 * pitch * 16 + sizeof(float) * (4 * 32 + (size_t)Vb * F);
 }
 
-template <int ITEMS, int RING, bool VEC, bool R2, int WPE = (RING == 2 ? 3 : (ITEMS <= 4 ? 2 : 1))>
+template <int ITEMS, int RING, bool VEC, bool R2, int WPE = (ITEMS == 1 ? 4 : (ITEMS <= 4 ? 2 : 1))>
 int launch_kdfh(vardrop_ctx* ctx, const KdfhArgs& a, int grid, size_t lds, hipStream_t s) {
   if (lds > 65536)
     VD_HIP(ctx, hipFuncSetAttribute((const void*)kdfh_kernel<ITEMS, RING, VEC, R2, WPE>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
@@ -756,7 +763,7 @@ extern "C" int vardrop_hash(vardrop_ctx* ctx, const float* x, int B, int N, int 
     return launch_kdfh<4, 4, true, true>(ctx, a, grid, lds, s);
   }
   if (vec) {
-    if (items <= 1) return launch_kdfh<1, 2, true, false, 4>(ctx, a, grid, lds, s);
+    if (items <= 1) return launch_kdfh<1, 2, true, false>(ctx, a, grid, lds, s);
     if (items <= 2) return launch_kdfh<2, 4, true, false>(ctx, a, grid, lds, s);
     if (items <= 4) return launch_kdfh<4, 4, true, false>(ctx, a, grid, lds, s);
     return launch_kdfh<8, 4, true, false>(ctx, a, grid, lds, s);
