@@ -14,7 +14,10 @@ Left open by the paper and fixed here as repository conventions:
     counter (n, 0, step_lo, step_hi) and key (seed_lo, seed_hi), u = r0<<32 | r1;
     a group keeps its n_i members with the smallest (u[n], n).  Smallest-key
     selection is a uniform sample without replacement;
-  * S is listed in ascending variate index.
+  * S is listed in ascending variate index;
+  * a second, deterministic sampler (the paper: "not limited to any specific sampling
+    method"): a group keeps the members whose mean amplitude spectrum is closest to the
+    group's mean spectrum (representative_sample below).
 """
 import numpy as np
 
@@ -69,3 +72,44 @@ def stratified_sample(hashes, gs, num, den, seed, step):
 def reduction_ratio(N, n_sel):
     """delta = 1 - N'/N."""
     return 1.0 - float(n_sel) / float(N)
+
+
+def spectrum_distances(abar, gid, G):
+    """Squared distance of every variate's mean amplitude spectrum to the mean spectrum of its group.
+
+    The distances decide which members a group keeps, so they are taken in the arithmetic of the kernel
+    (IEEE single precision, no fused multiply-add) and in a fixed order: the group mean is the sum of the
+    members' spectra in ascending variate index divided by the group size, and the distance sums
+    (abar[n, f] - mean[f])^2 over the candidate bins in ascending f.
+    """
+    A = np.asarray(abar, dtype=np.float32)
+    N, F = A.shape
+    total = np.zeros((G, F), dtype=np.float32)
+    size = np.zeros(G, dtype=np.int64)
+    for n in range(N):
+        total[gid[n]] = total[gid[n]] + A[n]
+        size[gid[n]] += 1
+    mean = total / size[:, None].astype(np.float32)
+    d = np.zeros(N, dtype=np.float32)
+    for f in range(F):
+        t = A[:, f] - mean[gid, f]
+        d = d + t * t
+    return d
+
+
+def representative_sample(hashes, abar, gs, num, den):
+    """Deterministic per-group sampler (Sec. 3.3 leaves the sampling method open): a group keeps the members whose
+    spectrum lies closest to the group's mean spectrum, ties to the lower variate index.
+    Returns (group_id int64 [N], sel int64 [N'] ascending, G)."""
+    gid, G = group_ids(hashes)
+    N = len(gid)
+    d = spectrum_distances(abar, gid, G)
+    kept = []
+    for i in range(G):
+        members = np.nonzero(gid == i)[0].tolist()
+        n_i = keep_count(len(members), gs, num, den)
+        members.sort(key=lambda n: (float(d[n]), n))
+        kept.extend(members[:n_i])
+    sel = np.asarray(sorted(kept), dtype=np.int64)
+    return gid, sel, G
+

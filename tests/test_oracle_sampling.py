@@ -138,3 +138,71 @@ def test_random_sampling_is_uniform_over_subsets():
         for n in s:
             member[n] += c
     assert np.allclose(member[g5] / trials, 2 / 5, atol=0.03)         # membership probability n_i/g
+
+
+# ---------------------------------------------------------------- deterministic representatives
+def spectra(rng, N, F, n_distinct):
+    """Hashes with n_distinct groups and spectra that scatter around one centre per group."""
+    h = random_hashes(rng, N, n_distinct)
+    centres = {int(v): rng.uniform(0.5, 5.0, F) for v in set(h.tolist())}
+    A = np.stack([centres[int(v)] + 0.2 * rng.standard_normal(F) for v in h])
+    return h, np.abs(A)
+
+
+def test_representative_is_the_member_closest_to_the_group_mean():
+    """gs = 1: brute force in float64 over every group, wherever the two best candidates are clearly apart."""
+    rng = np.random.default_rng(21)
+    h, A = spectra(rng, 120, 9, 11)
+    gid, sel, G = sampling.representative_sample(h, A, 1, 1, 1)
+    assert len(sel) == G
+    for g in range(G):
+        members = np.nonzero(gid == g)[0]
+        mean = A[members].mean(axis=0)
+        d = ((A[members] - mean) ** 2).sum(axis=1)
+        order = np.argsort(d, kind="stable")
+        if len(members) == 1 or d[order[1]] - d[order[0]] > 1e-4 * d[order[1]]:
+            assert members[order[0]] in sel
+        assert len(set(members.tolist()) & set(sel.tolist())) == 1
+
+
+@pytest.mark.parametrize("gs,num,den", [(0, 1, 4), (3, 1, 1), (2, 1, 2), (0, 1, 1)])
+def test_representative_counts_and_order(gs, num, den):
+    rng = np.random.default_rng(22)
+    h, A = spectra(rng, 200, 6, 17)
+    gid, sel, G = sampling.representative_sample(h, A, gs, num, den)
+    assert np.all(np.diff(sel) > 0)
+    for g in range(G):
+        members = np.nonzero(gid == g)[0]
+        kept = [n for n in members if n in set(sel.tolist())]
+        assert len(kept) == sampling.keep_count(len(members), gs, num, den)
+        # the kept members are the closest ones: no dropped member is strictly closer than a kept one
+        d = sampling.spectrum_distances(A, gid, G)
+        dropped = [n for n in members if n not in kept]
+        if dropped:
+            assert max(d[n] for n in kept) <= min(d[n] for n in dropped)
+
+
+def test_representative_ties_go_to_the_lower_index_and_scaling_is_irrelevant():
+    h = np.array([7, 7, 7, 7, 9, 9], dtype=np.uint64)
+    A = np.array([[1.0, 2.0]] * 4 + [[3.0, 1.0], [5.0, 1.0]])          # identical members; a pair equidistant from its mean
+    gid, sel, G = sampling.representative_sample(h, A, 2, 1, 1)
+    assert sel.tolist() == [0, 1, 4, 5]
+    gid, sel, G = sampling.representative_sample(h, A, 1, 1, 1)
+    assert sel.tolist() == [0, 4]
+    rng = np.random.default_rng(23)
+    h, A = spectra(rng, 90, 5, 8)
+    base = sampling.representative_sample(h, A.astype(np.float32), 2, 1, 1)[1]
+    for p in (-3, 4):                                                   # a power of two scales every float32 operation exactly
+        assert np.array_equal(sampling.representative_sample(h, (A.astype(np.float32) * np.float32(2.0 ** p)), 2, 1, 1)[1], base)
+
+
+def test_distances_match_float64_within_single_precision():
+    rng = np.random.default_rng(24)
+    h, A = spectra(rng, 150, 25, 12)
+    gid, G = sampling.group_ids(h)
+    d32 = sampling.spectrum_distances(A, gid, G)
+    for n in range(150):
+        members = np.nonzero(gid == gid[n])[0]
+        want = ((A[n] - A[members].mean(axis=0)) ** 2).sum()
+        assert abs(float(d32[n]) - want) <= 1e-5 * max(want, 1.0)
+
