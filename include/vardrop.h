@@ -153,6 +153,28 @@ int vardrop_sample(vardrop_ctx* ctx, const uint64_t* hash, int N,
                    void* ws, size_t ws_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------
+ * Deterministic representatives -- Sec. 3.3 leaves the sampling method open ("not limited to any
+ * specific sampling method").  Groups, group ids and the number n_i a group keeps are those of
+ * vardrop_sample; instead of a random draw a group keeps the n_i members whose mean amplitude spectrum
+ * (abar of vardrop_hash) lies closest to the group's mean spectrum, ties to the lower variate index:
+ *     mean_g[f] = (sum of abar[n][f] over the members n of g, ascending n) / |g|
+ *     d[n]      = sum over f (ascending) of (abar[n][f] - mean_g[f])^2
+ * in IEEE single precision without fused multiply-add, so that the selection is reproducible bit for
+ * bit by any implementation that follows this order.
+ *
+ *   abar   fp32 [N][F], F = number of candidate bins
+ *   ws     vardrop_sample_nearest_workspace_bytes(N, F), 256-byte aligned
+ * Other arguments, outputs and limits as vardrop_sample.  Cost: the grouping pass runs twice and the
+ * group means take O(G N F) operations; meant for the selection of fixed representatives, not tuned
+ * like the random sampler.
+ */
+size_t vardrop_sample_nearest_workspace_bytes(int N, int F);
+int vardrop_sample_nearest(vardrop_ctx* ctx, const uint64_t* hash, const float* abar, int N, int F,
+                           uint32_t gs, uint32_t ratio_num, uint32_t ratio_den,
+                           int32_t* group_id, int32_t* sel, int32_t* counts_dev, int32_t* counts_host,
+                           void* ws, size_t ws_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------
  * Gather of the kept tokens (Sec. 3.1: attention runs on the selected tokens only) and
  * its adjoint.
  *

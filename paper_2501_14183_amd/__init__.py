@@ -5,5 +5,5 @@ from .binding import (  # noqa: F401
     BF16, F32, Context, VarDropError, library_path, load_library,
     vardrop_attn_bwd, vardrop_attn_fwd, vardrop_embed_bwd, vardrop_embed_fwd, vardrop_gather, vardrop_gather_attn_fwd,
     vardrop_hash, vardrop_kernel_name,
-    vardrop_profile_read, vardrop_profile_select, vardrop_profile_stride, vardrop_sample, vardrop_scatter,
+    vardrop_profile_read, vardrop_profile_select, vardrop_profile_stride, vardrop_sample, vardrop_sample_nearest, vardrop_scatter,
 )

@@ -37,6 +37,9 @@ _SIGNATURES = {
     "vardrop_sample_workspace_bytes": (_c_size, [_c_int]),
     "vardrop_sample": (_c_int, [_ptr, _ptr, _c_int, _c_u32, _c_u32, _c_u32, _c_u64, _c_u64,
                                 _ptr, _ptr, _ptr, _ptr, _ptr, _c_size, _ptr]),
+    "vardrop_sample_nearest_workspace_bytes": (_c_size, [_c_int, _c_int]),
+    "vardrop_sample_nearest": (_c_int, [_ptr, _ptr, _ptr, _c_int, _c_int, _c_u32, _c_u32, _c_u32,
+                                        _ptr, _ptr, _ptr, _ptr, _ptr, _c_size, _ptr]),
     "vardrop_gather": (_c_int, [_ptr, _ptr, _c_int, _c_int, _c_int, _c_int, _ptr, _c_int, _ptr, _ptr]),
     "vardrop_scatter": (_c_int, [_ptr, _ptr, _c_int, _c_int, _c_int, _c_int, _ptr, _c_int, _ptr, _ptr]),
     "vardrop_embed_saved_bytes": (_c_size, [_c_int] * 4),
@@ -315,3 +318,19 @@ def vardrop_embed_bwd(ctx, dxs, L, saved, want_bias=True, ws=None, out=None, str
                                     _p(ws), ws.numel(), _stream(dxs, stream))
     ctx.check(rc, "vardrop_embed_bwd")
     return dWe, dbe
+
+
+def vardrop_sample_nearest(ctx, hsh, abar, gs, ratio_num, ratio_den, stream=None):
+    """hash int64 [N], abar float32 [N, F] -> (group_id int32 [N], sel int32 [N] (first N' valid), counts int32 [2]):
+    every group keeps the members closest to its mean spectrum."""
+    N, F = abar.shape
+    dev = hsh.device
+    gid = torch.empty((N,), dtype=torch.int32, device=dev)
+    sel = torch.empty((N,), dtype=torch.int32, device=dev)
+    counts = torch.empty((2,), dtype=torch.int32, device=dev)
+    ws = torch.empty(max(ctx._lib.vardrop_sample_nearest_workspace_bytes(N, F), 256), dtype=torch.uint8, device=dev)
+    rc = ctx._lib.vardrop_sample_nearest(ctx.handle, _p(hsh), _p(abar), N, F, gs, ratio_num, ratio_den,
+                                         _p(gid), _p(sel), _p(counts), None, _p(ws), ws.numel(), _stream(hsh, stream))
+    ctx.check(rc, "vardrop_sample_nearest")
+    return gid, sel, counts
+

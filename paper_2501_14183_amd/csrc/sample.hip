@@ -267,6 +267,7 @@ struct SampleArgs {
   int index_bits;      // log2(npad): room for a variate (or padding) index below the hash in a packed key
   uint32_t gs, num, den;
   uint32_t seed_lo, seed_hi, step_lo, step_hi;
+  const uint64_t* ext_keys;   // optional: key of variate n that orders the members of a group, instead of a Philox draw
 };
 
 // members kept from a group of `size` (Eq. 1 with the optional keep ratio)
@@ -476,9 +477,13 @@ __global__ __launch_bounds__(1024) void sample_kernel(SampleArgs a) {
     const uint32_t n = pay[p];
     const int g = scan[p];
     a.group_id[n] = g;
-    uint32_t r0, r1;
-    philox4x32_10(n, 0u, a.step_lo, a.step_hi, a.seed_lo, a.seed_hi, r0, r1);
-    key[p] = ((uint64_t)r0 << 32) | r1;
+    if (a.ext_keys) {
+      key[p] = a.ext_keys[n];
+    } else {
+      uint32_t r0, r1;
+      philox4x32_10(n, 0u, a.step_lo, a.step_hi, a.seed_lo, a.seed_hi, r0, r1);
+      key[p] = ((uint64_t)r0 << 32) | r1;
+    }
     pay[p] = ((uint32_t)g << 16) | n;
   }
   __syncthreads();
@@ -528,13 +533,59 @@ int next_pow2(int v) {
 
 extern "C" size_t vardrop_sample_workspace_bytes(int) { return 0; }
 
-extern "C" int vardrop_sample(vardrop_ctx* ctx, const uint64_t* hash, int N,
-                              uint32_t gs, uint32_t ratio_num, uint32_t ratio_den,
-                              uint64_t seed, uint64_t step,
-                              int32_t* group_id, int32_t* sel, int32_t* counts, int32_t* counts_host,
-                              void* ws, size_t ws_bytes, void* stream) {
-  (void)ws;
-  (void)ws_bytes;
+namespace {
+
+// ---- deterministic representatives: keys from the distance to the group's mean spectrum.
+// The first member of a group (lowest variate index) computes the group's mean spectrum: one thread per
+// candidate bin adds the members' values in ascending variate index and divides by the group size.
+// Single-precision IEEE operations without fused multiply-add throughout: these values decide which
+// members are kept, and the test oracle evaluates them in the same arithmetic and order.
+__global__ __launch_bounds__(256) void group_mean_kernel(const int32_t* __restrict__ gid, const float* __restrict__ abar,
+                                                        float* __restrict__ mean, int N, int F) {
+  __shared__ int earlier;
+  const int n = blockIdx.x, g = gid[n];
+  if (threadIdx.x == 0) earlier = 0;
+  __syncthreads();
+  for (int m = threadIdx.x; m < n; m += 256)
+    if (gid[m] == g) earlier = 1;
+  __syncthreads();
+  if (earlier) return;
+  for (int f = threadIdx.x; f < F; f += 256) {
+    float acc = 0.f;
+    int size = 0;
+    for (int m = n; m < N; ++m)
+      if (gid[m] == g) {
+        acc = acc + abar[(long long)m * F + f];
+        ++size;
+      }
+    mean[(long long)g * F + f] = acc / (float)size;       // (correctly rounded: the compiler's default for fp32 division)
+  }
+}
+// key[n] = bits of sum_f (abar[n][f] - mean[g][f])^2 (ascending f) in the upper half: non-negative floats order
+// like their bit patterns
+__global__ __launch_bounds__(256) void distance_key_kernel(const int32_t* __restrict__ gid, const float* __restrict__ abar,
+                                                          const float* __restrict__ mean, uint64_t* __restrict__ keys,
+                                                          int N, int F) {
+  const int n = blockIdx.x * 256 + threadIdx.x;
+  if (n >= N) return;
+  const float* row = abar + (long long)n * F;
+  const float* mu = mean + (long long)gid[n] * F;
+  float d = 0.f;
+  {
+#pragma clang fp contract(off)                  // product and sum are rounded separately (no fused multiply-add)
+    for (int f = 0; f < F; ++f) {
+      const float t = row[f] - mu[f];
+      const float sq = t * t;
+      d = d + sq;
+    }
+  }
+  keys[n] = (uint64_t)__float_as_uint(d) << 32;
+}
+
+int run_sample(vardrop_ctx* ctx, const uint64_t* hash, int N,
+               uint32_t gs, uint32_t ratio_num, uint32_t ratio_den,
+               uint64_t seed, uint64_t step, const uint64_t* ext_keys,
+               int32_t* group_id, int32_t* sel, int32_t* counts, int32_t* counts_host, void* stream) {
   if (!ctx || !hash || !group_id || !sel || !counts) return VARDROP_EINVAL;
   if (N < 1) return VARDROP_EINVAL;
   if (ratio_den == 0 || ratio_num > ratio_den) return VARDROP_EINVAL;
@@ -561,6 +612,7 @@ extern "C" int vardrop_sample(vardrop_ctx* ctx, const uint64_t* hash, int N,
   a.seed_hi = (uint32_t)(seed >> 32);
   a.step_lo = (uint32_t)step;
   a.step_hi = (uint32_t)(step >> 32);
+  a.ext_keys = ext_keys;
   hipStream_t s = (hipStream_t)stream;
   const void* fn = E == 2 ? (const void*)sample_kernel<2> : (E == 4 ? (const void*)sample_kernel<4> : (const void*)sample_kernel<8>);
   if (lds > 65536)
@@ -575,4 +627,39 @@ extern "C" int vardrop_sample(vardrop_ctx* ctx, const uint64_t* hash, int N,
   if (counts_host)
     VD_HIP(ctx, hipMemcpyAsync(counts_host, counts, 2 * sizeof(int32_t), hipMemcpyDeviceToHost, s));
   return VARDROP_OK;
+}
+
+}  // namespace
+
+extern "C" int vardrop_sample(vardrop_ctx* ctx, const uint64_t* hash, int N,
+                              uint32_t gs, uint32_t ratio_num, uint32_t ratio_den,
+                              uint64_t seed, uint64_t step,
+                              int32_t* group_id, int32_t* sel, int32_t* counts, int32_t* counts_host,
+                              void* ws, size_t ws_bytes, void* stream) {
+  (void)ws;
+  (void)ws_bytes;
+  return run_sample(ctx, hash, N, gs, ratio_num, ratio_den, seed, step, nullptr, group_id, sel, counts, counts_host, stream);
+}
+
+extern "C" size_t vardrop_sample_nearest_workspace_bytes(int N, int F) {
+  if (N < 1 || F < 1) return 0;
+  return vd_align_up((size_t)N * F * sizeof(float), 256) + vd_align_up((size_t)N * sizeof(uint64_t), 256);
+}
+
+extern "C" int vardrop_sample_nearest(vardrop_ctx* ctx, const uint64_t* hash, const float* abar, int N, int F,
+                                      uint32_t gs, uint32_t ratio_num, uint32_t ratio_den,
+                                      int32_t* group_id, int32_t* sel, int32_t* counts, int32_t* counts_host,
+                                      void* ws, size_t ws_bytes, void* stream) {
+  if (!ctx || !abar || F < 1) return VARDROP_EINVAL;
+  if (N >= 1 && (!ws || !vd_aligned(ws, 256) || ws_bytes < vardrop_sample_nearest_workspace_bytes(N, F))) return VARDROP_EWORKSPACE;
+  // group ids first (the members kept by this pass are overwritten below)
+  int rc = run_sample(ctx, hash, N, gs, ratio_num, ratio_den, 0, 0, nullptr, group_id, sel, counts, nullptr, stream);
+  if (rc) return rc;
+  hipStream_t s = (hipStream_t)stream;
+  float* mean = (float*)ws;
+  uint64_t* keys = (uint64_t*)((char*)ws + vd_align_up((size_t)N * F * sizeof(float), 256));
+  hipLaunchKernelGGL(group_mean_kernel, dim3(N), dim3(256), 0, s, group_id, abar, mean, N, F);
+  hipLaunchKernelGGL(distance_key_kernel, dim3(vd_ceil_div(N, 256)), dim3(256), 0, s, group_id, abar, mean, keys, N, F);
+  VD_LAUNCH_CHECK(ctx);
+  return run_sample(ctx, hash, N, gs, ratio_num, ratio_den, 0, 0, keys, group_id, sel, counts, counts_host, stream);
 }

@@ -98,3 +98,52 @@ def test_error_codes(vd, ctx):
     with pytest.raises(vd.VarDropError) as e:
         vd.vardrop_sample(ctx, torch.zeros(8193, dtype=torch.int64, device="cuda"), 0, 1, 1, 0, 0)
     assert e.value.code == -4
+
+
+# ---------------------------------------------------------------- deterministic representatives
+def check_nearest(vd, ctx, hashes, abar, gs, num, den):
+    abar32 = np.ascontiguousarray(abar, dtype=np.float32)
+    want_gid, want_sel, want_G = o_samp.representative_sample(hashes, abar32, gs, num, den)
+    h = torch.from_numpy(np.asarray(hashes, dtype=np.uint64).view(np.int64)).cuda()
+    gid, sel, counts = vd.vardrop_sample_nearest(ctx, h, torch.from_numpy(abar32).cuda(), gs, num, den)
+    torch.cuda.synchronize()
+    n_sel, G = (int(v) for v in counts.cpu())
+    assert G == want_G and n_sel == len(want_sel)
+    assert np.array_equal(gid.cpu().numpy().astype(np.int64), want_gid)
+    assert np.array_equal(sel.cpu().numpy()[:n_sel].astype(np.int64), want_sel)
+
+
+@pytest.mark.parametrize("name", wl.ORDER)
+def test_representatives_of_the_five_workloads_bit_exact(vd, ctx, name):
+    """Hashes and mean amplitude spectra from the oracle's k-DFH (rounded once to float32): the kept members match
+    the oracle's single-precision evaluation bit for bit, under the keep ratio and under Eq. 1 with gs = 1."""
+    import util_gpu
+    w, x, info, topk, hsh, abar = util_gpu.workload_inputs(name)
+    check_nearest(vd, ctx, hsh, abar, 0, w.ratio[0], w.ratio[1])
+    check_nearest(vd, ctx, hsh, abar, 1, 1, 1)
+
+
+@pytest.mark.parametrize("N,F,n_distinct,gs,num,den", [(1, 1, 1, 0, 1, 1), (5, 3, 1, 2, 1, 1), (64, 25, 5, 0, 1, 3),
+                                                       (129, 7, 129, 1, 1, 1), (1000, 85, 40, 5, 1, 1),
+                                                       (3000, 129, 7, 0, 1, 10)])
+def test_representatives_sizes_ties_and_large_groups(vd, ctx, N, F, n_distinct, gs, num, den):
+    rng = np.random.default_rng([N, F, n_distinct])
+    pool = rng.integers(0, 2 ** 62, size=n_distinct, dtype=np.uint64)
+    h = pool[rng.integers(0, n_distinct, size=N)]
+    A = np.abs(rng.standard_normal((N, F))) + 1.0
+    A[::3] = A[0]                                   # many identical spectra: ties go to the lower index
+    check_nearest(vd, ctx, h, A, gs, num, den)
+
+
+def test_representatives_error_codes(vd, ctx):
+    lib = vd.load_library()
+    h = torch.zeros(4, dtype=torch.int64, device="cuda")
+    A = torch.ones((4, 3), device="cuda")
+    out = [torch.empty(4, dtype=torch.int32, device="cuda") for _ in range(2)] + [torch.empty(2, dtype=torch.int32, device="cuda")]
+    rc = lib.vardrop_sample_nearest(ctx.handle, h.data_ptr(), A.data_ptr(), 4, 3, 0, 1, 1, out[0].data_ptr(), out[1].data_ptr(),
+                                    out[2].data_ptr(), None, None, 0, None)
+    assert rc == -2                                 # no workspace
+    ws = torch.empty(4096, dtype=torch.uint8, device="cuda")
+    rc = lib.vardrop_sample_nearest(ctx.handle, h.data_ptr(), A.data_ptr(), 4, 3, 0, 2, 1, out[0].data_ptr(), out[1].data_ptr(),
+                                    out[2].data_ptr(), None, ws.data_ptr(), ws.numel(), None)
+    assert rc == -1                                 # ratio above one
