@@ -109,8 +109,8 @@ const char* vardrop_kernel_name(int kernel_id);
  *   abar   fp32 [N][f_max-f_min+1] mean amplitudes, or NULL
  * Requires 1 <= k <= f_max-f_min+1, 0 <= f_min <= f_max <= floor(L/2), R^k < 2^63,
  * 2 <= L <= 1024, at most 512 candidate bins, and operand buffers that fit the 160 KiB LDS:
- * 2048 P + 512 + 4 V (f_max-f_min+1) bytes with P = 2 ceil(ceil(L/2) / 16) + 1, or
- * 4096 P + 512 + 4 V (f_max-f_min+1) with P = 2 ceil(L / 64) + 1 when the window length is a multiple
+ * 2048 P + 1024 + 4 V (f_max-f_min+1) bytes with P = 2 ceil(ceil(L/2) / 16) + 1, or
+ * 4096 P + 1024 + 4 V (f_max-f_min+1) with P = 2 ceil(L / 64) + 1 when the window length is a multiple
  * of 8 from 136 on and the rows are 16-byte aligned (x, sb, sn), where the kernel halves the
  * contraction length; V = 32/min(32, B rounded up to a power of two).  Always true for L <= 768 (EUNSUPPORTED
  * otherwise).  N == 0 is a no-op.  Arithmetic: the spectrum is contracted on the half-precision

@@ -15,6 +15,9 @@
 //     odd f:   Re =  v[0] + sum_{0<t<M/2} (v[t] - v[M-t]) cos(2 pi f t / L)
 //              Im = -sum_{0<t<M/2} (v[t] + v[M-t]) sin(2 pi f t / L) - v[M/2] sin(pi f / 2)
 // so every bin is a contraction over L/4 samples instead of L/2; even and odd bins get tiles of their own.
+// One or two bins that a parity set has left after its full tiles (bin 129 of the 129 candidates of a
+// 512-sample window) are contracted by the vector units from the same folded samples instead of occupying
+// a tile, and a wavefront, of their own.
 //
 // Arithmetic.  The contraction runs on the half-precision matrix cores at fp32 quality: every
 // operand is split as  v = hi + lo  with hi = fp16(v) and lo = fp16(v - hi), and
@@ -66,8 +69,12 @@ __device__ inline void split8(const float (&v)[8], Pieces& p) {
 // hi / lo, 2 / 3 = sine hi / lo.  Entries past the last contracted sample or the last bin are zero.
 // Bin of column `c` of bin tile `ct`.  Plain: consecutive bins from f_min.  Radix-2: the first nct_e tiles
 // hold the even candidate bins (from fe0, step 2), the rest the odd ones (from fo0).
+// With the radix-2 step, one or two bins of a parity set left over after its full tiles of 32 ("stray" bins: bin 129
+// of the 129 candidates of a 512-sample window) do not get a tile of their own: the vector units contract them.
+constexpr int kMaxStray = 4;
 struct BinMap {
   int r2, f_min, nct_e, fe0, fo0;
+  int n_stray, stray_f[kMaxStray];
 };
 __device__ inline int bin_of(const BinMap& m, int ct, int c) {
   if (!m.r2) return m.f_min + ct * 32 + c;
@@ -117,9 +124,21 @@ __global__ __launch_bounds__(256) void time_contiguous_kernel(const float* x, fl
   }
 }
 
+// cosine and sine of the stray bins as plain floats: stw[(i * Tp + t) * 2 + {0, 1}] for stray bin i, t < Tp
+__global__ void stray_twiddle_kernel(float* stw, int L, BinMap m, int T, int Tp) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= m.n_stray * Tp) return;
+  const int si = i / Tp, t = i - si * Tp;
+  double sn = 0.0, cs = 0.0;
+  if (t < T) sincospi(2.0 * (double)(((long long)m.stray_f[si] * t) % L) / (double)L, &sn, &cs);
+  stw[2 * i] = (float)cs;
+  stw[2 * i + 1] = (float)sn;
+}
+
 struct KdfhArgs {
   const float* x;
   const halfx8* tw;
+  const float* stw;    // twiddles of the stray bins (BinMap::n_stray > 0)
   int32_t* topk;
   uint64_t* hash;
   float* abar;
@@ -181,7 +200,8 @@ __device__ inline int wave_reduce(int v) {
 // 862 variates of 32 windows the grid is 3448 wavefronts, which only then are all resident at once (3 per SIMD
 // leave 376 of them waiting for a second round: 14.9 us instead of 11.7).  (Three for ITEMS = 2, which the LDS
 // would hold at L = 336, costs spills and was slower.)
-template <int ITEMS, int RING, bool VEC, bool R2, int WPE = (ITEMS == 1 ? 4 : (ITEMS <= 4 ? 2 : 1))>
+// STRAY: the instance that also contracts stray bins (R2 only).
+template <int ITEMS, int RING, bool VEC, bool R2, bool STRAY = false, int WPE = (ITEMS == 1 ? 4 : (ITEMS <= 4 ? 2 : 1))>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(WPE))) void kdfh_kernel(KdfhArgs a) {
   extern __shared__ halfx8 lds8[];
   const int L = a.L, F = a.F, T = a.T;
@@ -198,7 +218,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(WPE)))
   float* rowinv = reinterpret_cast<float*>(rowmax + 32);                   // [32] 1 / scale of a row
   float* xn1 = rowinv + 32;      // [32] scaled middle term of the cosine sum: x[L/2] (0 when L is odd); R2: u[L/4], even bins
   float* xn2 = xn1 + 32;         // [32] R2: scaled middle term of the sine sum, v[L/4], odd bins
-  float* asum = xn2 + 32;                                                  // [Vb][F]
+  float* samp = xn2 + 32;        // [kMaxStray][32] amplitudes of the stray bins, per row
+  float* asum = samp + kMaxStray * 32;                                     // [Vb][F]
 
   for (int i = tid; i < Vb * F; i += kThreads) asum[i] = 0.f;
   const bool even = (L & 1) == 0;
@@ -576,6 +597,50 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(WPE)))
           if (live) asum[(8 * (r >> 2) + 4 * half + (r & 3)) * F + c] += amp[r];
       }
     }
+
+    // ---- stray bins on the vector units: eight threads per row share the folded samples (operand pieces added
+    // back together), then one thread per (bin, variate) adds the rows of the variate in ascending order
+    if constexpr (R2 && STRAY) {
+      {
+        const int r = tid >> 3, part = tid & 7;
+        const int Tp = 8 * KG;
+        for (int si = 0; si < a.bins.n_stray; ++si) {
+          const int f = a.bins.stray_f[si];
+          const halfx8* base = opnd + ((f & 1) ? 128 * pitch : 0) + r * pitch;
+          const float4* tw4 = reinterpret_cast<const float4*>(a.stw + (size_t)si * Tp * 2);
+          float re = 0.f, im = 0.f;
+          for (int g = part; g < KG; g += 8) {
+            const halfx8 ch = base[g], cl = base[32 * pitch + g], sh = base[64 * pitch + g], sl = base[96 * pitch + g];
+#pragma unroll
+            for (int j2 = 0; j2 < 4; ++j2) {
+              const float4 w = tw4[4 * g + j2];            // cos, sin of t = 8 g + 2 j2 and of the next sample
+              re = fmaf((float)ch[2 * j2] + (float)cl[2 * j2], w.x, re);
+              im = fmaf((float)sh[2 * j2] + (float)sl[2 * j2], w.y, im);
+              re = fmaf((float)ch[2 * j2 + 1] + (float)cl[2 * j2 + 1], w.z, re);
+              im = fmaf((float)sh[2 * j2 + 1] + (float)sl[2 * j2 + 1], w.w, im);
+            }
+          }
+#pragma unroll
+          for (int o = 1; o <= 4; o <<= 1) {
+            re += __shfl_xor(re, o, 64);
+            im += __shfl_xor(im, o, 64);
+          }
+          if (part == 0) {
+            const float sg = (f & 2) ? -1.f : 1.f;           // (-1)^(f/2) for an even bin, sin(pi f / 2) for an odd one
+            const float rv = (f & 1) ? re : re + sg * xn1[r];
+            const float iv = (f & 1) ? im + sg * xn2[r] : im;
+            samp[si * 32 + r] = sqrtf(rv * rv + iv * iv) * rowinv[r];
+          }
+        }
+        __syncthreads();
+        for (int i = tid; i < a.bins.n_stray * Vb; i += kThreads) {
+          const int si = i / Vb, v = i - si * Vb;
+          float tot = 0.f;
+          for (int rr = 0; rr < rpv; ++rr) tot += samp[si * 32 + v * rpv + rr];
+          asum[v * F + (a.bins.stray_f[si] - a.f_min)] += tot;
+        }
+      }
+    }
   }
   __syncthreads();
 
@@ -634,16 +699,16 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(WPE)))
 }
 
 size_t kdfh_lds_bytes(int pitch, int F, int Vb, bool r2) {
-  return (size_t)(r2 ? 8 : 4) * 32 * pitch * 16 + sizeof(float) * (4 * 32 + (size_t)Vb * F);
+  return (size_t)(r2 ? 8 : 4) * 32 * pitch * 16 + sizeof(float) * ((4 + kMaxStray) * 32 + (size_t)Vb * F);
 }
 
-template <int ITEMS, int RING, bool VEC, bool R2, int WPE = (ITEMS == 1 ? 4 : (ITEMS <= 4 ? 2 : 1))>
+template <int ITEMS, int RING, bool VEC, bool R2, bool STRAY = false, int WPE = (ITEMS == 1 ? 4 : (ITEMS <= 4 ? 2 : 1))>
 int launch_kdfh(vardrop_ctx* ctx, const KdfhArgs& a, int grid, size_t lds, hipStream_t s) {
   if (lds > 65536)
-    VD_HIP(ctx, hipFuncSetAttribute((const void*)kdfh_kernel<ITEMS, RING, VEC, R2, WPE>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    VD_HIP(ctx, hipFuncSetAttribute((const void*)kdfh_kernel<ITEMS, RING, VEC, R2, STRAY, WPE>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
   {
     VdTimer timer(ctx, VARDROP_K_HASH, s);
-    hipLaunchKernelGGL((kdfh_kernel<ITEMS, RING, VEC, R2, WPE>), dim3(grid), dim3(kThreads), lds, s, a);
+    hipLaunchKernelGGL((kdfh_kernel<ITEMS, RING, VEC, R2, STRAY, WPE>), dim3(grid), dim3(kThreads), lds, s, a);
   }
   VD_LAUNCH_CHECK(ctx);
   return VARDROP_OK;
@@ -712,20 +777,39 @@ extern "C" int vardrop_hash(vardrop_ctx* ctx, const float* x, int B, int N, int 
   bins.fo0 = f_min + 1 - (f_min & 1);
   const int n_even = bins.fe0 <= f_max ? (f_max - bins.fe0) / 2 + 1 : 0;
   const int n_odd = bins.fo0 <= f_max ? (f_max - bins.fo0) / 2 + 1 : 0;
-  bins.nct_e = r2 ? vd_ceil_div(n_even, 32) : 0;
+  // tiles per parity set; one or two bins left over by a set that fills at least one tile are stray bins
+  int tiles_e = vd_ceil_div(n_even, 32), tiles_o = vd_ceil_div(n_odd, 32);
+  bins.n_stray = 0;
+  if (r2) {
+    if (n_even >= 32 && n_even % 32 >= 1 && n_even % 32 <= 2) {
+      tiles_e = n_even / 32;
+      for (int i = 0; i < n_even % 32; ++i) bins.stray_f[bins.n_stray++] = bins.fe0 + 2 * (tiles_e * 32 + i);
+    }
+    if (n_odd >= 32 && n_odd % 32 >= 1 && n_odd % 32 <= 2) {
+      tiles_o = n_odd / 32;
+      for (int i = 0; i < n_odd % 32; ++i) bins.stray_f[bins.n_stray++] = bins.fo0 + 2 * (tiles_o * 32 + i);
+    }
+  }
+  for (int i = bins.n_stray; i < kMaxStray; ++i) bins.stray_f[i] = 0;
+  bins.nct_e = r2 ? tiles_e : 0;
   const int T = r2 ? L / 4 : (L + 1) / 2;
   const int KS = vd_ceil_div(T, 16);
   const int steps = (KS + 3) & ~3;
-  const int nct = r2 ? bins.nct_e + vd_ceil_div(n_odd, 32) : vd_ceil_div(F, 32);
+  const int nct = r2 ? tiles_e + tiles_o : vd_ceil_div(F, 32);
+  const int Tp = 16 * KS;                                 // samples per row the operand entries cover
+  const size_t stw_off = (size_t)steps * nct * 4096;     // the stray bins' twiddles follow the table
   const int pitch = (2 * KS) | 1;
   const size_t lds = kdfh_lds_bytes(pitch, F, Vb, r2);
   if (lds > (size_t)ctx->lds_per_block) return VARDROP_EUNSUPPORTED;
-  if ((size_t)steps * nct * 4096 > kTwiddleBytes) return VARDROP_EUNSUPPORTED;   // (cannot happen within the limits above)
+  if (stw_off + (size_t)kMaxStray * Tp * 2 * sizeof(float) > kTwiddleBytes) return VARDROP_EUNSUPPORTED;   // (cannot happen within the limits above)
 
   if (ctx->twiddle_L != L || ctx->twiddle_fmin != f_min || ctx->twiddle_F != F || ctx->twiddle_r2 != bins.r2) {
     const int entries = steps * nct * 64;
     hipLaunchKernelGGL(twiddle_kernel, dim3(vd_ceil_div(entries, 256)), dim3(256), 0, s,
                        (halfx8*)ctx->twiddle, L, bins, f_max, T, steps, nct);
+    if (bins.n_stray > 0)
+      hipLaunchKernelGGL(stray_twiddle_kernel, dim3(vd_ceil_div(bins.n_stray * Tp, 256)), dim3(256), 0, s,
+                         (float*)((char*)ctx->twiddle + stw_off), L, bins, T, Tp);
     VD_LAUNCH_CHECK(ctx);
     ctx->twiddle_L = L;
     ctx->twiddle_fmin = f_min;
@@ -735,6 +819,7 @@ extern "C" int vardrop_hash(vardrop_ctx* ctx, const float* x, int B, int N, int 
   KdfhArgs a;
   a.x = x;
   a.tw = (const halfx8*)ctx->twiddle;
+  a.stw = (const float*)((const char*)ctx->twiddle + stw_off);
   a.topk = topk;
   a.hash = hash;
   a.abar = abar;
@@ -757,6 +842,11 @@ extern "C" int vardrop_hash(vardrop_ctx* ctx, const float* x, int B, int N, int 
   a.inv_B = 1.0f / (float)B;
   const int grid = vd_ceil_div(N, Vb);
   const int items = vd_ceil_div(32 * 2 * KS, kThreads);
+  if (r2 && bins.n_stray > 0) {
+    if (items <= 1) return launch_kdfh<1, 2, true, true, true>(ctx, a, grid, lds, s);
+    if (items <= 2) return launch_kdfh<2, 4, true, true, true>(ctx, a, grid, lds, s);
+    return launch_kdfh<4, 4, true, true, true>(ctx, a, grid, lds, s);
+  }
   if (r2) {
     if (items <= 1) return launch_kdfh<1, 2, true, true>(ctx, a, grid, lds, s);
     if (items <= 2) return launch_kdfh<2, 4, true, true>(ctx, a, grid, lds, s);
