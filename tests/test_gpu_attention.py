@@ -88,6 +88,16 @@ def test_bf16_ragged_token_counts_with_biases(vd, ctx, n):
     compare(got, want, "bf16", ("y",) + GRADS + ("dbq", "dbk", "dbv", "dbo"))
 
 
+@pytest.mark.parametrize("n", [129, 192, 257, 321])
+def test_bf16_ragged_token_counts_in_the_wide_launch_shape(vd, ctx, n):
+    """Enough (batch, head) pairs that the long-selection kernels run with four wavefronts and 128 rows per
+    workgroup (the shape the large workloads use), at token counts that end a block of 64 and of 128 early."""
+    xs, W, dy, b = random_case(1000 + n, 32, n, 512, "bf16", bias=False)
+    want = oracle_attention(xs, W, 8, dy)
+    got = run_gpu(vd, ctx, xs, W, 8, dy, "bf16")
+    compare(got, want, "bf16", ("y",) + GRADS)
+
+
 @pytest.mark.parametrize("B,n,d,H", [(4, 150, 192, 3), (8, 100, 320, 5), (6, 90, 64, 1)])
 def test_bf16_model_widths_off_the_tile_grid(vd, ctx, B, n, d, H):
     """d is a multiple of 64 but not of the 128-wide GEMM tiles; B*n large enough for sliced weight gradients."""
