@@ -32,7 +32,7 @@ def algorithmic_work(w, n):
 
     Bytes are what the method must move once (inputs read once, outputs written once); flops are
     those of the contractions the method defines (2 per multiply-add).  The second evaluation of
-    S = Q K^T and dP = dO V^T inside the two-kernel backward is not counted as useful work.
+    S = Q K^T and dP = dO V^T inside the two-part backward of long selections is not counted as useful work.
     """
     B, N, L, d = w.B, w.N, w.L, w.d
     M = B * n
@@ -49,6 +49,7 @@ def algorithmic_work(w, n):
         "gemm_do": (mm, 2.0 * M * d * d),
         "sdpa_bwd_dq": (mm, 4.0 * B * n * n * d),
         "sdpa_bwd_dkv": (mm, 6.0 * B * n * n * d),
+        "sdpa_bwd_dqkv": (mm, 10.0 * B * n * n * d),
         "gemm_dw": (mm, 8.0 * M * d * d),
         "reduce_dw": ("hbm", 4.0 * 4 * d * d * 2),
         "gemm_dxs": (mm, 6.0 * M * d * d),

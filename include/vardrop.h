@@ -82,6 +82,7 @@ enum {
   VARDROP_K_EMBED_ROWS,      /* kept windows: gather from the raw batch, standardise, convert */
   VARDROP_K_GEMM_EMBED,      /* xs = z We + be                                              */
   VARDROP_K_GEMM_DWE,        /* dWe = z^T dxs (K slices)                                    */
+  VARDROP_K_SDPA_BWD_DQKV,   /* bf16, n > 128, few workgroups: dQ, dK, dV in one launch (GEMM_DO then forms rowsum(dO * O)) */
   VARDROP_K_COUNT
 };
 int vardrop_profile_select(vardrop_ctx* ctx, int kernel_id);

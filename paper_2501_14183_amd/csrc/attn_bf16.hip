@@ -43,7 +43,7 @@ struct SdpaArgs {
   const bf16_t *dy, *wo;          // short selections: dO is formed inside the kernel from dy and Wo
   bf16_t *out, *dq, *dk, *dv;
   float *lse, *Dsum;
-  float* nlse2;                   // long selections: -log2(e) * lse, written by the dQ kernel for the dK/dV kernel
+  float* nlse2;                   // long selections: -log2(e) * lse, for the dK/dV part
   int n, d, H;
   float scale;
 };
@@ -262,18 +262,16 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
   }
 }
 
-// ---- backward, part 1: dQ and D = rowsum(dO * O).  A wavefront owns 32 QG queries (lane = query), loop over
+// ---- backward, part 1: dQ (D = rowsum(dO * O) comes with dO from the GEMM before).  A wavefront owns 32 QG queries (lane = query), loop over
 // key blocks: S^T = K q^T and dP^T = V dO^T from row fragments of the K and V tiles, dS^T in registers as the
 // right-hand operand of dQ^T = K^T dS^T, whose left operand is the K tile again, read transposed.
-template <int NW, int QG>
-__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) void sdpa_bwd_dq_bf16(SdpaArgs a) {
+template <int NW, int QG, bool DLOCAL>
+__device__ __forceinline__ void sdpa_bwd_dq_body(const SdpaArgs& a, int qb, int h, int b) {
   constexpr int NS = kRingStages;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int LPS = 16 / NW;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int col = lane & 31, half = lane >> 5;
-  int qb, h, b;
-  ring_block(a.H, qb, h, b);
   const int n = a.n;
   const long long ld = a.d;
   const long long base = (long long)b * n * ld + h * kDh;
@@ -291,14 +289,18 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
     const int qi = q0 + 32 * g + col;
     row_frags(qf[g], a.q + base, ld, qi, n, half);
     row_frags(dof[g], a.dout + base, ld, qi, n, half);
-    Frag of[4];
-    row_frags(of, a.o + base, ld, qi, n, half);
-    float dsum = 0.f;
+    if constexpr (DLOCAL) {   // D = rowsum(dO * O) formed here and left for the dK/dV kernel
+      Frag of[4];
+      row_frags(of, a.o + base, ld, qi, n, half);
+      float dsum = 0.f;
 #pragma unroll
-    for (int s = 0; s < 4; ++s)
+      for (int s = 0; s < 4; ++s)
 #pragma unroll
-      for (int e = 0; e < 8; ++e) dsum = fmaf(bf2f(dof[g][s].h[e]), bf2f(of[s].h[e]), dsum);
-    D[g] = dsum + __shfl_xor(dsum, 32, 64);
+        for (int e = 0; e < 8; ++e) dsum = fmaf(bf2f(dof[g][s].h[e]), bf2f(of[s].h[e]), dsum);
+      D[g] = dsum + __shfl_xor(dsum, 32, 64);
+    } else {
+      D[g] = a.Dsum[srow + min(qi, n - 1)];
+    }
     nlse2[g] = qi < n ? -a.lse[srow + qi] * kLog2e : -INFINITY;
   }
   const RingAddr ra = ring_addr(smem, lane);
@@ -369,7 +371,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
       bf16_t* row = a.dq + base + (long long)qi * ld;
       store_accT(row, acc[g][0], 0, half, a.scale);
       store_accT(row, acc[g][1], 1, half, a.scale);
-      if (half == 0) {
+      if (DLOCAL && half == 0) {
         a.Dsum[srow + qi] = D[g];
         a.nlse2[srow + qi] = nlse2[g];
       }
@@ -382,13 +384,11 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
 // fragments; P and dS in registers are the right-hand operands of dV^T = dO^T P and dK^T = Q^T dS, whose left
 // operands are the same tiles read transposed.
 template <int NW>
-__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) void sdpa_bwd_dkv_bf16(SdpaArgs a) {
+__device__ __forceinline__ void sdpa_bwd_dkv_body(const SdpaArgs& a, int kb, int h, int b) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int LPS = 16 / NW + 1;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int col = lane & 31, half = lane >> 5;
-  int kb, h, b;
-  ring_block(a.H, kb, h, b);
   const int n = a.n;
   const long long ld = a.d;
   const long long base = (long long)b * n * ld + h * kDh;
@@ -397,8 +397,8 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
   const bf16_t* op = a.dout + base;
   const int kj = (kb * NW + wave) * 32 + col;
   const int nb = (n + 63) >> 6;
-  // even wavefronts copy the block's -log2(e) * log-sum-exp values (written by the dQ kernel), odd ones its D
-  // (NW is even); queries past n repeat the last
+  // even wavefronts copy the block's -log2(e) * log-sum-exp values, odd ones its D (NW is even); queries past n
+  // repeat the last
   const float* stat = (wave & 1) ? a.Dsum + srow : a.nlse2 + srow;
   const int stat_off = 2 * kRingTile + (wave & 1) * 256;
 #define VD_ISSUE_Q(J, BUF)                                                                            \
@@ -499,6 +499,32 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
 }
 #undef VD_ROW4
 #undef VD_TR4
+
+// Many workgroups: two launches, D = rowsum(dO * O) and -log2(e) * lse written by the dQ kernel, whose matrix work
+// hides the read of O.
+template <int NW>
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) void sdpa_bwd_dq_bf16(SdpaArgs a) {
+  int xb, h, b;
+  ring_block(a.H, xb, h, b);
+  sdpa_bwd_dq_body<NW, 1, true>(a, xb, h, b);
+}
+template <int NW>
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) void sdpa_bwd_dkv_bf16(SdpaArgs a) {
+  int xb, h, b;
+  ring_block(a.H, xb, h, b);
+  sdpa_bwd_dkv_body<NW>(a, xb, h, b);
+}
+// Few workgroups: one launch, so that the two parts fill the chip's places together.  Of the workgroups of a
+// (batch, head) pair the first half take query blocks (dQ), the second half key blocks (dK, dV); neither part
+// reads what the other writes: D and -log2(e) * lse come with dO from the GEMM before.
+template <int NW>
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) void sdpa_bwd_dqkv_bf16(SdpaArgs a) {
+  int xb, h, b;
+  ring_block(a.H, xb, h, b);
+  const int nblk = (int)gridDim.x >> 1;
+  if (xb < nblk) sdpa_bwd_dq_body<NW, 1, false>(a, xb, h, b);
+  else sdpa_bwd_dkv_body<NW>(a, xb - nblk, h, b);
+}
 
 // ---- backward for short selections (n <= 128, the regime variate dropping produces): one workgroup
 // per (batch, head) holds Q, K, V and O of the head in LDS (asynchronous copies), forms the head's dO tile
@@ -1129,13 +1155,24 @@ int launch_sdpa_fwd(vardrop_ctx* ctx, const SdpaArgs& a, int B, hipStream_t s) {
   if (ring_fills(a, B, 128)) return launch_ring(ctx, VARDROP_K_SDPA_FWD, sdpa_fwd_bf16<4, 1>, 128, a, B, s);
   return launch_ring(ctx, VARDROP_K_SDPA_FWD, sdpa_fwd_bf16<2, 1>, 64, a, B, s);
 }
-int launch_sdpa_bwd_dq(vardrop_ctx* ctx, const SdpaArgs& a, int B, hipStream_t s) {
-  if (ring_fills(a, B, 128)) return launch_ring(ctx, VARDROP_K_SDPA_BWD_DQ, sdpa_bwd_dq_bf16<4, 1>, 128, a, B, s);
-  return launch_ring(ctx, VARDROP_K_SDPA_BWD_DQ, sdpa_bwd_dq_bf16<2, 1>, 64, a, B, s);
+// Fewer than two rounds of the chip's 512 workgroup places per part: both parts in one launch (measured: 1-2 %
+// of the step at 173 and 205 tokens; with more rounds the one launch gains nothing and the row sums in the dO GEMM
+// cost more than they do inside the dQ kernel).
+bool sdpa_bwd_paired(const SdpaArgs& a, int B) {
+  return !ring_fills(a, B, 128) || (long long)vd_ceil_div(a.n, 128) * a.H * B < 1024;   // (64-row blocks: always)
 }
-int launch_sdpa_bwd_dkv(vardrop_ctx* ctx, const SdpaArgs& a, int B, hipStream_t s) {
-  if (ring_fills(a, B, 128)) return launch_ring(ctx, VARDROP_K_SDPA_BWD_DKV, sdpa_bwd_dkv_bf16<4>, 128, a, B, s);
-  return launch_ring(ctx, VARDROP_K_SDPA_BWD_DKV, sdpa_bwd_dkv_bf16<2>, 64, a, B, s);
+int launch_sdpa_bwd(vardrop_ctx* ctx, const SdpaArgs& a, int B, hipStream_t s) {
+  if (!sdpa_bwd_paired(a, B)) {
+    const int rc = launch_ring(ctx, VARDROP_K_SDPA_BWD_DQ, sdpa_bwd_dq_bf16<4>, 128, a, B, s);
+    return rc ? rc : launch_ring(ctx, VARDROP_K_SDPA_BWD_DKV, sdpa_bwd_dkv_bf16<4>, 128, a, B, s);
+  }
+  VdTimer timer(ctx, VARDROP_K_SDPA_BWD_DQKV, s);
+  if (ring_fills(a, B, 128))
+    hipLaunchKernelGGL(sdpa_bwd_dqkv_bf16<4>, dim3(2 * vd_ceil_div(a.n, 128), a.H, B), dim3(256), kRingLds, s, a);
+  else
+    hipLaunchKernelGGL(sdpa_bwd_dqkv_bf16<2>, dim3(2 * vd_ceil_div(a.n, 64), a.H, B), dim3(128), kRingLds, s, a);
+  VD_LAUNCH_CHECK(ctx);
+  return VARDROP_OK;
 }
 
 }  // namespace
@@ -1251,18 +1288,24 @@ int vd_attn_bwd_bf16(vardrop_ctx* ctx, const void* dy, const void* xs, int B, in
   float* D = (float*)(dv + M * d);
   float* nlse2 = D + (size_t)B * H * n;
   int rc;
+  SdpaArgs a = {};
+  a.n = n; a.d = d; a.H = H;
+  const bool paired = sdpa_bwd_paired(a, B);
   if (n > kSmallN) {  // dO = dy Wo^T (short selections form their dO tiles inside the attention kernel)
     GemmBf16 g = {};
     g.set(0, dy, W[3], dO, nullptr);
     g.lda = d; g.ldb = d; g.ldc = d;
     g.M = (int)M; g.N = d; g.K = d; g.nseg = 1;
+    if (paired) {     // D = rowsum(dO * O) per head from the same tiles, and -log2(e) * lse beside it
+      g.rs_o = o; g.rs_out = D; g.rs_n = n; g.rs_H = H;
+      g.rs_aux_in = lse; g.rs_aux_out = nlse2; g.rs_aux_mul = -kLog2e;
+    }
     if ((rc = vd_gemm_bf16(ctx, VARDROP_K_GEMM_DO, g, 1, true, s))) return rc;
   }
-  SdpaArgs a = {};
   a.q = q; a.k = k; a.v = v; a.o = o; a.dout = dO; a.lse = const_cast<float*>(lse);
   a.dq = dq; a.dk = dk; a.dv = dv; a.Dsum = D; a.nlse2 = nlse2;
   a.dy = (const bf16_t*)dy; a.wo = (const bf16_t*)W[3];
-  a.n = n; a.d = d; a.H = H; a.scale = 1.0f / sqrtf((float)kDh);
+  a.scale = 1.0f / sqrtf((float)kDh);
   if (n <= kSmallN) {
     static int configured_device = -1;
     if (configured_device != ctx->device) {
@@ -1275,8 +1318,7 @@ int vd_attn_bwd_bf16(vardrop_ctx* ctx, const void* dy, const void* xs, int B, in
     }
     VD_LAUNCH_CHECK(ctx);
   } else {
-    if ((rc = launch_sdpa_bwd_dq(ctx, a, B, s))) return rc;
-    if ((rc = launch_sdpa_bwd_dkv(ctx, a, B, s))) return rc;
+    if ((rc = launch_sdpa_bwd(ctx, a, B, s))) return rc;
   }
   {
     // dxs = dq Wq^T + dk Wk^T + dv Wv^T

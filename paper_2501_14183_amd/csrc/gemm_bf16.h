@@ -19,6 +19,16 @@ struct GemmBf16 {
   int kchunk;         // K elements per slice (multiple of 64)
   int a_kpad;         // != 0: the rows of a k-contiguous A hold zeros from K up to the next multiple of 64, so K
                       // itself need not be one (B must then be n-contiguous: its last k-row is re-read, times zero)
+  // rs_out != nullptr (bf16 output, one matrix, N a multiple of 64): the epilogue also writes, per row m = b * rs_n + q
+  // and per 64-column head h, rs_out[(b * rs_H + h) * rs_n + q] = sum_c C[m][64 h + c] * rs_o[m][64 h + c] in fp32
+  // from the rounded C (rs_o has C's shape and leading dimension)
+  // and, when rs_aux_out != nullptr, rs_aux_out[i] = rs_aux_mul * rs_aux_in[i] at the same index i
+  const bf16_t* rs_o;
+  float* rs_out;
+  int rs_n, rs_H;
+  const float* rs_aux_in;
+  float* rs_aux_out;
+  float rs_aux_mul;
   void set(int z, const void* a, const void* b, void* c, const void* bias) {
     const bf16_t* pa = (const bf16_t*)a;
     const bf16_t* pb = (const bf16_t*)b;

@@ -299,6 +299,40 @@ __device__ __forceinline__ void gemm_async_tile(const GemmBf16& g, const int bx,
       *reinterpret_cast<u32x4*>(Cb + (long long)(m0 + row) * ldc_bytes + (long long)(n0 + c * EPC) * ES) = v;
     }
   }
+  if constexpr (!SPLIT) {
+    // per-head row sums of C * rs_o (see GemmBf16) from the rounded tile in LDS: a pair of neighbouring lanes
+    // takes the two 32-column halves of one head of one row, each in ascending column order
+    if (g.rs_out) {
+#pragma unroll
+      for (int u = 0; u < BM * 4 / 256; ++u) {
+        const int idx = u * 256 + threadIdx.x;
+        const int row = idx >> 2, c0 = ((idx >> 1) & 1) * 64 + (idx & 1) * 32;
+        const int m = m0 + row;
+        const bool live = m < g.M && n0 + c0 < g.N;
+        float p = 0.f;
+        if (live) {
+          const bf16_t* orow = g.rs_o + (long long)m * g.ldc + n0 + c0;
+#pragma unroll
+          for (int v4 = 0; v4 < 4; ++v4) {
+            const u32x4 cv = *reinterpret_cast<const u32x4*>(smem + row * CPITCH + (c0 + 8 * v4) * 2);
+            const u32x4 ov = *reinterpret_cast<const u32x4*>(orow + 8 * v4);
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+              p = fmaf(__uint_as_float(cv[w] << 16), __uint_as_float(ov[w] << 16), p);
+              p = fmaf(__uint_as_float(cv[w] & 0xffff0000u), __uint_as_float(ov[w] & 0xffff0000u), p);
+            }
+          }
+        }
+        p += __shfl_xor(p, 1, 64);
+        if (live && (idx & 1) == 0) {
+          const int b = m / g.rs_n;
+          const long long i = ((long long)b * g.rs_H + ((n0 + c0) >> 6)) * g.rs_n + (m - b * g.rs_n);
+          g.rs_out[i] = p;
+          if (g.rs_aux_out) g.rs_aux_out[i] = g.rs_aux_mul * g.rs_aux_in[i];
+        }
+      }
+    }
+  }
 }
 
 // LDS a workgroup of the asynchronous GEMM needs: the staging ring, or the output tile if that is larger
@@ -394,6 +428,7 @@ int launch_gemm_async(vardrop_ctx* ctx, int kid, const GemmBf16& g, int nz, hipS
   if ((g.K % 64 != 0 && (BKC || !g.a_kpad)) || g.N % 8 != 0 || (long long)g.M * g.lda >= (1ll << 31) ||
       (long long)g.K * g.ldb >= (1ll << 31))
     return VARDROP_EUNSUPPORTED;
+  if (g.rs_out && (nz != 1 || g.nseg > 1 || g.N % 64 != 0 || g.rs_n <= 0 || g.M % g.rs_n != 0)) return VARDROP_EUNSUPPORTED;
   const long long t128 = (long long)vd_ceil_div(g.N, 128) * vd_ceil_div(g.M, 128) * nz;
   const long long t64 = (long long)vd_ceil_div(g.N, 128) * vd_ceil_div(g.M, 64) * nz;
   if (t128 >= 512) return launch_gemm_async_cfg<true, BKC, false, 128, 2>(ctx, kid, g, nz, s);
