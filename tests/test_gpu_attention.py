@@ -98,9 +98,10 @@ def test_bf16_ragged_token_counts_in_the_wide_launch_shape(vd, ctx, n):
     compare(got, want, "bf16", ("y",) + GRADS)
 
 
-@pytest.mark.parametrize("B,n,d,H", [(4, 150, 192, 3), (8, 100, 320, 5), (6, 90, 64, 1)])
+@pytest.mark.parametrize("B,n,d,H", [(4, 150, 192, 3), (8, 100, 320, 5), (6, 90, 64, 1), (2, 130, 64, 1), (3, 200, 320, 5)])
 def test_bf16_model_widths_off_the_tile_grid(vd, ctx, B, n, d, H):
-    """d is a multiple of 64 but not of the 128-wide GEMM tiles; B*n large enough for sliced weight gradients."""
+    """d is a multiple of 64 but not of the 128-wide GEMM tiles; B*n large enough for sliced weight gradients; more
+    than 128 tokens with one head and with an odd head count (the dO product then forms the row sums of dO * O)."""
     xs, W, dy, b = random_case(7 * d + n, B, n, d, "bf16", bias=True)
     want = oracle_attention(xs, W, H, dy, tuple(b))
     got = run_gpu(vd, ctx, xs, W, H, dy, "bf16", biases=b)
