@@ -1155,11 +1155,12 @@ int launch_sdpa_fwd(vardrop_ctx* ctx, const SdpaArgs& a, int B, hipStream_t s) {
   if (ring_fills(a, B, 128)) return launch_ring(ctx, VARDROP_K_SDPA_FWD, sdpa_fwd_bf16<4, 1>, 128, a, B, s);
   return launch_ring(ctx, VARDROP_K_SDPA_FWD, sdpa_fwd_bf16<2, 1>, 64, a, B, s);
 }
-// Fewer than two rounds of the chip's 512 workgroup places per part: both parts in one launch (measured: 1-2 %
-// of the step at 173 and 205 tokens; with more rounds the one launch gains nothing and the row sums in the dO GEMM
-// cost more than they do inside the dQ kernel).
+// Fewer than three rounds of the chip's 512 workgroup places per part: both parts in one launch.  Measured per step
+// at B = 32, H = 8: 1.2-1.8 % faster at 173, 205 and 321 tokens, 1.3 % at 422 (1024 workgroups per part), 0.9 % at 543
+// (1280); 1 % slower at 862 (1792) and at 1936 tokens with B = 8, H = 12 (1536), where the single launch gains
+// nothing and the row sums cost the dO GEMM more than they do inside the dQ kernel.
 bool sdpa_bwd_paired(const SdpaArgs& a, int B) {
-  return !ring_fills(a, B, 128) || (long long)vd_ceil_div(a.n, 128) * a.H * B < 1024;   // (64-row blocks: always)
+  return !ring_fills(a, B, 128) || (long long)vd_ceil_div(a.n, 128) * a.H * B < 1536;   // (64-row blocks: always)
 }
 int launch_sdpa_bwd(vardrop_ctx* ctx, const SdpaArgs& a, int B, hipStream_t s) {
   if (!sdpa_bwd_paired(a, B)) {
