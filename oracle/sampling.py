@@ -17,7 +17,8 @@ Left open by the paper and fixed here as repository conventions:
   * S is listed in ascending variate index;
   * a second, deterministic sampler (the paper: "not limited to any specific sampling
     method"): a group keeps the members whose mean amplitude spectrum is closest to the
-    group's mean spectrum (representative_sample below).
+    group's mean spectrum (representative_sample below), distances in float64, ties to
+    the lower variate index.
 """
 import numpy as np
 
@@ -75,25 +76,19 @@ def reduction_ratio(N, n_sel):
 
 
 def spectrum_distances(abar, gid, G):
-    """Squared distance of every variate's mean amplitude spectrum to the mean spectrum of its group.
+    """Squared Euclidean distance of every variate's mean amplitude spectrum to the mean spectrum of its group:
 
-    The distances decide which members a group keeps, so they are taken in the arithmetic of the kernel
-    (IEEE single precision, no fused multiply-add) and in a fixed order: the group mean is the sum of the
-    members' spectra in ascending variate index divided by the group size, and the distance sums
-    (abar[n, f] - mean[f])^2 over the candidate bins in ascending f.
+        mean_g[f] = (1 / |g|) sum_{n in g} abar[n, f],      d[n] = sum_f (abar[n, f] - mean_{gid[n]}[f])^2,
+
+    the plain definition in float64 (the inputs are converted exactly).  Returns d as float64 [N].
     """
-    A = np.asarray(abar, dtype=np.float32)
-    N, F = A.shape
-    total = np.zeros((G, F), dtype=np.float32)
-    size = np.zeros(G, dtype=np.int64)
-    for n in range(N):
-        total[gid[n]] = total[gid[n]] + A[n]
-        size[gid[n]] += 1
-    mean = total / size[:, None].astype(np.float32)
-    d = np.zeros(N, dtype=np.float32)
-    for f in range(F):
-        t = A[:, f] - mean[gid, f]
-        d = d + t * t
+    A = np.asarray(abar, dtype=np.float64)
+    gid = np.asarray(gid)
+    d = np.zeros(A.shape[0], dtype=np.float64)
+    for g in range(G):
+        members = np.nonzero(gid == g)[0]
+        mean = A[members].sum(axis=0) / float(len(members))
+        d[members] = ((A[members] - mean) ** 2).sum(axis=1)
     return d
 
 

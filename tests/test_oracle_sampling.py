@@ -196,13 +196,54 @@ def test_representative_ties_go_to_the_lower_index_and_scaling_is_irrelevant():
         assert np.array_equal(sampling.representative_sample(h, (A.astype(np.float32) * np.float32(2.0 ** p)), 2, 1, 1)[1], base)
 
 
-def test_distances_match_float64_within_single_precision():
-    rng = np.random.default_rng(24)
-    h, A = spectra(rng, 150, 25, 12)
+def test_distances_hand_computed_example():
+    """Two groups; every number below is worked out by hand from the definition."""
+    h = np.array([5, 9, 5, 5, 9], dtype=np.uint64)
+    A = np.array([[1.0, 2.0], [10.0, 0.0], [3.0, 2.0], [2.0, 5.0], [10.0, 4.0]])
     gid, G = sampling.group_ids(h)
-    d32 = sampling.spectrum_distances(A, gid, G)
-    for n in range(150):
-        members = np.nonzero(gid == gid[n])[0]
-        want = ((A[n] - A[members].mean(axis=0)) ** 2).sum()
-        assert abs(float(d32[n]) - want) <= 1e-5 * max(want, 1.0)
+    # group of hash 5 = variates 0, 2, 3: mean (2, 3); distances 1 + 1, 1 + 1, 0 + 4
+    # group of hash 9 = variates 1, 4: mean (10, 2); distances 4, 4
+    assert sampling.spectrum_distances(A, gid, G).tolist() == [2.0, 4.0, 2.0, 4.0, 4.0]
+    assert sampling.representative_sample(h, A, 1, 1, 1)[1].tolist() == [0, 1]        # ties: the lower index
+    assert sampling.representative_sample(h, A, 2, 1, 1)[1].tolist() == [0, 1, 2, 4]
 
+
+def test_distances_brute_force_and_variance_identity():
+    """Pure-Python loops over a small input, and sum_{n in g} d[n] = sum_f (sum_n a^2 - |g| mean_f^2)."""
+    rng = np.random.default_rng(24)
+    h, A = spectra(rng, 60, 7, 6)
+    gid, G = sampling.group_ids(h)
+    d = sampling.spectrum_distances(A, gid, G)
+    for n in range(60):
+        members = [m for m in range(60) if gid[m] == gid[n]]
+        want = 0.0
+        for f in range(7):
+            mean = sum(float(A[m, f]) for m in members) / len(members)
+            want += (float(A[n, f]) - mean) ** 2
+        assert abs(d[n] - want) <= 1e-12 * max(want, 1.0)
+    for g in range(G):
+        members = np.nonzero(gid == g)[0]
+        total = sum(float(A[m, f]) ** 2 for m in members for f in range(7))
+        total -= len(members) * sum((sum(float(A[m, f]) for m in members) / len(members)) ** 2 for f in range(7))
+        assert abs(d[members].sum() - total) <= 1e-10 * max(total, 1.0)
+
+
+def test_distances_invariances_and_special_cases():
+    rng = np.random.default_rng(25)
+    h, A = spectra(rng, 80, 5, 9)
+    gid, G = sampling.group_ids(h)
+    d = sampling.spectrum_distances(A, gid, G)
+    # a shift common to all members of a group moves its mean along: distances unchanged
+    shift = rng.uniform(1.0, 2.0, (G, 5))
+    assert np.allclose(sampling.spectrum_distances(A + shift[gid], gid, G), d, rtol=1e-9, atol=1e-12)
+    # a permutation of the variates permutes the distances
+    perm = rng.permutation(80)
+    gid_p, _ = sampling.group_ids(h[perm])
+    assert np.allclose(sampling.spectrum_distances(A[perm], gid_p, G), d[perm], rtol=1e-12, atol=0)
+    # a group of one, and a group of identical members, sit on their mean
+    h1 = np.array([3, 4, 4, 4], dtype=np.uint64)
+    A1 = np.array([[1.5, 2.5], [0.25, 0.75], [0.25, 0.75], [0.25, 0.75]])
+    assert sampling.spectrum_distances(A1, *sampling.group_ids(h1)).tolist() == [0.0, 0.0, 0.0, 0.0]
+    # float32 inputs are taken exactly: the same values as float64 give the same distances
+    A32 = A.astype(np.float32)
+    assert np.array_equal(sampling.spectrum_distances(A32, gid, G), sampling.spectrum_distances(A32.astype(np.float64), gid, G))
