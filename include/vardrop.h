@@ -18,8 +18,20 @@
  *     device memory only inside vardrop_create.
  *   - Return value: VARDROP_OK (0) or a negative error code.  On an argument error
  *     nothing is enqueued and no output is touched.  Nothing throws, nothing aborts.
- *   - A context serves one device; calls that share a context must not overlap in time
- *     on different streams (the context caches a twiddle table).
+ *   - A context serves one device and one host thread at a time.  Work enqueued through one context on
+ *     different streams may overlap on the device, with one exception: the context keeps ONE cosine / sine
+ *     table for vardrop_hash, rebuilt (on the call's stream) whenever L, f_min or f_max differ from the
+ *     previous vardrop_hash call, so two vardrop_hash calls with different (L, f_min, f_max) must be ordered
+ *     by their streams (same stream, or an event between them); give each stream a context of its own to
+ *     lift that.  The timing hook below is host-side state of the context.
+ *   - Device-side token count.  The number of kept tokens N' is a result of vardrop_sample and lives in
+ *     device memory (counts[0]).  The entry points whose names end in _dev take a pointer to it instead of
+ *     a host integer, plus an upper bound n_max that sizes buffers and launches: nothing has to cross to the
+ *     host between sampling and attention, and since no launch parameter depends on N' a whole step can be
+ *     recorded once (a HIP graph) and replayed.  Rows are packed for the actual count, [B][N'][d], exactly
+ *     as the host-count entry points lay them out, in buffers sized for n_max.  If the device value is
+ *     outside [0, n_max] the call's kernels do nothing, and *status (device int32, optional) is set to 1;
+ *     the library never clears it.
  */
 #ifndef VARDROP_H
 #define VARDROP_H
@@ -43,7 +55,7 @@ enum {
 
 enum { VARDROP_F32 = 0, VARDROP_BF16 = 1 };   /* element type of tokens / weights */
 
-/* Creates a context on HIP device `device_id` (allocates a 64 KiB twiddle table there).
+/* Creates a context on HIP device `device_id` (allocates a 2 MiB cosine / sine table there).
  * Synchronous. */
 int vardrop_create(vardrop_ctx** out, int device_id);
 void vardrop_destroy(vardrop_ctx* ctx);
@@ -108,6 +120,9 @@ const char* vardrop_kernel_name(int kernel_id);
  *   topk   int32 [N][k]   bin indices, rank 1 first
  *   hash   uint64 [N]
  *   abar   fp32 [N][f_max-f_min+1] mean amplitudes, or NULL
+ * f_max < 0 selects the paper's default cut-off, vardrop_hash_default_cutoff(L) = ceil((floor(L/2)+1)/2)
+ * ("half of the number of positive frequencies", 25 at T = 96, App. E); f_min < 0 selects 1 (the mean, bin 0,
+ * is not a candidate: App. G prints the hash of a flat variate as 1-2-3).
  * Requires 1 <= k <= f_max-f_min+1, 0 <= f_min <= f_max <= floor(L/2), R^k < 2^63,
  * 2 <= L <= 1024, at most 512 candidate bins, and operand buffers that fit the 160 KiB LDS:
  * 2048 P + 1024 + 4 V (f_max-f_min+1) bytes with P = 2 ceil(ceil(L/2) / 16) + 1, or
@@ -122,6 +137,7 @@ const char* vardrop_kernel_name(int kernel_id);
  */
 size_t vardrop_hash_workspace_bytes(int B, int N, int L, int k, int f_min, int f_max);   /* st = 1: none */
 size_t vardrop_hash_strided_workspace_bytes(int B, int N, int L);                          /* st != 1 */
+int vardrop_hash_default_cutoff(int L);                                                    /* 0 when L < 2 */
 int vardrop_hash(vardrop_ctx* ctx, const float* x, int B, int N, int L,
                  int64_t sb, int64_t sn, int64_t st, int k, int f_min, int f_max,
                  int32_t* topk, uint64_t* hash, float* abar,
@@ -152,6 +168,17 @@ int vardrop_sample(vardrop_ctx* ctx, const uint64_t* hash, int N,
                    uint64_t seed, uint64_t step,
                    int32_t* group_id, int32_t* sel, int32_t* counts, int32_t* counts_host,
                    void* ws, size_t ws_bytes, void* stream);
+
+/* vardrop_sample with the Philox step counter in device memory: the kernel reads *step_dev (8-byte aligned
+ * device uint64) where vardrop_sample takes `step`, and with advance != 0 stores *step_dev + 1 back once the
+ * draw is done, so that a recorded launch draws a new selection at every replay (Sec. 3.3: a fresh random
+ * sample per training step).  No host copy of the counts: they stay in `counts`.  Calls that share a step_dev
+ * must be ordered by their streams. */
+int vardrop_sample_dev(vardrop_ctx* ctx, const uint64_t* hash, int N,
+                       uint32_t gs, uint32_t ratio_num, uint32_t ratio_den,
+                       uint64_t seed, uint64_t* step_dev, int advance,
+                       int32_t* group_id, int32_t* sel, int32_t* counts,
+                       void* ws, size_t ws_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------
  * Deterministic representatives -- Sec. 3.3 leaves the sampling method open ("not limited to any
@@ -189,6 +216,15 @@ int vardrop_gather(vardrop_ctx* ctx, const void* tokens, int B, int N, int d, in
                    const int32_t* sel, int n_sel, void* out, void* stream);
 int vardrop_scatter(vardrop_ctx* ctx, const void* dxs, int B, int N, int d, int dtype,
                     const int32_t* sel, int n_sel, void* dtokens, void* stream);
+
+/* The same with a device-side token count (see the general rules): n_sel_dev points to N' (device int32),
+ * n_sel_max <= N bounds it; out is [B][N'][d] packed, in a buffer of at least B * n_sel_max * d elements. */
+int vardrop_gather_dev(vardrop_ctx* ctx, const void* tokens, int B, int N, int d, int dtype,
+                       const int32_t* sel, const int32_t* n_sel_dev, int n_sel_max, int32_t* status,
+                       void* out, void* stream);
+int vardrop_scatter_dev(vardrop_ctx* ctx, const void* dxs, int B, int N, int d, int dtype,
+                        const int32_t* sel, const int32_t* n_sel_dev, int n_sel_max, int32_t* status,
+                        void* dtokens, void* stream);
 
 /* ---------------------------------------------------------------------------------
  * Token embedding of the kept variates only -- Sec. 3.1 / 3.3: the reduction works directly from the raw
@@ -241,7 +277,6 @@ int vardrop_embed_bwd(vardrop_ctx* ctx, const void* dxs, int B, int n_sel, int L
  * log-sum-exp; it does not store them.  VARDROP_BF16 also requires B*n*d < 2^31
  * (EUNSUPPORTED otherwise).  Sizes returned for n tokens also serve any call with fewer
  * tokens (same B, d, H), so buffers can be sized once for the largest selection.
- * Calls that share a context must not overlap in time on different streams.
  */
 size_t vardrop_attn_saved_bytes(int B, int n, int d, int H, int dtype);
 size_t vardrop_attn_workspace_bytes(int B, int n, int d, int H, int dtype);
@@ -267,6 +302,28 @@ int vardrop_attn_bwd(vardrop_ctx* ctx, const void* dy, const void* xs,
                      void* dxs, float* dWq, float* dWk, float* dWv, float* dWo,
                      float* dbq, float* dbk, float* dbv, float* dbo,
                      void* ws, size_t ws_bytes, void* stream);
+
+/* vardrop_gather_attn_fwd and vardrop_attn_bwd with a device-side token count (see the general rules; Eq. 2:
+ * the selection S, and with it N' = |S|, is data of the step, not a host quantity).  n_dev points to N',
+ * 1 <= n_max <= N bounds it.  xs, y, dy, dxs are [B][N'][d] packed in buffers of at least B * n_max * d
+ * elements; `saved` and `ws` are sized by vardrop_attn_saved_bytes / vardrop_attn_workspace_bytes for n_max, and
+ * the backward call must be given the same n_max as the forward call that wrote `saved`.  The kernels are chosen
+ * for n_max (VARDROP_BF16: the single-kernel path of short selections when n_max <= 128), results are those of
+ * the host-count entry points called with N'.  N' == 0 leaves y, xs, dxs untouched and zero-fills the weight
+ * gradients.  *status as in the general rules (forward and backward may share one). */
+int vardrop_gather_attn_fwd_dev(vardrop_ctx* ctx, const void* tokens, int B, int N, const int32_t* sel,
+                                const int32_t* n_dev, int n_max, int32_t* status,
+                                int d, int H, int dtype,
+                                const void* Wq, const void* Wk, const void* Wv, const void* Wo,
+                                const void* bq, const void* bk, const void* bv, const void* bo,
+                                void* xs, void* y, void* saved, void* ws, size_t ws_bytes, void* stream);
+int vardrop_attn_bwd_dev(vardrop_ctx* ctx, const void* dy, const void* xs,
+                         int B, const int32_t* n_dev, int n_max, int32_t* status, int d, int H, int dtype,
+                         const void* Wq, const void* Wk, const void* Wv, const void* Wo,
+                         const void* saved,
+                         void* dxs, float* dWq, float* dWk, float* dWv, float* dWo,
+                         float* dbq, float* dbk, float* dbv, float* dbo,
+                         void* ws, size_t ws_bytes, void* stream);
 
 #ifdef __cplusplus
 }

@@ -6,4 +6,5 @@ from .binding import (  # noqa: F401
     vardrop_attn_bwd, vardrop_attn_fwd, vardrop_embed_bwd, vardrop_embed_fwd, vardrop_gather, vardrop_gather_attn_fwd,
     vardrop_hash, vardrop_kernel_name,
     vardrop_profile_read, vardrop_profile_select, vardrop_profile_stride, vardrop_sample, vardrop_sample_nearest, vardrop_scatter,
+    vardrop_attn_bwd_dev, vardrop_gather_attn_fwd_dev, vardrop_gather_dev, vardrop_sample_dev, vardrop_scatter_dev,
 )

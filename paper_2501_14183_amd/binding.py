@@ -27,6 +27,7 @@ _SIGNATURES = {
     "vardrop_strerror": (ctypes.c_char_p, [_c_int]),
     "vardrop_last_hip_error": (_c_int, [_ptr]),
     "vardrop_hash_strided_workspace_bytes": (ctypes.c_size_t, [_c_int, _c_int, _c_int]),
+    "vardrop_hash_default_cutoff": (_c_int, [_c_int]),
     "vardrop_profile_select": (_c_int, [_ptr, _c_int]),
     "vardrop_profile_read": (_c_int, [_ptr, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(_c_int)]),
     "vardrop_profile_stride": (_c_int, [_ptr, _c_int]),
@@ -37,11 +38,15 @@ _SIGNATURES = {
     "vardrop_sample_workspace_bytes": (_c_size, [_c_int]),
     "vardrop_sample": (_c_int, [_ptr, _ptr, _c_int, _c_u32, _c_u32, _c_u32, _c_u64, _c_u64,
                                 _ptr, _ptr, _ptr, _ptr, _ptr, _c_size, _ptr]),
+    "vardrop_sample_dev": (_c_int, [_ptr, _ptr, _c_int, _c_u32, _c_u32, _c_u32, _c_u64, _ptr, _c_int,
+                                    _ptr, _ptr, _ptr, _ptr, _c_size, _ptr]),
     "vardrop_sample_nearest_workspace_bytes": (_c_size, [_c_int, _c_int]),
     "vardrop_sample_nearest": (_c_int, [_ptr, _ptr, _ptr, _c_int, _c_int, _c_u32, _c_u32, _c_u32,
                                         _ptr, _ptr, _ptr, _ptr, _ptr, _c_size, _ptr]),
     "vardrop_gather": (_c_int, [_ptr, _ptr, _c_int, _c_int, _c_int, _c_int, _ptr, _c_int, _ptr, _ptr]),
     "vardrop_scatter": (_c_int, [_ptr, _ptr, _c_int, _c_int, _c_int, _c_int, _ptr, _c_int, _ptr, _ptr]),
+    "vardrop_gather_dev": (_c_int, [_ptr, _ptr, _c_int, _c_int, _c_int, _c_int, _ptr, _ptr, _c_int, _ptr, _ptr, _ptr]),
+    "vardrop_scatter_dev": (_c_int, [_ptr, _ptr, _c_int, _c_int, _c_int, _c_int, _ptr, _ptr, _c_int, _ptr, _ptr, _ptr]),
     "vardrop_embed_saved_bytes": (_c_size, [_c_int] * 4),
     "vardrop_embed_workspace_bytes": (_c_size, [_c_int] * 5),
     "vardrop_embed_fwd": (_c_int, [_ptr, _ptr, _c_int, _c_int, _c_int, _c_i64, _c_i64, _ptr, _c_int, _c_int,
@@ -56,6 +61,10 @@ _SIGNATURES = {
                                 [_ptr, _ptr, _ptr, _ptr, _c_size, _ptr]),
     "vardrop_attn_bwd": (_c_int, [_ptr, _ptr, _ptr, _c_int, _c_int, _c_int, _c_int, _c_int] + [_ptr] * 4 +
                          [_ptr] + [_ptr] * 9 + [_ptr, _c_size, _ptr]),
+    "vardrop_gather_attn_fwd_dev": (_c_int, [_ptr, _ptr, _c_int, _c_int, _ptr, _ptr, _c_int, _ptr, _c_int, _c_int, _c_int] +
+                                    [_ptr] * 8 + [_ptr, _ptr, _ptr, _ptr, _c_size, _ptr]),
+    "vardrop_attn_bwd_dev": (_c_int, [_ptr, _ptr, _ptr, _c_int, _ptr, _c_int, _ptr, _c_int, _c_int, _c_int] + [_ptr] * 4 +
+                             [_ptr] + [_ptr] * 9 + [_ptr, _c_size, _ptr]),
 }
 
 
@@ -97,6 +106,15 @@ def _p(t):
 def _stream(t, stream=None):
     """Raw hipStream_t: `stream` (an integer handle, e.g. torch.cuda.Stream.cuda_stream) or torch's current one."""
     return torch.cuda.current_stream(t.device).cuda_stream if stream is None else stream
+
+
+def _own_buffers(stream, what, **bufs):
+    """Temporaries come from torch's allocator, which hands freed memory to work on torch's current stream: with a
+    raw `stream` handle the caller has to own every buffer the call uses."""
+    if stream is not None:
+        missing = [k for k, v in bufs.items() if v is None]
+        if missing:
+            raise TypeError("%s on a raw stream needs caller-owned %s" % (what, ", ".join(missing)))
 
 
 def _dtype_code(t):
@@ -170,7 +188,7 @@ def vardrop_hash(ctx, x, k, f_min=1, f_max=None, want_abar=False, out=None, stre
         raise TypeError("x must be float32 [B, N, L]")
     B, N, L = x.shape
     if f_max is None:
-        f_max = (L // 2 + 2) // 2
+        f_max = ctx._lib.vardrop_hash_default_cutoff(L)      # the paper's default cut-off (the library's rule)
     if out is not None:
         topk, hsh = out
     else:
@@ -178,6 +196,8 @@ def vardrop_hash(ctx, x, k, f_min=1, f_max=None, want_abar=False, out=None, stre
         hsh = torch.empty((N,), dtype=torch.int64, device=x.device)
     abar = torch.empty((N, f_max - f_min + 1), dtype=torch.float32, device=x.device) if want_abar else None
     sb, sn, st = x.stride()
+    if st != 1:
+        _own_buffers(stream, "vardrop_hash of a strided batch", ws=ws)
     if st != 1 and ws is None:
         ws = torch.empty(ctx._lib.vardrop_hash_strided_workspace_bytes(B, N, L), dtype=torch.uint8, device=x.device)
     rc = ctx._lib.vardrop_hash(ctx.handle, _p(x), B, N, L, sb, sn, st, k, f_min, f_max,
@@ -268,6 +288,7 @@ def vardrop_attn_bwd(ctx, dy, xs, Wq, Wk, Wv, Wo, H, saved, bias_grads=False, ws
     B, n, d = xs.shape
     code = _dtype_code(xs)
     nbytes = ctx._lib.vardrop_attn_workspace_bytes(B, n, d, H, code)
+    _own_buffers(stream, "vardrop_attn_bwd", ws=ws, out=out)
     if ws is None or ws.numel() < nbytes:
         ws = torch.empty((max(nbytes, 256),), dtype=torch.uint8, device=xs.device)
     if out is not None:
@@ -306,6 +327,7 @@ def vardrop_embed_bwd(ctx, dxs, L, saved, want_bias=True, ws=None, out=None, str
     `out`, when given, is that pair of preallocated tensors."""
     B, n_sel, d = dxs.shape
     dt = _dtype_code(dxs)
+    _own_buffers(stream, "vardrop_embed_bwd", ws=ws, out=out)
     if ws is None:
         ws = torch.empty(max(ctx._lib.vardrop_embed_workspace_bytes(B, n_sel, L, d, dt), 256), dtype=torch.uint8,
                          device=dxs.device)
@@ -325,6 +347,8 @@ def vardrop_sample_nearest(ctx, hsh, abar, gs, ratio_num, ratio_den, stream=None
     every group keeps the members closest to its mean spectrum."""
     N, F = abar.shape
     dev = hsh.device
+    if stream is not None:
+        raise TypeError("vardrop_sample_nearest allocates its workspace: call it on torch's current stream")
     gid = torch.empty((N,), dtype=torch.int32, device=dev)
     sel = torch.empty((N,), dtype=torch.int32, device=dev)
     counts = torch.empty((2,), dtype=torch.int32, device=dev)
@@ -334,3 +358,59 @@ def vardrop_sample_nearest(ctx, hsh, abar, gs, ratio_num, ratio_den, stream=None
     ctx.check(rc, "vardrop_sample_nearest")
     return gid, sel, counts
 
+
+
+# ---------------------------------------------------------------- device-side token count
+def vardrop_sample_dev(ctx, hsh, gs, ratio_num, ratio_den, seed, step_dev, advance, out, stream=None):
+    """vardrop_sample with the step counter in device memory (step_dev: int64 [1]); out = (group_id, sel, counts)."""
+    N = hsh.shape[0]
+    gid, sel, counts = out
+    rc = ctx._lib.vardrop_sample_dev(ctx.handle, _p(hsh), N, gs, ratio_num, ratio_den, seed, _p(step_dev), 1 if advance else 0,
+                                     _p(gid), _p(sel), _p(counts), None, 0, _stream(hsh, stream))
+    ctx.check(rc, "vardrop_sample_dev")
+    return gid, sel, counts
+
+
+def vardrop_gather_dev(ctx, tokens, sel, n_dev, n_max, out, status=None, stream=None):
+    """tokens [B, N, d], sel int32, n_dev int32 [1] on the device -> out (>= B * n_max * d elements), packed [B, N', d]."""
+    B, N, d = tokens.shape
+    rc = ctx._lib.vardrop_gather_dev(ctx.handle, _p(tokens), B, N, d, _dtype_code(tokens), _p(sel), _p(n_dev), n_max,
+                                     _p(status), _p(out), _stream(tokens, stream))
+    ctx.check(rc, "vardrop_gather_dev")
+    return out
+
+
+def vardrop_scatter_dev(ctx, dxs, sel, n_dev, n_max, out, status=None, stream=None):
+    """dxs packed [B, N', d] -> out [B, N, d] with zeros at dropped variates; N' read from n_dev on the device."""
+    B, N, d = out.shape
+    rc = ctx._lib.vardrop_scatter_dev(ctx.handle, _p(dxs), B, N, d, _dtype_code(out), _p(sel), _p(n_dev), n_max,
+                                      _p(status), _p(out), _stream(out, stream))
+    ctx.check(rc, "vardrop_scatter_dev")
+    return out
+
+
+def vardrop_gather_attn_fwd_dev(ctx, tokens, sel, n_dev, n_max, Wq, Wk, Wv, Wo, H, xs, y, saved,
+                                bq=None, bk=None, bv=None, bo=None, status=None, stream=None):
+    """Gather + attention forward with N' read on the device from n_dev (int32 [1]); xs, y hold >= B * n_max * d
+    elements and receive [B, N', d] packed; saved holds vardrop_attn_saved_bytes(B, n_max, d, H) bytes."""
+    B, N, d = tokens.shape
+    rc = ctx._lib.vardrop_gather_attn_fwd_dev(ctx.handle, _p(tokens), B, N, _p(sel), _p(n_dev), n_max, _p(status), d, H,
+                                              _dtype_code(tokens), _p(Wq), _p(Wk), _p(Wv), _p(Wo),
+                                              _p(bq), _p(bk), _p(bv), _p(bo), _p(xs), _p(y), _p(saved), None, 0,
+                                              _stream(tokens, stream))
+    ctx.check(rc, "vardrop_gather_attn_fwd_dev")
+    return xs, y, saved
+
+
+def vardrop_attn_bwd_dev(ctx, dy, xs, n_dev, n_max, Wq, Wk, Wv, Wo, H, saved, ws, out, status=None, stream=None):
+    """Attention backward with N' read on the device; out = (dxs, dWq, dWk, dWv, dWo[, dbq, dbk, dbv, dbo]);
+    B is taken from the weights' caller: dy, xs, dxs are flat or [B, n_max, d] buffers, so B = out[0].shape[0]."""
+    B = out[0].shape[0]
+    d = Wq.shape[0]
+    dxs, dW = out[0], list(out[1:5])
+    db = list(out[5:9]) if len(out) >= 9 else [None] * 4
+    rc = ctx._lib.vardrop_attn_bwd_dev(ctx.handle, _p(dy), _p(xs), B, _p(n_dev), n_max, _p(status), d, H, _dtype_code(Wq),
+                                       _p(Wq), _p(Wk), _p(Wv), _p(Wo), _p(saved), _p(dxs), *[_p(t) for t in dW],
+                                       *[_p(t) for t in db], _p(ws), ws.numel(), _stream(Wq, stream))
+    ctx.check(rc, "vardrop_attn_bwd_dev")
+    return out

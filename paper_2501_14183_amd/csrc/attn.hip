@@ -130,3 +130,68 @@ extern "C" int vardrop_attn_bwd(vardrop_ctx* ctx, const void* dy, const void* xs
                            (float*)dxs, dW, db, ws, s);
   return vd_attn_bwd_bf16(ctx, dy, xs, B, n, d, H, W, saved, dxs, dW, db, ws, s);
 }
+
+// ---------------------------------------------------------------- device-side token count
+// The same two steps with the number of kept tokens read by the kernels from device memory (it is a result of the
+// sampling step): nothing crosses to the host between sampling and attention, and the launches do not depend on the
+// count, so a whole step can be recorded once and replayed.
+extern "C" int vardrop_gather_attn_fwd_dev(vardrop_ctx* ctx, const void* tokens, int B, int N, const int32_t* sel,
+                                           const int32_t* n_dev, int n_max, int32_t* status,
+                                           int d, int H, int dtype,
+                                           const void* Wq, const void* Wk, const void* Wv, const void* Wo,
+                                           const void* bq, const void* bk, const void* bv, const void* bo,
+                                           void* xs, void* y, void* saved, void* ws, size_t ws_bytes, void* stream) {
+  (void)ws_bytes;
+  if (!ctx || !n_dev) return VARDROP_EINVAL;
+  if (N < 0 || n_max < 1 || n_max > N) return VARDROP_EINVAL;
+  int rc = check_shape(B, n_max, d, H, dtype);
+  if (rc) return rc;
+  if (B == 0) return VARDROP_OK;
+  if (!tokens || !sel || !xs || !vd_aligned(tokens, 16) || !vd_aligned(xs, 16)) return VARDROP_EINVAL;
+  if (dtype == VARDROP_BF16 && (long long)B * N * d >= (1ll << 31)) return VARDROP_EUNSUPPORTED;
+  if (!Wq || !Wk || !Wv || !Wo || !y || !saved) return VARDROP_EINVAL;
+  if (!vd_aligned(saved, 256)) return VARDROP_EWORKSPACE;
+  if (!vd_aligned(y, 16) || !vd_aligned(Wq, 16) || !vd_aligned(Wk, 16) || !vd_aligned(Wv, 16) || !vd_aligned(Wo, 16))
+    return VARDROP_EINVAL;
+  const void* W[4] = {Wq, Wk, Wv, Wo};
+  const void* bias[4] = {bq, bk, bv, bo};
+  hipStream_t s = (hipStream_t)stream;
+  const VdDevCount dn = {n_dev, status};
+  if (dtype == VARDROP_F32) {
+    rc = vd_gather(ctx, tokens, B, N, d, dtype, sel, n_max, xs, s, dn);
+    if (rc) return rc;
+    return vd_attn_fwd_f32(ctx, (const float*)xs, B, n_max, d, H, (const float* const*)W, (const float* const*)bias,
+                           (float*)y, saved, ws, s, VdDevCount{n_dev, nullptr});
+  }
+  return vd_attn_fwd_bf16(ctx, tokens, B, n_max, d, H, W, bias, y, saved, ws, s, sel, N, xs, dn);
+}
+
+extern "C" int vardrop_attn_bwd_dev(vardrop_ctx* ctx, const void* dy, const void* xs,
+                                    int B, const int32_t* n_dev, int n_max, int32_t* status, int d, int H, int dtype,
+                                    const void* Wq, const void* Wk, const void* Wv, const void* Wo,
+                                    const void* saved,
+                                    void* dxs, float* dWq, float* dWk, float* dWv, float* dWo,
+                                    float* dbq, float* dbk, float* dbv, float* dbo,
+                                    void* ws, size_t ws_bytes, void* stream) {
+  if (!ctx || !n_dev || n_max < 1) return VARDROP_EINVAL;
+  int rc = check_shape(B, n_max, d, H, dtype);
+  if (rc) return rc;
+  if (B < 1) return VARDROP_EINVAL;
+  if (!dWq || !dWk || !dWv || !dWo) return VARDROP_EINVAL;
+  if (!dy || !xs || !Wq || !Wk || !Wv || !Wo || !saved || !dxs) return VARDROP_EINVAL;
+  if (!ws || !vd_aligned(ws, 256) || ws_bytes < vardrop_attn_workspace_bytes(B, n_max, d, H, dtype))
+    return VARDROP_EWORKSPACE;
+  if (!vd_aligned(saved, 256)) return VARDROP_EWORKSPACE;
+  if (!vd_aligned(xs, 16) || !vd_aligned(dy, 16) || !vd_aligned(dxs, 16) || !vd_aligned(Wq, 16) ||
+      !vd_aligned(Wk, 16) || !vd_aligned(Wv, 16) || !vd_aligned(Wo, 16))
+    return VARDROP_EINVAL;
+  hipStream_t s = (hipStream_t)stream;
+  float* dW[4] = {dWq, dWk, dWv, dWo};
+  float* db[4] = {dbq, dbk, dbv, dbo};
+  const void* W[4] = {Wq, Wk, Wv, Wo};
+  const VdDevCount dn = {n_dev, status};
+  if (dtype == VARDROP_F32)
+    return vd_attn_bwd_f32(ctx, (const float*)dy, (const float*)xs, B, n_max, d, H, (const float* const*)W, saved,
+                           (float*)dxs, dW, db, ws, s, dn);
+  return vd_attn_bwd_bf16(ctx, dy, xs, B, n_max, d, H, W, saved, dxs, dW, db, ws, s, dn);
+}

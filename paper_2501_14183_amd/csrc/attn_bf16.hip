@@ -46,6 +46,9 @@ struct SdpaArgs {
   float* nlse2;                   // long selections: -log2(e) * lse, for the dK/dV part
   int n, d, H;
   float scale;
+  const int32_t* n_dev;           // device-side token count (then n is its bound, see vd_count)
+  int32_t* status;
+  int B;
 };
 
 // ---- kernels for long selections (n > 128): staging ring.  A stage holds two [64 tokens][64] bf16 tiles of a
@@ -100,13 +103,21 @@ __device__ inline RingAddr ring_addr(const unsigned char* smem, int lane) {
   }
   return r;
 }
-// the workgroup's place in an order in which each die works through whole (batch, head) pairs
-__device__ inline void ring_block(int H, int& xb, int& h, int& b) {
-  const int gx = gridDim.x;
-  const int t = xcd_contiguous(blockIdx.x + gx * (blockIdx.y + gridDim.y * blockIdx.z), gx * gridDim.y * gridDim.z);
+// The workgroup's place in an order in which each die works through whole (batch, head) pairs: gx workgroups per
+// pair, one-dimensional grid.  Resolves a device-side token count first (a.n becomes the count).  False: this
+// workgroup has nothing to do (surplus of a grid sized for the count's bound, or an invalid count).
+__device__ inline bool ring_block(SdpaArgs& a, int rows, int parts, int& xb, int& h, int& b) {
+  int n;
+  if (!vd_count(a.n_dev, a.n, n, a.status)) return false;
+  a.n = n;
+  const int gx = parts * ((n + rows - 1) / rows);
+  const int total = gx * a.H * a.B;
+  if ((int)blockIdx.x >= total) return false;
+  const int t = xcd_contiguous(blockIdx.x, total);
   xb = t % gx;
-  h = (t / gx) % H;
-  b = t / (gx * H);
+  h = (t / gx) % a.H;
+  b = t / (gx * a.H);
+  return true;
 }
 
 // four row-major fragments (k steps 0..3) of sub-tile KT of tile TILE
@@ -137,7 +148,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int col = lane & 31, half = lane >> 5;
   int qb, h, b;
-  ring_block(a.H, qb, h, b);
+  if (!ring_block(a, NW * 32 * QG, 1, qb, h, b)) return;
   const int n = a.n;
   const long long ld = a.d;
   const long long base = (long long)b * n * ld + h * kDh;
@@ -505,13 +516,13 @@ __device__ __forceinline__ void sdpa_bwd_dkv_body(const SdpaArgs& a, int kb, int
 template <int NW>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) void sdpa_bwd_dq_bf16(SdpaArgs a) {
   int xb, h, b;
-  ring_block(a.H, xb, h, b);
+  if (!ring_block(a, NW * 32, 1, xb, h, b)) return;
   sdpa_bwd_dq_body<NW, 1, true>(a, xb, h, b);
 }
 template <int NW>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) void sdpa_bwd_dkv_bf16(SdpaArgs a) {
   int xb, h, b;
-  ring_block(a.H, xb, h, b);
+  if (!ring_block(a, NW * 32, 1, xb, h, b)) return;
   sdpa_bwd_dkv_body<NW>(a, xb, h, b);
 }
 // Few workgroups: one launch, so that the two parts fill the chip's places together.  Of the workgroups of a
@@ -520,8 +531,8 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
 template <int NW>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) void sdpa_bwd_dqkv_bf16(SdpaArgs a) {
   int xb, h, b;
-  ring_block(a.H, xb, h, b);
-  const int nblk = (int)gridDim.x >> 1;
+  if (!ring_block(a, NW * 32, 2, xb, h, b)) return;
+  const int nblk = (a.n + NW * 32 - 1) / (NW * 32);
   if (xb < nblk) sdpa_bwd_dq_body<NW, 1, false>(a, xb, h, b);
   else sdpa_bwd_dkv_body<NW>(a, xb - nblk, h, b);
 }
@@ -585,7 +596,8 @@ __global__ __launch_bounds__(512) void sdpa_bwd_small_bf16(SdpaArgs a) {
   // heads fastest: a die's contiguous range covers whole batches, whose dy rows it then fetches once
   const int tix = xcd_contiguous(blockIdx.x + gridDim.x * blockIdx.y, gridDim.x * gridDim.y);
   const int h = tix % a.H, b = tix / a.H;
-  const int n = a.n;
+  int n;
+  if (!vd_count(a.n_dev, a.n, n, a.status) || n == 0) return;
   const long long ld = a.d;
   const long long base = (long long)b * n * ld + h * kDh;
   const long long srow = ((long long)b * a.H + h) * n;
@@ -858,6 +870,8 @@ struct FusedFwdArgs {
   float* lse;
   int n, d, H;
   float scale;
+  const int32_t* n_dev;           // device-side token count (then n is its bound, see vd_count)
+  int32_t* status;
 };
 constexpr int kFusedStage = kSmallN * 64 * 2 + 3 * 64 * 64 * 2;     // xs tile + three weight tiles: 40 KB
 constexpr int kFusedStages = 4;                    // 160 KB: all of a compute unit's LDS (three stages: 1.5 us more per step)
@@ -878,7 +892,9 @@ __global__ __launch_bounds__(512) void attn_fwd_small_bf16(FusedFwdArgs a) {
   // heads fastest: a die's contiguous range covers whole batches, whose tokens it then fetches once
   const int tix = xcd_contiguous(blockIdx.x + gridDim.x * blockIdx.y, gridDim.x * gridDim.y);
   const int h = tix % a.H, b = tix / a.H;
-  const int n = a.n, d = a.d;
+  int n;
+  if (!vd_count(a.n_dev, a.n, n, a.status) || n == 0) return;
+  const int d = a.d;
   const long long ld = d;
   const bf16_t* xs_b = a.xs + (long long)b * (a.sel ? a.N : n) * ld;
   const int total = d / 64;
@@ -889,12 +905,20 @@ __global__ __launch_bounds__(512) void attn_fwd_small_bf16(FusedFwdArgs a) {
   const bf16_t* srcB[3];
   u32x4 kept[2];                  // this thread's 16 bytes of two gathered rows, columns of head h
   int src_row[2];                 // requested here, used after the first weight copies have been issued
+  bool src_ok[2] = {true, true};  // an index outside [0, N) reads row 0 and stands for a zero row, as in the gather kernel
 #pragma unroll
   for (int u = 0; u < 2; ++u) {
     const int row = (u * 8 + wave) * 8 + (lane >> 3);
     src_row[u] = min(row, n - 1);
-    if (a.sel) src_row[u] = a.sel[src_row[u]];
+    if (a.sel) {
+      const int sidx = a.sel[src_row[u]];
+      src_ok[u] = (unsigned)sidx < (unsigned)a.N;
+      src_row[u] = src_ok[u] ? sidx : 0;
+    }
   }
+  // the token this lane owns in the product below (row wr * 32 + col of the tile): is its index valid?
+  bool own_ok = true;
+  if (a.sel) own_ok = (unsigned)a.sel[min((wave & 3) * 32 + (lane & 31), n - 1)] < (unsigned)a.N;
 #pragma unroll
   for (int u = 0; u < 3; ++u) {
     const bf16_t* Wz = u == 0 ? a.Wq : (u == 1 ? a.Wk : a.Wv);
@@ -991,6 +1015,12 @@ __global__ __launch_bounds__(512) void attn_fwd_small_bf16(FusedFwdArgs a) {
   }
 #undef VD_ISSUE
 
+  // a token whose index was out of range is a zero row: its products are exactly zero (the bias is still added)
+  if (!own_ok) {
+    acc[0] = zero16();
+    acc[1] = zero16();
+    acc[2] = zero16();
+  }
   // ---- Q, K, V tiles (bf16, with bias) into LDS: [token][64], 16-byte chunk position XORed with token % 8
   unsigned char* Qs = smem;
   unsigned char* Ks = Qs + kSmallTile;
@@ -1024,7 +1054,8 @@ __global__ __launch_bounds__(512) void attn_fwd_small_bf16(FusedFwdArgs a) {
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
       const int row = (u * 8 + wave) * 8 + (lane >> 3);
-      if (row < n) *reinterpret_cast<u32x4*>(a.xs_out + base + (long long)row * ld + (lane & 7) * 8) = kept[u];
+      if (row < n)
+        *reinterpret_cast<u32x4*>(a.xs_out + base + (long long)row * ld + (lane & 7) * 8) = src_ok[u] ? kept[u] : u32x4{0u, 0u, 0u, 0u};
     }
   }
 #pragma unroll
@@ -1127,11 +1158,18 @@ struct ColSumBf16 {
   float* dst[4];
   long long rows;
   int d;
+  const int32_t* n_dev;           // device-side token count: rows = n_mul * n
+  int n_max, n_mul;
 };
 __global__ __launch_bounds__(256) void colsum_bf16_kernel(ColSumBf16 a) {
   const bf16_t* src = a.src[blockIdx.y];
   float* dst = a.dst[blockIdx.y];
   if (!dst) return;
+  if (a.n_dev) {
+    int n;
+    if (!vd_count(a.n_dev, a.n_max, n)) return;
+    a.rows = (long long)a.n_mul * n;
+  }
   const int c = blockIdx.x * 256 + threadIdx.x;
   if (c >= a.d) return;
   float s = 0.f;
@@ -1142,62 +1180,44 @@ __global__ __launch_bounds__(256) void colsum_bf16_kernel(ColSumBf16 a) {
 // Launches of the kernels for long selections.  A workgroup of four wavefronts takes 128 queries (or keys)
 // when that still gives the chip two workgroups per compute unit, else two wavefronts take 64.  (Two query
 // groups per wavefront, QG = 2, halve the LDS reads per matrix instruction; measured, the kernels are not
-// bound by those: equal at 1936 tokens, slower at 862.)
+// bound by those: equal at 1936 tokens, slower at 862.)  With a device-side count a.n is its bound: the grid
+// and the choices below are made for the bound, and the workgroups the actual count does not need return at once.
 template <typename K>
-int launch_ring(vardrop_ctx* ctx, int kid, K kernel, int rows, const SdpaArgs& a, int B, hipStream_t s) {
+int launch_ring(vardrop_ctx* ctx, int kid, K kernel, int rows, int parts, const SdpaArgs& a, hipStream_t s) {
+  const long long grid = (long long)parts * vd_ceil_div(a.n, rows) * a.H * a.B;
+  if (grid >= (1ll << 31)) return VARDROP_EUNSUPPORTED;
   VdTimer timer(ctx, kid, s);
-  hipLaunchKernelGGL(kernel, dim3(vd_ceil_div(a.n, rows), a.H, B), dim3(rows >= 128 ? 256 : 128), kRingLds, s, a);
+  hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(rows >= 128 ? 256 : 128), kRingLds, s, a);
   VD_LAUNCH_CHECK(ctx);
   return VARDROP_OK;
 }
-bool ring_fills(const SdpaArgs& a, int B, int rows) { return (long long)vd_ceil_div(a.n, rows) * a.H * B >= 512; }
-int launch_sdpa_fwd(vardrop_ctx* ctx, const SdpaArgs& a, int B, hipStream_t s) {
-  if (ring_fills(a, B, 128)) return launch_ring(ctx, VARDROP_K_SDPA_FWD, sdpa_fwd_bf16<4, 1>, 128, a, B, s);
-  return launch_ring(ctx, VARDROP_K_SDPA_FWD, sdpa_fwd_bf16<2, 1>, 64, a, B, s);
+bool ring_fills(const SdpaArgs& a, int rows) { return (long long)vd_ceil_div(a.n, rows) * a.H * a.B >= 512; }
+int launch_sdpa_fwd(vardrop_ctx* ctx, const SdpaArgs& a, hipStream_t s) {
+  if (ring_fills(a, 128)) return launch_ring(ctx, VARDROP_K_SDPA_FWD, sdpa_fwd_bf16<4, 1>, 128, 1, a, s);
+  return launch_ring(ctx, VARDROP_K_SDPA_FWD, sdpa_fwd_bf16<2, 1>, 64, 1, a, s);
 }
 // Fewer than three rounds of the chip's 512 workgroup places per part: both parts in one launch.  Measured per step
 // at B = 32, H = 8: 1.2-1.8 % faster at 173, 205 and 321 tokens, 1.3 % at 422 (1024 workgroups per part), 0.9 % at 543
 // (1280); 1 % slower at 862 (1792) and at 1936 tokens with B = 8, H = 12 (1536), where the single launch gains
 // nothing and the row sums cost the dO GEMM more than they do inside the dQ kernel.
-bool sdpa_bwd_paired(const SdpaArgs& a, int B) {
-  return !ring_fills(a, B, 128) || (long long)vd_ceil_div(a.n, 128) * a.H * B < 1536;   // (64-row blocks: always)
+bool sdpa_bwd_paired(const SdpaArgs& a) {
+  return !ring_fills(a, 128) || (long long)vd_ceil_div(a.n, 128) * a.H * a.B < 1536;   // (64-row blocks: always)
 }
-int launch_sdpa_bwd(vardrop_ctx* ctx, const SdpaArgs& a, int B, hipStream_t s) {
-  if (!sdpa_bwd_paired(a, B)) {
-    const int rc = launch_ring(ctx, VARDROP_K_SDPA_BWD_DQ, sdpa_bwd_dq_bf16<4>, 128, a, B, s);
-    return rc ? rc : launch_ring(ctx, VARDROP_K_SDPA_BWD_DKV, sdpa_bwd_dkv_bf16<4>, 128, a, B, s);
+int launch_sdpa_bwd(vardrop_ctx* ctx, const SdpaArgs& a, hipStream_t s) {
+  if (!sdpa_bwd_paired(a)) {
+    const int rc = launch_ring(ctx, VARDROP_K_SDPA_BWD_DQ, sdpa_bwd_dq_bf16<4>, 128, 1, a, s);
+    return rc ? rc : launch_ring(ctx, VARDROP_K_SDPA_BWD_DKV, sdpa_bwd_dkv_bf16<4>, 128, 1, a, s);
   }
-  VdTimer timer(ctx, VARDROP_K_SDPA_BWD_DQKV, s);
-  if (ring_fills(a, B, 128))
-    hipLaunchKernelGGL(sdpa_bwd_dqkv_bf16<4>, dim3(2 * vd_ceil_div(a.n, 128), a.H, B), dim3(256), kRingLds, s, a);
-  else
-    hipLaunchKernelGGL(sdpa_bwd_dqkv_bf16<2>, dim3(2 * vd_ceil_div(a.n, 64), a.H, B), dim3(128), kRingLds, s, a);
-  VD_LAUNCH_CHECK(ctx);
-  return VARDROP_OK;
+  if (ring_fills(a, 128)) return launch_ring(ctx, VARDROP_K_SDPA_BWD_DQKV, sdpa_bwd_dqkv_bf16<4>, 128, 2, a, s);
+  return launch_ring(ctx, VARDROP_K_SDPA_BWD_DQKV, sdpa_bwd_dqkv_bf16<2>, 64, 2, a, s);
 }
 
 }  // namespace
 
-// Number of K slices of the weight-gradient GEMMs (K = B*n rows, 128 x 128 tiles).  They share a
-// launch with the input gradient, two workgroups per compute unit: enough slices that the two
-// together fill those 512 places when the input gradient leaves room, else enough for the weight
-// gradients alone to do so; slices hold at least 256 rows and are a multiple of the 64-row stage.
-int vd_attn_bf16_splitk(int d, long long M, int* kchunk) {
-  const int tiles = vd_ceil_div(d, 128) * vd_ceil_div(d, 128) * 4;
-  const long long dxs_wgs = (long long)vd_ceil_div((int)M, 64) * vd_ceil_div(d, 128);
-  int s = vd_ceil_div(512, tiles);
-  if (dxs_wgs < 512) {
-    const int fit = (int)((512 - dxs_wgs) / tiles);
-    if (fit >= 1 && fit < s) s = fit;
-  }
-  if (s > 8) s = 8;
-  while (s > 1 && M / s < 256) --s;
-  if (s < 1) s = 1;
-  int chunk = (int)vd_align_up((size_t)vd_ceil_div((int)M, s), 64);
-  if (chunk < 64) chunk = 64;
-  s = M > 0 ? vd_ceil_div((int)M, chunk) : 1;
-  if (kchunk) *kchunk = chunk;
-  return s;
+// largest slice count the rule above gives for any token count
+static int splitk_bound(int d) {
+  const int s = vd_ceil_div(512, vd_ceil_div(d, 128) * vd_ceil_div(d, 128) * 4);
+  return s > 8 ? 8 : s;
 }
 size_t vd_attn_bf16_partial_offset(int B, int n, int d, int H) {
   const size_t M = (size_t)B * n;
@@ -1213,14 +1233,19 @@ size_t vd_attn_bf16_ws_bytes(int B, int n, int d, int H) {
 // With `sel` (device, n ascending rows of [0, N)), `xs` holds the tokens of all N variates and the kept ones are
 // gathered on the way: inside the fused kernel for short selections, by the gather kernel otherwise; either
 // way `xs_out` [B][n][d] receives them.
+// With a device-side count (dn.dev) n is its bound: the five sub-buffers of `saved` start where they would for n
+// tokens, each holds its rows packed for the actual count, and the kernel path (short or long selection) is
+// chosen for the bound.
 int vd_attn_fwd_bf16(vardrop_ctx* ctx, const void* xs, int B, int n, int d, int H,
                      const void* const W[4], const void* const bias[4],
                      void* y, void* saved, void* ws, hipStream_t s,
-                     const int32_t* sel, int N, void* xs_out) {
+                     const int32_t* sel, int N, void* xs_out, VdDevCount dn) {
   (void)ws;
+  bool counted = false;          // has a kernel of this call been given dn.status yet?
   if (sel && n > kSmallN) {
-    const int grc = vardrop_gather(ctx, xs, B, N, d, VARDROP_BF16, sel, n, xs_out, (void*)s);
+    const int grc = vd_gather(ctx, xs, B, N, d, VARDROP_BF16, sel, n, xs_out, s, dn);
     if (grc) return grc;
+    counted = true;
     xs = xs_out;
     sel = nullptr;
   }
@@ -1241,6 +1266,7 @@ int vd_attn_fwd_bf16(vardrop_ctx* ctx, const void* xs, int B, int n, int d, int 
     f.bq = (const bf16_t*)bias[0]; f.bk = (const bf16_t*)bias[1]; f.bv = (const bf16_t*)bias[2];
     f.q = q; f.k = k; f.v = v; f.o = o; f.lse = lse;
     f.n = n; f.d = d; f.H = H; f.scale = 1.0f / sqrtf((float)kDh);
+    f.n_dev = dn.dev; f.status = dn.status;
     static int configured_device = -1;
     if (configured_device != ctx->device) {
       VD_HIP(ctx, hipFuncSetAttribute((const void*)attn_fwd_small_bf16, hipFuncAttributeMaxDynamicSharedMemorySize, kFusedLds));
@@ -1257,25 +1283,29 @@ int vd_attn_fwd_bf16(vardrop_ctx* ctx, const void* xs, int B, int n, int d, int 
     for (int z = 0; z < 3; ++z) g.set(z, xs, W[z], qkv[z], bias[z]);
     g.lda = d; g.ldb = d; g.ldc = d;
     g.M = (int)M; g.N = d; g.K = d; g.nseg = 1;
+    if (dn.dev) g.count_rows(dn.dev, counted ? nullptr : dn.status, n, B);
     rc = vd_gemm_bf16(ctx, VARDROP_K_GEMM_QKV, g, 3, false, s);
     if (rc) return rc;
     SdpaArgs a = {};
     a.q = q; a.k = k; a.v = v; a.out = o; a.lse = lse;
-    a.n = n; a.d = d; a.H = H; a.scale = 1.0f / sqrtf((float)kDh);
-    rc = launch_sdpa_fwd(ctx, a, B, s);
+    a.n = n; a.d = d; a.H = H; a.B = B; a.scale = 1.0f / sqrtf((float)kDh);
+    a.n_dev = dn.dev;
+    rc = launch_sdpa_fwd(ctx, a, s);
     if (rc) return rc;
   }
   GemmBf16 go = {};
   go.set(0, o, W[3], y, bias[3]);
   go.lda = d; go.ldb = d; go.ldc = d;
   go.M = (int)M; go.N = d; go.K = d; go.nseg = 1;
+  if (dn.dev) go.count_rows(dn.dev, nullptr, n, B);
   return vd_gemm_bf16(ctx, VARDROP_K_GEMM_OUT, go, 1, false, s);
 }
 
 // ws: dO, dq, dk, dv ([M][d] bf16 each), D and -log2(e) lse, fp32 [B][H][n] each, then the split-K partial products
+// (with a device-side count: sub-buffers placed for the bound n, rows packed for the actual count, as in the forward)
 int vd_attn_bwd_bf16(vardrop_ctx* ctx, const void* dy, const void* xs, int B, int n, int d, int H,
                      const void* const W[4], const void* saved, void* dxs,
-                     float* const dW[4], float* const db[4], void* ws, hipStream_t s) {
+                     float* const dW[4], float* const db[4], void* ws, hipStream_t s, VdDevCount dn) {
   const long long M = (long long)B * n;
   const bf16_t* q = (const bf16_t*)saved;
   const bf16_t* k = q + M * d;
@@ -1290,8 +1320,9 @@ int vd_attn_bwd_bf16(vardrop_ctx* ctx, const void* dy, const void* xs, int B, in
   float* nlse2 = D + (size_t)B * H * n;
   int rc;
   SdpaArgs a = {};
-  a.n = n; a.d = d; a.H = H;
-  const bool paired = sdpa_bwd_paired(a, B);
+  a.n = n; a.d = d; a.H = H; a.B = B;
+  a.n_dev = dn.dev;
+  const bool paired = sdpa_bwd_paired(a);
   if (n > kSmallN) {  // dO = dy Wo^T (short selections form their dO tiles inside the attention kernel)
     GemmBf16 g = {};
     g.set(0, dy, W[3], dO, nullptr);
@@ -1301,7 +1332,10 @@ int vd_attn_bwd_bf16(vardrop_ctx* ctx, const void* dy, const void* xs, int B, in
       g.rs_o = o; g.rs_out = D; g.rs_n = n; g.rs_H = H;
       g.rs_aux_in = lse; g.rs_aux_out = nlse2; g.rs_aux_mul = -kLog2e;
     }
+    if (dn.dev) g.count_rows(dn.dev, dn.status, n, B);
     if ((rc = vd_gemm_bf16(ctx, VARDROP_K_GEMM_DO, g, 1, true, s))) return rc;
+  } else {
+    a.status = dn.status;
   }
   a.q = q; a.k = k; a.v = v; a.o = o; a.dout = dO; a.lse = const_cast<float*>(lse);
   a.dq = dq; a.dk = dk; a.dv = dv; a.Dsum = D; a.nlse2 = nlse2;
@@ -1319,7 +1353,7 @@ int vd_attn_bwd_bf16(vardrop_ctx* ctx, const void* dy, const void* xs, int B, in
     }
     VD_LAUNCH_CHECK(ctx);
   } else {
-    if ((rc = launch_sdpa_bwd(ctx, a, B, s))) return rc;
+    if ((rc = launch_sdpa_bwd(ctx, a, s))) return rc;
   }
   {
     // dxs = dq Wq^T + dk Wk^T + dv Wv^T
@@ -1338,9 +1372,16 @@ int vd_attn_bwd_bf16(vardrop_ctx* ctx, const void* dy, const void* xs, int B, in
     int kchunk = 0;
     gw.splitk = vd_attn_bf16_splitk(d, M, &kchunk);
     gw.kchunk = kchunk;
-    if (gw.splitk > 1) {
-      float* part = (float*)((char*)ws + vd_attn_bf16_partial_offset(B, n, d, H));
-      gw.C0 = part;
+    float* part = (float*)((char*)ws + vd_attn_bf16_partial_offset(B, n, d, H));
+    gw.part = part;
+    if (dn.dev) {
+      // the kernels derive the slices from the count; the grid is sized for the largest number of them
+      gx.count_rows(dn.dev, nullptr, n, B);
+      gw.count_k(dn.dev, n, B);
+      gw.splitk = splitk_bound(d);
+      if ((rc = vd_gemm_bf16_bwd_pair(ctx, gx, gw, 4, s))) return rc;
+      if ((rc = vd_gemm_bf16_sum_slices(ctx, part, dW, (long long)d * d, gw.splitk, s, 4, &gw))) return rc;
+    } else if (gw.splitk > 1) {
       if ((rc = vd_gemm_bf16_bwd_pair(ctx, gx, gw, 4, s))) return rc;
       if ((rc = vd_gemm_bf16_sum_slices(ctx, part, dW, (long long)d * d, gw.splitk, s))) return rc;
     } else {   // few tokens: one slice, written directly
@@ -1353,9 +1394,9 @@ int vd_attn_bwd_bf16(vardrop_ctx* ctx, const void* dy, const void* xs, int B, in
     c.src[0] = dq; c.src[1] = dk; c.src[2] = dv; c.src[3] = (const bf16_t*)dy;
     for (int z = 0; z < 4; ++z) c.dst[z] = db[z];
     c.rows = M; c.d = d;
+    c.n_dev = dn.dev; c.n_max = n; c.n_mul = B;
     hipLaunchKernelGGL(colsum_bf16_kernel, dim3(vd_ceil_div(d, 256), 4), dim3(256), 0, s, c);
     VD_LAUNCH_CHECK(ctx);
   }
   return VARDROP_OK;
 }
-

@@ -18,13 +18,26 @@ struct GemmF32 {
   long long sam, sak, sbk, sbn;   // element strides of A(m,k) and B(k,n)
   int M, N, K, ldc;
   int nseg;                       // > 1: segments accumulate into C[0] (grid z must be 1)
+  // device-side token count (see vd_count): M (n_role 0) or K (n_role 1) becomes n_mul * n, at most its host value
+  const int32_t* n_dev;
+  int32_t* status;
+  int n_max, n_mul, n_role;
+  void count(const VdDevCount& dn, bool give_status, int nmax, int mul, int role) {
+    n_dev = dn.dev; status = give_status ? dn.status : nullptr; n_max = nmax; n_mul = mul; n_role = role;
+  }
 };
 
 __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmF32 g) {
   __shared__ float As[16][64 + 1];
   __shared__ float Bs[16][64 + 1];
+  if (g.n_dev) {
+    int n;
+    if (!vd_count(g.n_dev, g.n_max, n, g.status)) return;
+    if (g.n_role == 0) g.M = g.n_mul * n; else g.K = g.n_mul * n;
+  }
   const int z = blockIdx.z;
   const int m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
+  if (m0 >= g.M) return;
   const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
   float acc[4][4] = {};
   const int nseg = g.nseg > 1 ? g.nseg : 1;
@@ -109,9 +122,11 @@ constexpr int kTile = 32;
 template <int DH>
 __global__ __launch_bounds__(64) void sdpa_fwd_f32(const float* __restrict__ q, const float* __restrict__ k,
                                                   const float* __restrict__ v, float* __restrict__ o,
-                                                  float* __restrict__ lse, int n, int d, int H, float scale) {
+                                                  float* __restrict__ lse, int n, int d, int H, float scale,
+                                                  const int32_t* n_dev) {
   __shared__ float Ks[kTile][DH];
   __shared__ float Vs[kTile][DH];
+  if (!vd_count(n_dev, n, n) || (int)blockIdx.x * 64 >= n) return;
   const int b = blockIdx.z, h = blockIdx.y;
   const int i = blockIdx.x * 64 + threadIdx.x;
   const long long base = (long long)b * n * d + h * DH;
@@ -160,9 +175,10 @@ __global__ __launch_bounds__(64) void sdpa_bwd_dq_f32(const float* __restrict__ 
                                                      const float* __restrict__ v, const float* __restrict__ o,
                                                      const float* __restrict__ dout, const float* __restrict__ lse,
                                                      float* __restrict__ dq, float* __restrict__ Dsum,
-                                                     int n, int d, int H, float scale) {
+                                                     int n, int d, int H, float scale, const int32_t* n_dev) {
   __shared__ float Ks[kTile][DH];
   __shared__ float Vs[kTile][DH];
+  if (!vd_count(n_dev, n, n) || (int)blockIdx.x * 64 >= n) return;
   const int b = blockIdx.z, h = blockIdx.y;
   const int i = blockIdx.x * 64 + threadIdx.x;
   const long long base = (long long)b * n * d + h * DH;
@@ -213,10 +229,11 @@ __global__ __launch_bounds__(64) void sdpa_bwd_dkv_f32(const float* __restrict__
                                                       const float* __restrict__ v, const float* __restrict__ dout,
                                                       const float* __restrict__ lse, const float* __restrict__ Dsum,
                                                       float* __restrict__ dk, float* __restrict__ dv,
-                                                      int n, int d, int H, float scale) {
+                                                      int n, int d, int H, float scale, const int32_t* n_dev) {
   __shared__ float Qs[kTile][DH];
   __shared__ float Os[kTile][DH];
   __shared__ float Ls[kTile], Ds[kTile];
+  if (!vd_count(n_dev, n, n) || (int)blockIdx.x * 64 >= n) return;
   const int b = blockIdx.z, h = blockIdx.y;
   const int j = blockIdx.x * 64 + threadIdx.x;
   const long long base = (long long)b * n * d + h * DH;
@@ -274,11 +291,18 @@ struct ColSumF32 {
   float* dst[4];
   long long rows;
   int d;
+  const int32_t* n_dev;           // device-side token count: rows = n_mul * n
+  int n_max, n_mul;
 };
 __global__ __launch_bounds__(256) void colsum_f32_kernel(ColSumF32 a) {
   const float* src = a.src[blockIdx.y];
   float* dst = a.dst[blockIdx.y];
   if (!dst) return;
+  if (a.n_dev) {
+    int n;
+    if (!vd_count(a.n_dev, a.n_max, n)) return;
+    a.rows = (long long)a.n_mul * n;
+  }
   const int c = blockIdx.x * 256 + threadIdx.x;
   if (c >= a.d) return;
   float s = 0.f;
@@ -288,10 +312,10 @@ __global__ __launch_bounds__(256) void colsum_f32_kernel(ColSumF32 a) {
 
 template <int DH>
 int run_fwd_core(vardrop_ctx* ctx, const float* q, const float* k, const float* v, float* o, float* lse,
-                 int B, int n, int d, int H, hipStream_t s) {
+                 int B, int n, int d, int H, hipStream_t s, const int32_t* n_dev) {
   VdTimer timer(ctx, VARDROP_K_SDPA_FWD, s);
   hipLaunchKernelGGL(sdpa_fwd_f32<DH>, dim3(vd_ceil_div(n, 64), H, B), dim3(64), 0, s, q, k, v, o, lse, n, d, H,
-                     1.0f / sqrtf((float)DH));
+                     1.0f / sqrtf((float)DH), n_dev);
   VD_LAUNCH_CHECK(ctx);
   return VARDROP_OK;
 }
@@ -299,16 +323,16 @@ int run_fwd_core(vardrop_ctx* ctx, const float* q, const float* k, const float* 
 template <int DH>
 int run_bwd_core(vardrop_ctx* ctx, const float* q, const float* k, const float* v, const float* o, const float* dO,
                  const float* lse, float* dq, float* dk, float* dv, float* D, int B, int n, int d, int H,
-                 hipStream_t s) {
+                 hipStream_t s, const int32_t* n_dev) {
   const float scale = 1.0f / sqrtf((float)DH);
   dim3 grid(vd_ceil_div(n, 64), H, B);
   {
     VdTimer timer(ctx, VARDROP_K_SDPA_BWD_DQ, s);
-    hipLaunchKernelGGL(sdpa_bwd_dq_f32<DH>, grid, dim3(64), 0, s, q, k, v, o, dO, lse, dq, D, n, d, H, scale);
+    hipLaunchKernelGGL(sdpa_bwd_dq_f32<DH>, grid, dim3(64), 0, s, q, k, v, o, dO, lse, dq, D, n, d, H, scale, n_dev);
   }
   VD_LAUNCH_CHECK(ctx);
   VdTimer timer(ctx, VARDROP_K_SDPA_BWD_DKV, s);
-  hipLaunchKernelGGL(sdpa_bwd_dkv_f32<DH>, grid, dim3(64), 0, s, q, k, v, dO, lse, D, dk, dv, n, d, H, scale);
+  hipLaunchKernelGGL(sdpa_bwd_dkv_f32<DH>, grid, dim3(64), 0, s, q, k, v, dO, lse, D, dk, dv, n, d, H, scale, n_dev);
   VD_LAUNCH_CHECK(ctx);
   return VARDROP_OK;
 }
@@ -318,7 +342,7 @@ int run_bwd_core(vardrop_ctx* ctx, const float* q, const float* k, const float* 
 // saved: q, k, v, o ([M][d] fp32 each, M = B*n) then lse [B][H][n]
 int vd_attn_fwd_f32(vardrop_ctx* ctx, const float* xs, int B, int n, int d, int H,
                     const float* const W[4], const float* const bias[4],
-                    float* y, void* saved, void* ws, hipStream_t s) {
+                    float* y, void* saved, void* ws, hipStream_t s, VdDevCount dn) {
   (void)ws;
   const long long M = (long long)B * n;
   float* q = (float*)saved;
@@ -337,14 +361,15 @@ int vd_attn_fwd_f32(vardrop_ctx* ctx, const float* xs, int B, int n, int d, int 
   g.C[2] = v;
   g.sam = d; g.sak = 1; g.sbk = d; g.sbn = 1;
   g.M = (int)M; g.N = d; g.K = d; g.ldc = d; g.nseg = 1;
+  g.count(dn, true, n, B, 0);
   int rc = launch_gemm(ctx, VARDROP_K_GEMM_QKV, g, 3, s);
   if (rc) return rc;
   const int dh = d / H;
   switch (dh) {
-    case 16: rc = run_fwd_core<16>(ctx, q, k, v, o, lse, B, n, d, H, s); break;
-    case 32: rc = run_fwd_core<32>(ctx, q, k, v, o, lse, B, n, d, H, s); break;
-    case 64: rc = run_fwd_core<64>(ctx, q, k, v, o, lse, B, n, d, H, s); break;
-    case 128: rc = run_fwd_core<128>(ctx, q, k, v, o, lse, B, n, d, H, s); break;
+    case 16: rc = run_fwd_core<16>(ctx, q, k, v, o, lse, B, n, d, H, s, dn.dev); break;
+    case 32: rc = run_fwd_core<32>(ctx, q, k, v, o, lse, B, n, d, H, s, dn.dev); break;
+    case 64: rc = run_fwd_core<64>(ctx, q, k, v, o, lse, B, n, d, H, s, dn.dev); break;
+    case 128: rc = run_fwd_core<128>(ctx, q, k, v, o, lse, B, n, d, H, s, dn.dev); break;
     default: return VARDROP_EUNSUPPORTED;
   }
   if (rc) return rc;
@@ -352,13 +377,14 @@ int vd_attn_fwd_f32(vardrop_ctx* ctx, const float* xs, int B, int n, int d, int 
   go.A[0] = o; go.B[0] = W[3]; go.C[0] = y; go.bias[0] = bias[3];
   go.sam = d; go.sak = 1; go.sbk = d; go.sbn = 1;
   go.M = (int)M; go.N = d; go.K = d; go.ldc = d; go.nseg = 1;
+  go.count(dn, false, n, B, 0);
   return launch_gemm(ctx, VARDROP_K_GEMM_OUT, go, 1, s);
 }
 
 // ws: dO, dq, dk, dv ([M][d] fp32 each) then D [B][H][n]
 int vd_attn_bwd_f32(vardrop_ctx* ctx, const float* dy, const float* xs, int B, int n, int d, int H,
                     const float* const W[4], const void* saved, float* dxs,
-                    float* const dW[4], float* const db[4], void* ws, hipStream_t s) {
+                    float* const dW[4], float* const db[4], void* ws, hipStream_t s, VdDevCount dn) {
   const long long M = (long long)B * n;
   const float* q = (const float*)saved;
   const float* k = q + M * d;
@@ -376,14 +402,15 @@ int vd_attn_bwd_f32(vardrop_ctx* ctx, const float* dy, const float* xs, int B, i
     g.A[0] = dy; g.B[0] = W[3]; g.C[0] = dO;
     g.sam = d; g.sak = 1; g.sbk = 1; g.sbn = d;      // B(k, n) = Wo[n][k]
     g.M = (int)M; g.N = d; g.K = d; g.ldc = d; g.nseg = 1;
+    g.count(dn, true, n, B, 0);
     if ((rc = launch_gemm(ctx, VARDROP_K_GEMM_DO, g, 1, s))) return rc;
   }
   const int dh = d / H;
   switch (dh) {
-    case 16: rc = run_bwd_core<16>(ctx, q, k, v, o, dO, lse, dq, dk, dv, D, B, n, d, H, s); break;
-    case 32: rc = run_bwd_core<32>(ctx, q, k, v, o, dO, lse, dq, dk, dv, D, B, n, d, H, s); break;
-    case 64: rc = run_bwd_core<64>(ctx, q, k, v, o, dO, lse, dq, dk, dv, D, B, n, d, H, s); break;
-    case 128: rc = run_bwd_core<128>(ctx, q, k, v, o, dO, lse, dq, dk, dv, D, B, n, d, H, s); break;
+    case 16: rc = run_bwd_core<16>(ctx, q, k, v, o, dO, lse, dq, dk, dv, D, B, n, d, H, s, dn.dev); break;
+    case 32: rc = run_bwd_core<32>(ctx, q, k, v, o, dO, lse, dq, dk, dv, D, B, n, d, H, s, dn.dev); break;
+    case 64: rc = run_bwd_core<64>(ctx, q, k, v, o, dO, lse, dq, dk, dv, D, B, n, d, H, s, dn.dev); break;
+    case 128: rc = run_bwd_core<128>(ctx, q, k, v, o, dO, lse, dq, dk, dv, D, B, n, d, H, s, dn.dev); break;
     default: return VARDROP_EUNSUPPORTED;
   }
   if (rc) return rc;
@@ -392,6 +419,7 @@ int vd_attn_bwd_f32(vardrop_ctx* ctx, const float* dy, const float* xs, int B, i
     g.A[0] = o; g.B[0] = dy; g.C[0] = dW[3];
     g.sam = 1; g.sak = d; g.sbk = d; g.sbn = 1;      // A(m, k) = o[k][m]
     g.M = d; g.N = d; g.K = (int)M; g.ldc = d; g.nseg = 1;
+    g.count(dn, false, n, B, 1);
     if ((rc = launch_gemm(ctx, VARDROP_K_GEMM_DW, g, 1, s))) return rc;
   }
   {  // dWq, dWk, dWv = xs^T dq, xs^T dk, xs^T dv
@@ -402,6 +430,7 @@ int vd_attn_bwd_f32(vardrop_ctx* ctx, const float* dy, const float* xs, int B, i
     }
     g.sam = 1; g.sak = d; g.sbk = d; g.sbn = 1;
     g.M = d; g.N = d; g.K = (int)M; g.ldc = d; g.nseg = 1;
+    g.count(dn, false, n, B, 1);
     if ((rc = launch_gemm(ctx, VARDROP_K_GEMM_DW, g, 3, s))) return rc;
   }
   {  // dxs = dq Wq^T + dk Wk^T + dv Wv^T
@@ -413,6 +442,7 @@ int vd_attn_bwd_f32(vardrop_ctx* ctx, const float* dy, const float* xs, int B, i
     g.C[0] = dxs;
     g.sam = d; g.sak = 1; g.sbk = 1; g.sbn = d;
     g.M = (int)M; g.N = d; g.K = d; g.ldc = d; g.nseg = 3;
+    g.count(dn, false, n, B, 0);
     if ((rc = launch_gemm(ctx, VARDROP_K_GEMM_DXS, g, 1, s))) return rc;
   }
   if (db[0] || db[1] || db[2] || db[3]) {
@@ -420,6 +450,7 @@ int vd_attn_bwd_f32(vardrop_ctx* ctx, const float* dy, const float* xs, int B, i
     c.src[0] = dq; c.src[1] = dk; c.src[2] = dv; c.src[3] = dy;
     for (int z = 0; z < 4; ++z) c.dst[z] = db[z];
     c.rows = M; c.d = d;
+    c.n_dev = dn.dev; c.n_max = n; c.n_mul = B;
     hipLaunchKernelGGL(colsum_f32_kernel, dim3(vd_ceil_div(d, 256), 4), dim3(256), 0, s, c);
     VD_LAUNCH_CHECK(ctx);
   }

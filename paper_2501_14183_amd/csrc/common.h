@@ -52,11 +52,45 @@ struct VdTimer {
   }
 };
 
-static inline size_t vd_align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
-static inline bool vd_aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
-static inline int vd_ceil_div(int a, int b) { return (a + b - 1) / b; }
+// Token count of a call.  It is either the host integer `bound` itself (n_dev == nullptr) or an int32 in device
+// memory that every kernel of the call reads, with `bound` as its upper limit (what the buffers were sized for).
+// Returns false when the device value lies outside [0, bound]: the kernel then returns without touching memory,
+// and the first workgroup of the kernel that was handed `status` raises it.
+__device__ inline bool vd_count(const int32_t* n_dev, int bound, int& n, int32_t* status = nullptr) {
+  n = bound;
+  if (!n_dev) return true;
+  n = *n_dev;
+  if ((unsigned)n <= (unsigned)bound) return true;
+  if (status && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0 && threadIdx.y == 0) *status = 1;
+  return false;
+}
 
-int vd_attn_bf16_splitk(int d, long long M, int* kchunk);
+__host__ __device__ static inline size_t vd_align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+static inline bool vd_aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
+__host__ __device__ static inline int vd_ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+// Number of K slices of the weight-gradient GEMMs (K = B*n rows, 128 x 128 tiles).  They share a
+// launch with the input gradient, two workgroups per compute unit: enough slices that the two
+// together fill those 512 places when the input gradient leaves room, else enough for the weight
+// gradients alone to do so; slices hold at least 256 rows and are a multiple of the 64-row stage.
+// (Host and device: with a device-side token count the kernels evaluate it themselves.)
+__host__ __device__ static inline int vd_attn_bf16_splitk(int d, long long M, int* kchunk) {
+  const int tiles = vd_ceil_div(d, 128) * vd_ceil_div(d, 128) * 4;
+  const long long dxs_wgs = (long long)vd_ceil_div((int)M, 64) * vd_ceil_div(d, 128);
+  int s = vd_ceil_div(512, tiles);
+  if (dxs_wgs < 512) {
+    const int fit = (int)((512 - dxs_wgs) / tiles);
+    if (fit >= 1 && fit < s) s = fit;
+  }
+  if (s > 8) s = 8;
+  while (s > 1 && M / s < 256) --s;
+  if (s < 1) s = 1;
+  int chunk = (int)vd_align_up((size_t)vd_ceil_div((int)M, s), 64);
+  if (chunk < 64) chunk = 64;
+  s = M > 0 ? vd_ceil_div((int)M, chunk) : 1;
+  if (kchunk) *kchunk = chunk;
+  return s;
+}
 size_t vd_attn_bf16_partial_offset(int B, int n, int d, int H);
 size_t vd_attn_bf16_ws_bytes(int B, int n, int d, int H);
 
@@ -66,16 +100,24 @@ int vd_gemm_f32(vardrop_ctx*, int kid, const float* A, long long sam, long long 
                 int M, int N, int K, hipStream_t s);
 
 // attention back ends (attn_f32.hip, attn_bf16.hip); argument checks are done by the caller
+// A count that may live in device memory (see vd_count): with dev != nullptr the `n` of the call is its bound.
+struct VdDevCount {
+  const int32_t* dev;
+  int32_t* status;
+};
 int vd_attn_fwd_f32(vardrop_ctx*, const float* xs, int B, int n, int d, int H,
                     const float* const W[4], const float* const bias[4],
-                    float* y, void* saved, void* ws, hipStream_t s);
+                    float* y, void* saved, void* ws, hipStream_t s, VdDevCount dn = {nullptr, nullptr});
 int vd_attn_bwd_f32(vardrop_ctx*, const float* dy, const float* xs, int B, int n, int d, int H,
                     const float* const W[4], const void* saved, float* dxs,
-                    float* const dW[4], float* const db[4], void* ws, hipStream_t s);
+                    float* const dW[4], float* const db[4], void* ws, hipStream_t s, VdDevCount dn = {nullptr, nullptr});
 int vd_attn_fwd_bf16(vardrop_ctx*, const void* xs, int B, int n, int d, int H,
                      const void* const W[4], const void* const bias[4],
                      void* y, void* saved, void* ws, hipStream_t s,
-                     const int32_t* sel = nullptr, int N = 0, void* xs_out = nullptr);
+                     const int32_t* sel = nullptr, int N = 0, void* xs_out = nullptr, VdDevCount dn = {nullptr, nullptr});
 int vd_attn_bwd_bf16(vardrop_ctx*, const void* dy, const void* xs, int B, int n, int d, int H,
                      const void* const W[4], const void* saved, void* dxs,
-                     float* const dW[4], float* const db[4], void* ws, hipStream_t s);
+                     float* const dW[4], float* const db[4], void* ws, hipStream_t s, VdDevCount dn = {nullptr, nullptr});
+// gather / scatter with an optional device-side count (gather.hip); argument checks are done by the caller
+int vd_gather(vardrop_ctx*, const void* tokens, int B, int N, int d, int dtype, const int32_t* sel, int n_sel,
+              void* out, hipStream_t s, VdDevCount dn = {nullptr, nullptr});

@@ -212,7 +212,7 @@ extern "C" int vardrop_embed_bwd(vardrop_ctx* ctx, const void* dxs, int B, int n
     g.splitk = embed_splitk(L, d, M, &kchunk);
     g.kchunk = kchunk;
     if (g.splitk > 1) {
-      g.C0 = slices;
+      g.part = slices;
       if ((rc = vd_gemm_bf16_wgrad_split(ctx, VARDROP_K_GEMM_DWE, g, s))) return rc;
       float* out[4] = {dWe, nullptr, nullptr, nullptr};
       if ((rc = vd_gemm_bf16_sum_slices(ctx, slices, out, (long long)L * d, g.splitk, s, 1))) return rc;

@@ -14,7 +14,9 @@ template <> __device__ inline uint4 zero_unit<uint4>() { return make_uint4(0, 0,
 template <typename T>
 __global__ __launch_bounds__(256) void gather_kernel(const T* __restrict__ src, T* __restrict__ out,
                                                     const int32_t* __restrict__ sel,
-                                                    int B, int N, int n_sel, int row_units) {
+                                                    int B, int N, int n_sel, int row_units,
+                                                    const int32_t* n_dev, int32_t* status) {
+  if (!vd_count(n_dev, n_sel, n_sel, status)) return;     // device-side count: n_sel was its bound
   const int rows = B * n_sel;
   for (int row = blockIdx.x * blockDim.y + threadIdx.y; row < rows; row += gridDim.x * blockDim.y) {
     const int b = row / n_sel, j = row - b * n_sel;
@@ -34,7 +36,9 @@ __global__ __launch_bounds__(256) void gather_kernel(const T* __restrict__ src, 
 template <typename T>
 __global__ __launch_bounds__(256) void scatter_kernel(const T* __restrict__ src, T* __restrict__ dst,
                                                      const int32_t* __restrict__ sel,
-                                                     int B, int N, int n_sel, int row_units) {
+                                                     int B, int N, int n_sel, int row_units,
+                                                     const int32_t* n_dev, int32_t* status) {
+  if (!vd_count(n_dev, n_sel, n_sel, status)) return;
   const int rows = B * N;
   for (int row = blockIdx.x * blockDim.y + threadIdx.y; row < rows; row += gridDim.x * blockDim.y) {
     const int b = row / N, n = row - b * N;
@@ -60,7 +64,7 @@ int elem_size(int dtype) { return dtype == VARDROP_F32 ? 4 : (dtype == VARDROP_B
 
 template <bool kScatter>
 int launch(vardrop_ctx* ctx, const void* src, void* dst, const int32_t* sel, int B, int N, int n_sel,
-           int d, int dtype, hipStream_t s) {
+           int d, int dtype, hipStream_t s, VdDevCount dn = {nullptr, nullptr}) {
   const int es = elem_size(dtype);
   const long long row_bytes = (long long)d * es;
   const long long rows = (long long)B * (kScatter ? N : n_sel);
@@ -77,14 +81,14 @@ int launch(vardrop_ctx* ctx, const void* src, void* dst, const int32_t* sel, int
   dim3 grid((unsigned)blocks), block(tx, ty);
   VdTimer timer(ctx, kScatter ? VARDROP_K_SCATTER : VARDROP_K_GATHER, s);
   if (wide) {
-    if (kScatter) hipLaunchKernelGGL(scatter_kernel<Chunk16>, grid, block, 0, s, (const Chunk16*)src, (Chunk16*)dst, sel, B, N, n_sel, row_units);
-    else hipLaunchKernelGGL(gather_kernel<Chunk16>, grid, block, 0, s, (const Chunk16*)src, (Chunk16*)dst, sel, B, N, n_sel, row_units);
+    if (kScatter) hipLaunchKernelGGL(scatter_kernel<Chunk16>, grid, block, 0, s, (const Chunk16*)src, (Chunk16*)dst, sel, B, N, n_sel, row_units, dn.dev, dn.status);
+    else hipLaunchKernelGGL(gather_kernel<Chunk16>, grid, block, 0, s, (const Chunk16*)src, (Chunk16*)dst, sel, B, N, n_sel, row_units, dn.dev, dn.status);
   } else if (es == 4) {
-    if (kScatter) hipLaunchKernelGGL(scatter_kernel<uint32_t>, grid, block, 0, s, (const uint32_t*)src, (uint32_t*)dst, sel, B, N, n_sel, row_units);
-    else hipLaunchKernelGGL(gather_kernel<uint32_t>, grid, block, 0, s, (const uint32_t*)src, (uint32_t*)dst, sel, B, N, n_sel, row_units);
+    if (kScatter) hipLaunchKernelGGL(scatter_kernel<uint32_t>, grid, block, 0, s, (const uint32_t*)src, (uint32_t*)dst, sel, B, N, n_sel, row_units, dn.dev, dn.status);
+    else hipLaunchKernelGGL(gather_kernel<uint32_t>, grid, block, 0, s, (const uint32_t*)src, (uint32_t*)dst, sel, B, N, n_sel, row_units, dn.dev, dn.status);
   } else {
-    if (kScatter) hipLaunchKernelGGL(scatter_kernel<uint16_t>, grid, block, 0, s, (const uint16_t*)src, (uint16_t*)dst, sel, B, N, n_sel, row_units);
-    else hipLaunchKernelGGL(gather_kernel<uint16_t>, grid, block, 0, s, (const uint16_t*)src, (uint16_t*)dst, sel, B, N, n_sel, row_units);
+    if (kScatter) hipLaunchKernelGGL(scatter_kernel<uint16_t>, grid, block, 0, s, (const uint16_t*)src, (uint16_t*)dst, sel, B, N, n_sel, row_units, dn.dev, dn.status);
+    else hipLaunchKernelGGL(gather_kernel<uint16_t>, grid, block, 0, s, (const uint16_t*)src, (uint16_t*)dst, sel, B, N, n_sel, row_units, dn.dev, dn.status);
   }
   VD_LAUNCH_CHECK(ctx);
   return VARDROP_OK;
@@ -106,6 +110,33 @@ extern "C" int vardrop_gather(vardrop_ctx* ctx, const void* tokens, int B, int N
   if ((long long)B * n_sel == 0) return VARDROP_OK;
   if (!tokens || !out || !sel) return VARDROP_EINVAL;
   return launch<false>(ctx, tokens, out, sel, B, N, n_sel, d, dtype, (hipStream_t)stream);
+}
+
+int vd_gather(vardrop_ctx* ctx, const void* tokens, int B, int N, int d, int dtype, const int32_t* sel, int n_sel,
+              void* out, hipStream_t s, VdDevCount dn) {
+  return launch<false>(ctx, tokens, out, sel, B, N, n_sel, d, dtype, s, dn);
+}
+
+extern "C" int vardrop_gather_dev(vardrop_ctx* ctx, const void* tokens, int B, int N, int d, int dtype,
+                                  const int32_t* sel, const int32_t* n_sel_dev, int n_sel_max, int32_t* status,
+                                  void* out, void* stream) {
+  int rc = check(ctx, B, N, d, dtype, n_sel_max);
+  if (rc != VARDROP_OK) return rc;
+  if (!n_sel_dev) return VARDROP_EINVAL;
+  if ((long long)B * n_sel_max == 0) return VARDROP_OK;
+  if (!tokens || !out || !sel) return VARDROP_EINVAL;
+  return launch<false>(ctx, tokens, out, sel, B, N, n_sel_max, d, dtype, (hipStream_t)stream, VdDevCount{n_sel_dev, status});
+}
+
+extern "C" int vardrop_scatter_dev(vardrop_ctx* ctx, const void* dxs, int B, int N, int d, int dtype,
+                                   const int32_t* sel, const int32_t* n_sel_dev, int n_sel_max, int32_t* status,
+                                   void* dtokens, void* stream) {
+  int rc = check(ctx, B, N, d, dtype, n_sel_max);
+  if (rc != VARDROP_OK) return rc;
+  if (!n_sel_dev) return VARDROP_EINVAL;
+  if ((long long)B * N == 0) return VARDROP_OK;
+  if (!dtokens || !dxs || !sel) return VARDROP_EINVAL;
+  return launch<true>(ctx, dxs, dtokens, sel, B, N, n_sel_max, d, dtype, (hipStream_t)stream, VdDevCount{n_sel_dev, status});
 }
 
 extern "C" int vardrop_scatter(vardrop_ctx* ctx, const void* dxs, int B, int N, int d, int dtype,

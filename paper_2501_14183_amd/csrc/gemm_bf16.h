@@ -15,7 +15,8 @@ struct GemmBf16 {
   int lda, ldb, ldc;
   int M, N, K;
   int nseg;           // > 1: segments accumulate into C0
-  int splitk;         // > 1: grid.z = batches * splitk, slice s writes fp32 to C0 + (z * splitk + s) * M * N
+  int splitk;         // > 1: every matrix z is cut into splitk K slices, slice s writes fp32 to part + (z * splitk + s) * M * N
+  float* part;        //      (the partial products; with splitk == 1 the result goes to C[z] itself)
   int kchunk;         // K elements per slice (multiple of 64)
   int a_kpad;         // != 0: the rows of a k-contiguous A hold zeros from K up to the next multiple of 64, so K
                       // itself need not be one (B must then be n-contiguous: its last k-row is re-read, times zero)
@@ -29,6 +30,14 @@ struct GemmBf16 {
   const float* rs_aux_in;
   float* rs_aux_out;
   float rs_aux_mul;
+  // Device-side token count (n_dev != nullptr): the kernels read n = *n_dev (at most n_max, see vd_count) and the
+  // token dimension of the product becomes n_mul * n: M when n_role == 0 (with rs_n = n), K when n_role == 1, where
+  // the number and length of the K slices then follow from vd_attn_bf16_splitk on the device as well.
+  const int32_t* n_dev;
+  int32_t* status;
+  int n_max, n_mul, n_role;
+  void count_rows(const int32_t* dev, int32_t* st, int nmax, int mul) { n_dev = dev; status = st; n_max = nmax; n_mul = mul; n_role = 0; }
+  void count_k(const int32_t* dev, int nmax, int mul) { n_dev = dev; status = nullptr; n_max = nmax; n_mul = mul; n_role = 1; }
   void set(int z, const void* a, const void* b, void* c, const void* bias) {
     const bf16_t* pa = (const bf16_t*)a;
     const bf16_t* pb = (const bf16_t*)b;
@@ -48,12 +57,14 @@ int vd_gemm_bf16(vardrop_ctx* ctx, int kid, const GemmBf16& g, int nz, bool b_k_
 // C[z] = A[z]^T * B[z] in fp32 for nz matrices, both operands mn-contiguous ([K][M], [K][N]), one K slice.
 int vd_gemm_bf16_wgrad(vardrop_ctx* ctx, int kid, const GemmBf16& g, int nz, hipStream_t s);
 // One launch for the input gradient gx (k-contiguous operands, up to three segments) and the nzw weight
-// gradients gw (mn-contiguous operands, gw.splitk K slices, fp32 partial products in gw.C0).
+// gradients gw (mn-contiguous operands, gw.splitk K slices, fp32 partial products in gw.part).
 int vd_gemm_bf16_bwd_pair(vardrop_ctx* ctx, const GemmBf16& gx, const GemmBf16& gw, int nzw, hipStream_t s);
 // out[z][i] = sum_s part[z * splitk + s][i] for four matrices of `count` elements, slices in ascending order.
+// With `like` (a weight-gradient product with a device-side count) the slice count is the one that product's
+// kernel derives from the count; a single slice means the product wrote its result itself and nothing is done.
 int vd_gemm_bf16_sum_slices(vardrop_ctx* ctx, const float* part, float* const out[4], long long count, int splitk,
-                            hipStream_t s, int nz = 4);
+                            hipStream_t s, int nz = 4, const GemmBf16* like = nullptr);
 // C = A^T * B in fp32 for one matrix, both operands mn-contiguous, K cut into g.splitk slices of g.kchunk: the
-// partial products go to g.C0 ([splitk][M][N] fp32) when splitk > 1, the result itself (ldc) when it is 1.
+// partial products go to g.part ([splitk][M][N] fp32) when splitk > 1, the result itself (C0, ldc) when it is 1.
 int vd_gemm_bf16_wgrad_split(vardrop_ctx* ctx, int kid, const GemmBf16& g, hipStream_t s);
 #endif  // VARDROP_GEMM_BF16_H

@@ -11,14 +11,24 @@ struct SplitkReduce {
   float* out[4];
   long long count;     // elements per matrix
   int splitk;
+  // device-side token count: the slice count is the one the weight-gradient kernel derived from it (d = dn_d)
+  const int32_t* n_dev;
+  int n_max, n_mul, dn_d;
 };
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(SplitkReduce a) {
+  if (a.n_dev) {
+    int n;
+    if (!vd_count(a.n_dev, a.n_max, n)) return;
+    a.splitk = vd_attn_bf16_splitk(a.dn_d, (long long)a.n_mul * n, nullptr);
+    if (a.splitk <= 1 && n > 0) return;          // a single slice was written as the result itself
+    if (n == 0) a.splitk = 0;                    // no tokens: the gradients are zero
+  }
   const int z = blockIdx.y;
   const float4* src = reinterpret_cast<const float4*>(a.part + (long long)z * a.splitk * a.count);
   float4* dst = reinterpret_cast<float4*>(a.out[z]);
   const long long n4 = a.count >> 2;
   for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += (long long)gridDim.x * blockDim.x) {
-    float4 s = src[i];
+    float4 s = a.splitk > 0 ? src[i] : make_float4(0.f, 0.f, 0.f, 0.f);
     for (int k = 1; k < a.splitk; ++k) {
       const float4 v = src[(long long)k * n4 + i];
       s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
@@ -52,8 +62,12 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(SplitkReduce a) {
 // The product is formed transposed (the B fragment is the left operand of the instruction), so a
 // lane owns one output row and four consecutive columns per register quad; the tile goes through
 // LDS once more so that global stores are whole 16-byte chunks of consecutive rows.
+// The dimensions a kernel works with: those of the argument block, or what a device-side token count makes of them.
+struct GemmDims {
+  int M, K, splitk, kchunk, rs_n;
+};
 template <bool AKC, bool BKC, bool SPLIT, int BM, int BK, int NS>
-__device__ __forceinline__ void gemm_async_tile(const GemmBf16& g, const int bx, const int by, const int bz) {
+__device__ __forceinline__ void gemm_async_tile(const GemmBf16& g, const GemmDims& dm, const int bx, const int by, const int bz) {
   constexpr int BN = 128, MI = BM / 64, KS = BK / 16;
   constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE = A_BYTES + B_BYTES;
   constexpr int IA = A_BYTES / 4096, IB = B_BYTES / 4096, LPS = IA + IB;   // 1 KB copies per wavefront and stage
@@ -68,9 +82,9 @@ __device__ __forceinline__ void gemm_async_tile(const GemmBf16& g, const int bx,
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   const int col = lane & 31, half = lane >> 5;
-  const int zb = SPLIT ? bz / g.splitk : bz;
-  const int kbeg = SPLIT ? (bz % g.splitk) * g.kchunk : 0;
-  const int kend = SPLIT ? min(g.K, kbeg + g.kchunk) : g.K;
+  const int zb = SPLIT ? bz / dm.splitk : bz;
+  const int kbeg = SPLIT ? (bz % dm.splitk) * dm.kchunk : 0;
+  const int kend = SPLIT ? min(dm.K, kbeg + dm.kchunk) : dm.K;
   const int m0 = by * BM, n0 = bx * BN;
   const int nseg = g.nseg > 1 ? g.nseg : 1;
   const int nk = (kend - kbeg + BK - 1) / BK;
@@ -90,11 +104,11 @@ __device__ __forceinline__ void gemm_async_tile(const GemmBf16& g, const int bx,
   for (int u = 0; u < IA; ++u) {
     if constexpr (AKC) {
       const int row = (u * 4 + wave) * RPI + lane / CH;
-      goffA[u] = min(m0 + row, g.M - 1) * g.lda + ((lane % CH) ^ swz_kc<BK>(row)) * 8;
+      goffA[u] = min(m0 + row, dm.M - 1) * g.lda + ((lane % CH) ^ swz_kc<BK>(row)) * 8;
     } else {
       const int krow = (u * 4 + wave) * RPA + lane / CHA;
       if (u == 0) krowA = krow;
-      goffA[u] = min(m0 + ((lane % CHA) ^ swz_nc<BM>(krow)) * 8, g.M - 8);
+      goffA[u] = min(m0 + ((lane % CHA) ^ swz_nc<BM>(krow)) * 8, dm.M - 8);
     }
   }
 #pragma unroll
@@ -279,8 +293,8 @@ __device__ __forceinline__ void gemm_async_tile(const GemmBf16& g, const int bx,
   unsigned char* Cb;
   long long ldc_bytes;
   if constexpr (SPLIT) {
-    if (g.splitk > 1) {      // partial product of slice bz % splitk of matrix bz / splitk
-      Cb = reinterpret_cast<unsigned char*>(g.C0) + (long long)bz * g.M * g.N * 4;
+    if (dm.splitk > 1) {      // partial product of slice bz % splitk of matrix bz / splitk
+      Cb = reinterpret_cast<unsigned char*>(g.part) + (long long)bz * dm.M * g.N * 4;
       ldc_bytes = (long long)g.N * 4;
     } else {                 // a single slice is the result itself
       Cb = reinterpret_cast<unsigned char*>(zsel == 0 ? g.C0 : (zsel == 1 ? g.C1 : (zsel == 2 ? g.C2 : g.C3)));
@@ -294,7 +308,7 @@ __device__ __forceinline__ void gemm_async_tile(const GemmBf16& g, const int bx,
   for (int u = 0; u < BM * CPR / 256; ++u) {
     const int idx = u * 256 + threadIdx.x;
     const int row = idx / CPR, c = idx % CPR;
-    if (m0 + row < g.M && n0 + c * EPC < g.N) {
+    if (m0 + row < dm.M && n0 + c * EPC < g.N) {
       const u32x4 v = *reinterpret_cast<const u32x4*>(smem + row * CPITCH + c * 16);
       *reinterpret_cast<u32x4*>(Cb + (long long)(m0 + row) * ldc_bytes + (long long)(n0 + c * EPC) * ES) = v;
     }
@@ -308,7 +322,7 @@ __device__ __forceinline__ void gemm_async_tile(const GemmBf16& g, const int bx,
         const int idx = u * 256 + threadIdx.x;
         const int row = idx >> 2, c0 = ((idx >> 1) & 1) * 64 + (idx & 1) * 32;
         const int m = m0 + row;
-        const bool live = m < g.M && n0 + c0 < g.N;
+        const bool live = m < dm.M && n0 + c0 < g.N;
         float p = 0.f;
         if (live) {
           const bf16_t* orow = g.rs_o + (long long)m * g.ldc + n0 + c0;
@@ -325,8 +339,8 @@ __device__ __forceinline__ void gemm_async_tile(const GemmBf16& g, const int bx,
         }
         p += __shfl_xor(p, 1, 64);
         if (live && (idx & 1) == 0) {
-          const int b = m / g.rs_n;
-          const long long i = ((long long)b * g.rs_H + ((n0 + c0) >> 6)) * g.rs_n + (m - b * g.rs_n);
+          const int b = m / dm.rs_n;
+          const long long i = ((long long)b * g.rs_H + ((n0 + c0) >> 6)) * dm.rs_n + (m - b * dm.rs_n);
           g.rs_out[i] = p;
           if (g.rs_aux_out) g.rs_aux_out[i] = g.rs_aux_mul * g.rs_aux_in[i];
         }
@@ -341,32 +355,59 @@ constexpr int gemm_async_lds() {
   constexpr int ring = NS * (BM + 128) * BK * 2, out = BM * (128 * (SPLIT ? 4 : 2) + 16);
   return ring > out ? ring : out;
 }
+// The product's dimensions, with a device-side token count (GemmBf16::n_dev) resolved; false: nothing to do.
+__device__ __forceinline__ bool gemm_resolve(const GemmBf16& g, GemmDims& dm) {
+  dm.M = g.M; dm.K = g.K; dm.splitk = g.splitk; dm.kchunk = g.kchunk; dm.rs_n = g.rs_n;
+  if (!g.n_dev) return true;
+  int n;
+  if (!vd_count(g.n_dev, g.n_max, n, g.status)) return false;
+  if (g.n_role == 0) {
+    dm.M = g.n_mul * n;
+    dm.rs_n = n;
+  } else {
+    dm.K = g.n_mul * n;
+    int kchunk = 64;
+    dm.splitk = vd_attn_bf16_splitk(g.M, (long long)dm.K, &kchunk);
+    dm.kchunk = kchunk;
+  }
+  return dm.M > 0 && dm.K > 0;
+}
+// One-dimensional grid of at least nz * tiles workgroups (more when the launch was sized for the bound of a
+// device-side count: the surplus returns at once).
 template <bool AKC, bool BKC, bool SPLIT, int BM, int BK, int NS>
-__global__ __launch_bounds__(256, 2) void gemm_async_kernel(GemmBf16 g) {
+__global__ __launch_bounds__(256, 2) void gemm_async_kernel(GemmBf16 g, int nz) {
+  GemmDims dm;
+  if (!gemm_resolve(g, dm)) return;
   // tiles in the order n fastest, then m, then batch entry: a die's range shares its rows of A
-  const int gx = gridDim.x, gy = gridDim.y;
-  const int t = xcd_contiguous(blockIdx.x + gx * (blockIdx.y + gy * blockIdx.z), gx * gy * gridDim.z);
-  gemm_async_tile<AKC, BKC, SPLIT, BM, BK, NS>(g, t % gx, (t / gx) % gy, t / (gx * gy));
+  const int gx = (g.N + 127) >> 7, gy = (dm.M + BM - 1) / BM;
+  const int total = gx * gy * nz * (SPLIT ? dm.splitk : 1);
+  if ((int)blockIdx.x >= total) return;
+  const int t = xcd_contiguous(blockIdx.x, total);
+  gemm_async_tile<AKC, BKC, SPLIT, BM, BK, NS>(g, dm, t % gx, (t / gx) % gy, t / (gx * gy));
 }
 // The input gradient (gx: k-contiguous operands, up to three accumulated segments) and the weight
 // gradients (gw: mn-contiguous operands, K slices, fp32 partial products) depend on the same dQ, dK,
 // dV and on nothing of each other, so they share one launch: workgroups [0, nx) take tiles of gx,
 // the rest tiles of gw.  The longer-running input-gradient tiles are dispatched first.
 template <int BMX>
-__global__ __launch_bounds__(256, 2) void gemm_bwd_pair_kernel(GemmBf16 gx, GemmBf16 gw, int nx, int gxn, int gwn, int gwm) {
+__global__ __launch_bounds__(256, 2) void gemm_bwd_pair_kernel(GemmBf16 gx, GemmBf16 gw, int nzw) {
   // Each die takes a contiguous range of the input-gradient tiles (n fastest: a range shares its rows
   // of dQ, dK, dV) and a contiguous range of the weight-gradient tiles (n, then m, then K slice, then
   // matrix: a range shares its K slice of both operands); its input-gradient tiles come first.
-  const int nw = (int)gridDim.x - nx;
+  GemmDims dx, dw;
+  if (!gemm_resolve(gx, dx) || !gemm_resolve(gw, dw)) return;
+  const int gxn = (gx.N + 127) >> 7, gwn = (gw.N + 127) >> 7, gwm = (dw.M + 127) >> 7;
+  const int nx = gxn * ((dx.M + BMX - 1) / BMX), nw = gwn * gwm * nzw * dw.splitk;
+  if ((int)blockIdx.x >= nx + nw) return;
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
   const int cntx = (nx >> 3) + (xcd < (nx & 7) ? 1 : 0);
   const int startx = xcd_range_start(xcd, nx);
   if (slot < cntx) {
     const int t = startx + slot;
-    gemm_async_tile<true, true, false, BMX, 64, 2>(gx, t % gxn, t / gxn, 0);
+    gemm_async_tile<true, true, false, BMX, 64, 2>(gx, dx, t % gxn, t / gxn, 0);
   } else {
     const int t = xcd_range_start(xcd, nx + nw) - startx + (slot - cntx);
-    gemm_async_tile<false, false, true, 128, 64, 2>(gw, t % gwn, (t / gwn) % gwm, t / (gwn * gwm));
+    gemm_async_tile<false, false, true, 128, 64, 2>(gw, dw, t % gwn, (t / gwn) % gwm, t / (gwn * gwm));
   }
 }
 
@@ -384,10 +425,12 @@ int launch_gemm_async_cfg(vardrop_ctx* ctx, int kid, const GemmBf16& g, int nz, 
                                     hipFuncAttributeMaxDynamicSharedMemorySize, lds));
     configured_device = ctx->device;
   }
-  dim3 grid(vd_ceil_div(g.N, 128), vd_ceil_div(g.M, BM), nz * (SPLIT ? g.splitk : 1));
+  // (with a device-side count g.M or g.K and g.splitk hold the bounds the grid is sized for)
+  const long long grid = (long long)vd_ceil_div(g.N, 128) * vd_ceil_div(g.M, BM) * nz * (SPLIT ? g.splitk : 1);
+  if (grid >= (1ll << 31)) return VARDROP_EUNSUPPORTED;
   {
     VdTimer timer(ctx, kid, s);
-    hipLaunchKernelGGL((gemm_async_kernel<AKC, BKC, SPLIT, BM, BK, NS>), grid, dim3(256), lds, s, g);
+    hipLaunchKernelGGL((gemm_async_kernel<AKC, BKC, SPLIT, BM, BK, NS>), dim3((unsigned)grid), dim3(256), lds, s, g, nz);
   }
   VD_LAUNCH_CHECK(ctx);
   return VARDROP_OK;
@@ -407,7 +450,7 @@ int launch_gemm_bwd_pair_cfg(vardrop_ctx* ctx, const GemmBf16& gx, const GemmBf1
   const int nx = gxn * gxm, nw = gwn * gwm * nzw * gw.splitk;
   {
     VdTimer timer(ctx, VARDROP_K_GEMM_DW_DXS, s);
-    hipLaunchKernelGGL(gemm_bwd_pair_kernel<BMX>, dim3(nx + nw), dim3(256), lds, s, gx, gw, nx, gxn, gwn, gwm);
+    hipLaunchKernelGGL(gemm_bwd_pair_kernel<BMX>, dim3(nx + nw), dim3(256), lds, s, gx, gw, nzw);
   }
   VD_LAUNCH_CHECK(ctx);
   return VARDROP_OK;
@@ -465,8 +508,14 @@ int vd_gemm_bf16_wgrad_split(vardrop_ctx* ctx, int kid, const GemmBf16& g, hipSt
 }
 
 int vd_gemm_bf16_sum_slices(vardrop_ctx* ctx, const float* part, float* const out[4], long long count, int splitk,
-                            hipStream_t s, int nz) {
+                            hipStream_t s, int nz, const GemmBf16* like) {
   SplitkReduce r = {};
+  if (like && like->n_dev) {
+    r.n_dev = like->n_dev;
+    r.n_max = like->n_max;
+    r.n_mul = like->n_mul;
+    r.dn_d = like->M;
+  }
   r.part = part;
   for (int z = 0; z < nz; ++z) r.out[z] = out[z];
   r.count = count;

@@ -723,12 +723,18 @@ extern "C" size_t vardrop_hash_strided_workspace_bytes(int B, int N, int L) {
   return vd_align_up((size_t)B * (size_t)N * (size_t)L * sizeof(float), 256);
 }
 
+// Default cut-off (App. E: 25 at T = 96, "half of the number of positive frequencies"): half of the
+// floor(L/2) + 1 bins of the real spectrum, rounded up; with the first candidate at bin 1 it is also their number.
+extern "C" int vardrop_hash_default_cutoff(int L) { return L < 2 ? 0 : (L / 2 + 2) / 2; }
+
 extern "C" int vardrop_hash(vardrop_ctx* ctx, const float* x, int B, int N, int L,
                             int64_t sb, int64_t sn, int64_t st, int k, int f_min, int f_max,
                             int32_t* topk, uint64_t* hash, float* abar,
                             void* ws, size_t ws_bytes, void* stream) {
   if (!ctx) return VARDROP_EINVAL;
   if (B < 1 || N < 0 || L < 2) return VARDROP_EINVAL;
+  if (f_min < 0) f_min = 1;
+  if (f_max < 0) f_max = vardrop_hash_default_cutoff(L);
   if (f_min < 0 || f_max < f_min || f_max > L / 2) return VARDROP_EINVAL;
   const int F = f_max - f_min + 1;
   if (k < 1 || k > F) return VARDROP_EINVAL;

@@ -2,12 +2,14 @@
 //
 // N <= 8192 variates fit the LDS of one compute unit, so a single workgroup does the whole
 // step without global round trips:
-//   1. bitonic sort of (hash, n)            -> equal hashes become contiguous segments
-//   2. flag scan over the segments          -> dense group id (ascending hash), start, size
-//   3. bitonic sort of (group, u[n], n)     -> members of a group in random-key order,
-//      u[n] from Philox4x32-10, counter (n, 0, step_lo, step_hi), key (seed_lo, seed_hi)
-//   4. keep the first n_i of every segment  -> flag per variate
-//   5. flag scan in variate order           -> sel ascending, N'
+//   1. order the variates by (hash, n): 1024 order-preserving buckets over [min, max] of the hashes, the
+//      place of a pair inside its bucket by counting; inputs that crowd one bucket fall back to a bitonic
+//      sort of packed (hash, n) keys (registers, lane shuffles, LDS for the widest strides)
+//   2. head flags + block scan              -> dense group id (ascending hash), start, size
+//   3. u[n] from Philox4x32-10, counter (n, 0, step_lo, step_hi), key (seed_lo, seed_hi); the rank of a
+//      member inside its group by counting over the group (groups above 1024 members: a second sort by
+//      (group, u[n], n)); a member is kept when its rank is below n_i
+//   4. flags by variate + block scan        -> sel ascending, N'
 #include "common.h"
 
 namespace {
@@ -268,6 +270,8 @@ struct SampleArgs {
   uint32_t gs, num, den;
   uint32_t seed_lo, seed_hi, step_lo, step_hi;
   const uint64_t* ext_keys;   // optional: key of variate n that orders the members of a group, instead of a Philox draw
+  uint64_t* step_dev;         // optional: the step counter lives in device memory (read here instead of step_lo / step_hi)
+  int advance;                //   and is incremented once the draw is done, so that a recorded launch draws anew when replayed
 };
 
 // members kept from a group of `size` (Eq. 1 with the optional keep ratio)
@@ -473,6 +477,11 @@ __global__ __launch_bounds__(1024) void sample_kernel(SampleArgs a) {
     for (int off = 32; off >= 1; off >>= 1) m = max(m, __shfl_xor(m, off, 64));
     if ((tid & 63) == 0) atomicMax(&wsum[18], m);
   }
+  if (a.step_dev) {
+    const uint64_t step = *a.step_dev;
+    a.step_lo = (uint32_t)step;
+    a.step_hi = (uint32_t)(step >> 32);
+  }
   for (int p = tid; p < N; p += nt) {
     const uint32_t n = pay[p];
     const int g = scan[p];
@@ -520,6 +529,8 @@ __global__ __launch_bounds__(1024) void sample_kernel(SampleArgs a) {
   if (tid == 0) {
     a.counts[0] = n_sel;
     a.counts[1] = G;
+    // (every thread read the counter before the barriers of the scans above)
+    if (a.step_dev && a.advance) *a.step_dev = (((uint64_t)a.step_hi << 32) | a.step_lo) + 1;
   }
 }
 
@@ -585,7 +596,8 @@ __global__ __launch_bounds__(256) void distance_key_kernel(const int32_t* __rest
 int run_sample(vardrop_ctx* ctx, const uint64_t* hash, int N,
                uint32_t gs, uint32_t ratio_num, uint32_t ratio_den,
                uint64_t seed, uint64_t step, const uint64_t* ext_keys,
-               int32_t* group_id, int32_t* sel, int32_t* counts, int32_t* counts_host, void* stream) {
+               int32_t* group_id, int32_t* sel, int32_t* counts, int32_t* counts_host, void* stream,
+               uint64_t* step_dev = nullptr, int advance = 0) {
   if (!ctx || !hash || !group_id || !sel || !counts) return VARDROP_EINVAL;
   if (N < 1) return VARDROP_EINVAL;
   if (ratio_den == 0 || ratio_num > ratio_den) return VARDROP_EINVAL;
@@ -613,6 +625,8 @@ int run_sample(vardrop_ctx* ctx, const uint64_t* hash, int N,
   a.step_lo = (uint32_t)step;
   a.step_hi = (uint32_t)(step >> 32);
   a.ext_keys = ext_keys;
+  a.step_dev = step_dev;
+  a.advance = advance;
   hipStream_t s = (hipStream_t)stream;
   const void* fn = E == 2 ? (const void*)sample_kernel<2> : (E == 4 ? (const void*)sample_kernel<4> : (const void*)sample_kernel<8>);
   if (lds > 65536)
@@ -639,6 +653,18 @@ extern "C" int vardrop_sample(vardrop_ctx* ctx, const uint64_t* hash, int N,
   (void)ws;
   (void)ws_bytes;
   return run_sample(ctx, hash, N, gs, ratio_num, ratio_den, seed, step, nullptr, group_id, sel, counts, counts_host, stream);
+}
+
+extern "C" int vardrop_sample_dev(vardrop_ctx* ctx, const uint64_t* hash, int N,
+                                  uint32_t gs, uint32_t ratio_num, uint32_t ratio_den,
+                                  uint64_t seed, uint64_t* step_dev, int advance,
+                                  int32_t* group_id, int32_t* sel, int32_t* counts,
+                                  void* ws, size_t ws_bytes, void* stream) {
+  (void)ws;
+  (void)ws_bytes;
+  if (!step_dev || !vd_aligned(step_dev, 8)) return VARDROP_EINVAL;
+  return run_sample(ctx, hash, N, gs, ratio_num, ratio_den, seed, 0, nullptr, group_id, sel, counts, nullptr, stream,
+                    step_dev, advance);
 }
 
 extern "C" size_t vardrop_sample_nearest_workspace_bytes(int N, int F) {

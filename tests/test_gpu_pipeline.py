@@ -98,6 +98,33 @@ def test_gather_fused_into_the_forward_pass(vd, ctx, name):
         assert all(torch.equal(u, v) for u, v in zip(g1, g2))
 
 
+def test_out_of_range_index_gives_a_zero_row_in_the_fused_gather(vd, ctx):
+    """An index outside [0, N) stands for a zero row, inside the forward kernel (short selections) as in the gather
+    kernel (long ones): the fused call equals the two separate calls, no row of another batch element is read,
+    and the zero rows attend like tokens of zeros."""
+    rng = np.random.default_rng(3)
+    B, N, d, H = 2, 300, 128, 2
+    tok = to_dev(rng.standard_normal((B, N, d)).astype(np.float32), torch.bfloat16)
+    W = [to_dev((rng.standard_normal((d, d)) / np.sqrt(d)).astype(np.float32), torch.bfloat16) for _ in range(4)]
+    for n in (40, 128, 200):
+        sel_np = np.sort(rng.choice(N, size=n, replace=False)).astype(np.int32)
+        bad = [0, n // 2, n - 1]
+        sel_np[bad] = [-1, N, 2 ** 31 - 1]
+        sel = to_dev(sel_np)
+        xs, y, _ = vd.vardrop_gather_attn_fwd(ctx, tok, sel, n, *W, H)
+        xs2 = vd.vardrop_gather(ctx, tok, sel, n)
+        y2, _ = vd.vardrop_attn_fwd(ctx, xs2, *W, H)
+        torch.cuda.synchronize()
+        assert xs[:, bad].eq(0).all() and torch.equal(xs, xs2)
+        assert torch.equal(y, y2)
+        clean = tok.clone()
+        sel_ok = sel_np.copy()
+        sel_ok[bad] = [0, 1, 2]
+        want_xs = clean[:, to_dev(sel_ok.astype(np.int64))]
+        want_xs[:, bad] = 0
+        assert torch.equal(xs, want_xs)
+
+
 def test_gather_fused_error_codes(vd, ctx):
     tok = torch.zeros((2, 10, 128), dtype=torch.bfloat16, device="cuda")
     W = [torch.zeros((128, 128), dtype=torch.bfloat16, device="cuda") for _ in range(4)]
