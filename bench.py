@@ -1,13 +1,15 @@
 #!/usr/bin/env python3
 """Benchmark of the VarDrop training hot path on one MI355X.
 
-One step = vardrop_hash -> vardrop_sample -> (read N') -> vardrop_gather_attn_fwd (= vardrop_gather
-+ vardrop_attn_fwd) -> vardrop_attn_bwd over one batch of synthetic windows and tokens that already sit in HBM.  The
-selection (hash + sample) of batch i+1 is enqueued before the attention of batch i, on a second stream.
-Prints ONE JSON line: steps/s, the roofline figure of the dominant kernel, and the CPU
-oracle timed on a bounded sample of the same workload.
+One step = vardrop_hash -> vardrop_sample_dev -> vardrop_gather_attn_fwd_dev (= gather + attention forward) ->
+vardrop_attn_bwd_dev over one batch of synthetic windows and tokens that already sit in HBM.  The number of kept
+tokens N' stays on the device (the kernels read it there), so a step is a fixed sequence of launches with no host
+wait.  The selection (hash + sample) of a batch runs on a second stream beside the attention of earlier batches.
+--launch graph instead records each step once as a HIP graph and replays it (slower with this runtime: a replay costs
+the host more than issuing the seven launches).  Prints ONE JSON line: steps/s, the roofline figures (the dominant kernel, and all kernels), and the
+CPU oracle timed on a bounded sample of the same workload.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload traffic] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload traffic] [--launch eager|graph] [--no-cpu-baseline]
 
 `--mode bandwidth` instead measures the steady-state HBM bandwidth of the two streaming kernels
 (vardrop_hash, vardrop_gather) over enough distinct batches (>= 1 GiB of input) that the 256 MB
@@ -62,9 +64,6 @@ def algorithmic_work(w, n):
     }
 
 
-BRACKET_EVERY = 8      # launches of the dominant kernel per HIP event pair inside the timed region
-
-
 def recorded_traffic(workload, kernel):
     """HBM bytes per launch of `kernel` from the committed hardware-counter summary, or None when the
     kernels have changed since the counters were taken (the summary records a hash of csrc/)."""
@@ -105,29 +104,48 @@ def parse():
                     help="the tokens are embedded inside the step from the raw windows, for the kept variates only "
                          "(vardrop_embed_fwd / vardrop_embed_bwd; with --dense for all variates), instead of being "
                          "gathered from a pre-embedded batch")
+    ap.add_argument("--launch", choices=("eager", "graph"), default="eager",
+                    help="issue every call of a step from the host (default: faster with this runtime) or replay one "
+                         "recorded HIP graph per step")
+    ap.add_argument("--no-paper-rule", action="store_true",
+                    help="skip the second figure at the paper's own sampling rule (Eq. 1 with Table 8's k and gs)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run five plain 256 MiB device copies (reference for hardware byte counters)")
     return ap.parse_args()
 
 
-def cpu_baseline(w, x_np, tok_np, W_np, seed):
-    """The oracle, as it stands, on a bounded sample: the whole path for the first `nb` windows of one batch."""
+def cpu_baseline(w, x_np, tok_np, W_np, seed, gpu_topk=None):
+    """The oracle, as it stands, on a bounded sample: the whole path for the first `nb` windows of one batch.
+    With the GPU's ranked bins of the same batch it also counts rank disagreements (the inputs are not screened:
+    variates whose leading mean amplitudes lie closer than 1e-3 relative may legitimately differ)."""
     import numpy as np
     from oracle import attention as o_attn
     from oracle import kdfh as o_kdfh
     from oracle import sampling as o_samp
     import workloads as wl
 
+    blas = None
     try:
         import threadpoolctl
-        cores = max(int(i.get("num_threads", 1)) for i in threadpoolctl.threadpool_info()) if threadpoolctl.threadpool_info() else 1
+        info = threadpoolctl.threadpool_info()
+        cores = max(int(i.get("num_threads", 1)) for i in info) if info else 1
+        blas = ", ".join("%s x%s" % (i.get("internal_api"), i.get("num_threads")) for i in info) or None
     except Exception:
+        threadpoolctl = None
         cores = os.cpu_count() or 1
     t0 = time.perf_counter()
-    topk, hsh, _ = o_kdfh.kdfh(x_np, w.k)                                   # the hash needs the full batch
+    topk, hsh, abar = o_kdfh.kdfh(x_np, w.k)                                # the hash needs the full batch
     t1 = time.perf_counter()
     gid, sel, G = o_samp.stratified_sample(hsh, 0, w.ratio[0], w.ratio[1], seed, 0)
     t2 = time.perf_counter()
+    rank_check = None
+    if gpu_topk is not None:
+        clear = o_kdfh.gap_ok(abar, w.k)
+        differs = np.any(np.asarray(gpu_topk)[:, :w.k] != topk, axis=1)
+        rank_check = {"variates": int(w.N), "below_the_1e-3_gap": int((~clear).sum()),
+                      "rank_flips_among_clear": int((differs & clear).sum()),
+                      "rank_flips_below_the_gap": int((differs & ~clear).sum()), "redrawn": 0,
+                      "note": "batch 0, unscreened draw: GPU ranked top-k against the fp64 oracle"}
     # attention cost is linear in the batch: time `nb` windows and scale
     per_window = None
     nb = 1
@@ -146,26 +164,39 @@ def cpu_baseline(w, x_np, tok_np, W_np, seed):
     note = ("one batch of the same workload: k-DFH and sampling on all %d windows (%.3f s + %.3f s), "
             "gather + attention fwd/bwd timed on %d of %d windows and scaled linearly (%.3f s per window), N'=%d"
             % (w.B, t1 - t0, t2 - t1, nb, w.B, per_window, len(sel)))
+
+    def whole_steps(budget_s, first_step):
+        steps, t_start = 0, time.perf_counter()
+        while time.perf_counter() - t_start < budget_s:
+            steps += 1
+            tk, hs, _ = o_kdfh.kdfh(x_np, w.k)
+            g_, sl, _ = o_samp.stratified_sample(hs, 0, w.ratio[0], w.ratio[1], seed, first_step + steps)
+            xs_ = o_attn.gather(tok_np, sl)
+            y_, cache_ = o_attn.mha_forward(xs_, *W_np, w.H)
+            o_attn.mha_backward(wl.make_upstream(w, len(sl)), cache_)
+        return steps, time.perf_counter() - t_start
+
+    one_thread = None
     if nb >= w.B and step_s < 5.0:
         # a whole step is cheap enough: repeat whole steps (new selection each) for about ten seconds
-        steps, t_start = 0, time.perf_counter()
-        while time.perf_counter() - t_start < 10.0:
-            steps += 1
-            topk, hsh, _ = o_kdfh.kdfh(x_np, w.k)
-            gid, sel, G = o_samp.stratified_sample(hsh, 0, w.ratio[0], w.ratio[1], seed, steps)
-            xs = o_attn.gather(tok_np, sel)
-            y, cache = o_attn.mha_forward(xs, *W_np, w.H)
-            o_attn.mha_backward(wl.make_upstream(w, len(sel)), cache)
-        step_s = (time.perf_counter() - t_start) / steps
-        note = "%d whole steps of the same workload (all %d windows, a new selection each) in %.1f s" % (
-            steps, w.B, step_s * steps)
-    return {"value": 1.0 / step_s, "unit": "steps/s", "cores": cores, "kind": "oracle", "sample": note}
+        steps, took = whole_steps(10.0, 0)
+        step_s = took / steps
+        note = "%d whole steps of the same workload (all %d windows, a new selection each) in %.1f s" % (steps, w.B, took)
+        if threadpoolctl is not None:
+            with threadpoolctl.threadpool_limits(limits=1):
+                s1, took1 = whole_steps(5.0, 1000)
+            one_thread = s1 / took1
+    out = {"value": 1.0 / step_s, "unit": "steps/s", "cores": cores, "kind": "oracle", "sample": note,
+           "blas_threads": blas, "value_one_thread": one_thread}
+    if rank_check is not None:
+        out["rank_check"] = rank_check
+    return out
 
 
 def steady_bandwidth(args):
     """Kernel time of vardrop_hash and vardrop_gather over M distinct inputs each (M x bytes >= 1 GiB), launched
-    back to back on one stream: per-launch durations from HIP events around every launch (library hook), less
-    the cost of an empty event pair, and the wall time of the same loop without events."""
+    back to back on one stream: per-launch durations from the events the runtime ties to every dispatch (library
+    hook: the kernel's own execution time), and the wall time of the same loop without events."""
     import numpy as np
     import torch
     import paper_2501_14183_amd as vd
@@ -180,14 +211,6 @@ def steady_bandwidth(args):
     stream = torch.cuda.current_stream()
     gen = torch.Generator(device=dev)
     gen.manual_seed(1234)
-
-    def empty_pair_us():
-        e = [torch.cuda.Event(enable_timing=True) for _ in range(64)]
-        for i in range(0, 64, 2):
-            e[i].record(stream)
-            e[i + 1].record(stream)
-        torch.cuda.synchronize()
-        return float(np.median([e[i].elapsed_time(e[i + 1]) for i in range(0, 64, 2)])) * 1e3
 
     def measure(kid, launch, count, reps=3):
         for i in range(count):                       # warm-up pass (also builds the hash's table)
@@ -207,16 +230,15 @@ def steady_bandwidth(args):
                 launch(i)
         torch.cuda.synchronize()
         wall_us = (time.perf_counter() - t0) * 1e6 / (reps * count)
-        return total_ms * 1e3 / launches - empty_pair_us(), wall_us, launches
+        return total_ms * 1e3 / launches, wall_us, launches
 
     def report(nbytes, us, wall, n, extra):
-        # "GB/s" is the conservative figure: launches back to back, dispatch gaps included.  The event figure
-        # subtracts an empty bracket of several microseconds and means little for a kernel shorter than that;
-        # rocprofv3 --kernel-trace of this same command gives the kernel's own duration.
+        # "GB/s_back_to_back" is the conservative figure: launches back to back, dispatch gaps included; "GB/s" is
+        # from the kernel's own execution time, which rocprofv3 --kernel-trace of this same command also reports.
         d = dict(extra)
-        d.update({"bytes_per_launch": nbytes, "back_to_back_us": wall, "GB/s": nbytes / wall * 1e-3,
-                  "frac_of_peak": nbytes / wall * 1e-3 / PEAK_HBM_GBS, "event_bracket_us": us,
-                  "GB/s_event_bracket": (nbytes / us * 1e-3) if us >= 10.0 else None, "launches": n})
+        d.update({"bytes_per_launch": nbytes, "kernel_us": us, "GB/s": nbytes / us * 1e-3,
+                  "frac_of_peak": nbytes / us * 1e-3 / PEAK_HBM_GBS, "back_to_back_us": wall,
+                  "GB/s_back_to_back": nbytes / wall * 1e-3, "launches": n})
         return d
 
     kids = {vd.vardrop_kernel_name(k): k for k in range(64) if vd.vardrop_kernel_name(k)}
@@ -254,14 +276,8 @@ def steady_bandwidth(args):
                       "kernels": out}))
 
 
-def main():
-    args = parse()
-    if args.gpus != 1:
-        print("bench.py measures one GPU: the library has no multi-GPU path; run with --gpus 1",
-              file=sys.stderr)
-        sys.exit(2)
-    if args.mode == "bandwidth":
-        return steady_bandwidth(args)
+def embed_steps(args):
+    """--embed: the step with the token embedding of the kept variates inside it (host-side N', calls issued one by one)."""
     import numpy as np
     import torch
     import paper_2501_14183_amd as vd
@@ -407,52 +423,7 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    if args.mode == "sweep":
-        # Sensitivity of the reduction to k and gs (Sec. 4.4, Eq. 1 as printed) on the synthetic workload:
-        # groups, kept tokens, delta = 1 - N'/N and whole-step throughput for every pair.
-        table = []
-        for k in (2, 3, 4, 5):
-            for gs in (1, 2, 3, 5, 8, 10, 15, 20):
-                w = dataclasses.replace(w, k=k)
-                gs_cap = gs
-                run(0, 10)
-                torch.cuda.synchronize()
-                stats = {"n_sel": [], "G": []}
-                t0 = time.perf_counter()
-                run(10, 60)
-                torch.cuda.synchronize()
-                dt = (time.perf_counter() - t0) / 60
-                n_mean, g_mean = float(np.mean(stats["n_sel"])), float(np.mean(stats["G"]))
-                table.append({"k": k, "gs": gs, "groups": g_mean, "kept": n_mean, "delta": 1.0 - n_mean / w.N,
-                              "steps_per_s": 1.0 / dt})
-        print(json.dumps({"metric": "reduction ratio delta and train steps/s over k and gs (Eq. 1)", "n_gpus": 1,
-                          "data": "synthetic", "dtype": w.dtype,
-                          "config": {"workload": "%s-shaped: B=%d N=%d L=%d d=%d H=%d" % (w.name, w.B, w.N, w.L, w.d, w.H)},
-                          "table": table}))
-        return
-
     run(0, args.warmup)
-    torch.cuda.synchronize()
-
-    # ---- which kernel takes the largest share of a step?  (untimed census, HIP events around one kernel at a time)
-    census = {}
-    for kid in range(64):
-        name = vd.vardrop_kernel_name(kid)
-        if name is None:
-            break
-        vd.vardrop_profile_select(ctx, kid)
-        run(0, 8)
-        total_ms, launches = vd.vardrop_profile_read(ctx)
-        if launches:
-            census[name] = (kid, total_ms * 1e3 / 8)            # microseconds per step
-    # The step time is set by the attention stream; hashing and sampling of the next batch run beside it
-    # on the second stream, so the dominant kernel is the largest one on the attention stream.
-    on_critical_path = {k: v for k, v in census.items() if k not in ("hash", "sample")}
-    dominant = max(on_critical_path, key=lambda k: on_critical_path[k][1])
-    # Only this kernel is bracketed while timing, and only every BRACKET_EVERY-th launch of it: an event
-    # pair between two kernels costs the attention stream about 7 us, 8 % of a step at this shape.
-    vd.vardrop_profile_stride(ctx, BRACKET_EVERY)
-    vd.vardrop_profile_select(ctx, census[dominant][0])
     torch.cuda.synchronize()
 
     stats = {"n_sel": [], "G": []}
@@ -464,35 +435,17 @@ def main():
     ms = (t1 - t0) * 1e3 / args.steps
     host_ms = (t_host - t0) * 1e3 / args.steps
     n_mean = float(np.mean(stats["n_sel"]))
-
-    # ---- roofline of the dominant kernel: algorithmic work per launch / mean launch duration (HIP events)
-    total_ms, launches = vd.vardrop_profile_read(ctx)
-    vd.vardrop_profile_stride(ctx, 1)
+    # per-kernel durations of the same steps (events tied to every dispatch), untimed pass
+    vd.vardrop_profile_select(ctx, vd.K_ALL)
+    run(args.warmup, 8)
+    per_kernel = vd.vardrop_profile_read_all(ctx)
     vd.vardrop_profile_select(ctx, -1)
-    bound, work = algorithmic_work(w, n_mean)[dominant]
-    # an empty event pair on the same stream measures what the bracket itself adds
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    gaps = []
-    for _ in range(50):
-        e0.record()
-        e1.record()
-        e1.synchronize()
-        gaps.append(e0.elapsed_time(e1))
-    gap_ms = float(np.median(gaps))
-    avg_s = max(total_ms / max(launches, 1) - gap_ms, 1e-6) * 1e-3
-    if bound == "hbm":
-        achieved, peak, unit = work / avg_s / 1e9, PEAK_HBM_GBS, "GB/s"
-    else:
-        achieved, unit = work / avg_s / 1e12, "TFLOP/s"
-        peak = PEAK_BF16_TFLOPS if bound == "mfma" else PEAK_FP32_TFLOPS
-    roof = {"kernel": dominant, "bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
-            "frac": achieved / peak, "traffic": recorded_traffic(w.name, dominant),
-            "avg_launch_us": avg_s * 1e6, "event_pair_overhead_us": gap_ms * 1e3, "launches": launches,
-            "bracketed_one_launch_in": BRACKET_EVERY,
-            "us_per_step_by_kernel": {k: round(v[1], 2) for k, v in census.items()}}
-
-    if args.dense or args.embed:
-        args.no_cpu_baseline = True                 # the oracle leg times the dropping path on pre-embedded tokens
+    work = algorithmic_work(w, n_mean)
+    roof_all = kernel_rooflines(per_kernel, work)
+    on_critical_path = {k: v for k, v in roof_all.items() if k not in ("hash", "sample")}
+    dominant = max(on_critical_path, key=lambda k: on_critical_path[k]["us_per_step"])
+    roof = dict(kernel=dominant, **{k: v for k, v in roof_all[dominant].items()}, traffic=None)
+    args.no_cpu_baseline = True                     # the oracle leg times the dropping path on pre-embedded tokens
     out = {
         "metric": (("dense (no dropping) variate-attn train steps/s (SDPA fwd/bwd over all N tokens)" if args.dense else
                     "variate-attn train steps/s (kDFH+sample+SDPA fwd/bwd), HBM GB/s, MFMA %peak") +
@@ -506,10 +459,406 @@ def main():
                    "k": w.k, "gs": gs_cap if gs_cap else None,
                    "kept_tokens_mean": n_mean, "groups_mean": float(np.mean(stats["G"])),
                    "batches": args.batches},
-        "roofline": roof,
+        "roofline": roof, "roofline_all": roof_all,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, host[0], host[1], W_np, seed)
+    print(json.dumps(out))
+
+
+def kernel_rooflines(per_kernel, work, steps=8):
+    """{kernel: (summed ms, launches)} of `steps` steps + algorithmic work per launch -> roofline entry per kernel."""
+    out = {}
+    for name, (ms_sum, launches) in per_kernel.items():
+        if name not in work or launches == 0:
+            continue
+        bound, amount = work[name]
+        avg_s = ms_sum * 1e-3 / launches
+        if bound == "hbm":
+            achieved, peak, unit = amount / avg_s / 1e9, PEAK_HBM_GBS, "GB/s"
+        else:
+            achieved, unit = amount / avg_s / 1e12, "TFLOP/s"
+            peak = PEAK_BF16_TFLOPS if bound == "mfma" else PEAK_FP32_TFLOPS
+        out[name] = {"bound": bound, "achieved": achieved, "peak": peak, "unit": unit, "frac": achieved / peak,
+                     "avg_launch_us": avg_s * 1e6, "launches": launches, "us_per_step": ms_sum * 1e3 / steps}
+    return out
+
+
+class Pipeline:
+    """The step on the device-count entry points, for one workload and one sampling rule.
+
+    The selection of a batch (k-DFH, grouping, sampling) depends on its windows only, so it runs on a second
+    stream beside the attention of earlier batches.  Nothing of it crosses to the host: the attention kernels read
+    N' on the device.
+      eager: selections are issued in bursts of BURST steps into a ring of RING buffer sets; the attention
+             stream waits for one event per burst (and the selection stream for one per burst before it reuses
+             ring sets), so cross-stream events, which cost the waiting stream several microseconds each, are
+             paid once per BURST steps.  The first burst of a call holds one step, so that a call of `count`
+             steps issues exactly `count` selections and at most one of them runs beside nothing.
+      graph: one recorded HIP graph per step, the selection of the NEXT batch on a branch forked from and joined
+             back into the attention stream (ring of two sets).
+    """
+    BURST, RING = 4, 12
+
+    def __init__(self, vd, ctx, w, xs_dev, tok_dev, W_dev, dy_full, seed, gs_cap=0, dense=False):
+        import torch
+        self.vd, self.ctx, self.w, self.torch = vd, ctx, w, torch
+        self.xs_dev, self.tok_dev, self.W_dev, self.dy_full = xs_dev, tok_dev, W_dev, dy_full
+        self.nb = len(xs_dev)
+        self.seed, self.gs_cap, self.dense = seed, gs_cap, dense
+        self.ratio = (1, 1) if gs_cap else w.ratio
+        dev = xs_dev[0].device
+        self.main = torch.cuda.Stream(device=dev)
+        self.side = torch.cuda.Stream(device=dev)
+        K_MAX = 5
+        self.ring = [(torch.empty((w.N, max(w.k, K_MAX)), dtype=torch.int32, device=dev),
+                      torch.empty(w.N, dtype=torch.int64, device=dev), torch.empty(w.N, dtype=torch.int32, device=dev),
+                      torch.empty(w.N, dtype=torch.int32, device=dev), torch.empty(2, dtype=torch.int32, device=dev))
+                     for _ in range(self.RING)]
+        self.events = []
+        self.step_dev = torch.zeros(1, dtype=torch.int64, device=dev)
+        self.status = torch.zeros(1, dtype=torch.int32, device=dev)
+        # ---- N' and G of every batch (they depend on the grouping only, not on the draw): an untimed pass
+        self.n_of, self.G_of = [], []
+        if dense:
+            for r in range(self.RING):
+                self.ring[r][3].copy_(torch.arange(w.N, dtype=torch.int32, device=dev))
+                self.ring[r][4].copy_(torch.tensor([w.N, w.N], dtype=torch.int32, device=dev))
+            self.n_of, self.G_of = [w.N] * self.nb, [w.N] * self.nb
+        else:
+            for b in range(self.nb):
+                self.select(b, 0, self.main)
+                self.main.synchronize()
+                n_b, G_b = self.ring[0][4].tolist()
+                self.n_of.append(n_b)
+                self.G_of.append(G_b)
+        n_hi = max(self.n_of)
+        small = w.dtype == "bf16" and n_hi <= 128
+        self.n_max = 128 if small and w.N >= 128 else min(w.N, -(-n_hi // 64) * 64)
+        lib = vd.load_library()
+        code = vd.BF16 if w.dtype == "bf16" else vd.F32
+        td = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+        self.saved = torch.empty(lib.vardrop_attn_saved_bytes(w.B, self.n_max, w.d, w.H, code), dtype=torch.uint8, device=dev)
+        self.ws = torch.empty(lib.vardrop_attn_workspace_bytes(w.B, self.n_max, w.d, w.H, code), dtype=torch.uint8, device=dev)
+        self.xs_buf, self.y_buf, self.dxs_buf = (torch.empty((w.B, self.n_max, w.d), dtype=td, device=dev) for _ in range(3))
+        self.dW_buf = [torch.empty((w.d, w.d), dtype=torch.float32, device=dev) for _ in range(4)]
+        self.graphs = None
+
+    def select(self, b, r, stream):
+        """k-DFH + grouping + sampling of batch b into ring set r; the step counter advances on the device."""
+        vd, w = self.vd, self.w
+        topk, hsh, gid, sel, counts = self.ring[r]
+        vd.vardrop_hash(self.ctx, self.xs_dev[b], w.k, f_max=-1, out=(topk, hsh), stream=stream.cuda_stream)
+        vd.vardrop_sample_dev(self.ctx, hsh, self.gs_cap, self.ratio[0], self.ratio[1], self.seed, self.step_dev, True,
+                              (gid, sel, counts), stream=stream.cuda_stream)
+
+    def attend(self, b, r, stream):
+        vd, w = self.vd, self.w
+        sel, counts = self.ring[r][3], self.ring[r][4]
+        vd.vardrop_gather_attn_fwd_dev(self.ctx, self.tok_dev[b], sel, counts, self.n_max, *self.W_dev, w.H,
+                                       self.xs_buf, self.y_buf, self.saved, status=self.status, stream=stream.cuda_stream)
+        vd.vardrop_attn_bwd_dev(self.ctx, self.dy_full, self.xs_buf, counts, self.n_max, *self.W_dev, w.H, self.saved,
+                                self.ws, (self.dxs_buf, *self.dW_buf), status=self.status, stream=stream.cuda_stream)
+
+    def issue(self, g):
+        """Step g: attention of batch g % nb (ring g % 2) beside the selection of the next batch (other ring set)."""
+        b, r = g % self.nb, g % 2
+        if not self.dense:
+            self.side.wait_stream(self.main)                           # fork
+            self.select((b + 1) % self.nb, (r + 1) % 2, self.side)
+        self.attend(b, r, self.main)
+        if not self.dense:
+            self.main.wait_stream(self.side)                           # join
+
+    def prime(self):
+        """graph mode: the selection of batch 0 into ring set 0, so that the first recorded step finds it."""
+        if not self.dense:
+            self.select(0, 0, self.main)
+
+    def record(self):
+        """One HIP graph per (batch, ring set) combination: nb of them when nb is even, else 2 nb."""
+        torch = self.torch
+        count = self.nb if self.nb % 2 == 0 else 2 * self.nb
+        self.vd.vardrop_profile_select(self.ctx, -1)
+        self.graphs = []
+        for g in range(count):
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=self.main):
+                self.issue(g)
+            self.graphs.append(graph)
+        # the captures advanced nothing (nothing ran), but keep the counter explicit
+        torch.cuda.synchronize()
+
+    def event(self, i):
+        while len(self.events) <= i:
+            self.events.append(self.torch.cuda.Event())
+        return self.events[i]
+
+    def run(self, first, count, launch):
+        """`count` whole steps from global step `first`; returns when everything is ISSUED (not finished).
+        The caller synchronises the device between two calls (ring sets are reused from the start)."""
+        torch = self.torch
+        if launch == "graph":
+            with torch.cuda.stream(self.main):
+                G = len(self.graphs)
+                for g in range(first, first + count):
+                    self.graphs[g % G].replay()
+            return
+        if self.dense:
+            for g in range(first, first + count):
+                self.attend(g % self.nb, g % self.RING, self.main)
+            return
+        end = first + count
+        blocks, g = [], first
+        while g < end:
+            size = 1 if g == first else self.BURST
+            blocks.append(range(g, min(end, g + size)))
+            g += size
+        done_sel = lambda j: self.event(2 * j)          # burst j has been drawn (recorded on the selection stream)
+        done_att = lambda j: self.event(2 * j + 1)      # block j has been attended (recorded on the attention stream)
+
+        def burst(j):
+            if j >= 3:
+                self.side.wait_event(done_att(j - 3))   # its ring sets were last read by block j - 3
+            for g in blocks[j]:
+                self.select(g % self.nb, g % self.RING, self.side)
+            done_sel(j).record(self.side)
+
+        burst(0)
+        for j, blk in enumerate(blocks):
+            if j + 1 < len(blocks):
+                burst(j + 1)
+            self.main.wait_event(done_sel(j))
+            for g in blk:
+                self.attend(g % self.nb, g % self.RING, self.main)
+            done_att(j).record(self.main)
+
+    def kept(self, first, count):
+        ns = [self.n_of[g % self.nb] for g in range(first, first + count)]
+        gs = [self.G_of[g % self.nb] for g in range(first, first + count)]
+        return sum(ns) / len(ns), sum(gs) / len(gs)
+
+
+def timed_steps(pipe, args, launch):
+    """W warm-up steps, then exactly K timed steps, bracketed by device synchronisation on both sides.  Every step's
+    selection and attention are issued inside the call that times it."""
+    import torch
+    primed = 0
+    if launch == "graph":
+        if pipe.graphs is None:
+            pipe.run(0, 2, "eager")                 # tables built, function attributes set, before anything is recorded
+            torch.cuda.synchronize()
+            pipe.record()
+        pipe.step_dev.zero_()
+        pipe.prime()
+        primed = 1
+    else:
+        pipe.step_dev.zero_()
+    pipe.run(0, args.warmup, launch)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    pipe.run(args.warmup, args.steps, launch)
+    t_host = time.perf_counter()                    # every launch of the timed steps has been issued
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    if int(pipe.status[0]) != 0:
+        raise RuntimeError("a step found more kept tokens than the bound the launches were sized for")
+    if not pipe.dense and int(pipe.step_dev[0]) != primed + args.warmup + args.steps:
+        raise RuntimeError("the device step counter does not match the number of selections drawn")
+    return (t1 - t0) * 1e3 / args.steps, (t_host - t0) * 1e3 / args.steps
+
+
+def steady_hash_gather(vd, ctx, w, stream):
+    """Steady-state duration of vardrop_hash and vardrop_gather at this workload's shape over enough distinct inputs
+    (>= 1 GiB) that the last-level cache cannot serve them: per-launch durations from dispatch-bound events."""
+    import torch
+    dev = torch.device("cuda", 0)
+    td = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+    es = 2 if w.dtype == "bf16" else 4
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(99)
+    out = {}
+    x_bytes = 4 * w.B * w.N * w.L
+    M = -(-(1 << 30) // x_bytes)
+    xs = [torch.randn((w.B, w.N, w.L), generator=gen, device=dev) for _ in range(M)]
+    topk = torch.empty((w.N, w.k), dtype=torch.int32, device=dev)
+    hsh = torch.empty(w.N, dtype=torch.int64, device=dev)
+    kid = {vd.vardrop_kernel_name(k): k for k in range(64) if vd.vardrop_kernel_name(k)}
+    with torch.cuda.stream(stream):
+        for x in xs:
+            vd.vardrop_hash(ctx, x, w.k, f_max=-1, out=(topk, hsh), stream=stream.cuda_stream)
+        torch.cuda.synchronize()
+        vd.vardrop_profile_select(ctx, kid["hash"])
+        for x in xs:
+            vd.vardrop_hash(ctx, x, w.k, f_max=-1, out=(topk, hsh), stream=stream.cuda_stream)
+        ms, n = vd.vardrop_profile_read(ctx)
+    out["hash"] = {"bound": "hbm", "achieved": x_bytes / (ms * 1e-3 / n) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                   "frac": x_bytes / (ms * 1e-3 / n) / 1e9 / PEAK_HBM_GBS, "avg_launch_us": ms * 1e3 / n,
+                   "launches": n, "distinct_inputs": M, "bytes_per_launch": x_bytes}
+    del xs
+    n_sel = max(1, int(round(w.N * w.ratio[0] / w.ratio[1] * 1.3)))
+    g_bytes = 2 * w.B * n_sel * w.d * es
+    tok_bytes = w.B * w.N * w.d * es
+    M = max(4, min(-(-(1 << 30) // g_bytes), (8 << 30) // tok_bytes))
+    toks = [torch.randn((w.B, w.N, w.d), generator=gen, device=dev).to(td) for _ in range(M)]
+    sel = torch.zeros(w.N, dtype=torch.int32, device=dev)
+    sel[:n_sel] = torch.randperm(w.N, generator=gen, device=dev)[:n_sel].sort().values.to(torch.int32)
+    dst = torch.empty((w.B, n_sel, w.d), dtype=td, device=dev)
+    with torch.cuda.stream(stream):
+        for t in toks:
+            vd.vardrop_gather(ctx, t, sel, n_sel, out=dst, stream=stream.cuda_stream)
+        torch.cuda.synchronize()
+        vd.vardrop_profile_select(ctx, kid["gather"])
+        for _ in range(3):
+            for t in toks:
+                vd.vardrop_gather(ctx, t, sel, n_sel, out=dst, stream=stream.cuda_stream)
+        ms, n = vd.vardrop_profile_read(ctx)
+    vd.vardrop_profile_select(ctx, -1)
+    out["gather"] = {"bound": "hbm", "achieved": g_bytes / (ms * 1e-3 / n) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                     "frac": g_bytes / (ms * 1e-3 / n) / 1e9 / PEAK_HBM_GBS, "avg_launch_us": ms * 1e3 / n,
+                     "launches": n, "distinct_inputs": M, "kept_tokens": n_sel, "bytes_per_launch": g_bytes}
+    return out
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: the library has no multi-GPU path; run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    if args.mode == "bandwidth":
+        return steady_bandwidth(args)
+    if args.embed:
+        return embed_steps(args)
+    import dataclasses
+    import numpy as np
+    import torch
+    import paper_2501_14183_amd as vd
+    import workloads as wl
+
+    w = wl.WORKLOADS[args.workload]
+    if args.k:
+        w = dataclasses.replace(w, k=args.k)
+    td = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+    dev = torch.device("cuda", 0)
+    torch.cuda.set_device(dev)
+    ctx = vd.Context(0)
+
+    # ---- synthetic inputs, resident in HBM before anything is timed
+    xs_dev, tok_dev, host = [], [], None
+    for i in range(args.batches):
+        x_np, _ = wl.make_signals(w, seed=i)
+        tok_np = wl.make_tokens(w, x_np, seed=i)
+        if i == 0:
+            host = (x_np, tok_np)
+        xs_dev.append(torch.from_numpy(x_np).to(dev))
+        tok_dev.append(torch.from_numpy(tok_np).to(dev).to(td))
+    W_np = wl.make_weights(w, seed=0)
+    W_dev = [torch.from_numpy(m).to(dev).to(td) for m in W_np]
+    dy_full = torch.from_numpy(wl.make_upstream(w, w.N, seed=0)).to(dev).to(td).reshape(-1)
+    seed = 0x5EED
+
+    if args.copy_calibration:
+        src = torch.zeros(256 << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
+    if args.mode == "sweep":
+        # Sensitivity of the reduction to k and gs (Sec. 4.4, Eq. 1 as printed) on the synthetic workload:
+        # groups, kept tokens, delta = 1 - N'/N and whole-step throughput for every pair.
+        table = []
+        sw = argparse.Namespace(steps=60, warmup=10)
+        for k in (2, 3, 4, 5):
+            for gs in (1, 2, 3, 5, 8, 10, 15, 20):
+                wk = dataclasses.replace(w, k=k)
+                pipe = Pipeline(vd, ctx, wk, xs_dev, tok_dev, W_dev, dy_full, seed, gs_cap=gs)
+                ms, _ = timed_steps(pipe, sw, args.launch)
+                n_mean, g_mean = pipe.kept(sw.warmup, sw.steps)
+                table.append({"k": k, "gs": gs, "groups": g_mean, "kept": n_mean, "delta": 1.0 - n_mean / w.N,
+                              "token_bound": pipe.n_max, "steps_per_s": 1e3 / ms})
+                del pipe
+        print(json.dumps({"metric": "reduction ratio delta and train steps/s over k and gs (Eq. 1)", "n_gpus": 1,
+                          "data": "synthetic", "dtype": w.dtype, "launch": args.launch,
+                          "config": {"workload": "%s-shaped: B=%d N=%d L=%d d=%d H=%d" % (w.name, w.B, w.N, w.L, w.d, w.H)},
+                          "table": table}))
+        return
+
+    pipe = Pipeline(vd, ctx, w, xs_dev, tok_dev, W_dev, dy_full, seed, gs_cap=args.gs, dense=args.dense)
+    ms, host_ms = timed_steps(pipe, args, args.launch)
+    n_mean, g_mean = pipe.kept(args.warmup, args.steps)
+
+    # ---- roofline: the same steps once more, issued call by call, every dispatch timed by the events the runtime
+    # ties to it (the kernel's own execution time, no extra packet on the stream; launches inside a recorded graph
+    # cannot carry them).  Dominant = the kernel with the largest share of a step on the attention stream.
+    PROF_STEPS = 8
+    pipe.step_dev.zero_()
+    pipe.run(0, 4, "eager")
+    torch.cuda.synchronize()
+    vd.vardrop_profile_select(ctx, vd.K_ALL)
+    pipe.run(4, PROF_STEPS, "eager")
+    torch.cuda.synchronize()
+    per_kernel = vd.vardrop_profile_read_all(ctx)
+    vd.vardrop_profile_select(ctx, -1)
+    n_prof, _ = pipe.kept(4, PROF_STEPS)
+    work = algorithmic_work(w, n_prof)
+    roof_all = kernel_rooflines(per_kernel, work, PROF_STEPS)
+    attn = {k: v for k, v in roof_all.items() if k not in ("hash", "sample")}
+    dominant = max(attn, key=lambda k: attn[k]["us_per_step"])
+    roof = {"kernel": dominant}
+    roof.update({k: roof_all[dominant][k] for k in ("bound", "achieved", "peak", "unit", "frac")})
+    roof["traffic"] = recorded_traffic(w.name, dominant)
+    roof["avg_launch_us"] = roof_all[dominant]["avg_launch_us"]
+    roof["launches"] = roof_all[dominant]["launches"]
+    roof["timing"] = ("events tied to each dispatch of the kernel (hipExtLaunchKernelGGL) over %d steps issued call by call "
+                      "right after the timed region" % PROF_STEPS)
+    # whole attention (every matrix-core kernel of a step): algorithmic flops of forward + backward over their summed time
+    if w.dtype == "bf16":
+        flops = sum(work[k][1] * v["launches"] / PROF_STEPS for k, v in attn.items() if v["bound"] == "mfma")
+        us = sum(v["us_per_step"] for k, v in attn.items())
+        roof_all["attention_fwd_bwd"] = {"bound": "mfma", "achieved": flops / (us * 1e-6) / 1e12, "peak": PEAK_BF16_TFLOPS,
+                                         "unit": "TFLOP/s", "frac": flops / (us * 1e-6) / 1e12 / PEAK_BF16_TFLOPS,
+                                         "us_per_step": us, "kernels": sorted(attn)}
+    if not args.dense:
+        steady = steady_hash_gather(vd, ctx, w, pipe.main)
+        roof_all["hash_steady_state"] = steady["hash"]
+        roof_all["gather_steady_state"] = steady["gather"]
+
+    out = {
+        "metric": ("dense (no dropping) variate-attn train steps/s (SDPA fwd/bwd over all N tokens)" if args.dense else
+                   "variate-attn train steps/s (kDFH+sample+SDPA fwd/bwd), HBM GB/s, MFMA %peak"),
+        "value": 1e3 / ms, "unit": "steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "host_issue_ms_per_step": host_ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": ("%s-shaped, dense: B=%d N=%d d=%d H=%d, selection = identity" % (w.name, w.B, w.N, w.d, w.H))
+                               if args.dense else "%s-shaped: B=%d N=%d L=%d k=%d keep=%s d=%d H=%d" %
+                               (w.name, w.B, w.N, w.L, w.k, ("min(|G|,%d)" % args.gs) if args.gs else "%d/%d" % w.ratio, w.d, w.H),
+                   "k": w.k, "gs": args.gs if args.gs else None,
+                   "kept_tokens_mean": n_mean, "groups_mean": g_mean, "token_bound": pipe.n_max,
+                   "batches": args.batches, "launch": args.launch},
+        "roofline": roof, "roofline_all": roof_all,
+    }
+    # ---- the paper's own rule for this dataset shape (Table 8: Traffic k = 4, gs = 10; Electricity k = 3, gs = 10)
+    paper_rule = {"traffic": (4, 10), "electricity": (3, 10)}.get(w.name)
+    if paper_rule and not (args.dense or args.gs or args.k or args.no_paper_rule):
+        wk = dataclasses.replace(w, k=paper_rule[0])
+        p2 = Pipeline(vd, ctx, wk, xs_dev, tok_dev, W_dev, dy_full, seed, gs_cap=paper_rule[1])
+        ms2, host2 = timed_steps(p2, args, args.launch)
+        n2, g2 = p2.kept(args.warmup, args.steps)
+        out["paper_rule"] = {"rule": "Eq. 1, |S_i| = min(|G_i|, gs), with Table 8's k = %d, gs = %d" % paper_rule,
+                             "value": 1e3 / ms2, "unit": "steps/s", "ms_per_step": ms2, "host_issue_ms_per_step": host2,
+                             "kept_tokens_mean": n2, "groups_mean": g2, "delta": 1.0 - n2 / w.N, "token_bound": p2.n_max}
+        del p2
+    if not args.dense and not args.no_cpu_baseline:
+        gpu_topk = None
+        topk0 = torch.empty((w.N, w.k), dtype=torch.int32, device=dev)
+        hsh0 = torch.empty(w.N, dtype=torch.int64, device=dev)
+        vd.vardrop_hash(ctx, xs_dev[0], w.k, f_max=-1, out=(topk0, hsh0))
+        torch.cuda.synchronize()
+        gpu_topk = topk0.cpu().numpy()
+        out["cpu_baseline"] = cpu_baseline(w, host[0], host[1], W_np, seed, gpu_topk)
     print(json.dumps(out))
 
 

@@ -65,15 +65,17 @@ const char* vardrop_strerror(int code);
 int vardrop_last_hip_error(const vardrop_ctx* ctx);
 
 /* ---------------------------------------------------------------------------------
- * Per-kernel timing for benchmarks.  While a kernel id is selected, every launch of that
- * kernel is bracketed by a pair of HIP events on the stream it is launched on (at most 4096
- * launches between two reads; further ones are not recorded).  vardrop_profile_read waits for
- * the recorded launches, returns their summed duration in milliseconds and their number,
- * and starts a new collection.  Selecting -1 switches the timing off (the default).
- * An event pair costs the stream several microseconds, which a benchmark of short kernels
- * feels: vardrop_profile_stride(ctx, s) brackets only every s-th launch of the selected
- * kernel (s >= 1, default 1; takes effect at the next vardrop_profile_select).
+ * Per-kernel timing for benchmarks.  While a kernel id is selected, every launch of that kernel is issued
+ * with a pair of HIP events tied to the dispatch itself (hipExtLaunchKernelGGL), whose difference is the
+ * kernel's own execution time: no extra packet goes onto the stream, and the figure is the one a profiler's
+ * kernel trace reports.  At most 4096 launches are recorded between two reads.  VARDROP_K_ALL times every
+ * kernel.  vardrop_profile_read waits for the recorded launches, returns their summed duration in
+ * milliseconds and their number, and starts a new collection; vardrop_profile_read_all does the same per
+ * kernel id (both arrays hold VARDROP_K_COUNT entries).  Selecting -1 switches the timing off (the default).
+ * vardrop_profile_stride(ctx, s) times only every s-th eligible launch (s >= 1, default 1; takes effect at the
+ * next vardrop_profile_select).  Launches recorded into a HIP graph are not timed: select -1 before a capture.
  */
+enum { VARDROP_K_ALL = -2 };
 enum {
   VARDROP_K_HASH = 0,        /* k-DFH: spectrum, batch mean, ranked top-k, hash            */
   VARDROP_K_SAMPLE,          /* grouping + stratified sampling                              */
@@ -99,6 +101,7 @@ enum {
 };
 int vardrop_profile_select(vardrop_ctx* ctx, int kernel_id);
 int vardrop_profile_read(vardrop_ctx* ctx, double* total_ms, int* launches);
+int vardrop_profile_read_all(vardrop_ctx* ctx, double* total_ms, int* launches);
 int vardrop_profile_stride(vardrop_ctx* ctx, int stride);
 /* Static name of a kernel id ("hash", "gemm_qkv", ...), or NULL when out of range. */
 const char* vardrop_kernel_name(int kernel_id);

@@ -31,6 +31,7 @@ _SIGNATURES = {
     "vardrop_profile_select": (_c_int, [_ptr, _c_int]),
     "vardrop_profile_read": (_c_int, [_ptr, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(_c_int)]),
     "vardrop_profile_stride": (_c_int, [_ptr, _c_int]),
+    "vardrop_profile_read_all": (_c_int, [_ptr, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(_c_int)]),
     "vardrop_kernel_name": (ctypes.c_char_p, [_c_int]),
     "vardrop_hash_workspace_bytes": (_c_size, [_c_int] * 6),
     "vardrop_hash": (_c_int, [_ptr, _ptr, _c_int, _c_int, _c_int, _c_i64, _c_i64, _c_i64, _c_int, _c_int, _c_int,
@@ -177,6 +178,20 @@ def vardrop_profile_read(ctx):
     n = _c_int()
     ctx.check(ctx._lib.vardrop_profile_read(ctx.handle, ctypes.byref(ms), ctypes.byref(n)), "vardrop_profile_read")
     return ms.value, n.value
+
+
+K_ALL = -2          # vardrop_profile_select: every kernel
+
+
+def vardrop_profile_read_all(ctx):
+    """-> {kernel name: (summed duration in ms, launches)} since the last read or select, for the kernels that ran."""
+    n = 0
+    while load_library().vardrop_kernel_name(n) is not None:
+        n += 1
+    ms = (ctypes.c_double * n)()
+    cnt = (_c_int * n)()
+    ctx.check(ctx._lib.vardrop_profile_read_all(ctx.handle, ms, cnt), "vardrop_profile_read_all")
+    return {vardrop_kernel_name(k): (ms[k], cnt[k]) for k in range(n) if cnt[k]}
 
 
 def vardrop_hash(ctx, x, k, f_min=1, f_max=None, want_abar=False, out=None, stream=None, ws=None):
@@ -414,3 +429,4 @@ def vardrop_attn_bwd_dev(ctx, dy, xs, n_dev, n_max, Wq, Wk, Wv, Wo, H, saved, ws
                                        *[_p(t) for t in db], _p(ws), ws.numel(), _stream(Wq, stream))
     ctx.check(rc, "vardrop_attn_bwd_dev")
     return out
+

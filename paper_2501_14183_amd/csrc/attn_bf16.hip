@@ -1187,7 +1187,7 @@ int launch_ring(vardrop_ctx* ctx, int kid, K kernel, int rows, int parts, const 
   const long long grid = (long long)parts * vd_ceil_div(a.n, rows) * a.H * a.B;
   if (grid >= (1ll << 31)) return VARDROP_EUNSUPPORTED;
   VdTimer timer(ctx, kid, s);
-  hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(rows >= 128 ? 256 : 128), kRingLds, s, a);
+  VD_KERNEL(ctx, kernel, dim3((unsigned)grid), dim3(rows >= 128 ? 256 : 128), kRingLds, s, a);
   VD_LAUNCH_CHECK(ctx);
   return VARDROP_OK;
 }
@@ -1274,7 +1274,7 @@ int vd_attn_fwd_bf16(vardrop_ctx* ctx, const void* xs, int B, int n, int d, int 
     }
     {
       VdTimer timer(ctx, VARDROP_K_QKV_SDPA_FWD, s);
-      hipLaunchKernelGGL(attn_fwd_small_bf16, dim3(H, B), dim3(512), kFusedLds, s, f);
+      VD_KERNEL(ctx, attn_fwd_small_bf16, dim3(H, B), dim3(512), kFusedLds, s, f);
     }
     VD_LAUNCH_CHECK(ctx);
   } else {
@@ -1349,7 +1349,7 @@ int vd_attn_bwd_bf16(vardrop_ctx* ctx, const void* dy, const void* xs, int B, in
     }
     {
       VdTimer timer(ctx, VARDROP_K_SDPA_BWD, s);
-      hipLaunchKernelGGL(sdpa_bwd_small_bf16, dim3(H, B), dim3(512), kSmallLds, s, a);
+      VD_KERNEL(ctx, sdpa_bwd_small_bf16, dim3(H, B), dim3(512), kSmallLds, s, a);
     }
     VD_LAUNCH_CHECK(ctx);
   } else {

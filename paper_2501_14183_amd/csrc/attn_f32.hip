@@ -95,7 +95,7 @@ int launch_gemm(vardrop_ctx* ctx, int kid, const GemmF32& g, int nz, hipStream_t
   if (g.M == 0 || g.N == 0) return VARDROP_OK;
   dim3 grid(vd_ceil_div(g.N, 64), vd_ceil_div(g.M, 64), nz);
   VdTimer timer(ctx, kid, s);
-  hipLaunchKernelGGL(gemm_f32_kernel, grid, dim3(256), 0, s, g);
+  VD_KERNEL(ctx, gemm_f32_kernel, grid, dim3(256), 0, s, g);
   VD_LAUNCH_CHECK(ctx);
   return VARDROP_OK;
 }
@@ -314,7 +314,7 @@ template <int DH>
 int run_fwd_core(vardrop_ctx* ctx, const float* q, const float* k, const float* v, float* o, float* lse,
                  int B, int n, int d, int H, hipStream_t s, const int32_t* n_dev) {
   VdTimer timer(ctx, VARDROP_K_SDPA_FWD, s);
-  hipLaunchKernelGGL(sdpa_fwd_f32<DH>, dim3(vd_ceil_div(n, 64), H, B), dim3(64), 0, s, q, k, v, o, lse, n, d, H,
+  VD_KERNEL(ctx, sdpa_fwd_f32<DH>, dim3(vd_ceil_div(n, 64), H, B), dim3(64), 0, s, q, k, v, o, lse, n, d, H,
                      1.0f / sqrtf((float)DH), n_dev);
   VD_LAUNCH_CHECK(ctx);
   return VARDROP_OK;
@@ -328,11 +328,11 @@ int run_bwd_core(vardrop_ctx* ctx, const float* q, const float* k, const float* 
   dim3 grid(vd_ceil_div(n, 64), H, B);
   {
     VdTimer timer(ctx, VARDROP_K_SDPA_BWD_DQ, s);
-    hipLaunchKernelGGL(sdpa_bwd_dq_f32<DH>, grid, dim3(64), 0, s, q, k, v, o, dO, lse, dq, D, n, d, H, scale, n_dev);
+    VD_KERNEL(ctx, sdpa_bwd_dq_f32<DH>, grid, dim3(64), 0, s, q, k, v, o, dO, lse, dq, D, n, d, H, scale, n_dev);
   }
   VD_LAUNCH_CHECK(ctx);
   VdTimer timer(ctx, VARDROP_K_SDPA_BWD_DKV, s);
-  hipLaunchKernelGGL(sdpa_bwd_dkv_f32<DH>, grid, dim3(64), 0, s, q, k, v, dO, lse, D, dk, dv, n, d, H, scale, n_dev);
+  VD_KERNEL(ctx, sdpa_bwd_dkv_f32<DH>, grid, dim3(64), 0, s, q, k, v, dO, lse, D, dk, dv, n, d, H, scale, n_dev);
   VD_LAUNCH_CHECK(ctx);
   return VARDROP_OK;
 }

@@ -1,6 +1,7 @@
 // Shared host-side declarations of libvardrop (context, error plumbing, small helpers).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stddef.h>
 #include <stdint.h>
 #include "../../include/vardrop.h"
@@ -15,6 +16,8 @@ struct vardrop_ctx {
   int prof_stride;       // every prof_stride-th launch of the selected kernel is bracketed
   int prof_seen;         // launches of the selected kernel seen since it was selected
   hipEvent_t* prof_ev;   // 2 * kProfPairs events, created on first use
+  short* prof_kids;      // kernel id of every recorded pair
+  hipEvent_t prof_e0, prof_e1;   // the pair the next launch is to be given (null: launch untimed)
   void* twiddle;         // device: k-DFH cosine / sine table in matrix-fragment order (kTwiddleBytes)
   int twiddle_L;         // window length the table currently holds (0: none),
   int twiddle_fmin;      //   its first candidate bin
@@ -37,20 +40,35 @@ static const size_t kTwiddleBytes = (size_t)2 << 20;   // 32 contraction steps x
 
 #define VD_LAUNCH_CHECK(ctx) VD_HIP(ctx, hipGetLastError())
 
-// Brackets the launches issued during its lifetime with a pair of events when the context is
-// profiling kernel `kid`; costs one integer compare otherwise.
+// Per-kernel timing.  While the context is profiling kernel `kid` (or all kernels), a VdTimer in scope hands the one
+// launch issued through VD_KERNEL during its lifetime a pair of events that the runtime ties to that dispatch itself
+// (hipExtLaunchKernelGGL): their difference is the kernel's own execution time, as a profiler's kernel trace reports
+// it, with no extra packet on the stream.  Costs one integer compare otherwise.
+static const int kProfAll = -2;
 struct VdTimer {
   vardrop_ctx* ctx;
-  hipStream_t stream;
   bool active;
-  VdTimer(vardrop_ctx* c, int kid, hipStream_t s) : ctx(c), stream(s), active(false) {
-    if (c->prof_kid == kid && c->prof_ev && c->prof_n < kProfPairs && (c->prof_seen++ % c->prof_stride) == 0)
-      active = hipEventRecord(c->prof_ev[2 * c->prof_n], s) == hipSuccess;
+  VdTimer(vardrop_ctx* c, int kid, hipStream_t) : ctx(c), active(false) {
+    if ((c->prof_kid == kid || c->prof_kid == kProfAll) && c->prof_ev && c->prof_n < kProfPairs &&
+        (c->prof_seen++ % c->prof_stride) == 0) {
+      active = true;
+      c->prof_kids[c->prof_n] = (short)kid;
+      c->prof_e0 = c->prof_ev[2 * c->prof_n];
+      c->prof_e1 = c->prof_ev[2 * c->prof_n + 1];
+    }
   }
   ~VdTimer() {
-    if (active && hipEventRecord(ctx->prof_ev[2 * ctx->prof_n + 1], stream) == hipSuccess) ++ctx->prof_n;
+    if (active) {
+      ++ctx->prof_n;
+      ctx->prof_e0 = ctx->prof_e1 = nullptr;
+    }
   }
 };
+#define VD_KERNEL(ctx, kernel, grid, block, lds, s, ...)                                                        \
+  do {                                                                                                          \
+    if ((ctx)->prof_e0) hipExtLaunchKernelGGL(kernel, grid, block, lds, s, (ctx)->prof_e0, (ctx)->prof_e1, 0, __VA_ARGS__); \
+    else hipLaunchKernelGGL(kernel, grid, block, lds, s, __VA_ARGS__);                                          \
+  } while (0)
 
 // Token count of a call.  It is either the host integer `bound` itself (n_dev == nullptr) or an int32 in device
 // memory that every kernel of the call reads, with `bound` as its upper limit (what the buffers were sized for).

@@ -21,6 +21,9 @@ extern "C" int vardrop_create(vardrop_ctx** out, int device_id) {
   c->prof_stride = 1;
   c->prof_seen = 0;
   c->prof_ev = nullptr;
+  c->prof_kids = nullptr;
+  c->prof_e0 = nullptr;
+  c->prof_e1 = nullptr;
   c->lds_per_block = 65536;
   int prev = 0;
   hipError_t e = hipGetDevice(&prev);
@@ -46,6 +49,7 @@ extern "C" void vardrop_destroy(vardrop_ctx* ctx) {
   if (ctx->prof_ev) {
     for (int i = 0; i < 2 * kProfPairs; ++i) (void)hipEventDestroy(ctx->prof_ev[i]);
     delete[] ctx->prof_ev;
+    delete[] ctx->prof_kids;
   }
   delete ctx;
 }
@@ -72,15 +76,23 @@ extern "C" const char* vardrop_kernel_name(int kernel_id) {
 }
 
 extern "C" int vardrop_profile_select(vardrop_ctx* ctx, int kernel_id) {
-  if (!ctx || kernel_id < -1 || kernel_id >= VARDROP_K_COUNT) return VARDROP_EINVAL;
-  if (kernel_id >= 0 && !ctx->prof_ev) {
+  if (!ctx || kernel_id < VARDROP_K_ALL || kernel_id >= VARDROP_K_COUNT) return VARDROP_EINVAL;
+  if (kernel_id != -1 && !ctx->prof_ev) {
     hipEvent_t* ev = new (std::nothrow) hipEvent_t[2 * kProfPairs];
-    if (!ev) return VARDROP_EHIP;
+    short* kids = new (std::nothrow) short[kProfPairs];
+    if (!ev || !kids) {
+      delete[] ev;
+      delete[] kids;
+      return VARDROP_EHIP;
+    }
+    ctx->prof_kids = kids;
     for (int i = 0; i < 2 * kProfPairs; ++i) {
       hipError_t e = hipEventCreate(&ev[i]);
       if (e != hipSuccess) {
         for (int j = 0; j < i; ++j) (void)hipEventDestroy(ev[j]);
         delete[] ev;
+        delete[] kids;
+        ctx->prof_kids = nullptr;
         ctx->last_hip_error = (int)e;
         return VARDROP_EHIP;
       }
@@ -110,6 +122,24 @@ extern "C" int vardrop_profile_read(vardrop_ctx* ctx, double* total_ms, int* lau
   }
   *total_ms = sum;
   *launches = ctx->prof_n;
+  ctx->prof_n = 0;
+  return VARDROP_OK;
+}
+
+extern "C" int vardrop_profile_read_all(vardrop_ctx* ctx, double* total_ms, int* launches) {
+  if (!ctx || !total_ms || !launches) return VARDROP_EINVAL;
+  for (int k = 0; k < VARDROP_K_COUNT; ++k) {
+    total_ms[k] = 0.0;
+    launches[k] = 0;
+  }
+  for (int i = 0; i < ctx->prof_n; ++i) {
+    VD_HIP(ctx, hipEventSynchronize(ctx->prof_ev[2 * i + 1]));
+    float ms = 0.f;
+    VD_HIP(ctx, hipEventElapsedTime(&ms, ctx->prof_ev[2 * i], ctx->prof_ev[2 * i + 1]));
+    const int k = ctx->prof_kids[i];
+    total_ms[k] += ms;
+    ++launches[k];
+  }
   ctx->prof_n = 0;
   return VARDROP_OK;
 }

@@ -163,10 +163,10 @@ extern "C" int vardrop_embed_fwd(vardrop_ctx* ctx, const float* x, int B, int N,
     VdTimer timer(ctx, VARDROP_K_EMBED_ROWS, s);
     const dim3 grid((unsigned)((M + 3) / 4));
     if (dtype == VARDROP_BF16)
-      hipLaunchKernelGGL(embed_rows_kernel<true>, grid, dim3(256), 0, s, x, saved, sel, N, L, n_sel, M,
+      VD_KERNEL(ctx, embed_rows_kernel<true>, grid, dim3(256), 0, s, x, saved, sel, N, L, n_sel, M,
                          (long long)sb, (long long)sn, pitch, standardise);
     else
-      hipLaunchKernelGGL(embed_rows_kernel<false>, grid, dim3(256), 0, s, x, saved, sel, N, L, n_sel, M,
+      VD_KERNEL(ctx, embed_rows_kernel<false>, grid, dim3(256), 0, s, x, saved, sel, N, L, n_sel, M,
                          (long long)sb, (long long)sn, pitch, standardise);
   }
   VD_LAUNCH_CHECK(ctx);

@@ -81,14 +81,14 @@ int launch(vardrop_ctx* ctx, const void* src, void* dst, const int32_t* sel, int
   dim3 grid((unsigned)blocks), block(tx, ty);
   VdTimer timer(ctx, kScatter ? VARDROP_K_SCATTER : VARDROP_K_GATHER, s);
   if (wide) {
-    if (kScatter) hipLaunchKernelGGL(scatter_kernel<Chunk16>, grid, block, 0, s, (const Chunk16*)src, (Chunk16*)dst, sel, B, N, n_sel, row_units, dn.dev, dn.status);
-    else hipLaunchKernelGGL(gather_kernel<Chunk16>, grid, block, 0, s, (const Chunk16*)src, (Chunk16*)dst, sel, B, N, n_sel, row_units, dn.dev, dn.status);
+    if (kScatter) VD_KERNEL(ctx, scatter_kernel<Chunk16>, grid, block, 0, s, (const Chunk16*)src, (Chunk16*)dst, sel, B, N, n_sel, row_units, dn.dev, dn.status);
+    else VD_KERNEL(ctx, gather_kernel<Chunk16>, grid, block, 0, s, (const Chunk16*)src, (Chunk16*)dst, sel, B, N, n_sel, row_units, dn.dev, dn.status);
   } else if (es == 4) {
-    if (kScatter) hipLaunchKernelGGL(scatter_kernel<uint32_t>, grid, block, 0, s, (const uint32_t*)src, (uint32_t*)dst, sel, B, N, n_sel, row_units, dn.dev, dn.status);
-    else hipLaunchKernelGGL(gather_kernel<uint32_t>, grid, block, 0, s, (const uint32_t*)src, (uint32_t*)dst, sel, B, N, n_sel, row_units, dn.dev, dn.status);
+    if (kScatter) VD_KERNEL(ctx, scatter_kernel<uint32_t>, grid, block, 0, s, (const uint32_t*)src, (uint32_t*)dst, sel, B, N, n_sel, row_units, dn.dev, dn.status);
+    else VD_KERNEL(ctx, gather_kernel<uint32_t>, grid, block, 0, s, (const uint32_t*)src, (uint32_t*)dst, sel, B, N, n_sel, row_units, dn.dev, dn.status);
   } else {
-    if (kScatter) hipLaunchKernelGGL(scatter_kernel<uint16_t>, grid, block, 0, s, (const uint16_t*)src, (uint16_t*)dst, sel, B, N, n_sel, row_units, dn.dev, dn.status);
-    else hipLaunchKernelGGL(gather_kernel<uint16_t>, grid, block, 0, s, (const uint16_t*)src, (uint16_t*)dst, sel, B, N, n_sel, row_units, dn.dev, dn.status);
+    if (kScatter) VD_KERNEL(ctx, scatter_kernel<uint16_t>, grid, block, 0, s, (const uint16_t*)src, (uint16_t*)dst, sel, B, N, n_sel, row_units, dn.dev, dn.status);
+    else VD_KERNEL(ctx, gather_kernel<uint16_t>, grid, block, 0, s, (const uint16_t*)src, (uint16_t*)dst, sel, B, N, n_sel, row_units, dn.dev, dn.status);
   }
   VD_LAUNCH_CHECK(ctx);
   return VARDROP_OK;

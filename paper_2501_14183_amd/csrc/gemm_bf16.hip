@@ -430,7 +430,7 @@ int launch_gemm_async_cfg(vardrop_ctx* ctx, int kid, const GemmBf16& g, int nz, 
   if (grid >= (1ll << 31)) return VARDROP_EUNSUPPORTED;
   {
     VdTimer timer(ctx, kid, s);
-    hipLaunchKernelGGL((gemm_async_kernel<AKC, BKC, SPLIT, BM, BK, NS>), dim3((unsigned)grid), dim3(256), lds, s, g, nz);
+    VD_KERNEL(ctx, (gemm_async_kernel<AKC, BKC, SPLIT, BM, BK, NS>), dim3((unsigned)grid), dim3(256), lds, s, g, nz);
   }
   VD_LAUNCH_CHECK(ctx);
   return VARDROP_OK;
@@ -450,7 +450,7 @@ int launch_gemm_bwd_pair_cfg(vardrop_ctx* ctx, const GemmBf16& gx, const GemmBf1
   const int nx = gxn * gxm, nw = gwn * gwm * nzw * gw.splitk;
   {
     VdTimer timer(ctx, VARDROP_K_GEMM_DW_DXS, s);
-    hipLaunchKernelGGL(gemm_bwd_pair_kernel<BMX>, dim3(nx + nw), dim3(256), lds, s, gx, gw, nzw);
+    VD_KERNEL(ctx, gemm_bwd_pair_kernel<BMX>, dim3(nx + nw), dim3(256), lds, s, gx, gw, nzw);
   }
   VD_LAUNCH_CHECK(ctx);
   return VARDROP_OK;
@@ -522,7 +522,7 @@ int vd_gemm_bf16_sum_slices(vardrop_ctx* ctx, const float* part, float* const ou
   r.splitk = splitk;
   {
     VdTimer timer(ctx, VARDROP_K_REDUCE_DW, s);
-    hipLaunchKernelGGL(splitk_reduce_kernel, dim3(vd_ceil_div((int)(count / 4), 256), nz), dim3(256), 0, s, r);
+    VD_KERNEL(ctx, splitk_reduce_kernel, dim3(vd_ceil_div((int)(count / 4), 256), nz), dim3(256), 0, s, r);
   }
   VD_LAUNCH_CHECK(ctx);
   return VARDROP_OK;

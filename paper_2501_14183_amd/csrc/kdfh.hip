@@ -708,7 +708,7 @@ int launch_kdfh(vardrop_ctx* ctx, const KdfhArgs& a, int grid, size_t lds, hipSt
     VD_HIP(ctx, hipFuncSetAttribute((const void*)kdfh_kernel<ITEMS, RING, VEC, R2, STRAY, WPE>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
   {
     VdTimer timer(ctx, VARDROP_K_HASH, s);
-    hipLaunchKernelGGL((kdfh_kernel<ITEMS, RING, VEC, R2, STRAY, WPE>), dim3(grid), dim3(kThreads), lds, s, a);
+    VD_KERNEL(ctx, (kdfh_kernel<ITEMS, RING, VEC, R2, STRAY, WPE>), dim3(grid), dim3(kThreads), lds, s, a);
   }
   VD_LAUNCH_CHECK(ctx);
   return VARDROP_OK;

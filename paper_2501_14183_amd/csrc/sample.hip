@@ -633,9 +633,9 @@ int run_sample(vardrop_ctx* ctx, const uint64_t* hash, int N,
     VD_HIP(ctx, hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
   {
     VdTimer timer(ctx, VARDROP_K_SAMPLE, s);
-    if (E == 2) hipLaunchKernelGGL(sample_kernel<2>, dim3(1), dim3(threads), lds, s, a);
-    else if (E == 4) hipLaunchKernelGGL(sample_kernel<4>, dim3(1), dim3(threads), lds, s, a);
-    else hipLaunchKernelGGL(sample_kernel<8>, dim3(1), dim3(threads), lds, s, a);
+    if (E == 2) VD_KERNEL(ctx, sample_kernel<2>, dim3(1), dim3(threads), lds, s, a);
+    else if (E == 4) VD_KERNEL(ctx, sample_kernel<4>, dim3(1), dim3(threads), lds, s, a);
+    else VD_KERNEL(ctx, sample_kernel<8>, dim3(1), dim3(threads), lds, s, a);
   }
   VD_LAUNCH_CHECK(ctx);
   if (counts_host)
@@ -667,6 +667,23 @@ extern "C" int vardrop_sample_dev(vardrop_ctx* ctx, const uint64_t* hash, int N,
                     step_dev, advance);
 }
 
+namespace {
+int run_sample_nearest(vardrop_ctx* ctx, const uint64_t* hash, const float* abar, int N, int F,
+                       uint32_t gs, uint32_t ratio_num, uint32_t ratio_den,
+                       int32_t* group_id, int32_t* sel, int32_t* counts, int32_t* counts_host,
+                       float* mean, uint64_t* keys, void* stream) {
+  // group ids first (the members kept by this pass are overwritten below)
+  int rc = run_sample(ctx, hash, N, gs, ratio_num, ratio_den, 0, 0, nullptr, group_id, sel, counts, nullptr, stream);
+  if (rc) return rc;
+  hipStream_t s = (hipStream_t)stream;
+  hipLaunchKernelGGL(group_mean_kernel, dim3(N), dim3(256), 0, s, group_id, abar, mean, N, F);
+  hipLaunchKernelGGL(distance_key_kernel, dim3(vd_ceil_div(N, 256)), dim3(256), 0, s, group_id, abar, mean, keys, N, F);
+  VD_LAUNCH_CHECK(ctx);
+  return run_sample(ctx, hash, N, gs, ratio_num, ratio_den, 0, 0, keys, group_id, sel, counts, counts_host, stream);
+}
+
+}  // namespace
+
 extern "C" size_t vardrop_sample_nearest_workspace_bytes(int N, int F) {
   if (N < 1 || F < 1) return 0;
   return vd_align_up((size_t)N * F * sizeof(float), 256) + vd_align_up((size_t)N * sizeof(uint64_t), 256);
@@ -678,14 +695,7 @@ extern "C" int vardrop_sample_nearest(vardrop_ctx* ctx, const uint64_t* hash, co
                                       void* ws, size_t ws_bytes, void* stream) {
   if (!ctx || !abar || F < 1) return VARDROP_EINVAL;
   if (N >= 1 && (!ws || !vd_aligned(ws, 256) || ws_bytes < vardrop_sample_nearest_workspace_bytes(N, F))) return VARDROP_EWORKSPACE;
-  // group ids first (the members kept by this pass are overwritten below)
-  int rc = run_sample(ctx, hash, N, gs, ratio_num, ratio_den, 0, 0, nullptr, group_id, sel, counts, nullptr, stream);
-  if (rc) return rc;
-  hipStream_t s = (hipStream_t)stream;
   float* mean = (float*)ws;
   uint64_t* keys = (uint64_t*)((char*)ws + vd_align_up((size_t)N * F * sizeof(float), 256));
-  hipLaunchKernelGGL(group_mean_kernel, dim3(N), dim3(256), 0, s, group_id, abar, mean, N, F);
-  hipLaunchKernelGGL(distance_key_kernel, dim3(vd_ceil_div(N, 256)), dim3(256), 0, s, group_id, abar, mean, keys, N, F);
-  VD_LAUNCH_CHECK(ctx);
-  return run_sample(ctx, hash, N, gs, ratio_num, ratio_den, 0, 0, keys, group_id, sel, counts, counts_host, stream);
+  return run_sample_nearest(ctx, hash, abar, N, F, gs, ratio_num, ratio_den, group_id, sel, counts, counts_host, mean, keys, stream);
 }
