@@ -205,6 +205,17 @@ int vardrop_sample_nearest(vardrop_ctx* ctx, const uint64_t* hash, const float* 
                            int32_t* group_id, int32_t* sel, int32_t* counts_dev, int32_t* counts_host,
                            void* ws, size_t ws_bytes, void* stream);
 
+/* vardrop_sample_nearest for callers that cannot allocate device memory or hand over a workspace (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc): the group means and the distance keys
+ * live in a static device array of the library (4 MiB + 64 KiB per device, held until the process ends), whose
+ * address vardrop_create takes for its device.  Limits: N <= 8192 and N * F <= 2^20 (EUNSUPPORTED beyond).  The call
+ * itself allocates nothing and has no host copy of the counts.  Every call on a device shares that array: calls that
+ * overlap in time on one device (any contexts, any streams) race and must be ordered by the caller.  Results are
+ * identical to vardrop_sample_nearest. */
+int vardrop_sample_nearest_noalloc(vardrop_ctx* ctx, const uint64_t* hash, const float* abar, int N, int F,
+                                   uint32_t gs, uint32_t ratio_num, uint32_t ratio_den,
+                                   int32_t* group_id, int32_t* sel, int32_t* counts_dev, void* stream);
+
 /* ---------------------------------------------------------------------------------
  * Gather of the kept tokens (Sec. 3.1: attention runs on the selected tokens only) and
  * its adjoint.

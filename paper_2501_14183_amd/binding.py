@@ -44,6 +44,8 @@ _SIGNATURES = {
     "vardrop_sample_nearest_workspace_bytes": (_c_size, [_c_int, _c_int]),
     "vardrop_sample_nearest": (_c_int, [_ptr, _ptr, _ptr, _c_int, _c_int, _c_u32, _c_u32, _c_u32,
                                         _ptr, _ptr, _ptr, _ptr, _ptr, _c_size, _ptr]),
+    "vardrop_sample_nearest_noalloc": (_c_int, [_ptr, _ptr, _ptr, _c_int, _c_int, _c_u32, _c_u32, _c_u32,
+                                                _ptr, _ptr, _ptr, _ptr]),
     "vardrop_gather": (_c_int, [_ptr, _ptr, _c_int, _c_int, _c_int, _c_int, _ptr, _c_int, _ptr, _ptr]),
     "vardrop_scatter": (_c_int, [_ptr, _ptr, _c_int, _c_int, _c_int, _c_int, _ptr, _c_int, _ptr, _ptr]),
     "vardrop_gather_dev": (_c_int, [_ptr, _ptr, _c_int, _c_int, _c_int, _c_int, _ptr, _ptr, _c_int, _ptr, _ptr, _ptr]),
@@ -430,3 +432,12 @@ def vardrop_attn_bwd_dev(ctx, dy, xs, n_dev, n_max, Wq, Wk, Wv, Wo, H, saved, ws
     ctx.check(rc, "vardrop_attn_bwd_dev")
     return out
 
+
+def vardrop_sample_nearest_noalloc(ctx, hsh, abar, gs, ratio_num, ratio_den, out, stream=None):
+    """vardrop_sample_nearest on the library's static scratch (allocates nothing); out = (group_id, sel, counts)."""
+    N, F = abar.shape
+    gid, sel, counts = out
+    rc = ctx._lib.vardrop_sample_nearest_noalloc(ctx.handle, _p(hsh), _p(abar), N, F, gs, ratio_num, ratio_den,
+                                                 _p(gid), _p(sel), _p(counts), _stream(hsh, stream))
+    ctx.check(rc, "vardrop_sample_nearest_noalloc")
+    return gid, sel, counts

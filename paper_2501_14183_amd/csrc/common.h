@@ -24,6 +24,7 @@ struct vardrop_ctx {
   int twiddle_F;         //   its number of candidate bins
   int twiddle_r2;        //   and whether it is laid out for the radix-2 kernel
   int lds_per_block;     // bytes of LDS one workgroup may use
+  void* static_scratch;  // device address, on this context's device, of the static scratch array of sample.hip
 };
 
 static const int kMaxHashL = 1024;                    // longest window vardrop_hash takes
@@ -111,6 +112,9 @@ __host__ __device__ static inline int vd_attn_bf16_splitk(int d, long long M, in
 }
 size_t vd_attn_bf16_partial_offset(int B, int n, int d, int H);
 size_t vd_attn_bf16_ws_bytes(int B, int n, int d, int H);
+
+// device address of the static scratch array (sample.hip) on the current device; 0 or the hipError_t
+int vd_static_scratch_address(void** out);
 
 // strided fp32 GEMM of the fp32 back end (attn_f32.hip)
 int vd_gemm_f32(vardrop_ctx*, int kid, const float* A, long long sam, long long sak,

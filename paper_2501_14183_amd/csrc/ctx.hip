@@ -25,6 +25,7 @@ extern "C" int vardrop_create(vardrop_ctx** out, int device_id) {
   c->prof_e0 = nullptr;
   c->prof_e1 = nullptr;
   c->lds_per_block = 65536;
+  c->static_scratch = nullptr;
   int prev = 0;
   hipError_t e = hipGetDevice(&prev);
   if (e == hipSuccess) e = hipSetDevice(device_id);
@@ -33,6 +34,12 @@ extern "C" int vardrop_create(vardrop_ctx** out, int device_id) {
     if (hipDeviceGetAttribute(&v, hipDeviceAttributeMaxSharedMemoryPerBlock, device_id) == hipSuccess && v > 0)
       c->lds_per_block = v;
     e = hipMalloc(&c->twiddle, kTwiddleBytes);
+    // the static scratch array has one copy per device: its address is taken with this context's device current
+    if (e == hipSuccess) {
+      const int se = vd_static_scratch_address(&c->static_scratch);
+      if (se != 0) e = (hipError_t)se;
+    }
+    if (e != hipSuccess && c->twiddle) (void)hipFree(c->twiddle);
     (void)hipSetDevice(prev);
   }
   if (e != hipSuccess) {

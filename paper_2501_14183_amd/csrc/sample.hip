@@ -682,7 +682,33 @@ int run_sample_nearest(vardrop_ctx* ctx, const uint64_t* hash, const float* abar
   return run_sample(ctx, hash, N, gs, ratio_num, ratio_den, 0, 0, keys, group_id, sel, counts, counts_host, stream);
 }
 
+// Scratch of the entry point that allocates nothing: the group means ([G][F] floats, G F <= N F <= kStaticMeanFloats)
+// followed by the distance keys ([N] uint64, N <= kMaxN).  Part of the code object, one copy per device, held until
+// the process ends; every call on a device uses it, so calls that overlap on one device race.
+constexpr size_t kStaticMeanFloats = (size_t)1 << 20;
+constexpr size_t kStaticScratchBytes = kStaticMeanFloats * sizeof(float) + (size_t)kMaxN * sizeof(uint64_t);
 }  // namespace
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+// Device address of the scratch array on the current device (the array's name is only a host-side stand-in for it).
+int vd_static_scratch_address(void** out) {
+  void* p = nullptr;
+  const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+  if (e != hipSuccess || !p) return (int)(e != hipSuccess ? e : hipErrorInvalidSymbol);
+  *out = p;
+  return 0;
+}
+
+extern "C" int vardrop_sample_nearest_noalloc(vardrop_ctx* ctx, const uint64_t* hash, const float* abar, int N, int F,
+                                              uint32_t gs, uint32_t ratio_num, uint32_t ratio_den,
+                                              int32_t* group_id, int32_t* sel, int32_t* counts, void* stream) {
+  if (!ctx || !abar || F < 1) return VARDROP_EINVAL;
+  if (N > kMaxN || (N >= 1 && (size_t)N * (size_t)F > kStaticMeanFloats)) return VARDROP_EUNSUPPORTED;   // beyond the static scratch
+  if (!ctx->static_scratch) return VARDROP_EHIP;             // its address could not be taken when the context was made
+  float* mean = (float*)ctx->static_scratch;
+  uint64_t* keys = (uint64_t*)((char*)ctx->static_scratch + kStaticMeanFloats * sizeof(float));
+  return run_sample_nearest(ctx, hash, abar, N, F, gs, ratio_num, ratio_den, group_id, sel, counts, nullptr, mean, keys, stream);
+}
 
 extern "C" size_t vardrop_sample_nearest_workspace_bytes(int N, int F) {
   if (N < 1 || F < 1) return 0;
