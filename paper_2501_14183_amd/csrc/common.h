@@ -24,6 +24,7 @@ struct vardrop_ctx {
   int twiddle_F;         //   its number of candidate bins
   int twiddle_r2;        //   and whether it is laid out for the radix-2 kernel
   int lds_per_block;     // bytes of LDS one workgroup may use
+  int num_cus;           // compute units of the device
   void* static_scratch;  // device address, on this context's device, of the static scratch array of sample.hip
 };
 

@@ -25,6 +25,7 @@ extern "C" int vardrop_create(vardrop_ctx** out, int device_id) {
   c->prof_e0 = nullptr;
   c->prof_e1 = nullptr;
   c->lds_per_block = 65536;
+  c->num_cus = 256;
   c->static_scratch = nullptr;
   int prev = 0;
   hipError_t e = hipGetDevice(&prev);
@@ -33,6 +34,7 @@ extern "C" int vardrop_create(vardrop_ctx** out, int device_id) {
     int v = 0;
     if (hipDeviceGetAttribute(&v, hipDeviceAttributeMaxSharedMemoryPerBlock, device_id) == hipSuccess && v > 0)
       c->lds_per_block = v;
+    if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, device_id) == hipSuccess && v > 0) c->num_cus = v;
     e = hipMalloc(&c->twiddle, kTwiddleBytes);
     // the static scratch array has one copy per device: its address is taken with this context's device current
     if (e == hipSuccess) {

@@ -62,6 +62,26 @@ __device__ inline void split8(const float (&v)[8], Pieces& p) {
     p.lo[j] = (_Float16)(v[j] - (float)h);
   }
 }
+// The same split with fewer instructions, for values scaled into the normal range of fp16: the high piece is the
+// value truncated to fp16 (one conversion instruction per pair, and its float value is the input with the low 13
+// mantissa bits cleared), the low piece the remainder, which is exact in fp32, rounded to nearest.  A value below
+// 2^-14 loses part of its high piece (the truncating conversion then yields a subnormal): an absolute error below
+// 2^-24, against row maxima of at least 2^12.
+typedef _Float16 halfx2 __attribute__((ext_vector_type(2)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+__device__ inline void split8_trunc(const float (&v)[8], Pieces& p) {
+#pragma unroll
+  for (int j = 0; j < 8; j += 2) {
+    const halfx2 h = __builtin_bit_cast(halfx2, __builtin_amdgcn_cvt_pkrtz(v[j], v[j + 1]));
+    const floatx2 rem = {v[j] - __uint_as_float(__float_as_uint(v[j]) & 0xffffe000u),
+                         v[j + 1] - __uint_as_float(__float_as_uint(v[j + 1]) & 0xffffe000u)};
+    const halfx2 lo = __builtin_convertvector(rem, halfx2);
+    p.hi[j] = h[0];
+    p.hi[j + 1] = h[1];
+    p.lo[j] = lo[0];
+    p.lo[j + 1] = lo[1];
+  }
+}
 
 // Table of the twiddle pieces in fragment order: entry ((s * nct + ct) * 4 + kind) * 64 + lane holds,
 // for contraction step s and bin tile ct, the 8 halves of lane `lane` of the right-hand operand
@@ -698,8 +718,558 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(WPE)))
   }
 }
 
+
+// ================================================================== pipelined variant
+// The same computation for inputs whose rows can be read as aligned float4 (VEC), arranged so that the memory
+// reads, the vector work (fold, scale, split) and the matrix work of different row blocks overlap instead of
+// following each other.  A workgroup of eight wavefronts is persistent: it walks over variate groups
+// g = blockIdx.x, blockIdx.x + gridDim.x, ... and their row blocks.  Wavefronts 0-3 are producers: each owns 8 of
+// the 32 rows of a block, requests the rows of block t + 2 from memory while it folds, scales and splits block t + 1
+// into one of two LDS operand buffers (the row maximum is an LDS exchange inside the wavefront: no workgroup
+// barrier), and ranks the top-k of the group that block t - 1 completed.  Wavefronts 4-7 are consumers: they contract
+// block t from the other buffer on the matrix cores and add the amplitudes to the batch sums.  One workgroup barrier
+// per block hands the buffers over.
+constexpr int kPipeThreads = 512;
+
+template <int IW, bool R2>
+struct RawRows {
+  float a[IW][8], b[IW][8];                       // samples t0 .. t0+7 and (R2) the ones half a window later
+  float c[IW][8], d[IW][8];                       // mirror images (plain: c only)
+  float n1, n2;                                   // middle samples of the row of lanes 0..7
+};
+
+// requests the samples of this lane's items of row block (n0, rb): rows 8 pw .. 8 pw + 7 of the block
+template <int IW, bool R2>
+__device__ __forceinline__ void pipe_load(RawRows<IW, R2>& w, const KdfhArgs& a, int n0, int rb, int pw, int lane) {
+  const int L = a.L, T = a.T, KG = 2 * a.KS, rpv = 1 << a.log2_rpv;
+  const int M = L >> 1;
+  w.n1 = 0.f;
+  w.n2 = 0.f;
+  if (lane < 8) {
+    const int r = 8 * pw + lane;
+    const int nn = n0 + (r >> a.log2_rpv), bb = rb * 32 + (r & (rpv - 1));
+    if (nn < a.N && bb < a.B) {
+      const float* p = a.x + (long long)bb * a.sb + (long long)nn * a.sn;
+      if (R2) {
+        w.n1 = p[T];
+        w.n2 = p[T + M];
+      } else if ((L & 1) == 0) {
+        w.n1 = p[M];
+      }
+    }
+  }
+#pragma unroll
+  for (int it = 0; it < IW; ++it) {
+    const int i = min(it * 64 + lane, 8 * KG - 1);      // (a lane past the last item repeats it and stores nothing)
+    const int rl = i / KG;
+    const int g = i - rl * KG;
+    const int r = 8 * pw + rl;
+    const int t0 = 8 * g;
+    const int nn = n0 + (r >> a.log2_rpv), bb = rb * 32 + (r & (rpv - 1));
+    const float* p = a.x + (long long)min(bb, a.B - 1) * a.sb + (long long)min(nn, a.N - 1) * a.sn;
+    if constexpr (R2) {
+      const float4* pa4 = reinterpret_cast<const float4*>(p + t0);
+      const float4* pb4 = reinterpret_cast<const float4*>(p + M + t0);
+      const float4* pc4 = reinterpret_cast<const float4*>(p + (M - 8 - t0));     // x[M - t0 - 8 .. M - t0 - 1]
+      const float4* pd4 = reinterpret_cast<const float4*>(p + (L - 8 - t0));     // x[L - t0 - 8 .. L - t0 - 1]
+      const float4 a0 = pa4[0], a1 = pa4[1], b0 = pb4[0], b1 = pb4[1];
+      const float4 c0 = pc4[0], c1 = pc4[1], d0 = pd4[0], d1 = pd4[1];
+      w.c[it][0] = p[M - t0];
+      w.d[it][0] = p[min(L - t0, L - 1)];          // (t = 0 has no mirror image)
+      w.a[it][0] = a0.x; w.a[it][1] = a0.y; w.a[it][2] = a0.z; w.a[it][3] = a0.w;
+      w.a[it][4] = a1.x; w.a[it][5] = a1.y; w.a[it][6] = a1.z; w.a[it][7] = a1.w;
+      w.b[it][0] = b0.x; w.b[it][1] = b0.y; w.b[it][2] = b0.z; w.b[it][3] = b0.w;
+      w.b[it][4] = b1.x; w.b[it][5] = b1.y; w.b[it][6] = b1.z; w.b[it][7] = b1.w;
+      w.c[it][1] = c1.w; w.c[it][2] = c1.z; w.c[it][3] = c1.y; w.c[it][4] = c1.x;
+      w.c[it][5] = c0.w; w.c[it][6] = c0.z; w.c[it][7] = c0.y;
+      w.d[it][1] = d1.w; w.d[it][2] = d1.z; w.d[it][3] = d1.y; w.d[it][4] = d1.x;
+      w.d[it][5] = d0.w; w.d[it][6] = d0.z; w.d[it][7] = d0.y;
+    } else {
+      // mirror images x[L - t0 - 7 .. L - t0]: the aligned float4 at L - t0 - 8 (its last three samples), the one
+      // at L - t0 - 4 and one more sample; an item that starts past L - 8 reads the row's last 8 samples instead
+      // (none of its samples is inside the fold)
+      const int tc = min(t0, L - 8);
+      const float4* pd = reinterpret_cast<const float4*>(p + tc);
+      const float4* pm = reinterpret_cast<const float4*>(p + (L - 8 - tc));
+      const float4 u0 = pd[0], u1 = pd[1], ua = pm[0], ub = pm[1];
+      w.c[it][0] = p[min(L - tc, L - 1)];
+      w.a[it][0] = u0.x; w.a[it][1] = u0.y; w.a[it][2] = u0.z; w.a[it][3] = u0.w;
+      w.a[it][4] = u1.x; w.a[it][5] = u1.y; w.a[it][6] = u1.z; w.a[it][7] = u1.w;
+      w.c[it][1] = ub.w; w.c[it][2] = ub.z; w.c[it][3] = ub.y; w.c[it][4] = ub.x;
+      w.c[it][5] = ua.w; w.c[it][6] = ua.z; w.c[it][7] = ua.y;
+    }
+  }
+}
+
+// LDS of the pipelined kernel: two operand buffers, two sets of per-block floats, then the producers' row maxima.
+// (Accessors compute addresses from the set number: a struct of pointer arrays indexed at run time would live in
+// private memory.)
+struct PipeLds {
+  halfx8* base;
+  float* fbase;
+  int opnd_elems;           // halfx8 elements of one operand buffer: (R2 ? 8 : 4) * 32 * pitch
+  int set_floats;           // floats of one set: (3 + kMaxStray) * 32 + Vb * F
+  __device__ halfx8* opnd(int b) const { return base + b * opnd_elems; }
+  __device__ float* rowinv(int b) const { return fbase + b * set_floats; }                    // [32] 1 / scale of a row
+  __device__ float* xn1(int b) const { return fbase + b * set_floats + 32; }                  // [32] middle term, cosine sum
+  __device__ float* xn2(int b) const { return fbase + b * set_floats + 64; }                  // [32] middle term, sine sum (R2)
+  __device__ float* samp(int b) const { return fbase + b * set_floats + 96; }                 // [kMaxStray][32] stray bins per row
+  __device__ float* asum(int b) const { return fbase + b * set_floats + 96 + kMaxStray * 32; }   // [Vb][F] batch sums
+  __device__ unsigned* rowmax() const { return reinterpret_cast<unsigned*>(fbase + 2 * set_floats); }   // [32]
+  __device__ float* stw() const { return fbase + 2 * set_floats + 32; }    // [kMaxStray][2 Tp] cosine, sine of the stray bins (R2)
+};
+__host__ __device__ inline size_t pipe_lds_bytes(int pitch, int F, int Vb, bool r2) {
+  const size_t opnd = (size_t)(r2 ? 8 : 4) * 32 * pitch * 16;
+  return 2 * (opnd + sizeof(float) * ((3 + kMaxStray) * 32 + (size_t)Vb * F)) + 32 * sizeof(unsigned) +
+         (r2 ? sizeof(float) * kMaxStray * 2 * 8 * (size_t)(pitch - 1) : 0);      // pitch = 2 KS | 1: Tp = 8 (pitch - 1)
+}
+__device__ inline PipeLds pipe_lds(halfx8* base, int pitch, int F, int Vb, bool r2) {
+  PipeLds l;
+  l.base = base;
+  l.opnd_elems = (r2 ? 8 : 4) * 32 * pitch;
+  l.fbase = reinterpret_cast<float*>(base + 2 * l.opnd_elems);
+  l.set_floats = (3 + kMaxStray) * 32 + Vb * F;
+  return l;
+}
+
+// folds, scales and splits the rows `w` holds into operand buffer `b`
+template <int IW, bool R2>
+__device__ __forceinline__ void pipe_produce(RawRows<IW, R2>& w, const KdfhArgs& a, const PipeLds& l, int b,
+                                             int n0, int rb, int pw, int lane) {
+  const int T = a.T, KG = 2 * a.KS, rpv = 1 << a.log2_rpv, pitch = a.pitch;
+  // ---- largest magnitude of every row: the rows of this wavefront are its own, and LDS operations of one
+  // wavefront take effect in program order, so the exchange needs no workgroup barrier
+  unsigned* rowmax = l.rowmax();
+  if (lane < 8) rowmax[8 * pw + lane] = __float_as_uint(fmaxf(fabsf(w.n1), fabsf(w.n2)));
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  // Samples at t >= T need no masking: the loads read samples of the same row (so the row maximum is unchanged)
+  // and the table is zero there.  What does: rows past the end of the input are zero windows, and t = 0 has no
+  // mirror image.
+#pragma unroll
+  for (int it = 0; it < IW; ++it) {
+    const int i = min(it * 64 + lane, 8 * KG - 1);
+    const int rl = i / KG, g = i - rl * KG, r = 8 * pw + rl;
+    const int nn = n0 + (r >> a.log2_rpv), bb = rb * 32 + (r & (rpv - 1));
+    const bool ok = nn < a.N && bb < a.B;
+    if (__builtin_amdgcn_ballot_w64(!ok) != 0) {           // (uniform: only a group at the end of the input has such rows)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        w.a[it][j] = ok ? w.a[it][j] : 0.f;
+        w.c[it][j] = ok ? w.c[it][j] : 0.f;
+        if (R2) {
+          w.b[it][j] = ok ? w.b[it][j] : 0.f;
+          w.d[it][j] = ok ? w.d[it][j] : 0.f;
+        }
+      }
+    }
+    if (g == 0) {
+      w.c[it][0] = 0.f;
+      if (R2) w.d[it][0] = 0.f;
+    }
+    float mx = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      if constexpr (R2) {
+        const float xa_ = w.a[it][j], xb_ = w.b[it][j], xc_ = w.c[it][j], xd_ = w.d[it][j];
+        mx = fmaxf(fmaxf(mx, fmaxf(fabsf(xa_), fabsf(xb_))), fmaxf(fabsf(xc_), fabsf(xd_)));
+        const float u = xa_ + xb_, v = xa_ - xb_, um = xc_ + xd_, vm_ = xc_ - xd_;
+        w.a[it][j] = u + um;                      // even bins, cosine
+        w.b[it][j] = u - um;                      // even bins, sine   (t = 0: times sin 0)
+        w.c[it][j] = v - vm_;                     // odd bins, cosine
+        w.d[it][j] = v + vm_;                     // odd bins, sine
+      } else {
+        const float d = w.a[it][j], m = w.c[it][j];
+        mx = fmaxf(mx, fmaxf(fabsf(d), fabsf(m)));
+        w.a[it][j] = d + m;                       // cosine operand
+        w.c[it][j] = d - m;                       // sine operand   (t = 0: times sin 0)
+      }
+    }
+    if (it * 64 + lane < 8 * KG) atomicMax(&rowmax[r], __float_as_uint(mx));
+  }
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  // ---- scale by a power of two that brings the row's largest magnitude to [2^12, 2^13) (the folded values are
+  // sums of up to four samples: below 2^15), split, store
+  if (lane < 8) {
+    const int r = 8 * pw + lane;
+    const int se = min(max(266 - (int)(rowmax[r] >> 23), 1), 253);
+    const float sc = __uint_as_float((unsigned)se << 23);
+    l.rowinv(b)[r] = __uint_as_float((unsigned)(254 - se) << 23);
+    if (R2) {
+      l.xn1(b)[r] = (w.n1 + w.n2) * sc;
+      l.xn2(b)[r] = (w.n1 - w.n2) * sc;
+    } else {
+      l.xn1(b)[r] = w.n1 * sc;
+      l.xn2(b)[r] = 0.f;
+    }
+  }
+  halfx8* opnd = l.opnd(b);
+#pragma unroll
+  for (int it = 0; it < IW; ++it) {
+    const int i = min(it * 64 + lane, 8 * KG - 1);
+    const int rl = i / KG, g = i - rl * KG, r = 8 * pw + rl;
+    const int se = min(max(266 - (int)(rowmax[r] >> 23), 1), 253);
+    const float sc = __uint_as_float((unsigned)se << 23);
+    float s0[8], s1[8], s2[8], s3[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      s0[j] = w.a[it][j] * sc;
+      s1[j] = (R2 ? w.b[it][j] : w.c[it][j]) * sc;
+      if (R2) {
+        s2[j] = w.c[it][j] * sc;
+        s3[j] = w.d[it][j] * sc;
+      }
+    }
+    Pieces p0, p1, p2, p3;
+    split8_trunc(s0, p0);
+    split8_trunc(s1, p1);
+    if (R2) {
+      split8_trunc(s2, p2);
+      split8_trunc(s3, p3);
+    }
+    if (it * 64 + lane < 8 * KG) {
+      halfx8* q = opnd + r * pitch + g;
+      q[0] = p0.hi;
+      q[32 * pitch] = p0.lo;
+      q[64 * pitch] = p1.hi;
+      q[96 * pitch] = p1.lo;
+      if (R2) {
+        q[128 * pitch] = p2.hi;
+        q[160 * pitch] = p2.lo;
+        q[192 * pitch] = p3.hi;
+        q[224 * pitch] = p3.lo;
+      }
+    }
+  }
+}
+
+// ranked top-k and hash (Alg. 1 steps 4-5) of the variates v = cw, cw + 4, ... of a group, from its batch sums;
+// (the stray bins' row amplitudes of the group's last block have been added by the caller)
+__device__ __forceinline__ void pipe_rank(const KdfhArgs& a, float* asum, int n0, int cw, int lane) {
+  const int F = a.F, Vb = 32 >> a.log2_rpv;
+  const unsigned long long R = (unsigned long long)(a.L / 2 + 1);
+  for (int v = cw; v < Vb; v += 4) {
+    const int n = n0 + v;
+    if (n < a.N) {
+      const int nslot = (F + 63) >> 6;             // bin lane + 64 j lives in slot j: only these slots hold bins
+      float vals[kMaxBinsPerLane];
+#pragma unroll
+      for (int j = 0; j < kMaxBinsPerLane; ++j) {
+        const int idx = lane + 64 * j;
+        vals[j] = (j < nslot && idx < F) ? asum[v * F + idx] : -2.f;
+      }
+      unsigned long long h = 0;
+      if (F <= 64) {
+        const float mine = vals[0];
+        int rank = 0;
+        for (int j = 0; j < F; ++j) {
+          const float vj = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(mine), j));
+          rank += (vj > mine || (vj == mine && j < lane)) ? 1 : 0;
+        }
+        for (int r = 0; r < a.k; ++r) {
+          const unsigned long long mask = __ballot(lane < F && rank == r);
+          const int fsel = a.f_min + (__ffsll((long long)mask) - 1);
+          if (lane == 0) a.topk[(long long)n * a.k + r] = fsel;
+          h = h * R + (unsigned long long)(unsigned)fsel;
+        }
+      } else {
+        // k rounds: the largest value by one wavefront reduction, then the lowest bin that holds it: bin lane + 64 j
+        // grows with j before it grows with the lane, so it is the first set lane of the first non-empty ballot
+        for (int r = 0; r < a.k; ++r) {
+          int best = (int)0x80000000;
+#pragma unroll
+          for (int j = 0; j < kMaxBinsPerLane; ++j)
+            if (j < nslot) best = max(best, __float_as_int(vals[j]));
+          const int top = wave_reduce<true>(best);
+          int bi = -1;
+#pragma unroll
+          for (int j = kMaxBinsPerLane - 1; j >= 0; --j)
+            if (j < nslot) {
+              const unsigned long long m = __ballot(__float_as_int(vals[j]) == top);
+              if (m) bi = (__ffsll((long long)m) - 1) + 64 * j;
+            }
+#pragma unroll
+          for (int j = 0; j < kMaxBinsPerLane; ++j)
+            if (j < nslot && bi == lane + 64 * j) vals[j] = -2.f;
+          const int fsel = a.f_min + bi;
+          if (lane == 0) a.topk[(long long)n * a.k + r] = fsel;
+          h = h * R + (unsigned long long)(unsigned)fsel;
+        }
+      }
+      if (lane == 0) a.hash[n] = h;
+      if (a.abar)
+        for (int idx = lane; idx < F; idx += 64) a.abar[(long long)n * F + idx] = asum[v * F + idx] * a.inv_B;
+    }
+  }
+}
+
+// Workgroup barrier that orders LDS accesses only: outstanding global loads (the next block's rows, the table
+// pieces) and stores (the previous group's results) stay in flight across it.
+__device__ inline void pipe_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+template <int IW, bool R2, bool STRAY, int WPE>
+__global__ __launch_bounds__(kPipeThreads) __attribute__((amdgpu_waves_per_eu(WPE))) void kdfh_pipe_kernel(KdfhArgs a, int ngroups) {
+  extern __shared__ halfx8 lds8[];
+  const int F = a.F;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int col = lane & 31, half = lane >> 5;
+  const int rpv = 1 << a.log2_rpv;
+  const int Vb = 32 >> a.log2_rpv;               // variates per group
+  const int KG = 2 * a.KS;
+  const int pitch = a.pitch;
+  const PipeLds l = pipe_lds(lds8, pitch, F, Vb, R2);
+  if constexpr (R2 && STRAY)
+    for (int i = tid; i < a.bins.n_stray * 2 * 8 * KG; i += kPipeThreads) l.stw()[i] = a.stw[i];
+  // this workgroup's groups: blockIdx.x, blockIdx.x + gridDim.x, ...; block t of its sequence is row block
+  // t % nrb of its group number t / nrb
+  const int my_groups = ((int)blockIdx.x < ngroups) ? (ngroups - 1 - (int)blockIdx.x) / (int)gridDim.x + 1 : 0;
+  const int nblk = my_groups * a.nrb;
+  __syncthreads();
+  // What block u leaves to do once every consumer is done with it (the producers do it, so that no store of results
+  // sits in front of a consumer's table read): the wavefront's variates (v = w4, w4 + 4, ...) get
+  // their stray bins' row amplitudes added to the batch sums, and, when u was the last row block of its group,
+  // their ranked top-k and hash.
+  auto post = [&](int u, int w4) {
+    const int gq = u / a.nrb, rbp = u - gq * a.nrb;
+    float* asum = l.asum(gq & 1);
+    if constexpr (STRAY) {
+      const float* samp = l.samp(u & 1);
+      for (int v = w4; v < Vb; v += 4)
+        if (lane < a.bins.n_stray) {
+          float tot = 0.f;
+          for (int rr = 0; rr < rpv; ++rr) tot += samp[lane * 32 + v * rpv + rr];
+          float& dst = asum[v * F + (a.bins.stray_f[lane] - a.f_min)];
+          dst = rbp == 0 ? tot : dst + tot;      // (the first row block of a group starts its sums)
+        }
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    }
+    if (rbp == a.nrb - 1) pipe_rank(a, asum, ((int)blockIdx.x + gq * (int)gridDim.x) * Vb, w4, lane);
+  };
+  if (wave < 4) {
+    // ================================================================ producers
+    const int pw = wave;
+    RawRows<IW, R2> w0, w1;
+    if (nblk > 0) pipe_load(w0, a, (int)blockIdx.x * Vb, 0, pw, lane);
+#define KDFH_PRODUCE(CUR, NXT, T_)                                                                        \
+  {                                                                                                      \
+    const int t_ = (T_);                                                                                 \
+    if (t_ + 1 < nblk) {                                                                                 \
+      const int gq = (t_ + 1) / a.nrb;                                                                   \
+      pipe_load(NXT, a, ((int)blockIdx.x + gq * (int)gridDim.x) * Vb, (t_ + 1) - gq * a.nrb, pw, lane);  \
+    }                                                                                                    \
+    if (t_ >= 2) post(t_ - 2, pw);                   /* (the consumers finished block t_ - 2 before the last barrier) */ \
+    const int gq0 = t_ / a.nrb;                                                                          \
+    pipe_produce(CUR, a, l, t_ & 1, ((int)blockIdx.x + gq0 * (int)gridDim.x) * Vb, t_ - gq0 * a.nrb, pw, lane); \
+    pipe_barrier();                       /* block t_ is ready; the consumers are done with block t_ - 1 */ \
+  }
+    for (int t = 0; t < nblk; t += 2) {
+      KDFH_PRODUCE(w0, w1, t)
+      if (t + 1 < nblk) KDFH_PRODUCE(w1, w0, t + 1)
+    }
+#undef KDFH_PRODUCE
+    if (nblk >= 2) post(nblk - 2, pw);
+    pipe_barrier();                       // the consumers are done with the last block
+    if (nblk >= 1) post(nblk - 1, pw);
+    return;
+  }
+  // ================================================================== consumers
+  const int cw = wave - 4;
+  const int rot = (blockIdx.x + (blockIdx.x >> 8)) & 3;
+  const int ct0 = (cw + rot) & 3;                                    // first bin tile of this wavefront
+  const int nt = ct0 < a.nct ? (a.nct - ct0 + 3) / 4 : 0;            // and how many it takes
+  const int ctp = min(ct0, a.nct - 1);                               // (a wavefront without a tile loads one all the same)
+  Tw w0, w1, w2, w3;
+  for (int t = 0; t <= nblk; ++t) {
+    pipe_barrier();                       // block t is ready (t < nblk); every consumer is done with block t - 1
+    if (t == nblk) break;
+    const int b = t & 1, gq = t / a.nrb;
+    const halfx8* opnd = l.opnd(b);
+    float* asum = l.asum(gq & 1);
+    // the first row block of a group starts its batch sums (a plain store: no read in front of it), later ones add
+    const bool first_rb = t - gq * a.nrb == 0;
+    auto acc = [&](float& dst, float v) { dst = first_rb ? v : dst + v; };
+    const float* rowinv = l.rowinv(b);
+    const float* xn1 = l.xn1(b);
+    const float* xn2 = l.xn2(b);
+    // the table pieces of the wavefront's first tile are requested once; from then on the last steps of a block
+    // request those of the next block's first steps (the table does not depend on the block), so a block starts on
+    // pieces that are already there
+    if (t == 0) {
+      const halfx8* tb = a.tw + (size_t)ctp * 256 + lane;
+      const size_t sstride = (size_t)a.nct * 256;
+      load_tw(w0, tb);
+      load_tw(w1, tb + sstride);
+      load_tw(w2, tb + 2 * sstride);
+      load_tw(w3, tb + 3 * sstride);
+    }
+    Left la, lb;
+    for (int ti = 0; ti < nt; ++ti) {
+      const int ct = ct0 + 4 * ti;
+      floatx16 re = {}, im = {};
+      const halfx8* pa = opnd + ((R2 && ct >= a.bins.nct_e) ? 128 * pitch : 0) + col * pitch;
+      const halfx8* pn = opnd + ((R2 && ct + 4 >= a.bins.nct_e) ? 128 * pitch : 0) + col * pitch;
+      const halfx8 lo_unscale = {(_Float16)kLoUnscale, (_Float16)kLoUnscale, (_Float16)kLoUnscale, (_Float16)kLoUnscale,
+                                 (_Float16)kLoUnscale, (_Float16)kLoUnscale, (_Float16)kLoUnscale, (_Float16)kLoUnscale};
+#define KDFH_READ_LEFT(A, S)                                                              \
+  {                                                                                       \
+    const bool nx = (S) >= a.steps;           /* first step of the wavefront's next tile */ \
+    const halfx8* pl = nx ? pn : pa;                                                      \
+    const int g = min(2 * (nx ? 0 : (S)) + half, KG - 1); /* steps past KS: the table is zero there */ \
+    A.sh = pl[g];                                                                         \
+    A.sl = pl[32 * pitch + g];                                                            \
+    A.dh = pl[64 * pitch + g];                                                            \
+    A.dl = pl[96 * pitch + g];                                                            \
+  }
+#define KDFH_STEP(W, A, AN, S)                                                            \
+  {                                                                                       \
+    KDFH_READ_LEFT(AN, (S) + 1)                                                           \
+    const halfx8 shs = A.sh * lo_unscale, dhs = A.dh * lo_unscale;                        \
+    __builtin_amdgcn_sched_barrier(0);                                                    \
+    re = __builtin_amdgcn_mfma_f32_32x32x16_f16(A.sh, W.ch, re, 0, 0, 0);                 \
+    im = __builtin_amdgcn_mfma_f32_32x32x16_f16(A.dh, W.sh, im, 0, 0, 0);                 \
+    re = __builtin_amdgcn_mfma_f32_32x32x16_f16(shs, W.cl, re, 0, 0, 0);                  \
+    im = __builtin_amdgcn_mfma_f32_32x32x16_f16(dhs, W.sl, im, 0, 0, 0);                  \
+    re = __builtin_amdgcn_mfma_f32_32x32x16_f16(A.sl, W.ch, re, 0, 0, 0);                 \
+    im = __builtin_amdgcn_mfma_f32_32x32x16_f16(A.dl, W.sh, im, 0, 0, 0);                 \
+    __builtin_amdgcn_sched_barrier(0);                                                    \
+    {                                                                                     \
+      const bool wrap = (S) + 4 >= a.steps;   /* then: the next tile, or the first tile again for the next block */ \
+      const int s2 = wrap ? (S) + 4 - a.steps : (S) + 4;                                  \
+      const int c2 = wrap ? (ti + 1 < nt ? ct + 4 : ctp) : ct;                            \
+      load_tw(W, a.tw + ((size_t)s2 * a.nct + c2) * 256 + lane);                          \
+    }                                                                                     \
+    __builtin_amdgcn_sched_barrier(0);                                                    \
+  }
+      if (ti == 0) KDFH_READ_LEFT(la, 0)
+      for (int s = 0; s < a.steps; s += 4) {
+        KDFH_STEP(w0, la, lb, s)
+        KDFH_STEP(w1, lb, la, s + 1)
+        KDFH_STEP(w2, la, lb, s + 2)
+        KDFH_STEP(w3, lb, la, s + 3)
+      }
+#undef KDFH_READ_LEFT
+#undef KDFH_STEP
+      // ---- amplitudes, scaled back, and the batch sums (Alg. 1 step 3) of this bin tile
+      const int f = bin_of(a.bins, ct, col);
+      const int c = f - a.f_min;
+      float cr, ci;
+      if (!R2) {
+        cr = (f & 1) ? -1.f : 1.f;
+        ci = 0.f;
+      } else if (ct < a.bins.nct_e) {
+        cr = (f & 2) ? -1.f : 1.f;
+        ci = 0.f;
+      } else {
+        cr = 0.f;
+        ci = (f & 2) ? -1.f : 1.f;
+      }
+      float amp[16];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const float4 inv4 = *reinterpret_cast<const float4*>(rowinv + 8 * q + 4 * half);
+        const float4 m14 = *reinterpret_cast<const float4*>(xn1 + 8 * q + 4 * half);
+        const float4 m24 = *reinterpret_cast<const float4*>(xn2 + 8 * q + 4 * half);
+        const float inv[4] = {inv4.x, inv4.y, inv4.z, inv4.w};
+        const float m1[4] = {m14.x, m14.y, m14.z, m14.w};
+        const float m2[4] = {m24.x, m24.y, m24.z, m24.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int r = 4 * q + e;
+          const float rv = re[r] + cr * m1[e];
+          const float iv = im[r] + ci * m2[e];
+          amp[r] = sqrtf(rv * rv + iv * iv) * inv[e];
+        }
+      }
+      float qs[4];                                 // rows 8q + 4 half + 0..3
+#pragma unroll
+      for (int q = 0; q < 4; ++q) qs[q] = (amp[4 * q] + amp[4 * q + 1]) + (amp[4 * q + 2] + amp[4 * q + 3]);
+      const bool live = c < F;
+      if (a.log2_rpv >= 3) {
+        float vs[4];
+        if (a.log2_rpv == 3) {
+          vs[0] = qs[0]; vs[1] = qs[1]; vs[2] = qs[2]; vs[3] = qs[3];
+        } else if (a.log2_rpv == 4) {
+          vs[0] = qs[0] + qs[1]; vs[1] = qs[2] + qs[3]; vs[2] = 0.f; vs[3] = 0.f;
+        } else {
+          vs[0] = (qs[0] + qs[1]) + (qs[2] + qs[3]); vs[1] = 0.f; vs[2] = 0.f; vs[3] = 0.f;
+        }
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const float tot = vs[v] + __shfl_xor(vs[v], 32, 64);
+          if (live && half == 0 && v < Vb) acc(asum[v * F + c], tot);
+        }
+      } else if (a.log2_rpv == 2) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          if (live) acc(asum[(2 * q + half) * F + c], qs[q]);
+      } else if (a.log2_rpv == 1) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          if (live) {
+            acc(asum[(4 * q + 2 * half) * F + c], amp[4 * q] + amp[4 * q + 1]);
+            acc(asum[(4 * q + 2 * half + 1) * F + c], amp[4 * q + 2] + amp[4 * q + 3]);
+          }
+      } else {
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          if (live) acc(asum[(8 * (r >> 2) + 4 * half + (r & 3)) * F + c], amp[r]);
+      }
+    }
+    // ---- stray bins on the vector units: eight consumer threads per row share the folded samples (operand pieces
+    // added back together); their row amplitudes go to LDS and are added to the batch sums after the next barrier
+    if constexpr (R2 && STRAY) {
+      const int ctid = tid - 256;
+      const int r = ctid >> 3, part = ctid & 7;
+      const int Tp = 8 * KG;
+      float* samp = l.samp(b);
+      for (int si = 0; si < a.bins.n_stray; ++si) {
+        const int f = a.bins.stray_f[si];
+        const halfx8* base = opnd + ((f & 1) ? 128 * pitch : 0) + r * pitch;
+        const float4* tw4 = reinterpret_cast<const float4*>(l.stw() + (size_t)si * Tp * 2);   // (the copy in LDS)
+        float re = 0.f, im = 0.f;
+        for (int g = part; g < KG; g += 8) {
+          const halfx8 ch = base[g], cl = base[32 * pitch + g], sh = base[64 * pitch + g], sl = base[96 * pitch + g];
+#pragma unroll
+          for (int j2 = 0; j2 < 4; ++j2) {
+            const float4 tw = tw4[4 * g + j2];            // cos, sin of t = 8 g + 2 j2 and of the next sample
+            re = fmaf((float)ch[2 * j2] + (float)cl[2 * j2], tw.x, re);
+            im = fmaf((float)sh[2 * j2] + (float)sl[2 * j2], tw.y, im);
+            re = fmaf((float)ch[2 * j2 + 1] + (float)cl[2 * j2 + 1], tw.z, re);
+            im = fmaf((float)sh[2 * j2 + 1] + (float)sl[2 * j2 + 1], tw.w, im);
+          }
+        }
+#pragma unroll
+        for (int o = 1; o <= 4; o <<= 1) {
+          re += __shfl_xor(re, o, 64);
+          im += __shfl_xor(im, o, 64);
+        }
+        if (part == 0) {
+          const float sg = (f & 2) ? -1.f : 1.f;           // (-1)^(f/2) for an even bin, sin(pi f / 2) for an odd one
+          const float rv = (f & 1) ? re : re + sg * xn1[r];
+          const float iv = (f & 1) ? im + sg * xn2[r] : im;
+          samp[si * 32 + r] = sqrtf(rv * rv + iv * iv) * rowinv[r];
+        }
+      }
+    }
+  }
+}
+
 size_t kdfh_lds_bytes(int pitch, int F, int Vb, bool r2) {
   return (size_t)(r2 ? 8 : 4) * 32 * pitch * 16 + sizeof(float) * ((4 + kMaxStray) * 32 + (size_t)Vb * F);
+}
+
+// Pipelined kernel: workgroups persistent over the variate groups, as many as stay resident at once.
+template <int IW, bool R2, bool STRAY>
+int launch_kdfh_pipe(vardrop_ctx* ctx, const KdfhArgs& a, int ngroups, size_t lds, hipStream_t s) {
+  constexpr int WPE = 2;                                   // eight wavefronts of up to 256 registers: one workgroup per compute unit
+  if (lds > 65536)
+    VD_HIP(ctx, hipFuncSetAttribute((const void*)kdfh_pipe_kernel<IW, R2, STRAY, WPE>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+  const int grid = ngroups < ctx->num_cus ? ngroups : ctx->num_cus;
+  {
+    VdTimer timer(ctx, VARDROP_K_HASH, s);
+    VD_KERNEL(ctx, (kdfh_pipe_kernel<IW, R2, STRAY, WPE>), dim3(grid), dim3(kPipeThreads), lds, s, a, ngroups);
+  }
+  VD_LAUNCH_CHECK(ctx);
+  return VARDROP_OK;
 }
 
 template <int ITEMS, int RING, bool VEC, bool R2, bool STRAY = false, int WPE = (ITEMS == 1 ? 4 : (ITEMS <= 4 ? 2 : 1))>
@@ -848,6 +1418,15 @@ extern "C" int vardrop_hash(vardrop_ctx* ctx, const float* x, int B, int N, int 
   a.inv_B = 1.0f / (float)B;
   const int grid = vd_ceil_div(N, Vb);
   const int items = vd_ceil_div(32 * 2 * KS, kThreads);
+  // Long aligned windows with several row blocks per compute unit: the pipelined kernel (measured at 8192 variates
+  // of 8 windows of 512 samples: 61 against 67 microseconds; at 336 samples and below the one-block-per-workgroup
+  // kernel is as fast or faster and stays).
+  const size_t plds = pipe_lds_bytes(pitch, F, Vb, r2);
+  const int iw = vd_ceil_div(8 * 2 * KS, 64);             // items per producer lane: two sets of them must fit the registers
+  if (r2 && L >= 384 && iw <= 2 && plds <= (size_t)ctx->lds_per_block && (long long)grid * nrb >= 4ll * ctx->num_cus) {
+    if (bins.n_stray > 0) return launch_kdfh_pipe<2, true, true>(ctx, a, grid, plds, s);
+    return launch_kdfh_pipe<2, true, false>(ctx, a, grid, plds, s);
+  }
   if (r2 && bins.n_stray > 0) {
     if (items <= 1) return launch_kdfh<1, 2, true, true, true>(ctx, a, grid, lds, s);
     if (items <= 2) return launch_kdfh<2, 4, true, true, true>(ctx, a, grid, lds, s);

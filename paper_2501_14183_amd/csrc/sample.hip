@@ -322,6 +322,10 @@ __global__ __launch_bounds__(1024) void sample_kernel(SampleArgs a) {
   int* bcur = bstart + kBuckets + 1;                                   // [kBuckets]
   int* bmax = bcur + kBuckets;                                         // [1]
   const int tid = threadIdx.x, nt = blockDim.x;
+  // every thread's E hashes (variates tid, tid + nt, ...; npad = E * nt), read from memory once
+  uint64_t hreg[E];
+#pragma unroll
+  for (int e = 0; e < E; ++e) hreg[e] = tid + e * nt < N ? a.hash[tid + e * nt] : 0ull;
 
   // Sort 1, usual path.  (hash, n) pairs are dropped into kBuckets order-preserving buckets (equal
   // width over [min, max] of the hashes, a shift instead of a division); inside a bucket the position
@@ -337,11 +341,13 @@ __global__ __launch_bounds__(1024) void sample_kernel(SampleArgs a) {
     for (int i = tid; i <= kBuckets; i += nt) bstart[i] = 0;
     __syncthreads();
     unsigned long long lo = ~0ull, hi = 0ull;
-    for (int i = tid; i < N; i += nt) {
-      const unsigned long long h = a.hash[i];
-      lo = h < lo ? h : lo;
-      hi = h > hi ? h : hi;
-    }
+#pragma unroll
+    for (int e = 0; e < E; ++e)
+      if (tid + e * nt < N) {
+        const unsigned long long h = hreg[e];
+        lo = h < lo ? h : lo;
+        hi = h > hi ? h : hi;
+      }
     // one atomic per wavefront, not per thread: same-address LDS atomics serialise
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) {
@@ -357,7 +363,9 @@ __global__ __launch_bounds__(1024) void sample_kernel(SampleArgs a) {
     const unsigned long long hmin = mm[0], range = mm[1] - mm[0];
     int shift = 0;
     while ((range >> shift) >= (unsigned long long)kBuckets) ++shift;
-    for (int i = tid; i < N; i += nt) atomicAdd(&bstart[(int)((a.hash[i] - hmin) >> shift)], 1);
+#pragma unroll
+    for (int e = 0; e < E; ++e)
+      if (tid + e * nt < N) atomicAdd(&bstart[(int)((hreg[e] - hmin) >> shift)], 1);
     __syncthreads();
     {
       int m = 0;
@@ -371,12 +379,14 @@ __global__ __launch_bounds__(1024) void sample_kernel(SampleArgs a) {
       block_exclusive_scan(bstart, kBuckets, wsum);                    // counts -> bucket starts
       for (int i = tid; i < kBuckets; i += nt) bcur[i] = bstart[i];
       __syncthreads();
-      for (int i = tid; i < N; i += nt) {
-        const unsigned long long h = a.hash[i];
-        const int pos = atomicAdd(&bcur[(int)((h - hmin) >> shift)], 1);
-        key[pos] = h;
-        pay[pos] = (uint32_t)i;
-      }
+#pragma unroll
+      for (int e = 0; e < E; ++e)
+        if (tid + e * nt < N) {
+          const unsigned long long h = hreg[e];
+          const int pos = atomicAdd(&bcur[(int)((h - hmin) >> shift)], 1);
+          key[pos] = h;
+          pay[pos] = (uint32_t)(tid + e * nt);
+        }
       __syncthreads();
       for (int p = tid; p < N; p += nt) {
         const uint64_t kp = key[p];
@@ -416,14 +426,15 @@ __global__ __launch_bounds__(1024) void sample_kernel(SampleArgs a) {
   // network.  Padding keys are all ones and sort last.
   const int ib = a.index_bits;
   int too_wide = 0;                                   // bit 0: not in 32 bits, bit 1: not in 64 bits
-  for (int i = tid; i < N; i += nt) {
-    const uint64_t h = a.hash[i];
-    too_wide |= ((h >> (32 - ib)) != 0 ? 1 : 0) | ((h >> (64 - ib)) != 0 ? 2 : 0);
+  if (!sorted) {                                      // (uniform: every thread took the same branch above)
+#pragma unroll
+    for (int e = 0; e < E; ++e)
+      if (tid + e * nt < N) too_wide |= ((hreg[e] >> (32 - ib)) != 0 ? 1 : 0) | ((hreg[e] >> (64 - ib)) != 0 ? 2 : 0);
+    // (the block-wide OR is a logical one: reduce the two bits separately)
+    const int over32 = __syncthreads_or(too_wide & 1);
+    const int over64 = __syncthreads_or(too_wide & 2);
+    too_wide = (over32 ? 1 : 0) | (over64 ? 2 : 0);
   }
-  // (the block-wide OR is a logical one: reduce the two bits separately)
-  const int over32 = __syncthreads_or(too_wide & 1);
-  const int over64 = __syncthreads_or(too_wide & 2);
-  too_wide = (over32 ? 1 : 0) | (over64 ? 2 : 0);
   if (sorted) {
     // nothing left to do
   } else if (too_wide == 0) {

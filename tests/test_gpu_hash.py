@@ -96,6 +96,28 @@ def test_shapes_and_ragged_edges(vd, ctx, B, N, L, k):
     assert flips <= (~ok).sum()
 
 
+@pytest.mark.parametrize("B,N,L,k,f_min,f_max", [(8, 4099, 512, 5, 1, None), (40, 530, 448, 4, 1, None),
+                                                  (3, 8200, 384, 3, 1, None), (16, 2060, 512, 4, 0, 256),
+                                                  (8, 4100, 400, 3, 3, 66)])
+def test_long_windows_with_many_row_blocks_per_compute_unit(vd, ctx, B, N, L, k, f_min, f_max):
+    """Shapes that take the pipelined kernel (long aligned windows, at least four row blocks per compute unit): a
+    ragged last group, more than 32 windows per variate (two row blocks per group), groups of 8 variates, candidate
+    ranges with and without the mean and the Nyquist bin and with one or two bins beside the tiles."""
+    rng = np.random.default_rng(B * 1000 + L + N)
+    x = rng.standard_normal((B, N, L)).astype(np.float32)
+    t = np.arange(L)
+    lo, hi = max(f_min, 1), (o_kdfh.default_cutoff(L) if f_max is None else min(f_max, L // 2 - 1))
+    lines = rng.integers(lo, hi + 1, size=(N, 3))
+    phase = rng.uniform(0, 6, size=(B, N, 3))
+    for j in range(3):
+        x += ((4.0 / (1 + j)) * np.sin(2 * np.pi * lines[None, :, j, None] * t[None, None, :] / L + phase[:, :, j, None])).astype(np.float32)
+    x *= np.exp(rng.uniform(-3, 3, size=(1, N, 1))).astype(np.float32)            # per-variate scale
+    topk, hsh, want_topk, want_hash, flips, flips_screened, ok = compare(vd, ctx, x, k, f_min=f_min, f_max=f_max)
+    assert flips_screened == 0 and ok.sum() >= N // 2
+    assert np.array_equal(hsh[ok], want_hash[ok])
+    assert flips <= (~ok).sum()
+
+
 def test_candidate_range_parameters(vd, ctx):
     rng = np.random.default_rng(3)
     x = (rng.standard_normal((4, 6, 96)) + 2.0).astype(np.float32)        # large mean: bin 0 dominates when allowed
