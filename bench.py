@@ -61,6 +61,7 @@ def algorithmic_work(w, n):
         "embed_rows": ("hbm", 4.0 * M * L + float(es) * M * L),
         "gemm_embed": (mm, 2.0 * M * L * d),
         "gemm_dwe": (mm, 2.0 * M * L * d),
+        "embed_fused": (mm, 2.0 * M * L * d),
     }
 
 
@@ -276,196 +277,6 @@ def steady_bandwidth(args):
                       "kernels": out}))
 
 
-def embed_steps(args):
-    """--embed: the step with the token embedding of the kept variates inside it (host-side N', calls issued one by one)."""
-    import numpy as np
-    import torch
-    import paper_2501_14183_amd as vd
-    import workloads as wl
-
-    import dataclasses
-    w = wl.WORKLOADS[args.workload]
-    K_MAX = 5                                           # largest k of the sweep (sizes the top-k buffers)
-    if args.k:
-        w = dataclasses.replace(w, k=args.k)
-    gs_cap = args.gs                                    # > 0: Eq. 1 with this cap and no keep ratio
-    td = torch.bfloat16 if w.dtype == "bf16" else torch.float32
-    dev = torch.device("cuda", 0)
-    torch.cuda.set_device(dev)
-    ctx = vd.Context(0)
-
-    # ---- synthetic inputs, resident in HBM before anything is timed
-    xs_dev, tok_dev, host = [], [], None
-    for i in range(args.batches):
-        x_np, _ = wl.make_signals(w, seed=i)
-        tok_np = wl.make_tokens(w, x_np, seed=i)
-        if i == 0:
-            host = (x_np, tok_np)
-        xs_dev.append(torch.from_numpy(x_np).to(dev))
-        tok_dev.append(torch.from_numpy(tok_np).to(dev).to(td))
-    W_np = wl.make_weights(w, seed=0)
-    W_dev = [torch.from_numpy(m).to(dev).to(td) for m in W_np]
-    dy_full = torch.from_numpy(wl.make_upstream(w, w.N, seed=0)).to(dev).to(td).reshape(-1)
-    stream = torch.cuda.current_stream()
-    seed = 0x5EED
-    if args.embed:
-        gen = torch.Generator(device=dev)
-        gen.manual_seed(4321)
-        We_dev = (torch.randn((w.L, w.d), generator=gen, device=dev) / w.L ** 0.5).to(td)
-        be_dev = (0.1 * torch.randn(w.d, generator=gen, device=dev)).to(td)
-        all_idx = torch.arange(w.N, dtype=torch.int32, device=dev)
-    saved = ws = None
-    stats = {"n_sel": [], "G": []}
-
-    # The selection of a batch depends on its windows only, not on the model, so it runs LOOK batches
-    # ahead of the attention and on a stream of its own (default priority): the small k-DFH and sampling
-    # kernels then overlap the attention of earlier batches, and the 8-byte read-back of {N', G}
-    # that sizes the attention launch is complete when the host needs it.
-    # Cross-stream events on the attention stream cost several microseconds each (a marker packet
-    # between two kernels), so the attention stream carries none per step: the outputs of the
-    # selection live in a ring of RING buffer sets, and the host never runs more than RING - LOOK - FENCE
-    # batches ahead of the attention stream (one event every FENCE steps, waited for FENCE steps
-    # later), so a set is never rewritten while a gather may still read it.
-    LOOK, FENCE, RING = 2, 8, 32
-    pinned = [torch.zeros(2, dtype=torch.int32).pin_memory() for _ in range(RING)]
-    events = [torch.cuda.Event() for _ in range(RING)]
-    side = torch.cuda.Stream(device=dev)
-    main_h, side_h = stream.cuda_stream, side.cuda_stream      # raw handles: the binding then skips torch's stream lookup
-    sel_bufs = [(torch.empty((w.N, max(w.k, K_MAX)), dtype=torch.int32, device=dev), torch.empty(w.N, dtype=torch.int64, device=dev),
-                 torch.empty(w.N, dtype=torch.int32, device=dev), torch.empty(w.N, dtype=torch.int32, device=dev),
-                 torch.empty(2, dtype=torch.int32, device=dev)) for _ in range(RING)]
-    fences = {}                                         # step -> event recorded on the attention stream after it
-
-    def select(i):
-        if args.dense:
-            return
-        j = i % RING
-        topk, hsh, gid, sel, counts = sel_bufs[j]
-        vd.vardrop_hash(ctx, xs_dev[i % args.batches], w.k, out=(topk, hsh), stream=side_h)
-        num, den = (1, 1) if gs_cap else w.ratio
-        vd.vardrop_sample(ctx, hsh, gs_cap, num, den, seed, i, counts_host=pinned[j], out=(gid, sel, counts),
-                          stream=side_h)
-        events[j].record(side)
-
-    def attend(i):
-        nonlocal saved, ws
-        j = i % RING
-        tok = tok_dev[i % args.batches]
-        if args.dense:
-            n_sel, G = w.N, w.N
-            count = w.B * n_sel * w.d
-            shape = (w.B, n_sel, w.d)
-            xs = tok
-        else:
-            sel = sel_bufs[j][3]
-            events[j].synchronize()                # N' of batch i (launched LOOK steps earlier)
-            n_sel, G = int(pinned[j][0]), int(pinned[j][1])
-            count = w.B * n_sel * w.d
-            shape = (w.B, n_sel, w.d)
-        if args.embed:
-            # tokens of the kept variates (all of them with --dense) straight from the raw windows, then attention
-            xs, _ = vd.vardrop_embed_fwd(ctx, xs_dev[i % args.batches], all_idx if args.dense else sel, n_sel, We_dev, be_dev,
-                                         saved=esaved, out=xs_buf[:count].view(shape), stream=main_h)
-            y, saved = vd.vardrop_attn_fwd(ctx, xs, *W_dev, w.H, saved=saved, out=y_buf[:count].view(shape), stream=main_h)
-        elif args.dense:
-            y, saved = vd.vardrop_attn_fwd(ctx, xs, *W_dev, w.H, saved=saved, out=y_buf[:count].view(shape), stream=main_h)
-        else:
-            # gather + forward in one call: for N' <= 128 the forward kernel fetches the kept rows itself
-            xs, y, saved = vd.vardrop_gather_attn_fwd(ctx, tok, sel, n_sel, *W_dev, w.H, saved=saved,
-                                                      out=(xs_buf[:count].view(shape), y_buf[:count].view(shape)), stream=main_h)
-        dy = dy_full[:count].view(shape)
-        grads = vd.vardrop_attn_bwd(ctx, dy, xs, *W_dev, w.H, saved, ws=ws, out=(dxs_buf[:count].view(shape), *dW_buf),
-                                      stream=main_h)
-        if args.embed:
-            vd.vardrop_embed_bwd(ctx, grads[0], w.L, esaved, ws=ews, out=dWe_buf, stream=main_h)
-        stats["n_sel"].append(n_sel)
-        stats["G"].append(G)
-        return grads
-
-    def run(first, count):
-        """`count` whole steps: every batch gets its selection and its attention inside this call."""
-        torch.cuda.synchronize()                   # buffer sets are reused from the start: nothing of an earlier call is left
-        fences.clear()
-        for i in range(first, min(first + LOOK, first + count)):
-            select(i)
-        for i in range(first, first + count):
-            if (i - first) % FENCE == 0:
-                old = fences.pop(i - FENCE, None)
-                if old is not None:
-                    old.synchronize()              # the attention stream has finished step i - FENCE - 1
-                ev = torch.cuda.Event()
-                ev.record(stream)
-                fences[i] = ev
-            if i + LOOK < first + count:
-                select(i + LOOK)
-            attend(i)
-
-    # size the reusable buffers for the largest selection (never re-allocated inside the timed region)
-    lib = vd.load_library()
-    code = vd.BF16 if w.dtype == "bf16" else vd.F32
-    saved = torch.empty(lib.vardrop_attn_saved_bytes(w.B, w.N, w.d, w.H, code), dtype=torch.uint8, device=dev)
-    ws = torch.empty(lib.vardrop_attn_workspace_bytes(w.B, w.N, w.d, w.H, code), dtype=torch.uint8, device=dev)
-
-    if args.embed:
-        esaved = torch.empty(lib.vardrop_embed_saved_bytes(w.B, w.N, w.L, code), dtype=torch.uint8, device=dev)
-        ews = torch.empty(max(lib.vardrop_embed_workspace_bytes(w.B, w.N, w.L, w.d, code), 256), dtype=torch.uint8, device=dev)
-        dWe_buf = (torch.empty((w.L, w.d), dtype=torch.float32, device=dev), torch.empty(w.d, dtype=torch.float32, device=dev))
-
-    # outputs of a step, sized for the largest selection as well (every call writes all of what it returns)
-    xs_buf, y_buf, dxs_buf = (torch.empty(w.B * w.N * w.d, dtype=td, device=dev) for _ in range(3))
-    dW_buf = [torch.empty((w.d, w.d), dtype=torch.float32, device=dev) for _ in range(4)]
-
-    if args.copy_calibration:
-        src = torch.zeros(256 << 20, dtype=torch.uint8, device=dev)
-        dst = torch.empty_like(src)
-        for _ in range(5):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
-
-    run(0, args.warmup)
-    torch.cuda.synchronize()
-
-    stats = {"n_sel": [], "G": []}
-    t0 = time.perf_counter()
-    run(args.warmup, args.steps)
-    t_host = time.perf_counter()                   # every launch of the timed steps has been issued
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms = (t1 - t0) * 1e3 / args.steps
-    host_ms = (t_host - t0) * 1e3 / args.steps
-    n_mean = float(np.mean(stats["n_sel"]))
-    # per-kernel durations of the same steps (events tied to every dispatch), untimed pass
-    vd.vardrop_profile_select(ctx, vd.K_ALL)
-    run(args.warmup, 8)
-    per_kernel = vd.vardrop_profile_read_all(ctx)
-    vd.vardrop_profile_select(ctx, -1)
-    work = algorithmic_work(w, n_mean)
-    roof_all = kernel_rooflines(per_kernel, work)
-    on_critical_path = {k: v for k, v in roof_all.items() if k not in ("hash", "sample")}
-    dominant = max(on_critical_path, key=lambda k: on_critical_path[k]["us_per_step"])
-    roof = dict(kernel=dominant, **{k: v for k, v in roof_all[dominant].items()}, traffic=None)
-    args.no_cpu_baseline = True                     # the oracle leg times the dropping path on pre-embedded tokens
-    out = {
-        "metric": (("dense (no dropping) variate-attn train steps/s (SDPA fwd/bwd over all N tokens)" if args.dense else
-                    "variate-attn train steps/s (kDFH+sample+SDPA fwd/bwd), HBM GB/s, MFMA %peak") +
-                   (" + token embedding fwd/bwd inside the step" if args.embed else "")),
-        "value": 1e3 / ms, "unit": "steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms, "host_issue_ms_per_step": host_ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": w.dtype, "data": "synthetic",
-        "config": {"workload": ("%s-shaped, dense: B=%d N=%d d=%d H=%d, selection = identity" % (w.name, w.B, w.N, w.d, w.H))
-                               if args.dense else "%s-shaped: B=%d N=%d L=%d k=%d keep=%d/%d d=%d H=%d" %
-                               (w.name, w.B, w.N, w.L, w.k, w.ratio[0], w.ratio[1], w.d, w.H),
-                   "k": w.k, "gs": gs_cap if gs_cap else None,
-                   "kept_tokens_mean": n_mean, "groups_mean": float(np.mean(stats["G"])),
-                   "batches": args.batches},
-        "roofline": roof, "roofline_all": roof_all,
-    }
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, host[0], host[1], W_np, seed)
-    print(json.dumps(out))
-
-
 def kernel_rooflines(per_kernel, work, steps=8):
     """{kernel: (summed ms, launches)} of `steps` steps + algorithmic work per launch -> roofline entry per kernel."""
     out = {}
@@ -500,12 +311,13 @@ class Pipeline:
     """
     BURST, RING = 4, 12
 
-    def __init__(self, vd, ctx, w, xs_dev, tok_dev, W_dev, dy_full, seed, gs_cap=0, dense=False):
+    def __init__(self, vd, ctx, w, xs_dev, tok_dev, W_dev, dy_full, seed, gs_cap=0, dense=False, embed=None):
         import torch
         self.vd, self.ctx, self.w, self.torch = vd, ctx, w, torch
         self.xs_dev, self.tok_dev, self.W_dev, self.dy_full = xs_dev, tok_dev, W_dev, dy_full
         self.nb = len(xs_dev)
         self.seed, self.gs_cap, self.dense = seed, gs_cap, dense
+        self.embed = embed                          # (We, be): tokens are embedded from the raw windows inside the step
         self.ratio = (1, 1) if gs_cap else w.ratio
         dev = xs_dev[0].device
         self.main = torch.cuda.Stream(device=dev)
@@ -542,6 +354,10 @@ class Pipeline:
         self.ws = torch.empty(lib.vardrop_attn_workspace_bytes(w.B, self.n_max, w.d, w.H, code), dtype=torch.uint8, device=dev)
         self.xs_buf, self.y_buf, self.dxs_buf = (torch.empty((w.B, self.n_max, w.d), dtype=td, device=dev) for _ in range(3))
         self.dW_buf = [torch.empty((w.d, w.d), dtype=torch.float32, device=dev) for _ in range(4)]
+        if embed is not None:
+            self.esaved = torch.empty(lib.vardrop_embed_saved_bytes(w.B, self.n_max, w.L, code), dtype=torch.uint8, device=dev)
+            self.ews = torch.empty(max(lib.vardrop_embed_workspace_bytes(w.B, self.n_max, w.L, w.d, code), 256), dtype=torch.uint8, device=dev)
+            self.dWe_buf = (torch.empty((w.L, w.d), dtype=torch.float32, device=dev), torch.empty(w.d, dtype=torch.float32, device=dev))
         self.graphs = None
 
     def select(self, b, r, stream):
@@ -555,10 +371,20 @@ class Pipeline:
     def attend(self, b, r, stream):
         vd, w = self.vd, self.w
         sel, counts = self.ring[r][3], self.ring[r][4]
-        vd.vardrop_gather_attn_fwd_dev(self.ctx, self.tok_dev[b], sel, counts, self.n_max, *self.W_dev, w.H,
-                                       self.xs_buf, self.y_buf, self.saved, status=self.status, stream=stream.cuda_stream)
+        if self.embed is not None:
+            # tokens of the kept variates straight from the raw windows (no token tensor of all variates exists)
+            vd.vardrop_embed_fwd_dev(self.ctx, self.xs_dev[b], sel, counts, self.n_max, self.embed[0], self.embed[1],
+                                     self.xs_buf, self.esaved, status=self.status, stream=stream.cuda_stream)
+            vd.vardrop_attn_fwd_dev(self.ctx, self.xs_buf, counts, self.n_max, *self.W_dev, w.H, self.y_buf, self.saved,
+                                    status=self.status, stream=stream.cuda_stream)
+        else:
+            vd.vardrop_gather_attn_fwd_dev(self.ctx, self.tok_dev[b], sel, counts, self.n_max, *self.W_dev, w.H,
+                                           self.xs_buf, self.y_buf, self.saved, status=self.status, stream=stream.cuda_stream)
         vd.vardrop_attn_bwd_dev(self.ctx, self.dy_full, self.xs_buf, counts, self.n_max, *self.W_dev, w.H, self.saved,
                                 self.ws, (self.dxs_buf, *self.dW_buf), status=self.status, stream=stream.cuda_stream)
+        if self.embed is not None:
+            vd.vardrop_embed_bwd_dev(self.ctx, self.dxs_buf, counts, self.n_max, w.L, self.esaved, self.ews, self.dWe_buf,
+                                     stream=stream.cuda_stream)
 
     def issue(self, g):
         """Step g: attention of batch g % nb (ring g % 2) beside the selection of the next batch (other ring set)."""
@@ -728,8 +554,6 @@ def main():
         sys.exit(2)
     if args.mode == "bandwidth":
         return steady_bandwidth(args)
-    if args.embed:
-        return embed_steps(args)
     import dataclasses
     import numpy as np
     import torch
@@ -786,7 +610,13 @@ def main():
                           "table": table}))
         return
 
-    pipe = Pipeline(vd, ctx, w, xs_dev, tok_dev, W_dev, dy_full, seed, gs_cap=args.gs, dense=args.dense)
+    embed = None
+    if args.embed:
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(4321)
+        embed = ((torch.randn((w.L, w.d), generator=gen, device=dev) / w.L ** 0.5).to(td),
+                 (0.1 * torch.randn(w.d, generator=gen, device=dev)).to(td))
+    pipe = Pipeline(vd, ctx, w, xs_dev, tok_dev, W_dev, dy_full, seed, gs_cap=args.gs, dense=args.dense, embed=embed)
     ms, host_ms = timed_steps(pipe, args, args.launch)
     n_mean, g_mean = pipe.kept(args.warmup, args.steps)
 
@@ -821,14 +651,15 @@ def main():
         roof_all["attention_fwd_bwd"] = {"bound": "mfma", "achieved": flops / (us * 1e-6) / 1e12, "peak": PEAK_BF16_TFLOPS,
                                          "unit": "TFLOP/s", "frac": flops / (us * 1e-6) / 1e12 / PEAK_BF16_TFLOPS,
                                          "us_per_step": us, "kernels": sorted(attn)}
-    if not args.dense:
+    if not args.dense and not args.embed:
         steady = steady_hash_gather(vd, ctx, w, pipe.main)
         roof_all["hash_steady_state"] = steady["hash"]
         roof_all["gather_steady_state"] = steady["gather"]
 
     out = {
-        "metric": ("dense (no dropping) variate-attn train steps/s (SDPA fwd/bwd over all N tokens)" if args.dense else
-                   "variate-attn train steps/s (kDFH+sample+SDPA fwd/bwd), HBM GB/s, MFMA %peak"),
+        "metric": (("dense (no dropping) variate-attn train steps/s (SDPA fwd/bwd over all N tokens)" if args.dense else
+                    "variate-attn train steps/s (kDFH+sample+SDPA fwd/bwd), HBM GB/s, MFMA %peak") +
+                   (" + token embedding fwd/bwd of the kept variates inside the step" if args.embed else "")),
         "value": 1e3 / ms, "unit": "steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms, "host_issue_ms_per_step": host_ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
@@ -842,7 +673,7 @@ def main():
     }
     # ---- the paper's own rule for this dataset shape (Table 8: Traffic k = 4, gs = 10; Electricity k = 3, gs = 10)
     paper_rule = {"traffic": (4, 10), "electricity": (3, 10)}.get(w.name)
-    if paper_rule and not (args.dense or args.gs or args.k or args.no_paper_rule):
+    if paper_rule and not (args.dense or args.gs or args.k or args.no_paper_rule or args.embed):
         wk = dataclasses.replace(w, k=paper_rule[0])
         p2 = Pipeline(vd, ctx, wk, xs_dev, tok_dev, W_dev, dy_full, seed, gs_cap=paper_rule[1])
         ms2, host2 = timed_steps(p2, args, args.launch)
@@ -851,7 +682,7 @@ def main():
                              "value": 1e3 / ms2, "unit": "steps/s", "ms_per_step": ms2, "host_issue_ms_per_step": host2,
                              "kept_tokens_mean": n2, "groups_mean": g2, "delta": 1.0 - n2 / w.N, "token_bound": p2.n_max}
         del p2
-    if not args.dense and not args.no_cpu_baseline:
+    if not args.dense and not args.embed and not args.no_cpu_baseline:
         gpu_topk = None
         topk0 = torch.empty((w.N, w.k), dtype=torch.int32, device=dev)
         hsh0 = torch.empty(w.N, dtype=torch.int64, device=dev)

@@ -97,6 +97,7 @@ enum {
   VARDROP_K_GEMM_EMBED,      /* xs = z We + be                                              */
   VARDROP_K_GEMM_DWE,        /* dWe = z^T dxs (K slices)                                    */
   VARDROP_K_SDPA_BWD_DQKV,   /* bf16, n > 128, few workgroups: dQ, dK, dV in one launch (GEMM_DO then forms rowsum(dO * O)) */
+  VARDROP_K_EMBED_FUSED,     /* kept windows gathered, standardised and embedded in one launch (bf16, short windows) */
   VARDROP_K_COUNT
 };
 int vardrop_profile_select(vardrop_ctx* ctx, int kernel_id);
@@ -255,12 +256,18 @@ int vardrop_scatter_dev(vardrop_ctx* ctx, const void* dxs, int B, int N, int d, 
  *   sel    device int32 [n_sel], entries within 0..N-1 (an out-of-range entry gives a zero window)
  *   We     [L][d] row-major, `dtype`;  be [d], `dtype`, NULL = none
  *   saved  vardrop_embed_saved_bytes: the windows z in `dtype` (VARDROP_BF16: rows zero-padded to a
- *          multiple of 64 samples); written by fwd, read by bwd; 256-byte aligned
+ *          multiple of 64 samples; windows of at most 383 samples carry a one at position L, which makes the
+ *          bias gradient a row of the same product as dWe); written by fwd, read by bwd; 256-byte aligned
  *   dWe    fp32 [L][d], overwritten;  dbe fp32 [d], overwritten, NULL = skip
  *   ws     bwd only: vardrop_embed_workspace_bytes (partial sums of the gradients), 256-byte aligned
  * VARDROP_BF16 rounds z to bf16 and multiplies on the matrix cores with fp32 accumulation; it requires
  * d % 8 == 0, L % 8 == 0 and B*n_sel*max(d, L+63) < 2^31.  VARDROP_F32 is plain fp32.  2 <= L <= 1024.
  * n_sel == 0 is a no-op for fwd; bwd then zero-fills the gradients.
+ * VARDROP_BF16 windows of at most 383 samples take one kernel forward (gather through sel, standardisation and
+ * the product: the standardised window is formed inside the product's operand load and written to `saved` on
+ * the way) and one product plus its slice sum backward; longer windows and VARDROP_F32 take a standardisation
+ * kernel followed by the product.  The _dev variants read the count of kept windows on the device (see the
+ * general rules; xs and dxs packed [B][N'][d]; sizes for n_max; single-kernel path only, EUNSUPPORTED otherwise).
  */
 size_t vardrop_embed_saved_bytes(int B, int n_sel, int L, int dtype);
 size_t vardrop_embed_workspace_bytes(int B, int n_sel, int L, int d, int dtype);
@@ -271,6 +278,13 @@ int vardrop_embed_fwd(vardrop_ctx* ctx, const float* x, int B, int N, int L, int
 int vardrop_embed_bwd(vardrop_ctx* ctx, const void* dxs, int B, int n_sel, int L, int d, int dtype,
                       const void* saved, float* dWe, float* dbe,
                       void* ws, size_t ws_bytes, void* stream);
+int vardrop_embed_fwd_dev(vardrop_ctx* ctx, const float* x, int B, int N, int L, int64_t sb, int64_t sn,
+                          const int32_t* sel, const int32_t* n_dev, int n_max, int32_t* status, int standardise,
+                          const void* We, const void* be, int d, int dtype,
+                          void* xs, void* saved, void* stream);
+int vardrop_embed_bwd_dev(vardrop_ctx* ctx, const void* dxs, int B, const int32_t* n_dev, int n_max, int L, int d,
+                          int dtype, const void* saved, float* dWe, float* dbe,
+                          void* ws, size_t ws_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------
  * Multi-head scaled dot-product attention over the kept tokens -- Eq. 3,
@@ -331,6 +345,12 @@ int vardrop_gather_attn_fwd_dev(vardrop_ctx* ctx, const void* tokens, int B, int
                                 const void* Wq, const void* Wk, const void* Wv, const void* Wo,
                                 const void* bq, const void* bk, const void* bv, const void* bo,
                                 void* xs, void* y, void* saved, void* ws, size_t ws_bytes, void* stream);
+/* vardrop_attn_fwd with a device-side token count, for tokens that are already packed [B][N'][d]. */
+int vardrop_attn_fwd_dev(vardrop_ctx* ctx, const void* xs, int B, const int32_t* n_dev, int n_max, int32_t* status,
+                         int d, int H, int dtype,
+                         const void* Wq, const void* Wk, const void* Wv, const void* Wo,
+                         const void* bq, const void* bk, const void* bv, const void* bo,
+                         void* y, void* saved, void* ws, size_t ws_bytes, void* stream);
 int vardrop_attn_bwd_dev(vardrop_ctx* ctx, const void* dy, const void* xs,
                          int B, const int32_t* n_dev, int n_max, int32_t* status, int d, int H, int dtype,
                          const void* Wq, const void* Wk, const void* Wv, const void* Wo,

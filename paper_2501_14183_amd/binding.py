@@ -56,6 +56,12 @@ _SIGNATURES = {
                                    _ptr, _ptr, _c_int, _c_int, _ptr, _ptr, _ptr]),
     "vardrop_embed_bwd": (_c_int, [_ptr, _ptr, _c_int, _c_int, _c_int, _c_int, _c_int, _ptr, _ptr, _ptr,
                                    _ptr, _c_size, _ptr]),
+    "vardrop_embed_fwd_dev": (_c_int, [_ptr, _ptr, _c_int, _c_int, _c_int, _c_i64, _c_i64, _ptr, _ptr, _c_int, _ptr, _c_int,
+                                       _ptr, _ptr, _c_int, _c_int, _ptr, _ptr, _ptr]),
+    "vardrop_embed_bwd_dev": (_c_int, [_ptr, _ptr, _c_int, _ptr, _c_int, _c_int, _c_int, _c_int, _ptr, _ptr, _ptr,
+                                       _ptr, _c_size, _ptr]),
+    "vardrop_attn_fwd_dev": (_c_int, [_ptr, _ptr, _c_int, _ptr, _c_int, _ptr, _c_int, _c_int, _c_int] + [_ptr] * 8 +
+                             [_ptr, _ptr, _ptr, _c_size, _ptr]),
     "vardrop_attn_saved_bytes": (_c_size, [_c_int] * 5),
     "vardrop_attn_workspace_bytes": (_c_size, [_c_int] * 5),
     "vardrop_attn_fwd": (_c_int, [_ptr, _ptr, _c_int, _c_int, _c_int, _c_int, _c_int] + [_ptr] * 8 +
@@ -441,3 +447,34 @@ def vardrop_sample_nearest_noalloc(ctx, hsh, abar, gs, ratio_num, ratio_den, out
                                                  _p(gid), _p(sel), _p(counts), _stream(hsh, stream))
     ctx.check(rc, "vardrop_sample_nearest_noalloc")
     return gid, sel, counts
+
+
+def vardrop_attn_fwd_dev(ctx, xs, n_dev, n_max, Wq, Wk, Wv, Wo, H, y, saved, bq=None, bk=None, bv=None, bo=None,
+                         status=None, stream=None):
+    """Attention forward on packed tokens xs ([B, n_max, d] buffer holding [B, N', d]) with N' read on the device."""
+    B, d = xs.shape[0], Wq.shape[0]
+    rc = ctx._lib.vardrop_attn_fwd_dev(ctx.handle, _p(xs), B, _p(n_dev), n_max, _p(status), d, H, _dtype_code(Wq),
+                                       _p(Wq), _p(Wk), _p(Wv), _p(Wo), _p(bq), _p(bk), _p(bv), _p(bo),
+                                       _p(y), _p(saved), None, 0, _stream(xs, stream))
+    ctx.check(rc, "vardrop_attn_fwd_dev")
+    return y, saved
+
+
+def vardrop_embed_fwd_dev(ctx, x, sel, n_dev, n_max, We, be, xs, saved, standardise=True, status=None, stream=None):
+    """Embedding of the kept windows with their count read on the device; xs: [B, n_max, d] buffer, packed [B, N', d]."""
+    B, N, L = x.shape
+    rc = ctx._lib.vardrop_embed_fwd_dev(ctx.handle, _p(x), B, N, L, x.stride(0), x.stride(1), _p(sel), _p(n_dev), n_max,
+                                        _p(status), 1 if standardise else 0, _p(We), _p(be), We.shape[1], _dtype_code(We),
+                                        _p(xs), _p(saved), _stream(x, stream))
+    ctx.check(rc, "vardrop_embed_fwd_dev")
+    return xs, saved
+
+
+def vardrop_embed_bwd_dev(ctx, dxs, n_dev, n_max, L, saved, ws, out, stream=None):
+    """Weight gradients of the embedding with the count read on the device; out = (dWe, dbe or None)."""
+    B, d = dxs.shape[0], dxs.shape[-1]
+    dWe, dbe = out
+    rc = ctx._lib.vardrop_embed_bwd_dev(ctx.handle, _p(dxs), B, _p(n_dev), n_max, L, d, _dtype_code(dxs), _p(saved),
+                                        _p(dWe), _p(dbe), _p(ws), ws.numel(), _stream(dxs, stream))
+    ctx.check(rc, "vardrop_embed_bwd_dev")
+    return dWe, dbe

@@ -166,6 +166,32 @@ extern "C" int vardrop_gather_attn_fwd_dev(vardrop_ctx* ctx, const void* tokens,
   return vd_attn_fwd_bf16(ctx, tokens, B, n_max, d, H, W, bias, y, saved, ws, s, sel, N, xs, dn);
 }
 
+// The forward pass on tokens that are already packed for the count (as vardrop_embed_fwd_dev writes them).
+extern "C" int vardrop_attn_fwd_dev(vardrop_ctx* ctx, const void* xs, int B, const int32_t* n_dev, int n_max, int32_t* status,
+                                    int d, int H, int dtype,
+                                    const void* Wq, const void* Wk, const void* Wv, const void* Wo,
+                                    const void* bq, const void* bk, const void* bv, const void* bo,
+                                    void* y, void* saved, void* ws, size_t ws_bytes, void* stream) {
+  (void)ws_bytes;
+  if (!ctx || !n_dev || n_max < 1) return VARDROP_EINVAL;
+  int rc = check_shape(B, n_max, d, H, dtype);
+  if (rc) return rc;
+  if (B == 0) return VARDROP_OK;
+  if (!xs || !Wq || !Wk || !Wv || !Wo || !y || !saved) return VARDROP_EINVAL;
+  if (!vd_aligned(saved, 256)) return VARDROP_EWORKSPACE;
+  if (!vd_aligned(xs, 16) || !vd_aligned(y, 16) || !vd_aligned(Wq, 16) || !vd_aligned(Wk, 16) ||
+      !vd_aligned(Wv, 16) || !vd_aligned(Wo, 16))
+    return VARDROP_EINVAL;
+  const void* W[4] = {Wq, Wk, Wv, Wo};
+  const void* bias[4] = {bq, bk, bv, bo};
+  hipStream_t s = (hipStream_t)stream;
+  const VdDevCount dn = {n_dev, status};
+  if (dtype == VARDROP_F32)
+    return vd_attn_fwd_f32(ctx, (const float*)xs, B, n_max, d, H, (const float* const*)W, (const float* const*)bias,
+                           (float*)y, saved, ws, s, dn);
+  return vd_attn_fwd_bf16(ctx, xs, B, n_max, d, H, W, bias, y, saved, ws, s, nullptr, 0, nullptr, dn);
+}
+
 extern "C" int vardrop_attn_bwd_dev(vardrop_ctx* ctx, const void* dy, const void* xs,
                                     int B, const int32_t* n_dev, int n_max, int32_t* status, int d, int H, int dtype,
                                     const void* Wq, const void* Wk, const void* Wv, const void* Wo,

@@ -123,6 +123,19 @@ int vd_gemm_f32(vardrop_ctx*, int kid, const float* A, long long sam, long long 
                 int M, int N, int K, hipStream_t s);
 
 // attention back ends (attn_f32.hip, attn_bf16.hip); argument checks are done by the caller
+// K slices of the embedding's weight gradient dWe = z^T dxs (K = B * n_sel rows; tiles of 64 x 128): enough of them
+// to give the chip two workgroups per compute unit, at least 128 rows each, at most 16.  (Host and device.)
+__host__ __device__ static inline int vd_embed_splitk(int L, int d, long long M, int* kchunk) {
+  const int tiles = vd_ceil_div(L, 64) * vd_ceil_div(d, 128);
+  int s = vd_ceil_div(512, tiles);
+  if (s > 16) s = 16;
+  while (s > 1 && M / s < 128) --s;
+  int chunk = (int)vd_align_up((size_t)vd_ceil_div((int)M, s), 64);
+  if (chunk < 64) chunk = 64;
+  if (kchunk) *kchunk = chunk;
+  return M > 0 ? vd_ceil_div((int)M, chunk) : 1;
+}
+
 // A count that may live in device memory (see vd_count): with dev != nullptr the `n` of the call is its bound.
 struct VdDevCount {
   const int32_t* dev;

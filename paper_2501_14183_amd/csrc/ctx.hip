@@ -80,7 +80,7 @@ extern "C" const char* vardrop_kernel_name(int kernel_id) {
   static const char* const names[VARDROP_K_COUNT] = {
       "hash", "sample", "gather", "gemm_qkv", "sdpa_fwd", "gemm_out", "gemm_do",
       "sdpa_bwd_dq", "sdpa_bwd_dkv", "gemm_dw", "reduce_dw", "gemm_dxs", "scatter", "gemm_dw_dxs", "sdpa_bwd", "qkv_sdpa_fwd",
-      "embed_rows", "gemm_embed", "gemm_dwe", "sdpa_bwd_dqkv"};
+      "embed_rows", "gemm_embed", "gemm_dwe", "sdpa_bwd_dqkv", "embed_fused"};
   return (kernel_id >= 0 && kernel_id < VARDROP_K_COUNT) ? names[kernel_id] : nullptr;
 }
 

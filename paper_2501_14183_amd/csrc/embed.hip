@@ -2,6 +2,10 @@
 // variates, so the tokens of the dropped ones are never formed): xs = z We + be, where z are the kept
 // windows, optionally standardised over time, and its weight gradients dWe = z^T dxs, dbe = colsum(dxs).
 //
+// Short windows in bf16 (at most 383 samples) take one kernel forward: the standardisation happens inside the
+// operand load of the product (embed_fwd_fused_kernel below), and one product backward, which also yields the bias
+// gradient (a column of ones rides beside the window in the saved operand).  Everything else takes two steps.
+//
 // Two steps.  (1) One wavefront per kept window reads it from the raw batch through `sel` (coalesced:
 // consecutive lanes read consecutive samples), takes mean and variance with wavefront reductions in a
 // fixed order, and writes the standardised window in the operand type: bf16 rows padded with zeros to a
@@ -67,6 +71,193 @@ __global__ __launch_bounds__(256) void embed_rows_kernel(const float* __restrict
   }
 }
 
+
+// ------------------------------------------------------------------ fused forward (bf16, short windows)
+// xs[m][:] = z[m][:] We + be for a tile of 64 kept windows x 128 columns, with z formed inside the kernel: the
+// workgroup requests the whole We panel of its columns ([Lp][128], asynchronous copies into LDS), and while that
+// travels four threads per window read the tile's 64 windows from the raw batch through `sel`, standardise them
+// (mean and variance: partial sums of the four threads, joined in a fixed order) and write them as bf16 into the LDS tile the
+// matrix instruction reads its left operand from; the column tile 0 also writes them to `saved` for the backward
+// pass, with a one at sample position L (so that z^T dxs has the column sums of dxs, the bias gradient, as row L).
+// LDS: KT = Lp / 64 slices of the z tile ([64][64] bf16, 16-byte chunk position XORed with row % 8) and of the We
+// panel ([64][128] bf16, chunk position XORed as in the GEMM's n-contiguous operands), then reused for the output tile.
+struct EmbedFused {
+  const float* x;
+  const int32_t* sel;
+  const bf16_t* We;
+  const bf16_t* be;
+  bf16_t* xs;
+  bf16_t* saved;
+  long long sb, sn;
+  int N, L, Lp, n_sel, d, standardise;
+  int vec;                    // rows can be read as aligned float4 (x, sb, sn multiples of 4 elements)
+  long long M;
+  const int32_t* n_dev;       // device-side count of kept windows (then n_sel is its bound, see vd_count)
+  int32_t* status;
+  int B;
+};
+constexpr int kEmbedMaxKT = 6;
+
+template <int UL>   // samples per lane: Lp / 64
+__global__ __launch_bounds__(256, 2) void embed_fwd_fused_kernel(EmbedFused a) {
+  constexpr int BM = 64, BN = 128, A_SLICE = BM * 64 * 2, B_SLICE = 64 * BN * 2, CPITCH = BN * 2 + 16;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  int n_sel;
+  if (!vd_count(a.n_dev, a.n_sel, n_sel, a.status) || n_sel == 0) return;
+  const long long M = a.n_dev ? (long long)a.B * n_sel : a.M;
+  const int gx = (a.d + BN - 1) / BN, gy = (int)((M + BM - 1) / BM);
+  if ((int)blockIdx.x >= gx * gy) return;
+  const int t = xcd_contiguous(blockIdx.x, gx * gy);
+  const int bx = t % gx, by = t / gx;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int col = lane & 31, half = lane >> 5;
+  const int m0 = by * BM, n0 = bx * BN;
+  const int L = a.L, KT = a.Lp >> 6;
+  unsigned char* Az = smem;
+  unsigned char* Bs = smem + KT * A_SLICE;
+
+  // ---- the We panel: rows 64 kt .. 64 kt + 63 (clamped to the last row: those meet zeros of z), columns n0 .. n0 + 127
+  {
+    const int krow = wave * 4 + (lane >> 4);              // copy u covers k-rows 16 u + 4 wave .. + 3
+    for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int kr = u * 16 + krow;
+        const int cc = min(n0 + (((lane & 15) ^ swz_nc<BN>(kr)) * 8), a.d - 8);
+        dma16(a.We + (long long)min(kt * 64 + kr, L - 1) * a.d + cc, Bs + kt * B_SLICE + u * 4096 + wave * 1024);
+      }
+  }
+  // ---- the windows: four threads per row of the tile, thread j of a row takes its 16-byte chunks (8 samples)
+  // j, j + 4, ...; sums meet by two exchanges inside the group of four, in a fixed order
+  {
+    const int r = threadIdx.x >> 2, j = threadIdx.x & 3;
+    const long long m = m0 + r;
+    bool live = m < M;
+    const long long b = live ? m / n_sel : 0;
+    const int i = live ? (int)(m - b * n_sel) : 0;
+    const int n = live ? a.sel[i] : 0;
+    live = live && (unsigned)n < (unsigned)a.N;            // an index out of range stands for a zero window
+    const float* p = a.x + b * a.sb + (long long)(live ? n : 0) * a.sn;
+    const int nchunk = L >> 3;                             // (L is a multiple of 8)
+    float v[2 * UL][8];
+    float sum = 0.f;
+#pragma unroll
+    for (int c2 = 0; c2 < 2 * UL; ++c2) {
+      const int c = j + 4 * c2;
+      const bool in = live && c < nchunk;
+      if (a.vec) {
+        const float4* q = reinterpret_cast<const float4*>(p + 8 * (in ? c : 0));
+        const float4 lo = q[0], hi = q[1];
+        v[c2][0] = lo.x; v[c2][1] = lo.y; v[c2][2] = lo.z; v[c2][3] = lo.w;
+        v[c2][4] = hi.x; v[c2][5] = hi.y; v[c2][6] = hi.z; v[c2][7] = hi.w;
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[c2][e] = p[8 * (in ? c : 0) + e];
+      }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        v[c2][e] = in ? v[c2][e] : 0.f;
+        sum += v[c2][e];
+      }
+    }
+    if (a.standardise) {
+      sum += __shfl_xor(sum, 1, 64);
+      sum += __shfl_xor(sum, 2, 64);
+      const float mean = sum / (float)L;
+      float ss = 0.f;
+#pragma unroll
+      for (int c2 = 0; c2 < 2 * UL; ++c2) {
+        const bool in = j + 4 * c2 < nchunk;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          v[c2][e] = in ? v[c2][e] - mean : 0.f;
+          ss = fmaf(v[c2][e], v[c2][e], ss);
+        }
+      }
+      ss += __shfl_xor(ss, 1, 64);
+      ss += __shfl_xor(ss, 2, 64);
+      const float var = ss / (float)L;
+      const float inv = var > 0.f ? 1.0f / sqrtf(var) : 1.0f;      // (a constant window is all zeros already)
+#pragma unroll
+      for (int c2 = 0; c2 < 2 * UL; ++c2)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[c2][e] *= inv;
+    }
+#pragma unroll
+    for (int c2 = 0; c2 < 2 * UL; ++c2) {
+      const int c = j + 4 * c2;                            // chunk of the row: samples 8 c .. 8 c + 7, slice c / 8
+      u32x4 z;
+      z.x = pack2(v[c2][0], v[c2][1]); z.y = pack2(v[c2][2], v[c2][3]);
+      z.z = pack2(v[c2][4], v[c2][5]); z.w = pack2(v[c2][6], v[c2][7]);
+      *reinterpret_cast<u32x4*>(Az + (c >> 3) * A_SLICE + r * 128 + (((c & 7) ^ (r & 7)) * 16)) = z;
+      if (bx == 0 && m < M) {
+        if (c == nchunk) z.x = 0x3F80u;                    // a bf16 one at sample position L (see above)
+        *reinterpret_cast<u32x4*>(a.saved + m * a.Lp + 8 * c) = z;
+      }
+    }
+  }
+  wait_vm<0>();
+  __syncthreads();
+
+  // ---- product: wavefront (wm, wn) takes rows 32 wm .. + 31, columns 64 wn .. + 63; formed transposed so that a
+  // lane owns an output row
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
+  const int ra = wm * 32 + col;
+  uint32_t addrB[2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int krow = 8 * half + ((lane & 15) >> 2);
+    const int mn = wn * 64 + j * 32 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+    addrB[j] = lds0 + KT * A_SLICE + krow * (BN * 2) + (((mn >> 3) ^ swz_nc<BN>(krow)) * 16) + ((mn >> 2) & 1) * 8;
+  }
+  floatx16 acc[2] = {zero16(), zero16()};
+  for (int kt = 0; kt < KT; ++kt) {
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      Frag fa, fb[2];
+      lds_read16(fa.q, lds0 + kt * A_SLICE + ra * 128 + (((2 * ks + half) ^ (ra & 7)) * 16));
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const uint32_t base = addrB[j] + kt * B_SLICE + ks * 16 * BN * 2;
+        lds_read8_tr<0>(fb[j].d[0], base);
+        lds_read8_tr<4 * BN * 2>(fb[j].d[1], base);
+      }
+      wait_lds<0>(fa, fb[0], fb[1]);
+      acc[0] = mfma(fb[0], fa, acc[0]);
+      acc[1] = mfma(fb[1], fa, acc[1]);
+    }
+  }
+  // ---- output tile through LDS (bias added), then 16-byte chunks of whole rows
+  __syncthreads();
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int q4 = 0; q4 < 4; ++q4) {
+      const int nl = wn * 64 + j * 32 + 8 * q4 + 4 * half;
+      float bv[4] = {0.f, 0.f, 0.f, 0.f};
+      if (a.be && n0 + nl < a.d) {
+        const u32x2 b4 = *reinterpret_cast<const u32x2*>(a.be + n0 + nl);
+        bv[0] = __uint_as_float(b4.x << 16); bv[1] = __uint_as_float(b4.x & 0xffff0000u);
+        bv[2] = __uint_as_float(b4.y << 16); bv[3] = __uint_as_float(b4.y & 0xffff0000u);
+      }
+      u32x2 o;
+      o.x = pack2(acc[j][4 * q4] + bv[0], acc[j][4 * q4 + 1] + bv[1]);
+      o.y = pack2(acc[j][4 * q4 + 2] + bv[2], acc[j][4 * q4 + 3] + bv[3]);
+      *reinterpret_cast<u32x2*>(smem + ra * CPITCH + nl * 2) = o;
+    }
+  __syncthreads();
+#pragma unroll
+  for (int u = 0; u < BM * 16 / 256; ++u) {
+    const int idx = u * 256 + threadIdx.x;
+    const int row = idx >> 4, c = idx & 15;
+    if (m0 + row < M && n0 + c * 8 < a.d) {
+      const u32x4 v = *reinterpret_cast<const u32x4*>(smem + row * CPITCH + c * 16);
+      *reinterpret_cast<u32x4*>(a.xs + (m0 + row) * (long long)a.d + n0 + c * 8) = v;
+    }
+  }
+}
+
 // Column sums in two steps with a fixed order: part[j][c] = sum of rows [j * per, (j + 1) * per) of column c
 // (a thread per column, rows ascending), then dst[c] = sum_j part[j][c] (j ascending).
 constexpr int kColSlices = 64;
@@ -104,7 +295,15 @@ __global__ void embed_zero_kernel(float* p, long long count) {
     p[i] = 0.f;
 }
 
-int embed_pitch(int L, int dtype) { return dtype == VARDROP_BF16 ? (int)vd_align_up((size_t)L, 64) : L; }
+// bf16 windows short enough for the single-kernel forward (its LDS holds kEmbedMaxKT slices of 64 samples, one
+// position past the window included)
+bool embed_fused(int L, int dtype) { return dtype == VARDROP_BF16 && (L + 1 + 63) / 64 <= kEmbedMaxKT; }
+// row pitch of the saved windows: bf16 rows are padded to a multiple of 64 samples (fused path: of L + 1, the extra
+// position holds a one)
+int embed_pitch(int L, int dtype) {
+  if (dtype != VARDROP_BF16) return L;
+  return (int)vd_align_up((size_t)(embed_fused(L, dtype) ? L + 1 : L), 64);
+}
 
 int check(int B, int n_sel, int L, int d, int dtype) {
   if (B < 0 || n_sel < 0 || L < 2 || d < 1) return VARDROP_EINVAL;
@@ -116,18 +315,8 @@ int check(int B, int n_sel, int L, int d, int dtype) {
   return VARDROP_OK;
 }
 
-// K slices of dWe = z^T dxs (K = B * n_sel rows; tiles of 64 x 128): enough of them to give the chip two
-// workgroups per compute unit, at least 128 rows each, at most 16
-int embed_splitk(int L, int d, long long M, int* kchunk) {
-  const int tiles = vd_ceil_div(L, 64) * vd_ceil_div(d, 128);
-  int s = vd_ceil_div(512, tiles);
-  if (s > 16) s = 16;
-  while (s > 1 && M / s < 128) --s;
-  int chunk = (int)vd_align_up((size_t)vd_ceil_div((int)M, s), 64);
-  if (chunk < 64) chunk = 64;
-  *kchunk = chunk;
-  return M > 0 ? vd_ceil_div((int)M, chunk) : 1;
-}
+// (the K slices of dWe = z^T dxs follow vd_embed_splitk, common.h)
+int embed_splitk(int L, int d, long long M, int* kchunk) { return vd_embed_splitk(L, d, M, kchunk); }
 
 size_t embed_colsum_bytes(int d) { return vd_align_up((size_t)kColSlices * d * sizeof(float), 256); }
 
@@ -142,14 +331,28 @@ extern "C" size_t vardrop_embed_saved_bytes(int B, int n_sel, int L, int dtype) 
 extern "C" size_t vardrop_embed_workspace_bytes(int B, int n_sel, int L, int d, int dtype) {
   if (check(B, n_sel, L, d, dtype) != VARDROP_OK) return 0;
   // partial column sums of dxs (bias gradient), then, for bf16, room for the largest slice count of dWe
-  return embed_colsum_bytes(d) + (dtype == VARDROP_BF16 ? vd_align_up((size_t)16 * L * d * sizeof(float), 256) : 0);
+  return embed_colsum_bytes(d) + (dtype == VARDROP_BF16 ? vd_align_up((size_t)16 * (L + 8) * d * sizeof(float), 256) : 0);
 }
 
-extern "C" int vardrop_embed_fwd(vardrop_ctx* ctx, const float* x, int B, int N, int L, int64_t sb, int64_t sn,
-                                 const int32_t* sel, int n_sel, int standardise,
-                                 const void* We, const void* be, int d, int dtype,
-                                 void* xs, void* saved, void* stream) {
-  if (!ctx) return VARDROP_EINVAL;
+namespace {
+template <int UL>
+int launch_embed_fused(vardrop_ctx* ctx, const EmbedFused& a, long long M_bound, hipStream_t s) {
+  const int lds = UL * (64 * 64 * 2 + 64 * 128 * 2);
+  if (lds > 65536)
+    VD_HIP(ctx, hipFuncSetAttribute((const void*)embed_fwd_fused_kernel<UL>, hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+  const long long grid = (long long)vd_ceil_div(a.d, 128) * ((M_bound + 63) / 64);
+  {
+    VdTimer timer(ctx, VARDROP_K_EMBED_FUSED, s);
+    VD_KERNEL(ctx, embed_fwd_fused_kernel<UL>, dim3((unsigned)grid), dim3(256), lds, s, a);
+  }
+  VD_LAUNCH_CHECK(ctx);
+  return VARDROP_OK;
+}
+
+// n_sel is the count, or with dn.dev its bound
+int embed_fwd(vardrop_ctx* ctx, const float* x, int B, int N, int L, int64_t sb, int64_t sn,
+              const int32_t* sel, int n_sel, int standardise, const void* We, const void* be, int d, int dtype,
+              void* xs, void* saved, hipStream_t s, VdDevCount dn) {
   int rc = check(B, n_sel, L, d, dtype);
   if (rc) return rc;
   if (N < 0 || n_sel > N || sb < 0 || sn < 0) return VARDROP_EINVAL;
@@ -157,8 +360,25 @@ extern "C" int vardrop_embed_fwd(vardrop_ctx* ctx, const float* x, int B, int N,
   if (M == 0) return VARDROP_OK;
   if (!x || !sel || !We || !xs || !saved) return VARDROP_EINVAL;
   if (!vd_aligned(saved, 256)) return VARDROP_EWORKSPACE;
-  hipStream_t s = (hipStream_t)stream;
   const int pitch = embed_pitch(L, dtype);
+  if (embed_fused(L, dtype)) {
+    if (!vd_aligned(We, 16) || !vd_aligned(xs, 16)) return VARDROP_EINVAL;
+    EmbedFused a = {};
+    a.x = x; a.sel = sel; a.We = (const bf16_t*)We; a.be = (const bf16_t*)be;
+    a.xs = (bf16_t*)xs; a.saved = (bf16_t*)saved;
+    a.sb = sb; a.sn = sn; a.N = N; a.L = L; a.Lp = pitch; a.n_sel = n_sel; a.d = d; a.standardise = standardise;
+    a.M = M; a.n_dev = dn.dev; a.status = dn.status; a.B = B;
+    a.vec = vd_aligned(x, 16) && sb % 4 == 0 && sn % 4 == 0;
+    switch (pitch / 64) {
+      case 1: return launch_embed_fused<1>(ctx, a, M, s);
+      case 2: return launch_embed_fused<2>(ctx, a, M, s);
+      case 3: return launch_embed_fused<3>(ctx, a, M, s);
+      case 4: return launch_embed_fused<4>(ctx, a, M, s);
+      case 5: return launch_embed_fused<5>(ctx, a, M, s);
+      default: return launch_embed_fused<6>(ctx, a, M, s);
+    }
+  }
+  if (dn.dev) return VARDROP_EUNSUPPORTED;      // the two-step path takes a host count
   {
     VdTimer timer(ctx, VARDROP_K_EMBED_ROWS, s);
     const dim3 grid((unsigned)((M + 3) / 4));
@@ -182,14 +402,11 @@ extern "C" int vardrop_embed_fwd(vardrop_ctx* ctx, const float* x, int B, int N,
                      (float*)xs, d, (const float*)be, (int)M, d, L, s);
 }
 
-extern "C" int vardrop_embed_bwd(vardrop_ctx* ctx, const void* dxs, int B, int n_sel, int L, int d, int dtype,
-                                 const void* saved, float* dWe, float* dbe,
-                                 void* ws, size_t ws_bytes, void* stream) {
-  if (!ctx) return VARDROP_EINVAL;
+int embed_bwd(vardrop_ctx* ctx, const void* dxs, int B, int n_sel, int L, int d, int dtype,
+              const void* saved, float* dWe, float* dbe, void* ws, size_t ws_bytes, hipStream_t s, VdDevCount dn) {
   int rc = check(B, n_sel, L, d, dtype);
   if (rc) return rc;
   if (!dWe) return VARDROP_EINVAL;
-  hipStream_t s = (hipStream_t)stream;
   const long long M = (long long)B * n_sel;
   if (M == 0) {
     hipLaunchKernelGGL(embed_zero_kernel, dim3(64), dim3(256), 0, s, dWe, (long long)L * d);
@@ -203,6 +420,28 @@ extern "C" int vardrop_embed_bwd(vardrop_ctx* ctx, const void* dxs, int B, int n
   float* colpart = (float*)ws;
   float* slices = (float*)((char*)ws + embed_colsum_bytes(d));
   const int pitch = embed_pitch(L, dtype);
+  if (embed_fused(L, dtype)) {
+    // One product: [dWe ; dbe] = [z | 1]^T dxs, the operand rows L + 1 .. up to the next multiple of 8 are zeros.
+    // Its K slices always go through the partial sums (the result is not one contiguous matrix of the caller's).
+    GemmBf16 g = {};
+    g.set(0, saved, dxs, nullptr, nullptr);
+    g.lda = pitch; g.ldb = d; g.ldc = d;
+    g.M = (int)vd_align_up((size_t)L + 1, 8); g.N = d; g.K = (int)M; g.nseg = 1;
+    int kchunk = 0;
+    g.splitk = embed_splitk(g.M, d, M, &kchunk);
+    g.kchunk = kchunk;
+    g.part = slices;
+    g.force_part = 1;
+    if (dn.dev) {
+      g.count_k(dn.dev, n_sel, B);
+      g.n_role = 2;                                  // the slices follow the embedding's rule
+      g.splitk = 16;                                 // (the grid is sized for the largest number of slices)
+    }
+    if ((rc = vd_gemm_bf16_wgrad_split(ctx, VARDROP_K_GEMM_DWE, g, s))) return rc;
+    return vd_gemm_bf16_sum_rows(ctx, slices, dWe, (long long)L * d, dbe, d, (long long)g.M * d, g.splitk, s,
+                                 dn.dev ? &g : nullptr);
+  }
+  if (dn.dev) return VARDROP_EUNSUPPORTED;
   if (dtype == VARDROP_BF16) {
     GemmBf16 g = {};
     g.set(0, saved, dxs, dWe, nullptr);
@@ -228,4 +467,39 @@ extern "C" int vardrop_embed_bwd(vardrop_ctx* ctx, const void* dxs, int B, int n
     return rc;
   if (dbe) return embed_colsum(ctx, (const float*)dxs, colpart, dbe, M, d, s);
   return VARDROP_OK;
+}
+}  // namespace
+
+extern "C" int vardrop_embed_fwd(vardrop_ctx* ctx, const float* x, int B, int N, int L, int64_t sb, int64_t sn,
+                                 const int32_t* sel, int n_sel, int standardise,
+                                 const void* We, const void* be, int d, int dtype,
+                                 void* xs, void* saved, void* stream) {
+  if (!ctx) return VARDROP_EINVAL;
+  return embed_fwd(ctx, x, B, N, L, sb, sn, sel, n_sel, standardise, We, be, d, dtype, xs, saved, (hipStream_t)stream,
+                   VdDevCount{nullptr, nullptr});
+}
+
+extern "C" int vardrop_embed_fwd_dev(vardrop_ctx* ctx, const float* x, int B, int N, int L, int64_t sb, int64_t sn,
+                                     const int32_t* sel, const int32_t* n_dev, int n_max, int32_t* status, int standardise,
+                                     const void* We, const void* be, int d, int dtype,
+                                     void* xs, void* saved, void* stream) {
+  if (!ctx || !n_dev || n_max < 1) return VARDROP_EINVAL;
+  return embed_fwd(ctx, x, B, N, L, sb, sn, sel, n_max, standardise, We, be, d, dtype, xs, saved, (hipStream_t)stream,
+                   VdDevCount{n_dev, status});
+}
+
+extern "C" int vardrop_embed_bwd_dev(vardrop_ctx* ctx, const void* dxs, int B, const int32_t* n_dev, int n_max, int L, int d,
+                                     int dtype, const void* saved, float* dWe, float* dbe,
+                                     void* ws, size_t ws_bytes, void* stream) {
+  if (!ctx || !n_dev || n_max < 1 || B < 1) return VARDROP_EINVAL;
+  return embed_bwd(ctx, dxs, B, n_max, L, d, dtype, saved, dWe, dbe, ws, ws_bytes, (hipStream_t)stream,
+                   VdDevCount{n_dev, nullptr});
+}
+
+extern "C" int vardrop_embed_bwd(vardrop_ctx* ctx, const void* dxs, int B, int n_sel, int L, int d, int dtype,
+                                 const void* saved, float* dWe, float* dbe,
+                                 void* ws, size_t ws_bytes, void* stream) {
+  if (!ctx) return VARDROP_EINVAL;
+  return embed_bwd(ctx, dxs, B, n_sel, L, d, dtype, saved, dWe, dbe, ws, ws_bytes, (hipStream_t)stream,
+                   VdDevCount{nullptr, nullptr});
 }

@@ -16,7 +16,8 @@ struct GemmBf16 {
   int M, N, K;
   int nseg;           // > 1: segments accumulate into C0
   int splitk;         // > 1: every matrix z is cut into splitk K slices, slice s writes fp32 to part + (z * splitk + s) * M * N
-  float* part;        //      (the partial products; with splitk == 1 the result goes to C[z] itself)
+  float* part;        //      (the partial products; with splitk == 1 the result goes to C[z] itself,
+  int force_part;     //       unless force_part: then a single slice is a partial product as well)
   int kchunk;         // K elements per slice (multiple of 64)
   int a_kpad;         // != 0: the rows of a k-contiguous A hold zeros from K up to the next multiple of 64, so K
                       // itself need not be one (B must then be n-contiguous: its last k-row is re-read, times zero)
@@ -31,8 +32,9 @@ struct GemmBf16 {
   float* rs_aux_out;
   float rs_aux_mul;
   // Device-side token count (n_dev != nullptr): the kernels read n = *n_dev (at most n_max, see vd_count) and the
-  // token dimension of the product becomes n_mul * n: M when n_role == 0 (with rs_n = n), K when n_role == 1, where
-  // the number and length of the K slices then follow from vd_attn_bf16_splitk on the device as well.
+  // token dimension of the product becomes n_mul * n: M when n_role == 0 (with rs_n = n), K when n_role >= 1, where
+  // the number and length of the K slices then follow on the device as well: from vd_attn_bf16_splitk (n_role 1)
+  // or vd_embed_splitk (n_role 2).
   const int32_t* n_dev;
   int32_t* status;
   int n_max, n_mul, n_role;
@@ -67,4 +69,8 @@ int vd_gemm_bf16_sum_slices(vardrop_ctx* ctx, const float* part, float* const ou
 // C = A^T * B in fp32 for one matrix, both operands mn-contiguous, K cut into g.splitk slices of g.kchunk: the
 // partial products go to g.part ([splitk][M][N] fp32) when splitk > 1, the result itself (C0, ldc) when it is 1.
 int vd_gemm_bf16_wgrad_split(vardrop_ctx* ctx, int kid, const GemmBf16& g, hipStream_t s);
+// Sums `splitk` partial matrices ([splitk][stride] fp32, slices in ascending order) into two destinations: the first
+// `count0` elements of a matrix go to out0, the next `count1` to out1 (nullable); `like`: as for vd_gemm_bf16_sum_slices.
+int vd_gemm_bf16_sum_rows(vardrop_ctx* ctx, const float* part, float* out0, long long count0, float* out1, long long count1,
+                          long long stride, int splitk, hipStream_t s, const GemmBf16* like);
 #endif  // VARDROP_GEMM_BF16_H

@@ -15,6 +15,39 @@ struct SplitkReduce {
   const int32_t* n_dev;
   int n_max, n_mul, dn_d;
 };
+// One matrix of `stride` elements per slice, always `splitk` partial products (no direct result): its first count0
+// elements go to out0, the next count1 to out1 (nullable).  With a device-side count the slices follow the
+// embedding's rule (M = dn_m rows, N = dn_n columns).
+struct SplitkReduceRows {
+  const float* part;
+  float* out0;
+  float* out1;
+  long long count0, count1, stride;
+  int splitk;
+  const int32_t* n_dev;
+  int n_max, n_mul, dn_m, dn_n;
+};
+__global__ __launch_bounds__(256) void splitk_reduce_rows_kernel(SplitkReduceRows a) {
+  int splitk = a.splitk;
+  if (a.n_dev) {
+    int n;
+    if (!vd_count(a.n_dev, a.n_max, n)) return;
+    splitk = n == 0 ? 0 : vd_embed_splitk(a.dn_m, a.dn_n, (long long)a.n_mul * n, nullptr);   // no tokens: zero gradients
+  }
+  const long long total = a.count0 + (a.out1 ? a.count1 : 0);
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
+    const float* p = a.part + i;
+    float s = 0.f;
+    int k = 0;
+    for (; k + 4 <= splitk; k += 4) {            // four loads in flight, added in slice order
+      const float p0 = p[(long long)k * a.stride], p1 = p[(long long)(k + 1) * a.stride];
+      const float p2 = p[(long long)(k + 2) * a.stride], p3 = p[(long long)(k + 3) * a.stride];
+      s = ((s + p0) + p1) + p2 + p3;
+    }
+    for (; k < splitk; ++k) s += p[(long long)k * a.stride];
+    if (i < a.count0) a.out0[i] = s; else a.out1[i - a.count0] = s;
+  }
+}
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(SplitkReduce a) {
   if (a.n_dev) {
     int n;
@@ -293,7 +326,7 @@ __device__ __forceinline__ void gemm_async_tile(const GemmBf16& g, const GemmDim
   unsigned char* Cb;
   long long ldc_bytes;
   if constexpr (SPLIT) {
-    if (dm.splitk > 1) {      // partial product of slice bz % splitk of matrix bz / splitk
+    if (dm.splitk > 1 || g.force_part) {      // partial product of slice bz % splitk of matrix bz / splitk
       Cb = reinterpret_cast<unsigned char*>(g.part) + (long long)bz * dm.M * g.N * 4;
       ldc_bytes = (long long)g.N * 4;
     } else {                 // a single slice is the result itself
@@ -367,7 +400,8 @@ __device__ __forceinline__ bool gemm_resolve(const GemmBf16& g, GemmDims& dm) {
   } else {
     dm.K = g.n_mul * n;
     int kchunk = 64;
-    dm.splitk = vd_attn_bf16_splitk(g.M, (long long)dm.K, &kchunk);
+    dm.splitk = g.n_role == 2 ? vd_embed_splitk(g.M, g.N, (long long)dm.K, &kchunk)
+                              : vd_attn_bf16_splitk(g.M, (long long)dm.K, &kchunk);
     dm.kchunk = kchunk;
   }
   return dm.M > 0 && dm.K > 0;
@@ -505,6 +539,31 @@ int vd_gemm_bf16_wgrad_split(vardrop_ctx* ctx, int kid, const GemmBf16& g, hipSt
       (long long)g.K * g.lda >= (1ll << 31) || (long long)g.K * g.ldb >= (1ll << 31))
     return VARDROP_EUNSUPPORTED;
   return launch_gemm_async_cfg<false, false, true, 64, 2>(ctx, kid, g, 1, s);
+}
+
+int vd_gemm_bf16_sum_rows(vardrop_ctx* ctx, const float* part, float* out0, long long count0, float* out1, long long count1,
+                          long long stride, int splitk, hipStream_t s, const GemmBf16* like) {
+  SplitkReduceRows r = {};
+  if (like && like->n_dev) {
+    r.n_dev = like->n_dev;
+    r.n_max = like->n_max;
+    r.n_mul = like->n_mul;
+    r.dn_m = like->M;
+    r.dn_n = like->N;
+  }
+  r.part = part;
+  r.out0 = out0;
+  r.out1 = out1;
+  r.count0 = count0;
+  r.count1 = count1;
+  r.stride = stride;
+  r.splitk = splitk;
+  {
+    VdTimer timer(ctx, VARDROP_K_REDUCE_DW, s);
+    VD_KERNEL(ctx, splitk_reduce_rows_kernel, dim3((unsigned)((count0 + count1 + 255) / 256)), dim3(256), 0, s, r);
+  }
+  VD_LAUNCH_CHECK(ctx);
+  return VARDROP_OK;
 }
 
 int vd_gemm_bf16_sum_slices(vardrop_ctx* ctx, const float* part, float* const out[4], long long count, int splitk,

@@ -283,3 +283,53 @@ def test_sampling_draws_anew_at_every_replay_of_a_recorded_step(vd, ctx):
                     "dxs": rel_err(bufs.packed(bufs.dxs, w.B, n), want["dxs"])}
             assert all(e <= TOL[w.dtype] for e in errs.values()), errs
     assert len(seen) == 4
+
+
+def test_embedding_of_the_kept_windows_with_the_count_on_the_device(vd, ctx):
+    """Raw windows -> embedding of the kept variates -> attention forward / backward -> embedding gradients, every
+    call reading the count on the device; tokens, outputs and all gradients against the oracle for several counts
+    under one bound."""
+    from oracle import embedding as o_emb
+    rng = np.random.default_rng(11)
+    B, N, L, d, H, n_max = 3, 150, 96, 128, 2, 128
+    td = torch.bfloat16
+    x = (rng.standard_normal((B, N, L)) * rng.uniform(0.1, 5.0, size=(1, N, 1)) + rng.uniform(-3, 3, size=(1, N, 1))).astype(np.float32)
+    We = wl.quantise(rng.standard_normal((L, d)) / np.sqrt(L), "bf16")
+    be = wl.quantise(0.1 * rng.standard_normal(d), "bf16")
+    W = [wl.quantise(rng.standard_normal((d, d)) / np.sqrt(d), "bf16") for _ in range(4)]
+    x_t, We_t, be_t, W_t = to_dev(x), to_dev(We, td), to_dev(be, td), [to_dev(m, td) for m in W]
+    lib = vd.load_library()
+    bufs = Buffers(vd, B, N, d, H, td, n_max)
+    esaved = torch.empty(lib.vardrop_embed_saved_bytes(B, n_max, L, vd.BF16), dtype=torch.uint8, device="cuda")
+    ews = torch.empty(lib.vardrop_embed_workspace_bytes(B, n_max, L, d, vd.BF16), dtype=torch.uint8, device="cuda")
+    dWe = torch.empty((L, d), dtype=torch.float32, device="cuda")
+    dbe = torch.empty((d,), dtype=torch.float32, device="cuda")
+    n_dev = torch.zeros(1, dtype=torch.int32, device="cuda")
+    for n in (128, 1, 77):
+        sel_np = np.sort(rng.choice(N, size=n, replace=False))
+        sel = torch.zeros(N, dtype=torch.int32, device="cuda")
+        sel[:n] = to_dev(sel_np.astype(np.int32))
+        dy = wl.quantise(rng.standard_normal((B, n, d)), "bf16")
+        n_dev.fill_(n)
+        vd.vardrop_embed_fwd_dev(ctx, x_t, sel, n_dev, n_max, We_t, be_t, bufs.xs, esaved, status=bufs.status)
+        vd.vardrop_attn_fwd_dev(ctx, bufs.xs, n_dev, n_max, *W_t, H, bufs.y, bufs.saved, status=bufs.status)
+        vd.vardrop_attn_bwd_dev(ctx, to_dev(dy, td), bufs.xs, n_dev, n_max, *W_t, H, bufs.saved, bufs.ws,
+                                (bufs.dxs, *bufs.dW), status=bufs.status)
+        vd.vardrop_embed_bwd_dev(ctx, bufs.dxs, n_dev, n_max, L, esaved, ews, (dWe, dbe))
+        torch.cuda.synchronize()
+        assert int(bufs.status[0]) == 0
+        want_xs = o_emb.embed_forward(x, sel_np, We, be, True)
+        xs = bufs.packed(bufs.xs, B, n)
+        assert rel_err(xs, want_xs) <= TOL["bf16"]
+        xs_r = xs.float().cpu().numpy().astype(np.float64)                # the attention sees the rounded tokens
+        want = oracle_attention(xs_r, W, H, dy)
+        got = dict(y=bufs.packed(bufs.y, B, n), dxs=bufs.packed(bufs.dxs, B, n), dWq=bufs.dW[0], dWo=bufs.dW[3])
+        errs = {k: rel_err(v, want[k]) for k, v in got.items()}
+        assert all(e <= TOL["bf16"] for e in errs.values()), (n, errs)
+        dxs_r = bufs.packed(bufs.dxs, B, n).float().cpu().numpy().astype(np.float64)
+        want_dWe, want_dbe = o_emb.embed_backward(x, sel_np, dxs_r, True)
+        assert rel_err(dWe, want_dWe) <= TOL["bf16"] and rel_err(dbe, want_dbe) <= TOL["bf16"], n
+    n_dev.fill_(129)
+    vd.vardrop_embed_fwd_dev(ctx, x_t, sel, n_dev, n_max, We_t, be_t, bufs.xs, esaved, status=bufs.status)
+    torch.cuda.synchronize()
+    assert int(bufs.status[0]) == 1
