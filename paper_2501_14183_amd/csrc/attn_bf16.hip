@@ -58,10 +58,7 @@ struct SdpaArgs {
 // transposing read; LDS reads and their wait counters are written by hand (the compiler would wait for
 // every outstanding copy before any LDS read).
 constexpr int kRingTile = 64 * kDh * 2;
-// chunk position p of token row r holds source chunk p ^ ring_swz(r): a bijection of r % 8, so that the eight rows
-// of a row-fragment read spread over all banks, whose bits 1-2 are r % 4, so that the four rows x two chunks that
-// sixteen lanes of a transposing read touch do too
-__device__ inline int ring_swz(int row) { return ((row & 3) << 1) | ((row >> 2) & 1); }
+// (chunk position p of token row r holds source chunk p ^ tile_swz(r))
 constexpr int kRingStage = 2 * kRingTile + 512;
 constexpr int kRingStages = 3;
 constexpr int kRingLds = kRingStages * kRingStage;
@@ -76,7 +73,7 @@ __device__ inline void ring_issue(const bf16_t* p0, const bf16_t* p1, long long 
   for (int u = 0; u < 8 / NW; ++u) {
     const int rb = u * NW + wave;
     const int row = rb * 8 + (lane >> 3);
-    const long long off = (long long)min(j0 + row, n - 1) * ld + (((lane & 7) ^ ring_swz(row)) * 8);
+    const long long off = (long long)min(j0 + row, n - 1) * ld + (((lane & 7) ^ tile_swz(row)) * 8);
     dma16(p0 + off, stage + rb * 1024);
     dma16(p1 + off, stage + kRingTile + rb * 1024);
   }
@@ -84,9 +81,9 @@ __device__ inline void ring_issue(const bf16_t* p0, const bf16_t* p1, long long 
 // Per-lane LDS addresses (relative to a stage's first tile) of the two fragment kinds:
 //   row[s]: token row `col` of a 32-row sub-tile, k = 16 s + 8 half .. +7 (add 4096 per sub-tile);
 //   tr[dt]: transposed fragment, head dimensions 32 dt .. +31 as rows, four token rows 4 half + {0..3}
-//           (add 128 * (first token row of the 8-row group) and 1024 for the second group of four).
+//           (add 128 * 16 per further 16-row group); tr8[dt]: the same for token rows 8 + 4 half + {0..3}.
 struct RingAddr {
-  uint32_t lds0, row[4], tr[2];
+  uint32_t lds0, row[4], tr[2], tr8[2];
 };
 __device__ inline RingAddr ring_addr(const unsigned char* smem, int lane) {
   RingAddr r;
@@ -94,12 +91,13 @@ __device__ inline RingAddr ring_addr(const unsigned char* smem, int lane) {
   const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const unsigned char*)smem;
   r.lds0 = lds0;
 #pragma unroll
-  for (int s = 0; s < 4; ++s) r.row[s] = lds0 + col * 128 + (((2 * s + half) ^ ring_swz(col)) * 16);
+  for (int s = 0; s < 4; ++s) r.row[s] = lds0 + col * 128 + (((2 * s + half) ^ tile_swz(col)) * 16);
   const int kr = 4 * half + ((lane & 15) >> 2);
 #pragma unroll
   for (int dt = 0; dt < 2; ++dt) {
     const int mn = dt * 32 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-    r.tr[dt] = lds0 + kr * 128 + (((mn >> 3) ^ ring_swz(kr)) * 16) + ((mn >> 2) & 1) * 8;
+    r.tr[dt] = lds0 + kr * 128 + (((mn >> 3) ^ tile_swz(kr)) * 16) + ((mn >> 2) & 1) * 8;
+    r.tr8[dt] = lds0 + (kr + 8) * 128 + (((mn >> 3) ^ tile_swz(kr + 8)) * 16) + ((mn >> 2) & 1) * 8;
   }
   return r;
 }
@@ -129,13 +127,13 @@ __device__ inline bool ring_block(SdpaArgs& a, int rows, int parts, int& xb, int
 // four transposed fragments of the 32 token rows KT of tile TILE: F[2 * s2 + dt] = rows 16 s2 .., dimensions 32 dt ..
 #define VD_TR4(F, TILE, KT, SO)                                                                              \
   lds_read8_tr<(TILE) * kRingTile + ((KT) * 32) * 128>(F[0].d[0], ra.tr[0] + (SO));                          \
-  lds_read8_tr<(TILE) * kRingTile + ((KT) * 32 + 8) * 128>(F[0].d[1], ra.tr[0] + (SO));                      \
+  lds_read8_tr<(TILE) * kRingTile + ((KT) * 32) * 128>(F[0].d[1], ra.tr8[0] + (SO));                      \
   lds_read8_tr<(TILE) * kRingTile + ((KT) * 32) * 128>(F[1].d[0], ra.tr[1] + (SO));                          \
-  lds_read8_tr<(TILE) * kRingTile + ((KT) * 32 + 8) * 128>(F[1].d[1], ra.tr[1] + (SO));                      \
+  lds_read8_tr<(TILE) * kRingTile + ((KT) * 32) * 128>(F[1].d[1], ra.tr8[1] + (SO));                      \
   lds_read8_tr<(TILE) * kRingTile + ((KT) * 32 + 16) * 128>(F[2].d[0], ra.tr[0] + (SO));                     \
-  lds_read8_tr<(TILE) * kRingTile + ((KT) * 32 + 24) * 128>(F[2].d[1], ra.tr[0] + (SO));                     \
+  lds_read8_tr<(TILE) * kRingTile + ((KT) * 32 + 16) * 128>(F[2].d[1], ra.tr8[0] + (SO));                     \
   lds_read8_tr<(TILE) * kRingTile + ((KT) * 32 + 16) * 128>(F[3].d[0], ra.tr[1] + (SO));                     \
-  lds_read8_tr<(TILE) * kRingTile + ((KT) * 32 + 24) * 128>(F[3].d[1], ra.tr[1] + (SO));
+  lds_read8_tr<(TILE) * kRingTile + ((KT) * 32 + 16) * 128>(F[3].d[1], ra.tr8[1] + (SO));
 
 // ---- forward: a wavefront owns 32 QG queries (lane = query of each group), NW wavefronts share the K / V stages.
 // S^T = K q^T, online softmax on per-lane scalars, O^T = V^T P^T with the probability registers as the
@@ -558,7 +556,7 @@ typedef short s16x4 __attribute__((ext_vector_type(4)));
 // 16-byte chunk (k = 8*chunk ..) of a token row of a swizzled tile
 __device__ inline Frag small_row_frag(const unsigned char* tile, int row, int chunk) {
   Frag f;
-  f.q = *reinterpret_cast<const u32x4*>(tile + row * 128 + ((chunk ^ (row & 7)) * 16));
+  f.q = *reinterpret_cast<const u32x4*>(tile + row * 128 + ((chunk ^ tile_swz(row)) * 16));
   return f;
 }
 // transposing read of a swizzled tile: this lane receives, for column mn0 + lane % 16 of the 16-lane
@@ -569,7 +567,7 @@ __device__ inline Frag small_tr_frag(const unsigned char* tile, int krow0, int m
 #pragma unroll
   for (int rd = 0; rd < 2; ++rd) {
     const int krow = krow0 + 8 * rd + ((lane & 15) >> 2);
-    const unsigned char* p = tile + krow * 128 + (((mn >> 3) ^ (krow & 7)) * 16) + ((mn >> 2) & 1) * 8;
+    const unsigned char* p = tile + krow * 128 + (((mn >> 3) ^ tile_swz(krow)) * 16) + ((mn >> 2) & 1) * 8;
     const s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)p);
     f.d[rd] = __builtin_bit_cast(u32x2, v);
   }
@@ -613,18 +611,18 @@ __global__ __launch_bounds__(512) void sdpa_bwd_small_bf16(SdpaArgs a) {
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
       const int row = (u * 8 + wave) * 8 + (lane >> 3);
-      srcA[u] = dy_b + (long long)min(row, n - 1) * ld + (((lane & 7) ^ (row & 7)) * 8);
+      srcA[u] = dy_b + (long long)min(row, n - 1) * ld + (((lane & 7) ^ tile_swz(row)) * 8);
     }
     const int rowB = wave * 8 + (lane >> 3);
-    const bf16_t* srcB = a.wo + (long long)(h * kDh + rowB) * ld + (((lane & 7) ^ (rowB & 7)) * 8);
+    const bf16_t* srcB = a.wo + (long long)(h * kDh + rowB) * ld + (((lane & 7) ^ tile_swz(rowB)) * 8);
     const uint32_t ring0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)ring;
     uint32_t addrA[4], addrB[4];
     {
       const int ra = blk * 32 + col, rb = part * 32 + col;
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks) {
-        addrA[ks] = ring0 + ra * 128 + (((2 * ks + half) ^ (ra & 7)) * 16);
-        addrB[ks] = ring0 + A_BYTES + rb * 128 + (((2 * ks + half) ^ (rb & 7)) * 16);
+        addrA[ks] = ring0 + ra * 128 + (((2 * ks + half) ^ tile_swz(ra)) * 16);
+        addrB[ks] = ring0 + A_BYTES + rb * 128 + (((2 * ks + half) ^ tile_swz(rb)) * 16);
       }
     }
     floatx16 acc = zero16();
@@ -648,7 +646,7 @@ __global__ __launch_bounds__(512) void sdpa_bwd_small_bf16(SdpaArgs a) {
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
           const int row = (u * 8 + wave) * 8 + (lane >> 3);
-          const int chunk = (lane & 7) ^ (row & 7);
+          const int chunk = (lane & 7) ^ tile_swz(row);
           dma16(src[t] + (long long)min(row, n - 1) * ld + chunk * 8, smem + t * kSmallTile + (u * 8 + wave) * 1024);
         }
       }
@@ -702,7 +700,7 @@ __global__ __launch_bounds__(512) void sdpa_bwd_small_bf16(SdpaArgs a) {
       u32x2 o;
       o.x = pack2(acc[4 * q4], acc[4 * q4 + 1]);
       o.y = pack2(acc[4 * q4 + 2], acc[4 * q4 + 3]);
-      *reinterpret_cast<u32x2*>(dOs + row * 128 + (((dim >> 3) ^ (row & 7)) * 16) + ((dim >> 2) & 1) * 8) = o;
+      *reinterpret_cast<u32x2*>(dOs + row * 128 + (((dim >> 3) ^ tile_swz(row)) * 16) + ((dim >> 2) & 1) * 8) = o;
     }
   }
   __syncthreads();                      // the ring is free: the statistics and later dS^T may use its place
@@ -835,7 +833,7 @@ __global__ __launch_bounds__(512) void sdpa_bwd_small_bf16(SdpaArgs a) {
 #pragma unroll
         for (int rd = 0; rd < 2; ++rd) {
           const int krow = 16 * ks + 8 * half + 4 * rd + ((lane & 15) >> 2);
-          const unsigned char* p = Ks + krow * 128 + (((mn >> 3) ^ (krow & 7)) * 16) + ((mn >> 2) & 1) * 8;
+          const unsigned char* p = Ks + krow * 128 + (((mn >> 3) ^ tile_swz(krow)) * 16) + ((mn >> 2) & 1) * 8;
           const s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)p);
           kf.d[rd] = __builtin_bit_cast(u32x2, v);
         }
@@ -931,7 +929,7 @@ __global__ __launch_bounds__(512) void attn_fwd_small_bf16(FusedFwdArgs a) {
   {
     const int ra = wr * 32 + col;
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) addrA[ks] = lds0 + ra * 128 + (((2 * ks + half) ^ (ra & 7)) * 16);
+    for (int ks = 0; ks < 4; ++ks) addrA[ks] = lds0 + ra * 128 + (((2 * ks + half) ^ tile_swz(ra)) * 16);
   }
 #pragma unroll
   for (int j = 0; j < 3; ++j) {
@@ -961,7 +959,7 @@ __global__ __launch_bounds__(512) void attn_fwd_small_bf16(FusedFwdArgs a) {
 #pragma unroll
   for (int u = 0; u < 2; ++u) {
     const int row = (u * 8 + wave) * 8 + (lane >> 3);
-    srcA[u] = xs_b + (long long)src_row[u] * ld + (((lane & 7) ^ (row & 7)) * 8);
+    srcA[u] = xs_b + (long long)src_row[u] * ld + (((lane & 7) ^ tile_swz(row)) * 8);
   }
   VD_ISSUE_X(0)
 #pragma unroll
@@ -1044,7 +1042,7 @@ __global__ __launch_bounds__(512) void attn_fwd_small_bf16(FusedFwdArgs a) {
       u32x2 o;
       o.x = pack2(acc[j][4 * q4] + bv[0], acc[j][4 * q4 + 1] + bv[1]);
       o.y = pack2(acc[j][4 * q4 + 2] + bv[2], acc[j][4 * q4 + 3] + bv[3]);
-      *reinterpret_cast<u32x2*>(smem + z * kSmallTile + row * 128 + (((dim >> 3) ^ (row & 7)) * 16) + ((dim >> 2) & 1) * 8) = o;
+      *reinterpret_cast<u32x2*>(smem + z * kSmallTile + row * 128 + (((dim >> 3) ^ tile_swz(row)) * 16) + ((dim >> 2) & 1) * 8) = o;
     }
   }
   __syncthreads();
@@ -1064,7 +1062,7 @@ __global__ __launch_bounds__(512) void attn_fwd_small_bf16(FusedFwdArgs a) {
     const int z = idx / (kSmallN * 8), row = (idx / 8) % kSmallN, c = idx & 7;
     if (row < n) {
       bf16_t* dst = z == 0 ? a.q : (z == 1 ? a.k : a.v);
-      const u32x4 v = *reinterpret_cast<const u32x4*>(smem + z * kSmallTile + row * 128 + ((c ^ (row & 7)) * 16));
+      const u32x4 v = *reinterpret_cast<const u32x4*>(smem + z * kSmallTile + row * 128 + ((c ^ tile_swz(row)) * 16));
       *reinterpret_cast<u32x4*>(dst + base + (long long)row * ld + c * 8) = v;
     }
   }
@@ -1216,7 +1214,7 @@ int launch_sdpa_bwd(vardrop_ctx* ctx, const SdpaArgs& a, hipStream_t s) {
 
 // largest slice count the rule above gives for any token count
 static int splitk_bound(int d) {
-  const int s = vd_ceil_div(512, vd_ceil_div(d, 128) * vd_ceil_div(d, 128) * 4);
+  const int s = vd_ceil_div(512, vd_ceil_div(d, 64) * vd_ceil_div(d, 128) * 4);
   return s > 8 ? 8 : s;
 }
 size_t vd_attn_bf16_partial_offset(int B, int n, int d, int H) {

@@ -98,10 +98,24 @@ __device__ inline void wait_lds(Frag& a) {
 template <int N>
 __device__ inline void wait_lds_count() { asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N) : "memory"); }
 
+// Bank swizzles.  The LDS has 64 banks of 4 bytes: a 16-byte read is served 16 lanes per clock, an 8-byte read 32
+// lanes per clock, and either runs at full rate when those lanes touch 256 distinct bytes modulo 256.
+//   k-contiguous tile [row][BK]: 16 consecutive lanes read one 16-byte chunk of 16 consecutive rows.  With 128-byte
+//   rows (BK = 64) rows r and r + 2 share their 128-byte half of the banks, so the chunk index is XORed with
+//   (r >> 1) % 8; with 64-byte rows (BK = 32) four rows share 256 bytes and the XOR is (r >> 2) % 4.
+//   mn-contiguous tile [k][W]: 32 consecutive lanes of a transposing read take 64 consecutive bytes of each of the
+//   k-rows kr .. kr + 3 (the other half of the wavefront: kr + 8 ..).  The XOR depends on kr % 4 (and on bit 3 of kr
+//   where that costs nothing), so that the +4 and +16 row offsets of a fragment's further reads keep the pattern.
 template <int BK>
-__device__ inline int swz_kc(int row) { return BK == 32 ? (row >> 1) & 3 : row & 7; }
+__device__ inline int swz_kc(int row) { return BK == 32 ? (row >> 2) & 3 : (row >> 1) & 7; }
 template <int W>
-__device__ inline int swz_nc(int krow) { return W == 128 ? (((krow & 3) << 1) ^ (((krow >> 3) & 1) << 3)) : ((krow & 3) << 1); }
+__device__ inline int swz_nc(int krow) { return W == 128 ? ((krow & 3) << 2) : ((krow & 3) << 1); }
+// Tile [row][64] (128-byte rows) that is read both ways, by rows (16-byte chunks of 16 consecutive rows) and by the
+// transposing read (64 consecutive bytes of four consecutive rows): chunk position p of row r holds chunk
+// p ^ tile_swz(r).  Bit 2 of the XOR is bit 1 of r (rows r and r + 2 share a 128-byte half of the banks; a
+// transposing read then finds them in different 64-byte quarters), bits 1 and 0 are bits 2 and 3 of r, so the eight
+// rows of equal parity among 16 consecutive ones all differ.  Invariant under r += 16.
+__device__ inline int tile_swz(int row) { return ((row & 2) << 1) | ((row >> 1) & 2) | ((row >> 3) & 1); }
 // zeroes the elements k >= kvalid of a fragment holding k = 0..7
 __device__ inline void mask_frag(Frag& f, int kvalid) {
 #pragma unroll

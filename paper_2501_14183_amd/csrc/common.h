@@ -89,13 +89,13 @@ __host__ __device__ static inline size_t vd_align_up(size_t v, size_t a) { retur
 static inline bool vd_aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
 __host__ __device__ static inline int vd_ceil_div(int a, int b) { return (a + b - 1) / b; }
 
-// Number of K slices of the weight-gradient GEMMs (K = B*n rows, 128 x 128 tiles).  They share a
-// launch with the input gradient, two workgroups per compute unit: enough slices that the two
-// together fill those 512 places when the input gradient leaves room, else enough for the weight
-// gradients alone to do so; slices hold at least 256 rows and are a multiple of the 64-row stage.
+// Number of K slices of the weight-gradient GEMMs (K = B*n rows; counted in 64 x 128 tiles, the shape they have
+// whenever the slice count matters).  They share a launch with the input gradient, two workgroups per compute
+// unit: enough slices that the two together fill those 512 places when the input gradient leaves room, else
+// enough for the weight gradients alone to do so; slices hold at least 256 rows and are a multiple of the 64-row stage.
 // (Host and device: with a device-side token count the kernels evaluate it themselves.)
 __host__ __device__ static inline int vd_attn_bf16_splitk(int d, long long M, int* kchunk) {
-  const int tiles = vd_ceil_div(d, 128) * vd_ceil_div(d, 128) * 4;
+  const int tiles = vd_ceil_div(d, 64) * vd_ceil_div(d, 128) * 4;
   const long long dxs_wgs = (long long)vd_ceil_div((int)M, 64) * vd_ceil_div(d, 128);
   int s = vd_ceil_div(512, tiles);
   if (dxs_wgs < 512) {

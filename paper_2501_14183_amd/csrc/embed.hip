@@ -190,7 +190,7 @@ __global__ __launch_bounds__(256, 2) void embed_fwd_fused_kernel(EmbedFused a) {
       u32x4 z;
       z.x = pack2(v[c2][0], v[c2][1]); z.y = pack2(v[c2][2], v[c2][3]);
       z.z = pack2(v[c2][4], v[c2][5]); z.w = pack2(v[c2][6], v[c2][7]);
-      *reinterpret_cast<u32x4*>(Az + (c >> 3) * A_SLICE + r * 128 + (((c & 7) ^ (r & 7)) * 16)) = z;
+      *reinterpret_cast<u32x4*>(Az + (c >> 3) * A_SLICE + r * 128 + (((c & 7) ^ swz_kc<64>(r)) * 16)) = z;
       if (bx == 0 && m < M) {
         if (c == nchunk) z.x = 0x3F80u;                    // a bf16 one at sample position L (see above)
         *reinterpret_cast<u32x4*>(a.saved + m * a.Lp + 8 * c) = z;
@@ -216,7 +216,7 @@ __global__ __launch_bounds__(256, 2) void embed_fwd_fused_kernel(EmbedFused a) {
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
       Frag fa, fb[2];
-      lds_read16(fa.q, lds0 + kt * A_SLICE + ra * 128 + (((2 * ks + half) ^ (ra & 7)) * 16));
+      lds_read16(fa.q, lds0 + kt * A_SLICE + ra * 128 + (((2 * ks + half) ^ swz_kc<64>(ra)) * 16));
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
         const uint32_t base = addrB[j] + kt * B_SLICE + ks * 16 * BN * 2;

@@ -96,6 +96,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(SplitkReduce a) {
 // lane owns one output row and four consecutive columns per register quad; the tile goes through
 // LDS once more so that global stores are whole 16-byte chunks of consecutive rows.
 // The dimensions a kernel works with: those of the argument block, or what a device-side token count makes of them.
+constexpr int kGemmThreads = 512;     // four computing wavefronts and four copy wavefronts
 struct GemmDims {
   int M, K, splitk, kchunk, rs_n;
 };
@@ -113,7 +114,7 @@ __device__ __forceinline__ void gemm_async_tile(const GemmBf16& g, const GemmDim
   constexpr int CPITCH = BN * ES + 16;                                    // LDS row pitch of the output tile
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = (wave >> 1) & 1, wn = wave & 1;
   const int col = lane & 31, half = lane >> 5;
   const int zb = SPLIT ? bz / dm.splitk : bz;
   const int kbeg = SPLIT ? (bz % dm.splitk) * dm.kchunk : 0;
@@ -128,31 +129,41 @@ __device__ __forceinline__ void gemm_async_tile(const GemmBf16& g, const GemmDim
   const bf16_t* A0 = zsel == 0 ? g.A0 : (zsel == 1 ? A1 : (zsel == 2 ? A2 : g.A3));
   const bf16_t* B0 = zsel == 0 ? g.B0 : (zsel == 1 ? B1 : (zsel == 2 ? B2 : g.B3));
 
-  // ---- source offsets of this lane's copies (elements)
+  // ---- the copy wavefronts.  Wavefronts 4-7 do nothing but issue the asynchronous copies; wavefronts 0-3 never touch
+  // global memory inside the loop.  A copy instruction holds its wavefront until the memory pipeline takes it
+  // (300-500 clocks per slice for a wavefront's share), which would otherwise be time in which that wavefront
+  // issues neither LDS reads nor matrix instructions; one wavefront alone cannot issue a whole slice fast enough
+  // (about 32 bytes per clock), four reach the pipeline's 64-74.
+  const bool producer = wave >= 4;
+  const int w4 = wave & 3;
+  // source offsets (elements) of this copy wavefront's share: copy u fills LDS bytes [1024 (4 u + w4), + 1024) of the operand
   //   k-contiguous: clamped row * ld + chunk * 8, the slice start is added per stage
-  //   mn-contiguous: column offset; the k-row (first one in goffX[u] >> 16... kept separately) is clamped per stage
+  //   mn-contiguous: column offset; the k-row krowX + u * 4 * RPx is clamped per stage
+  static_assert((NS - 2) * LPS < 64, "the copy counter holds at most 63");
   int goffA[IA], goffB[IB];
-  int krowA = 0, krowB = 0;                 // k-row of copy 0 (mn-contiguous); copy u adds u * 4 * RPx
+  int krowA = 0, krowB = 0;
+  if (producer) {
 #pragma unroll
-  for (int u = 0; u < IA; ++u) {
-    if constexpr (AKC) {
-      const int row = (u * 4 + wave) * RPI + lane / CH;
-      goffA[u] = min(m0 + row, dm.M - 1) * g.lda + ((lane % CH) ^ swz_kc<BK>(row)) * 8;
-    } else {
-      const int krow = (u * 4 + wave) * RPA + lane / CHA;
-      if (u == 0) krowA = krow;
-      goffA[u] = min(m0 + ((lane % CHA) ^ swz_nc<BM>(krow)) * 8, dm.M - 8);
+    for (int u = 0; u < IA; ++u) {
+      if constexpr (AKC) {
+        const int row = (u * 4 + w4) * RPI + lane / CH;
+        goffA[u] = min(m0 + row, dm.M - 1) * g.lda + ((lane % CH) ^ swz_kc<BK>(row)) * 8;
+      } else {
+        const int krow = (u * 4 + w4) * RPA + lane / CHA;
+        if (u == 0) krowA = krow;
+        goffA[u] = min(m0 + ((lane % CHA) ^ swz_nc<BM>(krow)) * 8, dm.M - 8);
+      }
     }
-  }
 #pragma unroll
-  for (int u = 0; u < IB; ++u) {
-    if constexpr (BKC) {
-      const int row = (u * 4 + wave) * RPI + lane / CH;
-      goffB[u] = min(n0 + row, g.N - 1) * g.ldb + ((lane % CH) ^ swz_kc<BK>(row)) * 8;
-    } else {
-      const int krow = (u * 4 + wave) * RPB + lane / CHB;
-      if (u == 0) krowB = krow;
-      goffB[u] = min(n0 + ((lane % CHB) ^ swz_nc<BN>(krow)) * 8, g.N - 8);
+    for (int u = 0; u < IB; ++u) {
+      if constexpr (BKC) {
+        const int row = (u * 4 + w4) * RPI + lane / CH;
+        goffB[u] = min(n0 + row, g.N - 1) * g.ldb + ((lane % CH) ^ swz_kc<BK>(row)) * 8;
+      } else {
+        const int krow = (u * 4 + w4) * RPB + lane / CHB;
+        if (u == 0) krowB = krow;
+        goffB[u] = min(n0 + ((lane % CHB) ^ swz_nc<BN>(krow)) * 8, g.N - 8);
+      }
     }
   }
   // ---- fragment addresses (LDS bytes relative to a stage)
@@ -190,13 +201,13 @@ __device__ __forceinline__ void gemm_async_tile(const GemmBf16& g, const GemmDim
 #pragma unroll
     for (int j = 0; j < 2; ++j) acc[i][j] = zero16();
 
-  // ---- copy cursor
+  // ---- copy cursor (copy wavefront)
   int fseg = 0, fk = kbeg;
   const bf16_t* Ap = A0;
   const bf16_t* Bp = B0;
 #define VD_ISSUE_STAGE(BUF)                                                                        \
   {                                                                                                \
-    unsigned char* sp = smem + (BUF) * STAGE + wave * 1024;                                        \
+    unsigned char* sp = smem + (BUF) * STAGE + w4 * 1024;                                          \
     _Pragma("unroll") for (int u = 0; u < IA; ++u) {                                               \
       const bf16_t* p;                                                                             \
       if constexpr (AKC) p = Ap + fk + goffA[u];                                                   \
@@ -217,22 +228,32 @@ __device__ __forceinline__ void gemm_async_tile(const GemmBf16& g, const GemmDim
       Bp = fseg == 1 ? B1 : B2;                                                                    \
     }                                                                                              \
   }
+  if (producer) {
 #pragma unroll
-  for (int s = 0; s < NS - 1; ++s)
-    if (s < total) VD_ISSUE_STAGE(s)
-
+    for (int s = 0; s < NS - 1; ++s)
+      if (s < total) VD_ISSUE_STAGE(s)
+    for (int t0 = 0; t0 < total; t0 += NS) {
+#pragma unroll
+      for (int s = 0; s < NS; ++s) {
+        const int t = t0 + s;
+        if (t < total) {
+          // slice t has landed once at most `ahead` younger stages are still in flight
+          const int ahead = min(total - 1 - t, NS - 2);
+          if (NS >= 4 && ahead >= 2) wait_vm<(NS >= 4 ? 2 * LPS : 0)>();
+          else if (NS >= 3 && ahead == 1) wait_vm<(NS >= 3 ? LPS : 0)>();
+          else wait_vm<0>();
+          __builtin_amdgcn_s_barrier();     // slice t is in; everyone is done with slice t-1, whose buffer is filled next
+          if (t + NS - 1 < total) VD_ISSUE_STAGE((s + NS - 1) % NS)
+        }
+      }
+    }
+  } else {
   for (int t0 = 0; t0 < total; t0 += NS) {
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
       const int t = t0 + s;
       if (t < total) {
-        // slice t has landed once at most `ahead` younger stages are still in flight
-        const int ahead = min(total - 1 - t, NS - 2);
-        if (NS >= 4 && ahead >= 2) wait_vm<2 * LPS>();
-        else if (NS >= 3 && ahead == 1) wait_vm<LPS>();
-        else wait_vm<0>();
-        __builtin_amdgcn_s_barrier();     // everyone's copies of slice t are in; everyone is done with slice t-1
-        if (t + NS - 1 < total) VD_ISSUE_STAGE((s + NS - 1) % NS)
+        __builtin_amdgcn_s_barrier();     // the copy wavefront has seen slice t land
         const uint32_t so = s * STAGE;
         // valid k of this lane's first fragment; only the last slice of an mn-contiguous A can fall short
         int kvalid = 8;
@@ -289,12 +310,14 @@ __device__ __forceinline__ void gemm_async_tile(const GemmBf16& g, const GemmDim
       }
     }
   }
+  }
 #undef VD_ISSUE_STAGE
 
   // ---- epilogue.  acc[i][j] register 4*q4 + e is C[wm*BM/2 + i*32 + col][wn*64 + j*32 + 8*q4 + 4*half + e]
   // of the tile; it is written to LDS (with the bias), then stored as 16-byte chunks of whole rows.
   const bf16_t* bias = SPLIT ? nullptr : (zsel == 0 ? g.bias0 : (zsel == 1 ? g.bias1 : (zsel == 2 ? g.bias2 : g.bias3)));
   __syncthreads();                        // every wavefront is done reading the last slice
+  if (!producer)
 #pragma unroll
   for (int j = 0; j < 2; ++j)
 #pragma unroll
@@ -337,6 +360,7 @@ __device__ __forceinline__ void gemm_async_tile(const GemmBf16& g, const GemmDim
     Cb = reinterpret_cast<unsigned char*>(zsel == 0 ? g.C0 : (zsel == 1 ? g.C1 : (zsel == 2 ? g.C2 : g.C3)));
     ldc_bytes = (long long)g.ldc * 2;
   }
+  if (producer) return;                   // (no barrier follows)
 #pragma unroll
   for (int u = 0; u < BM * CPR / 256; ++u) {
     const int idx = u * 256 + threadIdx.x;
@@ -409,7 +433,7 @@ __device__ __forceinline__ bool gemm_resolve(const GemmBf16& g, GemmDims& dm) {
 // One-dimensional grid of at least nz * tiles workgroups (more when the launch was sized for the bound of a
 // device-side count: the surplus returns at once).
 template <bool AKC, bool BKC, bool SPLIT, int BM, int BK, int NS>
-__global__ __launch_bounds__(256, 2) void gemm_async_kernel(GemmBf16 g, int nz) {
+__global__ __launch_bounds__(kGemmThreads, 2) void gemm_async_kernel(GemmBf16 g, int nz) {
   GemmDims dm;
   if (!gemm_resolve(g, dm)) return;
   // tiles in the order n fastest, then m, then batch entry: a die's range shares its rows of A
@@ -423,25 +447,31 @@ __global__ __launch_bounds__(256, 2) void gemm_async_kernel(GemmBf16 g, int nz) 
 // gradients (gw: mn-contiguous operands, K slices, fp32 partial products) depend on the same dQ, dK,
 // dV and on nothing of each other, so they share one launch: workgroups [0, nx) take tiles of gx,
 // the rest tiles of gw.  The longer-running input-gradient tiles are dispatched first.
+// 64-row tiles run three 64-k copy stages deep (72 KB of LDS, two workgroups per compute unit), 128-row tiles four
+// 32-k stages (64 KB)
+template <int BMX> constexpr int pair_stages() { return BMX == 64 ? 3 : 4; }
+template <int BMX> constexpr int pair_bk() { return BMX == 64 ? 64 : 32; }
 template <int BMX>
-__global__ __launch_bounds__(256, 2) void gemm_bwd_pair_kernel(GemmBf16 gx, GemmBf16 gw, int nzw) {
+__global__ __launch_bounds__(kGemmThreads, 2) void gemm_bwd_pair_kernel(GemmBf16 gx, GemmBf16 gw, int nzw) {
   // Each die takes a contiguous range of the input-gradient tiles (n fastest: a range shares its rows
   // of dQ, dK, dV) and a contiguous range of the weight-gradient tiles (n, then m, then K slice, then
   // matrix: a range shares its K slice of both operands); its input-gradient tiles come first.
   GemmDims dx, dw;
   if (!gemm_resolve(gx, dx) || !gemm_resolve(gw, dw)) return;
-  const int gxn = (gx.N + 127) >> 7, gwn = (gw.N + 127) >> 7, gwm = (dw.M + 127) >> 7;
+  constexpr int BMW = BMX;      // rows of a weight-gradient tile
+  const int gxn = (gx.N + 127) >> 7, gwn = (gw.N + 127) >> 7, gwm = (dw.M + BMW - 1) / BMW;
   const int nx = gxn * ((dx.M + BMX - 1) / BMX), nw = gwn * gwm * nzw * dw.splitk;
   if ((int)blockIdx.x >= nx + nw) return;
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
   const int cntx = (nx >> 3) + (xcd < (nx & 7) ? 1 : 0);
   const int startx = xcd_range_start(xcd, nx);
+  constexpr int NS = pair_stages<BMX>();
   if (slot < cntx) {
     const int t = startx + slot;
-    gemm_async_tile<true, true, false, BMX, 64, 2>(gx, dx, t % gxn, t / gxn, 0);
+    gemm_async_tile<true, true, false, BMX, pair_bk<BMX>(), NS>(gx, dx, t % gxn, t / gxn, 0);
   } else {
     const int t = xcd_range_start(xcd, nx + nw) - startx + (slot - cntx);
-    gemm_async_tile<false, false, true, 128, 64, 2>(gw, dw, t % gwn, (t / gwn) % gwm, t / (gwn * gwm));
+    gemm_async_tile<false, false, true, BMW, pair_bk<BMX>(), NS>(gw, dw, t % gwn, (t / gwn) % gwm, t / (gwn * gwm));
   }
 }
 
@@ -464,7 +494,7 @@ int launch_gemm_async_cfg(vardrop_ctx* ctx, int kid, const GemmBf16& g, int nz, 
   if (grid >= (1ll << 31)) return VARDROP_EUNSUPPORTED;
   {
     VdTimer timer(ctx, kid, s);
-    VD_KERNEL(ctx, (gemm_async_kernel<AKC, BKC, SPLIT, BM, BK, NS>), dim3((unsigned)grid), dim3(256), lds, s, g, nz);
+    VD_KERNEL(ctx, (gemm_async_kernel<AKC, BKC, SPLIT, BM, BK, NS>), dim3((unsigned)grid), dim3(kGemmThreads), lds, s, g, nz);
   }
   VD_LAUNCH_CHECK(ctx);
   return VARDROP_OK;
@@ -472,7 +502,8 @@ int launch_gemm_async_cfg(vardrop_ctx* ctx, int kid, const GemmBf16& g, int nz, 
 // one launch for the input gradient gx and the sliced weight gradients gw (nzw matrices)
 template <int BMX>
 int launch_gemm_bwd_pair_cfg(vardrop_ctx* ctx, const GemmBf16& gx, const GemmBf16& gw, int nzw, hipStream_t s) {
-  constexpr int ldsx = gemm_async_lds<false, BMX, 64, 2>(), ldsw = gemm_async_lds<true, 128, 64, 2>();
+  constexpr int NS = pair_stages<BMX>();
+  constexpr int ldsx = gemm_async_lds<false, BMX, pair_bk<BMX>(), NS>(), ldsw = gemm_async_lds<true, BMX, pair_bk<BMX>(), NS>();
   constexpr int lds = ldsx > ldsw ? ldsx : ldsw;
   static int configured_device = -1;
   if (configured_device != ctx->device) {
@@ -480,11 +511,11 @@ int launch_gemm_bwd_pair_cfg(vardrop_ctx* ctx, const GemmBf16& gx, const GemmBf1
     configured_device = ctx->device;
   }
   const int gxn = vd_ceil_div(gx.N, 128), gxm = vd_ceil_div(gx.M, BMX);
-  const int gwn = vd_ceil_div(gw.N, 128), gwm = vd_ceil_div(gw.M, 128);
+  const int gwn = vd_ceil_div(gw.N, 128), gwm = vd_ceil_div(gw.M, BMX);
   const int nx = gxn * gxm, nw = gwn * gwm * nzw * gw.splitk;
   {
     VdTimer timer(ctx, VARDROP_K_GEMM_DW_DXS, s);
-    VD_KERNEL(ctx, gemm_bwd_pair_kernel<BMX>, dim3(nx + nw), dim3(256), lds, s, gx, gw, nzw);
+    VD_KERNEL(ctx, gemm_bwd_pair_kernel<BMX>, dim3(nx + nw), dim3(kGemmThreads), lds, s, gx, gw, nzw);
   }
   VD_LAUNCH_CHECK(ctx);
   return VARDROP_OK;
