@@ -8,7 +8,10 @@
 //   2. head flags + block scan              -> dense group id (ascending hash), start, size
 //   3. u[n] from Philox4x32-10, counter (n, 0, step_lo, step_hi), key (seed_lo, seed_hi); the rank of a
 //      member inside its group by counting over the group (groups above 1024 members: a second sort by
-//      (group, u[n], n)); a member is kept when its rank is below n_i
+//      (group, u[n], n)); a member is kept when its rank is below n_i.
+//      Up to 4096 variates steps 1 and 3 are one: u[n] is drawn while the hashes are on their way from memory, the
+//      count inside a bucket orders by (hash, u[n], n), and the rank of a member inside its group is its
+//      distance from the group's start.
 //   4. flags by variate + block scan        -> sel ascending, N'
 #include "common.h"
 
@@ -132,11 +135,11 @@ __device__ void bitonic_sort_keys(K* key, int npad) {
           if ((ok < k[e]) == keep_min) k[e] = ok;
         }
       } else if (stride == 4) {
-        in_thread_exchange_keys<K, E, 4>(k, tid, size);
+        if constexpr (E > 4) in_thread_exchange_keys<K, E, 4>(k, tid, size);
       } else if (stride == 2) {
-        in_thread_exchange_keys<K, E, 2>(k, tid, size);
+        if constexpr (E > 2) in_thread_exchange_keys<K, E, 2>(k, tid, size);
       } else {
-        in_thread_exchange_keys<K, E, 1>(k, tid, size);
+        if constexpr (E > 1) in_thread_exchange_keys<K, E, 1>(k, tid, size);
       }
     }
   }
@@ -197,11 +200,11 @@ __device__ void bitonic_sort(uint64_t* key, uint32_t* pay, int npad) {
           }
         }
       } else if (stride == 4) {
-        in_thread_exchange<E, 4, kByGroup>(k, p, tid, size);
+        if constexpr (E > 4) in_thread_exchange<E, 4, kByGroup>(k, p, tid, size);
       } else if (stride == 2) {
-        in_thread_exchange<E, 2, kByGroup>(k, p, tid, size);
+        if constexpr (E > 2) in_thread_exchange<E, 2, kByGroup>(k, p, tid, size);
       } else {
-        in_thread_exchange<E, 1, kByGroup>(k, p, tid, size);
+        if constexpr (E > 1) in_thread_exchange<E, 1, kByGroup>(k, p, tid, size);
       }
     }
   }
@@ -214,6 +217,39 @@ __device__ void bitonic_sort(uint64_t* key, uint32_t* pay, int npad) {
   __syncthreads();
 }
 
+// Inclusive prefix sum over the 64 lanes: four shifts inside the rows of 16 lanes, then the last lane of a row is
+// added to the next row and lane 31 to the upper half (lanes a step does not reach add zero).
+__device__ inline int wave_inclusive_sum(int v) {
+  v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xF, 0xF, false);   // row_shr:1
+  v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xF, 0xF, false);   // row_shr:2
+  v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xF, 0xF, false);   // row_shr:4
+  v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xF, 0xF, false);   // row_shr:8
+  v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xA, 0xF, false);   // row_bcast:15 into rows 1 and 3
+  v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xC, 0xF, false);   // row_bcast:31 into rows 2 and 3
+  return v;
+}
+// Minimum and maximum of a 64-bit value over the 64 lanes (same steps; lanes a step does not reach keep their
+// own value); valid in lane 63.
+__device__ inline void wave_minmax64(unsigned long long& lo, unsigned long long& hi) {
+#define VD_MM(CTRL, ROWS)                                                                                     \
+  {                                                                                                           \
+    const uint32_t l0 = (uint32_t)lo, l1 = (uint32_t)(lo >> 32), h0 = (uint32_t)hi, h1 = (uint32_t)(hi >> 32); \
+    const unsigned long long ol = ((unsigned long long)(uint32_t)__builtin_amdgcn_update_dpp((int)l1, (int)l1, CTRL, ROWS, 0xF, false) << 32) | \
+                                  (uint32_t)__builtin_amdgcn_update_dpp((int)l0, (int)l0, CTRL, ROWS, 0xF, false);  \
+    const unsigned long long oh = ((unsigned long long)(uint32_t)__builtin_amdgcn_update_dpp((int)h1, (int)h1, CTRL, ROWS, 0xF, false) << 32) | \
+                                  (uint32_t)__builtin_amdgcn_update_dpp((int)h0, (int)h0, CTRL, ROWS, 0xF, false);  \
+    lo = ol < lo ? ol : lo;                                                                                   \
+    hi = oh > hi ? oh : hi;                                                                                   \
+  }
+  VD_MM(0x111, 0xF)
+  VD_MM(0x112, 0xF)
+  VD_MM(0x114, 0xF)
+  VD_MM(0x118, 0xF)
+  VD_MM(0x142, 0xA)
+  VD_MM(0x143, 0xC)
+#undef VD_MM
+}
+
 // Exclusive prefix sum over vals[0..count) (count <= per * blockDim.x), in place; returns the total
 // to every thread.  `wsum` holds one slot per wavefront plus one.
 __device__ int block_exclusive_scan(int* vals, int count, int* wsum) {
@@ -223,24 +259,14 @@ __device__ int block_exclusive_scan(int* vals, int count, int* wsum) {
   int local = 0;
   for (int i = 0; i < per; ++i)
     if (begin + i < count) local += vals[begin + i];
-  int incl = local;
+  const int incl = wave_inclusive_sum(local);
   const int lane = tid & 63, wave = tid >> 6;
-#pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    const int o = __shfl_up(incl, off, 64);
-    if (lane >= off) incl += o;
-  }
   if (lane == 63) wsum[wave] = incl;
   __syncthreads();
-  if (tid < 64) {                                   // at most 16 wavefront totals: one shuffle scan
+  if (tid < 64) {                                   // at most 16 wavefront totals: one scan of the first wavefront
     const int nw = (nt + 63) >> 6;
     const int t = tid < nw ? wsum[tid] : 0;
-    int inc = t;
-#pragma unroll
-    for (int off = 1; off < 16; off <<= 1) {
-      const int o = __shfl_up(inc, off, 64);
-      if (tid >= off) inc += o;
-    }
+    const int inc = wave_inclusive_sum(t);
     if (tid < nw) wsum[tid] = inc - t;
     if (tid == nw - 1) wsum[nw] = inc;
   }
@@ -307,7 +333,34 @@ __device__ inline int count_before(const uint64_t* key, const uint32_t* pay, uin
   return r;
 }
 
-template <int E>
+// One 16-byte record per variate for the count inside a bucket: x = the hash's bits below the bucket index (all
+// that differs inside a bucket), (y, z) = u[n], w = n.  Number of records q in [s0, s1) that order before `me`.
+__device__ inline int count_before_rec(const uint4* rec, int s0, int s1, uint4 me) {
+  const unsigned long long um = ((unsigned long long)me.y << 32) | me.z;
+  int r = 0;
+  int q = s0;
+  for (; q + 4 <= s1; q += 4) {
+    uint4 o[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) o[u] = rec[q + u];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const unsigned long long uo = ((unsigned long long)o[u].y << 32) | o[u].z;
+      r += (o[u].x < me.x || (o[u].x == me.x && (uo < um || (uo == um && o[u].w < me.w)))) ? 1 : 0;
+    }
+  }
+  for (; q < s1; ++q) {
+    const uint4 o = rec[q];
+    const unsigned long long uo = ((unsigned long long)o.y << 32) | o.z;
+    r += (o.x < me.x || (o.x == me.x && (uo < um || (uo == um && o.w < me.w)))) ? 1 : 0;
+  }
+  return r;
+}
+
+// FUSED: one ordering by (hash, u[n], n) instead of one by (hash, n) and a ranking by (u[n], n) inside every group
+// (needs another 16 bytes of LDS per variate: up to 4096 of them; the hash's bits below the bucket index must fit
+// 32 bits, i.e. the hashes span less than 2^42, else the sorting networks take over).
+template <int E, bool FUSED>
 __global__ __launch_bounds__(1024) void sample_kernel(SampleArgs a) {
   extern __shared__ unsigned char smem[];
   const int N = a.N, npad = a.npad;
@@ -321,11 +374,36 @@ __global__ __launch_bounds__(1024) void sample_kernel(SampleArgs a) {
   int* bstart = reinterpret_cast<int*>(mm + 2);                        // [kBuckets + 1]
   int* bcur = bstart + kBuckets + 1;                                   // [kBuckets]
   int* bmax = bcur + kBuckets;                                         // [1]
+  uint4* rec = reinterpret_cast<uint4*>(
+      reinterpret_cast<unsigned char*>(bmax + 1) + ((16 - (reinterpret_cast<uintptr_t>(bmax + 1) & 15)) & 15));   // [npad], FUSED only
   const int tid = threadIdx.x, nt = blockDim.x;
   // every thread's E hashes (variates tid, tid + nt, ...; npad = E * nt), read from memory once
   uint64_t hreg[E];
 #pragma unroll
   for (int e = 0; e < E; ++e) hreg[e] = tid + e * nt < N ? a.hash[tid + e * nt] : 0ull;
+  // ... and, while they travel, the keys that order the members of a group
+  unsigned long long ureg[FUSED ? E : 1];
+  if constexpr (FUSED) {
+    if (a.step_dev) {
+      const uint64_t step = *a.step_dev;
+      a.step_lo = (uint32_t)step;
+      a.step_hi = (uint32_t)(step >> 32);
+    }
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+      const uint32_t n = (uint32_t)(tid + e * nt);
+      ureg[e] = 0ull;
+      if (n < (uint32_t)N) {
+        if (a.ext_keys) {
+          ureg[e] = a.ext_keys[n];
+        } else {
+          uint32_t r0, r1;
+          philox4x32_10(n, 0u, a.step_lo, a.step_hi, a.seed_lo, a.seed_hi, r0, r1);
+          ureg[e] = ((unsigned long long)r0 << 32) | r1;
+        }
+      }
+    }
+  }
 
   // Sort 1, usual path.  (hash, n) pairs are dropped into kBuckets order-preserving buckets (equal
   // width over [min, max] of the hashes, a shift instead of a division); inside a bucket the position
@@ -349,13 +427,8 @@ __global__ __launch_bounds__(1024) void sample_kernel(SampleArgs a) {
         hi = h > hi ? h : hi;
       }
     // one atomic per wavefront, not per thread: same-address LDS atomics serialise
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-      const unsigned long long ol = lane_xor((uint64_t)lo, off), oh = lane_xor((uint64_t)hi, off);
-      lo = ol < lo ? ol : lo;
-      hi = oh > hi ? oh : hi;
-    }
-    if ((tid & 63) == 0) {
+    wave_minmax64(lo, hi);
+    if ((tid & 63) == 63) {
       atomicMin(&mm[0], lo);
       atomicMax(&mm[1], hi);
     }
@@ -375,7 +448,7 @@ __global__ __launch_bounds__(1024) void sample_kernel(SampleArgs a) {
       if ((tid & 63) == 0) atomicMax(bmax, m);
     }
     __syncthreads();
-    if (*bmax <= kCountMax) {
+    if (*bmax <= kCountMax && (!FUSED || shift <= 32)) {
       block_exclusive_scan(bstart, kBuckets, wsum);                    // counts -> bucket starts
       for (int i = tid; i < kBuckets; i += nt) bcur[i] = bstart[i];
       __syncthreads();
@@ -386,6 +459,8 @@ __global__ __launch_bounds__(1024) void sample_kernel(SampleArgs a) {
           const int pos = atomicAdd(&bcur[(int)((h - hmin) >> shift)], 1);
           key[pos] = h;
           pay[pos] = (uint32_t)(tid + e * nt);
+          if constexpr (FUSED)
+            rec[pos] = make_uint4((uint32_t)((h - hmin) & ((1ull << shift) - 1ull)), (uint32_t)(ureg[e] >> 32), (uint32_t)ureg[e], (uint32_t)(tid + e * nt));
         }
       __syncthreads();
       for (int p = tid; p < N; p += nt) {
@@ -393,7 +468,8 @@ __global__ __launch_bounds__(1024) void sample_kernel(SampleArgs a) {
         const uint32_t np = pay[p];
         const int b = (int)((kp - hmin) >> shift);
         const int s0 = bstart[b], s1 = bcur[b];
-        scan[p] = s0 + count_before(key, pay, 0xffffffffu, s0, s1, kp, np);
+        if constexpr (FUSED) scan[p] = s0 + count_before_rec(rec, s0, s1, rec[p]);
+        else scan[p] = s0 + count_before(key, pay, 0xffffffffu, s0, s1, kp, np);
       }
       __syncthreads();
       uint64_t rk[E];
@@ -488,7 +564,8 @@ __global__ __launch_bounds__(1024) void sample_kernel(SampleArgs a) {
     for (int off = 32; off >= 1; off >>= 1) m = max(m, __shfl_xor(m, off, 64));
     if ((tid & 63) == 0) atomicMax(&wsum[18], m);
   }
-  if (a.step_dev) {
+  const bool ranked = FUSED && sorted;          // the order inside every group is already that of (u[n], n)
+  if (!FUSED && a.step_dev) {
     const uint64_t step = *a.step_dev;
     a.step_lo = (uint32_t)step;
     a.step_hi = (uint32_t)(step >> 32);
@@ -497,7 +574,9 @@ __global__ __launch_bounds__(1024) void sample_kernel(SampleArgs a) {
     const uint32_t n = pay[p];
     const int g = scan[p];
     a.group_id[n] = g;
-    if (a.ext_keys) {
+    if (ranked) {
+      // nothing to draw
+    } else if (a.ext_keys) {
       key[p] = a.ext_keys[n];
     } else {
       uint32_t r0, r1;
@@ -508,7 +587,13 @@ __global__ __launch_bounds__(1024) void sample_kernel(SampleArgs a) {
   }
   __syncthreads();
   const int max_group = wsum[18];
-  if (max_group <= kCountMax) {
+  if (ranked) {
+    for (int p = tid; p < N; p += nt) {
+      const uint32_t g = pay[p] >> 16, n = pay[p] & 0xffffu;
+      const int s0 = gstart[g], s1 = gstart[g + 1];
+      scan[n] = (uint32_t)(p - s0) < keep_count((uint32_t)(s1 - s0), a) ? 1 : 0;
+    }
+  } else if (max_group <= kCountMax) {
     // Groups are short: the rank of a member inside its group is a count over the group.
     for (int p = tid; p < N; p += nt) {
       const uint32_t g = pay[p] >> 16, n = pay[p] & 0xffffu;
@@ -615,9 +700,11 @@ int run_sample(vardrop_ctx* ctx, const uint64_t* hash, int N,
   if (N > kMaxN) return VARDROP_EUNSUPPORTED;
   int npad = next_pow2(N);
   if (npad < 128) npad = 128;
-  const size_t lds = (size_t)npad * 16 + 20 * 4 + (size_t)(npad + 1) * 2 + 14 + 16 + (2 * kBuckets + 2) * 4;
+  const bool fused = npad <= 4096;
+  const size_t lds = (size_t)npad * 16 + 20 * 4 + (size_t)(npad + 1) * 2 + 14 + 16 + (2 * kBuckets + 2) * 4 + (fused ? (size_t)npad * 16 + 16 : 0);
   if (lds > (size_t)ctx->lds_per_block) return VARDROP_EUNSUPPORTED;
-  const int E = npad <= 2048 ? 2 : (npad == 4096 ? 4 : 8);     // elements per thread of the sort
+  // elements per thread of the sort: as many threads as the workgroup may have, so that the counting loops are short
+  const int E = npad <= 1024 ? 1 : (npad <= 2048 ? 2 : (npad == 4096 ? 4 : 8));
   const int threads = npad / E;
   SampleArgs a;
   a.hash = hash;
@@ -639,14 +726,15 @@ int run_sample(vardrop_ctx* ctx, const uint64_t* hash, int N,
   a.step_dev = step_dev;
   a.advance = advance;
   hipStream_t s = (hipStream_t)stream;
-  const void* fn = E == 2 ? (const void*)sample_kernel<2> : (E == 4 ? (const void*)sample_kernel<4> : (const void*)sample_kernel<8>);
+  const void* fn = E == 1 ? (const void*)sample_kernel<1, true> : E == 2 ? (const void*)sample_kernel<2, true> : (E == 4 ? (const void*)sample_kernel<4, true> : (const void*)sample_kernel<8, false>);
   if (lds > 65536)
     VD_HIP(ctx, hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
   {
     VdTimer timer(ctx, VARDROP_K_SAMPLE, s);
-    if (E == 2) VD_KERNEL(ctx, sample_kernel<2>, dim3(1), dim3(threads), lds, s, a);
-    else if (E == 4) VD_KERNEL(ctx, sample_kernel<4>, dim3(1), dim3(threads), lds, s, a);
-    else VD_KERNEL(ctx, sample_kernel<8>, dim3(1), dim3(threads), lds, s, a);
+    if (E == 1) VD_KERNEL(ctx, (sample_kernel<1, true>), dim3(1), dim3(threads), lds, s, a);
+    else if (E == 2) VD_KERNEL(ctx, (sample_kernel<2, true>), dim3(1), dim3(threads), lds, s, a);
+    else if (E == 4) VD_KERNEL(ctx, (sample_kernel<4, true>), dim3(1), dim3(threads), lds, s, a);
+    else VD_KERNEL(ctx, (sample_kernel<8, false>), dim3(1), dim3(threads), lds, s, a);
   }
   VD_LAUNCH_CHECK(ctx);
   if (counts_host)
