@@ -88,10 +88,11 @@ def test_bf16_ragged_token_counts_with_biases(vd, ctx, n):
     compare(got, want, "bf16", ("y",) + GRADS + ("dbq", "dbk", "dbv", "dbo"))
 
 
-@pytest.mark.parametrize("n", [129, 192, 257, 321])
+@pytest.mark.parametrize("n", [129, 188, 192, 200, 256, 257, 321])
 def test_bf16_ragged_token_counts_in_the_wide_launch_shape(vd, ctx, n):
     """Enough (batch, head) pairs that the long-selection kernels run with four wavefronts and 128 rows per
-    workgroup (the shape the large workloads use), at token counts that end a block of 64 and of 128 early."""
+    workgroup (the shape the large workloads use), at token counts that end a block of 64 and of 128 early, the first
+    count past the single-kernel path (129) and the token count the paper reports for Traffic (188, Table 3)."""
     xs, W, dy, b = random_case(1000 + n, 32, n, 512, "bf16", bias=False)
     want = oracle_attention(xs, W, 8, dy)
     got = run_gpu(vd, ctx, xs, W, 8, dy, "bf16")

@@ -100,7 +100,7 @@ def test_step_with_the_count_on_the_device_matches_oracle(vd, ctx, name):
         print("%s bound %d: N'=%d errs=%s" % (name, n_max, n, {k: "%.1e" % v for k, v in errs.items()}))
 
 
-@pytest.mark.parametrize("n_max,counts", [(128, (1, 5, 31, 64, 127, 128)), (300, (1, 63, 128, 129, 200, 300)),
+@pytest.mark.parametrize("n_max,counts", [(128, (1, 5, 31, 64, 127, 128)), (300, (1, 63, 128, 129, 188, 200, 256, 300)),
                                           (96, (96, 17))])
 def test_ragged_counts_under_one_bound(vd, ctx, n_max, counts):
     """One set of buffers and one bound, many counts (bf16, with biases and bias gradients): every count against
