@@ -105,8 +105,11 @@ def parse():
                     help="the tokens are embedded inside the step from the raw windows, for the kept variates only "
                          "(vardrop_embed_fwd / vardrop_embed_bwd; with --dense for all variates), instead of being "
                          "gathered from a pre-embedded batch")
-    ap.add_argument("--launch", choices=("eager", "graph"), default="eager",
-                    help="issue every call of a step from the host (default: faster with this runtime) or replay one "
+    ap.add_argument("--launch", choices=("auto", "eager", "burst", "graph"), default="auto",
+                    help="eager: every call of a step issued from the host, the selection kernels placed beside chosen "
+                         "attention kernels; burst: the same calls with the selections in bursts of four on the second "
+                         "stream (less work for the host: better when a step is shorter than the host's time to issue "
+                         "it); auto (default): whichever of the two is faster in a short untimed trial; graph: one "
                          "recorded HIP graph per step")
     ap.add_argument("--no-paper-rule", action="store_true",
                     help="skip the second figure at the paper's own sampling rule (Eq. 1 with Table 8's k and gs)")
@@ -301,15 +304,23 @@ class Pipeline:
     The selection of a batch (k-DFH, grouping, sampling) depends on its windows only, so it runs on a second
     stream beside the attention of earlier batches.  Nothing of it crosses to the host: the attention kernels read
     N' on the device.
-      eager: selections are issued in bursts of BURST steps into a ring of RING buffer sets; the attention
+      eager: the selection of step g + LEAD is placed beside chosen kernels of step g: it starts when the attention
+             backward kernel of step g has finished, so that k-DFH and the one-workgroup sampling kernel run beside
+             the weight- and input-gradient kernel and the slice sum (which leave compute units and LDS free) and
+             are done when the next step's forward starts.  The two single-launch attention kernels need every
+             compute unit at once, and a selection kernel that holds one of them makes such a kernel wait a whole
+             round.  Measured at the Traffic shape: 79.1 us per step, against 80.7 with the k-DFH behind the forward
+             kernel instead, 84 with both behind the output projection, and 83.7 for unplaced bursts.  The placement
+             uses a completion event that rides on the kernel's own dispatch (vardrop_signal_after), so the
+             attention stream carries no event packets; it waits for the selection stream once per BURST steps.  A call of `count` steps issues
+             exactly `count` selections; the first LEAD of them run ahead of the call's first step.
+      burst: selections are issued in bursts of BURST steps into a ring of RING buffer sets; the attention
              stream waits for one event per burst (and the selection stream for one per burst before it reuses
-             ring sets), so cross-stream events, which cost the waiting stream several microseconds each, are
-             paid once per BURST steps.  The first burst of a call holds one step, so that a call of `count`
-             steps issues exactly `count` selections and at most one of them runs beside nothing.
+             ring sets).  The first burst of a call holds one step.
       graph: one recorded HIP graph per step, the selection of the NEXT batch on a branch forked from and joined
              back into the attention stream (ring of two sets).
     """
-    BURST, RING = 4, 12
+    BURST, RING, LEAD = 4, 12, 5
 
     def __init__(self, vd, ctx, w, xs_dev, tok_dev, W_dev, dy_full, seed, gs_cap=0, dense=False, embed=None):
         import torch
@@ -359,6 +370,31 @@ class Pipeline:
             self.ews = torch.empty(max(lib.vardrop_embed_workspace_bytes(w.B, self.n_max, w.L, w.d, code), 256), dtype=torch.uint8, device=dev)
             self.dWe_buf = (torch.empty((w.L, w.d), dtype=torch.float32, device=dev), torch.empty(w.d, dtype=torch.float32, device=dev))
         self.graphs = None
+        self.gate = None                           # (kernel id whose end starts the hash, ... the sampling) for eager mode
+        self.gate_events = None
+        self.placed = None
+
+    def set_gate(self, after):
+        """Kernel id (of this step's own launches) behind which a later step's selection is placed."""
+        torch = self.torch
+        self.gate = after
+        self.gate_events = []
+        for _ in range(self.RING):
+            ev = torch.cuda.Event()
+            ev.record(self.main)                   # creates the underlying event; its handle is reused from here on
+            self.gate_events.append(ev)
+        self.main.synchronize()
+        # raw handles and the runtime's own wait call: two waits per step through torch's wrappers cost the host
+        # more than the calls they order
+        import ctypes
+        self.hip = ctypes.CDLL("libamdhip64.so")
+        self.hip.hipStreamWaitEvent.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint]
+        self.hip.hipStreamWaitEvent.restype = ctypes.c_int
+        self.gate_handles = [ev.cuda_event for ev in self.gate_events]
+
+    def side_wait(self, handle):
+        if self.hip.hipStreamWaitEvent(self.side.cuda_stream, handle, 0) != 0:
+            raise RuntimeError("hipStreamWaitEvent failed")
 
     def select(self, b, r, stream):
         """k-DFH + grouping + sampling of batch b into ring set r; the step counter advances on the device."""
@@ -368,7 +404,7 @@ class Pipeline:
         vd.vardrop_sample_dev(self.ctx, hsh, self.gs_cap, self.ratio[0], self.ratio[1], self.seed, self.step_dev, True,
                               (gid, sel, counts), stream=stream.cuda_stream)
 
-    def attend(self, b, r, stream):
+    def attend(self, b, r, stream, gate=None):
         vd, w = self.vd, self.w
         sel, counts = self.ring[r][3], self.ring[r][4]
         if self.embed is not None:
@@ -380,6 +416,8 @@ class Pipeline:
         else:
             vd.vardrop_gather_attn_fwd_dev(self.ctx, self.tok_dev[b], sel, counts, self.n_max, *self.W_dev, w.H,
                                            self.xs_buf, self.y_buf, self.saved, status=self.status, stream=stream.cuda_stream)
+        if gate is not None:
+            vd.vardrop_signal_after(self.ctx, self.gate, gate)
         vd.vardrop_attn_bwd_dev(self.ctx, self.dy_full, self.xs_buf, counts, self.n_max, *self.W_dev, w.H, self.saved,
                                 self.ws, (self.dxs_buf, *self.dW_buf), status=self.status, stream=stream.cuda_stream)
         if self.embed is not None:
@@ -435,6 +473,25 @@ class Pipeline:
                 self.attend(g % self.nb, g % self.RING, self.main)
             return
         end = first + count
+        if launch == "eager" and self.gate is not None:
+            B4, LEAD = self.BURST, self.LEAD
+            drawn = lambda j: self.event(j)              # selections of steps first + 4 j .. first + 4 j + 3 are drawn
+            for g in range(first, min(end, first + LEAD)):
+                self.select(g % self.nb, g % self.RING, self.side)
+                if (g - first) % B4 == B4 - 1 or g == end - 1:
+                    drawn((g - first) // B4).record(self.side)
+            for g in range(first, end):
+                if (g - first) % B4 == 0:
+                    self.main.wait_event(drawn((g - first) // B4))
+                eb = self.gate_handles[g % self.RING]
+                t = g + LEAD
+                self.attend(g % self.nb, g % self.RING, self.main, gate=eb if t < end else None)
+                if t < end:
+                    self.side_wait(eb)
+                    self.select(t % self.nb, t % self.RING, self.side)
+                    if (t - first) % B4 == B4 - 1 or t == end - 1:
+                        drawn((t - first) // B4).record(self.side)
+            return
         blocks, g = [], first
         while g < end:
             size = 1 if g == first else self.BURST
@@ -463,6 +520,44 @@ class Pipeline:
         ns = [self.n_of[g % self.nb] for g in range(first, first + count)]
         gs = [self.G_of[g % self.nb] for g in range(first, first + count)]
         return sum(ns) / len(ns), sum(gs) / len(gs)
+
+
+def place_selection(pipe):
+    """eager mode: finds the attention kernels of this pipeline's steps (two untimed steps with every launch timed)
+    and places the selection behind the last attention backward kernel."""
+    import torch
+    vd, ctx = pipe.vd, pipe.ctx
+    if pipe.dense:
+        return
+    pipe.step_dev.zero_()
+    vd.vardrop_profile_select(ctx, vd.K_ALL)
+    pipe.run(0, 2, "burst")
+    torch.cuda.synchronize()
+    ran = set(vd.vardrop_profile_read_all(ctx))
+    vd.vardrop_profile_select(ctx, -1)
+    kid = {vd.vardrop_kernel_name(k): k for k in range(64) if vd.vardrop_kernel_name(k)}
+    bwd = next((name for name in ("sdpa_bwd", "sdpa_bwd_dqkv", "sdpa_bwd_dkv") if name in ran), None)
+    if bwd:
+        pipe.set_gate(kid[bwd])
+        pipe.placed = {"selection_starts_after": bwd}
+
+
+def choose_launch(pipe, args):
+    """--launch auto: places the selection, then tries eager and burst for a few untimed steps each."""
+    import copy
+    if args.launch != "auto":
+        if args.launch == "eager":
+            place_selection(pipe)
+        return args.launch
+    if pipe.dense:
+        return "burst"
+    place_selection(pipe)
+    if pipe.gate is None:
+        return "burst"
+    trial = copy.copy(args)
+    trial.steps, trial.warmup = 80, 20
+    best = min(("eager", "burst"), key=lambda mode: min(timed_steps(pipe, trial, mode)[0] for _ in range(2)))
+    return best
 
 
 def timed_steps(pipe, args, launch):
@@ -599,13 +694,13 @@ def main():
             for gs in (1, 2, 3, 5, 8, 10, 15, 20):
                 wk = dataclasses.replace(w, k=k)
                 pipe = Pipeline(vd, ctx, wk, xs_dev, tok_dev, W_dev, dy_full, seed, gs_cap=gs)
-                ms, _ = timed_steps(pipe, sw, args.launch)
+                ms, _ = timed_steps(pipe, sw, "burst" if args.launch == "auto" else args.launch)
                 n_mean, g_mean = pipe.kept(sw.warmup, sw.steps)
                 table.append({"k": k, "gs": gs, "groups": g_mean, "kept": n_mean, "delta": 1.0 - n_mean / w.N,
                               "token_bound": pipe.n_max, "steps_per_s": 1e3 / ms})
                 del pipe
         print(json.dumps({"metric": "reduction ratio delta and train steps/s over k and gs (Eq. 1)", "n_gpus": 1,
-                          "data": "synthetic", "dtype": w.dtype, "launch": args.launch,
+                          "data": "synthetic", "dtype": w.dtype, "launch": "burst" if args.launch == "auto" else args.launch,
                           "config": {"workload": "%s-shaped: B=%d N=%d L=%d d=%d H=%d" % (w.name, w.B, w.N, w.L, w.d, w.H)},
                           "table": table}))
         return
@@ -617,7 +712,8 @@ def main():
         embed = ((torch.randn((w.L, w.d), generator=gen, device=dev) / w.L ** 0.5).to(td),
                  (0.1 * torch.randn(w.d, generator=gen, device=dev)).to(td))
     pipe = Pipeline(vd, ctx, w, xs_dev, tok_dev, W_dev, dy_full, seed, gs_cap=args.gs, dense=args.dense, embed=embed)
-    ms, host_ms = timed_steps(pipe, args, args.launch)
+    launch = choose_launch(pipe, args)
+    ms, host_ms = timed_steps(pipe, args, launch)
     n_mean, g_mean = pipe.kept(args.warmup, args.steps)
 
     # ---- roofline: the same steps once more, issued call by call, every dispatch timed by the events the runtime
@@ -625,10 +721,10 @@ def main():
     # cannot carry them).  Dominant = the kernel with the largest share of a step on the attention stream.
     PROF_STEPS = 8
     pipe.step_dev.zero_()
-    pipe.run(0, 4, "eager")
+    pipe.run(0, 4, "burst")
     torch.cuda.synchronize()
     vd.vardrop_profile_select(ctx, vd.K_ALL)
-    pipe.run(4, PROF_STEPS, "eager")
+    pipe.run(4, PROF_STEPS, "burst")                 # (a kernel that carries a completion signal cannot be timed)
     torch.cuda.synchronize()
     per_kernel = vd.vardrop_profile_read_all(ctx)
     vd.vardrop_profile_select(ctx, -1)
@@ -668,7 +764,7 @@ def main():
                                (w.name, w.B, w.N, w.L, w.k, ("min(|G|,%d)" % args.gs) if args.gs else "%d/%d" % w.ratio, w.d, w.H),
                    "k": w.k, "gs": args.gs if args.gs else None,
                    "kept_tokens_mean": n_mean, "groups_mean": g_mean, "token_bound": pipe.n_max,
-                   "batches": args.batches, "launch": args.launch},
+                   "batches": args.batches, "launch": launch, "selection_placement": pipe.placed if launch == "eager" else None},
         "roofline": roof, "roofline_all": roof_all,
     }
     # ---- the paper's own rule for this dataset shape (Table 8: Traffic k = 4, gs = 10; Electricity k = 3, gs = 10)
@@ -676,11 +772,13 @@ def main():
     if paper_rule and not (args.dense or args.gs or args.k or args.no_paper_rule or args.embed):
         wk = dataclasses.replace(w, k=paper_rule[0])
         p2 = Pipeline(vd, ctx, wk, xs_dev, tok_dev, W_dev, dy_full, seed, gs_cap=paper_rule[1])
-        ms2, host2 = timed_steps(p2, args, args.launch)
+        launch2 = choose_launch(p2, args)
+        ms2, host2 = timed_steps(p2, args, launch2)
         n2, g2 = p2.kept(args.warmup, args.steps)
         out["paper_rule"] = {"rule": "Eq. 1, |S_i| = min(|G_i|, gs), with Table 8's k = %d, gs = %d" % paper_rule,
                              "value": 1e3 / ms2, "unit": "steps/s", "ms_per_step": ms2, "host_issue_ms_per_step": host2,
-                             "kept_tokens_mean": n2, "groups_mean": g2, "delta": 1.0 - n2 / w.N, "token_bound": p2.n_max}
+                             "kept_tokens_mean": n2, "groups_mean": g2, "delta": 1.0 - n2 / w.N, "token_bound": p2.n_max,
+                             "launch": launch2}
         del p2
     if not args.dense and not args.embed and not args.no_cpu_baseline:
         gpu_topk = None

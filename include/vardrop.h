@@ -104,6 +104,15 @@ int vardrop_profile_select(vardrop_ctx* ctx, int kernel_id);
 int vardrop_profile_read(vardrop_ctx* ctx, double* total_ms, int* launches);
 int vardrop_profile_read_all(vardrop_ctx* ctx, double* total_ms, int* launches);
 int vardrop_profile_stride(vardrop_ctx* ctx, int stride);
+/* Completion signal without a stream packet.  The next launch of kernel `kernel_id` through this context carries
+ * `event` (a hipEvent_t created by the caller; NULL cancels) as the completion event of its own dispatch: the event
+ * is complete when that kernel has finished, exactly as if it had been recorded on the stream right behind the
+ * kernel, but no packet of its own is put between two kernels of the stream (a recorded event holds the next kernel
+ * up by a few microseconds).  One-shot: the request is consumed by that launch, which is then not timed by the
+ * profiling hook.  A second stream can wait for the event (hipStreamWaitEvent after the call that launched the
+ * kernel has returned) to start work beside a chosen kernel of this stream.  Launches recorded into a HIP graph
+ * must not carry one.  Returns VARDROP_EINVAL for an unknown id. */
+int vardrop_signal_after(vardrop_ctx* ctx, int kernel_id, void* event);
 /* Static name of a kernel id ("hash", "gemm_qkv", ...), or NULL when out of range. */
 const char* vardrop_kernel_name(int kernel_id);
 

@@ -7,5 +7,5 @@ from .binding import (  # noqa: F401
     vardrop_hash, vardrop_kernel_name,
     vardrop_profile_read, vardrop_profile_select, vardrop_profile_stride, vardrop_sample, vardrop_sample_nearest, vardrop_scatter,
     vardrop_attn_bwd_dev, vardrop_gather_attn_fwd_dev, vardrop_gather_dev, vardrop_sample_dev, vardrop_scatter_dev,
-    vardrop_sample_nearest_noalloc, vardrop_attn_fwd_dev, vardrop_embed_fwd_dev, vardrop_embed_bwd_dev, vardrop_profile_read_all, K_ALL,
+    vardrop_sample_nearest_noalloc, vardrop_attn_fwd_dev, vardrop_embed_fwd_dev, vardrop_embed_bwd_dev, vardrop_profile_read_all, K_ALL, vardrop_signal_after,
 )

@@ -31,6 +31,7 @@ _SIGNATURES = {
     "vardrop_profile_select": (_c_int, [_ptr, _c_int]),
     "vardrop_profile_read": (_c_int, [_ptr, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(_c_int)]),
     "vardrop_profile_stride": (_c_int, [_ptr, _c_int]),
+    "vardrop_signal_after": (_c_int, [_ptr, _c_int, _ptr]),
     "vardrop_profile_read_all": (_c_int, [_ptr, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(_c_int)]),
     "vardrop_kernel_name": (ctypes.c_char_p, [_c_int]),
     "vardrop_hash_workspace_bytes": (_c_size, [_c_int] * 6),
@@ -178,6 +179,12 @@ def vardrop_profile_select(ctx, kid):
 def vardrop_profile_stride(ctx, stride):
     """Bracket only every `stride`-th launch of the selected kernel (takes effect at the next select)."""
     ctx.check(ctx._lib.vardrop_profile_stride(ctx.handle, stride), "vardrop_profile_stride")
+
+
+def vardrop_signal_after(ctx, kid, event):
+    """The next launch of kernel `kid` carries `event` (a raw hipEvent_t handle, e.g. torch.cuda.Event.cuda_event of
+    an event that has been recorded once; None cancels) as the completion event of its own dispatch."""
+    ctx.check(ctx._lib.vardrop_signal_after(ctx.handle, kid, ctypes.c_void_p(event) if event else None), "vardrop_signal_after")
 
 
 def vardrop_profile_read(ctx):

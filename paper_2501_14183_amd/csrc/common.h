@@ -18,6 +18,8 @@ struct vardrop_ctx {
   hipEvent_t* prof_ev;   // 2 * kProfPairs events, created on first use
   short* prof_kids;      // kernel id of every recorded pair
   hipEvent_t prof_e0, prof_e1;   // the pair the next launch is to be given (null: launch untimed)
+  int signal_kid;                // vardrop_signal_after: the next launch of this kernel id (-1: none) ...
+  hipEvent_t signal_event;       // ... carries this event as the completion event of its own dispatch
   void* twiddle;         // device: k-DFH cosine / sine table in matrix-fragment order (kTwiddleBytes)
   int twiddle_L;         // window length the table currently holds (0: none),
   int twiddle_fmin;      //   its first candidate bin
@@ -50,7 +52,14 @@ static const int kProfAll = -2;
 struct VdTimer {
   vardrop_ctx* ctx;
   bool active;
-  VdTimer(vardrop_ctx* c, int kid, hipStream_t) : ctx(c), active(false) {
+  bool signal;
+  VdTimer(vardrop_ctx* c, int kid, hipStream_t) : ctx(c), active(false), signal(false) {
+    if (c->signal_kid == kid && c->signal_event) {     // (a launch that signals is not timed)
+      signal = true;
+      c->prof_e0 = nullptr;
+      c->prof_e1 = c->signal_event;
+      return;
+    }
     if ((c->prof_kid == kid || c->prof_kid == kProfAll) && c->prof_ev && c->prof_n < kProfPairs &&
         (c->prof_seen++ % c->prof_stride) == 0) {
       active = true;
@@ -64,11 +73,16 @@ struct VdTimer {
       ++ctx->prof_n;
       ctx->prof_e0 = ctx->prof_e1 = nullptr;
     }
+    if (signal) {
+      ctx->prof_e1 = nullptr;
+      ctx->signal_kid = -1;
+      ctx->signal_event = nullptr;
+    }
   }
 };
 #define VD_KERNEL(ctx, kernel, grid, block, lds, s, ...)                                                        \
   do {                                                                                                          \
-    if ((ctx)->prof_e0) hipExtLaunchKernelGGL(kernel, grid, block, lds, s, (ctx)->prof_e0, (ctx)->prof_e1, 0, __VA_ARGS__); \
+    if ((ctx)->prof_e1) hipExtLaunchKernelGGL(kernel, grid, block, lds, s, (ctx)->prof_e0, (ctx)->prof_e1, 0, __VA_ARGS__); \
     else hipLaunchKernelGGL(kernel, grid, block, lds, s, __VA_ARGS__);                                          \
   } while (0)
 

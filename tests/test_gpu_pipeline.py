@@ -196,3 +196,42 @@ def test_pipelined_steps_in_the_benchmark_configuration(vd, ctx):
         got = dict(zip(("dxs", "dWq", "dWk", "dWv", "dWo"), grads), y=y)
         errs = {k: rel_err(v, want[k]) for k, v in got.items()}
         assert all(e <= TOL[w.dtype] for e in errs.values()), (i, errs)
+
+
+def test_completion_signal_rides_on_the_kernel_and_is_one_shot(vd, ctx):
+    """vardrop_signal_after: the event completes with the named kernel's launch, a second stream that waits for it
+    sees the kernel's output, the request is consumed by one launch, and an unknown id is refused."""
+    torch.manual_seed(3)
+    B, N, d, n = 4, 640, 512, 200
+    tok = torch.randn(B, N, d, device="cuda").to(torch.bfloat16)
+    sel = torch.sort(torch.randperm(N, device="cuda")[:n]).values.to(torch.int32)
+    kid = {vd.vardrop_kernel_name(k): k for k in range(64) if vd.vardrop_kernel_name(k)}
+    main, side = torch.cuda.Stream(), torch.cuda.Stream()
+    ev = torch.cuda.Event()
+    ev.record(main)                                   # creates the event; its handle is what the library is given
+    main.synchronize()
+    out = torch.zeros(B, n, d, dtype=torch.bfloat16, device="cuda")
+    copy = torch.zeros_like(out)
+    torch.cuda.synchronize()
+    for _ in range(3):
+        out.zero_()
+        copy.zero_()
+        torch.cuda.synchronize()
+        vd.vardrop_signal_after(ctx, kid["gather"], ev.cuda_event)
+        vd.vardrop_gather(ctx, tok, sel, n, out=out, stream=main.cuda_stream)
+        side.wait_event(ev)
+        with torch.cuda.stream(side):
+            copy.copy_(out)
+        side.synchronize()
+        assert ev.query()
+        assert torch.equal(copy, tok[:, sel.long(), :])
+    # consumed: the next launch carries nothing and can be timed as usual
+    vd.vardrop_profile_select(ctx, kid["gather"])
+    vd.vardrop_gather(ctx, tok, sel, n, out=out, stream=main.cuda_stream)
+    main.synchronize()
+    ms, launches = vd.vardrop_profile_read(ctx)
+    vd.vardrop_profile_select(ctx, -1)
+    assert launches == 1 and ms > 0
+    with pytest.raises(vd.VarDropError):
+        vd.vardrop_signal_after(ctx, 1000, ev.cuda_event)
+    vd.vardrop_signal_after(ctx, kid["gather"], None)      # cancelling is allowed
