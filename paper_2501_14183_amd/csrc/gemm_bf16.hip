@@ -412,6 +412,8 @@ constexpr int gemm_async_lds() {
   constexpr int ring = NS * (BM + 128) * BK * 2, out = BM * (128 * (SPLIT ? 4 : 2) + 16);
   return ring > out ? ring : out;
 }
+template <bool SPLIT, int BM, int BK, int NS>
+constexpr int gemm_async_lds_v = gemm_async_lds<SPLIT, BM, BK, NS>();
 // The product's dimensions, with a device-side token count (GemmBf16::n_dev) resolved; false: nothing to do.
 __device__ __forceinline__ bool gemm_resolve(const GemmBf16& g, GemmDims& dm) {
   dm.M = g.M; dm.K = g.K; dm.splitk = g.splitk; dm.kchunk = g.kchunk; dm.rs_n = g.rs_n;
@@ -447,31 +449,37 @@ __global__ __launch_bounds__(kGemmThreads, 2) void gemm_async_kernel(GemmBf16 g,
 // gradients (gw: mn-contiguous operands, K slices, fp32 partial products) depend on the same dQ, dK,
 // dV and on nothing of each other, so they share one launch: workgroups [0, nx) take tiles of gx,
 // the rest tiles of gw.  The longer-running input-gradient tiles are dispatched first.
-// 64-row tiles run three 64-k copy stages deep (72 KB of LDS, two workgroups per compute unit), 128-row tiles four
-// 32-k stages (64 KB)
-template <int BMX> constexpr int pair_stages() { return BMX == 64 ? 3 : 4; }
-template <int BMX> constexpr int pair_bk() { return BMX == 64 ? 64 : 32; }
-template <int BMX>
+// Tile shapes of the two kinds of workgroup: rows, k per copy stage, stages (BN = 128 always).
+template <int BMX_, int BKX_, int NSX_, int BMW_, int BKW_, int NSW_>
+struct PairCfg {
+  static constexpr int BMX = BMX_, BKX = BKX_, NSX = NSX_, BMW = BMW_, BKW = BKW_, NSW = NSW_;
+  static constexpr int ldsx = gemm_async_lds_v<false, BMX_, BKX_, NSX_>, ldsw = gemm_async_lds_v<true, BMW_, BKW_, NSW_>;
+  static constexpr int lds = ldsx > ldsw ? ldsx : ldsw;
+};
+// few tokens: 64-row tiles three 64-k stages deep for both (72 KB of LDS, two workgroups per compute unit);
+// many tokens: 128-row tiles on four 32-k stages (64 KB)
+typedef PairCfg<64, 64, 3, 64, 64, 3> PairSmall;
+typedef PairCfg<128, 32, 4, 128, 32, 4> PairLarge;
+template <typename CFG>
 __global__ __launch_bounds__(kGemmThreads, 2) void gemm_bwd_pair_kernel(GemmBf16 gx, GemmBf16 gw, int nzw) {
   // Each die takes a contiguous range of the input-gradient tiles (n fastest: a range shares its rows
   // of dQ, dK, dV) and a contiguous range of the weight-gradient tiles (n, then m, then K slice, then
   // matrix: a range shares its K slice of both operands); its input-gradient tiles come first.
   GemmDims dx, dw;
   if (!gemm_resolve(gx, dx) || !gemm_resolve(gw, dw)) return;
-  constexpr int BMW = BMX;      // rows of a weight-gradient tile
+  constexpr int BMX = CFG::BMX, BMW = CFG::BMW;
   const int gxn = (gx.N + 127) >> 7, gwn = (gw.N + 127) >> 7, gwm = (dw.M + BMW - 1) / BMW;
   const int nx = gxn * ((dx.M + BMX - 1) / BMX), nw = gwn * gwm * nzw * dw.splitk;
   if ((int)blockIdx.x >= nx + nw) return;
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
   const int cntx = (nx >> 3) + (xcd < (nx & 7) ? 1 : 0);
   const int startx = xcd_range_start(xcd, nx);
-  constexpr int NS = pair_stages<BMX>();
   if (slot < cntx) {
     const int t = startx + slot;
-    gemm_async_tile<true, true, false, BMX, pair_bk<BMX>(), NS>(gx, dx, t % gxn, t / gxn, 0);
+    gemm_async_tile<true, true, false, BMX, CFG::BKX, CFG::NSX>(gx, dx, t % gxn, t / gxn, 0);
   } else {
     const int t = xcd_range_start(xcd, nx + nw) - startx + (slot - cntx);
-    gemm_async_tile<false, false, true, BMW, pair_bk<BMX>(), NS>(gw, dw, t % gwn, (t / gwn) % gwm, t / (gwn * gwm));
+    gemm_async_tile<false, false, true, BMW, CFG::BKW, CFG::NSW>(gw, dw, t % gwn, (t / gwn) % gwm, t / (gwn * gwm));
   }
 }
 
@@ -500,22 +508,20 @@ int launch_gemm_async_cfg(vardrop_ctx* ctx, int kid, const GemmBf16& g, int nz, 
   return VARDROP_OK;
 }
 // one launch for the input gradient gx and the sliced weight gradients gw (nzw matrices)
-template <int BMX>
+template <typename CFG>
 int launch_gemm_bwd_pair_cfg(vardrop_ctx* ctx, const GemmBf16& gx, const GemmBf16& gw, int nzw, hipStream_t s) {
-  constexpr int NS = pair_stages<BMX>();
-  constexpr int ldsx = gemm_async_lds<false, BMX, pair_bk<BMX>(), NS>(), ldsw = gemm_async_lds<true, BMX, pair_bk<BMX>(), NS>();
-  constexpr int lds = ldsx > ldsw ? ldsx : ldsw;
+  constexpr int lds = CFG::lds;
   static int configured_device = -1;
   if (configured_device != ctx->device) {
-    VD_HIP(ctx, hipFuncSetAttribute((const void*)gemm_bwd_pair_kernel<BMX>, hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+    VD_HIP(ctx, hipFuncSetAttribute((const void*)gemm_bwd_pair_kernel<CFG>, hipFuncAttributeMaxDynamicSharedMemorySize, lds));
     configured_device = ctx->device;
   }
-  const int gxn = vd_ceil_div(gx.N, 128), gxm = vd_ceil_div(gx.M, BMX);
-  const int gwn = vd_ceil_div(gw.N, 128), gwm = vd_ceil_div(gw.M, BMX);
+  const int gxn = vd_ceil_div(gx.N, 128), gxm = vd_ceil_div(gx.M, CFG::BMX);
+  const int gwn = vd_ceil_div(gw.N, 128), gwm = vd_ceil_div(gw.M, CFG::BMW);
   const int nx = gxn * gxm, nw = gwn * gwm * nzw * gw.splitk;
   {
     VdTimer timer(ctx, VARDROP_K_GEMM_DW_DXS, s);
-    VD_KERNEL(ctx, gemm_bwd_pair_kernel<BMX>, dim3(nx + nw), dim3(kGemmThreads), lds, s, gx, gw, nzw);
+    VD_KERNEL(ctx, gemm_bwd_pair_kernel<CFG>, dim3(nx + nw), dim3(kGemmThreads), lds, s, gx, gw, nzw);
   }
   VD_LAUNCH_CHECK(ctx);
   return VARDROP_OK;
@@ -526,8 +532,8 @@ int launch_gemm_bwd_pair(vardrop_ctx* ctx, const GemmBf16& gx, const GemmBf16& g
       (long long)gw.K * gw.lda >= (1ll << 31) || (long long)gw.K * gw.ldb >= (1ll << 31))
     return VARDROP_EUNSUPPORTED;
   const long long t128 = (long long)vd_ceil_div(gx.N, 128) * vd_ceil_div(gx.M, 128);
-  if (t128 >= 512) return launch_gemm_bwd_pair_cfg<128>(ctx, gx, gw, nzw, s);
-  return launch_gemm_bwd_pair_cfg<64>(ctx, gx, gw, nzw, s);
+  if (t128 >= 512) return launch_gemm_bwd_pair_cfg<PairLarge>(ctx, gx, gw, nzw, s);
+  return launch_gemm_bwd_pair_cfg<PairSmall>(ctx, gx, gw, nzw, s);
 }
 
 template <bool BKC>
