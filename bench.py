@@ -106,11 +106,11 @@ def parse():
                          "(vardrop_embed_fwd / vardrop_embed_bwd; with --dense for all variates), instead of being "
                          "gathered from a pre-embedded batch")
     ap.add_argument("--launch", choices=("auto", "eager", "burst", "graph"), default="auto",
-                    help="eager: every call of a step issued from the host, the selection kernels placed beside chosen "
-                         "attention kernels; burst: the same calls with the selections in bursts of four on the second "
-                         "stream (less work for the host: better when a step is shorter than the host's time to issue "
-                         "it); auto (default): whichever of the two is faster in a short untimed trial; graph: one "
-                         "recorded HIP graph per step")
+                    help="eager: every call of a step issued from the host, the selection kernels placed behind a chosen "
+                         "attention kernel (the better of two placements in a short untimed trial); burst: the same "
+                         "calls with the selections in bursts of four on the second stream (less work for the host: "
+                         "better when a step is shorter than the host's time to issue it); auto (default): the fastest "
+                         "of all three in the trial; graph: one recorded HIP graph per step")
     ap.add_argument("--no-paper-rule", action="store_true",
                     help="skip the second figure at the paper's own sampling rule (Eq. 1 with Table 8's k and gs)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -304,16 +304,16 @@ class Pipeline:
     The selection of a batch (k-DFH, grouping, sampling) depends on its windows only, so it runs on a second
     stream beside the attention of earlier batches.  Nothing of it crosses to the host: the attention kernels read
     N' on the device.
-      eager: the selection of step g + LEAD is placed beside chosen kernels of step g: it starts when the attention
-             backward kernel of step g has finished, so that k-DFH and the one-workgroup sampling kernel run beside
-             the weight- and input-gradient kernel and the slice sum (which leave compute units and LDS free) and
-             are done when the next step's forward starts.  The two single-launch attention kernels need every
-             compute unit at once, and a selection kernel that holds one of them makes such a kernel wait a whole
-             round.  Measured at the Traffic shape: 79.1 us per step, against 80.7 with the k-DFH behind the forward
-             kernel instead, 84 with both behind the output projection, and 83.7 for unplaced bursts.  The placement
-             uses a completion event that rides on the kernel's own dispatch (vardrop_signal_after), so the
-             attention stream carries no event packets; it waits for the selection stream once per BURST steps.  A call of `count` steps issues
-             exactly `count` selections; the first LEAD of them run ahead of the call's first step.
+      eager: the selection of step g + LEAD is placed beside chosen kernels of step g: it starts when a named
+             attention kernel of step g has finished, either the forward kernel (the selection then runs beside
+             the output projection and what follows) or the attention backward kernel (beside the gradient GEMM).
+             The two single-launch attention kernels need every compute unit at once, and a selection kernel
+             that holds one of them makes such a kernel wait a whole round; the GEMMs between them leave compute
+             units and LDS free.  Which placement is better depends on the shape; a short trial decides.  The
+             placement uses a completion event that rides on the kernel's own dispatch (vardrop_signal_after), so
+             the attention stream carries no event packets; it waits for the selection stream once per BURST
+             steps.  A call of `count` steps issues exactly `count` selections; the first LEAD of them run ahead
+             of the call's first step.
       burst: selections are issued in bursts of BURST steps into a ring of RING buffer sets; the attention
              stream waits for one event per burst (and the selection stream for one per burst before it reuses
              ring sets).  The first burst of a call holds one step.
@@ -373,6 +373,7 @@ class Pipeline:
         self.gate = None                           # (kernel id whose end starts the hash, ... the sampling) for eager mode
         self.gate_events = None
         self.placed = None
+        self.trials_ms = None
 
     def set_gate(self, after):
         """Kernel id (of this step's own launches) behind which a later step's selection is placed."""
@@ -522,42 +523,55 @@ class Pipeline:
         return sum(ns) / len(ns), sum(gs) / len(gs)
 
 
-def place_selection(pipe):
-    """eager mode: finds the attention kernels of this pipeline's steps (two untimed steps with every launch timed)
-    and places the selection behind the last attention backward kernel."""
+def placements(pipe):
+    """eager mode: the attention kernels of this pipeline's steps (two untimed steps with every launch timed) behind
+    which a later step's selection can be placed: the forward attention kernel (the selection then runs beside the
+    output projection and what follows) and the last attention backward kernel (beside the gradient GEMMs)."""
     import torch
     vd, ctx = pipe.vd, pipe.ctx
     if pipe.dense:
-        return
+        return []
     pipe.step_dev.zero_()
     vd.vardrop_profile_select(ctx, vd.K_ALL)
     pipe.run(0, 2, "burst")
     torch.cuda.synchronize()
     ran = set(vd.vardrop_profile_read_all(ctx))
     vd.vardrop_profile_select(ctx, -1)
-    kid = {vd.vardrop_kernel_name(k): k for k in range(64) if vd.vardrop_kernel_name(k)}
+    fwd = next((name for name in ("qkv_sdpa_fwd", "sdpa_fwd") if name in ran), None)
     bwd = next((name for name in ("sdpa_bwd", "sdpa_bwd_dqkv", "sdpa_bwd_dkv") if name in ran), None)
-    if bwd:
-        pipe.set_gate(kid[bwd])
-        pipe.placed = {"selection_starts_after": bwd}
+    return [name for name in (fwd, bwd) if name]
+
+
+def place(pipe, name):
+    vd = pipe.vd
+    kid = {vd.vardrop_kernel_name(k): k for k in range(64) if vd.vardrop_kernel_name(k)}
+    pipe.set_gate(kid[name])
+    pipe.placed = {"selection_starts_after": name}
 
 
 def choose_launch(pipe, args):
-    """--launch auto: places the selection, then tries eager and burst for a few untimed steps each."""
+    """--launch auto: tries the burst pipeline and the eager pipeline with either placement of the selection for a
+    few untimed steps each and keeps the fastest; --launch eager does the same among the placements only."""
     import copy
-    if args.launch != "auto":
-        if args.launch == "eager":
-            place_selection(pipe)
-        return args.launch
-    if pipe.dense:
-        return "burst"
-    place_selection(pipe)
-    if pipe.gate is None:
+    if args.launch in ("burst", "graph") or pipe.dense:
+        return "burst" if pipe.dense else args.launch
+    names = placements(pipe)
+    if not names:
         return "burst"
     trial = copy.copy(args)
     trial.steps, trial.warmup = 80, 20
-    best = min(("eager", "burst"), key=lambda mode: min(timed_steps(pipe, trial, mode)[0] for _ in range(2)))
-    return best
+    results = {}
+    for name in names:
+        place(pipe, name)
+        results[name] = min(timed_steps(pipe, trial, "eager")[0] for _ in range(2))
+    if args.launch == "auto":
+        results["burst"] = min(timed_steps(pipe, trial, "burst")[0] for _ in range(2))
+    best = min(results, key=results.get)
+    pipe.trials_ms = results
+    if best == "burst":
+        return "burst"
+    place(pipe, best)
+    return "eager"
 
 
 def timed_steps(pipe, args, launch):
@@ -764,7 +778,8 @@ def main():
                                (w.name, w.B, w.N, w.L, w.k, ("min(|G|,%d)" % args.gs) if args.gs else "%d/%d" % w.ratio, w.d, w.H),
                    "k": w.k, "gs": args.gs if args.gs else None,
                    "kept_tokens_mean": n_mean, "groups_mean": g_mean, "token_bound": pipe.n_max,
-                   "batches": args.batches, "launch": launch, "selection_placement": pipe.placed if launch == "eager" else None},
+                   "batches": args.batches, "launch": launch, "selection_placement": pipe.placed if launch == "eager" else None,
+                   "launch_trials_ms_per_step": pipe.trials_ms},
         "roofline": roof, "roofline_all": roof_all,
     }
     # ---- the paper's own rule for this dataset shape (Table 8: Traffic k = 4, gs = 10; Electricity k = 3, gs = 10)

@@ -9,6 +9,7 @@
 //   * short selections (n <= 128, what variate dropping leaves) have kernels of their own that keep a
 //     whole head in LDS: projection + attention forward, and dO + the whole attention backward;
 //   * the projections and their gradients are the GEMMs of gemm_bf16.hip.
+#include <algorithm>
 #include "bf16_mfma.h"
 #include "gemm_bf16.h"
 
@@ -1213,9 +1214,11 @@ int launch_sdpa_bwd(vardrop_ctx* ctx, const SdpaArgs& a, hipStream_t s) {
 }  // namespace
 
 // largest slice count the rule above gives for any token count
-static int splitk_bound(int d) {
-  const int s = vd_ceil_div(512, vd_ceil_div(d, 64) * vd_ceil_div(d, 128) * 4);
-  return s > 8 ? 8 : s;
+// largest slice count of any token count up to n_max (the rule is not monotone)
+static int splitk_bound(int d, int B, int n_max) {
+  int s = 1;
+  for (int n = 1; n <= n_max; ++n) s = std::max(s, vd_attn_bf16_splitk(d, (long long)B * n, nullptr));
+  return s;
 }
 size_t vd_attn_bf16_partial_offset(int B, int n, int d, int H) {
   const size_t M = (size_t)B * n;
@@ -1376,16 +1379,11 @@ int vd_attn_bwd_bf16(vardrop_ctx* ctx, const void* dy, const void* xs, int B, in
       // the kernels derive the slices from the count; the grid is sized for the largest number of them
       gx.count_rows(dn.dev, nullptr, n, B);
       gw.count_k(dn.dev, n, B);
-      gw.splitk = splitk_bound(d);
-      if ((rc = vd_gemm_bf16_bwd_pair(ctx, gx, gw, 4, s))) return rc;
-      if ((rc = vd_gemm_bf16_sum_slices(ctx, part, dW, (long long)d * d, gw.splitk, s, 4, &gw))) return rc;
-    } else if (gw.splitk > 1) {
-      if ((rc = vd_gemm_bf16_bwd_pair(ctx, gx, gw, 4, s))) return rc;
-      if ((rc = vd_gemm_bf16_sum_slices(ctx, part, dW, (long long)d * d, gw.splitk, s))) return rc;
-    } else {   // few tokens: one slice, written directly
-      if ((rc = vd_gemm_bf16_wgrad(ctx, VARDROP_K_GEMM_DW, gw, 4, s))) return rc;
-      if ((rc = vd_gemm_bf16(ctx, VARDROP_K_GEMM_DXS, gx, 1, true, s))) return rc;
+      gw.splitk = splitk_bound(d, B, n);
     }
+    if ((rc = vd_gemm_bf16_bwd_pair(ctx, gx, gw, 4, s))) return rc;
+    // a single slice is written as the result itself
+    if (gw.splitk > 1 && (rc = vd_gemm_bf16_sum_slices(ctx, part, dW, (long long)d * d, gw.splitk, s, 4, dn.dev ? &gw : nullptr))) return rc;
   }
   if (db[0] || db[1] || db[2] || db[3]) {
     ColSumBf16 c = {};

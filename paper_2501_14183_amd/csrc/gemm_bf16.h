@@ -56,8 +56,6 @@ struct GemmBf16 {
 // C[z] = A[z] * op(B[z]) (+ bias) in bf16 for nz batch entries, or the sum over g.nseg segments into C[0].
 // A is k-contiguous [M][K]; B is k-contiguous [N][K] (b_k_contiguous) or n-contiguous [K][N].
 int vd_gemm_bf16(vardrop_ctx* ctx, int kid, const GemmBf16& g, int nz, bool b_k_contiguous, hipStream_t s);
-// C[z] = A[z]^T * B[z] in fp32 for nz matrices, both operands mn-contiguous ([K][M], [K][N]), one K slice.
-int vd_gemm_bf16_wgrad(vardrop_ctx* ctx, int kid, const GemmBf16& g, int nz, hipStream_t s);
 // One launch for the input gradient gx (k-contiguous operands, up to three segments) and the nzw weight
 // gradients gw (mn-contiguous operands, gw.splitk K slices, fp32 partial products in gw.part).
 int vd_gemm_bf16_bwd_pair(vardrop_ctx* ctx, const GemmBf16& gx, const GemmBf16& gw, int nzw, hipStream_t s);

@@ -96,6 +96,16 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(SplitkReduce a) {
 // lane owns one output row and four consecutive columns per register quad; the tile goes through
 // LDS once more so that global stores are whole 16-byte chunks of consecutive rows.
 // The dimensions a kernel works with: those of the argument block, or what a device-side token count makes of them.
+// waits until at most min(ahead, A) * LPS of this wavefront's copies are still in flight
+template <int A, int LPS>
+__device__ __forceinline__ void wait_ahead(int ahead) {
+  if constexpr (A <= 0) {
+    wait_vm<0>();
+  } else {
+    if (ahead >= A) wait_vm<A * LPS>();
+    else wait_ahead<A - 1, LPS>(ahead);
+  }
+}
 constexpr int kGemmThreads = 512;     // four computing wavefronts and four copy wavefronts
 struct GemmDims {
   int M, K, splitk, kchunk, rs_n;
@@ -239,9 +249,7 @@ __device__ __forceinline__ void gemm_async_tile(const GemmBf16& g, const GemmDim
         if (t < total) {
           // slice t has landed once at most `ahead` younger stages are still in flight
           const int ahead = min(total - 1 - t, NS - 2);
-          if (NS >= 4 && ahead >= 2) wait_vm<(NS >= 4 ? 2 * LPS : 0)>();
-          else if (NS >= 3 && ahead == 1) wait_vm<(NS >= 3 ? LPS : 0)>();
-          else wait_vm<0>();
+          wait_ahead<NS - 2, LPS>(ahead);
           __builtin_amdgcn_s_barrier();     // slice t is in; everyone is done with slice t-1, whose buffer is filled next
           if (t + NS - 1 < total) VD_ISSUE_STAGE((s + NS - 1) % NS)
         }
@@ -430,6 +438,13 @@ __device__ __forceinline__ bool gemm_resolve(const GemmBf16& g, GemmDims& dm) {
                               : vd_attn_bf16_splitk(g.M, (long long)dm.K, &kchunk);
     dm.kchunk = kchunk;
   }
+  // (no tokens: an input gradient has no rows to write; a weight gradient is all zeros, which its tiles write
+  // themselves: a product over no slices)
+  if (g.n_role != 0 && dm.K == 0) {
+    dm.splitk = 1;
+    dm.kchunk = 64;
+    return dm.M > 0;
+  }
   return dm.M > 0 && dm.K > 0;
 }
 // One-dimensional grid of at least nz * tiles workgroups (more when the launch was sized for the bound of a
@@ -456,9 +471,9 @@ struct PairCfg {
   static constexpr int ldsx = gemm_async_lds_v<false, BMX_, BKX_, NSX_>, ldsw = gemm_async_lds_v<true, BMW_, BKW_, NSW_>;
   static constexpr int lds = ldsx > ldsw ? ldsx : ldsw;
 };
-// few tokens: 64-row tiles three 64-k stages deep for both (72 KB of LDS, two workgroups per compute unit);
-// many tokens: 128-row tiles on four 32-k stages (64 KB)
-typedef PairCfg<64, 64, 3, 64, 64, 3> PairSmall;
+// few tokens: 128-row input-gradient tiles on two 64-k stages beside 64-row weight-gradient tiles three stages deep
+// (72 KB of LDS), one slice; many tokens: 128-row tiles on four 32-k stages for both (64 KB)
+typedef PairCfg<128, 64, 2, 64, 64, 3> PairSmall;
 typedef PairCfg<128, 32, 4, 128, 32, 4> PairLarge;
 template <typename CFG>
 __global__ __launch_bounds__(kGemmThreads, 2) void gemm_bwd_pair_kernel(GemmBf16 gx, GemmBf16 gw, int nzw) {
@@ -466,7 +481,9 @@ __global__ __launch_bounds__(kGemmThreads, 2) void gemm_bwd_pair_kernel(GemmBf16
   // of dQ, dK, dV) and a contiguous range of the weight-gradient tiles (n, then m, then K slice, then
   // matrix: a range shares its K slice of both operands); its input-gradient tiles come first.
   GemmDims dx, dw;
-  if (!gemm_resolve(gx, dx) || !gemm_resolve(gw, dw)) return;
+  const bool has_x = gemm_resolve(gx, dx);
+  if (!gemm_resolve(gw, dw)) return;          // (an invalid count; with no tokens only the weight-gradient tiles run)
+  if (!has_x) dx.M = 0;
   constexpr int BMX = CFG::BMX, BMW = CFG::BMW;
   const int gxn = (gx.N + 127) >> 7, gwn = (gw.N + 127) >> 7, gwm = (dw.M + BMW - 1) / BMW;
   const int nx = gxn * ((dx.M + BMX - 1) / BMX), nw = gwn * gwm * nzw * dw.splitk;
@@ -531,8 +548,9 @@ int launch_gemm_bwd_pair(vardrop_ctx* ctx, const GemmBf16& gx, const GemmBf16& g
       gw.M % 8 != 0 || gw.N % 8 != 0 || gw.kchunk % 64 != 0 || gw.splitk < 1 ||
       (long long)gw.K * gw.lda >= (1ll << 31) || (long long)gw.K * gw.ldb >= (1ll << 31))
     return VARDROP_EUNSUPPORTED;
-  const long long t128 = (long long)vd_ceil_div(gx.N, 128) * vd_ceil_div(gx.M, 128);
-  if (t128 >= 512) return launch_gemm_bwd_pair_cfg<PairLarge>(ctx, gx, gw, nzw, s);
+  // (with a device-side count gx.M is the bound: a count in the few-token range under a bound in the other one
+  // still runs correctly on the many-token tiles, with the single slice its own rule gives it)
+  if (vd_attn_bf16_many_tokens(gx.N, gx.M)) return launch_gemm_bwd_pair_cfg<PairLarge>(ctx, gx, gw, nzw, s);
   return launch_gemm_bwd_pair_cfg<PairSmall>(ctx, gx, gw, nzw, s);
 }
 
@@ -554,16 +572,6 @@ int launch_gemm_async(vardrop_ctx* ctx, int kid, const GemmBf16& g, int nz, hipS
 
 int vd_gemm_bf16(vardrop_ctx* ctx, int kid, const GemmBf16& g, int nz, bool b_k_contiguous, hipStream_t s) {
   return b_k_contiguous ? launch_gemm_async<true>(ctx, kid, g, nz, s) : launch_gemm_async<false>(ctx, kid, g, nz, s);
-}
-
-int vd_gemm_bf16_wgrad(vardrop_ctx* ctx, int kid, const GemmBf16& g, int nz, hipStream_t s) {
-  if (g.M == 0 || g.N == 0) return VARDROP_OK;
-  if (g.M % 8 != 0 || g.N % 8 != 0 || (long long)g.K * g.lda >= (1ll << 31) || (long long)g.K * g.ldb >= (1ll << 31))
-    return VARDROP_EUNSUPPORTED;
-  GemmBf16 one = g;
-  one.splitk = 1;
-  one.kchunk = (int)vd_align_up((size_t)g.K, 64);
-  return launch_gemm_async_cfg<false, false, true, 64, 2>(ctx, kid, one, nz, s);
 }
 
 int vd_gemm_bf16_bwd_pair(vardrop_ctx* ctx, const GemmBf16& gx, const GemmBf16& gw, int nzw, hipStream_t s) {
