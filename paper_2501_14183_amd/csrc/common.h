@@ -104,23 +104,27 @@ static inline bool vd_aligned(const void* p, size_t a) { return ((uintptr_t)p % 
 __host__ __device__ static inline int vd_ceil_div(int a, int b) { return (a + b - 1) / b; }
 
 // Number of K slices of the weight-gradient GEMMs (K = M = B*n rows).  They share a launch with the input gradient.
-// Few tokens (fewer than 512 input-gradient tiles of 128 rows): one slice, the 64 x 128 weight-gradient tiles walk
-// over all of K beside 128-row input-gradient tiles, one workgroup per compute unit, and no partial products
-// exist (a second slice makes that launch 3.5 us shorter at the Traffic shape and costs a 5 us launch that sums
-// the slices).  Many tokens: enough slices of 128 x 128 tiles for two workgroups per compute unit beside the
-// input gradient, at least 256 rows each, a multiple of the 64-row stage.
+// Few tokens (fewer than 512 input-gradient tiles of 128 rows): the 64 x 128 weight-gradient tiles walk over K
+// beside 128-row input-gradient tiles, one workgroup per compute unit, in slices of at most 4608 rows: one slice
+// up to there, so that no partial products exist (a second slice makes that launch 3.5 us shorter at the Traffic
+// shape and costs a 5 us launch that sums the slices).  Many tokens: enough slices of 128 x 128 tiles for two
+// workgroups per compute unit (counted as twice as many 64-row tiles), at least 256 rows each.  Slices are a
+// multiple of the 64-row stage.
 // (Host and device: with a device-side token count the kernels evaluate it themselves.)
 __host__ __device__ static inline bool vd_attn_bf16_many_tokens(int d, long long M) {
   return (long long)vd_ceil_div((int)M, 128) * vd_ceil_div(d, 128) >= 512;
 }
 __host__ __device__ static inline int vd_attn_bf16_splitk(int d, long long M, int* kchunk) {
-  int s = 1;
+  int s;
   if (vd_attn_bf16_many_tokens(d, M)) {
-    const int tiles = vd_ceil_div(d, 128) * vd_ceil_div(d, 128) * 4;
+    const int tiles = vd_ceil_div(d, 64) * vd_ceil_div(d, 128) * 4;
     s = vd_ceil_div(512, tiles);
     if (s > 8) s = 8;
     while (s > 1 && M / s < 256) --s;
+  } else {
+    s = vd_ceil_div((int)M, 4608);
   }
+  if (s < 1) s = 1;
   int chunk = (int)vd_align_up((size_t)vd_ceil_div((int)M, s), 64);
   if (chunk < 64) chunk = 64;
   s = M > 0 ? vd_ceil_div((int)M, chunk) : 1;
