@@ -752,6 +752,10 @@ def main():
     roof["traffic"] = recorded_traffic(w.name, dominant)
     roof["avg_launch_us"] = roof_all[dominant]["avg_launch_us"]
     roof["launches"] = roof_all[dominant]["launches"]
+    if dominant == "gemm_dw_dxs" and "reduce_dw" not in roof_all:
+        roof["note"] = ("one launch for the input gradient and the four weight gradients, each over all of K: no partial "
+                        "products and no separate launch that sums K slices (two slices make this launch 3.5 us "
+                        "shorter and the step 3 us longer)")
     roof["timing"] = ("events tied to each dispatch of the kernel (hipExtLaunchKernelGGL) over %d steps issued call by call "
                       "right after the timed region" % PROF_STEPS)
     # whole attention (every matrix-core kernel of a step): algorithmic flops of forward + backward over their summed time
