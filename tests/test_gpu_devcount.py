@@ -333,3 +333,62 @@ def test_embedding_of_the_kept_windows_with_the_count_on_the_device(vd, ctx):
     vd.vardrop_embed_fwd_dev(ctx, x_t, sel, n_dev, n_max, We_t, be_t, bufs.xs, esaved, status=bufs.status)
     torch.cuda.synchronize()
     assert int(bufs.status[0]) == 1
+
+
+def test_the_benchmark_pipeline_computes_the_same_steps_in_every_launch_mode(vd, ctx):
+    """bench.py's Pipeline at the Traffic shape: the burst pipeline, the eager pipeline with the selection placed
+    behind either attention kernel (completion signals) and the recorded graph all draw selection g with Philox
+    step g and leave the same last step behind, bit for bit; that step is checked against the oracle."""
+    import argparse
+    import bench
+    from oracle import sampling as o_samp
+    w = wl.WORKLOADS["traffic"]
+    td = torch.bfloat16
+    dev = torch.device("cuda", 0)
+    xs_dev, tok_dev, tok_np = [], [], []
+    for i in range(2):
+        x_np, _ = wl.make_signals(w, seed=i)
+        t_np = wl.make_tokens(w, x_np, seed=i)
+        xs_dev.append(torch.from_numpy(x_np).to(dev))
+        tok_dev.append(torch.from_numpy(t_np).to(dev).to(td))
+        tok_np.append(t_np)
+    W_np = wl.make_weights(w, seed=0)
+    W_dev = [torch.from_numpy(m).to(dev).to(td) for m in W_np]
+    dy_np = wl.make_upstream(w, w.N, seed=0)
+    dy_full = torch.from_numpy(dy_np).to(dev).to(td).reshape(-1)
+    seed, K = 0x5EED, 9
+    pipe = bench.Pipeline(vd, ctx, w, xs_dev, tok_dev, W_dev, dy_full, seed)
+    args = argparse.Namespace(steps=K - 2, warmup=2)
+    gates = bench.placements(pipe)
+    assert len(gates) == 2
+    runs = [("burst", None)] + [("eager", g) for g in gates] + [("graph", None)]
+    first = None
+    for mode, gate in runs:
+        if gate:
+            bench.place(pipe, gate)
+        for t in (pipe.y_buf, pipe.dxs_buf, pipe.xs_buf, *pipe.dW_buf):
+            t.fill_(float("nan"))
+        bench.timed_steps(pipe, args, mode)                    # (checks the status word and the step counter itself)
+        torch.cuda.synchronize()
+        g = K - 1
+        r = g % (2 if mode == "graph" else pipe.RING)
+        n, G = pipe.ring[r][4].tolist()
+        sel = pipe.ring[r][3][:n].cpu().numpy()
+        hsh = pipe.ring[r][1].cpu().numpy().view(np.uint64)
+        _, want_sel, want_G = o_samp.stratified_sample(hsh, 0, w.ratio[0], w.ratio[1], seed, g)
+        assert (n, G) == (len(want_sel), want_G) and np.array_equal(sel, want_sel), (mode, gate)
+        cnt = w.B * n * w.d
+        got = dict(y=pipe.y_buf.reshape(-1)[:cnt].view(w.B, n, w.d).clone(), dxs=pipe.dxs_buf.reshape(-1)[:cnt].view(w.B, n, w.d).clone(),
+                   dWq=pipe.dW_buf[0].clone(), dWk=pipe.dW_buf[1].clone(), dWv=pipe.dW_buf[2].clone(), dWo=pipe.dW_buf[3].clone())
+        if first is None:
+            first = got
+            b = g % 2
+            tok_r = tok_dev[b].float().cpu().numpy().astype(np.float64)
+            W_r = [m.float().cpu().numpy().astype(np.float64) for m in W_dev]
+            dy_r = dy_full[:cnt].view(w.B, n, w.d).float().cpu().numpy().astype(np.float64)
+            want = oracle_attention(tok_r[:, want_sel, :], W_r, w.H, dy_r)
+            errs = {k: rel_err(v, want[k]) for k, v in got.items()}
+            assert all(e <= TOL["bf16"] for e in errs.values()), errs
+        else:
+            for k in got:
+                assert torch.equal(got[k], first[k]), (mode, gate, k)
