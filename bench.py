@@ -312,11 +312,12 @@ class Pipeline:
              units and LDS free.  Which placement is better depends on the shape; a short trial decides.  The
              placement uses a completion event that rides on the kernel's own dispatch (vardrop_signal_after), so
              the attention stream carries no event packets; it waits for the selection stream once per BURST
-             steps.  A call of `count` steps issues exactly `count` selections; the first LEAD of them run ahead
-             of the call's first step.
+             steps.  A call of `count` steps issues exactly `count` selections; one runs ahead of the call's
+             first step and the lead grows by up to two per step to LEAD, the attention stream waiting per step
+             until it has (a call of few steps is then not held up by a block of selections at its start).
       burst: selections are issued in bursts of BURST steps into a ring of RING buffer sets; the attention
              stream waits for one event per burst (and the selection stream for one per burst before it reuses
-             ring sets).  The first burst of a call holds one step.
+             ring sets).  The first bursts of a call hold 1, 1 and 2 steps.
       graph: one recorded HIP graph per step, the selection of the NEXT batch on a branch forked from and joined
              back into the attention stream (ring of two sets).
     """
@@ -475,27 +476,39 @@ class Pipeline:
             return
         end = first + count
         if launch == "eager" and self.gate is not None:
-            B4, LEAD = self.BURST, self.LEAD
-            drawn = lambda j: self.event(j)              # selections of steps first + 4 j .. first + 4 j + 3 are drawn
-            for g in range(first, min(end, first + LEAD)):
-                self.select(g % self.nb, g % self.RING, self.side)
-                if (g - first) % B4 == B4 - 1 or g == end - 1:
-                    drawn((g - first) // B4).record(self.side)
+            # One selection runs ahead of the call's first step; the lead then grows by one selection per step up to
+            # LEAD (two selections behind a step's gated kernel while it catches up).  The attention stream waits
+            # for every selection of the first RAMP steps on its own and afterwards once per BURST steps.
+            B4, LEAD, RAMP = self.BURST, self.LEAD, 2 * self.BURST
+            drawn = lambda g: self.event(g % self.RING)  # selection g is drawn (recorded on the selection stream)
+            issued = first
+
+            def draw(gate):
+                nonlocal issued
+                if gate is not None:
+                    self.side_wait(gate)
+                self.select(issued % self.nb, issued % self.RING, self.side)
+                drawn(issued).record(self.side)
+                issued += 1
+
+            draw(None)
             for g in range(first, end):
-                if (g - first) % B4 == 0:
-                    self.main.wait_event(drawn((g - first) // B4))
+                k = g - first
+                if k < RAMP:
+                    self.main.wait_event(drawn(g))
+                elif k % B4 == 0:
+                    self.main.wait_event(drawn(min(g + B4 - 1, end - 1)))
+                target = min(end, g + 1 + LEAD)
+                n_new = min(2, target - issued)
                 eb = self.gate_handles[g % self.RING]
-                t = g + LEAD
-                self.attend(g % self.nb, g % self.RING, self.main, gate=eb if t < end else None)
-                if t < end:
-                    self.side_wait(eb)
-                    self.select(t % self.nb, t % self.RING, self.side)
-                    if (t - first) % B4 == B4 - 1 or t == end - 1:
-                        drawn((t - first) // B4).record(self.side)
+                self.attend(g % self.nb, g % self.RING, self.main, gate=eb if n_new > 0 else None)
+                for i in range(n_new):
+                    draw(eb if i == 0 else None)
             return
         blocks, g = [], first
         while g < end:
-            size = 1 if g == first else self.BURST
+            # (the bursts grow 1, 1, 2, 4, 4, ...: a burst runs beside the block before it, which must not be shorter)
+            size = (1, 1, 2)[len(blocks)] if len(blocks) < 3 else self.BURST
             blocks.append(range(g, min(end, g + size)))
             g += size
         done_sel = lambda j: self.event(2 * j)          # burst j has been drawn (recorded on the selection stream)
@@ -559,7 +572,7 @@ def choose_launch(pipe, args):
     if not names:
         return "burst"
     trial = copy.copy(args)
-    trial.steps, trial.warmup = 80, 20
+    trial.steps, trial.warmup = max(20, min(80, args.steps)), 20     # (as long as the timed run when that is short)
     results = {}
     for name in names:
         place(pipe, name)
