@@ -106,8 +106,8 @@ def parse():
                          "(vardrop_embed_fwd / vardrop_embed_bwd; with --dense for all variates), instead of being "
                          "gathered from a pre-embedded batch")
     ap.add_argument("--launch", choices=("auto", "eager", "burst", "graph"), default="auto",
-                    help="eager: every call of a step issued from the host, the selection kernels placed behind a chosen "
-                         "attention kernel (the better of two placements in a short untimed trial); burst: the same "
+                    help="eager: every call of a step issued from the host, the k-DFH and the sampling each placed behind a "
+                         "chosen attention kernel or left free (the best placement in a short untimed trial); burst: the same "
                          "calls with the selections in bursts of four on the second stream (less work for the host: "
                          "better when a step is shorter than the host's time to issue it); auto (default): the fastest "
                          "of all three in the trial; graph: one recorded HIP graph per step")
@@ -304,24 +304,25 @@ class Pipeline:
     The selection of a batch (k-DFH, grouping, sampling) depends on its windows only, so it runs on a second
     stream beside the attention of earlier batches.  Nothing of it crosses to the host: the attention kernels read
     N' on the device.
-      eager: the selection of step g + LEAD is placed beside chosen kernels of step g: it starts when a named
-             attention kernel of step g has finished, either the forward kernel (the selection then runs beside
-             the output projection and what follows) or the attention backward kernel (beside the gradient GEMM).
-             The two single-launch attention kernels need every compute unit at once, and a selection kernel
-             that holds one of them makes such a kernel wait a whole round; the GEMMs between them leave compute
-             units and LDS free.  Which placement is better depends on the shape; a short trial decides.  The
-             placement uses a completion event that rides on the kernel's own dispatch (vardrop_signal_after), so
-             the attention stream carries no event packets; it waits for the selection stream once per BURST
-             steps.  A call of `count` steps issues exactly `count` selections; one runs ahead of the call's
-             first step and the lead grows by up to two per step to LEAD, the attention stream waiting per step
-             until it has (a call of few steps is then not held up by a block of selections at its start).
+      eager: the selection of step g + LEAD is issued with step g and can be placed beside chosen kernels of it: its
+             k-DFH and its sampling each start when a named attention kernel of step g has finished (the forward
+             kernel: beside the output projection and what follows; the attention backward kernel: beside the
+             gradient GEMM), or as soon as the selection stream reaches them.  The two single-launch attention
+             kernels need every compute unit at once, and a selection kernel that holds one of them makes such a
+             kernel wait a whole round; the GEMMs between them leave compute units and LDS free.  Which placement
+             is better depends on the shape; a short trial decides.  A placement uses a completion event that
+             rides on the kernel's own dispatch (vardrop_signal_after), so the attention stream carries no event
+             packets; it waits for the selection stream once per BURST steps.  A call of `count` steps issues
+             exactly `count` selections; one runs ahead of the call's first step and the lead grows by up to two
+             per step to LEAD, the attention stream waiting per step until it has (a call of few steps is then
+             not held up by a block of selections at its start).
       burst: selections are issued in bursts of BURST steps into a ring of RING buffer sets; the attention
              stream waits for one event per burst (and the selection stream for one per burst before it reuses
              ring sets).  The first bursts of a call hold 1, 1 and 2 steps.
       graph: one recorded HIP graph per step, the selection of the NEXT batch on a branch forked from and joined
              back into the attention stream (ring of two sets).
     """
-    BURST, RING, LEAD = 4, 12, 5
+    BURST, RING, LEAD = 4, 16, 5
 
     def __init__(self, vd, ctx, w, xs_dev, tok_dev, W_dev, dy_full, seed, gs_cap=0, dense=False, embed=None):
         import torch
@@ -371,17 +372,18 @@ class Pipeline:
             self.ews = torch.empty(max(lib.vardrop_embed_workspace_bytes(w.B, self.n_max, w.L, w.d, code), 256), dtype=torch.uint8, device=dev)
             self.dWe_buf = (torch.empty((w.L, w.d), dtype=torch.float32, device=dev), torch.empty(w.d, dtype=torch.float32, device=dev))
         self.graphs = None
-        self.gate = None                           # (kernel id whose end starts the hash, ... the sampling) for eager mode
-        self.gate_events = None
+        self.gates = None                          # eager mode: ("fwd" | "bwd" | None, the same for the sampling)
+        self.kid_fwd = self.kid_bwd = None         # kernel ids a completion signal can ride on
         self.placed = None
         self.trials_ms = None
 
-    def set_gate(self, after):
-        """Kernel id (of this step's own launches) behind which a later step's selection is placed."""
+    def set_gates(self, hash_after, sample_after):
+        """eager mode: the k-DFH and the sampling of a later step's selection start when this step's forward attention
+        kernel ("fwd") or its attention backward kernel ("bwd") has finished; None: when the selection stream gets there."""
         torch = self.torch
-        self.gate = after
+        self.gates = (hash_after, sample_after)
         self.gate_events = []
-        for _ in range(self.RING):
+        for _ in range(2 * self.RING):
             ev = torch.cuda.Event()
             ev.record(self.main)                   # creates the underlying event; its handle is reused from here on
             self.gate_events.append(ev)
@@ -392,23 +394,33 @@ class Pipeline:
         self.hip = ctypes.CDLL("libamdhip64.so")
         self.hip.hipStreamWaitEvent.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint]
         self.hip.hipStreamWaitEvent.restype = ctypes.c_int
-        self.gate_handles = [ev.cuda_event for ev in self.gate_events]
+        handles = [ev.cuda_event for ev in self.gate_events]
+        self.gate_handles = {"fwd": handles[:self.RING], "bwd": handles[self.RING:]}
 
     def side_wait(self, handle):
         if self.hip.hipStreamWaitEvent(self.side.cuda_stream, handle, 0) != 0:
             raise RuntimeError("hipStreamWaitEvent failed")
 
-    def select(self, b, r, stream):
-        """k-DFH + grouping + sampling of batch b into ring set r; the step counter advances on the device."""
+    def select(self, b, r, stream, hash_gate=None, sample_gate=None):
+        """k-DFH + grouping + sampling of batch b into ring set r; the step counter advances on the device.  A gate is
+        an event handle the stream waits for before that kernel."""
         vd, w = self.vd, self.w
         topk, hsh, gid, sel, counts = self.ring[r]
+        if hash_gate is not None:
+            self.side_wait(hash_gate)
         vd.vardrop_hash(self.ctx, self.xs_dev[b], w.k, f_max=-1, out=(topk, hsh), stream=stream.cuda_stream)
+        if sample_gate is not None:
+            self.side_wait(sample_gate)
         vd.vardrop_sample_dev(self.ctx, hsh, self.gs_cap, self.ratio[0], self.ratio[1], self.seed, self.step_dev, True,
                               (gid, sel, counts), stream=stream.cuda_stream)
 
-    def attend(self, b, r, stream, gate=None):
+    def attend(self, b, r, stream, sig_fwd=None, sig_bwd=None):
+        """Forward and backward pass of batch b on the selection in ring set r.  sig_fwd / sig_bwd: event handles that
+        the forward attention kernel / the attention backward kernel of this step complete (see set_gates)."""
         vd, w = self.vd, self.w
         sel, counts = self.ring[r][3], self.ring[r][4]
+        if sig_fwd is not None:
+            vd.vardrop_signal_after(self.ctx, self.kid_fwd, sig_fwd)
         if self.embed is not None:
             # tokens of the kept variates straight from the raw windows (no token tensor of all variates exists)
             vd.vardrop_embed_fwd_dev(self.ctx, self.xs_dev[b], sel, counts, self.n_max, self.embed[0], self.embed[1],
@@ -418,8 +430,8 @@ class Pipeline:
         else:
             vd.vardrop_gather_attn_fwd_dev(self.ctx, self.tok_dev[b], sel, counts, self.n_max, *self.W_dev, w.H,
                                            self.xs_buf, self.y_buf, self.saved, status=self.status, stream=stream.cuda_stream)
-        if gate is not None:
-            vd.vardrop_signal_after(self.ctx, self.gate, gate)
+        if sig_bwd is not None:
+            vd.vardrop_signal_after(self.ctx, self.kid_bwd, sig_bwd)
         vd.vardrop_attn_bwd_dev(self.ctx, self.dy_full, self.xs_buf, counts, self.n_max, *self.W_dev, w.H, self.saved,
                                 self.ws, (self.dxs_buf, *self.dW_buf), status=self.status, stream=stream.cuda_stream)
         if self.embed is not None:
@@ -475,23 +487,21 @@ class Pipeline:
                 self.attend(g % self.nb, g % self.RING, self.main)
             return
         end = first + count
-        if launch == "eager" and self.gate is not None:
+        if launch == "eager" and self.gates is not None:
             # One selection runs ahead of the call's first step; the lead then grows by one selection per step up to
-            # LEAD (two selections behind a step's gated kernel while it catches up).  The attention stream waits
+            # LEAD (two selections behind a step's gated kernels while it catches up).  The attention stream waits
             # for every selection of the first RAMP steps on its own and afterwards once per BURST steps.
             B4, LEAD, RAMP = self.BURST, self.LEAD, 2 * self.BURST
             drawn = lambda g: self.event(g % self.RING)  # selection g is drawn (recorded on the selection stream)
             issued = first
 
-            def draw(gate):
+            def draw(hash_gate=None, sample_gate=None):
                 nonlocal issued
-                if gate is not None:
-                    self.side_wait(gate)
-                self.select(issued % self.nb, issued % self.RING, self.side)
+                self.select(issued % self.nb, issued % self.RING, self.side, hash_gate, sample_gate)
                 drawn(issued).record(self.side)
                 issued += 1
 
-            draw(None)
+            draw()
             for g in range(first, end):
                 k = g - first
                 if k < RAMP:
@@ -500,10 +510,22 @@ class Pipeline:
                     self.main.wait_event(drawn(min(g + B4 - 1, end - 1)))
                 target = min(end, g + 1 + LEAD)
                 n_new = min(2, target - issued)
-                eb = self.gate_handles[g % self.RING]
-                self.attend(g % self.nb, g % self.RING, self.main, gate=eb if n_new > 0 else None)
+                ev = {"fwd": self.gate_handles["fwd"][g % self.RING], "bwd": self.gate_handles["bwd"][g % self.RING], None: None}
+                used = self.gates if n_new > 0 else ()
+                # A sampling that waits for no kernel of this step could overwrite a ring set that an attention step
+                # far behind the host has yet to read (the host issues faster than the device works).  Every BURST
+                # steps this step's backward kernel then carries a signal, and the selection stream waits for the
+                # one of BURST steps ago: the steps that read the ring sets drawn next (RING steps back) are over.
+                guard = self.gates[1] is None and k % B4 == 0
+                self.attend(g % self.nb, g % self.RING, self.main, sig_fwd=ev["fwd"] if "fwd" in used else None,
+                            sig_bwd=ev["bwd"] if "bwd" in used or guard else None)
+                if guard and k >= B4:
+                    self.side_wait(self.gate_handles["bwd"][(g - B4) % self.RING])
                 for i in range(n_new):
-                    draw(eb if i == 0 else None)
+                    if i == 0:
+                        draw(ev[self.gates[0]], ev[self.gates[1]])
+                    else:
+                        draw()
             return
         blocks, g = [], first
         while g < end:
@@ -536,10 +558,13 @@ class Pipeline:
         return sum(ns) / len(ns), sum(gs) / len(gs)
 
 
+PLACEMENTS = ((None, None), ("fwd", None), ("bwd", None), ("fwd", "bwd"), (None, "bwd"), (None, "fwd"))
+
+
 def placements(pipe):
-    """eager mode: the attention kernels of this pipeline's steps (two untimed steps with every launch timed) behind
-    which a later step's selection can be placed: the forward attention kernel (the selection then runs beside the
-    output projection and what follows) and the last attention backward kernel (beside the gradient GEMMs)."""
+    """eager mode: finds the attention kernels of this pipeline's steps that a completion signal can ride on (two
+    untimed steps with every launch timed): the forward attention kernel and the last attention backward kernel.
+    Returns the (k-DFH after, sampling after) pairs a trial can choose from."""
     import torch
     vd, ctx = pipe.vd, pipe.ctx
     if pipe.dense:
@@ -552,38 +577,47 @@ def placements(pipe):
     vd.vardrop_profile_select(ctx, -1)
     fwd = next((name for name in ("qkv_sdpa_fwd", "sdpa_fwd") if name in ran), None)
     bwd = next((name for name in ("sdpa_bwd", "sdpa_bwd_dqkv", "sdpa_bwd_dkv") if name in ran), None)
-    return [name for name in (fwd, bwd) if name]
-
-
-def place(pipe, name):
-    vd = pipe.vd
+    if fwd is None or bwd is None:
+        return []
     kid = {vd.vardrop_kernel_name(k): k for k in range(64) if vd.vardrop_kernel_name(k)}
-    pipe.set_gate(kid[name])
-    pipe.placed = {"selection_starts_after": name}
+    pipe.kid_fwd, pipe.kid_bwd = kid[fwd], kid[bwd]
+    pipe.gate_names = {"fwd": fwd, "bwd": bwd, None: None}
+    return list(PLACEMENTS)
+
+
+def placement_name(gates):
+    return "hash:%s,sample:%s" % tuple(g or "free" for g in gates)
+
+
+def place(pipe, gates):
+    """Needs placements(pipe) to have run."""
+    pipe.set_gates(*gates)
+    pipe.placed = {"hash_starts_after": pipe.gate_names[gates[0]], "sampling_starts_after": pipe.gate_names[gates[1]]}
 
 
 def choose_launch(pipe, args):
-    """--launch auto: tries the burst pipeline and the eager pipeline with either placement of the selection for a
+    """--launch auto: tries the burst pipeline and the eager pipeline with every placement of the selection for a
     few untimed steps each and keeps the fastest; --launch eager does the same among the placements only."""
     import copy
     if args.launch in ("burst", "graph") or pipe.dense:
         return "burst" if pipe.dense else args.launch
-    names = placements(pipe)
-    if not names:
+    cands = placements(pipe)
+    if not cands:
         return "burst"
     trial = copy.copy(args)
     trial.steps, trial.warmup = max(20, min(80, args.steps)), 20     # (as long as the timed run when that is short)
-    results = {}
-    for name in names:
-        place(pipe, name)
-        results[name] = min(timed_steps(pipe, trial, "eager")[0] for _ in range(2))
+    results, by_name = {}, {}
+    for gates in cands:
+        place(pipe, gates)
+        by_name[placement_name(gates)] = gates
+        results[placement_name(gates)] = min(timed_steps(pipe, trial, "eager")[0] for _ in range(2))
     if args.launch == "auto":
         results["burst"] = min(timed_steps(pipe, trial, "burst")[0] for _ in range(2))
     best = min(results, key=results.get)
     pipe.trials_ms = results
     if best == "burst":
         return "burst"
-    place(pipe, best)
+    place(pipe, by_name[best])
     return "eager"
 
 
@@ -810,7 +844,7 @@ def main():
         out["paper_rule"] = {"rule": "Eq. 1, |S_i| = min(|G_i|, gs), with Table 8's k = %d, gs = %d" % paper_rule,
                              "value": 1e3 / ms2, "unit": "steps/s", "ms_per_step": ms2, "host_issue_ms_per_step": host2,
                              "kept_tokens_mean": n2, "groups_mean": g2, "delta": 1.0 - n2 / w.N, "token_bound": p2.n_max,
-                             "launch": launch2}
+                             "launch": launch2, "selection_placement": p2.placed if launch2 == "eager" else None}
         del p2
     if not args.dense and not args.embed and not args.no_cpu_baseline:
         gpu_topk = None

@@ -336,9 +336,10 @@ def test_embedding_of_the_kept_windows_with_the_count_on_the_device(vd, ctx):
 
 
 def test_the_benchmark_pipeline_computes_the_same_steps_in_every_launch_mode(vd, ctx):
-    """bench.py's Pipeline at the Traffic shape: the burst pipeline, the eager pipeline with the selection placed
-    behind either attention kernel (completion signals) and the recorded graph all draw selection g with Philox
-    step g and leave the same last step behind, bit for bit; that step is checked against the oracle."""
+    """bench.py's Pipeline at the Traffic shape: the burst pipeline, the eager pipeline with every placement of the
+    k-DFH and the sampling behind the attention kernels (completion signals) and the recorded graph all draw
+    selection g with Philox step g and leave the same last step behind, bit for bit; that step is checked against
+    the oracle."""
     import argparse
     import bench
     from oracle import sampling as o_samp
@@ -360,7 +361,7 @@ def test_the_benchmark_pipeline_computes_the_same_steps_in_every_launch_mode(vd,
     pipe = bench.Pipeline(vd, ctx, w, xs_dev, tok_dev, W_dev, dy_full, seed)
     args = argparse.Namespace(steps=K - 2, warmup=2)
     gates = bench.placements(pipe)
-    assert len(gates) == 2
+    assert len(gates) == len(bench.PLACEMENTS) and ("fwd", "bwd") in gates
     runs = [("burst", None)] + [("eager", g) for g in gates] + [("graph", None)]
     first = None
     for mode, gate in runs:
