@@ -1,6 +1,8 @@
 """GPU multi-head attention forward/backward against the fp64 oracle.
 
-Tolerance (per tensor): max|gpu - oracle| / max|oracle| <= 2e-2 for bf16, 1e-5 for fp32.
+Tolerance (per tensor): max|gpu - oracle| / max|oracle| <= 2e-2 for bf16, 1e-5 for fp32, and on top of that the
+element-wise bounds of util_gpu.elem_err (RMS of the difference, and every element against a relative term plus a
+floor proportional to the tensor's RMS), so that small elements are constrained as well.
 The oracle receives the same bf16- (or fp32-) representable inputs, converted to fp64.
 """
 import numpy as np
@@ -8,7 +10,7 @@ import pytest
 import torch
 
 import workloads as wl
-from util_gpu import TOL, oracle_attention, rel_err, to_dev, torch_dtype
+from util_gpu import TOL, elem_err, oracle_attention, rel_err, to_dev, torch_dtype
 
 pytestmark = pytest.mark.gpu
 
@@ -61,6 +63,10 @@ def compare(got, want, dtype, names):
             errs[k] = float(diff / max(np.abs(want[k]).max(), floor))
     bad = {k: v for k, v in errs.items() if not v <= TOL[dtype]}
     assert not bad, "relative errors above %g: %s (all: %s)" % (TOL[dtype], bad, errs)
+    # element-wise (the two bias gradients that vanish identically or nearly so keep the scale chosen above)
+    fine = {k: elem_err(got[k], want[k], dtype) for k in names if k not in ("dbq", "dbk")}
+    bad = {k: v for k, v in fine.items() if v is not None and not (v[0] <= 1.0 and v[1] <= 1.0)}
+    assert not bad, "element-wise bounds exceeded (rms ratio, element ratio; both must be <= 1): %s (all: %s)" % (bad, fine)
     return errs
 
 

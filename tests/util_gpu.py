@@ -28,6 +28,30 @@ def rel_err(got, want):
     return float(np.abs(got - want).max() / (scale if scale > 0 else 1.0))
 
 
+# Element-wise bounds for the attention tensors, relative to the RMS of the oracle's tensor rather than to its largest
+# element.  bf16: every intermediate (Q, K, V, P, O, y; dO, dP, dS, dQ, dK, dV, the gradients) is rounded to 8
+# significant bits, a relative error of at most 2^-9 on every term of the sums that follow; per stage that is about
+# 2^-9 / sqrt(3) = 1.1e-3 of the result's RMS, six to eight stages in quadrature 3-4e-3 (measured 2.2e-3 .. 4.6e-3, and
+# 8.9e-3 for the two-token case whose score gradients nearly cancel), and the worst of ~10^6 elements lies 5-6 sigma
+# out (measured up to 3.7e-2 of the RMS, 6.5e-2 with two tokens).  fp32: 4e-7 and 3e-6 measured.
+#   rms(gpu - oracle) <= RMS_TOL * rms(oracle)   and   |gpu - oracle|_i <= ELEM_REL * |oracle_i| + ELEM_ABS * rms(oracle)
+RMS_TOL = {"bf16": 1.5e-2, "fp32": 4e-6}
+ELEM_REL = {"bf16": 2.0 ** -7, "fp32": 1e-6}
+ELEM_ABS = {"bf16": 8e-2, "fp32": 3e-5}
+
+
+def elem_err(got, want, dtype):
+    """(rms(diff) / rms(want) / RMS_TOL, max_i |diff_i| / (ELEM_REL |want_i| + ELEM_ABS rms(want))): both must be <= 1.
+    None for a tensor that is identically zero in the oracle (no scale of its own)."""
+    got = got.detach().float().cpu().numpy().astype(np.float64) if isinstance(got, torch.Tensor) else np.asarray(got)
+    rms = float(np.sqrt(np.mean(want * want)))
+    if rms == 0.0:
+        return None
+    diff = np.abs(got - want)
+    return (float(np.sqrt(np.mean(diff * diff))) / rms / RMS_TOL[dtype],
+            float((diff / (ELEM_REL[dtype] * np.abs(want) + ELEM_ABS[dtype] * rms)).max()))
+
+
 @functools.lru_cache(maxsize=None)
 def workload_inputs(name, screened=True):
     """Windows of a workload, screened with the oracle's amplitude-gap rule, plus the oracle's k-DFH output."""
