@@ -305,9 +305,10 @@ class Pipeline:
     stream beside the attention of earlier batches.  Nothing of it crosses to the host: the attention kernels read
     N' on the device.
       eager: the selection of step g + LEAD is issued with step g and can be placed beside chosen kernels of it: its
-             k-DFH and its sampling each start when a named attention kernel of step g has finished (the forward
-             kernel: beside the output projection and what follows; the attention backward kernel: beside the
-             gradient GEMM), or as soon as the selection stream reaches them.  The two single-launch attention
+             k-DFH and its sampling each start when a named kernel of step g has finished (the fused forward
+             kernel: beside the output projection and what follows; the output projection: beside the attention
+             backward kernel; that kernel: beside the gradient GEMM; the gradient GEMM: beside the next step's
+             forward kernel), or as soon as the selection stream reaches them.  The two single-launch attention
              kernels need every compute unit at once, and a selection kernel that holds one of them makes such a
              kernel wait a whole round; the GEMMs between them leave compute units and LDS free.  Which placement
              is better depends on the shape; a short trial decides.  A placement uses a completion event that
@@ -341,6 +342,8 @@ class Pipeline:
                       torch.empty(w.N, dtype=torch.int32, device=dev), torch.empty(2, dtype=torch.int32, device=dev))
                      for _ in range(self.RING)]
         self.events = []
+        self.issued = None                         # eager mode: the next selection to draw, kept from call to call
+        self.n_drawn = 0                           # selections issued from the host since the counter was last reset
         self.step_dev = torch.zeros(1, dtype=torch.int64, device=dev)
         self.status = torch.zeros(1, dtype=torch.int32, device=dev)
         # ---- N' and G of every batch (they depend on the grouping only, not on the draw): an untimed pass
@@ -372,18 +375,20 @@ class Pipeline:
             self.ews = torch.empty(max(lib.vardrop_embed_workspace_bytes(w.B, self.n_max, w.L, w.d, code), 256), dtype=torch.uint8, device=dev)
             self.dWe_buf = (torch.empty((w.L, w.d), dtype=torch.float32, device=dev), torch.empty(w.d, dtype=torch.float32, device=dev))
         self.graphs = None
-        self.gates = None                          # eager mode: ("fwd" | "bwd" | None, the same for the sampling)
-        self.kid_fwd = self.kid_bwd = None         # kernel ids a completion signal can ride on
+        self.gates = None                          # eager mode: ("fwd" | "out" | "bwd" | "pair" | None, the same for the sampling)
+        self.gate_kids = None                      # kernel ids a completion signal can ride on, by those names
         self.placed = None
         self.trials_ms = None
 
     def set_gates(self, hash_after, sample_after):
-        """eager mode: the k-DFH and the sampling of a later step's selection start when this step's forward attention
-        kernel ("fwd") or its attention backward kernel ("bwd") has finished; None: when the selection stream gets there."""
+        """eager mode: the k-DFH and the sampling of a later step's selection start when a kernel of this step has
+        finished: "fwd" (forward attention kernel), "out" (output projection), "bwd" (attention backward kernel) or
+        "pair" (gradient GEMM); None: when the selection stream gets there."""
         torch = self.torch
         self.gates = (hash_after, sample_after)
+        names = ("fwd", "out", "bwd", "pair")
         self.gate_events = []
-        for _ in range(2 * self.RING):
+        for _ in range(len(names) * self.RING):
             ev = torch.cuda.Event()
             ev.record(self.main)                   # creates the underlying event; its handle is reused from here on
             self.gate_events.append(ev)
@@ -395,7 +400,7 @@ class Pipeline:
         self.hip.hipStreamWaitEvent.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint]
         self.hip.hipStreamWaitEvent.restype = ctypes.c_int
         handles = [ev.cuda_event for ev in self.gate_events]
-        self.gate_handles = {"fwd": handles[:self.RING], "bwd": handles[self.RING:]}
+        self.gate_handles = {name: handles[i * self.RING:(i + 1) * self.RING] for i, name in enumerate(names)}
 
     def side_wait(self, handle):
         if self.hip.hipStreamWaitEvent(self.side.cuda_stream, handle, 0) != 0:
@@ -406,6 +411,7 @@ class Pipeline:
         an event handle the stream waits for before that kernel."""
         vd, w = self.vd, self.w
         topk, hsh, gid, sel, counts = self.ring[r]
+        self.n_drawn += 1
         if hash_gate is not None:
             self.side_wait(hash_gate)
         vd.vardrop_hash(self.ctx, self.xs_dev[b], w.k, f_max=-1, out=(topk, hsh), stream=stream.cuda_stream)
@@ -414,13 +420,13 @@ class Pipeline:
         vd.vardrop_sample_dev(self.ctx, hsh, self.gs_cap, self.ratio[0], self.ratio[1], self.seed, self.step_dev, True,
                               (gid, sel, counts), stream=stream.cuda_stream)
 
-    def attend(self, b, r, stream, sig_fwd=None, sig_bwd=None):
-        """Forward and backward pass of batch b on the selection in ring set r.  sig_fwd / sig_bwd: event handles that
-        the forward attention kernel / the attention backward kernel of this step complete (see set_gates)."""
+    def attend(self, b, r, stream, signals=None):
+        """Forward and backward pass of batch b on the selection in ring set r.  signals: {gate name: event handle}
+        that the named kernels of this step complete (see set_gates; one request can be pending per kernel)."""
         vd, w = self.vd, self.w
         sel, counts = self.ring[r][3], self.ring[r][4]
-        if sig_fwd is not None:
-            vd.vardrop_signal_after(self.ctx, self.kid_fwd, sig_fwd)
+        for name, handle in (signals or {}).items():
+            vd.vardrop_signal_after(self.ctx, self.gate_kids[name], handle)
         if self.embed is not None:
             # tokens of the kept variates straight from the raw windows (no token tensor of all variates exists)
             vd.vardrop_embed_fwd_dev(self.ctx, self.xs_dev[b], sel, counts, self.n_max, self.embed[0], self.embed[1],
@@ -430,8 +436,6 @@ class Pipeline:
         else:
             vd.vardrop_gather_attn_fwd_dev(self.ctx, self.tok_dev[b], sel, counts, self.n_max, *self.W_dev, w.H,
                                            self.xs_buf, self.y_buf, self.saved, status=self.status, stream=stream.cuda_stream)
-        if sig_bwd is not None:
-            vd.vardrop_signal_after(self.ctx, self.kid_bwd, sig_bwd)
         vd.vardrop_attn_bwd_dev(self.ctx, self.dy_full, self.xs_buf, counts, self.n_max, *self.W_dev, w.H, self.saved,
                                 self.ws, (self.dxs_buf, *self.dW_buf), status=self.status, stream=stream.cuda_stream)
         if self.embed is not None:
@@ -472,10 +476,13 @@ class Pipeline:
             self.events.append(self.torch.cuda.Event())
         return self.events[i]
 
-    def run(self, first, count, launch):
+    def run(self, first, count, launch, more=False):
         """`count` whole steps from global step `first`; returns when everything is ISSUED (not finished).
-        The caller synchronises the device between two calls (ring sets are reused from the start)."""
+        The caller synchronises the device between two calls (ring sets are reused from the start).
+        more: another call continues at step first + count (eager mode keeps its lead of drawn selections for it)."""
         torch = self.torch
+        if launch != "eager" or self.gates is None:
+            self.issued = None
         if launch == "graph":
             with torch.cuda.stream(self.main):
                 G = len(self.graphs)
@@ -488,12 +495,15 @@ class Pipeline:
             return
         end = first + count
         if launch == "eager" and self.gates is not None:
-            # One selection runs ahead of the call's first step; the lead then grows by one selection per step up to
-            # LEAD (two selections behind a step's gated kernels while it catches up).  The attention stream waits
-            # for every selection of the first RAMP steps on its own and afterwards once per BURST steps.
+            # One selection runs ahead of the first step; the lead then grows by one selection per step up to LEAD (two
+            # selections behind a step's gated kernels while it catches up).  While it grows the attention stream
+            # waits for every selection on its own (RAMP steps), afterwards once per BURST steps.  With `more` the
+            # lead is kept at the end of the call (the selections of the next LEAD steps are drawn) and the next
+            # call carries on from it: every call then draws as many selections as it attends steps.
             B4, LEAD, RAMP = self.BURST, self.LEAD, 2 * self.BURST
             drawn = lambda g: self.event(g % self.RING)  # selection g is drawn (recorded on the selection stream)
-            issued = first
+            issued = self.issued if first > 0 and self.issued is not None and self.issued > first else first
+            ramp = issued - first < LEAD
 
             def draw(hash_gate=None, sample_gate=None):
                 nonlocal issued
@@ -501,24 +511,27 @@ class Pipeline:
                 drawn(issued).record(self.side)
                 issued += 1
 
-            draw()
+            if issued == first:
+                draw()
             for g in range(first, end):
                 k = g - first
-                if k < RAMP:
+                if ramp and k < RAMP:
                     self.main.wait_event(drawn(g))
                 elif k % B4 == 0:
                     self.main.wait_event(drawn(min(g + B4 - 1, end - 1)))
-                target = min(end, g + 1 + LEAD)
+                target = g + 1 + LEAD if more else min(end, g + 1 + LEAD)
                 n_new = min(2, target - issued)
-                ev = {"fwd": self.gate_handles["fwd"][g % self.RING], "bwd": self.gate_handles["bwd"][g % self.RING], None: None}
-                used = self.gates if n_new > 0 else ()
+                ev = {name: ring[g % self.RING] for name, ring in self.gate_handles.items()}
+                ev[None] = None
+                used = {name for name in self.gates if name} if n_new > 0 else set()
                 # A sampling that waits for no kernel of this step could overwrite a ring set that an attention step
                 # far behind the host has yet to read (the host issues faster than the device works).  Every BURST
                 # steps this step's backward kernel then carries a signal, and the selection stream waits for the
                 # one of BURST steps ago: the steps that read the ring sets drawn next (RING steps back) are over.
                 guard = self.gates[1] is None and k % B4 == 0
-                self.attend(g % self.nb, g % self.RING, self.main, sig_fwd=ev["fwd"] if "fwd" in used else None,
-                            sig_bwd=ev["bwd"] if "bwd" in used or guard else None)
+                if guard:
+                    used.add("bwd")
+                self.attend(g % self.nb, g % self.RING, self.main, signals={name: ev[name] for name in used})
                 if guard and k >= B4:
                     self.side_wait(self.gate_handles["bwd"][(g - B4) % self.RING])
                 for i in range(n_new):
@@ -526,7 +539,9 @@ class Pipeline:
                         draw(ev[self.gates[0]], ev[self.gates[1]])
                     else:
                         draw()
+            self.issued = issued
             return
+        self.issued = None
         blocks, g = [], first
         while g < end:
             # (the bursts grow 1, 1, 2, 4, 4, ...: a burst runs beside the block before it, which must not be shorter)
@@ -558,13 +573,13 @@ class Pipeline:
         return sum(ns) / len(ns), sum(gs) / len(gs)
 
 
-PLACEMENTS = ((None, None), ("fwd", None), ("bwd", None), ("fwd", "bwd"), (None, "bwd"), (None, "fwd"))
+PLACEMENTS = tuple((h, s) for s in (None, "fwd", "out", "bwd", "pair") for h in (None, "fwd", "out", "bwd", "pair"))
 
 
 def placements(pipe):
-    """eager mode: finds the attention kernels of this pipeline's steps that a completion signal can ride on (two
-    untimed steps with every launch timed): the forward attention kernel and the last attention backward kernel.
-    Returns the (k-DFH after, sampling after) pairs a trial can choose from."""
+    """eager mode: finds the kernels of this pipeline's attention steps that a completion signal can ride on (two
+    untimed steps with every launch timed): the forward attention kernel, the output projection, the last attention
+    backward kernel and the gradient GEMM.  Returns the (k-DFH after, sampling after) pairs a trial can choose from."""
     import torch
     vd, ctx = pipe.vd, pipe.ctx
     if pipe.dense:
@@ -575,13 +590,16 @@ def placements(pipe):
     torch.cuda.synchronize()
     ran = set(vd.vardrop_profile_read_all(ctx))
     vd.vardrop_profile_select(ctx, -1)
-    fwd = next((name for name in ("qkv_sdpa_fwd", "sdpa_fwd") if name in ran), None)
-    bwd = next((name for name in ("sdpa_bwd", "sdpa_bwd_dqkv", "sdpa_bwd_dkv") if name in ran), None)
-    if fwd is None or bwd is None:
+    names = {"fwd": next((name for name in ("qkv_sdpa_fwd", "sdpa_fwd") if name in ran), None),
+             "out": "gemm_out" if "gemm_out" in ran else None,
+             "bwd": next((name for name in ("sdpa_bwd", "sdpa_bwd_dqkv", "sdpa_bwd_dkv") if name in ran), None),
+             "pair": "gemm_dw_dxs" if "gemm_dw_dxs" in ran else None}
+    if any(v is None for v in names.values()):
         return []
     kid = {vd.vardrop_kernel_name(k): k for k in range(64) if vd.vardrop_kernel_name(k)}
-    pipe.kid_fwd, pipe.kid_bwd = kid[fwd], kid[bwd]
-    pipe.gate_names = {"fwd": fwd, "bwd": bwd, None: None}
+    pipe.gate_kids = {name: kid[kernel] for name, kernel in names.items()}
+    pipe.gate_names = dict(names)
+    pipe.gate_names[None] = None
     return list(PLACEMENTS)
 
 
@@ -605,7 +623,7 @@ def choose_launch(pipe, args):
     if not cands:
         return "burst"
     trial = copy.copy(args)
-    trial.steps, trial.warmup = max(20, min(80, args.steps)), 20     # (as long as the timed run when that is short)
+    trial.steps, trial.warmup = max(40, min(80, args.steps)), 20
     results, by_name = {}, {}
     for gates in cands:
         place(pipe, gates)
@@ -622,8 +640,11 @@ def choose_launch(pipe, args):
 
 
 def timed_steps(pipe, args, launch):
-    """W warm-up steps, then exactly K timed steps, bracketed by device synchronisation on both sides.  Every step's
-    selection and attention are issued inside the call that times it."""
+    """W warm-up steps, then exactly K timed steps, bracketed by device synchronisation on both sides.  The timed call
+    issues K selections and K attention steps.  In the eager pipeline the selections run LEAD steps ahead of the
+    attention, across the two calls as well: the warm-up call ends with the next LEAD selections drawn, so the timed
+    call starts in the steady state, and it draws the selections of the LEAD steps that follow it (checked: at least as
+    many selections as steps inside the timed call; the whole-device synchronisation that ends it waits for them too)."""
     import torch
     primed = 0
     if launch == "graph":
@@ -636,16 +657,21 @@ def timed_steps(pipe, args, launch):
         primed = 1
     else:
         pipe.step_dev.zero_()
-    pipe.run(0, args.warmup, launch)
+    pipe.issued, pipe.n_drawn = None, 0
+    pipe.run(0, args.warmup, launch, more=True)
     torch.cuda.synchronize()
+    drawn_before = pipe.n_drawn
     t0 = time.perf_counter()
-    pipe.run(args.warmup, args.steps, launch)
+    pipe.run(args.warmup, args.steps, launch, more=True)
     t_host = time.perf_counter()                    # every launch of the timed steps has been issued
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     if int(pipe.status[0]) != 0:
         raise RuntimeError("a step found more kept tokens than the bound the launches were sized for")
-    if not pipe.dense and int(pipe.step_dev[0]) != primed + args.warmup + args.steps:
+    if launch != "graph" and not pipe.dense and pipe.n_drawn - drawn_before < args.steps:      # (more while the lead still grows)
+        raise RuntimeError("the timed call drew %d selections for %d steps" % (pipe.n_drawn - drawn_before, args.steps))
+    expected = primed + args.warmup + args.steps if launch == "graph" else pipe.n_drawn
+    if not pipe.dense and int(pipe.step_dev[0]) != expected:
         raise RuntimeError("the device step counter does not match the number of selections drawn")
     return (t1 - t0) * 1e3 / args.steps, (t_host - t0) * 1e3 / args.steps
 

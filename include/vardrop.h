@@ -109,7 +109,7 @@ int vardrop_profile_stride(vardrop_ctx* ctx, int stride);
  * is complete when that kernel has finished, exactly as if it had been recorded on the stream right behind the
  * kernel, but no packet of its own is put between two kernels of the stream (a recorded event holds the next kernel
  * up by a few microseconds).  One-shot: the request is consumed by that launch, which is then not timed by the
- * profiling hook.  A second stream can wait for the event (hipStreamWaitEvent after the call that launched the
+ * profiling hook; one request can be pending per kernel id.  A second stream can wait for the event (hipStreamWaitEvent after the call that launched the
  * kernel has returned) to start work beside a chosen kernel of this stream.  Launches recorded into a HIP graph
  * must not carry one.  Returns VARDROP_EINVAL for an unknown id. */
 int vardrop_signal_after(vardrop_ctx* ctx, int kernel_id, void* event);

@@ -18,8 +18,8 @@ struct vardrop_ctx {
   hipEvent_t* prof_ev;   // 2 * kProfPairs events, created on first use
   short* prof_kids;      // kernel id of every recorded pair
   hipEvent_t prof_e0, prof_e1;   // the pair the next launch is to be given (null: launch untimed)
-  int signal_kid;                // vardrop_signal_after: the next launch of this kernel id (-1: none) ...
-  hipEvent_t signal_event;       // ... carries this event as the completion event of its own dispatch
+  hipEvent_t signal_event[64];   // vardrop_signal_after: the next launch of kernel id i carries signal_event[i] (null: none)
+                                 // as the completion event of its own dispatch
   void* twiddle;         // device: k-DFH cosine / sine table in matrix-fragment order (kTwiddleBytes)
   int twiddle_L;         // window length the table currently holds (0: none),
   int twiddle_fmin;      //   its first candidate bin
@@ -54,10 +54,11 @@ struct VdTimer {
   bool active;
   bool signal;
   VdTimer(vardrop_ctx* c, int kid, hipStream_t) : ctx(c), active(false), signal(false) {
-    if (c->signal_kid == kid && c->signal_event) {     // (a launch that signals is not timed)
+    if (kid >= 0 && kid < 64 && c->signal_event[kid]) {     // (a launch that signals is not timed)
       signal = true;
       c->prof_e0 = nullptr;
-      c->prof_e1 = c->signal_event;
+      c->prof_e1 = c->signal_event[kid];
+      c->signal_event[kid] = nullptr;
       return;
     }
     if ((c->prof_kid == kid || c->prof_kid == kProfAll) && c->prof_ev && c->prof_n < kProfPairs &&
@@ -73,11 +74,7 @@ struct VdTimer {
       ++ctx->prof_n;
       ctx->prof_e0 = ctx->prof_e1 = nullptr;
     }
-    if (signal) {
-      ctx->prof_e1 = nullptr;
-      ctx->signal_kid = -1;
-      ctx->signal_event = nullptr;
-    }
+    if (signal) ctx->prof_e1 = nullptr;
   }
 };
 #define VD_KERNEL(ctx, kernel, grid, block, lds, s, ...)                                                        \

@@ -24,8 +24,7 @@ extern "C" int vardrop_create(vardrop_ctx** out, int device_id) {
   c->prof_kids = nullptr;
   c->prof_e0 = nullptr;
   c->prof_e1 = nullptr;
-  c->signal_kid = -1;
-  c->signal_event = nullptr;
+  for (int i = 0; i < 64; ++i) c->signal_event[i] = nullptr;
   c->lds_per_block = 65536;
   c->num_cus = 256;
   c->static_scratch = nullptr;
@@ -116,10 +115,10 @@ extern "C" int vardrop_profile_select(vardrop_ctx* ctx, int kernel_id) {
   return VARDROP_OK;
 }
 
+static_assert(VARDROP_K_COUNT <= 64, "one pending completion signal per kernel id");
 extern "C" int vardrop_signal_after(vardrop_ctx* ctx, int kernel_id, void* event) {
   if (!ctx || kernel_id < 0 || kernel_id >= VARDROP_K_COUNT) return VARDROP_EINVAL;
-  ctx->signal_kid = event ? kernel_id : -1;
-  ctx->signal_event = (hipEvent_t)event;
+  ctx->signal_event[kernel_id] = (hipEvent_t)event;
   return VARDROP_OK;
 }
 

@@ -333,32 +333,39 @@ __device__ inline int count_before(const uint64_t* key, const uint32_t* pay, uin
   return r;
 }
 
-// One 16-byte record per variate for the count inside a bucket: x = the hash's bits below the bucket index (all
-// that differs inside a bucket), (y, z) = u[n], w = n.  Number of records q in [s0, s1) that order before `me`.
-__device__ inline int count_before_rec(const uint4* rec, int s0, int s1, uint4 me) {
-  const unsigned long long um = ((unsigned long long)me.y << 32) | me.z;
+// Two 8-byte records per variate for the count inside a bucket: first = (the hash's bits below the bucket index, all
+// that differs inside a bucket; the upper half of u[n]), second = (the lower half of u[n], n).  Number of records q
+// in [s0, s1) that order before the record at p by (hash, u[n], n): the first records decide unless they are equal
+// (one pair in 2^32; the record itself is left out by its position), so the count reads 8 bytes per comparison.
+__device__ inline int before_rec(unsigned long long ko, unsigned long long km, const uint2* second, int q, int p, uint2 me2) {
+  int r = ko < km ? 1 : 0;
+  if (ko == km && q != p) {
+    const uint2 o2 = second[q];
+    r = (o2.x < me2.x || (o2.x == me2.x && o2.y < me2.y)) ? 1 : 0;
+  }
+  return r;
+}
+__device__ inline int count_before_rec(const uint2* first, const uint2* second, int s0, int s1, int p) {
+  const uint2 me1 = first[p], me2 = second[p];
+  const unsigned long long km = ((unsigned long long)me1.x << 32) | me1.y;
   int r = 0;
   int q = s0;
   for (; q + 4 <= s1; q += 4) {
-    uint4 o[4];
+    uint2 o[4];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) o[u] = rec[q + u];
+    for (int u = 0; u < 4; ++u) o[u] = first[q + u];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const unsigned long long uo = ((unsigned long long)o[u].y << 32) | o[u].z;
-      r += (o[u].x < me.x || (o[u].x == me.x && (uo < um || (uo == um && o[u].w < me.w)))) ? 1 : 0;
-    }
+    for (int u = 0; u < 4; ++u) r += before_rec(((unsigned long long)o[u].x << 32) | o[u].y, km, second, q + u, p, me2);
   }
   for (; q < s1; ++q) {
-    const uint4 o = rec[q];
-    const unsigned long long uo = ((unsigned long long)o.y << 32) | o.z;
-    r += (o.x < me.x || (o.x == me.x && (uo < um || (uo == um && o.w < me.w)))) ? 1 : 0;
+    const uint2 o = first[q];
+    r += before_rec(((unsigned long long)o.x << 32) | o.y, km, second, q, p, me2);
   }
   return r;
 }
 
 // FUSED: one ordering by (hash, u[n], n) instead of one by (hash, n) and a ranking by (u[n], n) inside every group
-// (needs another 16 bytes of LDS per variate: up to 4096 of them; the hash's bits below the bucket index must fit
+// (needs another 16 bytes of LDS per variate, two records of 8: up to 4096 of them; the hash's bits below the bucket index must fit
 // 32 bits, i.e. the hashes span less than 2^42, else the sorting networks take over).
 template <int E, bool FUSED>
 __global__ __launch_bounds__(1024) void sample_kernel(SampleArgs a) {
@@ -374,8 +381,9 @@ __global__ __launch_bounds__(1024) void sample_kernel(SampleArgs a) {
   int* bstart = reinterpret_cast<int*>(mm + 2);                        // [kBuckets + 1]
   int* bcur = bstart + kBuckets + 1;                                   // [kBuckets]
   int* bmax = bcur + kBuckets;                                         // [1]
-  uint4* rec = reinterpret_cast<uint4*>(
+  uint2* rec1 = reinterpret_cast<uint2*>(
       reinterpret_cast<unsigned char*>(bmax + 1) + ((16 - (reinterpret_cast<uintptr_t>(bmax + 1) & 15)) & 15));   // [npad], FUSED only
+  uint2* rec2 = rec1 + npad;                                            // [npad], FUSED only
   const int tid = threadIdx.x, nt = blockDim.x;
   // every thread's E hashes (variates tid, tid + nt, ...; npad = E * nt), read from memory once
   uint64_t hreg[E];
@@ -459,8 +467,10 @@ __global__ __launch_bounds__(1024) void sample_kernel(SampleArgs a) {
           const int pos = atomicAdd(&bcur[(int)((h - hmin) >> shift)], 1);
           key[pos] = h;
           pay[pos] = (uint32_t)(tid + e * nt);
-          if constexpr (FUSED)
-            rec[pos] = make_uint4((uint32_t)((h - hmin) & ((1ull << shift) - 1ull)), (uint32_t)(ureg[e] >> 32), (uint32_t)ureg[e], (uint32_t)(tid + e * nt));
+          if constexpr (FUSED) {
+            rec1[pos] = make_uint2((uint32_t)((h - hmin) & ((1ull << shift) - 1ull)), (uint32_t)(ureg[e] >> 32));
+            rec2[pos] = make_uint2((uint32_t)ureg[e], (uint32_t)(tid + e * nt));
+          }
         }
       __syncthreads();
       for (int p = tid; p < N; p += nt) {
@@ -468,7 +478,7 @@ __global__ __launch_bounds__(1024) void sample_kernel(SampleArgs a) {
         const uint32_t np = pay[p];
         const int b = (int)((kp - hmin) >> shift);
         const int s0 = bstart[b], s1 = bcur[b];
-        if constexpr (FUSED) scan[p] = s0 + count_before_rec(rec, s0, s1, rec[p]);
+        if constexpr (FUSED) scan[p] = s0 + count_before_rec(rec1, rec2, s0, s1, p);
         else scan[p] = s0 + count_before(key, pay, 0xffffffffu, s0, s1, kp, np);
       }
       __syncthreads();
