@@ -471,9 +471,10 @@ struct PairCfg {
   static constexpr int ldsx = gemm_async_lds_v<false, BMX_, BKX_, NSX_>, ldsw = gemm_async_lds_v<true, BMW_, BKW_, NSW_>;
   static constexpr int lds = ldsx > ldsw ? ldsx : ldsw;
 };
-// few tokens: 128-row input-gradient tiles on two 64-k stages beside 64-row weight-gradient tiles three stages deep
-// (72 KB of LDS), one slice; many tokens: 128-row tiles on four 32-k stages for both (64 KB)
-typedef PairCfg<128, 64, 2, 64, 64, 3> PairSmall;
+// few tokens: 128-row input-gradient tiles beside 64-row weight-gradient tiles, both on three 64-k stages (96 KB of
+// LDS; with two stages an input-gradient tile waits 1000 of 1700 clocks per slice for its copies), one slice;
+// many tokens: 128-row tiles on four 32-k stages for both (64 KB)
+typedef PairCfg<128, 64, 3, 64, 64, 3> PairSmall;
 typedef PairCfg<128, 32, 4, 128, 32, 4> PairLarge;
 template <typename CFG>
 __global__ __launch_bounds__(kGemmThreads, 2) void gemm_bwd_pair_kernel(GemmBf16 gx, GemmBf16 gw, int nzw) {
