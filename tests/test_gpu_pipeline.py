@@ -236,3 +236,37 @@ def test_completion_signal_rides_on_the_kernel_and_is_one_shot(vd, ctx):
     with pytest.raises(vd.VarDropError):
         vd.vardrop_signal_after(ctx, 1000, ev.cuda_event)
     vd.vardrop_signal_after(ctx, kid["gather"], None)      # cancelling is allowed
+
+
+def test_two_kernels_of_one_call_can_each_carry_a_signal(vd, ctx):
+    """One request can be pending per kernel id: the forward attention kernel and the output projection of one
+    vardrop_attn_fwd call each complete their own event, in launch order, and a request for a kernel the call does
+    not launch stays pending without disturbing it."""
+    w = wl.WORKLOADS["electricity"]
+    td = torch_dtype(w.dtype)
+    rng = np.random.default_rng(11)
+    n = 96
+    xs = to_dev(wl.quantise(rng.standard_normal((w.B, n, w.d)), w.dtype), td)
+    W_t = [to_dev(m, td) for m in wl.make_weights(w)]
+    kid = {vd.vardrop_kernel_name(k): k for k in range(64) if vd.vardrop_kernel_name(k)}
+    main = torch.cuda.Stream()
+    events = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    for ev in events:
+        ev.record(main)
+    main.synchronize()
+    y0, _ = vd.vardrop_attn_fwd(ctx, xs, *W_t, w.H)
+    torch.cuda.synchronize()
+    lib = vd.load_library()
+    code = vd.BF16
+    saved = torch.empty(lib.vardrop_attn_saved_bytes(w.B, n, w.d, w.H, code), dtype=torch.uint8, device="cuda")
+    y = torch.empty_like(y0)
+    vd.vardrop_signal_after(ctx, kid["qkv_sdpa_fwd"], events[0].cuda_event)
+    vd.vardrop_signal_after(ctx, kid["gemm_out"], events[1].cuda_event)
+    vd.vardrop_signal_after(ctx, kid["scatter"], events[2].cuda_event)         # not launched by this call
+    vd.vardrop_attn_fwd(ctx, xs, *W_t, w.H, saved=saved, out=y, stream=main.cuda_stream)
+    events[1].synchronize()
+    assert events[0].query() and events[1].query()
+    assert events[0].elapsed_time(events[1]) > 0                                # the projection finished later
+    main.synchronize()
+    assert torch.equal(y, y0)
+    vd.vardrop_signal_after(ctx, kid["scatter"], None)
