@@ -342,7 +342,8 @@ int vardrop_attn_bwd(vardrop_ctx* ctx, const void* dy, const void* xs,
 
 /* vardrop_gather_attn_fwd and vardrop_attn_bwd with a device-side token count (see the general rules; Eq. 2:
  * the selection S, and with it N' = |S|, is data of the step, not a host quantity).  n_dev points to N',
- * 1 <= n_max <= N bounds it.  xs, y, dy, dxs are [B][N'][d] packed in buffers of at least B * n_max * d
+ * 1 <= n_max <= N bounds it.  `sel` must be readable up to n_max entries (those from N' on are ignored; the
+ * selection vardrop_sample writes has N).  xs, y, dy, dxs are [B][N'][d] packed in buffers of at least B * n_max * d
  * elements; `saved` and `ws` are sized by vardrop_attn_saved_bytes / vardrop_attn_workspace_bytes for n_max, and
  * the backward call must be given the same n_max as the forward call that wrote `saved`.  The kernels are chosen
  * for n_max (VARDROP_BF16: the single-kernel path of short selections when n_max <= 128), results are those of

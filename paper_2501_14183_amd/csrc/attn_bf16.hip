@@ -891,17 +891,48 @@ __global__ __launch_bounds__(512) void attn_fwd_small_bf16(FusedFwdArgs a) {
   // heads fastest: a die's contiguous range covers whole batches, whose tokens it then fetches once
   const int tix = xcd_contiguous(blockIdx.x + gridDim.x * blockIdx.y, gridDim.x * gridDim.y);
   const int h = tix % a.H, b = tix / a.H;
-  int n;
-  if (!vd_count(a.n_dev, a.n, n, a.status) || n == 0) return;
   const int d = a.d;
   const long long ld = d;
-  const bf16_t* xs_b = a.xs + (long long)b * (a.sel ? a.N : n) * ld;
   const int total = d / 64;
 
-  // ---- copy sources.  xs: copy u covers token rows 8*(8u + wave) .. +7.  Weights: copy u belongs to
-  // matrix u and covers its k-rows 8*wave .. +7 of the slice.
-  const bf16_t* srcA[2];
+  // ---- Start-up.  The token count and the token indices come from memory that an earlier kernel wrote, two
+  // dependent round trips before the first token row can be requested.  Nothing of the weight tiles depends on
+  // them: the weight copies of the first slice go out first.  The indices are requested together with the count,
+  // at positions clamped by the bound of the count (the caller's `sel` is readable that far); the entries at and
+  // past the count are replaced once it is known.
   const bf16_t* srcB[3];
+#pragma unroll
+  for (int u = 0; u < 3; ++u) {
+    const bf16_t* Wz = u == 0 ? a.Wq : (u == 1 ? a.Wk : a.Wv);
+    const int krow = wave * 8 + (lane >> 3);
+    srcB[u] = Wz + (long long)krow * ld + h * kDh + (((lane & 7) ^ swz_nc<64>(krow)) * 8);
+  }
+  int fk = 0;        // slice whose copies are issued next
+#define VD_ISSUE_W(BUF)                                                                             \
+  {                                                                                                \
+    unsigned char* sp = smem + (BUF) * STAGE + wave * 1024;                                        \
+    _Pragma("unroll") for (int u = 0; u < 3; ++u)                                                  \
+      dma16(srcB[u] + (long long)fk * 64 * ld, sp + A_BYTES + u * BT);                             \
+  }
+  VD_ISSUE_W(0)
+  const int own_row = (wave & 3) * 32 + (lane & 31);         // the token this lane owns in the product below
+  int spec[2] = {0, 0}, spec_own = 0, spec_first = 0;
+  if (a.sel) {
+#pragma unroll
+    for (int u = 0; u < 2; ++u) spec[u] = a.sel[min((u * 8 + wave) * 8 + (lane >> 3), a.n - 1)];
+    spec_own = a.sel[min(own_row, a.n - 1)];
+    spec_first = a.sel[0];
+  }
+  int n;
+  if (!vd_count(a.n_dev, a.n, n, a.status) || n == 0) {
+    wait_vm<0>();                          // (the copies in flight write into this workgroup's LDS)
+    return;
+  }
+  const bf16_t* xs_b = a.xs + (long long)b * (a.sel ? a.N : n) * ld;
+
+  // ---- copy sources of the token rows.  Copy u covers token rows 8*(8u + wave) .. +7; rows past the count stand
+  // for the first token (any real token: they only have to be finite, every use of them is masked).
+  const bf16_t* srcA[2];
   u32x4 kept[2];                  // this thread's 16 bytes of two gathered rows, columns of head h
   int src_row[2];                 // requested here, used after the first weight copies have been issued
   bool src_ok[2] = {true, true};  // an index outside [0, N) reads row 0 and stands for a zero row, as in the gather kernel
@@ -910,20 +941,14 @@ __global__ __launch_bounds__(512) void attn_fwd_small_bf16(FusedFwdArgs a) {
     const int row = (u * 8 + wave) * 8 + (lane >> 3);
     src_row[u] = min(row, n - 1);
     if (a.sel) {
-      const int sidx = a.sel[src_row[u]];
+      const int sidx = row < n ? spec[u] : spec_first;
       src_ok[u] = (unsigned)sidx < (unsigned)a.N;
       src_row[u] = src_ok[u] ? sidx : 0;
     }
   }
-  // the token this lane owns in the product below (row wr * 32 + col of the tile): is its index valid?
+  // is the index of the token this lane owns valid?  (rows past the count: no matter)
   bool own_ok = true;
-  if (a.sel) own_ok = (unsigned)a.sel[min((wave & 3) * 32 + (lane & 31), n - 1)] < (unsigned)a.N;
-#pragma unroll
-  for (int u = 0; u < 3; ++u) {
-    const bf16_t* Wz = u == 0 ? a.Wq : (u == 1 ? a.Wk : a.Wv);
-    const int krow = wave * 8 + (lane >> 3);
-    srcB[u] = Wz + (long long)krow * ld + h * kDh + (((lane & 7) ^ swz_nc<64>(krow)) * 8);
-  }
+  if (a.sel) own_ok = own_row >= n || (unsigned)spec_own < (unsigned)a.N;
   // ---- fragment addresses relative to a stage
   const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
   uint32_t addrA[4], addrB[3];
@@ -941,13 +966,6 @@ __global__ __launch_bounds__(512) void attn_fwd_small_bf16(FusedFwdArgs a) {
   }
   floatx16 acc[3] = {zero16(), zero16(), zero16()};
 
-  int fk = 0;        // slice whose copies are issued next
-#define VD_ISSUE_W(BUF)                                                                             \
-  {                                                                                                \
-    unsigned char* sp = smem + (BUF) * STAGE + wave * 1024;                                        \
-    _Pragma("unroll") for (int u = 0; u < 3; ++u)                                                  \
-      dma16(srcB[u] + (long long)fk * 64 * ld, sp + A_BYTES + u * BT);                             \
-  }
 #define VD_ISSUE_X(BUF)                                                                             \
   {                                                                                                \
     unsigned char* sp = smem + (BUF) * STAGE + wave * 1024;                                        \
@@ -955,8 +973,6 @@ __global__ __launch_bounds__(512) void attn_fwd_small_bf16(FusedFwdArgs a) {
     ++fk;                                                                                          \
   }
 #define VD_ISSUE(BUF) { VD_ISSUE_W(BUF) VD_ISSUE_X(BUF) }
-  // the weight tiles of the first slice go first: the token rows may still be waiting for their indices
-  VD_ISSUE_W(0)
 #pragma unroll
   for (int u = 0; u < 2; ++u) {
     const int row = (u * 8 + wave) * 8 + (lane >> 3);

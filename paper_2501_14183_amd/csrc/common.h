@@ -85,7 +85,7 @@ struct VdTimer {
 
 // Token count of a call.  It is either the host integer `bound` itself (n_dev == nullptr) or an int32 in device
 // memory that every kernel of the call reads, with `bound` as its upper limit (what the buffers were sized for).
-// Returns false when the device value lies outside [0, bound]: the kernel then returns without touching memory,
+// Returns false when the device value lies outside [0, bound]: the kernel then returns without writing to memory,
 // and the first workgroup of the kernel that was handed `status` raises it.
 __device__ inline bool vd_count(const int32_t* n_dev, int bound, int& n, int32_t* status = nullptr) {
   n = bound;
