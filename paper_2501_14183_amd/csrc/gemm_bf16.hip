@@ -110,9 +110,15 @@ constexpr int kGemmThreads = 512;     // four computing wavefronts and four copy
 struct GemmDims {
   int M, K, splitk, kchunk, rs_n;
 };
-template <bool AKC, bool BKC, bool SPLIT, int BM, int BK, int NS>
+// KH (a 64-row tile of fp32 partial products from mn-contiguous operands on 64-k stages): the four computing
+// wavefronts are two column halves x two halves of every K slice instead of 2 x 2 blocks of the tile.  A wavefront
+// then owns all 64 rows, reads 2 KB + 2 KB of fragments per 16-k step instead of 1 KB + 2 KB for half the matrix
+// instructions' worth of it (32 KB of LDS reads per slice instead of 48 KB, which is what bounds this tile), and
+// the two K halves are added through LDS before the epilogue, lower half first.
+template <bool AKC, bool BKC, bool SPLIT, int BM, int BK, int NS, bool KH = false>
 __device__ __forceinline__ void gemm_async_tile(const GemmBf16& g, const GemmDims& dm, const int bx, const int by, const int bz) {
-  constexpr int BN = 128, MI = BM / 64, KS = BK / 16;
+  static_assert(!KH || (!AKC && !BKC && SPLIT && BM == 64 && BK == 64), "K halves: 64-row weight-gradient tiles on 64-k stages");
+  constexpr int BN = 128, MI = KH ? 2 : BM / 64, KS = BK / 16;
   constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE = A_BYTES + B_BYTES;
   constexpr int IA = A_BYTES / 4096, IB = B_BYTES / 4096, LPS = IA + IB;   // 1 KB copies per wavefront and stage
   constexpr int CH = BK / 8;                                              // 16-byte chunks per k-contiguous row
@@ -124,7 +130,9 @@ __device__ __forceinline__ void gemm_async_tile(const GemmBf16& g, const GemmDim
   constexpr int CPITCH = BN * ES + 16;                                    // LDS row pitch of the output tile
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int wm = (wave >> 1) & 1, wn = wave & 1;
+  const int wm = KH ? 0 : (wave >> 1) & 1, wn = wave & 1;
+  const int kh = KH ? (wave >> 1) & 1 : 0;                                // which two of a slice's four 16-k steps
+  constexpr int MROWS = KH ? BM : BM / 2;                                 // tile rows a computing wavefront covers
   const int col = lane & 31, half = lane >> 5;
   const int zb = SPLIT ? bz / dm.splitk : bz;
   const int kbeg = SPLIT ? (bz % dm.splitk) * dm.kchunk : 0;
@@ -182,13 +190,13 @@ __device__ __forceinline__ void gemm_async_tile(const GemmBf16& g, const GemmDim
 #pragma unroll
   for (int i = 0; i < MI; ++i) {
     if constexpr (AKC) {
-      const int ra = wm * (BM / 2) + i * 32 + col;
+      const int ra = wm * MROWS + i * 32 + col;
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) addrA[i][ks] = lds0 + ra * (BK * 2) + (((2 * ks + half) ^ swz_kc<BK>(ra)) * 16);
     } else {
       const int krow = 8 * half + ((lane & 15) >> 2);
-      const int mn = wm * (BM / 2) + i * 32 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-      addrA[i][0] = lds0 + krow * (BM * 2) + (((mn >> 3) ^ swz_nc<BM>(krow)) * 16) + ((mn >> 2) & 1) * 8;
+      const int mn = wm * MROWS + i * 32 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+      addrA[i][0] = lds0 + krow * (BM * 2) + (((mn >> 3) ^ swz_nc<BM>(krow)) * 16) + ((mn >> 2) & 1) * 8 + kh * 32 * BM * 2;
     }
   }
 #pragma unroll
@@ -201,7 +209,7 @@ __device__ __forceinline__ void gemm_async_tile(const GemmBf16& g, const GemmDim
     } else {
       const int krow = 8 * half + ((lane & 15) >> 2);
       const int mn = wn * 64 + j * 32 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-      addrB[j][0] = lds0 + A_BYTES + krow * (BN * 2) + (((mn >> 3) ^ swz_nc<BN>(krow)) * 16) + ((mn >> 2) & 1) * 8;
+      addrB[j][0] = lds0 + A_BYTES + krow * (BN * 2) + (((mn >> 3) ^ swz_nc<BN>(krow)) * 16) + ((mn >> 2) & 1) * 8 + kh * 32 * BN * 2;
     }
   }
 
@@ -265,7 +273,7 @@ __device__ __forceinline__ void gemm_async_tile(const GemmBf16& g, const GemmDim
         const uint32_t so = s * STAGE;
         // valid k of this lane's first fragment; only the last slice of an mn-contiguous A can fall short
         int kvalid = 8;
-        if constexpr (!AKC) kvalid = t == total - 1 ? kend - (kbeg + (nk - 1) * BK + 8 * half) : 8 + 16 * KS;
+        if constexpr (!AKC) kvalid = t == total - 1 ? kend - (kbeg + (nk - 1) * BK + 8 * half + 32 * kh) : 8 + 16 * KS;
         Frag fa[2][2], fb[2][2];
 #define VD_READ_STEP(KS_, SET)                                                                     \
   {                                                                                                \
@@ -300,7 +308,7 @@ __device__ __forceinline__ void gemm_async_tile(const GemmBf16& g, const GemmDim
     __builtin_amdgcn_sched_barrier(0);                                                             \
   }
         VD_READ_STEP(0, 0)
-        if constexpr (KS == 2) {
+        if constexpr (KS == 2 || KH) {
           VD_READ_STEP(1, 1)
           VD_MFMA_STEP(0, 0, OPK)
           VD_MFMA_STEP(1, 1, 0)
@@ -321,11 +329,35 @@ __device__ __forceinline__ void gemm_async_tile(const GemmBf16& g, const GemmDim
   }
 #undef VD_ISSUE_STAGE
 
-  // ---- epilogue.  acc[i][j] register 4*q4 + e is C[wm*BM/2 + i*32 + col][wn*64 + j*32 + 8*q4 + 4*half + e]
+  // ---- epilogue.  acc[i][j] register 4*q4 + e is C[wm*MROWS + i*32 + col][wn*64 + j*32 + 8*q4 + 4*half + e]
   // of the tile; it is written to LDS (with the bias), then stored as 16-byte chunks of whole rows.
   const bf16_t* bias = SPLIT ? nullptr : (zsel == 0 ? g.bias0 : (zsel == 1 ? g.bias1 : (zsel == 2 ? g.bias2 : g.bias3)));
   __syncthreads();                        // every wavefront is done reading the last slice
-  if (!producer)
+  if constexpr (KH) {
+    // the upper K half hands its sums over through LDS; the lower half adds them to its own (lower + upper)
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+      if (!producer && kh == 1 - pass) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+          for (int q4 = 0; q4 < 4; ++q4)
+#pragma unroll
+            for (int i = 0; i < MI; ++i) {
+              float4* p = reinterpret_cast<float4*>(smem + (i * 32 + col) * CPITCH + (wn * 64 + j * 32 + 8 * q4 + 4 * half) * 4);
+              if (pass == 0) {
+                *p = make_float4(acc[i][j][4 * q4], acc[i][j][4 * q4 + 1], acc[i][j][4 * q4 + 2], acc[i][j][4 * q4 + 3]);
+              } else {
+                const float4 v = *p;
+                acc[i][j][4 * q4] += v.x; acc[i][j][4 * q4 + 1] += v.y; acc[i][j][4 * q4 + 2] += v.z; acc[i][j][4 * q4 + 3] += v.w;
+              }
+            }
+      }
+      if (pass == 0) __syncthreads();
+    }
+    // (a lane of the lower half reads and rewrites only its own elements: no barrier in between)
+  }
+  if (!producer && kh == 0)
 #pragma unroll
   for (int j = 0; j < 2; ++j)
 #pragma unroll
@@ -339,7 +371,7 @@ __device__ __forceinline__ void gemm_async_tile(const GemmBf16& g, const GemmDim
       }
 #pragma unroll
       for (int i = 0; i < MI; ++i) {
-        unsigned char* p = smem + (wm * (BM / 2) + i * 32 + col) * CPITCH + nl * ES;
+        unsigned char* p = smem + (wm * MROWS + i * 32 + col) * CPITCH + nl * ES;
         if constexpr (SPLIT) {
           float4 o = make_float4(acc[i][j][4 * q4], acc[i][j][4 * q4 + 1], acc[i][j][4 * q4 + 2], acc[i][j][4 * q4 + 3]);
           *reinterpret_cast<float4*>(p) = o;
@@ -465,16 +497,18 @@ __global__ __launch_bounds__(kGemmThreads, 2) void gemm_async_kernel(GemmBf16 g,
 // dV and on nothing of each other, so they share one launch: workgroups [0, nx) take tiles of gx,
 // the rest tiles of gw.  The longer-running input-gradient tiles are dispatched first.
 // Tile shapes of the two kinds of workgroup: rows, k per copy stage, stages (BN = 128 always).
-template <int BMX_, int BKX_, int NSX_, int BMW_, int BKW_, int NSW_>
+template <int BMX_, int BKX_, int NSX_, int BMW_, int BKW_, int NSW_, bool KHW_ = false>
 struct PairCfg {
   static constexpr int BMX = BMX_, BKX = BKX_, NSX = NSX_, BMW = BMW_, BKW = BKW_, NSW = NSW_;
+  static constexpr bool KHW = KHW_;                // the weight-gradient tiles' wavefronts split every K slice in halves
   static constexpr int ldsx = gemm_async_lds_v<false, BMX_, BKX_, NSX_>, ldsw = gemm_async_lds_v<true, BMW_, BKW_, NSW_>;
   static constexpr int lds = ldsx > ldsw ? ldsx : ldsw;
 };
-// few tokens: 128-row input-gradient tiles beside 64-row weight-gradient tiles, both on three 64-k stages (96 KB of
-// LDS; with two stages an input-gradient tile waits 1000 of 1700 clocks per slice for its copies), one slice;
+// few tokens: 128-row input-gradient tiles beside 64-row weight-gradient tiles (wavefronts in K halves), both on
+// three 64-k stages (96 KB of LDS; with two stages an input-gradient tile waits 1000 of 1700 clocks per slice for
+// its copies), one slice;
 // many tokens: 128-row tiles on four 32-k stages for both (64 KB)
-typedef PairCfg<128, 64, 3, 64, 64, 3> PairSmall;
+typedef PairCfg<128, 64, 3, 64, 64, 3, true> PairSmall;
 typedef PairCfg<128, 32, 4, 128, 32, 4> PairLarge;
 template <typename CFG>
 __global__ __launch_bounds__(kGemmThreads, 2) void gemm_bwd_pair_kernel(GemmBf16 gx, GemmBf16 gw, int nzw) {
@@ -497,7 +531,7 @@ __global__ __launch_bounds__(kGemmThreads, 2) void gemm_bwd_pair_kernel(GemmBf16
     gemm_async_tile<true, true, false, BMX, CFG::BKX, CFG::NSX>(gx, dx, t % gxn, t / gxn, 0);
   } else {
     const int t = xcd_range_start(xcd, nx + nw) - startx + (slot - cntx);
-    gemm_async_tile<false, false, true, BMW, CFG::BKW, CFG::NSW>(gw, dw, t % gwn, (t / gwn) % gwm, t / (gwn * gwm));
+    gemm_async_tile<false, false, true, BMW, CFG::BKW, CFG::NSW, CFG::KHW>(gw, dw, t % gwn, (t / gwn) % gwm, t / (gwn * gwm));
   }
 }
 
