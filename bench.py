@@ -4,12 +4,13 @@
 One step = vardrop_hash -> vardrop_sample_dev -> vardrop_gather_attn_fwd_dev (= gather + attention forward) ->
 vardrop_attn_bwd_dev over one batch of synthetic windows and tokens that already sit in HBM.  The number of kept
 tokens N' stays on the device (the kernels read it there), so a step is a fixed sequence of launches with no host
-wait.  The selection (hash + sample) of a batch runs on a second stream beside the attention of earlier batches.
---launch graph instead records each step once as a HIP graph and replays it (slower with this runtime: a replay costs
-the host more than issuing the seven launches).  Prints ONE JSON line: steps/s, the roofline figures (the dominant kernel, and all kernels), and the
-CPU oracle timed on a bounded sample of the same workload.
+wait.  The selection (hash + sample) of a batch runs on a second stream beside the attention of earlier batches;
+where it runs is chosen by a short untimed trial (--launch auto, see Pipeline).  --launch graph instead records each
+step once as a HIP graph and replays it (slower with this runtime: a replay costs the host more than issuing the
+launches).  Prints ONE JSON line: steps/s, the roofline figures (the dominant kernel, and all kernels), a second
+figure at the paper's own sampling rule, and the CPU oracle timed on a bounded sample of the same workload.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload traffic] [--launch eager|graph] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload traffic] [--launch auto|eager|burst|graph] [--no-cpu-baseline]
 
 `--mode bandwidth` instead measures the steady-state HBM bandwidth of the two streaming kernels
 (vardrop_hash, vardrop_gather) over enough distinct batches (>= 1 GiB of input) that the 256 MB
