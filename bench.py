@@ -484,6 +484,8 @@ class Pipeline:
         torch = self.torch
         if launch != "eager" or self.gates is None:
             self.issued = None
+        if count <= 0:
+            return
         if launch == "graph":
             with torch.cuda.stream(self.main):
                 G = len(self.graphs)
